@@ -1,0 +1,284 @@
+// TEST INFRASTRUCTURE ONLY -- plain, slow, single-threaded CPU oracle for the
+// fusion-candidate evaluator.  It shares no code with the HIP library and is
+// never called by it; only the tests, the smoke check and the benchmark's CPU
+// baseline leg may load this file.
+//
+// What it computes, written out as the definitions themselves:
+//
+//  * Contraction of a base training DAG by a fusion labelling.  A fused op is
+//    the set of original ops carrying one label, its internal dependencies
+//    disappear and the dependencies that cross groups become the edges of the
+//    candidate module (Sec. 3.3: a fused op is a subgraph whose nodes are the
+//    original ops and whose edges are their dependencies).  A fused gradient
+//    tensor has the sum of its members' sizes (Sec. 2.3); every feature
+//    column is summed the same way.  The adjacency is 0/1 (Sec. 3.3.1 input
+//    (2)), so parallel edges collapse and self loops are dropped.
+//    Numbering is a choice of this build: groups are numbered by ascending
+//    smallest member index; neighbour lists are ascending.
+//
+//  * The estimator's forward pass in the fixed architecture of this build:
+//    per layer, the mean over predecessors and the mean over successors
+//    (neighbourhood encoding, Sec. 3.3.1 first equation, with uniform
+//    coefficients and separate weights per direction and for the node
+//    itself), a linear map plus bias and ReLU; a sum over all nodes of the
+//    graph (Sec. 3.3.1 second equation); then fully connected layers with
+//    ReLU and a scalar output (Sec. 3.3.2).
+//
+// Numerics: values are stored as fp32, every sum and dot product is
+// accumulated in fp64 and rounded once.  With bf16 != 0 the storage points
+// that the bf16 device path rounds (contracted features, all activations,
+// both means, the layer and head matrices) are rounded to bfloat16
+// (round-to-nearest-even); accumulation stays fp64.
+//
+// Parity pins (tests, CPU only): identity / single-group partitions, the
+// dense quotient  [P^T A P > 0] - diag  over all partitions of tiny graphs,
+// conservation of feature sums, label-bijection and node-permutation
+// invariance, a dense-adjacency float64 forward pass on <= 16 nodes, zero
+// weights (bias-only closed form), identity self-weights (readout equals
+// column sums), edgeless graphs, and one hand-worked example.  Agreement with
+// the paper's *trained* estimator: parity unpinned (no weights or data exist).
+#include <cstdint>
+#include <cstring>
+#include <cmath>
+#include <set>
+#include <utility>
+#include <vector>
+
+namespace {
+
+float round_bf16(float x) {
+  uint32_t u;
+  std::memcpy(&u, &x, 4);
+  if ((u & 0x7F800000u) == 0x7F800000u) return x;  // inf / nan unchanged
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  u &= 0xFFFF0000u;
+  std::memcpy(&x, &u, 4);
+  return x;
+}
+
+inline float store(double v, int bf16) {
+  float f = static_cast<float>(v);
+  return bf16 ? round_bf16(f) : f;
+}
+
+// One candidate.  rowptr/col describe the base graph (n nodes), label[v] is
+// an arbitrary integer in [0, n).  Outputs use local numbering 0..G-1.
+// Returns 0, or 3 when a label is out of range.
+int contract_one(int n, const int32_t* rowptr, const int32_t* col, const float* X, int F,
+                 const int32_t* label, int bf16,
+                 std::vector<int32_t>& new_id, int& G,
+                 std::vector<int32_t>& out_rowptr, std::vector<int32_t>& out_col,
+                 std::vector<int32_t>& in_rowptr, std::vector<int32_t>& in_col,
+                 std::vector<float>& Xc, std::vector<int32_t>& cnt) {
+  for (int v = 0; v < n; ++v)
+    if (label[v] < 0 || label[v] >= n) return 3;
+  // groups numbered in order of first appearance when scanning v upwards
+  std::vector<int32_t> id_of_label(n, -1);
+  new_id.assign(n, 0);
+  G = 0;
+  for (int v = 0; v < n; ++v) {
+    if (id_of_label[label[v]] < 0) id_of_label[label[v]] = G++;
+    new_id[v] = id_of_label[label[v]];
+  }
+  // feature sums and member counts
+  std::vector<double> acc(static_cast<size_t>(G) * F, 0.0);
+  cnt.assign(G, 0);
+  for (int v = 0; v < n; ++v) {
+    cnt[new_id[v]] += 1;
+    for (int f = 0; f < F; ++f) acc[static_cast<size_t>(new_id[v]) * F + f] += X[static_cast<size_t>(v) * F + f];
+  }
+  Xc.resize(static_cast<size_t>(G) * F);
+  for (size_t i = 0; i < Xc.size(); ++i) Xc[i] = store(acc[i], bf16);
+  // edge set of the quotient graph
+  std::set<std::pair<int32_t, int32_t>> fwd, bwd;
+  for (int u = 0; u < n; ++u)
+    for (int e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+      int32_t a = new_id[u], b = new_id[col[e]];
+      if (a != b) {
+        fwd.insert({a, b});
+        bwd.insert({b, a});
+      }
+    }
+  out_rowptr.assign(G + 1, 0);
+  in_rowptr.assign(G + 1, 0);
+  out_col.clear();
+  in_col.clear();
+  for (const auto& p : fwd) {
+    out_rowptr[p.first + 1] += 1;
+    out_col.push_back(p.second);
+  }
+  for (const auto& p : bwd) {
+    in_rowptr[p.first + 1] += 1;
+    in_col.push_back(p.second);
+  }
+  for (int g = 0; g < G; ++g) {
+    out_rowptr[g + 1] += out_rowptr[g];
+    in_rowptr[g + 1] += in_rowptr[g];
+  }
+  return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Rounds x[0..n) to bfloat16 values in place (still stored as fp32).
+void orc_round_bf16(float* x, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) x[i] = round_bf16(x[i]);
+}
+
+// Contracts every candidate and lays the results out block-diagonally:
+// candidate c owns nodes [node_off[c], node_off[c+1]) and edges
+// [edge_off[c], edge_off[c+1]); rowptr entries are global edge positions and
+// col entries are global node numbers.  Base graph b occupies rows
+// [g_node_off[b], g_node_off[b+1]) of X, its rowptr (n_b+1 entries starting
+// at 0) starts at g_node_off[b] + b and its col at g_edge_off[b].
+// cnt (optional) receives the member count per contracted node.
+// Capacities: new_id has cand_off[C] entries; node arrays cap_nodes (+1 for
+// rowptr), edge arrays cap_edges.  Returns 0, 3 (bad label), 4 (capacity).
+int orc_contract_batch(int n_graphs, const int32_t* g_node_off, const int32_t* g_edge_off,
+                       const int32_t* rowptr, const int32_t* col, const float* X, int F,
+                       int n_cand, const int32_t* cand_graph, const int64_t* cand_off,
+                       const int32_t* label, int bf16,
+                       int64_t cap_nodes, int64_t cap_edges,
+                       int32_t* node_off, int32_t* edge_off, int32_t* new_id,
+                       int32_t* out_rowptr, int32_t* out_col, int32_t* in_rowptr, int32_t* in_col,
+                       float* Xc, int32_t* cnt) {
+  (void)n_graphs;
+  int64_t nt = 0, et = 0;
+  node_off[0] = 0;
+  edge_off[0] = 0;
+  std::vector<int32_t> nid, orp, oc, irp, ic, ct;
+  std::vector<float> xc;
+  for (int c = 0; c < n_cand; ++c) {
+    int b = cand_graph[c];
+    int n = g_node_off[b + 1] - g_node_off[b];
+    int G = 0;
+    int rc = contract_one(n, rowptr + g_node_off[b] + b, col + g_edge_off[b],
+                          X + static_cast<size_t>(g_node_off[b]) * F, F, label + cand_off[c], bf16,
+                          nid, G, orp, oc, irp, ic, xc, ct);
+    if (rc) return rc;
+    int64_t E = static_cast<int64_t>(oc.size());
+    if (nt + G > cap_nodes || et + E > cap_edges) return 4;
+    for (int v = 0; v < n; ++v) new_id[cand_off[c] + v] = nid[v];
+    for (int g = 0; g < G; ++g) {
+      out_rowptr[nt + g] = static_cast<int32_t>(et + orp[g]);
+      in_rowptr[nt + g] = static_cast<int32_t>(et + irp[g]);
+      if (cnt) cnt[nt + g] = ct[g];
+    }
+    for (int64_t e = 0; e < E; ++e) {
+      out_col[et + e] = static_cast<int32_t>(nt + oc[e]);
+      in_col[et + e] = static_cast<int32_t>(nt + ic[e]);
+    }
+    std::memcpy(Xc + static_cast<size_t>(nt) * F, xc.data(), xc.size() * sizeof(float));
+    nt += G;
+    et += E;
+    node_off[c + 1] = static_cast<int32_t>(nt);
+    edge_off[c + 1] = static_cast<int32_t>(et);
+  }
+  out_rowptr[nt] = static_cast<int32_t>(et);
+  in_rowptr[nt] = static_cast<int32_t>(et);
+  return 0;
+}
+
+// Forward pass over a block-diagonal batch (layout as produced above).
+//   W_layers: concat over l of W^l, row-major [3d, H], d = F for l = 0 else H;
+//             rows [0,d) multiply the node's own vector, [d,2d) the mean over
+//             predecessors, [2d,3d) the mean over successors.
+//   b_layers: concat of b^l [H].
+//   head:     W1[H,H] | b1[H] | W2[H,H] | b2[H] | w3[H] | b3[1]; W row-major [in,out].
+//   pred[c]:  predicted time of candidate c.
+//   h_last (optional, [Ntot,H]) and readout (optional, [C,H]) receive the last
+//   layer's activations and the per-graph sums.
+void orc_gnn_forward(int n_cand, const int32_t* node_off,
+                     const int32_t* out_rowptr, const int32_t* out_col,
+                     const int32_t* in_rowptr, const int32_t* in_col,
+                     const float* Xc, int F, int H, int L, int bf16,
+                     const float* W_layers, const float* b_layers, const float* head,
+                     float* pred, float* h_last, float* readout) {
+  const int64_t Ntot = node_off[n_cand];
+  // weights as the device path stores them
+  size_t wlen = 0;
+  for (int l = 0; l < L; ++l) wlen += static_cast<size_t>(3) * (l == 0 ? F : H) * H;
+  std::vector<float> W(W_layers, W_layers + wlen);
+  const size_t HH = static_cast<size_t>(H) * H;
+  std::vector<float> hd(head, head + 2 * HH + 3 * H + 1);
+  if (bf16) {
+    for (auto& w : W) w = round_bf16(w);
+    for (size_t i = 0; i < HH; ++i) hd[i] = round_bf16(hd[i]);                     // W1
+    for (size_t i = 0; i < HH; ++i) hd[HH + H + i] = round_bf16(hd[HH + H + i]);   // W2
+    for (int i = 0; i < H; ++i) hd[2 * HH + 2 * H + i] = round_bf16(hd[2 * HH + 2 * H + i]);  // w3
+  }
+  const float* W1 = hd.data();
+  const float* b1 = W1 + HH;
+  const float* W2 = b1 + H;
+  const float* b2 = W2 + HH;
+  const float* w3 = b2 + H;
+  const float* b3 = w3 + H;
+
+  int dmax = F > H ? F : H;
+  std::vector<float> h(static_cast<size_t>(Ntot) * dmax), hn(static_cast<size_t>(Ntot) * dmax);
+  std::vector<float> hin(static_cast<size_t>(Ntot) * dmax), hout(static_cast<size_t>(Ntot) * dmax);
+  for (int64_t v = 0; v < Ntot; ++v)
+    for (int k = 0; k < F; ++k) h[v * F + k] = bf16 ? round_bf16(Xc[v * F + k]) : Xc[v * F + k];
+
+  std::vector<double> acc(dmax > H ? dmax : H);
+  const float* Wl = W.data();
+  const float* bl = b_layers;
+  int d = F;
+  for (int l = 0; l < L; ++l) {
+    // mean over predecessors / successors; an empty neighbourhood gives 0
+    for (int64_t v = 0; v < Ntot; ++v) {
+      for (int dir = 0; dir < 2; ++dir) {
+        const int32_t* rp = dir == 0 ? in_rowptr : out_rowptr;
+        const int32_t* ci = dir == 0 ? in_col : out_col;
+        float* dst = (dir == 0 ? hin.data() : hout.data()) + v * d;
+        int deg = rp[v + 1] - rp[v];
+        for (int k = 0; k < d; ++k) acc[k] = 0.0;
+        for (int e = rp[v]; e < rp[v + 1]; ++e)
+          for (int k = 0; k < d; ++k) acc[k] += h[static_cast<int64_t>(ci[e]) * d + k];
+        for (int k = 0; k < d; ++k) dst[k] = deg ? store(acc[k] / deg, bf16) : 0.0f;
+      }
+    }
+    // h' = ReLU([h | h_in | h_out] W + b)
+    for (int64_t v = 0; v < Ntot; ++v) {
+      for (int j = 0; j < H; ++j) acc[j] = bl[j];
+      const float* parts[3] = {h.data() + v * d, hin.data() + v * d, hout.data() + v * d};
+      for (int p = 0; p < 3; ++p)
+        for (int k = 0; k < d; ++k) {
+          double a = parts[p][k];
+          const float* wrow = Wl + (static_cast<size_t>(p) * d + k) * H;
+          for (int j = 0; j < H; ++j) acc[j] += a * wrow[j];
+        }
+      for (int j = 0; j < H; ++j) hn[v * H + j] = store(acc[j] > 0.0 ? acc[j] : 0.0, bf16);
+    }
+    h.swap(hn);
+    Wl += static_cast<size_t>(3) * d * H;
+    bl += H;
+    d = H;
+  }
+  if (h_last) std::memcpy(h_last, h.data(), static_cast<size_t>(Ntot) * H * sizeof(float));
+
+  std::vector<double> r(H), z1(H), z2(H);
+  std::vector<float> rf(H), z1f(H), z2f(H);
+  for (int c = 0; c < n_cand; ++c) {
+    for (int j = 0; j < H; ++j) r[j] = 0.0;
+    for (int64_t v = node_off[c]; v < node_off[c + 1]; ++v)
+      for (int j = 0; j < H; ++j) r[j] += h[v * H + j];
+    for (int j = 0; j < H; ++j) rf[j] = static_cast<float>(r[j]);
+    if (readout) std::memcpy(readout + static_cast<size_t>(c) * H, rf.data(), H * sizeof(float));
+    for (int j = 0; j < H; ++j) z1[j] = b1[j];
+    for (int k = 0; k < H; ++k)
+      for (int j = 0; j < H; ++j) z1[j] += static_cast<double>(rf[k]) * W1[static_cast<size_t>(k) * H + j];
+    for (int j = 0; j < H; ++j) z1f[j] = static_cast<float>(z1[j] > 0.0 ? z1[j] : 0.0);
+    for (int j = 0; j < H; ++j) z2[j] = b2[j];
+    for (int k = 0; k < H; ++k)
+      for (int j = 0; j < H; ++j) z2[j] += static_cast<double>(z1f[k]) * W2[static_cast<size_t>(k) * H + j];
+    for (int j = 0; j < H; ++j) z2f[j] = static_cast<float>(z2[j] > 0.0 ? z2[j] : 0.0);
+    double t = b3[0];
+    for (int j = 0; j < H; ++j) t += static_cast<double>(z2f[j]) * w3[j];
+    pred[c] = static_cast<float>(t);
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,134 @@
+"""ctypes front end of the CPU oracle (test infrastructure only).
+
+Loads oracle/dc_oracle.cpp, compiled with g++ into oracle/_build/.  Nothing in
+the product package imports this module; it knows nothing of the HIP library.
+Only argument marshalling happens here: every number comes out of the C++.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dc_oracle.cpp")
+_SO = os.path.join(_HERE, "_build", "libdc_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(_SO) and os.path.getmtime(_SO) >= os.path.getmtime(_SRC):
+        return _SO
+    os.makedirs(os.path.dirname(_SO), exist_ok=True)
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", _SO, _SRC])
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = C.CDLL(_SO)
+        _lib.orc_contract_batch.restype = C.c_int
+        _lib.orc_gnn_forward.restype = None
+        _lib.orc_round_bf16.restype = None
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class Batch:
+    """Block-diagonal batch of contracted graphs (global numbering)."""
+    n_cand: int
+    F: int
+    node_off: np.ndarray
+    edge_off: np.ndarray
+    new_id: np.ndarray
+    out_rowptr: np.ndarray
+    out_col: np.ndarray
+    in_rowptr: np.ndarray
+    in_col: np.ndarray
+    Xc: np.ndarray
+    cnt: np.ndarray
+
+    @property
+    def ntot(self) -> int:
+        return int(self.node_off[-1])
+
+    @property
+    def etot(self) -> int:
+        return int(self.edge_off[-1])
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    y = np.ascontiguousarray(x, dtype=np.float32).copy()
+    _load().orc_round_bf16(_p(y), C.c_int64(y.size))
+    return y
+
+
+def contract(w, bf16: Optional[bool] = None) -> Batch:
+    """Contracts all candidates of workload `w` (a workloads.Workload)."""
+    lib = _load()
+    if bf16 is None:
+        bf16 = w.model.dtype == "bf16"
+    F = w.model.F
+    gno, geo = w.g_node_off(), w.g_edge_off()
+    rowptr, col, X = w.cat_rowptr(), w.cat_col(), w.cat_X()
+    cand_graph = np.ascontiguousarray(w.cand_graph, dtype=np.int32)
+    cand_off = np.ascontiguousarray(w.cand_off, dtype=np.int64)
+    label = np.ascontiguousarray(w.group_id, dtype=np.int32)
+    Cn = w.n_cand
+    cap_n = int(cand_off[-1])
+    cap_e = int(sum(int(geo[b + 1] - geo[b]) for b in cand_graph))
+    node_off = np.zeros(Cn + 1, np.int32)
+    edge_off = np.zeros(Cn + 1, np.int32)
+    new_id = np.zeros(max(cap_n, 1), np.int32)
+    orp = np.zeros(cap_n + 1, np.int32)
+    irp = np.zeros(cap_n + 1, np.int32)
+    oc = np.zeros(max(cap_e, 1), np.int32)
+    ic = np.zeros(max(cap_e, 1), np.int32)
+    Xc = np.zeros((max(cap_n, 1), F), np.float32)
+    cnt = np.zeros(max(cap_n, 1), np.int32)
+    rc = lib.orc_contract_batch(C.c_int(len(w.graphs)), _p(gno), _p(geo), _p(rowptr), _p(col), _p(X), C.c_int(F),
+                                C.c_int(Cn), _p(cand_graph), _p(cand_off), _p(label), C.c_int(int(bf16)),
+                                C.c_int64(cap_n), C.c_int64(cap_e),
+                                _p(node_off), _p(edge_off), _p(new_id), _p(orp), _p(oc), _p(irp), _p(ic),
+                                _p(Xc), _p(cnt))
+    if rc != 0:
+        raise ValueError(f"oracle contraction failed with status {rc}")
+    nt, et = int(node_off[-1]), int(edge_off[-1])
+    return Batch(Cn, F, node_off, edge_off, new_id[:cap_n], orp[:nt + 1], oc[:et], irp[:nt + 1], ic[:et],
+                 Xc[:nt], cnt[:nt])
+
+
+def gnn_forward(b: Batch, model, weights, bf16: Optional[bool] = None, want_hidden: bool = False):
+    """Predicted time per candidate; with want_hidden also (h_last, readout)."""
+    lib = _load()
+    if bf16 is None:
+        bf16 = model.dtype == "bf16"
+    pred = np.zeros(b.n_cand, np.float32)
+    h_last = np.zeros((max(b.ntot, 1), model.H), np.float32) if want_hidden else None
+    ro = np.zeros((max(b.n_cand, 1), model.H), np.float32) if want_hidden else None
+    Wl = np.ascontiguousarray(weights.layers, dtype=np.float32)
+    bl = np.ascontiguousarray(weights.biases, dtype=np.float32)
+    hd = np.ascontiguousarray(weights.head, dtype=np.float32)
+    Xc = np.ascontiguousarray(b.Xc, dtype=np.float32)
+    lib.orc_gnn_forward(C.c_int(b.n_cand), _p(b.node_off), _p(b.out_rowptr), _p(b.out_col),
+                        _p(b.in_rowptr), _p(b.in_col), _p(Xc), C.c_int(model.F), C.c_int(model.H),
+                        C.c_int(model.L), C.c_int(int(bf16)), _p(Wl), _p(bl), _p(hd),
+                        _p(pred), _p(h_last), _p(ro))
+    if want_hidden:
+        return pred, h_last[:b.ntot], ro[:b.n_cand]
+    return pred
+
+
+def evaluate(w, bf16: Optional[bool] = None) -> np.ndarray:
+    """contract + forward: one predicted time per candidate of workload w."""
+    return gnn_forward(contract(w, bf16), w.model, w.weights, bf16)
