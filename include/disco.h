@@ -1,0 +1,179 @@
+/* disco.h -- C ABI of the MI355X fusion-candidate evaluator.
+ *
+ * The strategy search of the paper (Alg. 1) repeatedly asks a cost model
+ * Cost(H') for the per-iteration training time of a candidate module H': the
+ * base module H_in with an op-fusion strategy and a tensor-fusion strategy
+ * applied (Sec. 3.2).  This library evaluates batches of such candidates on
+ * one GPU.  A candidate is a base training DAG (compute ops plus gradient
+ * all-reduce tensors) and one integer label per base node; nodes with equal
+ * labels form one fused op / one fused gradient tensor.
+ *
+ *   dc_contract_graphs  builds the candidate modules: per candidate the
+ *                       quotient graph by label (Sec. 3.3: a fused op is the
+ *                       subgraph of its original ops; dependencies that cross
+ *                       groups remain) with summed node features (Sec. 2.3:
+ *                       the size of a fused tensor is the sum of its members'
+ *                       sizes; every feature column is summed).
+ *   dc_gnn_forward      runs the estimator on a batch of contracted graphs:
+ *                       per layer the mean over predecessors and the mean
+ *                       over successors next to the node's own vector, a
+ *                       linear map, bias and ReLU (Sec. 3.3.1, neighbourhood
+ *                       encoding); a sum over all nodes of each graph
+ *                       (Sec. 3.3.1, second equation); fully connected layers
+ *                       with ReLU and a scalar output (Sec. 3.3.2).
+ *   dc_eval_candidates  = contract + forward: the batched Cost() call.
+ *
+ * Conventions
+ *  - Every call returns a dc_status; nothing throws or aborts.
+ *  - "host" pointers are read synchronously during the call.  "dev" pointers
+ *    are device memory owned by the caller (e.g. torch tensors) and are
+ *    read/written asynchronously on `stream` (a hipStream_t passed as void*,
+ *    NULL = default stream).  Outputs are valid once the stream has reached
+ *    the end of the call's work.
+ *  - Errors the host can see (null pointer, negative size, shapes the kernels
+ *    do not support, capacity exceeded by host-known sizes) return at once
+ *    with nothing enqueued.  Errors only the device can see (label outside
+ *    [0,N), candidate/base-graph mismatch, contracted totals above capacity)
+ *    set a device status word; the affected call writes no further output and
+ *    dc_check() reports it.
+ *  - The library never validates that a fusion is legal (fusible op kinds, no
+ *    dependency cycle): the search checks validity before it calls Cost()
+ *    (Alg. 1, "if H' is valid").  Contraction and forward pass are defined
+ *    for every labelling.
+ *  - All integer arrays are int32.  Limits: a base graph has fewer than 65536
+ *    nodes; all totals fit in int32; F and H are multiples of 16, H <= 512.
+ *  - Calls on one dc_ctx must not overlap (the context owns scratch memory).
+ */
+#ifndef DISCO_H_
+#define DISCO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dc_ctx dc_ctx; /* opaque; owns device copies of base graphs, weights and scratch */
+
+typedef enum {
+  DC_OK = 0,
+  DC_ERR_INVALID_ARG = 1,   /* null pointer, negative size, call order                        */
+  DC_ERR_BAD_GRAPH = 2,     /* base graph malformed (rowptr not monotone, col out of range)   */
+  DC_ERR_BAD_PARTITION = 3, /* label outside [0,N) or candidate length != base graph size     */
+  DC_ERR_CAPACITY = 4,      /* sizes exceed what dc_config / the dc_batch buffers allow        */
+  DC_ERR_OOM = 5,           /* device allocation failed                                       */
+  DC_ERR_HIP = 6,           /* a HIP runtime call failed (see dc_last_error)                  */
+  DC_ERR_UNSUPPORTED = 7    /* shape outside the limits listed above                          */
+} dc_status;
+
+typedef enum { DC_F32 = 0, DC_BF16 = 1 } dc_dtype;
+
+/* Model shape and per-call capacities.
+ *   F, H, L          input features, hidden width, number of message-passing layers
+ *   dtype            DC_F32: fp32 storage and fp32 matrix arithmetic.
+ *                    DC_BF16: contracted features, activations, both means and the
+ *                    layer/head matrices are bfloat16 (round to nearest even);
+ *                    sums, means, matrix accumulation, bias, ReLU and the head are fp32.
+ *   max_cand         candidates per call
+ *   max_base_nodes   bound on sum over candidates of base-graph node counts (= labels per call)
+ *   max_base_edges   bound on sum over candidates of base-graph edge counts
+ *   max_nodes        bound on contracted nodes per call; 0 means max_base_nodes
+ *   max_edges        bound on contracted edges per call; 0 means max_base_edges           */
+typedef struct {
+  int32_t F, H, L;
+  int32_t dtype;
+  int64_t max_cand;
+  int64_t max_base_nodes;
+  int64_t max_base_edges;
+  int64_t max_nodes;
+  int64_t max_edges;
+} dc_config;
+
+/* A batch of contracted graphs, block diagonal: candidate c owns nodes
+ * [node_off[c], node_off[c+1]) and edges [edge_off[c], edge_off[c+1]).  Groups are
+ * numbered by ascending smallest member index.  out_rowptr/out_col list each node's
+ * successors, in_rowptr/in_col its predecessors, both ascending; rowptr entries are
+ * global edge positions, col entries global node numbers.  All arrays are device
+ * memory owned by the caller; cap_* are the caller's allocation sizes.            */
+typedef struct {
+  int32_t n_cand;      /* written by dc_contract_graphs                                     */
+  int64_t cap_nodes;   /* rows available in Xc; out_rowptr/in_rowptr hold cap_nodes+1       */
+  int64_t cap_edges;   /* entries available in out_col / in_col                             */
+  int32_t* node_off;   /* dev [n_cand+1]                                                    */
+  int32_t* edge_off;   /* dev [n_cand+1]                                                    */
+  int32_t* new_id;     /* dev [sum of base node counts] contracted node (local) per label   */
+  int32_t* out_rowptr; /* dev [cap_nodes+1]                                                 */
+  int32_t* out_col;    /* dev [cap_edges]                                                   */
+  int32_t* in_rowptr;  /* dev [cap_nodes+1]                                                 */
+  int32_t* in_col;     /* dev [cap_edges]                                                   */
+  void* Xc;            /* dev [cap_nodes, F] row-major, fp32 or bf16 per dc_config.dtype    */
+} dc_batch;
+
+/* Creates a context and allocates all scratch for the given capacities (device memory;
+ * see dc_workspace_bytes).  The current HIP device at the time of the call is used.   */
+dc_status dc_create(dc_ctx** out, const dc_config* cfg);
+dc_status dc_destroy(dc_ctx* ctx);
+
+/* Device bytes dc_create will allocate for cfg (excluding base graphs and weights). */
+size_t dc_workspace_bytes(const dc_config* cfg);
+
+/* Estimator weights, host fp32; the context keeps a converted device copy.
+ *   W_layers  concat over l of W^l, row-major [3d, H], d = F for l = 0 else H; rows
+ *             [0,d) act on the node's own vector, [d,2d) on the predecessor mean,
+ *             [2d,3d) on the successor mean.
+ *   b_layers  concat of b^l [H].
+ *   head      W1[H,H] | b1[H] | W2[H,H] | b2[H] | w3[H] | b3[1], W row-major [in,out]:
+ *             z1 = ReLU(r W1 + b1), z2 = ReLU(z1 W2 + b2), t = z2.w3 + b3.              */
+dc_status dc_set_weights(dc_ctx* ctx, const float* W_layers, const float* b_layers, const float* head,
+                         void* stream);
+
+/* Base graphs (set once, candidates refer to them by index).  All host pointers.
+ *   g_node_off [n+1], g_edge_off [n+1]  node / edge offsets of the graphs
+ *   rowptr     concatenated per-graph CSR row pointers: graph b has N_b+1 entries
+ *              starting at position g_node_off[b] + b, values relative to the graph (start 0)
+ *   col        concatenated successor lists, local node numbers; graph b at g_edge_off[b]
+ *   X          [sum N_b, F] fp32 node features
+ * Rows need not be sorted or duplicate free.  Returns DC_ERR_BAD_GRAPH on malformed input. */
+dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_node_off,
+                             const int32_t* g_edge_off, const int32_t* rowptr, const int32_t* col,
+                             const float* X, void* stream);
+
+/* Contracts n_cand candidates.  cand_graph dev [n_cand] base-graph index; cand_off dev
+ * [n_cand+1] offsets into group_id (cand_off[c+1]-cand_off[c] must equal the node count
+ * of graph cand_graph[c]); group_id dev labels in [0, N).  Fills every array of *out
+ * (host struct, device arrays) and sets out->n_cand.                                   */
+dc_status dc_contract_graphs(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph,
+                             const int32_t* cand_off, const int32_t* group_id, dc_batch* out, void* stream);
+
+/* Forward pass over a batch laid out as above (typically the output of
+ * dc_contract_graphs; node_off[n_cand] must not exceed the context's max_nodes).
+ * pred dev [n_cand] fp32: predicted per-iteration time per candidate.            */
+dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* stream);
+
+/* dc_contract_graphs into context-owned buffers followed by dc_gnn_forward. */
+dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                             const int32_t* group_id, float* pred, void* stream);
+
+/* Waits for `stream`, then returns the first device-detected error since the last
+ * dc_check (DC_OK if none) and clears it.                                          */
+dc_status dc_check(dc_ctx* ctx, void* stream);
+
+/* After a synchronised dc_contract_graphs / dc_eval_candidates: totals of the last
+ * contraction (contracted nodes, contracted edges).  Synchronises `stream`.        */
+dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* stream);
+
+/* Human-readable detail of the last error on this context; owned by the context. */
+const char* dc_last_error(const dc_ctx* ctx);
+
+/* Timing hooks for benchmarks: average milliseconds per launch of each kernel family
+ * over the calls made since dc_profile_begin, measured with HIP events on the call's
+ * stream.  names/ms receive up to `cap` entries; returns the number of families.
+ * Profiling serialises nothing but adds event records; leave it off in production.    */
+dc_status dc_profile_begin(dc_ctx* ctx);
+int32_t dc_profile_end(dc_ctx* ctx, const char** names, float* total_ms, int32_t* launches, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISCO_H_ */

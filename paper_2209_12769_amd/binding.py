@@ -1,0 +1,277 @@
+"""ctypes binding of libdisco.so -- argument marshalling only.
+
+The module-level functions carry the names of the C ABI (include/disco.h) and
+pass raw pointers; every step of the evaluation runs in the HIP kernels.
+PyTorch is used for device memory and streams only.  There is no fallback: if
+the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdisco.so")
+
+DC_OK = 0
+DC_ERR_INVALID_ARG = 1
+DC_ERR_BAD_GRAPH = 2
+DC_ERR_BAD_PARTITION = 3
+DC_ERR_CAPACITY = 4
+DC_ERR_OOM = 5
+DC_ERR_HIP = 6
+DC_ERR_UNSUPPORTED = 7
+DC_F32 = 0
+DC_BF16 = 1
+STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "DC_ERR_BAD_PARTITION",
+                4: "DC_ERR_CAPACITY", 5: "DC_ERR_OOM", 6: "DC_ERR_HIP", 7: "DC_ERR_UNSUPPORTED"}
+
+
+class DcConfig(C.Structure):
+    _fields_ = [("F", C.c_int32), ("H", C.c_int32), ("L", C.c_int32), ("dtype", C.c_int32),
+                ("max_cand", C.c_int64), ("max_base_nodes", C.c_int64), ("max_base_edges", C.c_int64),
+                ("max_nodes", C.c_int64), ("max_edges", C.c_int64)]
+
+
+class DcBatch(C.Structure):
+    _fields_ = [("n_cand", C.c_int32), ("cap_nodes", C.c_int64), ("cap_edges", C.c_int64),
+                ("node_off", C.c_void_p), ("edge_off", C.c_void_p), ("new_id", C.c_void_p),
+                ("out_rowptr", C.c_void_p), ("out_col", C.c_void_p), ("in_rowptr", C.c_void_p),
+                ("in_col", C.c_void_p), ("Xc", C.c_void_p)]
+
+
+class DiscoError(RuntimeError):
+    def __init__(self, status: int, detail: str = ""):
+        self.status = status
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {detail}")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2209_12769_amd.build)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, fp = C.c_void_p, C.c_int32, C.POINTER(C.c_float)
+        L.dc_create.argtypes = [C.POINTER(vp), C.POINTER(DcConfig)]
+        L.dc_destroy.argtypes = [vp]
+        L.dc_workspace_bytes.argtypes = [C.POINTER(DcConfig)]
+        L.dc_workspace_bytes.restype = C.c_size_t
+        L.dc_set_weights.argtypes = [vp, vp, vp, vp, vp]
+        L.dc_set_base_graphs.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        L.dc_contract_graphs.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp]
+        L.dc_gnn_forward.argtypes = [vp, C.POINTER(DcBatch), vp, vp]
+        L.dc_eval_candidates.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.dc_check.argtypes = [vp, vp]
+        L.dc_last_totals.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
+        L.dc_last_error.argtypes = [vp]
+        L.dc_last_error.restype = C.c_char_p
+        L.dc_profile_begin.argtypes = [vp]
+        L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
+        for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_base_graphs", "dc_contract_graphs",
+                  "dc_gnn_forward", "dc_eval_candidates", "dc_check", "dc_last_totals", "dc_profile_begin",
+                  "dc_profile_end"):
+            getattr(L, n).restype = i32
+        _lib = L
+    return _lib
+
+
+# ---- the C ABI, name for name -------------------------------------------------
+def dc_workspace_bytes(cfg: DcConfig) -> int:
+    return int(lib().dc_workspace_bytes(C.byref(cfg)))
+
+
+def dc_create(cfg: DcConfig) -> Tuple[int, Optional[int]]:
+    h = C.c_void_p()
+    st = lib().dc_create(C.byref(h), C.byref(cfg))
+    return st, h.value
+
+
+def dc_destroy(ctx: int) -> int:
+    return lib().dc_destroy(ctx)
+
+
+def dc_set_weights(ctx, W_layers: np.ndarray, b_layers: np.ndarray, head: np.ndarray, stream: int = 0) -> int:
+    return lib().dc_set_weights(ctx, W_layers.ctypes.data, b_layers.ctypes.data, head.ctypes.data, stream)
+
+
+def dc_set_base_graphs(ctx, n_graphs, g_node_off, g_edge_off, rowptr, col, X, stream: int = 0) -> int:
+    return lib().dc_set_base_graphs(ctx, n_graphs, g_node_off.ctypes.data, g_edge_off.ctypes.data,
+                                    rowptr.ctypes.data, col.ctypes.data if col.size else None, X.ctypes.data, stream)
+
+
+def dc_contract_graphs(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, batch: DcBatch, stream: int = 0) -> int:
+    return lib().dc_contract_graphs(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, C.byref(batch), stream)
+
+
+def dc_gnn_forward(ctx, batch: DcBatch, pred_ptr, stream: int = 0) -> int:
+    return lib().dc_gnn_forward(ctx, C.byref(batch), pred_ptr, stream)
+
+
+def dc_eval_candidates(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, pred_ptr, stream: int = 0) -> int:
+    return lib().dc_eval_candidates(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, pred_ptr, stream)
+
+
+def dc_check(ctx, stream: int = 0) -> int:
+    return lib().dc_check(ctx, stream)
+
+
+def dc_last_totals(ctx, stream: int = 0) -> Tuple[int, int, int]:
+    n, e = C.c_int64(), C.c_int64()
+    st = lib().dc_last_totals(ctx, C.byref(n), C.byref(e), stream)
+    return st, n.value, e.value
+
+
+def dc_last_error(ctx) -> str:
+    return lib().dc_last_error(ctx).decode()
+
+
+def dc_profile_begin(ctx) -> int:
+    return lib().dc_profile_begin(ctx)
+
+
+def dc_profile_end(ctx) -> Dict[str, Tuple[float, int]]:
+    cap = 16
+    names = (C.c_char_p * cap)()
+    ms = (C.c_float * cap)()
+    cnt = (C.c_int32 * cap)()
+    n = lib().dc_profile_end(ctx, names, ms, cnt, cap)
+    return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(min(n, cap))}
+
+
+# ---- convenience wrapper over torch device memory --------------------------------
+@dataclass
+class DeviceBatch:
+    """Device arrays of one dc_batch (torch tensors own the memory)."""
+    c: DcBatch
+    node_off: "object"
+    edge_off: "object"
+    new_id: "object"
+    out_rowptr: "object"
+    out_col: "object"
+    in_rowptr: "object"
+    in_col: "object"
+    Xc: "object"
+
+
+class Evaluator:
+    """Owns one dc_ctx.  Methods move pointers across the C ABI; nothing is computed in Python."""
+
+    def __init__(self, F: int, H: int, L: int, dtype: str, max_cand: int, max_base_nodes: int, max_base_edges: int,
+                 max_nodes: int = 0, max_edges: int = 0, device: str = "cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = DcConfig(F, H, L, DC_BF16 if dtype == "bf16" else DC_F32, max_cand, max_base_nodes,
+                            max_base_edges, max_nodes, max_edges)
+        self.dtype = dtype
+        st, h = dc_create(self.cfg)
+        if st != DC_OK:
+            raise DiscoError(st, "dc_create")
+        self.ctx = h
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            dc_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _ok(self, st: int, what: str):
+        if st != DC_OK:
+            raise DiscoError(st, f"{what}: {dc_last_error(self.ctx)}")
+
+    def set_weights(self, weights):
+        W = np.ascontiguousarray(weights.layers, dtype=np.float32)
+        b = np.ascontiguousarray(weights.biases, dtype=np.float32)
+        hd = np.ascontiguousarray(weights.head, dtype=np.float32)
+        self._ok(dc_set_weights(self.ctx, W, b, hd, self._stream()), "dc_set_weights")
+
+    def set_base_graphs(self, g_node_off, g_edge_off, rowptr, col, X):
+        gno = np.ascontiguousarray(g_node_off, dtype=np.int32)
+        geo = np.ascontiguousarray(g_edge_off, dtype=np.int32)
+        rp = np.ascontiguousarray(rowptr, dtype=np.int32)
+        ci = np.ascontiguousarray(col, dtype=np.int32)
+        Xf = np.ascontiguousarray(X, dtype=np.float32)
+        self._ok(dc_set_base_graphs(self.ctx, len(gno) - 1, gno, geo, rp, ci, Xf, self._stream()), "dc_set_base_graphs")
+
+    def to_device(self, a: np.ndarray):
+        return self.torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(self.device)
+
+    def alloc_batch(self, n_cand: int, n_labels: int, cap_nodes: int, cap_edges: int) -> DeviceBatch:
+        t = self.torch
+        i32 = dict(dtype=t.int32, device=self.device)
+        node_off = t.empty(n_cand + 1, **i32)
+        edge_off = t.empty(n_cand + 1, **i32)
+        new_id = t.empty(max(n_labels, 1), **i32)
+        orp = t.empty(cap_nodes + 1, **i32)
+        irp = t.empty(cap_nodes + 1, **i32)
+        oc = t.empty(max(cap_edges, 1), **i32)
+        ic = t.empty(max(cap_edges, 1), **i32)
+        Xc = t.empty((max(cap_nodes, 1), self.cfg.F), dtype=t.bfloat16 if self.dtype == "bf16" else t.float32,
+                     device=self.device)
+        c = DcBatch(n_cand, cap_nodes, cap_edges, node_off.data_ptr(), edge_off.data_ptr(), new_id.data_ptr(),
+                    orp.data_ptr(), oc.data_ptr(), irp.data_ptr(), ic.data_ptr(), Xc.data_ptr())
+        return DeviceBatch(c, node_off, edge_off, new_id, orp, oc, irp, ic, Xc)
+
+    def contract_graphs(self, cand_graph, cand_off, group_id, batch: DeviceBatch) -> DeviceBatch:
+        n_cand = int(cand_graph.numel())
+        self._ok(dc_contract_graphs(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(),
+                                    group_id.data_ptr(), batch.c, self._stream()), "dc_contract_graphs")
+        return batch
+
+    def gnn_forward(self, batch: DeviceBatch, pred=None):
+        if pred is None:
+            pred = self.torch.empty(max(batch.c.n_cand, 1), dtype=self.torch.float32, device=self.device)
+        self._ok(dc_gnn_forward(self.ctx, batch.c, pred.data_ptr(), self._stream()), "dc_gnn_forward")
+        return pred[:batch.c.n_cand]
+
+    def eval_candidates(self, cand_graph, cand_off, group_id, pred=None):
+        n_cand = int(cand_graph.numel())
+        if pred is None:
+            pred = self.torch.empty(max(n_cand, 1), dtype=self.torch.float32, device=self.device)
+        self._ok(dc_eval_candidates(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(),
+                                    group_id.data_ptr(), pred.data_ptr(), self._stream()), "dc_eval_candidates")
+        return pred[:n_cand]
+
+    def check(self) -> int:
+        return dc_check(self.ctx, self._stream())
+
+    def last_totals(self) -> Tuple[int, int]:
+        st, n, e = dc_last_totals(self.ctx, self._stream())
+        self._ok(st, "dc_last_totals")
+        return n, e
+
+    def profile_begin(self):
+        self._ok(dc_profile_begin(self.ctx), "dc_profile_begin")
+
+    def profile_end(self):
+        return dc_profile_end(self.ctx)
+
+
+def evaluator_for(w, slack: float = 1.0, max_nodes: int = 0, max_edges: int = 0, device: str = "cuda:0") -> Evaluator:
+    """Evaluator sized for workload `w` (a workloads.Workload) with its base graphs and weights set."""
+    geo = w.g_edge_off()
+    nb = int(w.cand_off[-1])
+    eb = int(sum(int(geo[b + 1] - geo[b]) for b in w.cand_graph))
+    ev = Evaluator(w.model.F, w.model.H, w.model.L, w.model.dtype, max(w.n_cand, 1), max(int(nb * slack), 1),
+                   max(int(eb * slack), 1), max_nodes, max_edges, device)
+    ev.set_base_graphs(w.g_node_off(), geo, w.cat_rowptr(), w.cat_col(), w.cat_X())
+    ev.set_weights(w.weights)
+    return ev

@@ -1,0 +1,593 @@
+// C ABI of libdisco: context, argument checks, memory, launches (gfx950 only).
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace dc;
+
+namespace dc {
+void Profiler::begin(int family, hipStream_t s) {
+  if (!on || n >= kCap) return;
+  while (created < 2 * (n + 1)) {
+    if (hipEventCreate(&ev[created]) != hipSuccess) return;
+    ++created;
+  }
+  fam[n] = family;
+  (void)hipEventRecord(ev[2 * n], s);
+}
+void Profiler::end(hipStream_t s) {
+  if (!on || n >= kCap || created < 2 * (n + 1)) return;
+  (void)hipEventRecord(ev[2 * n + 1], s);
+  ++n;
+}
+}  // namespace dc
+
+struct dc_ctx {
+  dc_config cfg;
+  int device = 0;
+  int n_cu = 256;
+  int lds_limit = 64 * 1024;
+  // one device arena for all scratch
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  ContractTmp tmp{};
+  BatchView ib{};           // context-owned batch used by dc_eval_candidates
+  void* act[2] = {nullptr, nullptr};
+  void* agg[2] = {nullptr, nullptr};
+  int* status = nullptr;    // [2]
+  int* totals = nullptr;    // [2]
+  int* h_pinned = nullptr;  // [4] pinned host mirror for status / totals
+  // weights
+  void* W = nullptr;
+  float* b = nullptr;
+  float* head = nullptr;
+  bool have_weights = false;
+  // base graphs
+  BaseGraphs bg{};
+  char* bg_mem = nullptr;
+  int max_gn = 0, max_ge = 0, min_need = 0;
+  bool have_graphs = false;
+  char* slab = nullptr;
+  size_t slab_stride = 0;
+  int slab_wgs = 0;
+  Profiler prof;
+  std::string err;
+};
+
+namespace {
+
+const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update", "readout_head"};
+
+size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Arena {
+  size_t off = 0;
+  char* base = nullptr;
+  template <typename T>
+  T* take(size_t count) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += al(count * sizeof(T));
+    return p;
+  }
+};
+
+struct Caps {
+  long long C, NB, EB, NN, NE;
+};
+Caps caps_of(const dc_config& c) {
+  Caps k;
+  k.C = c.max_cand;
+  k.NB = c.max_base_nodes;
+  k.EB = c.max_base_edges;
+  k.NN = c.max_nodes > 0 ? c.max_nodes : c.max_base_nodes;
+  k.NE = c.max_edges > 0 ? c.max_edges : c.max_base_edges;
+  return k;
+}
+
+// Lays out every scratch array; with base == nullptr only the size is computed.
+size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
+  const Caps k = caps_of(cfg);
+  const size_t es = cfg.dtype == DC_BF16 ? 2 : 4;
+  const size_t D = cfg.F > cfg.H ? cfg.F : cfg.H;
+  Arena a;
+  a.base = base;
+  int* status = a.take<int>(64);
+  int* totals = a.take<int>(64);
+  ContractTmp t;
+  t.tmp_eoff = a.take<int>(k.C + 1);
+  t.members = a.take<int>(k.NB + 1);
+  t.mstart = a.take<int>(k.NB + k.C + 1);
+  t.orp = a.take<int>(k.NB + k.C + 1);
+  t.irp = a.take<int>(k.NB + k.C + 1);
+  t.oc = a.take<int>(k.EB + 1);
+  t.ic = a.take<int>(k.EB + 1);
+  t.Gc = a.take<int>(k.C + 1);
+  t.Ec = a.take<int>(k.C + 1);
+  BatchView b;
+  b.node_off = a.take<int>(k.C + 1);
+  b.edge_off = a.take<int>(k.C + 1);
+  b.new_id = a.take<int>(k.NB + 1);
+  b.out_rowptr = a.take<int>(k.NN + 1);
+  b.in_rowptr = a.take<int>(k.NN + 1);
+  b.out_col = a.take<int>(k.NE + 1);
+  b.in_col = a.take<int>(k.NE + 1);
+  b.Xc = a.take<char>((size_t)(k.NN + 1) * cfg.F * es);
+  b.cap_nodes = k.NN;
+  b.cap_edges = k.NE;
+  void* act0 = a.take<char>((size_t)(k.NN + 1) * cfg.H * es);
+  void* act1 = a.take<char>((size_t)(k.NN + 1) * cfg.H * es);
+  void* agg0 = a.take<char>((size_t)(k.NN + 1) * D * es);
+  void* agg1 = a.take<char>((size_t)(k.NN + 1) * D * es);
+  if (ctx) {
+    ctx->status = status;
+    ctx->totals = totals;
+    ctx->tmp = t;
+    ctx->ib = b;
+    ctx->act[0] = act0;
+    ctx->act[1] = act1;
+    ctx->agg[0] = agg0;
+    ctx->agg[1] = agg1;
+  }
+  return a.off;
+}
+
+dc_status cfg_check(const dc_config* c, std::string* why) {
+  if (!c) return DC_ERR_INVALID_ARG;
+  if (c->dtype != DC_F32 && c->dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+  if (c->max_cand < 0 || c->max_base_nodes < 0 || c->max_base_edges < 0 || c->max_nodes < 0 || c->max_edges < 0)
+    return DC_ERR_INVALID_ARG;
+  if (!gnn_shape_supported(c->F, c->H, c->L)) {
+    if (why) *why = "need F % 16 == 0, H % 32 == 0, F,H <= 512, L >= 1";
+    return (c->F <= 0 || c->H <= 0 || c->L <= 0) ? DC_ERR_INVALID_ARG : DC_ERR_UNSUPPORTED;
+  }
+  const long long lim = 2000000000LL;
+  if (c->max_cand > lim || c->max_base_nodes + c->max_cand > lim || c->max_base_edges > lim) {
+    if (why) *why = "totals must fit in int32";
+    return DC_ERR_UNSUPPORTED;
+  }
+  return DC_OK;
+}
+
+dc_status fail(dc_ctx* ctx, dc_status st, const std::string& msg) {
+  if (ctx) ctx->err = msg;
+  return st;
+}
+
+dc_status hip_fail(dc_ctx* ctx, hipError_t e, const char* what) {
+  char buf[256];
+  snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+  if (ctx) ctx->err = buf;
+  return e == hipErrorOutOfMemory ? DC_ERR_OOM : DC_ERR_HIP;
+}
+
+dc_status do_contract(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                      const int32_t* group_id, const BatchView& out, hipStream_t s) {
+  ContractLaunch a;
+  a.bg = ctx->bg;
+  a.max_graph_nodes = ctx->max_gn;
+  a.max_graph_edges = ctx->max_ge;
+  a.min_graph_need = ctx->min_need;
+  a.n_cand = n_cand;
+  a.cand_graph = cand_graph;
+  a.cand_off = cand_off;
+  a.group_id = group_id;
+  a.tmp = ctx->tmp;
+  a.out = out;
+  a.F = ctx->cfg.F;
+  a.bf16 = ctx->cfg.dtype == DC_BF16;
+  a.max_base_nodes = ctx->cfg.max_base_nodes;
+  a.max_base_edges = ctx->cfg.max_base_edges;
+  a.status = ctx->status;
+  a.totals = ctx->totals;
+  a.slab = ctx->slab;
+  a.slab_stride = ctx->slab_stride;
+  a.slab_wgs = ctx->slab_wgs;
+  a.lds_limit = ctx->lds_limit;
+  hipError_t e = launch_contract(a, ctx->prof.on ? &ctx->prof : nullptr, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "contraction launch");
+  return DC_OK;
+}
+
+dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred, hipStream_t s) {
+  GnnArgs g;
+  g.n_cand = n_cand;
+  g.node_off = in.node_off;
+  g.out_rowptr = in.out_rowptr;
+  g.out_col = in.out_col;
+  g.in_rowptr = in.in_rowptr;
+  g.in_col = in.in_col;
+  g.Xc = in.Xc;
+  g.F = ctx->cfg.F;
+  g.H = ctx->cfg.H;
+  g.L = ctx->cfg.L;
+  g.bf16 = ctx->cfg.dtype == DC_BF16;
+  g.W = ctx->W;
+  g.b = ctx->b;
+  g.head = ctx->head;
+  g.act[0] = ctx->act[0];
+  g.act[1] = ctx->act[1];
+  g.agg[0] = ctx->agg[0];
+  g.agg[1] = ctx->agg[1];
+  g.pred = pred;
+  g.status = ctx->status;
+  g.n_cu = ctx->n_cu;
+  hipError_t e = launch_gnn_forward(g, ctx->prof.on ? &ctx->prof : nullptr, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "forward launch");
+  return DC_OK;
+}
+
+// Device-side guard for dc_gnn_forward on caller-provided batches.
+__global__ void check_batch_kernel(const int* node_off, int C, long long max_nodes, int* status) {
+  if (node_off[C] > max_nodes || node_off[0] != 0) set_error(status, (int)DC_ERR_CAPACITY);
+}
+
+__global__ void empty_batch_kernel(int* node_off, int* edge_off, int* orp, int* irp, int* totals) {
+  node_off[0] = 0;
+  edge_off[0] = 0;
+  orp[0] = 0;
+  irp[0] = 0;
+  totals[0] = 0;
+  totals[1] = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dc_workspace_bytes(const dc_config* cfg) {
+  if (cfg_check(cfg, nullptr) != DC_OK) return 0;
+  return carve(*cfg, nullptr, nullptr);
+}
+
+dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
+  if (!out) return DC_ERR_INVALID_ARG;
+  *out = nullptr;
+  std::string why;
+  dc_status st = cfg_check(cfg, &why);
+  if (st != DC_OK) return st;
+  dc_ctx* ctx = new (std::nothrow) dc_ctx();
+  if (!ctx) return DC_ERR_OOM;
+  ctx->cfg = *cfg;
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e != hipSuccess) {
+    delete ctx;
+    return DC_ERR_HIP;
+  }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess) {
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    size_t lds = prop.sharedMemPerBlock;
+    if (prop.sharedMemPerBlockOptin > lds) lds = prop.sharedMemPerBlockOptin;
+    if (lds > 160 * 1024) lds = 160 * 1024;
+    // keep room for the kernel's static LDS
+    ctx->lds_limit = (int)lds - 1024;
+    if (ctx->lds_limit > 48 * 1024 && contract_set_lds_limit(ctx->lds_limit) != hipSuccess) {
+      (void)hipGetLastError();
+      ctx->lds_limit = 48 * 1024;
+    }
+  }
+  ctx->arena_bytes = carve(*cfg, nullptr, nullptr);
+  e = hipMalloc(reinterpret_cast<void**>(&ctx->arena), ctx->arena_bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return DC_ERR_OOM;
+  }
+  carve(*cfg, ctx->arena, ctx);
+  e = hipMemset(ctx->status, 0, 64 * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(ctx->totals, 0, 64 * sizeof(int));
+  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 64 * sizeof(int), hipHostMallocDefault);
+  const size_t es = cfg->dtype == DC_BF16 ? 2 : 4;
+  const size_t HH = (size_t)cfg->H * cfg->H;
+  if (e == hipSuccess) e = hipMalloc(&ctx->W, packed_weight_elems(cfg->F, cfg->H, cfg->L) * es);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->b), (size_t)cfg->L * cfg->H * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->head), (2 * HH + 3 * cfg->H + 1) * sizeof(float));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    dc_destroy(ctx);
+    return e == hipErrorOutOfMemory ? DC_ERR_OOM : DC_ERR_HIP;
+  }
+  *out = ctx;
+  return DC_OK;
+}
+
+dc_status dc_destroy(dc_ctx* ctx) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  (void)hipDeviceSynchronize();
+  for (int i = 0; i < ctx->prof.created; ++i) (void)hipEventDestroy(ctx->prof.ev[i]);
+  if (ctx->arena) (void)hipFree(ctx->arena);
+  if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
+  if (ctx->W) (void)hipFree(ctx->W);
+  if (ctx->b) (void)hipFree(ctx->b);
+  if (ctx->head) (void)hipFree(ctx->head);
+  if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
+  if (ctx->slab) (void)hipFree(ctx->slab);
+  delete ctx;
+  return DC_OK;
+}
+
+dc_status dc_set_weights(dc_ctx* ctx, const float* W_layers, const float* b_layers, const float* head,
+                         void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!W_layers || !b_layers || !head) return fail(ctx, DC_ERR_INVALID_ARG, "null weight pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dc_config& c = ctx->cfg;
+  const int bf16 = c.dtype == DC_BF16;
+  const size_t es = bf16 ? 2 : 4;
+  const size_t nW = packed_weight_elems(c.F, c.H, c.L);
+  std::vector<char> packed(nW * es);
+  pack_weights_host(W_layers, c.F, c.H, c.L, bf16, packed.data());
+  const size_t HH = (size_t)c.H * c.H;
+  std::vector<float> hd(head, head + 2 * HH + 3 * c.H + 1);
+  if (bf16) {
+    // the head matrices are stored as bf16-representable fp32 values
+    auto rnd = [](float x) {
+      unsigned u;
+      memcpy(&u, &x, 4);
+      if ((u & 0x7F800000u) == 0x7F800000u) return x;
+      u += 0x7FFFu + ((u >> 16) & 1u);
+      u &= 0xFFFF0000u;
+      memcpy(&x, &u, 4);
+      return x;
+    };
+    for (size_t i = 0; i < HH; ++i) hd[i] = rnd(hd[i]);
+    for (size_t i = 0; i < HH; ++i) hd[HH + c.H + i] = rnd(hd[HH + c.H + i]);
+    for (int i = 0; i < c.H; ++i) hd[2 * HH + 2 * c.H + i] = rnd(hd[2 * HH + 2 * c.H + i]);
+  }
+  hipError_t e = hipMemcpyAsync(ctx->W, packed.data(), nW * es, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(ctx->b, b_layers, (size_t)c.L * c.H * sizeof(float), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(ctx->head, hd.data(), hd.size() * sizeof(float), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);   // host staging buffers die at return
+  if (e != hipSuccess) return hip_fail(ctx, e, "dc_set_weights copy");
+  ctx->have_weights = true;
+  return DC_OK;
+}
+
+dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_node_off, const int32_t* g_edge_off,
+                             const int32_t* rowptr, const int32_t* col, const float* X, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (n_graphs <= 0 || !g_node_off || !g_edge_off || !rowptr || !X)
+    return fail(ctx, DC_ERR_INVALID_ARG, "null pointer or no graphs");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (g_node_off[0] != 0 || g_edge_off[0] != 0) return fail(ctx, DC_ERR_BAD_GRAPH, "offsets must start at 0");
+  int max_gn = 0, max_ge = 0, min_need = INT32_MAX;
+  for (int b = 0; b < n_graphs; ++b) {
+    const long long n = (long long)g_node_off[b + 1] - g_node_off[b];
+    const long long e = (long long)g_edge_off[b + 1] - g_edge_off[b];
+    if (n < 0 || e < 0) return fail(ctx, DC_ERR_BAD_GRAPH, "offsets not monotone");
+    if (n >= 65536) return fail(ctx, DC_ERR_UNSUPPORTED, "a base graph must have fewer than 65536 nodes");
+    if (e > 0 && !col) return fail(ctx, DC_ERR_INVALID_ARG, "null col");
+    const int32_t* rp = rowptr + g_node_off[b] + b;
+    if (rp[0] != 0 || rp[n] != e) return fail(ctx, DC_ERR_BAD_GRAPH, "rowptr must run from 0 to the edge count");
+    for (long long v = 0; v < n; ++v)
+      if (rp[v + 1] < rp[v]) return fail(ctx, DC_ERR_BAD_GRAPH, "rowptr not monotone");
+    const int32_t* ci = col + g_edge_off[b];
+    for (long long k = 0; k < e; ++k)
+      if (ci[k] < 0 || ci[k] >= n) return fail(ctx, DC_ERR_BAD_GRAPH, "col out of range");
+    if (n > max_gn) max_gn = (int)n;
+    if (e > max_ge) max_ge = (int)e;
+    const int need = contract_working_set_bytes((int)n, (int)e);
+    if (need < min_need) min_need = need;
+  }
+  const long long NT = g_node_off[n_graphs], ET = g_edge_off[n_graphs];
+  // predecessor lists (transpose), sources ascending
+  std::vector<int32_t> crp((size_t)NT + n_graphs), cci((size_t)(ET > 0 ? ET : 1));
+  for (int b = 0; b < n_graphs; ++b) {
+    const int n = g_node_off[b + 1] - g_node_off[b];
+    const int32_t* rp = rowptr + g_node_off[b] + b;
+    const int32_t* ci = col + g_edge_off[b];
+    int32_t* trp = crp.data() + g_node_off[b] + b;
+    int32_t* tci = cci.data() + g_edge_off[b];
+    for (int v = 0; v <= n; ++v) trp[v] = 0;
+    for (int k = 0; k < rp[n]; ++k) trp[ci[k] + 1] += 1;
+    for (int v = 0; v < n; ++v) trp[v + 1] += trp[v];
+    std::vector<int32_t> cur(trp, trp + n);
+    for (int u = 0; u < n; ++u)
+      for (int k = rp[u]; k < rp[u + 1]; ++k) tci[cur[ci[k]]++] = u;
+  }
+  // one device block: gno | geo | rowptr | col | crowptr | ccol | X
+  Arena a;
+  a.take<int>(n_graphs + 1);
+  a.take<int>(n_graphs + 1);
+  a.take<int>(NT + n_graphs);
+  a.take<int>(ET + 1);
+  a.take<int>(NT + n_graphs);
+  a.take<int>(ET + 1);
+  a.take<float>((size_t)NT * ctx->cfg.F + 4);
+  char* mem = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&mem), a.off);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, DC_ERR_OOM, "base graph allocation failed");
+  }
+  Arena d;
+  d.base = mem;
+  int* d_gno = d.take<int>(n_graphs + 1);
+  int* d_geo = d.take<int>(n_graphs + 1);
+  int* d_rp = d.take<int>(NT + n_graphs);
+  int* d_ci = d.take<int>(ET + 1);
+  int* d_crp = d.take<int>(NT + n_graphs);
+  int* d_cci = d.take<int>(ET + 1);
+  float* d_X = d.take<float>((size_t)NT * ctx->cfg.F + 4);
+  e = hipMemcpyAsync(d_gno, g_node_off, (n_graphs + 1) * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_geo, g_edge_off, (n_graphs + 1) * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_rp, rowptr, (size_t)(NT + n_graphs) * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && ET > 0) e = hipMemcpyAsync(d_ci, col, (size_t)ET * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_crp, crp.data(), (size_t)(NT + n_graphs) * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && ET > 0) e = hipMemcpyAsync(d_cci, cci.data(), (size_t)ET * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && NT > 0) e = hipMemcpyAsync(d_X, X, (size_t)NT * ctx->cfg.F * sizeof(float), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  char* slab = nullptr;
+  size_t slab_stride = 0;
+  int slab_wgs = 0;
+  if (e == hipSuccess && contract_working_set_bytes(max_gn, max_ge) > ctx->lds_limit) {
+    slab_stride = al((size_t)contract_working_set_bytes(max_gn, max_ge));
+    slab_wgs = ctx->n_cu * 2;
+    e = hipMalloc(reinterpret_cast<void**>(&slab), slab_stride * slab_wgs);
+  }
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(mem);
+    return hip_fail(ctx, e, "dc_set_base_graphs copy");
+  }
+  (void)hipDeviceSynchronize();   // earlier calls may still read the old graphs
+  if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
+  if (ctx->slab) (void)hipFree(ctx->slab);
+  ctx->bg_mem = mem;
+  ctx->slab = slab;
+  ctx->slab_stride = slab_stride;
+  ctx->slab_wgs = slab_wgs;
+  ctx->bg.n_graphs = n_graphs;
+  ctx->bg.gno = d_gno;
+  ctx->bg.geo = d_geo;
+  ctx->bg.rowptr = d_rp;
+  ctx->bg.col = d_ci;
+  ctx->bg.crowptr = d_crp;
+  ctx->bg.ccol = d_cci;
+  ctx->bg.X = d_X;
+  ctx->max_gn = max_gn;
+  ctx->max_ge = max_ge;
+  ctx->min_need = min_need;
+  ctx->have_graphs = true;
+  return DC_OK;
+}
+
+dc_status dc_contract_graphs(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                             const int32_t* group_id, dc_batch* out, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!out || n_cand < 0) return fail(ctx, DC_ERR_INVALID_ARG, "null batch or negative count");
+  if (!ctx->have_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_base_graphs has not been called");
+  if (n_cand > ctx->cfg.max_cand) return fail(ctx, DC_ERR_CAPACITY, "n_cand exceeds max_cand");
+  if (!out->node_off || !out->edge_off || !out->new_id || !out->out_rowptr || !out->out_col || !out->in_rowptr ||
+      !out->in_col || !out->Xc || out->cap_nodes < 0 || out->cap_edges < 0)
+    return fail(ctx, DC_ERR_INVALID_ARG, "dc_batch has a null array or negative capacity");
+  if (n_cand > 0 && (!cand_graph || !cand_off || !group_id)) return fail(ctx, DC_ERR_INVALID_ARG, "null candidate array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  out->n_cand = n_cand;
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  BatchView v;
+  v.node_off = out->node_off;
+  v.edge_off = out->edge_off;
+  v.new_id = out->new_id;
+  v.out_rowptr = out->out_rowptr;
+  v.out_col = out->out_col;
+  v.in_rowptr = out->in_rowptr;
+  v.in_col = out->in_col;
+  v.Xc = out->Xc;
+  v.cap_nodes = out->cap_nodes;
+  v.cap_edges = out->cap_edges;
+  if (n_cand == 0) {
+    hipLaunchKernelGGL(empty_batch_kernel, dim3(1), dim3(1), 0, s, out->node_off, out->edge_off, out->out_rowptr,
+                       out->in_rowptr, ctx->totals);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? DC_OK : hip_fail(ctx, e, "empty batch");
+  }
+  return do_contract(ctx, n_cand, cand_graph, cand_off, group_id, v, s);
+}
+
+dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!in || in->n_cand < 0) return fail(ctx, DC_ERR_INVALID_ARG, "null batch or negative count");
+  if (!ctx->have_weights) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_weights has not been called");
+  if (in->n_cand > ctx->cfg.max_cand) return fail(ctx, DC_ERR_CAPACITY, "n_cand exceeds max_cand");
+  if (in->n_cand == 0) return DC_OK;
+  if (!pred || !in->node_off || !in->out_rowptr || !in->out_col || !in->in_rowptr || !in->in_col || !in->Xc)
+    return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  const Caps k = caps_of(ctx->cfg);
+  hipLaunchKernelGGL(check_batch_kernel, dim3(1), dim3(1), 0, s, in->node_off, in->n_cand, k.NN, ctx->status);
+  BatchView v;
+  v.node_off = in->node_off;
+  v.edge_off = in->edge_off;
+  v.new_id = in->new_id;
+  v.out_rowptr = in->out_rowptr;
+  v.out_col = in->out_col;
+  v.in_rowptr = in->in_rowptr;
+  v.in_col = in->in_col;
+  v.Xc = in->Xc;
+  v.cap_nodes = in->cap_nodes;
+  v.cap_edges = in->cap_edges;
+  return do_forward(ctx, in->n_cand, v, pred, s);
+}
+
+dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                             const int32_t* group_id, float* pred, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (n_cand < 0) return fail(ctx, DC_ERR_INVALID_ARG, "negative count");
+  if (!ctx->have_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_base_graphs has not been called");
+  if (!ctx->have_weights) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_weights has not been called");
+  if (n_cand > ctx->cfg.max_cand) return fail(ctx, DC_ERR_CAPACITY, "n_cand exceeds max_cand");
+  if (n_cand == 0) return DC_OK;
+  if (!cand_graph || !cand_off || !group_id || !pred) return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  dc_status st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s);
+  if (st != DC_OK) return st;
+  return do_forward(ctx, n_cand, ctx->ib, pred, s);
+}
+
+dc_status dc_check(dc_ctx* ctx, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(ctx->h_pinned, ctx->status, 2 * sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipMemsetAsync(ctx->status + 1, 0, sizeof(int), s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "dc_check");
+  const int code = ctx->h_pinned[1];
+  if (code != 0) {
+    ctx->err = code == DC_ERR_BAD_PARTITION ? "device: label out of range or candidate/base-graph mismatch"
+             : code == DC_ERR_CAPACITY      ? "device: sizes exceed the configured or provided capacity"
+                                            : "device: error";
+  }
+  return static_cast<dc_status>(code);
+}
+
+dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* stream) {
+  if (!ctx || !n_nodes || !n_edges) return DC_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(ctx->h_pinned + 8, ctx->totals, 2 * sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "dc_last_totals");
+  *n_nodes = ctx->h_pinned[8];
+  *n_edges = ctx->h_pinned[9];
+  return DC_OK;
+}
+
+const char* dc_last_error(const dc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+dc_status dc_profile_begin(dc_ctx* ctx) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  ctx->prof.on = true;
+  ctx->prof.n = 0;
+  return DC_OK;
+}
+
+int32_t dc_profile_end(dc_ctx* ctx, const char** names, float* total_ms, int32_t* launches, int32_t cap) {
+  if (!ctx) return 0;
+  ctx->prof.on = false;
+  float ms[kFamCount] = {0};
+  int cnt[kFamCount] = {0};
+  for (int i = 0; i < ctx->prof.n; ++i) {
+    if (hipEventSynchronize(ctx->prof.ev[2 * i + 1]) != hipSuccess) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, ctx->prof.ev[2 * i], ctx->prof.ev[2 * i + 1]) == hipSuccess) {
+      ms[ctx->prof.fam[i]] += t;
+      cnt[ctx->prof.fam[i]] += 1;
+    }
+  }
+  ctx->prof.n = 0;
+  for (int f = 0; f < kFamCount && f < cap; ++f) {
+    if (names) names[f] = kFamilyNames[f];
+    if (total_ms) total_ms[f] = ms[f];
+    if (launches) launches[f] = cnt[f];
+  }
+  return kFamCount;
+}
+
+}  // extern "C"

@@ -1,0 +1,123 @@
+// Internal declarations shared by the HIP sources of libdisco (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "disco.h"
+
+namespace dc {
+
+// Device status words: [0] first error of the running call (later kernels of the
+// call read it and return without writing), [1] first error since dc_check.
+__device__ __forceinline__ void set_error(int* status, int code) {
+  atomicCAS(&status[0], 0, code);
+  atomicCAS(&status[1], 0, code);
+}
+
+// Base graphs as the kernels see them (device pointers).
+struct BaseGraphs {
+  int n_graphs;
+  const int* gno;      // [n_graphs+1] node offsets
+  const int* geo;      // [n_graphs+1] edge offsets
+  const int* rowptr;   // successors: graph b at gno[b] + b, N_b+1 local entries
+  const int* col;      // graph b at geo[b], local node numbers
+  const int* crowptr;  // predecessors, same layout
+  const int* ccol;
+  const float* X;      // [sum N_b, F]
+};
+
+// Scratch written by the per-candidate contraction kernel and consumed by the
+// finalise kernel.  Node-indexed arrays use slot cand_off[c] + c (one extra
+// entry per candidate), edge-indexed arrays use slot tmp_eoff[c].
+struct ContractTmp {
+  int* tmp_eoff;   // [C+1] exclusive scan of base edge counts
+  int* members;    // [sum N] base nodes grouped by contracted node, ascending inside a group
+  int* mstart;     // [sum N + C] start of each group in members (G+1 entries per candidate)
+  int* orp;        // [sum N + C] local out rowptr (G+1 entries)
+  int* irp;        // [sum N + C] local in rowptr
+  int* oc;         // [sum E] local out columns
+  int* ic;         // [sum E] local in columns
+  int* Gc;         // [C] contracted node count
+  int* Ec;         // [C] contracted edge count
+};
+
+struct BatchView {
+  int* node_off;
+  int* edge_off;
+  int* new_id;
+  int* out_rowptr;
+  int* out_col;
+  int* in_rowptr;
+  int* in_col;
+  void* Xc;
+  long long cap_nodes;
+  long long cap_edges;
+};
+
+// Optional per-kernel timing with HIP events on the launch stream.
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamReadout, kFamCount };
+struct Profiler {
+  bool on = false;
+  static constexpr int kCap = 4096;
+  hipEvent_t ev[2 * kCap];
+  int fam[kCap];
+  int n = 0;
+  int created = 0;
+  void begin(int family, hipStream_t s);
+  void end(hipStream_t s);
+};
+
+struct ContractLaunch {
+  BaseGraphs bg;
+  int max_graph_nodes, max_graph_edges;   // largest base graph
+  int min_graph_need;                      // smallest per-graph working-set bytes
+  int n_cand;
+  const int* cand_graph;
+  const int* cand_off;
+  const int* group_id;
+  ContractTmp tmp;
+  BatchView out;
+  int F, bf16;
+  long long max_base_nodes, max_base_edges;
+  int* status;
+  int* totals;       // [2] contracted nodes, edges of this call
+  char* slab;        // global working sets for graphs that do not fit in LDS
+  size_t slab_stride;
+  int slab_wgs;
+  int lds_limit;
+};
+hipError_t launch_contract(const ContractLaunch& a, Profiler* prof, hipStream_t s);
+int contract_working_set_bytes(int n_nodes, int n_edges);
+hipError_t contract_set_lds_limit(int bytes);
+
+struct GnnArgs {
+  int n_cand;
+  const int* node_off;
+  const int* out_rowptr;
+  const int* out_col;
+  const int* in_rowptr;
+  const int* in_col;
+  const void* Xc;
+  int F, H, L, bf16;
+  const void* W;        // layer matrices in device layout
+  const float* b;       // biases fp32
+  const float* head;    // fp32 head (bf16-representable matrices on the bf16 path)
+  void* act[2];         // ping/pong activations [max_nodes, H]
+  void* agg[2];         // predecessor mean / successor mean [max_nodes, max(F,H)]
+  float* pred;
+  const int* status;
+  int n_cu;
+};
+hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s);
+// Elements (of the storage dtype) of all layer matrices in device layout.
+size_t packed_weight_elems(int F, int H, int L);
+// Host side: converts row-major fp32 W^l into the device layout of the dtype
+// (fp32: unchanged; bf16: [k/8][H][8] so that a lane's 8 consecutive k sit together).
+void pack_weights_host(const float* W_layers, int F, int H, int L, int bf16, void* dst);
+bool gnn_shape_supported(int F, int H, int L);
+
+__global__ void reset_status_kernel(int* status);
+
+static inline __host__ __device__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+}  // namespace dc

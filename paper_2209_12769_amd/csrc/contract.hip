@@ -1,0 +1,475 @@
+// Graph contraction of fusion candidates (gfx950).
+//
+// A candidate is a base training DAG plus one label per node; nodes with equal
+// labels form one fused op or one fused gradient tensor (strategy space of
+// Sec. 3.2).  The fused op is the subgraph of its original ops (Sec. 3.3), so the
+// candidate module is the quotient graph: dependencies inside a group vanish,
+// those that cross groups stay, parallel ones collapse (0/1 adjacency,
+// Sec. 3.3.1).  Node features are summed per group (Sec. 2.3: the size of a fused
+// tensor is the sum of its members' sizes).
+//
+// One workgroup contracts one candidate entirely in LDS (or, for base graphs
+// that do not fit, in a per-workgroup slab of global memory with the same
+// layout).  Results go to per-candidate scratch slots; after a scan of the
+// contracted sizes over the batch a second kernel places them block-diagonally
+// and reduces the features.
+//
+// Output is canonical, hence unique: groups are numbered by ascending smallest
+// member index and every neighbour list is ascending.
+#include <limits.h>
+
+#include "common.h"
+
+namespace dc {
+namespace {
+
+constexpr int kCT = 512;        // threads per contraction workgroup
+constexpr int kCW = kCT / 64;   // waves per workgroup
+constexpr int kSmallRow = 32;   // rows up to this length are sorted by one thread
+constexpr unsigned short kSelf = 0xFFFF;
+
+typedef unsigned short u16;
+
+// Byte offsets of the per-candidate working arrays (same on host and device).
+struct Slab {
+  int A, MS, UL, BM, NID, MEM, RAW, total;
+};
+__host__ __device__ inline int align16(int x) { return (x + 15) & ~15; }
+__host__ __device__ inline Slab slab_layout(int N, int E) {
+  Slab s;
+  int o = 0;
+  s.A = o;   o = align16(o + 4 * (N + 1));          // int   [N+1] label->first / cursors / raw offsets
+  s.MS = o;  o = align16(o + 4 * (N + 1));          // int   [N+1] group start in MEM
+  s.UL = o;  o = align16(o + 4 * (N + 1));          // int   [N+1] flags / row lengths / local rowptr
+  s.BM = o;  o = align16(o + 4 * kCW * ((N + 31) / 32 + 1));  // per-wave bitmaps
+  s.NID = o; o = align16(o + 2 * (N + 1));          // u16   [N] contracted id per base node
+  s.MEM = o; o = align16(o + 2 * (N + 1));          // u16   [N] base nodes grouped by contracted id
+  s.RAW = o; o = align16(o + 2 * (E + 1));          // u16   [E] remapped neighbours, grouped by row
+  s.total = o;
+  return s;
+}
+
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int y = __shfl_up(x, o, 64);
+    if (lane >= o) x += y;
+  }
+  return x;
+}
+
+// Exclusive scan of in[0..n) into out[0..n) (may alias) by the whole workgroup;
+// returns the total.  Each thread owns a contiguous chunk.  Ends with a barrier.
+__device__ __forceinline__ int block_exscan(const int* in, int* out, int n, int* wsum) {
+  const int t = threadIdx.x, T = blockDim.x;
+  const int K = (n + T - 1) / T;
+  const int lo = min(t * K, n), hi = min(lo + K, n);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += in[i];
+  const int inc = wave_incl_scan(s);
+  if ((t & 63) == 63) wsum[t >> 6] = inc;
+  __syncthreads();
+  int woff = 0, total = 0;
+  const int nw = T >> 6;
+  for (int i = 0; i < nw; ++i) {
+    int x = wsum[i];
+    if (i < (t >> 6)) woff += x;
+    total += x;
+  }
+  int run = woff + inc - s;
+  for (int i = lo; i < hi; ++i) {
+    int x = in[i];
+    out[i] = run;
+    run += x;
+  }
+  __syncthreads();
+  return total;
+}
+
+__device__ __forceinline__ void insertion_sort(u16* a, int n) {
+  for (int i = 1; i < n; ++i) {
+    u16 key = a[i];
+    int j = i - 1;
+    while (j >= 0 && a[j] > key) {
+      a[j + 1] = a[j];
+      --j;
+    }
+    a[j + 1] = key;
+  }
+}
+
+// The body works on plain pointers; instantiated once with LDS pointers and
+// once with global-memory pointers.
+template <bool kLds>
+__device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b, int N, char* base, const Slab& L,
+                                             const int* cand_off, const int* label, const ContractTmp& tmp,
+                                             int* new_id_out, int* status, int* wsum) {
+  const int t = threadIdx.x, T = blockDim.x, lane = t & 63, wave = t >> 6;
+  int* A = reinterpret_cast<int*>(base + L.A);
+  int* MS = reinterpret_cast<int*>(base + L.MS);
+  int* UL = reinterpret_cast<int*>(base + L.UL);
+  const int bm_words = (N + 31) / 32 + 1;
+  unsigned* BM = reinterpret_cast<unsigned*>(base + L.BM) + wave * bm_words;
+  u16* NID = reinterpret_cast<u16*>(base + L.NID);
+  u16* MEM = reinterpret_cast<u16*>(base + L.MEM);
+  u16* RAW = reinterpret_cast<u16*>(base + L.RAW);
+
+  const int coff = cand_off[c];
+  const int* lab = label + coff;
+  int* nid_out = new_id_out + coff;
+  const int nslot = coff + c;
+  const int eslot = tmp.tmp_eoff[c];
+
+  // ---- relabel: groups numbered by ascending smallest member -----------------
+  int bad = 0;
+  for (int v = t; v < N; v += T) {
+    A[v] = INT_MAX;
+    int l = lab[v];
+    bad |= (l < 0) | (l >= N);
+  }
+  {
+    unsigned* bmall = reinterpret_cast<unsigned*>(base + L.BM);
+    for (int i = t; i < kCW * bm_words; i += T) bmall[i] = 0u;
+  }
+  if (__syncthreads_or(bad)) {
+    if (t == 0) {
+      set_error(status, (int)DC_ERR_BAD_PARTITION);
+      tmp.Gc[c] = 0;
+      tmp.Ec[c] = 0;
+    }
+    return;
+  }
+  for (int v = t; v < N; v += T) atomicMin(&A[lab[v]], v);
+  __syncthreads();
+  for (int v = t; v < N; v += T) UL[v] = (A[lab[v]] == v) ? 1 : 0;
+  __syncthreads();
+  const int G = block_exscan(UL, UL, N, wsum);
+  if (t == 0) UL[N] = G;
+  __syncthreads();
+  for (int v = t; v < N; v += T)
+    if (UL[v + 1] != UL[v]) A[lab[v]] = UL[v];   // head of its group: rank among heads
+  __syncthreads();
+  for (int v = t; v < N; v += T) {
+    int g = A[lab[v]];
+    NID[v] = (u16)g;
+    nid_out[v] = g;
+  }
+  __syncthreads();
+
+  // ---- member lists: counting sort by group, ascending inside a group ---------
+  for (int g = t; g < G; g += T) A[g] = 0;
+  __syncthreads();
+  for (int v = t; v < N; v += T) atomicAdd(&A[NID[v]], 1);
+  __syncthreads();
+  block_exscan(A, MS, G, wsum);
+  if (t == 0) MS[G] = N;
+  __syncthreads();
+  for (int g = t; g < G; g += T) A[g] = MS[g];
+  __syncthreads();
+  for (int v = t; v < N; v += T) {
+    int pos = atomicAdd(&A[NID[v]], 1);
+    MEM[pos] = (u16)v;
+  }
+  __syncthreads();
+  {
+    int big = 0;
+    for (int g = t; g < G; g += T) {
+      int s = MS[g], n = MS[g + 1] - s;
+      if (n > kSmallRow) big = 1;
+      else if (n > 1) insertion_sort(MEM + s, n);
+    }
+    if (__syncthreads_or(big)) {
+      // large groups: ordered compaction by one wave each
+      for (int g = wave; g < G; g += kCW) {
+        const int s = MS[g], n = MS[g + 1] - s;
+        if (n <= kSmallRow) continue;
+        int cnt = 0;
+        for (int v0 = 0; v0 < N; v0 += 64) {
+          int v = v0 + lane;
+          bool f = v < N && NID[v] == g;
+          unsigned long long m = __ballot(f);
+          if (f) MEM[s + cnt + __popcll(m & ((1ull << lane) - 1ull))] = (u16)v;
+          cnt += __popcll(m);
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int i = t; i < N; i += T) tmp.members[coff + i] = MEM[i];
+  for (int g = t; g <= G; g += T) tmp.mstart[nslot + g] = MS[g];
+
+  // ---- neighbour lists: successors (dir 0), then predecessors (dir 1) ----------
+  int Ec = 0;
+  for (int dir = 0; dir < 2; ++dir) {
+    const int* rp = (dir == 0 ? bg.rowptr : bg.crowptr) + bg.gno[b] + b;
+    const int* ci = (dir == 0 ? bg.col : bg.ccol) + bg.geo[b];
+    int* t_rp = (dir == 0 ? tmp.orp : tmp.irp) + nslot;
+    int* t_ci = (dir == 0 ? tmp.oc : tmp.ic) + eslot;
+
+    for (int i = t; i < N; i += T) {
+      int u = MEM[i];
+      A[i] = rp[u + 1] - rp[u];
+    }
+    __syncthreads();
+    const int Eraw = block_exscan(A, A, N, wsum);
+    if (t == 0) A[N] = Eraw;
+    __syncthreads();
+    for (int i = t; i < N; i += T) {
+      const int u = MEM[i];
+      const int g = NID[u];
+      int o = A[i];
+      for (int e = rp[u]; e < rp[u + 1]; ++e) {
+        int w = NID[ci[e]];
+        RAW[o++] = (w == g) ? kSelf : (u16)w;
+      }
+    }
+    __syncthreads();
+    int big = 0;
+    for (int g = t; g < G; g += T) {
+      const int s = A[MS[g]], n = A[MS[g + 1]] - s;
+      if (n > kSmallRow) {
+        big = 1;
+      } else {
+        u16* a = RAW + s;
+        insertion_sort(a, n);
+        int m = 0;
+        for (int i = 0; i < n; ++i) {
+          u16 x = a[i];
+          if (x == kSelf) break;
+          if (m == 0 || a[m - 1] != x) a[m++] = x;
+        }
+        UL[g] = m;
+      }
+    }
+    if (__syncthreads_or(big)) {
+      // long rows: mark neighbours in a per-wave bitmap, then list the set bits
+      const int W = (G + 31) / 32;
+      for (int g = wave; g < G; g += kCW) {
+        const int s = A[MS[g]], n = A[MS[g + 1]] - s;
+        if (n <= kSmallRow) continue;
+        for (int i = lane; i < n; i += 64) {
+          u16 x = RAW[s + i];
+          if (x != kSelf) atomicOr(&BM[x >> 5], 1u << (x & 31));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        int cnt = 0;
+        for (int w0 = 0; w0 < W; w0 += 64) {
+          const int w = w0 + lane;
+          unsigned bits = (w < W) ? BM[w] : 0u;
+          if (bits) BM[w] = 0u;
+          const int pc = __popc(bits);
+          const int inc = wave_incl_scan(pc);
+          int o = s + cnt + inc - pc;
+          while (bits) {
+            int bpos = __ffs(bits) - 1;
+            RAW[o++] = (u16)((w << 5) + bpos);
+            bits &= bits - 1;
+          }
+          cnt += __shfl(inc, 63, 64);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        if (lane == 0) UL[g] = cnt;
+      }
+      __syncthreads();
+    }
+    Ec = block_exscan(UL, UL, G, wsum);
+    if (t == 0) UL[G] = Ec;
+    __syncthreads();
+    for (int g = t; g <= G; g += T) t_rp[g] = UL[g];
+    for (int g = t; g < G; g += T) {
+      const int s = A[MS[g]], o = UL[g], n = UL[g + 1] - o;
+      for (int k = 0; k < n; ++k) t_ci[o + k] = RAW[s + k];
+    }
+    __syncthreads();
+  }
+  if (t == 0) {
+    tmp.Gc[c] = G;
+    tmp.Ec[c] = Ec;
+  }
+}
+
+extern __shared__ __attribute__((aligned(16))) char dc_smem[];
+
+template <bool kLds>
+__global__ __launch_bounds__(kCT) void contract_kernel(BaseGraphs bg, int C, const int* cand_graph,
+                                                        const int* cand_off, const int* label, ContractTmp tmp,
+                                                        int* new_id_out, int* status, char* gslab,
+                                                        size_t slab_stride, int lds_bytes) {
+  __shared__ int wsum[kCW];
+  if (status[0] != 0) return;
+  for (int c = blockIdx.x; c < C; c += gridDim.x) {
+    const int b = cand_graph[c];
+    const int N = bg.gno[b + 1] - bg.gno[b];
+    const int E = bg.geo[b + 1] - bg.geo[b];
+    const Slab L = slab_layout(N, E);
+    const bool fits = L.total <= lds_bytes;
+    if (fits != kLds) continue;
+    if (kLds) {
+      contract_one<true>(bg, c, b, N, dc_smem, L, cand_off, label, tmp, new_id_out, status, wsum);
+    } else {
+      contract_one<false>(bg, c, b, N, gslab + (size_t)blockIdx.x * slab_stride, L, cand_off, label, tmp,
+                          new_id_out, status, wsum);
+    }
+    __syncthreads();
+  }
+}
+
+// Validates the candidate list and scans the base edge counts (one workgroup).
+__global__ __launch_bounds__(1024) void prep_kernel(BaseGraphs bg, int C, const int* cand_graph, const int* cand_off,
+                                                     int* tmp_eoff, long long max_base_nodes,
+                                                     long long max_base_edges, int* status) {
+  __shared__ int wsum[16];
+  const int t = threadIdx.x, T = blockDim.x;
+  int bad = 0;
+  for (int c = t; c < C; c += T) {
+    const int b = cand_graph[c];
+    int e = 0;
+    if (b < 0 || b >= bg.n_graphs) {
+      bad = 1;
+    } else {
+      const int n = bg.gno[b + 1] - bg.gno[b];
+      if (cand_off[c + 1] - cand_off[c] != n) bad = 1;
+      e = bg.geo[b + 1] - bg.geo[b];
+    }
+    tmp_eoff[c] = e;
+  }
+  if (t == 0 && cand_off[0] != 0) bad = 1;
+  bad = __syncthreads_or(bad);
+  if (bad) {
+    if (t == 0) set_error(status, (int)DC_ERR_BAD_PARTITION);
+    return;
+  }
+  // 64-bit check of the edge total before the 32-bit scan
+  long long es = 0;
+  for (int c = t; c < C; c += T) es += tmp_eoff[c];
+  __shared__ long long esum[16];
+  for (int o = 32; o > 0; o >>= 1) es += __shfl_down(es, o, 64);
+  if ((t & 63) == 0) esum[t >> 6] = es;
+  __syncthreads();
+  long long tot = 0;
+  for (int i = 0; i < (T >> 6); ++i) tot += esum[i];
+  if (tot > max_base_edges || (long long)cand_off[C] > max_base_nodes) {
+    if (t == 0) set_error(status, (int)DC_ERR_CAPACITY);
+    return;
+  }
+  const int total = block_exscan(tmp_eoff, tmp_eoff, C, wsum);
+  if (t == 0) tmp_eoff[C] = total;
+}
+
+// Scans contracted sizes over the batch and checks the output capacities.
+__global__ __launch_bounds__(1024) void scan_sizes_kernel(int C, const int* Gc, const int* Ec, int* node_off,
+                                                           int* edge_off, long long cap_nodes, long long cap_edges,
+                                                           int* status, int* totals) {
+  __shared__ int wsum[16];
+  if (status[0] != 0) return;
+  const int nt = block_exscan(Gc, node_off, C, wsum);
+  const int et = block_exscan(Ec, edge_off, C, wsum);
+  if (threadIdx.x == 0) {
+    node_off[C] = nt;
+    edge_off[C] = et;
+    totals[0] = nt;
+    totals[1] = et;
+    if (nt > cap_nodes || et > cap_edges) set_error(status, (int)DC_ERR_CAPACITY);
+  }
+}
+
+__device__ __forceinline__ unsigned short f2bf(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7F800000u) == 0x7F800000u) return (unsigned short)(u >> 16);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+// Places candidate c's lists at their block-diagonal position and sums features.
+template <bool kBf16>
+__global__ __launch_bounds__(256) void finalize_kernel(BaseGraphs bg, int C, const int* cand_graph,
+                                                        const int* cand_off, ContractTmp tmp, BatchView out, int F,
+                                                        const int* status) {
+  if (status[0] != 0) return;
+  const int c = blockIdx.x, t = threadIdx.x, T = blockDim.x;
+  const int b = cand_graph[c];
+  const int coff = cand_off[c];
+  const int nslot = coff + c, eslot = tmp.tmp_eoff[c];
+  const int n0 = out.node_off[c], e0 = out.edge_off[c];
+  const int G = tmp.Gc[c], E = tmp.Ec[c];
+  const int gend = (c == C - 1) ? G + 1 : G;   // the last candidate also writes the closing entry
+  for (int g = t; g < gend; g += T) {
+    out.out_rowptr[n0 + g] = e0 + tmp.orp[nslot + g];
+    out.in_rowptr[n0 + g] = e0 + tmp.irp[nslot + g];
+  }
+  for (int k = t; k < E; k += T) {
+    out.out_col[e0 + k] = n0 + tmp.oc[eslot + k];
+    out.in_col[e0 + k] = n0 + tmp.ic[eslot + k];
+  }
+  // feature sums: members in ascending base index, fp32 accumulation, one rounding
+  const int q = F >> 2;
+  const float4* X4 = reinterpret_cast<const float4*>(bg.X) + (size_t)bg.gno[b] * q;
+  const int* ms = tmp.mstart + nslot;
+  const int* mem = tmp.members + coff;
+  for (int i = t; i < G * q; i += T) {
+    const int g = i / q, f = i - g * q;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int m = ms[g]; m < ms[g + 1]; ++m) {
+      const float4 x = X4[(size_t)mem[m] * q + f];
+      acc.x += x.x;
+      acc.y += x.y;
+      acc.z += x.z;
+      acc.w += x.w;
+    }
+    const size_t row = (size_t)(n0 + g);
+    if (kBf16) {
+      uint2 p;
+      p.x = (unsigned)f2bf(acc.x) | ((unsigned)f2bf(acc.y) << 16);
+      p.y = (unsigned)f2bf(acc.z) | ((unsigned)f2bf(acc.w) << 16);
+      reinterpret_cast<uint2*>(out.Xc)[row * q + f] = p;
+    } else {
+      reinterpret_cast<float4*>(out.Xc)[row * q + f] = acc;
+    }
+  }
+}
+
+}  // namespace
+
+int contract_working_set_bytes(int n_nodes, int n_edges) { return slab_layout(n_nodes, n_edges).total; }
+
+__global__ void reset_status_kernel(int* status) { status[0] = 0; }
+
+hipError_t launch_contract(const ContractLaunch& a, Profiler* prof, hipStream_t s) {
+  if (a.n_cand <= 0) return hipSuccess;
+  const int C = a.n_cand;
+  if (prof) prof->begin(kFamPrep, s);
+  hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, s, a.bg, C, a.cand_graph, a.cand_off, a.tmp.tmp_eoff,
+                     a.max_base_nodes, a.max_base_edges, a.status);
+  if (prof) prof->end(s);
+  const int need = slab_layout(a.max_graph_nodes, a.max_graph_edges).total;
+  const int lds_bytes = need <= a.lds_limit ? need : a.lds_limit;
+  if (prof) prof->begin(kFamContract, s);
+  if (a.min_graph_need <= a.lds_limit) {   // at least one base graph fits in LDS
+    hipLaunchKernelGGL(contract_kernel<true>, dim3(C), dim3(kCT), lds_bytes, s, a.bg, C, a.cand_graph, a.cand_off,
+                       a.group_id, a.tmp, a.out.new_id, a.status, (char*)nullptr, (size_t)0, lds_bytes);
+  }
+  if (need > a.lds_limit) {                // at least one base graph needs the global slab
+    hipLaunchKernelGGL(contract_kernel<false>, dim3(a.slab_wgs), dim3(kCT), 0, s, a.bg, C, a.cand_graph,
+                       a.cand_off, a.group_id, a.tmp, a.out.new_id, a.status, a.slab, a.slab_stride, lds_bytes);
+  }
+  if (prof) prof->end(s);
+  if (prof) prof->begin(kFamFinalize, s);
+  hipLaunchKernelGGL(scan_sizes_kernel, dim3(1), dim3(1024), 0, s, C, a.tmp.Gc, a.tmp.Ec, a.out.node_off,
+                     a.out.edge_off, a.out.cap_nodes, a.out.cap_edges, a.status, a.totals);
+  if (a.bf16)
+    hipLaunchKernelGGL(finalize_kernel<true>, dim3(C), dim3(256), 0, s, a.bg, C, a.cand_graph, a.cand_off, a.tmp,
+                       a.out, a.F, a.status);
+  else
+    hipLaunchKernelGGL(finalize_kernel<false>, dim3(C), dim3(256), 0, s, a.bg, C, a.cand_graph, a.cand_off, a.tmp,
+                       a.out, a.F, a.status);
+  if (prof) prof->end(s);
+  return hipGetLastError();
+}
+
+hipError_t contract_set_lds_limit(int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&contract_kernel<true>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace dc

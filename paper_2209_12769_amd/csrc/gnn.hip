@@ -1,0 +1,407 @@
+// Estimator forward pass over a block-diagonal batch of contracted graphs (gfx950).
+//
+// Per layer (neighbourhood encoding, Sec. 3.3.1, with uniform coefficients and
+// one weight block each for the node itself, its predecessors and successors):
+//     h_in[v]  = mean over predecessors u of h[u]      (0 if none)
+//     h_out[v] = mean over successors  w of h[w]       (0 if none)
+//     h'[v]    = ReLU([h[v] | h_in[v] | h_out[v]] W + b)
+// then a sum over the nodes of each graph (Sec. 3.3.1, second equation) and a
+// head of fully connected layers with ReLU and a scalar output (Sec. 3.3.2).
+//
+// Kernels: aggregate (HBM/L2-bound gather), update (the dense contraction, on
+// MFMA: bf16 32x32x16 with fp32 accumulation, or fp32 32x32x2), readout_head.
+// All grids are sized from the device-resident node total, so no host
+// synchronisation is needed between contraction and forward pass.
+#include <string.h>
+
+#include "common.h"
+
+namespace dc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf2f(u16 x) { return __uint_as_float((unsigned)x << 16); }
+__device__ __forceinline__ u16 f2bf(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7F800000u) == 0x7F800000u) return (u16)(u >> 16);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+
+// ---------------------------------------------------------------------------
+// aggregate: one 16-byte column chunk of one (node, direction) per lane group
+// ---------------------------------------------------------------------------
+template <bool kBf16>
+__global__ __launch_bounds__(256) void aggregate_kernel(const void* __restrict__ h, int d,
+                                                         const int* __restrict__ in_rp, const int* __restrict__ in_ci,
+                                                         const int* __restrict__ out_rp,
+                                                         const int* __restrict__ out_ci, void* __restrict__ h_in,
+                                                         void* __restrict__ h_out, const int* __restrict__ node_off,
+                                                         int C, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  constexpr int kPer = kBf16 ? 8 : 4;          // elements per 16-byte chunk
+  const int cpr = d / kPer;                    // chunks per row
+  const long long ntot = node_off[C];
+  const long long total = 2 * ntot * cpr;
+  const uint4* __restrict__ h4 = reinterpret_cast<const uint4*>(h);
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const long long item = idx / cpr;
+    const int ch = (int)(idx - item * cpr);
+    const long long v = item >> 1;
+    const int dir = (int)(item & 1);
+    const int* rp = dir ? out_rp : in_rp;
+    const int* ci = dir ? out_ci : in_ci;
+    const int s = rp[v], e = rp[v + 1];
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int k = s; k < e; ++k) {
+      const uint4 x = h4[(size_t)ci[k] * cpr + ch];
+      if (kBf16) {
+        acc[0] += __uint_as_float(x.x << 16);
+        acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
+        acc[2] += __uint_as_float(x.y << 16);
+        acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
+        acc[4] += __uint_as_float(x.z << 16);
+        acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
+        acc[6] += __uint_as_float(x.w << 16);
+        acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+      } else {
+        acc[0] += __uint_as_float(x.x);
+        acc[1] += __uint_as_float(x.y);
+        acc[2] += __uint_as_float(x.z);
+        acc[3] += __uint_as_float(x.w);
+      }
+    }
+    const float sc = (e > s) ? 1.0f / (float)(e - s) : 0.0f;
+    uint4 o;
+    if (kBf16) {
+      o.x = (unsigned)f2bf(acc[0] * sc) | ((unsigned)f2bf(acc[1] * sc) << 16);
+      o.y = (unsigned)f2bf(acc[2] * sc) | ((unsigned)f2bf(acc[3] * sc) << 16);
+      o.z = (unsigned)f2bf(acc[4] * sc) | ((unsigned)f2bf(acc[5] * sc) << 16);
+      o.w = (unsigned)f2bf(acc[6] * sc) | ((unsigned)f2bf(acc[7] * sc) << 16);
+    } else {
+      o.x = __float_as_uint(acc[0] * sc);
+      o.y = __float_as_uint(acc[1] * sc);
+      o.z = __float_as_uint(acc[2] * sc);
+      o.w = __float_as_uint(acc[3] * sc);
+    }
+    uint4* dst = reinterpret_cast<uint4*>(dir ? h_out : h_in);
+    dst[(size_t)v * cpr + ch] = o;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// update: h' = ReLU([h | h_in | h_out] W + b) on MFMA
+// ---------------------------------------------------------------------------
+// Tile BM x BN per workgroup, WM x WN per wave, K advanced in steps of BK that
+// never straddle the three operand segments (BK divides d).
+//   bf16: A tile in LDS row-major with a 16-byte pad per row (conflict-free
+//         16-byte fragment reads); W is stored [k/8][H][8] so that the B tile is a
+//         straight copy and fragment reads are contiguous across lanes.
+//   fp32: A rows padded by one float, B rows padded to an odd multiple of 32.
+template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
+    const void* __restrict__ A0, const void* __restrict__ A1, const void* __restrict__ A2, int d,
+    const void* __restrict__ Wl, const float* __restrict__ bias, void* __restrict__ out, int H,
+    const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int ASTR = kBf16 ? (BK + 8) : (BK + 1);                     // elements per A row in LDS
+  constexpr int BSTR = kBf16 ? BN * 8 : (BN + ((BN % 64 == 0) ? 32 : 0));  // elements per B "row"
+  constexpr int A_BYTES = BM * ASTR * (kBf16 ? 2 : 4);
+  constexpr int B_BYTES = (kBf16 ? (BK / 8) : BK) * BSTR * (kBf16 ? 2 : 4);
+  __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
+  u16* As16 = reinterpret_cast<u16*>(smem);
+  u16* Bs16 = reinterpret_cast<u16*>(smem + A_BYTES);
+  float* As32 = reinterpret_cast<float*>(smem);
+  float* Bs32 = reinterpret_cast<float*>(smem + A_BYTES);
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / (BN / WN), wn = wave % (BN / WN);
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int ntot = node_off[C];
+  const int nct = H / BN;
+  const int ntiles = ((ntot + BM - 1) / BM) * nct;
+  const int K = 3 * d;
+
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int m0 = (tile / nct) * BM;
+    const int n0 = (tile % nct) * BN;
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += BK) {
+      const int seg = k0 / d;
+      const int koff = k0 - seg * d;
+      const void* Aseg = seg == 0 ? A0 : (seg == 1 ? A1 : A2);
+      if (kBf16) {
+        constexpr int CH = BK / 8;   // 16-byte chunks per A row
+        for (int i = t; i < BM * CH; i += NT) {
+          const int r = i / CH, ch = i - r * CH;
+          const int gr = m0 + r;
+          uint4 x = make_uint4(0u, 0u, 0u, 0u);
+          if (gr < ntot) x = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(Aseg) + (size_t)gr * d + koff + ch * 8);
+          *reinterpret_cast<uint4*>(As16 + r * ASTR + ch * 8) = x;
+        }
+        const u16* Wp = reinterpret_cast<const u16*>(Wl);
+        for (int i = t; i < CH * BN; i += NT) {
+          const int k8 = i / BN, n = i - k8 * BN;
+          const uint4 x = *reinterpret_cast<const uint4*>(Wp + ((size_t)(k0 / 8 + k8) * H + n0 + n) * 8);
+          *reinterpret_cast<uint4*>(Bs16 + k8 * BSTR + n * 8) = x;
+        }
+      } else {
+        constexpr int CH = BK / 4;   // float4 chunks per A row
+        for (int i = t; i < BM * CH; i += NT) {
+          const int r = i / CH, ch = i - r * CH;
+          const int gr = m0 + r;
+          float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (gr < ntot) x = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(Aseg) + (size_t)gr * d + koff + ch * 4);
+          float* p = As32 + r * ASTR + ch * 4;
+          p[0] = x.x; p[1] = x.y; p[2] = x.z; p[3] = x.w;
+        }
+        const float* Wf = reinterpret_cast<const float*>(Wl);
+        constexpr int CB = BN / 4;
+        for (int i = t; i < BK * CB; i += NT) {
+          const int kk = i / CB, c4 = i - kk * CB;
+          const float4 x = *reinterpret_cast<const float4*>(Wf + (size_t)(k0 + kk) * H + n0 + c4 * 4);
+          float* p = Bs32 + kk * BSTR + c4 * 4;
+          p[0] = x.x; p[1] = x.y; p[2] = x.z; p[3] = x.w;
+        }
+      }
+      __syncthreads();
+      if (kBf16) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+          bf16x8 a[TM], b[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            a[i] = *reinterpret_cast<const bf16x8*>(As16 + (wm * WM + i * 32 + l32) * ASTR + ks * 16 + lh * 8);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            b[j] = *reinterpret_cast<const bf16x8*>(Bs16 + (ks * 2 + lh) * BSTR + (wn * WN + j * 32 + l32) * 8);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < BK / 2; ++ks) {
+          float a[TM], b[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) a[i] = As32[(wm * WM + i * 32 + l32) * ASTR + ks * 2 + lh];
+#pragma unroll
+          for (int j = 0; j < TN; ++j) b[j] = Bs32[(ks * 2 + lh) * BSTR + wn * WN + j * 32 + l32];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+      }
+      __syncthreads();
+    }
+    // epilogue: accumulator register v of lane (l32, lh) holds row 8*(v/4)+4*lh+(v%4), column l32
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * WN + j * 32 + l32;
+      const float bj = bias[col];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+          if (row < ntot) {
+            const float y = fmaxf(acc[i][j][v] + bj, 0.f);
+            if (kBf16) reinterpret_cast<u16*>(out)[(size_t)row * H + col] = f2bf(y);
+            else reinterpret_cast<float*>(out)[(size_t)row * H + col] = y;
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// readout + head: one workgroup per candidate; sums in fp64, fixed order
+// ---------------------------------------------------------------------------
+template <bool kBf16>
+__global__ __launch_bounds__(256) void readout_head_kernel(const void* __restrict__ h, int H,
+                                                            const int* __restrict__ node_off, int C,
+                                                            const float* __restrict__ head, float* __restrict__ pred,
+                                                            const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  constexpr int kPer = kBf16 ? 8 : 4;
+  __shared__ double red[256 * kPer];   // [row group][H] partial sums
+  __shared__ float r[512], z[512];
+  __shared__ double wred[4];
+  const int c = blockIdx.x, t = threadIdx.x;
+  const int n0 = node_off[c], n1 = node_off[c + 1];
+  const int cpr = H / kPer;            // 16-byte chunks per row (<= 256 for H <= 1024)
+  const int rg = 256 / cpr;            // rows handled in parallel
+  const int myr = t / cpr, ch = t - myr * cpr;
+  double acc[kPer];
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) acc[i] = 0.0;
+  if (myr < rg) {
+    const uint4* h4 = reinterpret_cast<const uint4*>(h);
+    for (int v = n0 + myr; v < n1; v += rg) {
+      const uint4 x = h4[(size_t)v * cpr + ch];
+      if constexpr (kBf16) {
+        acc[0] += (double)__uint_as_float(x.x << 16);
+        acc[1] += (double)__uint_as_float(x.x & 0xFFFF0000u);
+        acc[2] += (double)__uint_as_float(x.y << 16);
+        acc[3] += (double)__uint_as_float(x.y & 0xFFFF0000u);
+        acc[4] += (double)__uint_as_float(x.z << 16);
+        acc[5] += (double)__uint_as_float(x.z & 0xFFFF0000u);
+        acc[6] += (double)__uint_as_float(x.w << 16);
+        acc[7] += (double)__uint_as_float(x.w & 0xFFFF0000u);
+      } else {
+        acc[0] += (double)__uint_as_float(x.x);
+        acc[1] += (double)__uint_as_float(x.y);
+        acc[2] += (double)__uint_as_float(x.z);
+        acc[3] += (double)__uint_as_float(x.w);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) red[myr * H + ch * kPer + i] = acc[i];
+  }
+  __syncthreads();
+  for (int j = t; j < H; j += 256) {
+    double s = 0.0;
+    for (int g = 0; g < rg; ++g) s += red[g * H + j];
+    r[j] = (float)s;
+  }
+  __syncthreads();
+  const float* W1 = head;
+  const float* b1 = W1 + (size_t)H * H;
+  const float* W2 = b1 + H;
+  const float* b2 = W2 + (size_t)H * H;
+  const float* w3 = b2 + H;
+  const float* b3 = w3 + H;
+  for (int j = t; j < H; j += 256) {
+    double s = b1[j];
+    for (int k = 0; k < H; ++k) s += (double)r[k] * (double)W1[(size_t)k * H + j];
+    z[j] = (float)(s > 0.0 ? s : 0.0);
+  }
+  __syncthreads();
+  for (int j = t; j < H; j += 256) {
+    double s = b2[j];
+    for (int k = 0; k < H; ++k) s += (double)z[k] * (double)W2[(size_t)k * H + j];
+    r[j] = (float)(s > 0.0 ? s : 0.0);     // r now holds z2
+  }
+  __syncthreads();
+  double p = 0.0;
+  for (int j = t; j < H; j += 256) p += (double)r[j] * (double)w3[j];
+  for (int o = 32; o > 0; o >>= 1) p += __shfl_down(p, o, 64);
+  if ((t & 63) == 0) wred[t >> 6] = p;
+  __syncthreads();
+  if (t == 0) pred[c] = (float)((double)b3[0] + wred[0] + wred[1] + wred[2] + wred[3]);
+}
+
+template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
+void launch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, const void* Wl,
+                   const float* bias, void* out, hipStream_t s) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  hipLaunchKernelGGL((update_kernel<kBf16, BM, BN, BK, WM, WN>), dim3(a.n_cu * 2), dim3(NT), 0, s, A0, A1, A2, d, Wl,
+                     bias, out, a.H, a.node_off, a.n_cand, a.status);
+}
+
+template <bool kBf16, int BK>
+void dispatch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, const void* Wl,
+                     const float* bias, void* out, hipStream_t s) {
+  const int H = a.H;
+  if (H % 256 == 0) launch_update<kBf16, 128, 256, BK, 64, 64>(a, A0, A1, A2, d, Wl, bias, out, s);
+  else if (H % 128 == 0) launch_update<kBf16, 128, 128, BK, 32, 64>(a, A0, A1, A2, d, Wl, bias, out, s);
+  else if (H % 64 == 0) launch_update<kBf16, 128, 64, BK, 32, 32>(a, A0, A1, A2, d, Wl, bias, out, s);
+  else launch_update<kBf16, 128, 32, BK, 32, 32>(a, A0, A1, A2, d, Wl, bias, out, s);
+}
+
+}  // namespace
+
+bool gnn_shape_supported(int F, int H, int L) {
+  return F > 0 && H > 0 && L > 0 && F % 16 == 0 && H % 32 == 0 && H <= 512 && F <= 512;
+}
+
+size_t packed_weight_elems(int F, int H, int L) {
+  size_t n = 0;
+  for (int l = 0; l < L; ++l) n += (size_t)3 * (l == 0 ? F : H) * H;
+  return n;
+}
+
+static unsigned short host_f2bf(float x) {
+  unsigned u;
+  memcpy(&u, &x, 4);
+  if ((u & 0x7F800000u) == 0x7F800000u) return (unsigned short)(u >> 16);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+void pack_weights_host(const float* W_layers, int F, int H, int L, int bf16, void* dst) {
+  if (!bf16) {
+    memcpy(dst, W_layers, packed_weight_elems(F, H, L) * sizeof(float));
+    return;
+  }
+  unsigned short* o = static_cast<unsigned short*>(dst);
+  const float* w = W_layers;
+  for (int l = 0; l < L; ++l) {
+    const int K = 3 * (l == 0 ? F : H);
+    for (int k = 0; k < K; ++k)
+      for (int n = 0; n < H; ++n) o[((size_t)(k / 8) * H + n) * 8 + (k % 8)] = host_f2bf(w[(size_t)k * H + n]);
+    o += (size_t)K * H;
+    w += (size_t)K * H;
+  }
+}
+
+hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
+  if (a.n_cand <= 0) return hipSuccess;
+  const void* hcur = a.Xc;
+  int d = a.F;
+  const size_t esz = a.bf16 ? 2 : 4;
+  const char* Wl = static_cast<const char*>(a.W);
+  const float* bl = a.b;
+  const int agg_grid = a.n_cu * 8;
+  for (int l = 0; l < a.L; ++l) {
+    void* hnext = a.act[l & 1];
+    if (prof) prof->begin(kFamAggregate, s);
+    if (a.bf16)
+      hipLaunchKernelGGL(aggregate_kernel<true>, dim3(agg_grid), dim3(256), 0, s, hcur, d, a.in_rowptr, a.in_col,
+                         a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
+    else
+      hipLaunchKernelGGL(aggregate_kernel<false>, dim3(agg_grid), dim3(256), 0, s, hcur, d, a.in_rowptr, a.in_col,
+                         a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
+    if (prof) prof->end(s);
+    if (prof) prof->begin(kFamUpdate, s);
+    if (a.bf16) {
+      if (d % 64 == 0) dispatch_update<true, 64>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+      else dispatch_update<true, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+    } else {
+      if (d % 32 == 0) dispatch_update<false, 32>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+      else dispatch_update<false, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+    }
+    if (prof) prof->end(s);
+    Wl += (size_t)3 * d * a.H * esz;
+    bl += a.H;
+    hcur = hnext;
+    d = a.H;
+  }
+  if (prof) prof->begin(kFamReadout, s);
+  if (a.bf16)
+    hipLaunchKernelGGL(readout_head_kernel<true>, dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
+                       a.head, a.pred, a.status);
+  else
+    hipLaunchKernelGGL(readout_head_kernel<false>, dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
+                       a.head, a.pred, a.status);
+  if (prof) prof->end(s);
+  return hipGetLastError();
+}
+
+}  // namespace dc

@@ -1,0 +1,255 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by
+element on the same seeded inputs.  Contraction (ids, offsets, neighbour lists)
+must match bit for bit; predicted times within rel 1e-5 (fp32 path) or 2e-2
+(bf16 path, against the oracle with the same bf16 storage points)."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2209_12769_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_12769_amd import binding
+    binding.lib()
+    return binding
+
+
+def rel_err(got, ref):
+    """Relative error per candidate with a floor of 1e-3 x median |ref| under the
+    denominator, so that outputs that cancel to ~0 do not make the ratio meaningless."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    floor = 1e-3 * float(np.median(np.abs(ref))) if ref.size else 0.0
+    return np.abs(got - ref) / np.maximum(np.maximum(np.abs(ref), floor), 1e-30)
+
+
+def bf16_to_f32(t):
+    return t.float().cpu().numpy()
+
+
+def gpu_contract(B, w, ev=None, slack_nodes=None):
+    ev = ev or B.evaluator_for(w)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    nb = int(w.cand_off[-1])
+    geo = w.g_edge_off()
+    eb = int(sum(int(geo[b + 1] - geo[b]) for b in w.cand_graph))
+    batch = ev.alloc_batch(w.n_cand, nb, nb if slack_nodes is None else slack_nodes, eb)
+    ev.contract_graphs(cg, co, gid, batch)
+    return ev, batch
+
+
+def check_contraction(B, w, ev=None):
+    print(f"[contract] {w.name} C={w.n_cand}", flush=True)
+    ev, batch = gpu_contract(B, w, ev)
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    ref = orc.contract(w)
+    nt, et = ev.last_totals()
+    assert (nt, et) == (ref.ntot, ref.etot)
+    assert np.array_equal(batch.node_off.cpu().numpy(), ref.node_off)
+    assert np.array_equal(batch.edge_off.cpu().numpy(), ref.edge_off)
+    assert np.array_equal(batch.new_id.cpu().numpy()[:ref.new_id.size], ref.new_id)
+    assert np.array_equal(batch.out_rowptr.cpu().numpy()[:nt + 1], ref.out_rowptr)
+    assert np.array_equal(batch.in_rowptr.cpu().numpy()[:nt + 1], ref.in_rowptr)
+    assert np.array_equal(batch.out_col.cpu().numpy()[:et], ref.out_col)
+    assert np.array_equal(batch.in_col.cpu().numpy()[:et], ref.in_col)
+    Xc = bf16_to_f32(batch.Xc)[:nt]
+    if w.model.dtype == "bf16":
+        # fp32 sums in ascending member order, one rounding: at most one bf16 step from the oracle
+        assert np.all(np.abs(Xc - ref.Xc) <= np.abs(ref.Xc) * 2.0 ** -7 + 1e-30)
+        assert np.mean(Xc == ref.Xc) > 0.999
+    else:
+        np.testing.assert_allclose(Xc, ref.Xc, rtol=2e-6, atol=0)
+    return ev, batch, ref
+
+
+def check_forward(B, w, ev, batch, ref, sample=None):
+    pred = ev.gnn_forward(batch).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    if sample is None:
+        want = orc.gnn_forward(ref, w.model, w.weights)
+        got = pred
+    else:
+        sub = orc.contract(w.subset(sample))
+        want = orc.gnn_forward(sub, w.model, w.weights)
+        got = pred[sample]
+    err = rel_err(got, want)
+    print(f"[forward] {w.name} dtype={w.model.dtype} max rel err {err.max():.3e} (n={len(want)})", flush=True)
+    assert err.max() <= TOL[w.model.dtype], (err.max(), int(err.argmax()))
+    return pred
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name,n", [("cfg1", 1), ("cfg1", 5), ("cfg2", 256), ("cfg3", 96), ("cfg4", 24)])
+def test_configs_contract_and_forward(B, name, n):
+    w = wl.make(name, n)
+    ev, batch, ref = check_contraction(B, w)
+    pred = check_forward(B, w, ev, batch, ref)
+    # dc_eval_candidates is contract + forward on context-owned buffers: same kernels, same numbers
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    both = ev.eval_candidates(cg, co, gid).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    assert np.array_equal(both, pred)
+    again = ev.eval_candidates(cg, co, gid).cpu().numpy()
+    assert np.array_equal(both, again)                         # deterministic
+    ev.close()
+
+
+def test_cfg5_heterogeneous_graphs_lds_and_global_paths(B):
+    # graphs from 100 to 20000 ops: small ones are contracted in LDS, large ones in the global slab
+    w = wl.make("cfg5", 24, n_graphs=12)
+    sizes = sorted(g.n for g in w.graphs)
+    print("cfg5 graph sizes", sizes, flush=True)
+    ev, batch, ref = check_contraction(B, w)
+    idx = [int(i) for i in np.argsort([w.graphs[b].n for b in w.cand_graph])[[0, 1, w.n_cand // 2, -1]]]
+    check_forward(B, w, ev, batch, ref, sample=idx)
+    ev.close()
+
+
+def test_fp32_and_bf16_on_the_same_small_batch(B):
+    for dtype in ("f32", "bf16"):
+        for F, H, L in [(16, 32, 2), (32, 64, 1), (48, 96, 2), (64, 256, 2), (16, 512, 1)]:
+            g = wl.random_dag(7, 300, 0.02, F)
+            labs = wl.random_labels(8, g.n, 90, C=7)
+            w = wl.custom(f"rand-{dtype}-{F}-{H}-{L}", wl.ModelSpec(F, H, L, dtype), [g], [labs], seed=3)
+            ev, batch, ref = check_contraction(B, w)
+            check_forward(B, w, ev, batch, ref)
+            ev.close()
+
+
+def test_arbitrary_partitions_large_groups_and_long_rows(B):
+    # few groups on a dense-ish graph: member lists > 32 (ordered compaction path) and
+    # neighbour rows > 32 raw entries (bitmap path), plus cyclic quotients
+    g = wl.random_dag(11, 700, 0.05, 16)
+    labs = np.concatenate([wl.random_labels(12, g.n, 6, C=3), wl.random_labels(13, g.n, 40, C=3),
+                           wl.random_labels(14, g.n, 400, C=3)])
+    w = wl.custom("dense", wl.ModelSpec(16, 32, 2, "f32"), [g], [labs], seed=5)
+    ev, batch, ref = check_contraction(B, w)
+    check_forward(B, w, ev, batch, ref)
+    ev.close()
+
+
+def test_identity_and_single_group(B):
+    g = wl.random_dag(21, 500, 0.01, 32)
+    labs = np.stack([np.arange(g.n, dtype=np.int32), np.full(g.n, 7, np.int32),
+                     wl.Rng(5, 5).permutation(g.n).astype(np.int32)])
+    w = wl.custom("special", wl.ModelSpec(32, 32, 2, "f32"), [g], [labs], seed=6)
+    ev, batch, ref = check_contraction(B, w)
+    off = batch.node_off.cpu().numpy()
+    assert off[1] - off[0] == g.n and off[2] - off[1] == 1 and off[3] - off[2] == g.n
+    orp = batch.out_rowptr.cpu().numpy()
+    assert np.array_equal(orp[:g.n + 1], g.rowptr)               # identity partition: the base graph itself
+    assert np.array_equal(batch.out_col.cpu().numpy()[:g.e], g.col)
+    check_forward(B, w, ev, batch, ref)
+    ev.close()
+
+
+def test_edgeless_and_tiny_graphs(B):
+    n = 5
+    g0 = wl.BaseGraph(n, n, np.zeros(n + 1, np.int32), np.zeros(0, np.int32),
+                      wl.Rng(1, 1).uniform(n * 16).reshape(n, 16).astype(np.float32))
+    g1 = wl.BaseGraph(1, 1, np.zeros(2, np.int32), np.zeros(0, np.int32), np.ones((1, 16), np.float32))
+    g2 = wl.random_dag(3, 9, 0.5, 16)
+    labs = [np.array([[0, 1, 2, 3, 4], [4, 4, 2, 2, 0]], np.int32), np.zeros((2, 1), np.int32),
+            wl.random_labels(4, 9, 4, C=2)]
+    w = wl.custom("tiny", wl.ModelSpec(16, 32, 3, "f32"), [g0, g1, g2], labs, seed=7)
+    ev, batch, ref = check_contraction(B, w)
+    check_forward(B, w, ev, batch, ref)
+    ev.close()
+
+
+def test_empty_batch(B):
+    w = wl.make("cfg1", 1)
+    ev = B.evaluator_for(w)
+    z = ev.torch.zeros(1, dtype=ev.torch.int32, device=ev.device)
+    batch = ev.alloc_batch(0, 0, 4, 4)
+    ev.contract_graphs(z[:0], z, z[:0], batch)
+    assert ev.check() == B.DC_OK
+    assert batch.node_off.cpu().numpy()[0] == 0 and ev.last_totals() == (0, 0)
+    assert ev.eval_candidates(z[:0], z, z[:0]).numel() == 0
+    ev.close()
+
+
+def test_device_detected_errors(B):
+    w = wl.make("cfg2", 4)
+    ev = B.evaluator_for(w)
+    cg, co = ev.to_device(w.cand_graph), ev.to_device(w.cand_off)
+    bad = w.group_id.copy()
+    bad[w.graphs[0].n + 3] = w.graphs[0].n            # label == N in candidate 1
+    pred = ev.eval_candidates(cg, co, ev.to_device(bad))
+    assert ev.check() == B.DC_ERR_BAD_PARTITION
+    assert ev.check() == B.DC_OK                       # cleared by the previous check
+    # candidate length that does not match its base graph
+    co2 = w.cand_off.copy()
+    co2[-1] -= 1
+    ev.eval_candidates(cg, ev.to_device(co2), ev.to_device(w.group_id))
+    assert ev.check() == B.DC_ERR_BAD_PARTITION
+    # base-graph index out of range
+    cg2 = w.cand_graph.copy()
+    cg2[2] = 9
+    ev.eval_candidates(ev.to_device(cg2), co, ev.to_device(w.group_id))
+    assert ev.check() == B.DC_ERR_BAD_PARTITION
+    # output capacity too small: detected on the device, nothing written past the buffers
+    gid = ev.to_device(w.group_id)
+    nb = int(w.cand_off[-1])
+    small = ev.alloc_batch(w.n_cand, nb, 100, 100)
+    ev.contract_graphs(cg, co, gid, small)
+    assert ev.check() == B.DC_ERR_CAPACITY
+    # and the context still works afterwards
+    good = ev.eval_candidates(cg, co, gid).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    ref = orc.evaluate(w)
+    assert rel_err(good, ref).max() <= TOL["f32"]
+    # host-detected: more candidates than the context was created for
+    with pytest.raises(B.DiscoError) as ei:
+        w8 = wl.make("cfg2", 8)
+        ev.eval_candidates(ev.to_device(w8.cand_graph), ev.to_device(w8.cand_off), ev.to_device(w8.group_id))
+    assert ei.value.status == B.DC_ERR_CAPACITY
+    ev.close()
+
+
+def test_bad_base_graph_is_rejected_on_the_host(B):
+    ev = B.Evaluator(16, 32, 1, "f32", 4, 100, 100)
+    X = np.zeros((3, 16), np.float32)
+    ok = dict(g_node_off=np.array([0, 3]), g_edge_off=np.array([0, 2]), rowptr=np.array([0, 1, 2, 2]),
+              col=np.array([1, 2]), X=X)
+    for patch in (dict(col=np.array([1, 3])), dict(rowptr=np.array([0, 2, 1, 2])), dict(rowptr=np.array([0, 1, 1, 1]))):
+        with pytest.raises(B.DiscoError) as ei:
+            ev.set_base_graphs(**{**ok, **patch})
+        assert ei.value.status == B.DC_ERR_BAD_GRAPH
+    ev.set_base_graphs(**ok)
+    ev.close()
+
+
+def test_unsorted_duplicate_base_edges_are_accepted(B):
+    # rows need not be sorted or duplicate free: the contraction sorts and dedups
+    g = wl.random_dag(31, 60, 0.1, 16)
+    rp = [0]
+    ci = []
+    rng = wl.Rng(32, 0)
+    for u in range(g.n):
+        row = list(g.col[g.rowptr[u]:g.rowptr[u + 1]])
+        row = row + row[:1]                                   # one duplicate
+        row = [row[i] for i in rng.permutation(len(row))] if row else row
+        ci += row
+        rp.append(len(ci))
+    g2 = wl.BaseGraph(g.n, g.n, np.array(rp, np.int32), np.array(ci, np.int32), g.X)
+    labs = wl.random_labels(33, g.n, 20, C=3)
+    model = wl.ModelSpec(16, 32, 1, "f32")
+    w_clean = wl.custom("clean", model, [g], [labs], seed=1)
+    w_dirty = wl.custom("dirty", model, [g2], [labs], seed=1)
+    ev, batch = gpu_contract(B, w_dirty)
+    assert ev.check() == B.DC_OK
+    ref = orc.contract(w_clean)
+    assert np.array_equal(batch.out_col.cpu().numpy()[:ref.etot], ref.out_col)
+    assert np.array_equal(batch.in_col.cpu().numpy()[:ref.etot], ref.in_col)
+    assert np.array_equal(batch.out_rowptr.cpu().numpy()[:ref.ntot + 1], ref.out_rowptr)
+    ev.close()
