@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the fusion-candidate evaluator on one MI355X.
+
+A step is one pass of the whole hot path (dc_eval_candidates: contraction of
+every candidate, all message-passing layers, readout and head) over one batch
+of synthetic candidates that is already resident in HBM.  Prints one JSON line:
+candidates/s, the roofline position of the dominant kernel (timed live with HIP
+events on the launch stream) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def algorithmic_work(w, ntot, etot):
+    """Bytes / flops each kernel family must move or compute per step (what the
+    method needs, not what an implementation happens to touch)."""
+    m = w.model
+    s = 2 if m.dtype == "bf16" else 4
+    nb = int(w.cand_off[-1])
+    C = w.n_cand
+    base = sum(4 * (g.n + 1) + 4 * g.e + 4 * g.n * m.F for g in w.graphs)       # read once per batch
+    contract = 4 * nb + 4 * nb + ntot * m.F * s + 2 * 4 * (ntot + C + etot) + base
+    agg_b, upd_f, upd_b = 0, 0, 0
+    d = m.F
+    for _ in range(m.L):
+        agg_b += ntot * d * s + 2 * ntot * d * s + 2 * 4 * (ntot + etot)
+        upd_f += 2 * ntot * 3 * d * m.H
+        upd_b += ntot * (3 * d + m.H) * s + 3 * d * m.H * s
+        d = m.H
+    return {"contract": {"bytes": contract}, "aggregate": {"bytes": agg_b},
+            "update": {"flops": upd_f, "bytes": upd_b}, "readout_head": {"bytes": ntot * m.H * s}}
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    recorded in profiles/traffic_<workload>.txt as '<kernel>_traffic_bytes_per_launch: N'."""
+    p = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(p):
+        return None
+    for line in open(p):
+        if line.startswith(f"{kernel}_traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def cpu_baseline(w, seconds_target=15.0):
+    from oracle import oracle as orc
+    probe = w.subset([0])
+    t0 = time.perf_counter()
+    orc.evaluate(probe)
+    per = max(time.perf_counter() - t0, 1e-4)
+    n = int(max(1, min(w.n_cand, seconds_target / per)))
+    idx = np.linspace(0, w.n_cand - 1, n).astype(np.int64)
+    sub = w.subset(idx)
+    t0 = time.perf_counter()
+    orc.evaluate(sub)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n} of {w.n_cand} candidates of {w.name}, evenly spaced, contract+forward, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--n-cand", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; candidates are independent, so more GPUs would each take a "
+              "slice of the batch, but that is not part of this build. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2209_12769_amd import binding as B
+    from paper_2209_12769_amd import workloads as wl
+
+    w = wl.make(args.workload, args.n_cand)
+    ev = B.evaluator_for(w)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    pred = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
+    for _ in range(args.warmup):
+        ev.eval_candidates(cg, co, gid, pred)
+    torch.cuda.synchronize()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    ntot, etot = ev.last_totals()
+
+    ev.profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev.eval_candidates(cg, co, gid, pred)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fam = ev.profile_end()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+
+    work = algorithmic_work(w, ntot, etot)
+    fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
+    kernels = {}
+    for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
+                      ("readout_head", "readout_head")):
+        ms_total, launches = fam[key]
+        per_step_ms = ms_total / args.steps
+        k = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches / args.steps}
+        if per_step_ms > 0:
+            k["GB/s"] = round(work[name]["bytes"] / (per_step_ms * 1e-3) / 1e9, 1)
+            if "flops" in work[name]:
+                k["TFLOP/s"] = round(work[name]["flops"] / (per_step_ms * 1e-3) / 1e12, 2)
+        kernels[name] = k
+    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    if dom == "update":
+        peak = PEAK_MFMA_TFLOPS[w.model.dtype]
+        ach = kernels[dom].get("TFLOP/s", 0.0)
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": round(ach / peak, 4), "traffic": read_traffic(w.name, dom),
+                "avg_launch_ms": round(kernels[dom]["ms_per_step"] / max(kernels[dom]["launches_per_step"], 1), 4)}
+    else:
+        ach = kernels[dom].get("GB/s", 0.0)
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": read_traffic(w.name, dom),
+                "avg_launch_ms": round(kernels[dom]["ms_per_step"] / max(kernels[dom]["launches_per_step"], 1), 4)}
+
+    out = {
+        "metric": "fusion candidates evaluated/sec (contract+GNN) on 1 MI355X",
+        "value": round(w.n_cand * args.steps / dt, 1),
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.model.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "candidates": w.n_cand, "base_graphs": len(w.graphs),
+                   "base_nodes": int(np.mean([g.n for g in w.graphs])), "contracted_nodes": ntot,
+                   "contracted_edges": etot, "F": w.model.F, "H": w.model.H, "L": w.model.L},
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    ev.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
