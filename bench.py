@@ -32,15 +32,23 @@ def algorithmic_work(w, ntot, etot):
     C = w.n_cand
     base = sum(4 * (g.n + 1) + 4 * g.e + 4 * g.n * m.F for g in w.graphs)       # read once per batch
     contract = 4 * nb + 4 * nb + ntot * m.F * s + 2 * 4 * (ntot + C + etot) + base
-    agg_b, upd_f, upd_b = 0, 0, 0
+    agg_b, upd_f, upd_b, fus_f, fus_b = 0, 0, 0, 0, 0
     d = m.F
     for _ in range(m.L):
-        agg_b += ntot * d * s + 2 * ntot * d * s + 2 * 4 * (ntot + etot)
-        upd_f += 2 * ntot * 3 * d * m.H
-        upd_b += ntot * (3 * d + m.H) * s + 3 * d * m.H * s
+        fused = m.dtype == "bf16" and m.H in (128, 256) and d % 64 == 0
+        idx = 2 * 4 * (ntot + etot)
+        flops = 2 * ntot * 3 * d * m.H
+        if fused:       # means never leave the chip: read h, write h', read the neighbour lists and W
+            fus_f += flops
+            fus_b += ntot * d * s + ntot * m.H * s + idx + 3 * d * m.H * s
+        else:           # read h, write both means; then read [h|h_in|h_out] and W, write h'
+            agg_b += ntot * d * s + 2 * ntot * d * s + idx
+            upd_f += flops
+            upd_b += ntot * (3 * d + m.H) * s + 3 * d * m.H * s
         d = m.H
     return {"contract": {"bytes": contract}, "aggregate": {"bytes": agg_b},
-            "update": {"flops": upd_f, "bytes": upd_b}, "readout_head": {"bytes": ntot * m.H * s}}
+            "update": {"flops": upd_f, "bytes": upd_b}, "fused_layer": {"flops": fus_f, "bytes": fus_b},
+            "readout_head": {"bytes": ntot * m.H * s}}
 
 
 def read_traffic(workload, kernel):
@@ -113,8 +121,10 @@ def main():
     fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
     kernels = {}
     for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
-                      ("readout_head", "readout_head")):
+                      ("fused_layer", "fused_layer"), ("readout_head", "readout_head")):
         ms_total, launches = fam[key]
+        if launches == 0:
+            continue
         per_step_ms = ms_total / args.steps
         k = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches / args.steps}
         if per_step_ms > 0:
@@ -123,7 +133,7 @@ def main():
                 k["TFLOP/s"] = round(work[name]["flops"] / (per_step_ms * 1e-3) / 1e12, 2)
         kernels[name] = k
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-    if dom == "update":
+    if dom in ("update", "fused_layer"):
         peak = PEAK_MFMA_TFLOPS[w.model.dtype]
         ach = kernels[dom].get("TFLOP/s", 0.0)
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",

@@ -1,5 +1,6 @@
 // C ABI of libdisco: context, argument checks, memory, launches (gfx950 only).
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -55,13 +56,15 @@ struct dc_ctx {
   char* slab = nullptr;
   size_t slab_stride = 0;
   int slab_wgs = 0;
+  int allow_fused = 1;
   Profiler prof;
   std::string err;
 };
 
 namespace {
 
-const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update", "readout_head"};
+const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
+                                             "fused_layer", "readout_head"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -216,6 +219,7 @@ dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pr
   g.pred = pred;
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;
+  g.allow_fused = ctx->allow_fused;
   hipError_t e = launch_gnn_forward(g, ctx->prof.on ? &ctx->prof : nullptr, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "forward launch");
   return DC_OK;
@@ -253,6 +257,10 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
   dc_ctx* ctx = new (std::nothrow) dc_ctx();
   if (!ctx) return DC_ERR_OOM;
   ctx->cfg = *cfg;
+  {
+    const char* env = getenv("DC_DISABLE_FUSED");   // debugging aid: run the unfused layer kernels
+    ctx->allow_fused = !(env && env[0] == '1');
+  }
   hipError_t e = hipGetDevice(&ctx->device);
   if (e != hipSuccess) {
     delete ctx;

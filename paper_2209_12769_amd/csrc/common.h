@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamReadout, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamReadout, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -107,6 +107,7 @@ struct GnnArgs {
   float* pred;
   const int* status;
   int n_cu;
+  int allow_fused;      // 0 forces the separate aggregate + update kernels
 };
 hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s);
 // Elements (of the storage dtype) of all layer matrices in device layout.
@@ -115,6 +116,10 @@ size_t packed_weight_elems(int F, int H, int L);
 // (fp32: unchanged; bf16: [k/8][H][8] so that a lane's 8 consecutive k sit together).
 void pack_weights_host(const float* W_layers, int F, int H, int L, int bf16, void* dst);
 bool gnn_shape_supported(int F, int H, int L);
+// gnn_fused.hip: one layer with both neighbour means folded into the A-tile load (bf16).
+bool fused_layer_supported(int d, int H, int bf16);
+hipError_t launch_fused_layer(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                              hipStream_t s);
 
 __global__ void reset_status_kernel(int* status);
 

@@ -371,23 +371,30 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   const int agg_grid = a.n_cu * 8;
   for (int l = 0; l < a.L; ++l) {
     void* hnext = a.act[l & 1];
-    if (prof) prof->begin(kFamAggregate, s);
-    if (a.bf16)
-      hipLaunchKernelGGL(aggregate_kernel<true>, dim3(agg_grid), dim3(256), 0, s, hcur, d, a.in_rowptr, a.in_col,
-                         a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
-    else
-      hipLaunchKernelGGL(aggregate_kernel<false>, dim3(agg_grid), dim3(256), 0, s, hcur, d, a.in_rowptr, a.in_col,
-                         a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
-    if (prof) prof->end(s);
-    if (prof) prof->begin(kFamUpdate, s);
-    if (a.bf16) {
-      if (d % 64 == 0) dispatch_update<true, 64>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
-      else dispatch_update<true, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+    if (a.allow_fused && fused_layer_supported(d, a.H, a.bf16)) {
+      if (prof) prof->begin(kFamFused, s);
+      hipError_t e = launch_fused_layer(hcur, d, a, Wl, bl, hnext, s);
+      if (prof) prof->end(s);
+      if (e != hipSuccess) return e;
     } else {
-      if (d % 32 == 0) dispatch_update<false, 32>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
-      else dispatch_update<false, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+      if (prof) prof->begin(kFamAggregate, s);
+      if (a.bf16)
+        hipLaunchKernelGGL(aggregate_kernel<true>, dim3(agg_grid), dim3(256), 0, s, hcur, d, a.in_rowptr, a.in_col,
+                           a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
+      else
+        hipLaunchKernelGGL(aggregate_kernel<false>, dim3(agg_grid), dim3(256), 0, s, hcur, d, a.in_rowptr, a.in_col,
+                           a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
+      if (prof) prof->end(s);
+      if (prof) prof->begin(kFamUpdate, s);
+      if (a.bf16) {
+        if (d % 64 == 0) dispatch_update<true, 64>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+        else dispatch_update<true, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+      } else {
+        if (d % 32 == 0) dispatch_update<false, 32>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+        else dispatch_update<false, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
+      }
+      if (prof) prof->end(s);
     }
-    if (prof) prof->end(s);
     Wl += (size_t)3 * d * a.H * esz;
     bl += a.H;
     hcur = hnext;

@@ -253,3 +253,22 @@ def test_unsorted_duplicate_base_edges_are_accepted(B):
     assert np.array_equal(batch.in_col.cpu().numpy()[:ref.etot], ref.in_col)
     assert np.array_equal(batch.out_rowptr.cpu().numpy()[:ref.ntot + 1], ref.out_rowptr)
     ev.close()
+
+
+def test_fused_layer_matches_the_separate_kernels_bit_for_bit(B, monkeypatch):
+    # same arithmetic in the same order: the fused layer and aggregate + update agree exactly
+    for name, n in (("cfg4", 12), ("cfg3", 40)):
+        w = wl.make(name, n)
+        ev = B.evaluator_for(w)
+        cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+        fused = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.close()
+        monkeypatch.setenv("DC_DISABLE_FUSED", "1")
+        ev2 = B.evaluator_for(w)
+        plain = ev2.eval_candidates(ev2.to_device(w.cand_graph), ev2.to_device(w.cand_off),
+                                    ev2.to_device(w.group_id)).cpu().numpy()
+        assert ev2.check() == B.DC_OK
+        ev2.close()
+        monkeypatch.delenv("DC_DISABLE_FUSED")
+        assert np.array_equal(fused, plain), (name, np.abs(fused - plain).max())
