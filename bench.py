@@ -119,9 +119,11 @@ def main():
 
     work = algorithmic_work(w, ntot, etot)
     fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
+    # a fused layer = the pre-pass for rows with long neighbour lists + the MFMA kernel
+    fam["fused_all"] = (fam["fused_layer"][0] + fam["aggregate_heavy"][0], fam["fused_layer"][1])
     kernels = {}
     for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
-                      ("fused_layer", "fused_layer"), ("readout_head", "readout_head")):
+                      ("fused_layer", "fused_all"), ("readout_head", "readout_head")):
         ms_total, launches = fam[key]
         if launches == 0:
             continue

@@ -40,6 +40,7 @@ struct dc_ctx {
   BatchView ib{};           // context-owned batch used by dc_eval_candidates
   void* act[2] = {nullptr, nullptr};
   void* agg[2] = {nullptr, nullptr};
+  void* desc[2] = {nullptr, nullptr};
   int* status = nullptr;    // [2]
   int* totals = nullptr;    // [2]
   int* h_pinned = nullptr;  // [4] pinned host mirror for status / totals
@@ -64,7 +65,7 @@ struct dc_ctx {
 namespace {
 
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
-                                             "fused_layer", "readout_head"};
+                                             "fused_layer", "aggregate_heavy", "readout_head"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -126,6 +127,8 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   void* act1 = a.take<char>((size_t)(k.NN + 1) * cfg.H * es);
   void* agg0 = a.take<char>((size_t)(k.NN + 1) * D * es);
   void* agg1 = a.take<char>((size_t)(k.NN + 1) * D * es);
+  void* desc0 = a.take<char>((size_t)(k.NN + 1) * 16);
+  void* desc1 = a.take<char>((size_t)(k.NN + 1) * 16);
   if (ctx) {
     ctx->status = status;
     ctx->totals = totals;
@@ -135,6 +138,8 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
     ctx->act[1] = act1;
     ctx->agg[0] = agg0;
     ctx->agg[1] = agg1;
+    ctx->desc[0] = desc0;
+    ctx->desc[1] = desc1;
   }
   return a.off;
 }
@@ -216,6 +221,8 @@ dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pr
   g.act[1] = ctx->act[1];
   g.agg[0] = ctx->agg[0];
   g.agg[1] = ctx->agg[1];
+  g.desc[0] = ctx->desc[0];
+  g.desc[1] = ctx->desc[1];
   g.pred = pred;
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;

@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamReadout, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamHeavy, kFamReadout, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -104,6 +104,7 @@ struct GnnArgs {
   const float* head;    // fp32 head (bf16-representable matrices on the bf16 path)
   void* act[2];         // ping/pong activations [max_nodes, H]
   void* agg[2];         // predecessor mean / successor mean [max_nodes, max(F,H)]
+  void* desc[2];        // gather descriptors [max_nodes] x 16 bytes per direction
   float* pred;
   const int* status;
   int n_cu;
@@ -121,7 +122,22 @@ bool fused_layer_supported(int d, int H, int bf16);
 hipError_t launch_fused_layer(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                               hipStream_t s);
 
+// gnn_layer256.hip: wave-specialised fused layer for d = H = 256 (bf16); uses a.agg[] for rows with long lists.
+bool layer256_supported(int d, int H, int bf16);
+hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
+hipError_t launch_layer256(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                           Profiler* prof, hipStream_t s);
+
 __global__ void reset_status_kernel(int* status);
+
+// fp32 -> bf16, round to nearest even, in hardware (v_cvt_pk_bf16_f32): a in the low half
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ unsigned short to_bf16(float a) { return (unsigned short)(pack_bf16x2(a, 0.f) & 0xFFFFu); }
 
 static inline __host__ __device__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 

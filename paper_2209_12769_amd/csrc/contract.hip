@@ -23,7 +23,7 @@
 namespace dc {
 namespace {
 
-constexpr int kCT = 512;        // threads per contraction workgroup
+constexpr int kCT = 1024;       // threads per contraction workgroup
 constexpr int kCW = kCT / 64;   // waves per workgroup
 constexpr int kSmallRow = 32;   // rows up to this length are sorted by one thread
 constexpr unsigned short kSelf = 0xFFFF;
@@ -44,7 +44,7 @@ __host__ __device__ inline Slab slab_layout(int N, int E) {
   s.BM = o;  o = align16(o + 4 * kCW * ((N + 31) / 32 + 1));  // per-wave bitmaps
   s.NID = o; o = align16(o + 2 * (N + 1));          // u16   [N] contracted id per base node
   s.MEM = o; o = align16(o + 2 * (N + 1));          // u16   [N] base nodes grouped by contracted id
-  s.RAW = o; o = align16(o + 2 * (E + 1));          // u16   [E] remapped neighbours, grouped by row
+  s.RAW = o; o = align16(o + 2 * ((E > N ? E : N) + 1));   // u16 [max(E,N)] labels, later remapped neighbours by row
   s.total = o;
   return s;
 }
@@ -123,10 +123,13 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
 
   // ---- relabel: groups numbered by ascending smallest member -----------------
   int bad = 0;
+  u16* LAB = RAW;                 // labels stay in LDS until the ids are known; RAW is unused until then
+#pragma unroll 4
   for (int v = t; v < N; v += T) {
     A[v] = INT_MAX;
     int l = lab[v];
     bad |= (l < 0) | (l >= N);
+    LAB[v] = (u16)l;
   }
   {
     unsigned* bmall = reinterpret_cast<unsigned*>(base + L.BM);
@@ -140,18 +143,18 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
     }
     return;
   }
-  for (int v = t; v < N; v += T) atomicMin(&A[lab[v]], v);
+  for (int v = t; v < N; v += T) atomicMin(&A[LAB[v]], v);
   __syncthreads();
-  for (int v = t; v < N; v += T) UL[v] = (A[lab[v]] == v) ? 1 : 0;
+  for (int v = t; v < N; v += T) UL[v] = (A[LAB[v]] == v) ? 1 : 0;
   __syncthreads();
   const int G = block_exscan(UL, UL, N, wsum);
   if (t == 0) UL[N] = G;
   __syncthreads();
   for (int v = t; v < N; v += T)
-    if (UL[v + 1] != UL[v]) A[lab[v]] = UL[v];   // head of its group: rank among heads
+    if (UL[v + 1] != UL[v]) A[LAB[v]] = UL[v];   // head of its group: rank among heads
   __syncthreads();
   for (int v = t; v < N; v += T) {
-    int g = A[lab[v]];
+    int g = A[LAB[v]];
     NID[v] = (u16)g;
     nid_out[v] = g;
   }
@@ -207,6 +210,7 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
     int* t_rp = (dir == 0 ? tmp.orp : tmp.irp) + nslot;
     int* t_ci = (dir == 0 ? tmp.oc : tmp.ic) + eslot;
 
+#pragma unroll 4
     for (int i = t; i < N; i += T) {
       int u = MEM[i];
       A[i] = rp[u + 1] - rp[u];
@@ -215,13 +219,33 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
     const int Eraw = block_exscan(A, A, N, wsum);
     if (t == 0) A[N] = Eraw;
     __syncthreads();
-    for (int i = t; i < N; i += T) {
-      const int u = MEM[i];
-      const int g = NID[u];
-      int o = A[i];
-      for (int e = rp[u]; e < rp[u + 1]; ++e) {
-        int w = NID[ci[e]];
-        RAW[o++] = (w == g) ? kSelf : (u16)w;
+    // four member slots per thread and round: their row starts and first neighbours are
+    // requested together so that the global-memory latency is paid once per round
+    for (int i0 = t; i0 < N; i0 += 4 * T) {
+      int uu[4], o[4], dg[4], r0[4], c0[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * T;
+        const bool ok = i < N;
+        uu[j] = ok ? MEM[i] : 0;
+        o[j] = ok ? A[i] : 0;
+        dg[j] = ok ? A[i + 1] - A[i] : 0;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r0[j] = dg[j] > 0 ? rp[uu[j]] : 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) c0[j] = dg[j] > 0 ? ci[r0[j]] : 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (dg[j] > 0) {
+          const int g = NID[uu[j]];
+          int w = NID[c0[j]];
+          RAW[o[j]] = (w == g) ? kSelf : (u16)w;
+          for (int k = 1; k < dg[j]; ++k) {
+            w = NID[ci[r0[j] + k]];
+            RAW[o[j] + k] = (w == g) ? kSelf : (u16)w;
+          }
+        }
       }
     }
     __syncthreads();
@@ -374,12 +398,6 @@ __global__ __launch_bounds__(1024) void scan_sizes_kernel(int C, const int* Gc, 
   }
 }
 
-__device__ __forceinline__ unsigned short f2bf(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7F800000u) == 0x7F800000u) return (unsigned short)(u >> 16);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
-}
 
 // Places candidate c's lists at their block-diagonal position and sums features.
 template <bool kBf16>
@@ -420,8 +438,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(BaseGraphs bg, int C, con
     const size_t row = (size_t)(n0 + g);
     if (kBf16) {
       uint2 p;
-      p.x = (unsigned)f2bf(acc.x) | ((unsigned)f2bf(acc.y) << 16);
-      p.y = (unsigned)f2bf(acc.z) | ((unsigned)f2bf(acc.w) << 16);
+      p.x = pack_bf16x2(acc.x, acc.y);
+      p.y = pack_bf16x2(acc.z, acc.w);
       reinterpret_cast<uint2*>(out.Xc)[row * q + f] = p;
     } else {
       reinterpret_cast<float4*>(out.Xc)[row * q + f] = acc;

@@ -24,12 +24,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned short u16;
 
 __device__ __forceinline__ float bf2f(u16 x) { return __uint_as_float((unsigned)x << 16); }
-__device__ __forceinline__ u16 f2bf(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7F800000u) == 0x7F800000u) return (u16)(u >> 16);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (u16)(u >> 16);
-}
 
 // ---------------------------------------------------------------------------
 // aggregate: one 16-byte column chunk of one (node, direction) per lane group
@@ -78,10 +72,10 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const void* __restrict__
     const float sc = (e > s) ? 1.0f / (float)(e - s) : 0.0f;
     uint4 o;
     if (kBf16) {
-      o.x = (unsigned)f2bf(acc[0] * sc) | ((unsigned)f2bf(acc[1] * sc) << 16);
-      o.y = (unsigned)f2bf(acc[2] * sc) | ((unsigned)f2bf(acc[3] * sc) << 16);
-      o.z = (unsigned)f2bf(acc[4] * sc) | ((unsigned)f2bf(acc[5] * sc) << 16);
-      o.w = (unsigned)f2bf(acc[6] * sc) | ((unsigned)f2bf(acc[7] * sc) << 16);
+      o.x = pack_bf16x2(acc[0] * sc, acc[1] * sc);
+      o.y = pack_bf16x2(acc[2] * sc, acc[3] * sc);
+      o.z = pack_bf16x2(acc[4] * sc, acc[5] * sc);
+      o.w = pack_bf16x2(acc[6] * sc, acc[7] * sc);
     } else {
       o.x = __float_as_uint(acc[0] * sc);
       o.y = __float_as_uint(acc[1] * sc);
@@ -221,7 +215,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
           const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
           if (row < ntot) {
             const float y = fmaxf(acc[i][j][v] + bj, 0.f);
-            if (kBf16) reinterpret_cast<u16*>(out)[(size_t)row * H + col] = f2bf(y);
+            if (kBf16) reinterpret_cast<u16*>(out)[(size_t)row * H + col] = to_bf16(y);
             else reinterpret_cast<float*>(out)[(size_t)row * H + col] = y;
           }
         }
@@ -369,9 +363,19 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   const char* Wl = static_cast<const char*>(a.W);
   const float* bl = a.b;
   const int agg_grid = a.n_cu * 8;
+  if (a.allow_fused && a.L > 1 && layer256_supported(a.H, a.H, a.bf16)) {
+    // neighbour descriptors depend on the graphs only: built once, used by every hidden layer
+    if (prof) prof->begin(kFamHeavy, s);
+    hipError_t e = launch_build_desc(a, s);
+    if (prof) prof->end(s);
+    if (e != hipSuccess) return e;
+  }
   for (int l = 0; l < a.L; ++l) {
     void* hnext = a.act[l & 1];
-    if (a.allow_fused && fused_layer_supported(d, a.H, a.bf16)) {
+    if (a.allow_fused && layer256_supported(d, a.H, a.bf16)) {
+      hipError_t e = launch_layer256(hcur, a, Wl, bl, hnext, prof, s);
+      if (e != hipSuccess) return e;
+    } else if (a.allow_fused && fused_layer_supported(d, a.H, a.bf16)) {
       if (prof) prof->begin(kFamFused, s);
       hipError_t e = launch_fused_layer(hcur, d, a, Wl, bl, hnext, s);
       if (prof) prof->end(s);

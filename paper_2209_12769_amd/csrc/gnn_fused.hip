@@ -42,15 +42,9 @@ struct Lds {
   static constexpr int TOTAL = CI_OFF + 2 * kCiCap * 4;
 };
 
-__device__ __forceinline__ u16 f2bf(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7F800000u) == 0x7F800000u) return (u16)(u >> 16);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (u16)(u >> 16);
-}
-__device__ __forceinline__ unsigned pack2(float a, float b) { return (unsigned)f2bf(a) | ((unsigned)f2bf(b) << 16); }
+__device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
 
-__device__ __forceinline__ void add8(float* acc, const v4u& x) {
+__device__ __forceinline__ void add8(float* acc, const v4u x) {
   acc[0] += __uint_as_float(x.x << 16);
   acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
   acc[2] += __uint_as_float(x.y << 16);

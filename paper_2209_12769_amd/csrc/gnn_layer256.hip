@@ -1,0 +1,438 @@
+// Wave-specialised fused layer for the bulk shape d = H = 256, bf16 (gfx950):
+//     h'[v] = ReLU([h[v] | mean_pred(h)[v] | mean_succ(h)[v]] W + b)
+// (neighbourhood encoding of Sec. 3.3.1 with uniform coefficients), with both
+// means formed on the fly so that a layer reads h once and writes h' once.
+//
+// One workgroup of 8 waves per CU.  Waves 0-3 only issue MFMAs: each owns a
+// 64 x 128 block of the 128 x 256 output tile, reads its A/B fragments from LDS
+// and prefetches the next B chunk of W.  Waves 4-7 only move data: per K chunk
+// of 64 columns each lane owns four (row, 16-byte column) items; it issues the
+// loads of chunk j+2 (the node's own row, or up to kU neighbour rows), then
+// reduces chunk j+1 (issued one step earlier) in fp32 in ascending neighbour
+// order, scales by 1/deg, rounds to bf16 and writes the A chunk into the LDS set
+// the MFMA waves read in the next step.  Rows with more than kU neighbours get
+// their mean from a pre-pass (aggregate_heavy) so that no lane ever walks a long
+// neighbour list inside this kernel.  All waves meet at one barrier per step;
+// the step sequence runs across tiles, so loads for the next tile are in flight
+// while the current one finishes.
+#include <type_traits>
+
+#include "common.h"
+
+namespace dc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short u16;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kBM = 128, kBN = 256, kBK = 64, kD = 256;
+constexpr int kNT = 512;
+constexpr int kU = 3;                       // neighbours gathered in-kernel per row and direction
+constexpr int kNK = 3 * kD / kBK;           // 12 K chunks per tile
+constexpr int kCPR = kD / 8;                // 16-byte chunks per row of h
+constexpr int kASTR = kBK + 8;
+constexpr int kABytes = kBM * kASTR * 2;    // 18432
+constexpr int kBBytes = (kBK / 8) * kBN * 8 * 2;   // 32768
+constexpr int kSetBytes = kABytes + kBBytes;
+constexpr int kOStr = 128 + 8;              // staging row stride (elements) of an MFMA wave
+constexpr int kStageBytes = 32 * kOStr * 2; // 8704 per MFMA wave
+constexpr int kLdsTotal = 2 * kSetBytes + 4 * kStageBytes;
+
+__device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
+__device__ __forceinline__ void add8(float* acc, const v4u x) {
+  acc[0] += __uint_as_float(x.x << 16);
+  acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
+  acc[2] += __uint_as_float(x.y << 16);
+  acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
+  acc[4] += __uint_as_float(x.z << 16);
+  acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
+  acc[6] += __uint_as_float(x.w << 16);
+  acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+}
+
+extern __shared__ __attribute__((aligned(16))) char dc_l256_smem[];
+
+// One step of a data-moving wave: issue the loads of job s+2 into stage PAR and reduce
+// job s+1 (stage 1-PAR, loaded one step ago) into its LDS set.  Every call issues
+// exactly one descriptor load and 4 x kU row loads, with no branch around a vector
+// load, so the in-order load counter lets the reduction run while the new loads fly.
+// Row addresses are 32-bit byte offsets from a per-tile base row: a graph has fewer
+// than 65536 nodes, so every neighbour lies within 65536 rows of the tile.
+struct MoverConst {
+  const char* h;        // activations of this layer
+  const char* hin;      // pre-pass means (rows with long lists), predecessors / successors
+  const char* hout;
+  const v4i* desc_in;
+  const v4i* desc_out;
+  char* smem;
+  int ntot, tile0, per, ar, ach;
+};
+
+template <int PAR>
+__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], unsigned (&off)[2][4][kU],
+                                           int (&dgs)[2][4], v4i& dpend, const MoverConst c) {
+  constexpr unsigned kRowBytes = kD * 2;
+  {
+    const int J = min(s + 2, S - 1);        // clamped: the load count never changes
+    const int ti = J / kNK, kc = J - ti * kNK;
+    const int m0 = (c.tile0 + ti * c.per) * kBM;
+    const int base_row = max(m0 - 65536, 0);
+    const unsigned colb = (unsigned)c.ach * 16u;
+    // file the descriptor fetched one step ago: neighbour ids become byte offsets
+    {
+      const unsigned f0 = (unsigned)(dpend.x - base_row) * kRowBytes + colb;
+      const unsigned f1 = (unsigned)(dpend.y - base_row) * kRowBytes + colb;
+      const unsigned f2 = (unsigned)(dpend.z - base_row) * kRowBytes + colb;
+      const int fd = dpend.w;
+#define DC_FILE(dd, ii) { off[dd][ii][0] = f0; off[dd][ii][1] = f1; off[dd][ii][2] = f2; dgs[dd][ii] = fd; }
+      switch (kc) {
+        case 1: DC_FILE(0, 0) break;
+        case 2: DC_FILE(0, 1) break;
+        case 3: DC_FILE(0, 2) break;
+        case 4: DC_FILE(0, 3) break;
+        case 5: DC_FILE(1, 0) break;
+        case 6: DC_FILE(1, 1) break;
+        case 7: DC_FILE(1, 2) break;
+        case 8: DC_FILE(1, 3) break;
+        default: break;
+      }
+#undef DC_FILE
+    }
+    {
+      const int k = min(kc, 7);
+      const int r = min(m0 + c.ar + 32 * (k & 3), c.ntot - 1);
+      const v4i* dsrc = (k >> 2) ? c.desc_out : c.desc_in;
+      dpend = dsrc[r];
+    }
+    const int seg = kc >> 2;
+    const unsigned kcoff = (unsigned)(kc & 3) * 128u;                     // 64 columns = 128 bytes
+    const char* hb = c.h + (size_t)base_row * kRowBytes;                  // uniform
+    const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = min(m0 + c.ar + 32 * i, c.ntot - 1);               // rows past the end are never stored
+      const unsigned own = (unsigned)(row - base_row) * kRowBytes + colb;
+      const unsigned g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
+      const unsigned g1 = seg == 2 ? off[1][i][1] : off[0][i][1];
+      const unsigned g2 = seg == 2 ? off[1][i][2] : off[0][i][2];
+      const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+      const bool self = seg == 0;
+      const bool pre = !self && dg > kU;                                  // mean comes from the pre-pass
+      const unsigned o0 = ((self || pre) ? own : g0) + kcoff;
+      const unsigned o1 = (self ? own : g1) + kcoff;
+      const unsigned o2 = (self ? own : g2) + kcoff;
+      const char* b0 = pre ? pb : hb;
+      ax[PAR][i][0] = *reinterpret_cast<const v4u*>(b0 + o0);
+      ax[PAR][i][1] = *reinterpret_cast<const v4u*>(hb + o1);
+      ax[PAR][i][2] = *reinterpret_cast<const v4u*>(hb + o2);
+    }
+  }
+  if (s + 1 >= 0 && s + 1 < S) {
+    const int J = s + 1;
+    const int ti = J / kNK, kc = J - ti * kNK;
+    const int seg = kc >> 2;
+    u16* dst = reinterpret_cast<u16*>(c.smem + (J & 1) * kSetBytes);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+      // branch-free mean: slot u counts iff u < deg; x * 1 and + 0 are exact, so the sum
+      // is the same fp32 sum in ascending neighbour order as a loop over the list
+      const float m0f = dg > 0 ? 1.0f : 0.0f, m1f = dg > 1 ? 1.0f : 0.0f, m2f = dg > 2 ? 1.0f : 0.0f;
+      const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
+      const v4u x0 = ax[1 - PAR][i][0], x1 = ax[1 - PAR][i][1], x2 = ax[1 - PAR][i][2];
+      v4u o;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        float lo = __uint_as_float(x0[w] << 16) * m0f;
+        float hi = __uint_as_float(x0[w] & 0xFFFF0000u) * m0f;
+        lo = fmaf(__uint_as_float(x1[w] << 16), m1f, lo);
+        hi = fmaf(__uint_as_float(x1[w] & 0xFFFF0000u), m1f, hi);
+        lo = fmaf(__uint_as_float(x2[w] << 16), m2f, lo);
+        hi = fmaf(__uint_as_float(x2[w] & 0xFFFF0000u), m2f, hi);
+        o[w] = pack_bf16x2(lo * sc, hi * sc);
+      }
+      const bool raw = seg == 0 || dg > kU;   // own row, or the pre-computed (already rounded) mean
+      o = raw ? x0 : o;
+      *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = o;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kNT) void layer256_kernel(
+    const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
+    const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
+    const float* __restrict__ bias, u16* __restrict__ out, const int* __restrict__ node_off, int C,
+    const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  char* smem = dc_l256_smem;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int ntot = node_off[C];
+  const int ntiles = (ntot + kBM - 1) / kBM;
+  // XCD-contiguous tile ranges (workgroups are dealt round-robin over the 8 XCDs)
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per = gridDim.x >> 3;
+  const int tpx = (ntiles + 7) >> 3;
+  const int lim = min(tpx, ntiles - xcd * tpx);
+  const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
+  const int S = nt_wg * kNK;                // steps of this workgroup
+  const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
+
+  if (wave < 4) {
+    // =========================== MFMA waves ===========================================
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    u16* stage = reinterpret_cast<u16*>(smem + 2 * kSetBytes + wave * kStageBytes);
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int mt = t;                        // 0..255 among the MFMA lanes
+    for (int s = -2; s < S; ++s) {
+      // prefetch the B chunk of step s+1 (W is [k/8][H][8]: a chunk is one contiguous run)
+      v4u bx[8];
+      const bool pre = s + 1 >= 0 && s + 1 < S;
+      if (pre) {
+        const int kcn = (s + 1) % kNK;
+        const v4u* wsrc = reinterpret_cast<const v4u*>(Wp) + (size_t)(kcn * (kBK / 8)) * kBN;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bx[i] = wsrc[mt + i * 256];
+      }
+      if (s >= 0) {
+        const u16* As = reinterpret_cast<const u16*>(smem + (s & 1) * kSetBytes);
+        const u16* Bs = reinterpret_cast<const u16*>(smem + (s & 1) * kSetBytes + kABytes);
+#pragma unroll
+        for (int ks = 0; ks < kBK / 16; ++ks) {
+          bf16x8 a[2], b[4];
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            a[i] = *reinterpret_cast<const bf16x8*>(As + (wm * 64 + i * 32 + l32) * kASTR + ks * 16 + lh * 8);
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            b[j] = *reinterpret_cast<const bf16x8*>(Bs + ((ks * 2 + lh) * kBN + wn * 128 + j * 32 + l32) * 8);
+          // operands swapped: accumulator tile is (column, row); a lane owns one output row
+          // and four consecutive columns per register quad
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        }
+      }
+      if (pre) {
+        v4u* Bn = reinterpret_cast<v4u*>(smem + ((s + 1) & 1) * kSetBytes + kABytes);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Bn[mt + i * 256] = bx[i];
+      }
+      if (s >= 0 && (s % kNK) == kNK - 1) {
+        // ---- tile finished: bias, ReLU, bf16, wave-local staging, 16-byte row-contiguous stores
+        const int ti = s / kNK;
+        const int m0 = (xcd * tpx + slot + ti * per) * kBM;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int c0 = j * 32 + 8 * q + 4 * lh;          // column inside the wave's 128
+              const float4 bq = *reinterpret_cast<const float4*>(bias + wn * 128 + c0);
+              v2u p;
+              p.x = pack2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
+              p.y = pack2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
+              *reinterpret_cast<v2u*>(stage + l32 * kOStr + c0) = p;
+#pragma unroll
+              for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
+            }
+          }
+          __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const int idx = lane + 64 * k;
+            const int r = idx >> 4, c = idx & 15;
+            const int gr = m0 + wm * 64 + i * 32 + r;
+            const v4u val = *reinterpret_cast<const v4u*>(stage + r * kOStr + c * 8);
+            if (gr < ntot) *reinterpret_cast<v4u*>(out + (size_t)gr * kBN + wn * 128 + c * 8) = val;
+          }
+          __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
+      __syncthreads();
+    }
+  } else {
+    // =========================== data-moving waves ====================================
+    // Every step issues exactly one descriptor load and 4 x kU row loads and contains no
+    // branch around a vector load, so the hardware's in-order load counter lets the
+    // reduction of the older chunk proceed while the newer chunk's loads are in flight.
+    const int lt = t - 256;
+    unsigned off[2][4][kU];                  // byte offsets of the gathered rows [direction][item][slot]
+    int dgs[2][4];                           // degrees [direction][item]
+    v4u ax[2][4][kU];                        // rows in flight [stage][item][slot]
+    v4i dpend = v4i{0, 0, 0, 0};             // descriptor loaded in the previous step
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      dgs[0][i] = 0;
+      dgs[1][i] = 0;
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        off[0][i][u] = 0u;
+        off[1][i][u] = 0u;
+        ax[0][i][u] = v4u{0u, 0u, 0u, 0u};
+        ax[1][i][u] = v4u{0u, 0u, 0u, 0u};
+      }
+    }
+    MoverConst mc;
+    mc.h = reinterpret_cast<const char*>(h);
+    mc.hin = reinterpret_cast<const char*>(hin_heavy);
+    mc.hout = reinterpret_cast<const char*>(hout_heavy);
+    mc.desc_in = desc_in;
+    mc.desc_out = desc_out;
+    mc.smem = smem;
+    mc.ntot = ntot;
+    mc.tile0 = xcd * tpx + slot;
+    mc.per = per;
+    mc.ar = lt >> 3;                         // rows ar + 32*i, 16-byte column ach of the chunk
+    mc.ach = lt & 7;
+    // S is even (12 jobs per tile), so the loop is unrolled by two with fixed register stages
+    for (int s = -2; s < S; s += 2) {
+      mover_step<0>(s, S, ax, off, dgs, dpend, mc);
+      __syncthreads();
+      mover_step<1>(s + 1, S, ax, off, dgs, dpend, mc);
+      __syncthreads();
+    }
+  }
+}
+
+// One gather descriptor per node and direction: the first kU neighbours (unused slots
+// and rows left to the pre-pass point at the node itself, always a valid row) and the
+// degree.  Depends only on the graphs, so it is built once per forward pass.
+__global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__ in_rp, const int* __restrict__ in_ci,
+                                                          const int* __restrict__ out_rp,
+                                                          const int* __restrict__ out_ci, v4i* __restrict__ desc_in,
+                                                          v4i* __restrict__ desc_out,
+                                                          const int* __restrict__ node_off, int C,
+                                                          const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const long long ntot = node_off[C];
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < 2 * ntot;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int dir = idx >= ntot;
+    const int v = (int)(dir ? idx - ntot : idx);
+    const int* rp = dir ? out_rp : in_rp;
+    const int* ci = dir ? out_ci : in_ci;
+    const int s = rp[v], dg = rp[v + 1] - s;
+    v4i d = v4i{v, v, v, dg};
+    if (dg <= kU) {
+      if (dg > 0) d.x = ci[s];
+      if (dg > 1) d.y = ci[s + 1];
+      if (dg > 2) d.z = ci[s + 2];
+    }
+    (dir ? desc_out : desc_in)[v] = d;
+  }
+}
+
+// Means of rows with more than kU neighbours (both directions), written at the rows'
+// own positions in h_in / h_out; all other rows are left untouched.  Each thread tests
+// one (row, direction) pair (coalesced row-pointer reads); the pairs that qualify are
+// then served by the wave, two at a time, 32 lanes per 512-byte row.
+__global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restrict__ h,
+                                                               const int* __restrict__ in_rp,
+                                                               const int* __restrict__ in_ci,
+                                                               const int* __restrict__ out_rp,
+                                                               const int* __restrict__ out_ci, u16* __restrict__ h_in,
+                                                               u16* __restrict__ h_out,
+                                                               const int* __restrict__ node_off, int C,
+                                                               const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int ntot = node_off[C];
+  const long long total = 2LL * ntot;
+  const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
+  const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+  for (long long base = (long long)blockIdx.x * blockDim.x; base < total; base += (long long)gridDim.x * blockDim.x) {
+    const long long p = base + threadIdx.x;
+    int v = 0, dir = 0, s = 0, e = 0;
+    if (p < total) {
+      dir = p >= ntot;
+      v = (int)(dir ? p - ntot : p);
+      const int* rp = dir ? out_rp : in_rp;
+      s = rp[v];
+      e = rp[v + 1];
+    }
+    unsigned long long todo = __ballot(e - s > kU);
+    while (todo) {
+      // lanes 0-31 take the lowest pending pair, lanes 32-63 the next one (if any)
+      const int first = __ffsll((long long)todo) - 1;
+      const unsigned long long rest = todo & (todo - 1);
+      const int second = rest ? __ffsll((long long)rest) - 1 : -1;
+      todo = rest ? (rest & (rest - 1)) : 0ull;
+      const int src = half ? second : first;
+      const int sl = src < 0 ? 0 : src;
+      const int mv = __shfl(v, sl, 64), md = __shfl(dir, sl, 64), ms = __shfl(s, sl, 64), me = __shfl(e, sl, 64);
+      if (src >= 0) {
+        const int* ci = md ? out_ci : in_ci;
+        float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int k = ms;
+        for (; k + 1 < me; k += 2) {           // two rows in flight; added in ascending order
+          const v4u x0 = h4[(size_t)ci[k] * kCPR + l32];
+          const v4u x1 = h4[(size_t)ci[k + 1] * kCPR + l32];
+          add8(a8, x0);
+          add8(a8, x1);
+        }
+        if (k < me) add8(a8, h4[(size_t)ci[k] * kCPR + l32]);
+        const float sc = 1.0f / (float)(me - ms);
+        v4u o;
+        o.x = pack2(a8[0] * sc, a8[1] * sc);
+        o.y = pack2(a8[2] * sc, a8[3] * sc);
+        o.z = pack2(a8[4] * sc, a8[5] * sc);
+        o.w = pack2(a8[6] * sc, a8[7] * sc);
+        reinterpret_cast<v4u*>(md ? h_out : h_in)[(size_t)mv * kCPR + l32] = o;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+bool layer256_supported(int d, int H, int bf16) { return bf16 && d == kD && H == kBN; }
+
+static_assert(kU == 3, "a descriptor holds three neighbour ids and the degree");
+
+hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(build_desc_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
+                     a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.node_off, a.n_cand,
+                     a.status);
+  return hipGetLastError();
+}
+
+hipError_t launch_layer256(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                           Profiler* prof, hipStream_t s) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer256_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const u16* hh = static_cast<const u16*>(h);
+  if (prof) prof->begin(kFamHeavy, s);
+  hipLaunchKernelGGL(aggregate_heavy_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, hh, a.in_rowptr, a.in_col,
+                     a.out_rowptr, a.out_col, static_cast<u16*>(a.agg[0]), static_cast<u16*>(a.agg[1]), a.node_off,
+                     a.n_cand, a.status);
+  if (prof) prof->end(s);
+  if (prof) prof->begin(kFamFused, s);
+  const int grid = ((a.n_cu + 7) / 8) * 8;
+  hipLaunchKernelGGL(layer256_kernel, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
+                     static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
+                     static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(Wl), bias, static_cast<u16*>(out),
+                     a.node_off, a.n_cand, a.status);
+  if (prof) prof->end(s);
+  return hipGetLastError();
+}
+
+}  // namespace dc
