@@ -139,6 +139,25 @@ __device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
 }
 __device__ __forceinline__ unsigned short to_bf16(float a) { return (unsigned short)(pack_bf16x2(a, 0.f) & 0xFFFFu); }
 
+// Adds the two bf16 values packed in x to the fp32 accumulators (lo half -> lo, hi half
+// -> hi), each scaled by the bf16 factor `one` (1.0 = 0x3F80 to add, 0 to skip), with one
+// V_DOT2C_F32_BF16 per half: acc + x.lo*one + x.hi*0.  The products are exact; the
+// hardware's final add may differ from an IEEE round-to-nearest add by one fp32 ulp,
+// so every kernel that forms a neighbour sum uses this one helper.  The factor must live
+// in a register: the assembler folds the constant 0x3F80 into the inline operand "1.0",
+// which this instruction does not read as a packed bf16 pair (checked on the device).
+__device__ __forceinline__ unsigned bf16_one_reg() {
+  unsigned k;
+  asm volatile("v_mov_b32 %0, 0x3f80" : "=v"(k));
+  return k;
+}
+__device__ __forceinline__ void bf16_pair_add(float& lo, float& hi, unsigned x, unsigned one) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t v = __builtin_bit_cast(bf16x2_t, x);
+  lo = __builtin_amdgcn_fdot2_f32_bf16(v, __builtin_bit_cast(bf16x2_t, one), lo, false);
+  hi = __builtin_amdgcn_fdot2_f32_bf16(v, __builtin_bit_cast(bf16x2_t, one << 16), hi, false);
+}
+
 static inline __host__ __device__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 }  // namespace dc

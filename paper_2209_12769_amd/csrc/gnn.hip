@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const void* __restrict__
   const long long ntot = node_off[C];
   const long long total = 2 * ntot * cpr;
   const uint4* __restrict__ h4 = reinterpret_cast<const uint4*>(h);
+  const unsigned one = bf16_one_reg();
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
     const long long item = idx / cpr;
@@ -51,18 +52,29 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const void* __restrict__
     const int* ci = dir ? out_ci : in_ci;
     const int s = rp[v], e = rp[v + 1];
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int k = s; k < e; ++k) {
-      const uint4 x = h4[(size_t)ci[k] * cpr + ch];
-      if (kBf16) {
-        acc[0] += __uint_as_float(x.x << 16);
-        acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
-        acc[2] += __uint_as_float(x.y << 16);
-        acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
-        acc[4] += __uint_as_float(x.z << 16);
-        acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
-        acc[6] += __uint_as_float(x.w << 16);
-        acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
-      } else {
+    if (kBf16) {
+      // first neighbour unpacked exactly, the others added in ascending order
+      if (e > s) {
+        const uint4 x = h4[(size_t)ci[s] * cpr + ch];
+        acc[0] = __uint_as_float(x.x << 16);
+        acc[1] = __uint_as_float(x.x & 0xFFFF0000u);
+        acc[2] = __uint_as_float(x.y << 16);
+        acc[3] = __uint_as_float(x.y & 0xFFFF0000u);
+        acc[4] = __uint_as_float(x.z << 16);
+        acc[5] = __uint_as_float(x.z & 0xFFFF0000u);
+        acc[6] = __uint_as_float(x.w << 16);
+        acc[7] = __uint_as_float(x.w & 0xFFFF0000u);
+      }
+      for (int k = s + 1; k < e; ++k) {
+        const uint4 x = h4[(size_t)ci[k] * cpr + ch];
+        bf16_pair_add(acc[0], acc[1], x.x, one);
+        bf16_pair_add(acc[2], acc[3], x.y, one);
+        bf16_pair_add(acc[4], acc[5], x.z, one);
+        bf16_pair_add(acc[6], acc[7], x.w, one);
+      }
+    } else {
+      for (int k = s; k < e; ++k) {
+        const uint4 x = h4[(size_t)ci[k] * cpr + ch];
         acc[0] += __uint_as_float(x.x);
         acc[1] += __uint_as_float(x.y);
         acc[2] += __uint_as_float(x.z);

@@ -44,15 +44,21 @@ struct Lds {
 
 __device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
 
-__device__ __forceinline__ void add8(float* acc, const v4u x) {
-  acc[0] += __uint_as_float(x.x << 16);
-  acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
-  acc[2] += __uint_as_float(x.y << 16);
-  acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
-  acc[4] += __uint_as_float(x.z << 16);
-  acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
-  acc[6] += __uint_as_float(x.w << 16);
-  acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+__device__ __forceinline__ void set8(float* acc, const v4u x) {   // first neighbour: exact unpack
+  acc[0] = __uint_as_float(x.x << 16);
+  acc[1] = __uint_as_float(x.x & 0xFFFF0000u);
+  acc[2] = __uint_as_float(x.y << 16);
+  acc[3] = __uint_as_float(x.y & 0xFFFF0000u);
+  acc[4] = __uint_as_float(x.z << 16);
+  acc[5] = __uint_as_float(x.z & 0xFFFF0000u);
+  acc[6] = __uint_as_float(x.w << 16);
+  acc[7] = __uint_as_float(x.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void add8(float* acc, const v4u x, unsigned one) {   // further neighbours
+  bf16_pair_add(acc[0], acc[1], x.x, one);
+  bf16_pair_add(acc[2], acc[3], x.y, one);
+  bf16_pair_add(acc[4], acc[5], x.z, one);
+  bf16_pair_add(acc[6], acc[7], x.w, one);
 }
 
 extern __shared__ __attribute__((aligned(16))) char dc_fused_smem[];
@@ -87,6 +93,7 @@ __global__ __launch_bounds__(kNT, 2) void fused_layer_kernel(
   const int nk = 3 * d / kBK;
   const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
   const int ar = t >> 3, ach = t & 7;     // this thread's A rows are ar + 32*i, 16-byte column ach
+  const unsigned one = bf16_one_reg();
 
   // Each XCD (workgroups are dealt round-robin over the 8 XCDs) sweeps one contiguous
   // range of tiles, so the rows a tile gathers were written / read through the same L2.
@@ -182,12 +189,12 @@ __global__ __launch_bounds__(kNT, 2) void fused_layer_kernel(
         for (int i = 0; i < kAItems; ++i) {
           float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           const int dg = adeg[i], s = ast[i];
-          if (dg > 0) add8(a8, ax[i][0]);
-          if (dg > 1) add8(a8, ax[i][1]);
+          if (dg > 0) set8(a8, ax[i][0]);
+          if (dg > 1) add8(a8, ax[i][1], one);
           for (int u = 2; u < dg; ++u) {
             const int un = stg ? sci[s + u] : gci[s + u];
             const v4u x = h4[(size_t)un * cpr + cc];
-            add8(a8, x);
+            add8(a8, x, one);
           }
           const float sc = dg > 0 ? 1.0f / (float)dg : 0.0f;
           v4u o;

@@ -43,15 +43,21 @@ constexpr int kStageBytes = 32 * kOStr * 2; // 8704 per MFMA wave
 constexpr int kLdsTotal = 2 * kSetBytes + 4 * kStageBytes;
 
 __device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
-__device__ __forceinline__ void add8(float* acc, const v4u x) {
-  acc[0] += __uint_as_float(x.x << 16);
-  acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
-  acc[2] += __uint_as_float(x.y << 16);
-  acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
-  acc[4] += __uint_as_float(x.z << 16);
-  acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
-  acc[6] += __uint_as_float(x.w << 16);
-  acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+__device__ __forceinline__ void set8(float* acc, const v4u x) {   // first neighbour: exact unpack
+  acc[0] = __uint_as_float(x.x << 16);
+  acc[1] = __uint_as_float(x.x & 0xFFFF0000u);
+  acc[2] = __uint_as_float(x.y << 16);
+  acc[3] = __uint_as_float(x.y & 0xFFFF0000u);
+  acc[4] = __uint_as_float(x.z << 16);
+  acc[5] = __uint_as_float(x.z & 0xFFFF0000u);
+  acc[6] = __uint_as_float(x.w << 16);
+  acc[7] = __uint_as_float(x.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void add8(float* acc, const v4u x, unsigned one) {   // further neighbours
+  bf16_pair_add(acc[0], acc[1], x.x, one);
+  bf16_pair_add(acc[2], acc[3], x.y, one);
+  bf16_pair_add(acc[4], acc[5], x.z, one);
+  bf16_pair_add(acc[6], acc[7], x.w, one);
 }
 
 extern __shared__ __attribute__((aligned(16))) char dc_l256_smem[];
@@ -111,24 +117,32 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
     const int seg = kc >> 2;
     const unsigned kcoff = (unsigned)(kc & 3) * 128u;                     // 64 columns = 128 bytes
     const char* hb = c.h + (size_t)base_row * kRowBytes;                  // uniform
-    const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
+    if (seg == 0) {
+      // the node's own rows; the two extra requests of each item repeat the address (they hit
+      // the first one's cache line) and only keep the number of loads per step constant
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = min(m0 + c.ar + 32 * i, c.ntot - 1);               // rows past the end are never stored
-      const unsigned own = (unsigned)(row - base_row) * kRowBytes + colb;
-      const unsigned g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
-      const unsigned g1 = seg == 2 ? off[1][i][1] : off[0][i][1];
-      const unsigned g2 = seg == 2 ? off[1][i][2] : off[0][i][2];
-      const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
-      const bool self = seg == 0;
-      const bool pre = !self && dg > kU;                                  // mean comes from the pre-pass
-      const unsigned o0 = ((self || pre) ? own : g0) + kcoff;
-      const unsigned o1 = (self ? own : g1) + kcoff;
-      const unsigned o2 = (self ? own : g2) + kcoff;
-      const char* b0 = pre ? pb : hb;
-      ax[PAR][i][0] = *reinterpret_cast<const v4u*>(b0 + o0);
-      ax[PAR][i][1] = *reinterpret_cast<const v4u*>(hb + o1);
-      ax[PAR][i][2] = *reinterpret_cast<const v4u*>(hb + o2);
+      for (int i = 0; i < 4; ++i) {
+        const int row = min(m0 + c.ar + 32 * i, c.ntot - 1);             // rows past the end are never stored
+        const unsigned own = (unsigned)(row - base_row) * kRowBytes + colb + kcoff;
+        ax[PAR][i][0] = *reinterpret_cast<const v4u*>(hb + own);
+        ax[PAR][i][1] = *reinterpret_cast<const v4u*>(hb + own);
+        ax[PAR][i][2] = *reinterpret_cast<const v4u*>(hb + own);
+      }
+    } else {
+      const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const unsigned g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
+        const unsigned g1 = seg == 2 ? off[1][i][1] : off[0][i][1];
+        const unsigned g2 = seg == 2 ? off[1][i][2] : off[0][i][2];
+        const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+        // rows left to the pre-pass have all three offsets on the row itself (see build_desc):
+        // slot 0 then reads the row's finished mean from the pre-pass buffer
+        const char* b0 = dg > kU ? pb : hb;
+        ax[PAR][i][0] = *reinterpret_cast<const v4u*>(b0 + (g0 + kcoff));
+        ax[PAR][i][1] = *reinterpret_cast<const v4u*>(hb + (g1 + kcoff));
+        ax[PAR][i][2] = *reinterpret_cast<const v4u*>(hb + (g2 + kcoff));
+      }
     }
   }
   if (s + 1 >= 0 && s + 1 < S) {
@@ -136,28 +150,30 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
     const int ti = J / kNK, kc = J - ti * kNK;
     const int seg = kc >> 2;
     u16* dst = reinterpret_cast<u16*>(c.smem + (J & 1) * kSetBytes);
+    if (seg == 0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
-      // branch-free mean: slot u counts iff u < deg; x * 1 and + 0 are exact, so the sum
-      // is the same fp32 sum in ascending neighbour order as a loop over the list
-      const float m0f = dg > 0 ? 1.0f : 0.0f, m1f = dg > 1 ? 1.0f : 0.0f, m2f = dg > 2 ? 1.0f : 0.0f;
-      const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
-      const v4u x0 = ax[1 - PAR][i][0], x1 = ax[1 - PAR][i][1], x2 = ax[1 - PAR][i][2];
-      v4u o;
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = ax[1 - PAR][i][0];
+    } else {
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        float lo = __uint_as_float(x0[w] << 16) * m0f;
-        float hi = __uint_as_float(x0[w] & 0xFFFF0000u) * m0f;
-        lo = fmaf(__uint_as_float(x1[w] << 16), m1f, lo);
-        hi = fmaf(__uint_as_float(x1[w] & 0xFFFF0000u), m1f, hi);
-        lo = fmaf(__uint_as_float(x2[w] << 16), m2f, lo);
-        hi = fmaf(__uint_as_float(x2[w] & 0xFFFF0000u), m2f, hi);
-        o[w] = pack_bf16x2(lo * sc, hi * sc);
+      for (int i = 0; i < 4; ++i) {
+        const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+        // branch-free mean in ascending neighbour order: slot u counts iff u < deg
+        const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
+        const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
+        const v4u x0 = ax[1 - PAR][i][0], x1 = ax[1 - PAR][i][1], x2 = ax[1 - PAR][i][2];
+        v4u o;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float lo = __uint_as_float(x0[w] << 16);
+          float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
+          bf16_pair_add(lo, hi, x1[w], k1);
+          bf16_pair_add(lo, hi, x2[w], k2);
+          o[w] = pack_bf16x2(lo * sc, hi * sc);
+        }
+        o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
+        *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = o;
       }
-      const bool raw = seg == 0 || dg > kU;   // own row, or the pre-computed (already rounded) mean
-      o = raw ? x0 : o;
-      *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = o;
     }
   }
 }
@@ -354,6 +370,7 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
   const long long total = 2LL * ntot;
   const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
   const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+  const unsigned one = bf16_one_reg();
   for (long long base = (long long)blockIdx.x * blockDim.x; base < total; base += (long long)gridDim.x * blockDim.x) {
     const long long p = base + threadIdx.x;
     int v = 0, dir = 0, s = 0, e = 0;
@@ -377,14 +394,15 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
       if (src >= 0) {
         const int* ci = md ? out_ci : in_ci;
         float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        int k = ms;
+        set8(a8, h4[(size_t)ci[ms] * kCPR + l32]);     // a pair here has more than kU >= 1 neighbours
+        int k = ms + 1;
         for (; k + 1 < me; k += 2) {           // two rows in flight; added in ascending order
           const v4u x0 = h4[(size_t)ci[k] * kCPR + l32];
           const v4u x1 = h4[(size_t)ci[k + 1] * kCPR + l32];
-          add8(a8, x0);
-          add8(a8, x1);
+          add8(a8, x0, one);
+          add8(a8, x1, one);
         }
-        if (k < me) add8(a8, h4[(size_t)ci[k] * kCPR + l32]);
+        if (k < me) add8(a8, h4[(size_t)ci[k] * kCPR + l32], one);
         const float sc = 1.0f / (float)(me - ms);
         v4u o;
         o.x = pack2(a8[0] * sc, a8[1] * sc);
