@@ -62,6 +62,40 @@ __device__ __forceinline__ void add8(float* acc, const v4u x, unsigned one) {   
 
 extern __shared__ __attribute__((aligned(16))) char dc_l256_smem[];
 
+// The data-moving waves keep two jobs' worth of loads in flight while they reduce a third.
+// The compiler's own wait-count bookkeeping gives up on that (it falls back to waiting for
+// every outstanding load), so their vector loads are issued through these helpers, which the
+// compiler does not track, and the waits are placed by hand.  Loads return in issue order,
+// so "at most N newer loads outstanding" is exactly what s_waitcnt vmcnt(N) waits for.
+__device__ __forceinline__ v4u load16_async(const char* uniform_base, unsigned byte_off) {
+  v4u r;
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(r) : "v"(byte_off), "s"(uniform_base) : "memory");
+  return r;
+}
+__device__ __forceinline__ v4u load16_async(const char* addr) {
+  v4u r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(addr) : "memory");
+  return r;
+}
+__device__ __forceinline__ v4i load16i_async(const v4i* addr) {
+  v4i r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(addr) : "memory");
+  return r;
+}
+// Waits until at most N loads issued after the listed registers' loads are outstanding; the
+// registers are named as operands so that no use of them can be scheduled before the wait.
+template <int N>
+__device__ __forceinline__ void wait_loads(v4u (&a)[4][kU]) {
+  asm volatile("s_waitcnt vmcnt(%12)"
+               : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]),
+                 "+v"(a[2][0]), "+v"(a[2][1]), "+v"(a[2][2]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(a[3][2])
+               : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_loads(v4i& d) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(d) : "n"(N));
+}
+
 // One step of a data-moving wave: issue the loads of job s+2 into stage PAR and reduce
 // job s+1 (stage 1-PAR, loaded one step ago) into its LDS set.  Every call issues
 // exactly one descriptor load and 4 x kU row loads, with no branch around a vector
@@ -78,23 +112,28 @@ struct MoverConst {
   int ntot, tile0, per, ar, ach;
 };
 
-template <int PAR>
-__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], unsigned (&off)[2][4][kU],
-                                           int (&dgs)[2][4], v4i& dpend, const MoverConst c) {
+// Q = (s + 3) % 3 is the register stage that receives job s+3; job s+1 sits in stage
+// (Q + 1) % 3 and job s+2 (in flight) in stage (Q + 2) % 3.
+template <int Q>
+__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], unsigned (&off)[2][4][kU],
+                                           int (&dgs)[2][4], v4i (&dq)[3], const MoverConst c) {
   constexpr unsigned kRowBytes = kD * 2;
+  constexpr int QC = (Q + 1) % 3;
   {
-    const int J = min(s + 2, S - 1);        // clamped: the load count never changes
+    const int J = min(s + 3, S - 1);        // clamped: the load count never changes
     const int ti = J / kNK, kc = J - ti * kNK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
     const int base_row = max(m0 - 65536, 0);
     const unsigned colb = (unsigned)c.ach * 16u;
-    // file the descriptor fetched one step ago: neighbour ids become byte offsets
+    // file the descriptor requested two steps ago: neighbour ids become byte offsets
     {
-      const unsigned f0 = (unsigned)(dpend.x - base_row) * kRowBytes + colb;
-      const unsigned f1 = (unsigned)(dpend.y - base_row) * kRowBytes + colb;
-      const unsigned f2 = (unsigned)(dpend.z - base_row) * kRowBytes + colb;
-      const int fd = dpend.w;
-#define DC_FILE(dd, ii) { off[dd][ii][0] = f0; off[dd][ii][1] = f1; off[dd][ii][2] = f2; dgs[dd][ii] = fd; }
+      wait_loads<12 + 13>(dq[QC]);           // newer: the rest of its own step and all of the next
+      const v4i dd = dq[QC];
+      const unsigned f0 = (unsigned)(dd.x - base_row) * kRowBytes + colb;
+      const unsigned f1 = (unsigned)(dd.y - base_row) * kRowBytes + colb;
+      const unsigned f2 = (unsigned)(dd.z - base_row) * kRowBytes + colb;
+      const int fd = dd.w;
+#define DC_FILE(dd_, ii_) { off[dd_][ii_][0] = f0; off[dd_][ii_][1] = f1; off[dd_][ii_][2] = f2; dgs[dd_][ii_] = fd; }
       switch (kc) {
         case 1: DC_FILE(0, 0) break;
         case 2: DC_FILE(0, 1) break;
@@ -109,10 +148,14 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
 #undef DC_FILE
     }
     {
-      const int k = min(kc, 7);
-      const int r = min(m0 + c.ar + 32 * (k & 3), c.ntot - 1);
+      // request the descriptor that job J+2 files: slot k of the tile of job J+1
+      const int Jn = min(J + 1, S - 1);
+      const int tn = Jn / kNK;
+      const int k = min(Jn - tn * kNK, 7);
+      const int mn = (c.tile0 + tn * c.per) * kBM;
+      const int r = min(mn + c.ar + 32 * (k & 3), c.ntot - 1);
       const v4i* dsrc = (k >> 2) ? c.desc_out : c.desc_in;
-      dpend = dsrc[r];
+      dq[Q] = load16i_async(dsrc + r);
     }
     const int seg = kc >> 2;
     const unsigned kcoff = (unsigned)(kc & 3) * 128u;                     // 64 columns = 128 bytes
@@ -124,9 +167,9 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
       for (int i = 0; i < 4; ++i) {
         const int row = min(m0 + c.ar + 32 * i, c.ntot - 1);             // rows past the end are never stored
         const unsigned own = (unsigned)(row - base_row) * kRowBytes + colb + kcoff;
-        ax[PAR][i][0] = *reinterpret_cast<const v4u*>(hb + own);
-        ax[PAR][i][1] = *reinterpret_cast<const v4u*>(hb + own);
-        ax[PAR][i][2] = *reinterpret_cast<const v4u*>(hb + own);
+        ax[Q][i][0] = load16_async(hb, own);
+        ax[Q][i][1] = load16_async(hb, own);
+        ax[Q][i][2] = load16_async(hb, own);
       }
     } else {
       const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
@@ -139,9 +182,9 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
         // rows left to the pre-pass have all three offsets on the row itself (see build_desc):
         // slot 0 then reads the row's finished mean from the pre-pass buffer
         const char* b0 = dg > kU ? pb : hb;
-        ax[PAR][i][0] = *reinterpret_cast<const v4u*>(b0 + (g0 + kcoff));
-        ax[PAR][i][1] = *reinterpret_cast<const v4u*>(hb + (g1 + kcoff));
-        ax[PAR][i][2] = *reinterpret_cast<const v4u*>(hb + (g2 + kcoff));
+        ax[Q][i][0] = load16_async(b0 + (g0 + kcoff));
+        ax[Q][i][1] = load16_async(hb, g1 + kcoff);
+        ax[Q][i][2] = load16_async(hb, g2 + kcoff);
       }
     }
   }
@@ -150,10 +193,11 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
     const int ti = J / kNK, kc = J - ti * kNK;
     const int seg = kc >> 2;
     u16* dst = reinterpret_cast<u16*>(c.smem + (J & 1) * kSetBytes);
+    wait_loads<13 + 13>(ax[QC]);             // newer: the two jobs requested after this one
     if (seg == 0) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = ax[1 - PAR][i][0];
+        *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = ax[QC][i][0];
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -161,7 +205,7 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
         // branch-free mean in ascending neighbour order: slot u counts iff u < deg
         const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
         const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
-        const v4u x0 = ax[1 - PAR][i][0], x1 = ax[1 - PAR][i][1], x2 = ax[1 - PAR][i][2];
+        const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][1], x2 = ax[QC][i][2];
         v4u o;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -174,6 +218,89 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[2][4][kU], un
         o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
         *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = o;
       }
+    }
+  }
+}
+
+// One step of an MFMA wave: request the B chunk of job s+2 (stage PAR), run the MFMAs of
+// job s, hand the B chunk of job s+1 (stage 1-PAR, requested one step ago) to LDS and, at
+// the end of a tile, write the tile out.
+struct MfmaConst {
+  const u16* Wp;
+  const float* bias;
+  u16* out;
+  char* smem;
+  u16* stage;
+  int ntot, tile0, per, wm, wn, l32, lh, lane, mt;
+};
+
+template <int PAR>
+__device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], v4u (&bx)[2][8], const MfmaConst c) {
+  if (s + 2 >= 0) {
+    // W is [k/8][H][8]: the B tile of a chunk is one contiguous run (index clamped at the end)
+    const int kcn = min(s + 2, S - 1) % kNK;
+    const v4u* wsrc = reinterpret_cast<const v4u*>(c.Wp) + (size_t)(kcn * (kBK / 8)) * kBN;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bx[PAR][i] = wsrc[c.mt + i * 256];
+  }
+  if (s >= 0) {
+    const u16* As = reinterpret_cast<const u16*>(c.smem + (s & 1) * kSetBytes);
+    const u16* Bs = reinterpret_cast<const u16*>(c.smem + (s & 1) * kSetBytes + kABytes);
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+      bf16x8 a[2], b[4];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(As + (c.wm * 64 + i * 32 + c.l32) * kASTR + ks * 16 + c.lh * 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(Bs + ((ks * 2 + c.lh) * kBN + c.wn * 128 + j * 32 + c.l32) * 8);
+      // operands swapped: accumulator tile is (column, row); a lane owns one output row
+      // and four consecutive columns per register quad
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    }
+  }
+  if (s + 1 >= 0 && s + 1 < S) {
+    v4u* Bn = reinterpret_cast<v4u*>(c.smem + ((s + 1) & 1) * kSetBytes + kABytes);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) Bn[c.mt + i * 256] = bx[1 - PAR][i];
+  }
+  if (s >= 0 && (s % kNK) == kNK - 1) {
+    // ---- tile finished: bias, ReLU, bf16, wave-local staging, 16-byte row-contiguous stores
+    const int ti = s / kNK;
+    const int m0 = (c.tile0 + ti * c.per) * kBM;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int c0 = j * 32 + 8 * q + 4 * c.lh;          // column inside the wave's 128
+          const float4 bq = *reinterpret_cast<const float4*>(c.bias + c.wn * 128 + c0);
+          v2u p;
+          p.x = pack2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
+          p.y = pack2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
+          *reinterpret_cast<v2u*>(c.stage + c.l32 * kOStr + c0) = p;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int idx = c.lane + 64 * k;
+        const int r = idx >> 4, cc = idx & 15;
+        const int gr = m0 + c.wm * 64 + i * 32 + r;
+        const v4u val = *reinterpret_cast<const v4u*>(c.stage + r * kOStr + cc * 8);
+        if (gr < c.ntot) *reinterpret_cast<v4u*>(c.out + (size_t)gr * kBN + c.wn * 128 + cc * 8) = val;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
@@ -196,11 +323,10 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
   const int S = nt_wg * kNK;                // steps of this workgroup
   const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
 
+  if (S == 0) return;                       // no tile for this workgroup (uniform)
+  // Both kinds of wave run S + 3 steps (s = -3 .. S-1) with one barrier per step.
   if (wave < 4) {
     // =========================== MFMA waves ===========================================
-    const int wm = wave >> 1, wn = wave & 1;
-    const int l32 = lane & 31, lh = lane >> 5;
-    u16* stage = reinterpret_cast<u16*>(smem + 2 * kSetBytes + wave * kStageBytes);
     f32x16 acc[2][4];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -208,89 +334,41 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    const int mt = t;                        // 0..255 among the MFMA lanes
-    for (int s = -2; s < S; ++s) {
-      // prefetch the B chunk of step s+1 (W is [k/8][H][8]: a chunk is one contiguous run)
-      v4u bx[8];
-      const bool pre = s + 1 >= 0 && s + 1 < S;
-      if (pre) {
-        const int kcn = (s + 1) % kNK;
-        const v4u* wsrc = reinterpret_cast<const v4u*>(Wp) + (size_t)(kcn * (kBK / 8)) * kBN;
+    v4u bx[2][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) bx[i] = wsrc[mt + i * 256];
-      }
-      if (s >= 0) {
-        const u16* As = reinterpret_cast<const u16*>(smem + (s & 1) * kSetBytes);
-        const u16* Bs = reinterpret_cast<const u16*>(smem + (s & 1) * kSetBytes + kABytes);
-#pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-          bf16x8 a[2], b[4];
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-            a[i] = *reinterpret_cast<const bf16x8*>(As + (wm * 64 + i * 32 + l32) * kASTR + ks * 16 + lh * 8);
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            b[j] = *reinterpret_cast<const bf16x8*>(Bs + ((ks * 2 + lh) * kBN + wn * 128 + j * 32 + l32) * 8);
-          // operands swapped: accumulator tile is (column, row); a lane owns one output row
-          // and four consecutive columns per register quad
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
-        }
-      }
-      if (pre) {
-        v4u* Bn = reinterpret_cast<v4u*>(smem + ((s + 1) & 1) * kSetBytes + kABytes);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) Bn[mt + i * 256] = bx[i];
-      }
-      if (s >= 0 && (s % kNK) == kNK - 1) {
-        // ---- tile finished: bias, ReLU, bf16, wave-local staging, 16-byte row-contiguous stores
-        const int ti = s / kNK;
-        const int m0 = (xcd * tpx + slot + ti * per) * kBM;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int c0 = j * 32 + 8 * q + 4 * lh;          // column inside the wave's 128
-              const float4 bq = *reinterpret_cast<const float4*>(bias + wn * 128 + c0);
-              v2u p;
-              p.x = pack2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
-              p.y = pack2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
-              *reinterpret_cast<v2u*>(stage + l32 * kOStr + c0) = p;
-#pragma unroll
-              for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
-            }
-          }
-          __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const int idx = lane + 64 * k;
-            const int r = idx >> 4, c = idx & 15;
-            const int gr = m0 + wm * 64 + i * 32 + r;
-            const v4u val = *reinterpret_cast<const v4u*>(stage + r * kOStr + c * 8);
-            if (gr < ntot) *reinterpret_cast<v4u*>(out + (size_t)gr * kBN + wn * 128 + c * 8) = val;
-          }
-          __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-        }
-      }
+    for (int i = 0; i < 8; ++i) {
+      bx[0][i] = v4u{0u, 0u, 0u, 0u};
+      bx[1][i] = v4u{0u, 0u, 0u, 0u};
+    }
+    MfmaConst mc;
+    mc.Wp = Wp;
+    mc.bias = bias;
+    mc.out = out;
+    mc.smem = smem;
+    mc.stage = reinterpret_cast<u16*>(smem + 2 * kSetBytes + wave * kStageBytes);
+    mc.ntot = ntot;
+    mc.tile0 = xcd * tpx + slot;
+    mc.per = per;
+    mc.wm = wave >> 1;
+    mc.wn = wave & 1;
+    mc.l32 = lane & 31;
+    mc.lh = lane >> 5;
+    mc.lane = lane;
+    mc.mt = t;
+    __syncthreads();                          // step -3: only the data-moving waves work
+    for (int s = -2; s < S; s += 2) {         // S is a multiple of 12
+      mfma_step<0>(s, S, acc, bx, mc);
+      __syncthreads();
+      mfma_step<1>(s + 1, S, acc, bx, mc);
       __syncthreads();
     }
   } else {
     // =========================== data-moving waves ====================================
-    // Every step issues exactly one descriptor load and 4 x kU row loads and contains no
-    // branch around a vector load, so the hardware's in-order load counter lets the
-    // reduction of the older chunk proceed while the newer chunk's loads are in flight.
     const int lt = t - 256;
     unsigned off[2][4][kU];                  // byte offsets of the gathered rows [direction][item][slot]
     int dgs[2][4];                           // degrees [direction][item]
-    v4u ax[2][4][kU];                        // rows in flight [stage][item][slot]
-    v4i dpend = v4i{0, 0, 0, 0};             // descriptor loaded in the previous step
+    v4u ax[3][4][kU];                        // rows in flight [stage][item][slot]
+    v4i dq[3];                               // descriptors in flight
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       dgs[0][i] = 0;
@@ -301,6 +379,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
         off[1][i][u] = 0u;
         ax[0][i][u] = v4u{0u, 0u, 0u, 0u};
         ax[1][i][u] = v4u{0u, 0u, 0u, 0u};
+        ax[2][i][u] = v4u{0u, 0u, 0u, 0u};
       }
     }
     MoverConst mc;
@@ -315,11 +394,23 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.per = per;
     mc.ar = lt >> 3;                         // rows ar + 32*i, 16-byte column ach of the chunk
     mc.ach = lt & 7;
-    // S is even (12 jobs per tile), so the loop is unrolled by two with fixed register stages
-    for (int s = -2; s < S; s += 2) {
-      mover_step<0>(s, S, ax, off, dgs, dpend, mc);
+    dq[0] = v4i{0, 0, 0, 0};
+    dq[1] = v4i{0, 0, 0, 0};
+    dq[2] = v4i{0, 0, 0, 0};
+    {
+      // descriptor slot 0 of the first tile has no earlier step to be requested in; job 1
+      // files the descriptor of stage (1 - 2) mod 3 = 2
+      const int r = min(mc.tile0 * kBM + mc.ar, ntot - 1);
+      dq[2] = desc_in[r];
+    }
+    __builtin_amdgcn_s_waitcnt(0);           // nothing of the set-up may still be in flight
+
+    for (int s = -3; s < S; s += 3) {        // S + 3 is a multiple of 3
+      mover_step<0>(s, S, ax, off, dgs, dq, mc);
       __syncthreads();
-      mover_step<1>(s + 1, S, ax, off, dgs, dpend, mc);
+      mover_step<1>(s + 1, S, ax, off, dgs, dq, mc);
+      __syncthreads();
+      mover_step<2>(s + 2, S, ax, off, dgs, dq, mc);
       __syncthreads();
     }
   }
