@@ -37,10 +37,12 @@ constexpr int kCPR = kD / 8;                // 16-byte chunks per row of h
 constexpr int kASTR = kBK + 8;
 constexpr int kABytes = kBM * kASTR * 2;    // 18432
 constexpr int kBBytes = (kBK / 8) * kBN * 8 * 2;   // 32768
-constexpr int kSetBytes = kABytes + kBBytes;
-constexpr int kOStr = 128 + 8;              // staging row stride (elements) of an MFMA wave
-constexpr int kStageBytes = 32 * kOStr * 2; // 8704 per MFMA wave
-constexpr int kLdsTotal = 2 * kSetBytes + 4 * kStageBytes;
+constexpr int kBOff = 2 * kABytes;          // two A buffers (job parity), then a ring of three B buffers
+constexpr int kOStr = 64 + 8;               // staging row stride (elements) of an MFMA wave
+constexpr int kStageBytes = 32 * kOStr * 2; // 4608 per MFMA wave: 32 rows x 64 columns per pass
+constexpr int kStageOff = kBOff + 3 * kBBytes;
+constexpr int kLdsTotal = kStageOff + 4 * kStageBytes;
+typedef __attribute__((address_space(3))) char lds_char;
 
 __device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
 __device__ __forceinline__ void set8(float* acc, const v4u x) {   // first neighbour: exact unpack
@@ -81,6 +83,18 @@ __device__ __forceinline__ v4i load16i_async(const v4i* addr) {
   v4i r;
   asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(addr) : "memory");
   return r;
+}
+// 16 bytes per lane from global memory straight into LDS (no registers): lane l of the wave
+// writes lds_base + 16*l.  Untracked by the compiler as well; waited for with wait_vm<N>().
+__device__ __forceinline__ void load16_to_lds(const void* gaddr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14;
+  // the other two counters are left at their maximum (no wait)
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 // Waits until at most N loads issued after the listed registers' loads are outstanding; the
 // registers are named as operands so that no use of them can be scheduled before the wait.
@@ -192,7 +206,7 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], un
     const int J = s + 1;
     const int ti = J / kNK, kc = J - ti * kNK;
     const int seg = kc >> 2;
-    u16* dst = reinterpret_cast<u16*>(c.smem + (J & 1) * kSetBytes);
+    u16* dst = reinterpret_cast<u16*>(c.smem + (J & 1) * kABytes);
     wait_loads<13 + 13>(ax[QC]);             // newer: the two jobs requested after this one
     if (seg == 0) {
 #pragma unroll
@@ -222,30 +236,35 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], un
   }
 }
 
-// One step of an MFMA wave: request the B chunk of job s+2 (stage PAR), run the MFMAs of
-// job s, hand the B chunk of job s+1 (stage 1-PAR, requested one step ago) to LDS and, at
-// the end of a tile, write the tile out.
+// One step of an MFMA wave: request the B chunk of job s+2 (straight into its LDS ring
+// slot), run the MFMAs of job s, make sure the B chunk of job s+1 has landed and, at the end
+// of a tile, write the tile out.
 struct MfmaConst {
   const u16* Wp;
   const float* bias;
   u16* out;
   char* smem;
   u16* stage;
-  int ntot, tile0, per, wm, wn, l32, lh, lane, mt;
+  unsigned lds0;        // LDS byte address of smem
+  int ntot, tile0, per, wm, wn, l32, lh, lane, wave;
 };
 
-template <int PAR>
-__device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], v4u (&bx)[2][8], const MfmaConst c) {
+__device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
   if (s + 2 >= 0) {
-    // W is [k/8][H][8]: the B tile of a chunk is one contiguous run (index clamped at the end)
-    const int kcn = min(s + 2, S - 1) % kNK;
-    const v4u* wsrc = reinterpret_cast<const v4u*>(c.Wp) + (size_t)(kcn * (kBK / 8)) * kBN;
+    // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run; each wave moves
+    // eight 1 KB pieces of it (chunk index clamped at the end: the count of loads is fixed)
+    const int jn = min(s + 2, S - 1);
+    const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % kNK) * kBBytes;
+    const unsigned ring = c.lds0 + kBOff + (unsigned)((s + 2) % 3) * kBBytes;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) bx[PAR][i] = wsrc[c.mt + i * 256];
+    for (int i = 0; i < 8; ++i) {
+      const int piece = c.wave * 8 + i;     // c.wave is wave-uniform by construction (readfirstlane)
+      load16_to_lds(wsrc + piece * 1024 + c.lane * 16, ring + piece * 1024);
+    }
   }
   if (s >= 0) {
-    const u16* As = reinterpret_cast<const u16*>(c.smem + (s & 1) * kSetBytes);
-    const u16* Bs = reinterpret_cast<const u16*>(c.smem + (s & 1) * kSetBytes + kABytes);
+    const u16* As = reinterpret_cast<const u16*>(c.smem + (s & 1) * kABytes);
+    const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (s % 3) * kBBytes);
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       bf16x8 a[2], b[4];
@@ -264,45 +283,49 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], v4u
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   }
-  if (s + 1 >= 0 && s + 1 < S) {
-    v4u* Bn = reinterpret_cast<v4u*>(c.smem + ((s + 1) & 1) * kSetBytes + kABytes);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) Bn[c.mt + i * 256] = bx[1 - PAR][i];
-  }
-  if (s >= 0 && (s % kNK) == kNK - 1) {
+  const bool tile_end = s >= 0 && (s % kNK) == kNK - 1;
+  if (tile_end) {
     // ---- tile finished: bias, ReLU, bf16, wave-local staging, 16-byte row-contiguous stores
     const int ti = s / kNK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int jh = 0; jh < 2; ++jh) {      // 32 rows x 64 columns per pass through the staging area
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int c0 = j * 32 + 8 * q + 4 * c.lh;          // column inside the wave's 128
-          const float4 bq = *reinterpret_cast<const float4*>(c.bias + c.wn * 128 + c0);
-          v2u p;
-          p.x = pack2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
-          p.y = pack2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
-          *reinterpret_cast<v2u*>(c.stage + c.l32 * kOStr + c0) = p;
+        for (int jj = 0; jj < 2; ++jj) {
+          const int j = 2 * jh + jj;
 #pragma unroll
-          for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
+          for (int q = 0; q < 4; ++q) {
+            const int c0 = jj * 32 + 8 * q + 4 * c.lh;           // column inside the pass
+            int cb = c.wn * 128 + jh * 64 + c0;
+            asm volatile("" : "+v"(cb));   // opaque: keeps the bias loads out of the step loop's live set
+            const float4 bq = *reinterpret_cast<const float4*>(c.bias + cb);
+            v2u p;
+            p.x = pack2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
+            p.y = pack2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
+            *reinterpret_cast<v2u*>(c.stage + c.l32 * kOStr + c0) = p;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
+          }
         }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-      __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int idx = c.lane + 64 * k;
-        const int r = idx >> 4, cc = idx & 15;
-        const int gr = m0 + c.wm * 64 + i * 32 + r;
-        const v4u val = *reinterpret_cast<const v4u*>(c.stage + r * kOStr + cc * 8);
-        if (gr < c.ntot) *reinterpret_cast<v4u*>(c.out + (size_t)gr * kBN + c.wn * 128 + cc * 8) = val;
+        for (int k = 0; k < 4; ++k) {
+          const int idx = c.lane + 64 * k;
+          const int r = idx >> 3, cc = idx & 7;
+          const int gr = m0 + c.wm * 64 + i * 32 + r;
+          const v4u val = *reinterpret_cast<const v4u*>(c.stage + r * kOStr + cc * 8);
+          if (gr < c.ntot) *reinterpret_cast<v4u*>(c.out + (size_t)gr * kBN + c.wn * 128 + jh * 64 + cc * 8) = val;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
-      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-      __builtin_amdgcn_wave_barrier();
     }
+    wait_vm<0>();      // the tile's stores share the counter with the B requests: drain everything
   }
+  wait_vm<8>();        // all but the eight requests of this step: the B chunk of job s+1 is in LDS
 }
 
 __global__ __launch_bounds__(kNT) void layer256_kernel(
@@ -334,18 +357,13 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    v4u bx[2][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      bx[0][i] = v4u{0u, 0u, 0u, 0u};
-      bx[1][i] = v4u{0u, 0u, 0u, 0u};
-    }
     MfmaConst mc;
     mc.Wp = Wp;
     mc.bias = bias;
     mc.out = out;
     mc.smem = smem;
-    mc.stage = reinterpret_cast<u16*>(smem + 2 * kSetBytes + wave * kStageBytes);
+    mc.stage = reinterpret_cast<u16*>(smem + kStageOff + wave * kStageBytes);
+    mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256_smem);
     mc.ntot = ntot;
     mc.tile0 = xcd * tpx + slot;
     mc.per = per;
@@ -354,12 +372,10 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.l32 = lane & 31;
     mc.lh = lane >> 5;
     mc.lane = lane;
-    mc.mt = t;
+    mc.wave = __builtin_amdgcn_readfirstlane(wave);   // scalar: the LDS base of a DMA load must be uniform
     __syncthreads();                          // step -3: only the data-moving waves work
-    for (int s = -2; s < S; s += 2) {         // S is a multiple of 12
-      mfma_step<0>(s, S, acc, bx, mc);
-      __syncthreads();
-      mfma_step<1>(s + 1, S, acc, bx, mc);
+    for (int s = -2; s < S; ++s) {
+      mfma_step(s, S, acc, mc);
       __syncthreads();
     }
   } else {
