@@ -19,6 +19,10 @@
 
 #include "common.h"
 
+#ifndef DC_SPLIT_SIMD
+#define DC_SPLIT_SIMD 0
+#endif
+
 namespace dc {
 namespace {
 
@@ -32,6 +36,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kBM = 128, kBN = 256, kBK = 64, kD = 256;
 constexpr int kNT = 512;
 constexpr int kU = 3;                       // neighbours gathered in-kernel per row and direction
+constexpr bool kSplitSimd = DC_SPLIT_SIMD;
 constexpr int kNK = 3 * kD / kBK;           // 12 K chunks per tile
 constexpr int kCPR = kD / 8;                // 16-byte chunks per row of h
 constexpr int kASTR = kBK + 8;
@@ -348,7 +353,11 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
 
   if (S == 0) return;                       // no tile for this workgroup (uniform)
   // Both kinds of wave run S + 3 steps (s = -3 .. S-1) with one barrier per step.
-  if (wave < 4) {
+  // Waves are dealt to the four SIMDs round-robin.  kSplitSimd puts both kinds of wave on
+  // separate SIMDs (waves 0,1,4,5 issue MFMAs on SIMD 0/1; waves 2,3,6,7 move data on SIMD 2/3).
+  const bool is_mfma = kSplitSimd ? ((wave & 2) == 0) : (wave < 4);
+  const int role_wave = kSplitSimd ? ((wave & 1) | ((wave >> 2) << 1)) : (wave & 3);   // 0..3 within the role
+  if (is_mfma) {
     // =========================== MFMA waves ===========================================
     f32x16 acc[2][4];
 #pragma unroll
@@ -362,17 +371,17 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.bias = bias;
     mc.out = out;
     mc.smem = smem;
-    mc.stage = reinterpret_cast<u16*>(smem + kStageOff + wave * kStageBytes);
+    mc.stage = reinterpret_cast<u16*>(smem + kStageOff + role_wave * kStageBytes);
     mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256_smem);
     mc.ntot = ntot;
     mc.tile0 = xcd * tpx + slot;
     mc.per = per;
-    mc.wm = wave >> 1;
-    mc.wn = wave & 1;
+    mc.wm = role_wave >> 1;
+    mc.wn = role_wave & 1;
     mc.l32 = lane & 31;
     mc.lh = lane >> 5;
     mc.lane = lane;
-    mc.wave = __builtin_amdgcn_readfirstlane(wave);   // scalar: the LDS base of a DMA load must be uniform
+    mc.wave = __builtin_amdgcn_readfirstlane(role_wave);   // scalar: the LDS base of a DMA load must be uniform
     __syncthreads();                          // step -3: only the data-moving waves work
     for (int s = -2; s < S; ++s) {
       mfma_step(s, S, acc, mc);
@@ -380,7 +389,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     }
   } else {
     // =========================== data-moving waves ====================================
-    const int lt = t - 256;
+    const int lt = role_wave * 64 + lane;
     unsigned off[2][4][kU];                  // byte offsets of the gathered rows [direction][item][slot]
     int dgs[2][4];                           // degrees [direction][item]
     v4u ax[3][4][kU];                        // rows in flight [stage][item][slot]
@@ -450,11 +459,11 @@ __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__
     const int* rp = dir ? out_rp : in_rp;
     const int* ci = dir ? out_ci : in_ci;
     const int s = rp[v], dg = rp[v + 1] - s;
-    v4i d = v4i{v, v, v, dg};
-    if (dg <= kU) {
-      if (dg > 0) d.x = ci[s];
-      if (dg > 1) d.y = ci[s + 1];
-      if (dg > 2) d.z = ci[s + 2];
+    v4i d = v4i{v, v, v, dg};          // rows left to the pre-pass (and empty lists) point at the row itself
+    if (dg <= kU && dg > 0) {
+      d.x = ci[s];                     // unused slots repeat the first neighbour: same cache line, never summed
+      d.y = dg > 1 ? ci[s + 1] : d.x;
+      d.z = dg > 2 ? ci[s + 2] : d.x;
     }
     (dir ? desc_out : desc_in)[v] = d;
   }
