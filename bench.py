@@ -32,22 +32,27 @@ def algorithmic_work(w, ntot, etot):
     C = w.n_cand
     base = sum(4 * (g.n + 1) + 4 * g.e + 4 * g.n * m.F for g in w.graphs)       # read once per batch
     contract = 4 * nb + 4 * nb + ntot * m.F * s + 2 * 4 * (ntot + C + etot) + base
-    agg_b, upd_f, upd_b, fus_f, fus_b = 0, 0, 0, 0, 0
+    agg_b, upd_f, upd_b = 0, 0, 0
+    fus = {"fused_layer": [0, 0], "layer256": [0, 0]}
     d = m.F
     for _ in range(m.L):
+        bulk = m.dtype == "bf16" and m.H == 256 and d == 256
         fused = m.dtype == "bf16" and m.H in (128, 256) and d % 64 == 0
         idx = 2 * 4 * (ntot + etot)
         flops = 2 * ntot * 3 * d * m.H
         if fused:       # means never leave the chip: read h, write h', read the neighbour lists and W
-            fus_f += flops
-            fus_b += ntot * d * s + ntot * m.H * s + idx + 3 * d * m.H * s
+            k = fus["layer256" if bulk else "fused_layer"]
+            k[0] += flops
+            k[1] += ntot * d * s + ntot * m.H * s + idx + 3 * d * m.H * s
         else:           # read h, write both means; then read [h|h_in|h_out] and W, write h'
             agg_b += ntot * d * s + 2 * ntot * d * s + idx
             upd_f += flops
             upd_b += ntot * (3 * d + m.H) * s + 3 * d * m.H * s
         d = m.H
     return {"contract": {"bytes": contract}, "aggregate": {"bytes": agg_b},
-            "update": {"flops": upd_f, "bytes": upd_b}, "fused_layer": {"flops": fus_f, "bytes": fus_b},
+            "update": {"flops": upd_f, "bytes": upd_b},
+            "fused_layer": {"flops": fus["fused_layer"][0], "bytes": fus["fused_layer"][1]},
+            "layer256": {"flops": fus["layer256"][0], "bytes": fus["layer256"][1]},
             "readout_head": {"bytes": ntot * m.H * s}}
 
 
@@ -87,6 +92,9 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--n-cand", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
+                         "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; candidates are independent, so more GPUs would each take a "
@@ -94,6 +102,16 @@ def main():
         sys.exit(2)
 
     import torch
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * (1 << 20) // 4
+        x = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        y = torch.empty_like(x)
+        for _ in range(5):
+            torch.neg(x, out=y)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_mib": args.copy_calibration, "launches": 5,
+                          "read_bytes_per_launch": n * 4, "write_bytes_per_launch": n * 4}))
+        return
     from paper_2209_12769_amd import binding as B
     from paper_2209_12769_amd import workloads as wl
 
@@ -119,23 +137,23 @@ def main():
 
     work = algorithmic_work(w, ntot, etot)
     fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
-    # a fused layer = the pre-pass for rows with long neighbour lists + the MFMA kernel
-    fam["fused_all"] = (fam["fused_layer"][0] + fam["aggregate_heavy"][0], fam["fused_layer"][1])
     kernels = {}
     for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
-                      ("fused_layer", "fused_all"), ("readout_head", "readout_head")):
+                      ("fused_layer", "fused_layer"), ("layer256", "layer256"),
+                      ("aggregate_heavy", "aggregate_heavy"), ("build_desc", "build_desc"),
+                      ("readout_head", "readout_head")):
         ms_total, launches = fam[key]
         if launches == 0:
             continue
         per_step_ms = ms_total / args.steps
         k = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches / args.steps}
-        if per_step_ms > 0:
+        if per_step_ms > 0 and name in work:
             k["GB/s"] = round(work[name]["bytes"] / (per_step_ms * 1e-3) / 1e9, 1)
             if "flops" in work[name]:
                 k["TFLOP/s"] = round(work[name]["flops"] / (per_step_ms * 1e-3) / 1e12, 2)
         kernels[name] = k
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-    if dom in ("update", "fused_layer"):
+    if dom in ("update", "fused_layer", "layer256"):
         peak = PEAK_MFMA_TFLOPS[w.model.dtype]
         ach = kernels[dom].get("TFLOP/s", 0.0)
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",

@@ -65,7 +65,8 @@ struct dc_ctx {
 namespace {
 
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
-                                             "fused_layer", "aggregate_heavy", "readout_head"};
+                                             "fused_layer", "layer256", "aggregate_heavy", "build_desc",
+                                             "readout_head"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 

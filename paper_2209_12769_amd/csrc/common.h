@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamHeavy, kFamReadout, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamHeavy, kFamDesc, kFamReadout, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;

@@ -377,7 +377,7 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   const int agg_grid = a.n_cu * 8;
   if (a.allow_fused && a.L > 1 && layer256_supported(a.H, a.H, a.bf16)) {
     // neighbour descriptors depend on the graphs only: built once, used by every hidden layer
-    if (prof) prof->begin(kFamHeavy, s);
+    if (prof) prof->begin(kFamDesc, s);
     hipError_t e = launch_build_desc(a, s);
     if (prof) prof->end(s);
     if (e != hipSuccess) return e;

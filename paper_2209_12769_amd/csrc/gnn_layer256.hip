@@ -559,7 +559,7 @@ hipError_t launch_layer256(const void* h, const GnnArgs& a, const void* Wl, cons
                      a.out_rowptr, a.out_col, static_cast<u16*>(a.agg[0]), static_cast<u16*>(a.agg[1]), a.node_off,
                      a.n_cand, a.status);
   if (prof) prof->end(s);
-  if (prof) prof->begin(kFamFused, s);
+  if (prof) prof->begin(kFamLayer256, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
   hipLaunchKernelGGL(layer256_kernel, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
                      static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
