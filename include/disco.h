@@ -41,7 +41,7 @@
  *    (Alg. 1, "if H' is valid").  Contraction and forward pass are defined
  *    for every labelling.
  *  - All integer arrays are int32.  Limits: a base graph has fewer than 65536
- *    nodes; all totals fit in int32; F and H are multiples of 16, H <= 512.
+ *    nodes; all totals fit in int32; F is a multiple of 16, H a multiple of 32, both <= 512.
  *  - Calls on one dc_ctx must not overlap (the context owns scratch memory).
  */
 #ifndef DISCO_H_
@@ -148,6 +148,10 @@ dc_status dc_contract_graphs(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
 
 /* Forward pass over a batch laid out as above (typically the output of
  * dc_contract_graphs; node_off[n_cand] must not exceed the context's max_nodes).
+ * The batch is validated on the device first (offsets ascending from 0, every graph
+ * below 65536 nodes, row pointers ascending within cap_edges, every neighbour inside its
+ * own graph); a violation makes the call a no-op that dc_check reports as
+ * DC_ERR_BAD_GRAPH or DC_ERR_CAPACITY.
  * pred dev [n_cand] fp32: predicted per-iteration time per candidate.            */
 dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* stream);
 

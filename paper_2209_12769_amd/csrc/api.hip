@@ -233,9 +233,49 @@ dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pr
   return DC_OK;
 }
 
-// Device-side guard for dc_gnn_forward on caller-provided batches.
-__global__ void check_batch_kernel(const int* node_off, int C, long long max_nodes, int* status) {
-  if (node_off[C] > max_nodes || node_off[0] != 0) set_error(status, (int)DC_ERR_CAPACITY);
+// Device-side guard for dc_gnn_forward on caller-provided batches: sizes within the
+// capacity, every graph below 65536 nodes, row pointers ascending and within the edge
+// capacity, every neighbour inside its own graph.  One thread per node; on any
+// violation the status word is set and every later kernel of the call returns at once.
+__global__ __launch_bounds__(256) void check_batch_kernel(const int* __restrict__ node_off, int C, long long max_nodes,
+                                                           long long cap_edges, const int* __restrict__ out_rp,
+                                                           const int* __restrict__ out_ci,
+                                                           const int* __restrict__ in_rp,
+                                                           const int* __restrict__ in_ci, int* status) {
+  const long long ntot = node_off[C];
+  if (ntot > max_nodes || ntot < 0 || node_off[0] != 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) set_error(status, (int)DC_ERR_CAPACITY);
+    return;
+  }
+  bool bad = false;
+  for (long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x; c < C; c += (long long)gridDim.x * blockDim.x) {
+    const int n = node_off[c + 1] - node_off[c];
+    bad |= n < 0 || n >= 65536;
+  }
+  for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < ntot;
+       v += (long long)gridDim.x * blockDim.x) {
+    int lo = 0, hi = C;                       // graph of v: last c with node_off[c] <= v
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (node_off[mid] <= v) lo = mid; else hi = mid;
+    }
+    const int g0 = node_off[lo], g1 = node_off[lo + 1];
+    bad |= v >= g1;                           // offsets not ascending
+    for (int dir = 0; dir < 2 && !bad; ++dir) {
+      const int* rp = dir ? out_rp : in_rp;
+      const int* ci = dir ? out_ci : in_ci;
+      const int s = rp[v], e = rp[v + 1];
+      if (s < 0 || e < s || e > cap_edges || e - s >= 65536) {
+        bad = true;
+        break;
+      }
+      for (int k = s; k < e; ++k) {
+        const int u = ci[k];
+        bad |= u < g0 || u >= g1;
+      }
+    }
+  }
+  if (bad) set_error(status, (int)DC_ERR_BAD_GRAPH);
 }
 
 __global__ void empty_batch_kernel(int* node_off, int* edge_off, int* orp, int* irp, int* totals) {
@@ -517,7 +557,9 @@ dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* str
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
   const Caps k = caps_of(ctx->cfg);
-  hipLaunchKernelGGL(check_batch_kernel, dim3(1), dim3(1), 0, s, in->node_off, in->n_cand, k.NN, ctx->status);
+  hipLaunchKernelGGL(check_batch_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, s, in->node_off, in->n_cand,
+                     (long long)(in->cap_nodes < k.NN ? in->cap_nodes : k.NN), (long long)in->cap_edges, in->out_rowptr, in->out_col, in->in_rowptr,
+                     in->in_col, ctx->status);
   BatchView v;
   v.node_off = in->node_off;
   v.edge_off = in->edge_off;
@@ -559,6 +601,7 @@ dc_status dc_check(dc_ctx* ctx, void* stream) {
   if (code != 0) {
     ctx->err = code == DC_ERR_BAD_PARTITION ? "device: label out of range or candidate/base-graph mismatch"
              : code == DC_ERR_CAPACITY      ? "device: sizes exceed the configured or provided capacity"
+             : code == DC_ERR_BAD_GRAPH     ? "device: batch malformed (offsets, row pointers or a neighbour out of its graph)"
                                             : "device: error";
   }
   return static_cast<dc_status>(code);

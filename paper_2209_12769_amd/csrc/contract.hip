@@ -428,13 +428,26 @@ __global__ __launch_bounds__(256) void finalize_kernel(BaseGraphs bg, int C, con
   for (int i = t; i < G * q; i += T) {
     const int g = i / q, f = i - g * q;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int m = ms[g]; m < ms[g + 1]; ++m) {
-      const float4 x = X4[(size_t)mem[m] * q + f];
-      acc.x += x.x;
-      acc.y += x.y;
-      acc.z += x.z;
-      acc.w += x.w;
+    int m = ms[g];
+    const int me = ms[g + 1];
+#define DC_ADD(x_) { acc.x += x_.x; acc.y += x_.y; acc.z += x_.z; acc.w += x_.w; }
+    for (; m + 3 < me; m += 4) {               // four member rows in flight, added in member order
+      const int i0 = mem[m], i1 = mem[m + 1], i2 = mem[m + 2], i3 = mem[m + 3];
+      const float4 x0 = X4[(size_t)i0 * q + f], x1 = X4[(size_t)i1 * q + f];
+      const float4 x2 = X4[(size_t)i2 * q + f], x3 = X4[(size_t)i3 * q + f];
+      DC_ADD(x0) DC_ADD(x1) DC_ADD(x2) DC_ADD(x3)
     }
+    if (m + 1 < me) {
+      const int i0 = mem[m], i1 = mem[m + 1];
+      const float4 x0 = X4[(size_t)i0 * q + f], x1 = X4[(size_t)i1 * q + f];
+      DC_ADD(x0) DC_ADD(x1)
+      m += 2;
+    }
+    if (m < me) {
+      const float4 x0 = X4[(size_t)mem[m] * q + f];
+      DC_ADD(x0)
+    }
+#undef DC_ADD
     const size_t row = (size_t)(n0 + g);
     if (kBf16) {
       uint2 p;

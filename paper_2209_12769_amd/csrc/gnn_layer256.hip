@@ -471,8 +471,8 @@ __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__
 
 // Means of rows with more than kU neighbours (both directions), written at the rows'
 // own positions in h_in / h_out; all other rows are left untouched.  Each thread tests
-// one (row, direction) pair (coalesced row-pointer reads); the pairs that qualify are
-// then served by the wave, two at a time, 32 lanes per 512-byte row.
+// one (row, direction) pair; the pairs that qualify are then served by the wave, two at
+// a time, 32 lanes per 512-byte row.  The grid must be a multiple of 8 workgroups.
 __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restrict__ h,
                                                                const int* __restrict__ in_rp,
                                                                const int* __restrict__ in_ci,
@@ -487,12 +487,18 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
   const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
   const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
   const unsigned one = bf16_one_reg();
-  for (long long base = (long long)blockIdx.x * blockDim.x; base < total; base += (long long)gridDim.x * blockDim.x) {
-    const long long p = base + threadIdx.x;
+  // Chunks of 128 rows x 2 directions.  Workgroups are dealt round-robin to the eight
+  // XCDs, each with its own L2: every XCD takes one contiguous eighth of the chunks, so
+  // a row that serves several long lists (they lie close together) is fetched once.
+  const long long n_chunks = (total + blockDim.x - 1) / blockDim.x;
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, per_x = gridDim.x >> 3;
+  const long long c_begin = n_chunks * xcd / 8, c_end = n_chunks * (xcd + 1) / 8;
+  for (long long chunk = c_begin + j; chunk < c_end; chunk += per_x) {
+    const long long p = chunk * blockDim.x + threadIdx.x;
     int v = 0, dir = 0, s = 0, e = 0;
     if (p < total) {
-      dir = p >= ntot;
-      v = (int)(dir ? p - ntot : p);
+      dir = (int)(p & 1);
+      v = (int)(p >> 1);
       const int* rp = dir ? out_rp : in_rp;
       s = rp[v];
       e = rp[v + 1];
@@ -509,16 +515,31 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
       const int mv = __shfl(v, sl, 64), md = __shfl(dir, sl, 64), ms = __shfl(s, sl, 64), me = __shfl(e, sl, 64);
       if (src >= 0) {
         const int* ci = md ? out_ci : in_ci;
+        const int deg = me - ms, hb = half << 5;
         float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        set8(a8, h4[(size_t)ci[ms] * kCPR + l32]);     // a pair here has more than kU >= 1 neighbours
-        int k = ms + 1;
-        for (; k + 1 < me; k += 2) {           // two rows in flight; added in ascending order
-          const v4u x0 = h4[(size_t)ci[k] * kCPR + l32];
-          const v4u x1 = h4[(size_t)ci[k + 1] * kCPR + l32];
-          add8(a8, x0, one);
-          add8(a8, x1, one);
+        // the 32 lanes first fetch up to 32 neighbour ids in one coalesced load and then
+        // hand them round, so that no row load waits for an index load of its own;
+        // rows are added in ascending list order, four in flight
+        for (int b0 = 0; b0 < deg; b0 += 32) {
+          const int nb = min(32, deg - b0);
+          const int mine = l32 < nb ? ci[ms + b0 + l32] : 0;
+          int k = 0;
+          if (b0 == 0) {                        // a pair here has more than kU >= 1 neighbours
+            set8(a8, h4[(size_t)__shfl(mine, hb, 64) * kCPR + l32]);
+            k = 1;
+          }
+          for (; k + 3 < nb; k += 4) {
+            const v4u x0 = h4[(size_t)__shfl(mine, hb + k, 64) * kCPR + l32];
+            const v4u x1 = h4[(size_t)__shfl(mine, hb + k + 1, 64) * kCPR + l32];
+            const v4u x2 = h4[(size_t)__shfl(mine, hb + k + 2, 64) * kCPR + l32];
+            const v4u x3 = h4[(size_t)__shfl(mine, hb + k + 3, 64) * kCPR + l32];
+            add8(a8, x0, one);
+            add8(a8, x1, one);
+            add8(a8, x2, one);
+            add8(a8, x3, one);
+          }
+          for (; k < nb; ++k) add8(a8, h4[(size_t)__shfl(mine, hb + k, 64) * kCPR + l32], one);
         }
-        if (k < me) add8(a8, h4[(size_t)ci[k] * kCPR + l32], one);
         const float sc = 1.0f / (float)(me - ms);
         v4u o;
         o.x = pack2(a8[0] * sc, a8[1] * sc);

@@ -216,6 +216,49 @@ def test_device_detected_errors(B):
     ev.close()
 
 
+def test_gnn_forward_validates_a_caller_batch_on_the_device(B):
+    """A batch that did not come from dc_contract_graphs is checked before any layer kernel
+    reads it: a neighbour outside its own graph, descending row pointers or descending
+    offsets make the call a no-op that dc_check reports."""
+    w = wl.make("cfg2", 6)
+    ev, batch = gpu_contract(B, w)
+    assert ev.check() == B.DC_OK
+    ref = orc.evaluate(w)
+    good = ev.gnn_forward(batch).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    assert rel_err(good, ref).max() <= TOL["f32"]
+    n1 = int(batch.node_off[1].item())
+    # neighbour pointing into the next graph
+    keep = int(batch.in_col[0].item())
+    batch.in_col[0] = n1 + 1
+    ev.gnn_forward(batch)
+    assert ev.check() == B.DC_ERR_BAD_GRAPH
+    batch.in_col[0] = keep
+    # negative neighbour
+    keep = int(batch.out_col[3].item())
+    batch.out_col[3] = -7
+    ev.gnn_forward(batch)
+    assert ev.check() == B.DC_ERR_BAD_GRAPH
+    batch.out_col[3] = keep
+    # row pointers that step backwards
+    keep = int(batch.out_rowptr[5].item())
+    batch.out_rowptr[5] = int(batch.out_rowptr[7].item()) + 1
+    ev.gnn_forward(batch)
+    assert ev.check() == B.DC_ERR_BAD_GRAPH
+    batch.out_rowptr[5] = keep
+    # graph offsets that step backwards
+    keep = int(batch.node_off[2].item())
+    batch.node_off[2] = 0
+    ev.gnn_forward(batch)
+    assert ev.check() == B.DC_ERR_BAD_GRAPH
+    batch.node_off[2] = keep
+    # repaired: same predictions as before
+    again = ev.gnn_forward(batch).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    assert np.array_equal(again, good)
+    ev.close()
+
+
 def test_bad_base_graph_is_rejected_on_the_host(B):
     ev = B.Evaluator(16, 32, 1, "f32", 4, 100, 100)
     X = np.zeros((3, 16), np.float32)
