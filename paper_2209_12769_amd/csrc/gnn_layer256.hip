@@ -39,14 +39,20 @@ constexpr int kU = 3;                       // neighbours gathered in-kernel per
 constexpr bool kSplitSimd = DC_SPLIT_SIMD;
 constexpr int kNK = 3 * kD / kBK;           // 12 K chunks per tile
 constexpr int kCPR = kD / 8;                // 16-byte chunks per row of h
-constexpr int kASTR = kBK + 8;
-constexpr int kABytes = kBM * kASTR * 2;    // 18432
+// LDS: a ring of three A chunks (128 rows x 64 columns, no padding: the 16-byte pieces of a row
+// are XOR-swizzled so that fragment reads stay conflict free and a row-contiguous DMA piece of
+// 1 KB is eight whole rows), a ring of three B chunks, and one 32 x 64 staging area per MFMA wave.
+constexpr int kARow = kBK * 2;              // 128 bytes per A row
+constexpr int kABytes = kBM * kARow;        // 16384
 constexpr int kBBytes = (kBK / 8) * kBN * 8 * 2;   // 32768
-constexpr int kBOff = 2 * kABytes;          // two A buffers (job parity), then a ring of three B buffers
-constexpr int kOStr = 64 + 8;               // staging row stride (elements) of an MFMA wave
-constexpr int kStageBytes = 32 * kOStr * 2; // 4608 per MFMA wave: 32 rows x 64 columns per pass
+constexpr int kBOff = 3 * kABytes;
+constexpr int kStageBytes = 32 * kARow;     // 4096 per MFMA wave: 32 rows x 64 columns per pass, same swizzle
 constexpr int kStageOff = kBOff + 3 * kBBytes;
 constexpr int kLdsTotal = kStageOff + 4 * kStageBytes;
+static_assert(kLdsTotal <= 160 * 1024, "one workgroup per CU owns the whole LDS");
+// byte offset of 16-byte piece c (0..7) of row r in a swizzled 128-byte-row area
+__device__ __forceinline__ int swz(int r, int c) { return r * kARow + ((c ^ ((r >> 1) & 7)) << 4); }
+constexpr int kSelfChunks = kD / kBK;       // the first four K chunks of a tile are the node's own row
 typedef __attribute__((address_space(3))) char lds_char;
 
 __device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
@@ -101,6 +107,21 @@ __device__ __forceinline__ void wait_vm() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
+// vmcnt(12) if `more` (wave-uniform) is non-zero, else vmcnt(8), as one statement: two separate
+// wait sites in an if/else around the tile epilogue made the register allocator spill.
+__device__ __forceinline__ void wait_vm_8_or_12(int more) {
+  asm volatile(
+      "s_cmp_lg_u32 %0, 0\n\t"
+      "s_cbranch_scc1 .Ldc_w12_%=\n\t"
+      "s_waitcnt vmcnt(8)\n\t"
+      "s_branch .Ldc_wend_%=\n"
+      ".Ldc_w12_%=:\n\t"
+      "s_waitcnt vmcnt(12)\n"
+      ".Ldc_wend_%=:"
+      :
+      : "s"(more)
+      : "scc", "memory");
+}
 // Waits until at most N loads issued after the listed registers' loads are outstanding; the
 // registers are named as operands so that no use of them can be scheduled before the wait.
 template <int N>
@@ -115,10 +136,13 @@ __device__ __forceinline__ void wait_loads(v4i& d) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(d) : "n"(N));
 }
 
-// One step of a data-moving wave: issue the loads of job s+2 into stage PAR and reduce
-// job s+1 (stage 1-PAR, loaded one step ago) into its LDS set.  Every call issues
-// exactly one descriptor load and 4 x kU row loads, with no branch around a vector
-// load, so the in-order load counter lets the reduction run while the new loads fly.
+// One step of a data-moving wave: issue the loads of job s+3 into register stage Q and
+// reduce job s+1 (stage (Q+1)%3, loaded two steps ago) into its LDS ring slot.  The first
+// kSelfChunks jobs of a tile are the node's own rows: those go from global memory straight
+// into LDS (issued by the MFMA waves) and cost this wave nothing.  A gather job issues
+// exactly 4 x kU row loads and every step exactly one descriptor load, with no branch
+// around a single vector load, so the in-order load counter says how many newer loads may
+// still be in flight when an older one is needed.
 // Row addresses are 32-bit byte offsets from a per-tile base row: a graph has fewer
 // than 65536 nodes, so every neighbour lies within 65536 rows of the tile.
 struct MoverConst {
@@ -128,8 +152,26 @@ struct MoverConst {
   const v4i* desc_in;
   const v4i* desc_out;
   char* smem;
-  int ntot, tile0, per, ar, ach;
+  int ntot, tile0, per, ar, ach, aoff;
 };
+
+// 1 if job J (clamped to the last job, as the loads are) gathers neighbour rows
+__device__ __forceinline__ int is_gather(int J, int S) { return (min(J, S - 1) % kNK) >= kSelfChunks; }
+
+// s_waitcnt vmcnt(base + 12 * n), n in 0..2, chosen at run time (wave-uniform)
+template <int BASE>
+__device__ __forceinline__ void wait_vm_sel(int n) {
+  if (n == 2) wait_vm<BASE + 24>();
+  else if (n == 1) wait_vm<BASE + 12>();
+  else wait_vm<BASE>();
+}
+// Names registers as operands of an empty statement placed after a wait, so that no use of
+// them can be scheduled before it.
+__device__ __forceinline__ void pin(v4u (&a)[4][kU]) {
+  asm volatile("" : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]),
+                    "+v"(a[2][0]), "+v"(a[2][1]), "+v"(a[2][2]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(a[3][2]));
+}
+__device__ __forceinline__ void pin(v4i& d) { asm volatile("" : "+v"(d)); }
 
 // Q = (s + 3) % 3 is the register stage that receives job s+3; job s+1 sits in stage
 // (Q + 1) % 3 and job s+2 (in flight) in stage (Q + 2) % 3.
@@ -138,15 +180,18 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], un
                                            int (&dgs)[2][4], v4i (&dq)[3], const MoverConst c) {
   constexpr unsigned kRowBytes = kD * 2;
   constexpr int QC = (Q + 1) % 3;
+  const int g1 = is_gather(s + 1, S), g2 = is_gather(s + 2, S), g3 = is_gather(s + 3, S);
   {
-    const int J = min(s + 3, S - 1);        // clamped: the load count never changes
+    const int J = min(s + 3, S - 1);        // clamped: the last job's loads are simply repeated
     const int ti = J / kNK, kc = J - ti * kNK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
     const int base_row = max(m0 - 65536, 0);
     const unsigned colb = (unsigned)c.ach * 16u;
-    // file the descriptor requested two steps ago: neighbour ids become byte offsets
+    // file the descriptor requested two steps ago: neighbour ids become byte offsets.
+    // Newer than it: the row loads of its own step (job s+1) and all of the next step (job s+2).
     {
-      wait_loads<12 + 13>(dq[QC]);           // newer: the rest of its own step and all of the next
+      wait_vm_sel<1>(g1 + g2);
+      pin(dq[QC]);
       const v4i dd = dq[QC];
       const unsigned f0 = (unsigned)(dd.x - base_row) * kRowBytes + colb;
       const unsigned f1 = (unsigned)(dd.y - base_row) * kRowBytes + colb;
@@ -176,91 +221,98 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], un
       const v4i* dsrc = (k >> 2) ? c.desc_out : c.desc_in;
       dq[Q] = load16i_async(dsrc + r);
     }
-    const int seg = kc >> 2;
-    const unsigned kcoff = (unsigned)(kc & 3) * 128u;                     // 64 columns = 128 bytes
-    const char* hb = c.h + (size_t)base_row * kRowBytes;                  // uniform
-    if (seg == 0) {
-      // the node's own rows; the two extra requests of each item repeat the address (they hit
-      // the first one's cache line) and only keep the number of loads per step constant
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = min(m0 + c.ar + 32 * i, c.ntot - 1);             // rows past the end are never stored
-        const unsigned own = (unsigned)(row - base_row) * kRowBytes + colb + kcoff;
-        ax[Q][i][0] = load16_async(hb, own);
-        ax[Q][i][1] = load16_async(hb, own);
-        ax[Q][i][2] = load16_async(hb, own);
-      }
-    } else {
+    if (g3) {
+      const int seg = kc >> 2;
+      const unsigned kcoff = (unsigned)(kc & 3) * 128u;                     // 64 columns = 128 bytes
+      const char* hb = c.h + (size_t)base_row * kRowBytes;                  // uniform
       const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const unsigned g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
-        const unsigned g1 = seg == 2 ? off[1][i][1] : off[0][i][1];
-        const unsigned g2 = seg == 2 ? off[1][i][2] : off[0][i][2];
+        const unsigned ga = seg == 2 ? off[1][i][1] : off[0][i][1];
+        const unsigned gb = seg == 2 ? off[1][i][2] : off[0][i][2];
         const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
         // rows left to the pre-pass have all three offsets on the row itself (see build_desc):
         // slot 0 then reads the row's finished mean from the pre-pass buffer
         const char* b0 = dg > kU ? pb : hb;
         ax[Q][i][0] = load16_async(b0 + (g0 + kcoff));
-        ax[Q][i][1] = load16_async(hb, g1 + kcoff);
-        ax[Q][i][2] = load16_async(hb, g2 + kcoff);
+        ax[Q][i][1] = load16_async(hb, ga + kcoff);
+        ax[Q][i][2] = load16_async(hb, gb + kcoff);
       }
     }
   }
-  if (s + 1 >= 0 && s + 1 < S) {
+  if (s + 1 >= 0 && s + 1 < S && g1) {
     const int J = s + 1;
     const int ti = J / kNK, kc = J - ti * kNK;
     const int seg = kc >> 2;
-    u16* dst = reinterpret_cast<u16*>(c.smem + (J & 1) * kABytes);
-    wait_loads<13 + 13>(ax[QC]);             // newer: the two jobs requested after this one
-    if (seg == 0) {
+    char* dst = c.smem + (J % 3) * kABytes + c.aoff;
+    // newer than this job's rows: the descriptor and rows of the two steps since
+    wait_vm_sel<2>(g2 + g3);
+    pin(ax[QC]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = ax[QC][i][0];
-    } else {
+    for (int i = 0; i < 4; ++i) {
+      const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+      // branch-free mean in ascending neighbour order: slot u counts iff u < deg
+      const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
+      const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
+      const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][1], x2 = ax[QC][i][2];
+      v4u o;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
-        // branch-free mean in ascending neighbour order: slot u counts iff u < deg
-        const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
-        const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
-        const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][1], x2 = ax[QC][i][2];
-        v4u o;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float lo = __uint_as_float(x0[w] << 16);
-          float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
-          bf16_pair_add(lo, hi, x1[w], k1);
-          bf16_pair_add(lo, hi, x2[w], k2);
-          o[w] = pack_bf16x2(lo * sc, hi * sc);
-        }
-        o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
-        *reinterpret_cast<v4u*>(dst + (c.ar + 32 * i) * kASTR + c.ach * 8) = o;
+      for (int w = 0; w < 4; ++w) {
+        float lo = __uint_as_float(x0[w] << 16);
+        float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
+        bf16_pair_add(lo, hi, x1[w], k1);
+        bf16_pair_add(lo, hi, x2[w], k2);
+        o[w] = pack_bf16x2(lo * sc, hi * sc);
       }
+      o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
+      *reinterpret_cast<v4u*>(dst + 32 * i * kARow) = o;      // rows ar + 32 i share the swizzle of row ar
     }
   }
 }
 
-// One step of an MFMA wave: request the B chunk of job s+2 (straight into its LDS ring
-// slot), run the MFMAs of job s, make sure the B chunk of job s+1 has landed and, at the end
-// of a tile, write the tile out.
+// One step of an MFMA wave: request the B chunk of job s+2 and, if that job is one of the
+// node's own chunks, its A chunk as well (both straight into their LDS ring slots), run the
+// MFMAs of job s, make sure everything requested one step ago has landed and, at the end of
+// a tile, write the tile out.
 struct MfmaConst {
   const u16* Wp;
+  const char* h;
   const float* bias;
   u16* out;
   char* smem;
-  u16* stage;
+  char* stage;
   unsigned lds0;        // LDS byte address of smem
-  int ntot, tile0, per, wm, wn, l32, lh, lane, wave;
+  int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
 
 __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
+  int a_dma = 0;
   if (s + 2 >= 0) {
+    const int J = s + 2;
+    const int ti = J / kNK, kc = J - ti * kNK;
+    if (J < S && kc < kSelfChunks) {
+      // the node's own rows need no arithmetic: 128 rows x 128 bytes = sixteen 1 KB pieces of
+      // eight rows, four per wave; lane l fills position l&7 of row l>>3 of its piece, which
+      // under the swizzle holds column piece (l&7) ^ ((row>>1)&7).  Rows past the end are
+      // clamped to the last row (read, never stored).
+      a_dma = 1;
+      const int m0 = (c.tile0 + ti * c.per) * kBM;
+      const unsigned aring = c.lds0 + (unsigned)(J % 3) * kABytes;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int piece = c.wave * 4 + i;
+        const int r = piece * 8 + (c.lane >> 3);
+        const int col = (c.lane & 7) ^ ((r >> 1) & 7);
+        const int row = min(m0 + r, c.ntot - 1);
+        load16_to_lds(c.h + (size_t)row * (kD * 2) + kc * kARow + col * 16, aring + piece * 1024);
+      }
+    }
     // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run; each wave moves
     // eight 1 KB pieces of it (chunk index clamped at the end: the count of loads is fixed)
-    const int jn = min(s + 2, S - 1);
+    const int jn = min(J, S - 1);
     const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % kNK) * kBBytes;
-    const unsigned ring = c.lds0 + kBOff + (unsigned)((s + 2) % 3) * kBBytes;
+    const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int piece = c.wave * 8 + i;     // c.wave is wave-uniform by construction (readfirstlane)
@@ -268,14 +320,15 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
     }
   }
   if (s >= 0) {
-    const u16* As = reinterpret_cast<const u16*>(c.smem + (s & 1) * kABytes);
+    const char* As = c.smem + (s % 3) * kABytes;
     const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (s % 3) * kBBytes);
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       bf16x8 a[2], b[4];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(As + (c.wm * 64 + i * 32 + c.l32) * kASTR + ks * 16 + c.lh * 8);
+      for (int i = 0; i < 2; ++i)          // rows wm*64 + i*32 + l32 all share the swizzle of row l32
+        a[i] = *reinterpret_cast<const bf16x8*>(As + (c.wm * 64 + i * 32 + c.l32) * kARow +
+                                                (((ks * 2 + c.lh) ^ c.sw) << 4));
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         b[j] = *reinterpret_cast<const bf16x8*>(Bs + ((ks * 2 + c.lh) * kBN + c.wn * 128 + j * 32 + c.l32) * 8);
@@ -288,11 +341,53 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   }
+  // All but this step's requests (eight W pieces and, for one of the node's own chunks, four
+  // A pieces): everything requested one step ago, which job s+1 needs, is in LDS.  Loads
+  // complete in issue order, so this holds whatever stores of an earlier tile are still
+  // on their way; placed before the tile's stores so that it never waits for those.
+  wait_vm_8_or_12(__builtin_amdgcn_readfirstlane(a_dma));
   const bool tile_end = s >= 0 && (s % kNK) == kNK - 1;
   if (tile_end) {
-    // ---- tile finished: bias, ReLU, bf16, wave-local staging, 16-byte row-contiguous stores
+    // ---- tile finished.  First bias and ReLU in place, one group of 32 columns at a time,
+    // with the next group's bias in flight; no load follows a store, so nothing here waits
+    // for a store to be acknowledged.
     const int ti = s / kNK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
+    float4 bq[4];
+    {
+      int cb = c.wn * 128 + 4 * c.lh;
+      asm volatile("" : "+v"(cb));         // opaque: keeps the bias loads out of the step loop's live set
+#pragma unroll
+      for (int q = 0; q < 4; ++q) bq[q] = *reinterpret_cast<const float4*>(c.bias + cb + 8 * q);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float4 cur[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) cur[q] = bq[q];
+      if (j < 3) {
+        int cb = c.wn * 128 + (j + 1) * 32 + 4 * c.lh;
+        asm volatile("" : "+v"(cb));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bq[q] = *reinterpret_cast<const float4*>(c.bias + cb + 8 * q);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc[i][j][4 * q + 0] = fmaxf(acc[i][j][4 * q + 0] + cur[q].x, 0.f);
+          acc[i][j][4 * q + 1] = fmaxf(acc[i][j][4 * q + 1] + cur[q].y, 0.f);
+          acc[i][j][4 * q + 2] = fmaxf(acc[i][j][4 * q + 2] + cur[q].z, 0.f);
+          acc[i][j][4 * q + 3] = fmaxf(acc[i][j][4 * q + 3] + cur[q].w, 0.f);
+        }
+    }
+    // keep the whole of that phase ahead of the first store (the optimiser would otherwise
+    // sink the second half of it below the first pass's stores, and its waits with it)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(acc[i][j]));
+    // ---- then bf16, wave-local staging, 16-byte row-contiguous stores
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -302,14 +397,11 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
           const int j = 2 * jh + jj;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int c0 = jj * 32 + 8 * q + 4 * c.lh;           // column inside the pass
-            int cb = c.wn * 128 + jh * 64 + c0;
-            asm volatile("" : "+v"(cb));   // opaque: keeps the bias loads out of the step loop's live set
-            const float4 bq = *reinterpret_cast<const float4*>(c.bias + cb);
             v2u p;
-            p.x = pack2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
-            p.y = pack2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
-            *reinterpret_cast<v2u*>(c.stage + c.l32 * kOStr + c0) = p;
+            p.x = pack2(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1]);
+            p.y = pack2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            // 16-byte piece jj*4 + q of staging row l32, half lh of the piece
+            *reinterpret_cast<v2u*>(c.stage + c.l32 * kARow + (((jj * 4 + q) ^ c.sw) << 4) + 8 * c.lh) = p;
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
           }
@@ -321,16 +413,14 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
           const int idx = c.lane + 64 * k;
           const int r = idx >> 3, cc = idx & 7;
           const int gr = m0 + c.wm * 64 + i * 32 + r;
-          const v4u val = *reinterpret_cast<const v4u*>(c.stage + r * kOStr + cc * 8);
+          const v4u val = *reinterpret_cast<const v4u*>(c.stage + swz(r, cc));
           if (gr < c.ntot) *reinterpret_cast<v4u*>(c.out + (size_t)gr * kBN + c.wn * 128 + jh * 64 + cc * 8) = val;
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         __builtin_amdgcn_wave_barrier();
       }
     }
-    wait_vm<0>();      // the tile's stores share the counter with the B requests: drain everything
   }
-  wait_vm<8>();        // all but the eight requests of this step: the B chunk of job s+1 is in LDS
 }
 
 __global__ __launch_bounds__(kNT) void layer256_kernel(
@@ -371,7 +461,8 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.bias = bias;
     mc.out = out;
     mc.smem = smem;
-    mc.stage = reinterpret_cast<u16*>(smem + kStageOff + role_wave * kStageBytes);
+    mc.h = reinterpret_cast<const char*>(h);
+    mc.stage = smem + kStageOff + role_wave * kStageBytes;
     mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256_smem);
     mc.ntot = ntot;
     mc.tile0 = xcd * tpx + slot;
@@ -381,6 +472,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.l32 = lane & 31;
     mc.lh = lane >> 5;
     mc.lane = lane;
+    mc.sw = ((lane & 31) >> 1) & 7;
     mc.wave = __builtin_amdgcn_readfirstlane(role_wave);   // scalar: the LDS base of a DMA load must be uniform
     __syncthreads();                          // step -3: only the data-moving waves work
     for (int s = -2; s < S; ++s) {
@@ -419,6 +511,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.per = per;
     mc.ar = lt >> 3;                         // rows ar + 32*i, 16-byte column ach of the chunk
     mc.ach = lt & 7;
+    mc.aoff = swz(mc.ar, mc.ach);
     dq[0] = v4i{0, 0, 0, 0};
     dq[1] = v4i{0, 0, 0, 0};
     dq[2] = v4i{0, 0, 0, 0};
