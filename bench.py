@@ -33,15 +33,15 @@ def algorithmic_work(w, ntot, etot):
     base = sum(4 * (g.n + 1) + 4 * g.e + 4 * g.n * m.F for g in w.graphs)       # read once per batch
     contract = 4 * nb + 4 * nb + ntot * m.F * s + 2 * 4 * (ntot + C + etot) + base
     agg_b, upd_f, upd_b = 0, 0, 0
-    fus = {"fused_layer": [0, 0], "layer256": [0, 0]}
+    fus = {"fused_layer": [0, 0], "layer256": [0, 0], "layer256_d64": [0, 0]}
     d = m.F
     for _ in range(m.L):
-        bulk = m.dtype == "bf16" and m.H == 256 and d == 256
+        bulk = m.dtype == "bf16" and m.H == 256 and d in (256, 64)
         fused = m.dtype == "bf16" and m.H in (128, 256) and d % 64 == 0
         idx = 2 * 4 * (ntot + etot)
         flops = 2 * ntot * 3 * d * m.H
         if fused:       # means never leave the chip: read h, write h', read the neighbour lists and W
-            k = fus["layer256" if bulk else "fused_layer"]
+            k = fus[("layer256" if d == 256 else "layer256_d64") if bulk else "fused_layer"]
             k[0] += flops
             k[1] += ntot * d * s + ntot * m.H * s + idx + 3 * d * m.H * s
         else:           # read h, write both means; then read [h|h_in|h_out] and W, write h'
@@ -53,6 +53,7 @@ def algorithmic_work(w, ntot, etot):
             "update": {"flops": upd_f, "bytes": upd_b},
             "fused_layer": {"flops": fus["fused_layer"][0], "bytes": fus["fused_layer"][1]},
             "layer256": {"flops": fus["layer256"][0], "bytes": fus["layer256"][1]},
+            "layer256_d64": {"flops": fus["layer256_d64"][0], "bytes": fus["layer256_d64"][1]},
             "readout_head": {"bytes": ntot * m.H * s}}
 
 
@@ -139,7 +140,7 @@ def main():
     fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
     kernels = {}
     for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
-                      ("fused_layer", "fused_layer"), ("layer256", "layer256"),
+                      ("fused_layer", "fused_layer"), ("layer256", "layer256"), ("layer256_d64", "layer256_d64"),
                       ("aggregate_heavy", "aggregate_heavy"), ("build_desc", "build_desc"),
                       ("readout_head", "readout_head")):
         ms_total, launches = fam[key]
@@ -153,7 +154,7 @@ def main():
                 k["TFLOP/s"] = round(work[name]["flops"] / (per_step_ms * 1e-3) / 1e12, 2)
         kernels[name] = k
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-    if dom in ("update", "fused_layer", "layer256"):
+    if dom in ("update", "fused_layer", "layer256", "layer256_d64"):
         peak = PEAK_MFMA_TFLOPS[w.model.dtype]
         ach = kernels[dom].get("TFLOP/s", 0.0)
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",

@@ -65,7 +65,7 @@ struct dc_ctx {
 namespace {
 
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
-                                             "fused_layer", "layer256", "aggregate_heavy", "build_desc",
+                                             "fused_layer", "layer256", "layer256_d64", "aggregate_heavy", "build_desc",
                                              "readout_head"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }

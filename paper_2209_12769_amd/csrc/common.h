@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamHeavy, kFamDesc, kFamReadout, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamReadout, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -122,10 +122,10 @@ bool fused_layer_supported(int d, int H, int bf16);
 hipError_t launch_fused_layer(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                               hipStream_t s);
 
-// gnn_layer256.hip: wave-specialised fused layer for d = H = 256 (bf16); uses a.agg[] for rows with long lists.
+// gnn_layer256.hip: wave-specialised fused layer for H = 256, d = 256 or 64 (bf16); uses a.agg[] for rows with long lists.
 bool layer256_supported(int d, int H, int bf16);
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
-hipError_t launch_layer256(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s);
 
 __global__ void reset_status_kernel(int* status);

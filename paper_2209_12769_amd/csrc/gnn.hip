@@ -375,8 +375,8 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   const char* Wl = static_cast<const char*>(a.W);
   const float* bl = a.b;
   const int agg_grid = a.n_cu * 8;
-  if (a.allow_fused && a.L > 1 && layer256_supported(a.H, a.H, a.bf16)) {
-    // neighbour descriptors depend on the graphs only: built once, used by every hidden layer
+  if (a.allow_fused && (layer256_supported(a.F, a.H, a.bf16) || (a.L > 1 && layer256_supported(a.H, a.H, a.bf16)))) {
+    // neighbour descriptors depend on the graphs only: built once, used by every layer that gathers through them
     if (prof) prof->begin(kFamDesc, s);
     hipError_t e = launch_build_desc(a, s);
     if (prof) prof->end(s);
@@ -385,7 +385,7 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   for (int l = 0; l < a.L; ++l) {
     void* hnext = a.act[l & 1];
     if (a.allow_fused && layer256_supported(d, a.H, a.bf16)) {
-      hipError_t e = launch_layer256(hcur, a, Wl, bl, hnext, prof, s);
+      hipError_t e = launch_layer256(hcur, d, a, Wl, bl, hnext, prof, s);
       if (e != hipSuccess) return e;
     } else if (a.allow_fused && fused_layer_supported(d, a.H, a.bf16)) {
       if (prof) prof->begin(kFamFused, s);

@@ -1,4 +1,4 @@
-// Wave-specialised fused layer for the bulk shape d = H = 256, bf16 (gfx950):
+// Wave-specialised fused layer for output width H = 256 and input width d = 256 or 64, bf16 (gfx950):
 //     h'[v] = ReLU([h[v] | mean_pred(h)[v] | mean_succ(h)[v]] W + b)
 // (neighbourhood encoding of Sec. 3.3.1 with uniform coefficients), with both
 // means formed on the fly so that a layer reads h once and writes h' once.
@@ -19,10 +19,6 @@
 
 #include "common.h"
 
-#ifndef DC_SPLIT_SIMD
-#define DC_SPLIT_SIMD 0
-#endif
-
 namespace dc {
 namespace {
 
@@ -33,12 +29,24 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kBM = 128, kBN = 256, kBK = 64, kD = 256;
+constexpr int kBM = 128, kBN = 256, kBK = 64;
 constexpr int kNT = 512;
 constexpr int kU = 3;                       // neighbours gathered in-kernel per row and direction
-constexpr bool kSplitSimd = DC_SPLIT_SIMD;
-constexpr int kNK = 3 * kD / kBK;           // 12 K chunks per tile
-constexpr int kCPR = kD / 8;                // 16-byte chunks per row of h
+// Shape constants for input width D = 64 * DCH: K = 3 D in chunks of 64 columns, the first
+// DCH of them the node's own row.  A lane needs eight gather descriptors per tile (two
+// directions x four items).  With DCH = 4 each serves four jobs: one is requested per step
+// (RQ = 1) and filed, two steps later, into a per-tile table, in time for its first use.
+// With DCH = 1 a direction is a single job: that job's four descriptors are requested
+// together (RQ = 4) and used directly when its rows are requested (DIRECT).
+template <int DCH>
+struct Shape {
+  static_assert(DCH == 4 || DCH == 1, "input widths 256 and 64");
+  static constexpr int D = 64 * DCH;
+  static constexpr int NK = 3 * DCH;
+  static constexpr bool DIRECT = DCH == 1;
+  static constexpr int RQ = DIRECT ? 4 : 1;
+  static constexpr unsigned ROWB = D * 2;     // bytes per row of h
+};
 // LDS: a ring of three A chunks (128 rows x 64 columns, no padding: the 16-byte pieces of a row
 // are XOR-swizzled so that fragment reads stay conflict free and a row-contiguous DMA piece of
 // 1 KB is eight whole rows), a ring of three B chunks, and one 32 x 64 staging area per MFMA wave.
@@ -52,7 +60,6 @@ constexpr int kLdsTotal = kStageOff + 4 * kStageBytes;
 static_assert(kLdsTotal <= 160 * 1024, "one workgroup per CU owns the whole LDS");
 // byte offset of 16-byte piece c (0..7) of row r in a swizzled 128-byte-row area
 __device__ __forceinline__ int swz(int r, int c) { return r * kARow + ((c ^ ((r >> 1) & 7)) << 4); }
-constexpr int kSelfChunks = kD / kBK;       // the first four K chunks of a tile are the node's own row
 typedef __attribute__((address_space(3))) char lds_char;
 
 __device__ __forceinline__ unsigned pack2(float a, float b) { return pack_bf16x2(a, b); }
@@ -122,27 +129,13 @@ __device__ __forceinline__ void wait_vm_8_or_12(int more) {
       : "s"(more)
       : "scc", "memory");
 }
-// Waits until at most N loads issued after the listed registers' loads are outstanding; the
-// registers are named as operands so that no use of them can be scheduled before the wait.
-template <int N>
-__device__ __forceinline__ void wait_loads(v4u (&a)[4][kU]) {
-  asm volatile("s_waitcnt vmcnt(%12)"
-               : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]),
-                 "+v"(a[2][0]), "+v"(a[2][1]), "+v"(a[2][2]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(a[3][2])
-               : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void wait_loads(v4i& d) {
-  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(d) : "n"(N));
-}
-
 // One step of a data-moving wave: issue the loads of job s+3 into register stage Q and
 // reduce job s+1 (stage (Q+1)%3, loaded two steps ago) into its LDS ring slot.  The first
-// kSelfChunks jobs of a tile are the node's own rows: those go from global memory straight
-// into LDS (issued by the MFMA waves) and cost this wave nothing.  A gather job issues
-// exactly 4 x kU row loads and every step exactly one descriptor load, with no branch
-// around a single vector load, so the in-order load counter says how many newer loads may
-// still be in flight when an older one is needed.
+// DCH jobs of a tile are the node's own rows: those go from global memory straight into
+// LDS (issued by the MFMA waves) and cost this wave nothing.  A gather job issues exactly
+// 4 x kU row loads and every step exactly RQ descriptor loads, with no branch around a
+// single vector load, so the in-order load counter says how many newer loads may still be
+// in flight when an older one is needed.
 // Row addresses are 32-bit byte offsets from a per-tile base row: a graph has fewer
 // than 65536 nodes, so every neighbour lies within 65536 rows of the tile.
 struct MoverConst {
@@ -156,9 +149,10 @@ struct MoverConst {
 };
 
 // 1 if job J (clamped to the last job, as the loads are) gathers neighbour rows
-__device__ __forceinline__ int is_gather(int J, int S) { return (min(J, S - 1) % kNK) >= kSelfChunks; }
+template <int DCH>
+__device__ __forceinline__ int is_gather(int J, int S) { return (min(J, S - 1) % Shape<DCH>::NK) >= DCH; }
 
-// s_waitcnt vmcnt(base + 12 * n), n in 0..2, chosen at run time (wave-uniform)
+// s_waitcnt vmcnt(BASE + 12 * n), n in 0..2, chosen at run time (wave-uniform)
 template <int BASE>
 __device__ __forceinline__ void wait_vm_sel(int n) {
   if (n == 2) wait_vm<BASE + 24>();
@@ -173,65 +167,100 @@ __device__ __forceinline__ void pin(v4u (&a)[4][kU]) {
 }
 __device__ __forceinline__ void pin(v4i& d) { asm volatile("" : "+v"(d)); }
 
+// Descriptors of job (tile starting at row m, chunk kc), request r of RQ.  Table mode: the
+// job files slot kc of its tile (direction kc >> 2, item kc & 3; chunks 8.. repeat slot 7,
+// unused).  Direct mode: item r of the job's own direction (the node's own chunk has
+// none: it repeats the predecessors', unused).
+template <int DCH>
+__device__ __forceinline__ const v4i* desc_addr(const MoverConst& c, int m, int kc, int r) {
+  int dir, item;
+  if (Shape<DCH>::DIRECT) {
+    dir = kc / DCH == 2;
+    item = r;
+  } else {
+    const int k = min(kc, 7);
+    dir = k >> 2;
+    item = k & 3;
+  }
+  const int row = min(m + c.ar + 32 * item, c.ntot - 1);
+  return (dir ? c.desc_out : c.desc_in) + row;
+}
+
 // Q = (s + 3) % 3 is the register stage that receives job s+3; job s+1 sits in stage
 // (Q + 1) % 3 and job s+2 (in flight) in stage (Q + 2) % 3.
-template <int Q>
-__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], unsigned (&off)[2][4][kU],
-                                           int (&dgs)[2][4], v4i (&dq)[3], const MoverConst c) {
-  constexpr unsigned kRowBytes = kD * 2;
+template <int DCH, int Q>
+__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], int (&sdeg)[3][4],
+                                           unsigned (&off)[2][4][kU], int (&dgs)[2][4],
+                                           v4i (&dq)[3][Shape<DCH>::RQ], const MoverConst c) {
+  constexpr int NK = Shape<DCH>::NK, RQ = Shape<DCH>::RQ;
+  constexpr unsigned kRowBytes = Shape<DCH>::ROWB;
   constexpr int QC = (Q + 1) % 3;
-  const int g1 = is_gather(s + 1, S), g2 = is_gather(s + 2, S), g3 = is_gather(s + 3, S);
+  const int g1 = is_gather<DCH>(s + 1, S), g2 = is_gather<DCH>(s + 2, S), g3 = is_gather<DCH>(s + 3, S);
   {
     const int J = min(s + 3, S - 1);        // clamped: the last job's loads are simply repeated
-    const int ti = J / kNK, kc = J - ti * kNK;
+    const int ti = J / NK, kc = J - ti * NK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
     const int base_row = max(m0 - 65536, 0);
     const unsigned colb = (unsigned)c.ach * 16u;
-    // file the descriptor requested two steps ago: neighbour ids become byte offsets.
-    // Newer than it: the row loads of its own step (job s+1) and all of the next step (job s+2).
-    {
-      wait_vm_sel<1>(g1 + g2);
-      pin(dq[QC]);
-      const v4i dd = dq[QC];
+    // The descriptors requested two steps ago are needed now.  Newer than the last of them:
+    // the row loads of its own step (job s+1) and all of the next step (its descriptors and
+    // job s+2).
+    wait_vm_sel<RQ>(g1 + g2);
+#pragma unroll
+    for (int r = 0; r < RQ; ++r) pin(dq[QC][r]);
+    if (!Shape<DCH>::DIRECT) {
+      // table mode: file the one descriptor; neighbour ids become byte offsets
+      const v4i dd = dq[QC][0];
       const unsigned f0 = (unsigned)(dd.x - base_row) * kRowBytes + colb;
       const unsigned f1 = (unsigned)(dd.y - base_row) * kRowBytes + colb;
       const unsigned f2 = (unsigned)(dd.z - base_row) * kRowBytes + colb;
       const int fd = dd.w;
 #define DC_FILE(dd_, ii_) { off[dd_][ii_][0] = f0; off[dd_][ii_][1] = f1; off[dd_][ii_][2] = f2; dgs[dd_][ii_] = fd; }
       switch (kc) {
-        case 1: DC_FILE(0, 0) break;
-        case 2: DC_FILE(0, 1) break;
-        case 3: DC_FILE(0, 2) break;
-        case 4: DC_FILE(0, 3) break;
-        case 5: DC_FILE(1, 0) break;
-        case 6: DC_FILE(1, 1) break;
-        case 7: DC_FILE(1, 2) break;
-        case 8: DC_FILE(1, 3) break;
+        case 0: DC_FILE(0, 0) break;
+        case 1: DC_FILE(0, 1) break;
+        case 2: DC_FILE(0, 2) break;
+        case 3: DC_FILE(0, 3) break;
+        case 4: DC_FILE(1, 0) break;
+        case 5: DC_FILE(1, 1) break;
+        case 6: DC_FILE(1, 2) break;
+        case 7: DC_FILE(1, 3) break;
         default: break;
       }
 #undef DC_FILE
     }
+    v4i dnow[4];                              // direct mode: this job's descriptors
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dnow[i] = dq[QC][Shape<DCH>::DIRECT ? i : 0];
     {
-      // request the descriptor that job J+2 files: slot k of the tile of job J+1
-      const int Jn = min(J + 1, S - 1);
-      const int tn = Jn / kNK;
-      const int k = min(Jn - tn * kNK, 7);
-      const int mn = (c.tile0 + tn * c.per) * kBM;
-      const int r = min(mn + c.ar + 32 * (k & 3), c.ntot - 1);
-      const v4i* dsrc = (k >> 2) ? c.desc_out : c.desc_in;
-      dq[Q] = load16i_async(dsrc + r);
+      // request the descriptors that job J+2 will need
+      const int J2 = min(J + 2, S - 1);
+      const int t2 = J2 / NK, c2 = J2 - t2 * NK;
+      const int m2 = (c.tile0 + t2 * c.per) * kBM;
+#pragma unroll
+      for (int r = 0; r < RQ; ++r) dq[Q][r] = load16i_async(desc_addr<DCH>(c, m2, c2, r));
     }
     if (g3) {
-      const int seg = kc >> 2;
-      const unsigned kcoff = (unsigned)(kc & 3) * 128u;                     // 64 columns = 128 bytes
+      const int seg = kc / DCH;
+      const unsigned kcoff = (unsigned)(kc - seg * DCH) * 128u;             // 64 columns = 128 bytes
       const char* hb = c.h + (size_t)base_row * kRowBytes;                  // uniform
       const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const unsigned g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
-        const unsigned ga = seg == 2 ? off[1][i][1] : off[0][i][1];
-        const unsigned gb = seg == 2 ? off[1][i][2] : off[0][i][2];
-        const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+        unsigned g0, ga, gb;
+        int dg;
+        if (Shape<DCH>::DIRECT) {
+          g0 = (unsigned)(dnow[i].x - base_row) * kRowBytes + colb;
+          ga = (unsigned)(dnow[i].y - base_row) * kRowBytes + colb;
+          gb = (unsigned)(dnow[i].z - base_row) * kRowBytes + colb;
+          dg = dnow[i].w;
+        } else {
+          g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
+          ga = seg == 2 ? off[1][i][1] : off[0][i][1];
+          gb = seg == 2 ? off[1][i][2] : off[0][i][2];
+          dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+        }
+        sdeg[Q][i] = dg;                   // travels with the rows: the filed copy may be replaced before they are reduced
         // rows left to the pre-pass have all three offsets on the row itself (see build_desc):
         // slot 0 then reads the row's finished mean from the pre-pass buffer
         const char* b0 = dg > kU ? pb : hb;
@@ -243,15 +272,13 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], un
   }
   if (s + 1 >= 0 && s + 1 < S && g1) {
     const int J = s + 1;
-    const int ti = J / kNK, kc = J - ti * kNK;
-    const int seg = kc >> 2;
     char* dst = c.smem + (J % 3) * kABytes + c.aoff;
-    // newer than this job's rows: the descriptor and rows of the two steps since
-    wait_vm_sel<2>(g2 + g3);
+    // newer than this job's rows: the descriptors and rows of the two steps since
+    wait_vm_sel<2 * RQ>(g2 + g3);
     pin(ax[QC]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int dg = seg == 2 ? dgs[1][i] : dgs[0][i];
+      const int dg = sdeg[QC][i];
       // branch-free mean in ascending neighbour order: slot u counts iff u < deg
       const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
       const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
@@ -286,12 +313,14 @@ struct MfmaConst {
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
 
+template <int DCH>
 __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
+  constexpr int NK = Shape<DCH>::NK;
   int a_dma = 0;
   if (s + 2 >= 0) {
     const int J = s + 2;
-    const int ti = J / kNK, kc = J - ti * kNK;
-    if (J < S && kc < kSelfChunks) {
+    const int ti = J / NK, kc = J - ti * NK;
+    if (J < S && kc < DCH) {
       // the node's own rows need no arithmetic: 128 rows x 128 bytes = sixteen 1 KB pieces of
       // eight rows, four per wave; lane l fills position l&7 of row l>>3 of its piece, which
       // under the swizzle holds column piece (l&7) ^ ((row>>1)&7).  Rows past the end are
@@ -305,13 +334,13 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
         const int r = piece * 8 + (c.lane >> 3);
         const int col = (c.lane & 7) ^ ((r >> 1) & 7);
         const int row = min(m0 + r, c.ntot - 1);
-        load16_to_lds(c.h + (size_t)row * (kD * 2) + kc * kARow + col * 16, aring + piece * 1024);
+        load16_to_lds(c.h + (size_t)row * Shape<DCH>::ROWB + kc * kARow + col * 16, aring + piece * 1024);
       }
     }
     // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run; each wave moves
     // eight 1 KB pieces of it (chunk index clamped at the end: the count of loads is fixed)
     const int jn = min(J, S - 1);
-    const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % kNK) * kBBytes;
+    const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % NK) * kBBytes;
     const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -346,12 +375,12 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   // complete in issue order, so this holds whatever stores of an earlier tile are still
   // on their way; placed before the tile's stores so that it never waits for those.
   wait_vm_8_or_12(__builtin_amdgcn_readfirstlane(a_dma));
-  const bool tile_end = s >= 0 && (s % kNK) == kNK - 1;
+  const bool tile_end = s >= 0 && (s % NK) == NK - 1;
   if (tile_end) {
     // ---- tile finished.  First bias and ReLU in place, one group of 32 columns at a time,
     // with the next group's bias in flight; no load follows a store, so nothing here waits
     // for a store to be acknowledged.
-    const int ti = s / kNK;
+    const int ti = s / NK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
     float4 bq[4];
     {
@@ -423,11 +452,13 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   }
 }
 
+template <int DCH>
 __global__ __launch_bounds__(kNT) void layer256_kernel(
     const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
     const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
     const float* __restrict__ bias, u16* __restrict__ out, const int* __restrict__ node_off, int C,
     const int* __restrict__ status) {
+  constexpr int NK = Shape<DCH>::NK, RQ = Shape<DCH>::RQ;
   if (status[0] != 0) return;
   char* smem = dc_l256_smem;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -438,16 +469,13 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
   const int tpx = (ntiles + 7) >> 3;
   const int lim = min(tpx, ntiles - xcd * tpx);
   const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
-  const int S = nt_wg * kNK;                // steps of this workgroup
-  const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
+  const int S = nt_wg * NK;                 // steps of this workgroup (a multiple of 3)
 
   if (S == 0) return;                       // no tile for this workgroup (uniform)
-  // Both kinds of wave run S + 3 steps (s = -3 .. S-1) with one barrier per step.
-  // Waves are dealt to the four SIMDs round-robin.  kSplitSimd puts both kinds of wave on
-  // separate SIMDs (waves 0,1,4,5 issue MFMAs on SIMD 0/1; waves 2,3,6,7 move data on SIMD 2/3).
-  const bool is_mfma = kSplitSimd ? ((wave & 2) == 0) : (wave < 4);
-  const int role_wave = kSplitSimd ? ((wave & 1) | ((wave >> 2) << 1)) : (wave & 3);   // 0..3 within the role
-  if (is_mfma) {
+  // Both kinds of wave run S + 3 steps (s = -3 .. S-1) with one barrier per step.  Waves are
+  // dealt to the four SIMDs round-robin, so every SIMD hosts one wave of each kind.
+  const int role_wave = wave & 3;
+  if (wave < 4) {
     // =========================== MFMA waves ===========================================
     f32x16 acc[2][4];
 #pragma unroll
@@ -476,7 +504,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.wave = __builtin_amdgcn_readfirstlane(role_wave);   // scalar: the LDS base of a DMA load must be uniform
     __syncthreads();                          // step -3: only the data-moving waves work
     for (int s = -2; s < S; ++s) {
-      mfma_step(s, S, acc, mc);
+      mfma_step<DCH>(s, S, acc, mc);
       __syncthreads();
     }
   } else {
@@ -485,11 +513,14 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     unsigned off[2][4][kU];                  // byte offsets of the gathered rows [direction][item][slot]
     int dgs[2][4];                           // degrees [direction][item]
     v4u ax[3][4][kU];                        // rows in flight [stage][item][slot]
-    v4i dq[3];                               // descriptors in flight
+    int sdeg[3][4];                          // their degrees
+    v4i dq[3][RQ];                           // descriptors in flight
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       dgs[0][i] = 0;
       dgs[1][i] = 0;
+#pragma unroll
+      for (int q = 0; q < 3; ++q) sdeg[q][i] = 0;
 #pragma unroll
       for (int u = 0; u < kU; ++u) {
         off[0][i][u] = 0u;
@@ -512,23 +543,25 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.ar = lt >> 3;                         // rows ar + 32*i, 16-byte column ach of the chunk
     mc.ach = lt & 7;
     mc.aoff = swz(mc.ar, mc.ach);
-    dq[0] = v4i{0, 0, 0, 0};
-    dq[1] = v4i{0, 0, 0, 0};
-    dq[2] = v4i{0, 0, 0, 0};
     {
-      // descriptor slot 0 of the first tile has no earlier step to be requested in; job 1
-      // files the descriptor of stage (1 - 2) mod 3 = 2
-      const int r = min(mc.tile0 * kBM + mc.ar, ntot - 1);
-      dq[2] = desc_in[r];
+      // the descriptors that jobs 0 and 1 file have no earlier step to be requested in:
+      // step -3 files stage 1, step -2 files stage 2
+      const int m = mc.tile0 * kBM;
+#pragma unroll
+      for (int r = 0; r < RQ; ++r) {
+        dq[0][r] = v4i{0, 0, 0, 0};
+        dq[1][r] = *desc_addr<DCH>(mc, m, 0, r);
+        dq[2][r] = *desc_addr<DCH>(mc, m, 1, r);
+      }
     }
     __builtin_amdgcn_s_waitcnt(0);           // nothing of the set-up may still be in flight
 
     for (int s = -3; s < S; s += 3) {        // S + 3 is a multiple of 3
-      mover_step<0>(s, S, ax, off, dgs, dq, mc);
+      mover_step<DCH, 0>(s, S, ax, sdeg, off, dgs, dq, mc);
       __syncthreads();
-      mover_step<1>(s + 1, S, ax, off, dgs, dq, mc);
+      mover_step<DCH, 1>(s + 1, S, ax, sdeg, off, dgs, dq, mc);
       __syncthreads();
-      mover_step<2>(s + 2, S, ax, off, dgs, dq, mc);
+      mover_step<DCH, 2>(s + 2, S, ax, sdeg, off, dgs, dq, mc);
       __syncthreads();
     }
   }
@@ -564,8 +597,10 @@ __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__
 
 // Means of rows with more than kU neighbours (both directions), written at the rows'
 // own positions in h_in / h_out; all other rows are left untouched.  Each thread tests
-// one (row, direction) pair; the pairs that qualify are then served by the wave, two at
-// a time, 32 lanes per 512-byte row.  The grid must be a multiple of 8 workgroups.
+// one (row, direction) pair; the pairs that qualify are then served by the wave, 64 / LPR
+// at a time, LPR = D / 8 lanes (16 bytes each) per row.  The grid must be a multiple of
+// 8 workgroups.
+template <int LPR>
 __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restrict__ h,
                                                                const int* __restrict__ in_rp,
                                                                const int* __restrict__ in_ci,
@@ -574,11 +609,12 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
                                                                u16* __restrict__ h_out,
                                                                const int* __restrict__ node_off, int C,
                                                                const int* __restrict__ status) {
+  constexpr int NSG = 64 / LPR;              // pairs served at a time
   if (status[0] != 0) return;
   const int ntot = node_off[C];
   const long long total = 2LL * ntot;
   const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
-  const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+  const int lane = threadIdx.x & 63, sg = lane / LPR, ll = lane % LPR, hb = sg * LPR;
   const unsigned one = bf16_one_reg();
   // Chunks of 128 rows x 2 directions.  Workgroups are dealt round-robin to the eight
   // XCDs, each with its own L2: every XCD takes one contiguous eighth of the chunks, so
@@ -598,48 +634,50 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
     }
     unsigned long long todo = __ballot(e - s > kU);
     while (todo) {
-      // lanes 0-31 take the lowest pending pair, lanes 32-63 the next one (if any)
-      const int first = __ffsll((long long)todo) - 1;
-      const unsigned long long rest = todo & (todo - 1);
-      const int second = rest ? __ffsll((long long)rest) - 1 : -1;
-      todo = rest ? (rest & (rest - 1)) : 0ull;
-      const int src = half ? second : first;
+      // lane group g takes the g-th lowest pending pair (if there is one)
+      int src = -1;
+#pragma unroll
+      for (int g = 0; g < NSG; ++g) {
+        const int b = todo ? __ffsll((long long)todo) - 1 : -1;
+        todo = todo ? (todo & (todo - 1)) : 0ull;
+        if (sg == g) src = b;
+      }
       const int sl = src < 0 ? 0 : src;
       const int mv = __shfl(v, sl, 64), md = __shfl(dir, sl, 64), ms = __shfl(s, sl, 64), me = __shfl(e, sl, 64);
       if (src >= 0) {
         const int* ci = md ? out_ci : in_ci;
-        const int deg = me - ms, hb = half << 5;
+        const int deg = me - ms;
         float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        // the 32 lanes first fetch up to 32 neighbour ids in one coalesced load and then
-        // hand them round, so that no row load waits for an index load of its own;
+        // the group's lanes first fetch up to LPR neighbour ids in one coalesced load and
+        // then hand them round, so that no row load waits for an index load of its own;
         // rows are added in ascending list order, four in flight
-        for (int b0 = 0; b0 < deg; b0 += 32) {
-          const int nb = min(32, deg - b0);
-          const int mine = l32 < nb ? ci[ms + b0 + l32] : 0;
+        for (int b0 = 0; b0 < deg; b0 += LPR) {
+          const int nb = min(LPR, deg - b0);
+          const int mine = ll < nb ? ci[ms + b0 + ll] : 0;
           int k = 0;
           if (b0 == 0) {                        // a pair here has more than kU >= 1 neighbours
-            set8(a8, h4[(size_t)__shfl(mine, hb, 64) * kCPR + l32]);
+            set8(a8, h4[(size_t)__shfl(mine, hb, 64) * LPR + ll]);
             k = 1;
           }
           for (; k + 3 < nb; k += 4) {
-            const v4u x0 = h4[(size_t)__shfl(mine, hb + k, 64) * kCPR + l32];
-            const v4u x1 = h4[(size_t)__shfl(mine, hb + k + 1, 64) * kCPR + l32];
-            const v4u x2 = h4[(size_t)__shfl(mine, hb + k + 2, 64) * kCPR + l32];
-            const v4u x3 = h4[(size_t)__shfl(mine, hb + k + 3, 64) * kCPR + l32];
+            const v4u x0 = h4[(size_t)__shfl(mine, hb + k, 64) * LPR + ll];
+            const v4u x1 = h4[(size_t)__shfl(mine, hb + k + 1, 64) * LPR + ll];
+            const v4u x2 = h4[(size_t)__shfl(mine, hb + k + 2, 64) * LPR + ll];
+            const v4u x3 = h4[(size_t)__shfl(mine, hb + k + 3, 64) * LPR + ll];
             add8(a8, x0, one);
             add8(a8, x1, one);
             add8(a8, x2, one);
             add8(a8, x3, one);
           }
-          for (; k < nb; ++k) add8(a8, h4[(size_t)__shfl(mine, hb + k, 64) * kCPR + l32], one);
+          for (; k < nb; ++k) add8(a8, h4[(size_t)__shfl(mine, hb + k, 64) * LPR + ll], one);
         }
-        const float sc = 1.0f / (float)(me - ms);
+        const float sc = 1.0f / (float)deg;
         v4u o;
         o.x = pack2(a8[0] * sc, a8[1] * sc);
         o.y = pack2(a8[2] * sc, a8[3] * sc);
         o.z = pack2(a8[4] * sc, a8[5] * sc);
         o.w = pack2(a8[6] * sc, a8[7] * sc);
-        reinterpret_cast<v4u*>(md ? h_out : h_in)[(size_t)mv * kCPR + l32] = o;
+        reinterpret_cast<v4u*>(md ? h_out : h_in)[(size_t)mv * LPR + ll] = o;
       }
     }
   }
@@ -647,7 +685,7 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
 
 }  // namespace
 
-bool layer256_supported(int d, int H, int bf16) { return bf16 && d == kD && H == kBN; }
+bool layer256_supported(int d, int H, int bf16) { return bf16 && H == kBN && (d == 256 || d == 64); }
 
 static_assert(kU == 3, "a descriptor holds three neighbour ids and the degree");
 
@@ -658,29 +696,42 @@ hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_layer256(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
-                           Profiler* prof, hipStream_t s) {
+namespace {
+
+template <int DCH>
+hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out, Profiler* prof,
+                        hipStream_t s) {
   static bool attr_done = false;
+  auto kern = layer256_kernel<DCH>;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer256_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const u16* hh = static_cast<const u16*>(h);
   if (prof) prof->begin(kFamHeavy, s);
-  hipLaunchKernelGGL(aggregate_heavy_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, hh, a.in_rowptr, a.in_col,
+  hipLaunchKernelGGL(aggregate_heavy_kernel<8 * DCH>, dim3(a.n_cu * 8), dim3(256), 0, s, hh, a.in_rowptr, a.in_col,
                      a.out_rowptr, a.out_col, static_cast<u16*>(a.agg[0]), static_cast<u16*>(a.agg[1]), a.node_off,
                      a.n_cand, a.status);
   if (prof) prof->end(s);
-  if (prof) prof->begin(kFamLayer256, s);
+  if (prof) prof->begin(DCH == 4 ? kFamLayer256 : kFamLayer64, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
-  hipLaunchKernelGGL(layer256_kernel, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
                      static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
                      static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(Wl), bias, static_cast<u16*>(out),
                      a.node_off, a.n_cand, a.status);
   if (prof) prof->end(s);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                           Profiler* prof, hipStream_t s) {
+  if (d == 256) return launch_shape<4>(h, a, Wl, bias, out, prof, s);
+  if (d == 64) return launch_shape<1>(h, a, Wl, bias, out, prof, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace dc
