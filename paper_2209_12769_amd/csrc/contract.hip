@@ -25,7 +25,7 @@ namespace {
 
 constexpr int kCT = 1024;       // threads per contraction workgroup
 constexpr int kCW = kCT / 64;   // waves per workgroup
-constexpr int kSmallRow = 32;   // rows up to this length are sorted by one thread
+constexpr int kSmallRow = 16;   // lists up to this length are sorted by one thread in registers, up to 64 by a wave
 constexpr unsigned short kSelf = 0xFFFF;
 
 typedef unsigned short u16;
@@ -87,16 +87,67 @@ __device__ __forceinline__ int block_exscan(const int* in, int* out, int n, int*
   return total;
 }
 
-__device__ __forceinline__ void insertion_sort(u16* a, int n) {
-  for (int i = 1; i < n; ++i) {
-    u16 key = a[i];
-    int j = i - 1;
-    while (j >= 0 && a[j] > key) {
-      a[j + 1] = a[j];
-      --j;
-    }
-    a[j + 1] = key;
+// Short lists (up to 16 entries) are sorted by one thread each, in registers, with a
+// fixed compare-exchange network (Batcher's odd-even merge sort): no dependent chain
+// through memory, and the same instruction stream for every lane.  Unused places hold
+// kSelf (0xFFFF), which sorts to the end.
+template <int NN>
+__device__ __forceinline__ void sort_network(unsigned (&v)[NN]) {
+#pragma unroll
+  for (int p = 1; p < NN; p <<= 1)
+#pragma unroll
+    for (int k = p; k >= 1; k >>= 1)
+#pragma unroll
+      for (int j = k % p; j + k < NN; j += 2 * k)
+#pragma unroll
+        for (int i = 0; i < k; ++i)
+          if (i + j + k < NN && (i + j) / (2 * p) == (i + j + k) / (2 * p)) {
+            const unsigned lo = min(v[i + j], v[i + j + k]), hi = max(v[i + j], v[i + j + k]);
+            v[i + j] = lo;
+            v[i + j + k] = hi;
+          }
+}
+
+// Sorts a[0..n) ascending, drops entries equal to kSelf and repeats; returns the count kept.
+template <int NN>
+__device__ __forceinline__ int sort_unique_small(u16* a, int n) {
+  unsigned v[NN];
+#pragma unroll
+  for (int k = 0; k < NN; ++k) v[k] = k < n ? (unsigned)a[k] : (unsigned)kSelf;
+  sort_network<NN>(v);
+  int m = 0;
+#pragma unroll
+  for (int k = 0; k < NN; ++k) {
+    const bool keep = v[k] != (unsigned)kSelf && (k == 0 || v[k] != v[k - 1]);
+    if (keep) a[m++] = (u16)v[k];
   }
+  return m;
+}
+
+// Picks the smallest network that covers every list of the wave (n is 0 for lanes without one).
+__device__ __forceinline__ int sort_unique_by_class(u16* a, int n) {
+  if (__any(n > 8)) return sort_unique_small<16>(a, n);
+  if (__any(n > 4)) return sort_unique_small<8>(a, n);
+  if (__any(n > 1)) return sort_unique_small<4>(a, n);
+  return (n == 1 && a[0] != kSelf) ? 1 : 0;
+}
+
+// Same for one list of up to 64 entries held by a whole wave (lane i holds entry i).
+__device__ __forceinline__ bool rank64(unsigned x, int lane, int n, int& pos, int& m) {
+  bool first = lane < n && x != kSelf;
+  for (int j = 0; j < n; ++j) {
+    const unsigned y = (unsigned)__shfl((int)x, j, 64);
+    if (j < lane && y == x) first = false;
+  }
+  const unsigned long long kb = __ballot(first);
+  int p = 0;
+  for (int j = 0; j < n; ++j) {
+    const unsigned y = (unsigned)__shfl((int)x, j, 64);
+    if (((kb >> j) & 1ull) && y < x) ++p;
+  }
+  pos = p;
+  m = __popcll(kb);
+  return first;
 }
 
 // The body works on plain pointers; instantiated once with LDS pointers and
@@ -176,17 +227,33 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
   }
   __syncthreads();
   {
+    // ascending order inside each group (the atomics above placed members in arrival order)
     int big = 0;
-    for (int g = t; g < G; g += T) {
-      int s = MS[g], n = MS[g + 1] - s;
-      if (n > kSmallRow) big = 1;
-      else if (n > 1) insertion_sort(MEM + s, n);
+    for (int g0 = 0; g0 < G; g0 += T) {         // uniform trip count: the wave votes on the network size
+      const int g = g0 + t;
+      int s = 0, n = 0;
+      if (g < G) {
+        s = MS[g];
+        n = MS[g + 1] - s;
+      }
+      if (n > kSmallRow) {
+        big = 1;
+        n = 0;
+      }
+      sort_unique_by_class(MEM + s, n);          // members are distinct: all are kept
     }
     if (__syncthreads_or(big)) {
-      // large groups: ordered compaction by one wave each
       for (int g = wave; g < G; g += kCW) {
         const int s = MS[g], n = MS[g + 1] - s;
         if (n <= kSmallRow) continue;
+        if (n <= 64) {
+          const unsigned x = lane < n ? MEM[s + lane] : kSelf;
+          int pos, m;
+          const bool keep = rank64(x, lane, n, pos, m);
+          if (keep) MEM[s + pos] = (u16)x;
+          continue;
+        }
+        // large groups: ordered compaction over all nodes
         int cnt = 0;
         for (int v0 = 0; v0 < N; v0 += 64) {
           int v = v0 + lane;
@@ -196,8 +263,8 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
           cnt += __popcll(m);
         }
       }
-      __syncthreads();
     }
+    __syncthreads();
   }
   for (int i = t; i < N; i += T) tmp.members[coff + i] = MEM[i];
   for (int g = t; g <= G; g += T) tmp.mstart[nslot + g] = MS[g];
@@ -250,28 +317,35 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
     }
     __syncthreads();
     int big = 0;
-    for (int g = t; g < G; g += T) {
-      const int s = A[MS[g]], n = A[MS[g + 1]] - s;
-      if (n > kSmallRow) {
-        big = 1;
-      } else {
-        u16* a = RAW + s;
-        insertion_sort(a, n);
-        int m = 0;
-        for (int i = 0; i < n; ++i) {
-          u16 x = a[i];
-          if (x == kSelf) break;
-          if (m == 0 || a[m - 1] != x) a[m++] = x;
-        }
-        UL[g] = m;
+    for (int g0 = 0; g0 < G; g0 += T) {         // uniform trip count: the wave votes on the network size
+      const int g = g0 + t;
+      int s = 0, n = 0;
+      if (g < G) {
+        s = A[MS[g]];
+        n = A[MS[g + 1]] - s;
       }
+      const bool here = n <= kSmallRow;
+      if (!here) {
+        big = 1;
+        n = 0;
+      }
+      const int m = sort_unique_by_class(RAW + s, n);
+      if (here && g < G) UL[g] = m;
     }
     if (__syncthreads_or(big)) {
-      // long rows: mark neighbours in a per-wave bitmap, then list the set bits
       const int W = (G + 31) / 32;
       for (int g = wave; g < G; g += kCW) {
         const int s = A[MS[g]], n = A[MS[g + 1]] - s;
         if (n <= kSmallRow) continue;
+        if (n <= 64) {
+          const unsigned x = lane < n ? RAW[s + lane] : kSelf;
+          int pos, m;
+          const bool keep = rank64(x, lane, n, pos, m);
+          if (keep) RAW[s + pos] = (u16)x;
+          if (lane == 0) UL[g] = m;
+          continue;
+        }
+        // long rows: mark neighbours in a per-wave bitmap, then list the set bits
         for (int i = lane; i < n; i += 64) {
           u16 x = RAW[s + i];
           if (x != kSelf) atomicOr(&BM[x >> 5], 1u << (x & 31));
@@ -295,8 +369,8 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         if (lane == 0) UL[g] = cnt;
       }
-      __syncthreads();
     }
+    __syncthreads();
     Ec = block_exscan(UL, UL, G, wsum);
     if (t == 0) UL[G] = Ec;
     __syncthreads();
