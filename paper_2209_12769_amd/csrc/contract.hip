@@ -32,7 +32,7 @@ typedef unsigned short u16;
 
 // Byte offsets of the per-candidate working arrays (same on host and device).
 struct Slab {
-  int A, MS, UL, BM, NID, MEM, RAW, total;
+  int A, MS, UL, BM, NID, MEM, RAW, LST, total;
 };
 __host__ __device__ inline int align16(int x) { return (x + 15) & ~15; }
 __host__ __device__ inline Slab slab_layout(int N, int E) {
@@ -45,6 +45,7 @@ __host__ __device__ inline Slab slab_layout(int N, int E) {
   s.NID = o; o = align16(o + 2 * (N + 1));          // u16   [N] contracted id per base node
   s.MEM = o; o = align16(o + 2 * (N + 1));          // u16   [N] base nodes grouped by contracted id
   s.RAW = o; o = align16(o + 2 * ((E > N ? E : N) + 1));   // u16 [max(E,N)] labels, later remapped neighbours by row
+  s.LST = o; o = align16(o + 2 * (N + 1));          // u16   [N] lists set aside for the second sorting pass
   s.total = o;
   return s;
 }
@@ -165,6 +166,8 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
   u16* NID = reinterpret_cast<u16*>(base + L.NID);
   u16* MEM = reinterpret_cast<u16*>(base + L.MEM);
   u16* RAW = reinterpret_cast<u16*>(base + L.RAW);
+  u16* LST = reinterpret_cast<u16*>(base + L.LST);
+  int* lst_cnt = wsum + kCW;       // one more word behind the scan's wave sums
 
   const int coff = cand_off[c];
   const int* lab = label + coff;
@@ -227,8 +230,11 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
   }
   __syncthreads();
   {
-    // ascending order inside each group (the atomics above placed members in arrival order)
-    int big = 0;
+    // ascending order inside each group (the atomics above placed members in arrival order):
+    // groups of up to 16 at once, one thread each; longer ones are set aside and taken
+    // densely packed afterwards (up to 32: one thread; up to 64: one wave; else all nodes)
+    if (t == 0) *lst_cnt = 0;
+    __syncthreads();
     for (int g0 = 0; g0 < G; g0 += T) {         // uniform trip count: the wave votes on the network size
       const int g = g0 + t;
       int s = 0, n = 0;
@@ -237,15 +243,33 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
         n = MS[g + 1] - s;
       }
       if (n > kSmallRow) {
-        big = 1;
+        LST[atomicAdd(lst_cnt, 1)] = (u16)g;
         n = 0;
       }
       sort_unique_by_class(MEM + s, n);          // members are distinct: all are kept
     }
+    __syncthreads();
+    const int nl = *lst_cnt;
+    int big = 0;
+    for (int i0 = 0; i0 < nl; i0 += T) {
+      const int i = i0 + t;
+      int s = 0, n = 0;
+      if (i < nl) {
+        const int g = LST[i];
+        s = MS[g];
+        n = MS[g + 1] - s;
+        if (n > 32) {
+          big = 1;
+          n = 0;
+        }
+      }
+      if (__any(n > 0)) sort_unique_small<32>(MEM + s, n);
+    }
     if (__syncthreads_or(big)) {
-      for (int g = wave; g < G; g += kCW) {
+      for (int i = wave; i < nl; i += kCW) {
+        const int g = LST[i];
         const int s = MS[g], n = MS[g + 1] - s;
-        if (n <= kSmallRow) continue;
+        if (n <= 32) continue;
         if (n <= 64) {
           const unsigned x = lane < n ? MEM[s + lane] : kSelf;
           int pos, m;
@@ -316,7 +340,9 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
       }
     }
     __syncthreads();
-    int big = 0;
+    // same three passes as for the member lists; here entries equal to kSelf and repeats go
+    if (t == 0) *lst_cnt = 0;
+    __syncthreads();
     for (int g0 = 0; g0 < G; g0 += T) {         // uniform trip count: the wave votes on the network size
       const int g = g0 + t;
       int s = 0, n = 0;
@@ -326,17 +352,38 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
       }
       const bool here = n <= kSmallRow;
       if (!here) {
-        big = 1;
+        LST[atomicAdd(lst_cnt, 1)] = (u16)g;
         n = 0;
       }
       const int m = sort_unique_by_class(RAW + s, n);
       if (here && g < G) UL[g] = m;
     }
+    __syncthreads();
+    const int nl = *lst_cnt;
+    int big = 0;
+    for (int i0 = 0; i0 < nl; i0 += T) {
+      const int i = i0 + t;
+      int s = 0, n = 0, g = 0;
+      if (i < nl) {
+        g = LST[i];
+        s = A[MS[g]];
+        n = A[MS[g + 1]] - s;
+        if (n > 32) {
+          big = 1;
+          n = 0;
+        }
+      }
+      if (__any(n > 0)) {
+        const int m = sort_unique_small<32>(RAW + s, n);
+        if (n > 0) UL[g] = m;
+      }
+    }
     if (__syncthreads_or(big)) {
       const int W = (G + 31) / 32;
-      for (int g = wave; g < G; g += kCW) {
+      for (int i = wave; i < nl; i += kCW) {
+        const int g = LST[i];
         const int s = A[MS[g]], n = A[MS[g + 1]] - s;
-        if (n <= kSmallRow) continue;
+        if (n <= 32) continue;
         if (n <= 64) {
           const unsigned x = lane < n ? RAW[s + lane] : kSelf;
           int pos, m;
@@ -346,8 +393,8 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
           continue;
         }
         // long rows: mark neighbours in a per-wave bitmap, then list the set bits
-        for (int i = lane; i < n; i += 64) {
-          u16 x = RAW[s + i];
+        for (int i2 = lane; i2 < n; i2 += 64) {
+          u16 x = RAW[s + i2];
           if (x != kSelf) atomicOr(&BM[x >> 5], 1u << (x & 31));
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
@@ -394,7 +441,7 @@ __global__ __launch_bounds__(kCT) void contract_kernel(BaseGraphs bg, int C, con
                                                         const int* cand_off, const int* label, ContractTmp tmp,
                                                         int* new_id_out, int* status, char* gslab,
                                                         size_t slab_stride, int lds_bytes) {
-  __shared__ int wsum[kCW];
+  __shared__ int wsum[kCW + 1];
   if (status[0] != 0) return;
   for (int c = blockIdx.x; c < C; c += gridDim.x) {
     const int b = cand_graph[c];
