@@ -114,19 +114,29 @@ __device__ __forceinline__ void wait_vm() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
-// vmcnt(12) if `more` (wave-uniform) is non-zero, else vmcnt(8), as one statement: two separate
-// wait sites in an if/else around the tile epilogue made the register allocator spill.
-__device__ __forceinline__ void wait_vm_8_or_12(int more) {
+// s_waitcnt vmcnt(4 * n4), n4 in 0..3 (wave-uniform), as one statement: separate wait sites in
+// an if/else around the tile epilogue made the register allocator spill.
+__device__ __forceinline__ void wait_vm_times4(int n4) {
   asm volatile(
-      "s_cmp_lg_u32 %0, 0\n\t"
+      "s_cmp_eq_u32 %0, 3\n\t"
       "s_cbranch_scc1 .Ldc_w12_%=\n\t"
+      "s_cmp_eq_u32 %0, 2\n\t"
+      "s_cbranch_scc1 .Ldc_w8_%=\n\t"
+      "s_cmp_eq_u32 %0, 1\n\t"
+      "s_cbranch_scc1 .Ldc_w4_%=\n\t"
+      "s_waitcnt vmcnt(0)\n\t"
+      "s_branch .Ldc_wend_%=\n"
+      ".Ldc_w4_%=:\n\t"
+      "s_waitcnt vmcnt(4)\n\t"
+      "s_branch .Ldc_wend_%=\n"
+      ".Ldc_w8_%=:\n\t"
       "s_waitcnt vmcnt(8)\n\t"
       "s_branch .Ldc_wend_%=\n"
       ".Ldc_w12_%=:\n\t"
       "s_waitcnt vmcnt(12)\n"
       ".Ldc_wend_%=:"
       :
-      : "s"(more)
+      : "s"(n4)
       : "scc", "memory");
 }
 // One step of a data-moving wave: issue the loads of job s+3 into register stage Q and
@@ -316,7 +326,7 @@ struct MfmaConst {
 template <int DCH>
 __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
   constexpr int NK = Shape<DCH>::NK;
-  int a_dma = 0;
+  int n_req = 0;                            // requests of this step, in fours
   if (s + 2 >= 0) {
     const int J = s + 2;
     const int ti = J / NK, kc = J - ti * NK;
@@ -325,7 +335,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
       // eight rows, four per wave; lane l fills position l&7 of row l>>3 of its piece, which
       // under the swizzle holds column piece (l&7) ^ ((row>>1)&7).  Rows past the end are
       // clamped to the last row (read, never stored).
-      a_dma = 1;
+      n_req += 1;
       const int m0 = (c.tile0 + ti * c.per) * kBM;
       const unsigned aring = c.lds0 + (unsigned)(J % 3) * kABytes;
 #pragma unroll
@@ -338,14 +348,19 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
       }
     }
     // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run; each wave moves
-    // eight 1 KB pieces of it (chunk index clamped at the end: the count of loads is fixed)
-    const int jn = min(J, S - 1);
-    const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % NK) * kBBytes;
-    const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
+    // eight 1 KB pieces of it (chunk index clamped at the end: the count of loads is fixed).
+    // With three chunks in all (DCH = 1) chunk k always lands in ring slot k: the ring then
+    // holds the whole of W and only the first tile loads it.
+    if (NK > 3 || J < NK) {
+      n_req += 2;
+      const int jn = min(J, S - 1);
+      const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % NK) * kBBytes;
+      const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int piece = c.wave * 8 + i;     // c.wave is wave-uniform by construction (readfirstlane)
-      load16_to_lds(wsrc + piece * 1024 + c.lane * 16, ring + piece * 1024);
+      for (int i = 0; i < 8; ++i) {
+        const int piece = c.wave * 8 + i;   // c.wave is wave-uniform by construction (readfirstlane)
+        load16_to_lds(wsrc + piece * 1024 + c.lane * 16, ring + piece * 1024);
+      }
     }
   }
   if (s >= 0) {
@@ -370,11 +385,11 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   }
-  // All but this step's requests (eight W pieces and, for one of the node's own chunks, four
+  // All but this step's requests (eight W pieces and/or, for one of the node's own chunks, four
   // A pieces): everything requested one step ago, which job s+1 needs, is in LDS.  Loads
   // complete in issue order, so this holds whatever stores of an earlier tile are still
   // on their way; placed before the tile's stores so that it never waits for those.
-  wait_vm_8_or_12(__builtin_amdgcn_readfirstlane(a_dma));
+  wait_vm_times4(__builtin_amdgcn_readfirstlane(n_req));
   const bool tile_end = s >= 0 && (s % NK) == NK - 1;
   if (tile_end) {
     // ---- tile finished.  First bias and ReLU in place, one group of 32 columns at a time,
