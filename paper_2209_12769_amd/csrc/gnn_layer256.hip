@@ -139,8 +139,8 @@ __device__ __forceinline__ void wait_vm_times4(int n4) {
       : "s"(n4)
       : "scc", "memory");
 }
-// One step of a data-moving wave: issue the loads of job s+3 into register stage Q and
-// reduce job s+1 (stage (Q+1)%3, loaded two steps ago) into its LDS ring slot.  The first
+// One step of a data-moving wave: request the rows of job s+3 into register stage Q and
+// reduce job s+1 (stage (Q+1)%3, requested two steps ago) into its LDS ring slot.  The first
 // DCH jobs of a tile are the node's own rows: those go from global memory straight into
 // LDS (issued by the MFMA waves) and cost this wave nothing.  A gather job issues exactly
 // 4 x kU row loads and every step exactly RQ descriptor loads, with no branch around a
@@ -250,13 +250,42 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
 #pragma unroll
       for (int r = 0; r < RQ; ++r) dq[Q][r] = load16i_async(desc_addr<DCH>(c, m2, c2, r));
     }
-    if (g3) {
-      const int seg = kc / DCH;
-      const unsigned kcoff = (unsigned)(kc - seg * DCH) * 128u;             // 64 columns = 128 bytes
-      const char* hb = c.h + (size_t)base_row * kRowBytes;                  // uniform
-      const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
+    // Reduce job s+1 and request the rows of job s+3 item by item, so that the arithmetic of
+    // one fills the time the load unit takes to accept the requests of the other (a request
+    // stalls the wave while the unit's queue is full).  The rows of job s+1 must have landed
+    // before the first item: newer than them are the descriptors and rows of the step before
+    // and this step's descriptors.
+    const bool reduce = s + 1 >= 0 && s + 1 < S && g1;
+    if (reduce) {
+      wait_vm_sel<2 * RQ>(g2);
+      pin(ax[QC]);
+    }
+    const int seg = kc / DCH;
+    const unsigned kcoff = (unsigned)(kc - seg * DCH) * 128u;               // 64 columns = 128 bytes
+    const char* hb = c.h + (size_t)base_row * kRowBytes;                    // uniform
+    const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
+    char* dst = c.smem + ((s + 1 + 3) % 3) * kABytes + c.aoff;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {
+      if (reduce) {
+        const int dg = sdeg[QC][i];
+        // branch-free mean in ascending neighbour order: slot u counts iff u < deg
+        const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
+        const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
+        const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][1], x2 = ax[QC][i][2];
+        v4u o;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float lo = __uint_as_float(x0[w] << 16);
+          float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
+          bf16_pair_add(lo, hi, x1[w], k1);
+          bf16_pair_add(lo, hi, x2[w], k2);
+          o[w] = pack_bf16x2(lo * sc, hi * sc);
+        }
+        o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
+        *reinterpret_cast<v4u*>(dst + 32 * i * kARow) = o;    // rows ar + 32 i share the swizzle of row ar
+      }
+      if (g3) {
         unsigned g0, ga, gb;
         int dg;
         if (Shape<DCH>::DIRECT) {
@@ -270,7 +299,7 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
           gb = seg == 2 ? off[1][i][2] : off[0][i][2];
           dg = seg == 2 ? dgs[1][i] : dgs[0][i];
         }
-        sdeg[Q][i] = dg;                   // travels with the rows: the filed copy may be replaced before they are reduced
+        sdeg[Q][i] = dg;                      // travels with the rows: the filed copy may be replaced before they are reduced
         // rows left to the pre-pass have all three offsets on the row itself (see build_desc):
         // slot 0 then reads the row's finished mean from the pre-pass buffer
         const char* b0 = dg > kU ? pb : hb;
@@ -278,32 +307,6 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
         ax[Q][i][1] = load16_async(hb, ga + kcoff);
         ax[Q][i][2] = load16_async(hb, gb + kcoff);
       }
-    }
-  }
-  if (s + 1 >= 0 && s + 1 < S && g1) {
-    const int J = s + 1;
-    char* dst = c.smem + (J % 3) * kABytes + c.aoff;
-    // newer than this job's rows: the descriptors and rows of the two steps since
-    wait_vm_sel<2 * RQ>(g2 + g3);
-    pin(ax[QC]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int dg = sdeg[QC][i];
-      // branch-free mean in ascending neighbour order: slot u counts iff u < deg
-      const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
-      const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
-      const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][1], x2 = ax[QC][i][2];
-      v4u o;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        float lo = __uint_as_float(x0[w] << 16);
-        float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
-        bf16_pair_add(lo, hi, x1[w], k1);
-        bf16_pair_add(lo, hi, x2[w], k2);
-        o[w] = pack_bf16x2(lo * sc, hi * sc);
-      }
-      o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
-      *reinterpret_cast<v4u*>(dst + 32 * i * kARow) = o;      // rows ar + 32 i share the swizzle of row ar
     }
   }
 }

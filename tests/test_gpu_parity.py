@@ -174,6 +174,20 @@ def test_every_list_length_class_of_the_contraction(B):
     ev.close()
 
 
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name,n_forward", [("cfg3", 8), ("cfg4", 0), ("cfg5", 3)])
+def test_full_size_contraction_of_every_candidate(B, name, n_forward):
+    # the configurations at their full candidate counts (1024, 4096, 8192 over 64 base graphs):
+    # every array of the contraction bit for bit, predictions on a few candidates
+    w = wl.make(name, None)
+    ev, batch, ref = check_contraction(B, w)
+    if n_forward:
+        order = np.argsort([w.graphs[b].n for b in w.cand_graph], kind="stable")
+        idx = sorted({int(order[i]) for i in np.linspace(0, w.n_cand - 1, n_forward).astype(int)})
+        check_forward(B, w, ev, batch, ref, sample=idx)
+    ev.close()
+
+
 def test_full_size_bulk_batch_sampled_and_deterministic(B):
     # the benchmark's own launch: 4096 candidates of the bulk shape through dc_eval_candidates;
     # sampled candidates against the oracle, the whole vector against a second run
