@@ -24,6 +24,18 @@
 //    graph (Sec. 3.3.1 second equation); then fully connected layers with
 //    ReLU and a scalar output (Sec. 3.3.2).
 //
+//  * The same forward pass with the neighbourhood encoding of Sec. 3.3.1 taken with
+//    attention coefficients (orc_gnn_forward_attn).  The paper names K heads, a
+//    coefficient gamma^k_ij per neighbour j of i (i included) and one weight
+//    matrix W^k per head, but prints no formula for gamma; this build reads it
+//    the way graph attention networks do (a reading, labelled as such):
+//        z_j = W e'_j,   u^k_ij = LeakyReLU_0.2(a_src^k . z^k_i + a_dst^k . z^k_j),
+//        gamma^k_ij = softmax over j in N_i of u^k_ij,
+//        e^k_i = ReLU(sum_j gamma^k_ij z^k_j + b^k),
+//    heads being contiguous blocks of H/K columns.  N_i is the list
+//    (i, predecessors ascending, successors ascending); a node that is both a
+//    predecessor and a successor counts twice.
+//
 // Numerics: values are stored as fp32, every sum and dot product is
 // accumulated in fp64 and rounded once.  With bf16 != 0 the storage points
 // that the bf16 device path rounds (contracted features, all activations,
@@ -37,6 +49,10 @@
 // weights (bias-only closed form), identity self-weights (readout equals
 // column sums), edgeless graphs, and one hand-worked example.  Agreement with
 // the paper's *trained* estimator: parity unpinned (no weights or data exist).
+// Attention variant: zero attention vectors (closed form: plain mean over N_i),
+// a dense masked-softmax float64 formulation on small graphs, a single-node graph,
+// invariance to a shift of all scores of a node, and one hand-worked example;
+// that gamma has this form in the paper's own code: parity unpinned.
 #include <cstdint>
 #include <cstring>
 #include <cmath>
@@ -116,6 +132,45 @@ int contract_one(int n, const int32_t* rowptr, const int32_t* col, const float* 
     in_rowptr[g + 1] += in_rowptr[g];
   }
   return 0;
+}
+
+// Sum over the nodes of each graph (Sec. 3.3.1, second equation) and the fully connected
+// layers with ReLU and a scalar output (Sec. 3.3.2).
+void readout_and_head(int n_cand, const int32_t* node_off, const float* h, int H, int bf16, const float* head,
+                      float* pred, float* readout) {
+  const size_t HH = static_cast<size_t>(H) * H;
+  std::vector<float> hd(head, head + 2 * HH + 3 * H + 1);
+  if (bf16) {
+    for (size_t i = 0; i < HH; ++i) hd[i] = round_bf16(hd[i]);                     // W1
+    for (size_t i = 0; i < HH; ++i) hd[HH + H + i] = round_bf16(hd[HH + H + i]);   // W2
+    for (int i = 0; i < H; ++i) hd[2 * HH + 2 * H + i] = round_bf16(hd[2 * HH + 2 * H + i]);  // w3
+  }
+  const float* W1 = hd.data();
+  const float* b1 = W1 + HH;
+  const float* W2 = b1 + H;
+  const float* b2 = W2 + HH;
+  const float* w3 = b2 + H;
+  const float* b3 = w3 + H;
+  std::vector<double> r(H), z1(H), z2(H);
+  std::vector<float> rf(H), z1f(H), z2f(H);
+  for (int c = 0; c < n_cand; ++c) {
+    for (int j = 0; j < H; ++j) r[j] = 0.0;
+    for (int64_t v = node_off[c]; v < node_off[c + 1]; ++v)
+      for (int j = 0; j < H; ++j) r[j] += h[static_cast<size_t>(v) * H + j];
+    for (int j = 0; j < H; ++j) rf[j] = static_cast<float>(r[j]);
+    if (readout) std::memcpy(readout + static_cast<size_t>(c) * H, rf.data(), H * sizeof(float));
+    for (int j = 0; j < H; ++j) z1[j] = b1[j];
+    for (int k = 0; k < H; ++k)
+      for (int j = 0; j < H; ++j) z1[j] += static_cast<double>(rf[k]) * W1[static_cast<size_t>(k) * H + j];
+    for (int j = 0; j < H; ++j) z1f[j] = static_cast<float>(z1[j] > 0.0 ? z1[j] : 0.0);
+    for (int j = 0; j < H; ++j) z2[j] = b2[j];
+    for (int k = 0; k < H; ++k)
+      for (int j = 0; j < H; ++j) z2[j] += static_cast<double>(z1f[k]) * W2[static_cast<size_t>(k) * H + j];
+    for (int j = 0; j < H; ++j) z2f[j] = static_cast<float>(z2[j] > 0.0 ? z2[j] : 0.0);
+    double t = b3[0];
+    for (int j = 0; j < H; ++j) t += static_cast<double>(z2f[j]) * w3[j];
+    pred[c] = static_cast<float>(t);
+  }
 }
 
 }  // namespace
@@ -201,20 +256,8 @@ void orc_gnn_forward(int n_cand, const int32_t* node_off,
   size_t wlen = 0;
   for (int l = 0; l < L; ++l) wlen += static_cast<size_t>(3) * (l == 0 ? F : H) * H;
   std::vector<float> W(W_layers, W_layers + wlen);
-  const size_t HH = static_cast<size_t>(H) * H;
-  std::vector<float> hd(head, head + 2 * HH + 3 * H + 1);
-  if (bf16) {
+  if (bf16)
     for (auto& w : W) w = round_bf16(w);
-    for (size_t i = 0; i < HH; ++i) hd[i] = round_bf16(hd[i]);                     // W1
-    for (size_t i = 0; i < HH; ++i) hd[HH + H + i] = round_bf16(hd[HH + H + i]);   // W2
-    for (int i = 0; i < H; ++i) hd[2 * HH + 2 * H + i] = round_bf16(hd[2 * HH + 2 * H + i]);  // w3
-  }
-  const float* W1 = hd.data();
-  const float* b1 = W1 + HH;
-  const float* W2 = b1 + H;
-  const float* b2 = W2 + HH;
-  const float* w3 = b2 + H;
-  const float* b3 = w3 + H;
 
   int dmax = F > H ? F : H;
   std::vector<float> h(static_cast<size_t>(Ntot) * dmax), hn(static_cast<size_t>(Ntot) * dmax);
@@ -258,27 +301,94 @@ void orc_gnn_forward(int n_cand, const int32_t* node_off,
     d = H;
   }
   if (h_last) std::memcpy(h_last, h.data(), static_cast<size_t>(Ntot) * H * sizeof(float));
+  readout_and_head(n_cand, node_off, h.data(), H, bf16, head, pred, readout);
+}
 
-  std::vector<double> r(H), z1(H), z2(H);
-  std::vector<float> rf(H), z1f(H), z2f(H);
-  for (int c = 0; c < n_cand; ++c) {
-    for (int j = 0; j < H; ++j) r[j] = 0.0;
-    for (int64_t v = node_off[c]; v < node_off[c + 1]; ++v)
-      for (int j = 0; j < H; ++j) r[j] += h[v * H + j];
-    for (int j = 0; j < H; ++j) rf[j] = static_cast<float>(r[j]);
-    if (readout) std::memcpy(readout + static_cast<size_t>(c) * H, rf.data(), H * sizeof(float));
-    for (int j = 0; j < H; ++j) z1[j] = b1[j];
-    for (int k = 0; k < H; ++k)
-      for (int j = 0; j < H; ++j) z1[j] += static_cast<double>(rf[k]) * W1[static_cast<size_t>(k) * H + j];
-    for (int j = 0; j < H; ++j) z1f[j] = static_cast<float>(z1[j] > 0.0 ? z1[j] : 0.0);
-    for (int j = 0; j < H; ++j) z2[j] = b2[j];
-    for (int k = 0; k < H; ++k)
-      for (int j = 0; j < H; ++j) z2[j] += static_cast<double>(z1f[k]) * W2[static_cast<size_t>(k) * H + j];
-    for (int j = 0; j < H; ++j) z2f[j] = static_cast<float>(z2[j] > 0.0 ? z2[j] : 0.0);
-    double t = b3[0];
-    for (int j = 0; j < H; ++j) t += static_cast<double>(z2f[j]) * w3[j];
-    pred[c] = static_cast<float>(t);
+// Forward pass with attention coefficients (see the header of this file).
+//   W_layers: concat over l of W^l, row-major [d_l, H] (d_0 = F, else H).
+//   att:      concat over l of a_src^l [H] | a_dst^l [H] (head k owns columns k*H/K ..).
+//   b_layers: concat of b^l [H].
+void orc_gnn_forward_attn(int n_cand, const int32_t* node_off,
+                          const int32_t* out_rowptr, const int32_t* out_col,
+                          const int32_t* in_rowptr, const int32_t* in_col,
+                          const float* Xc, int F, int H, int L, int K, int bf16,
+                          const float* W_layers, const float* att, const float* b_layers, const float* head,
+                          float* pred, float* h_last, float* readout) {
+  const int64_t Ntot = node_off[n_cand];
+  const int Dh = H / K;
+  size_t wlen = 0;
+  for (int l = 0; l < L; ++l) wlen += static_cast<size_t>(l == 0 ? F : H) * H;
+  std::vector<float> W(W_layers, W_layers + wlen);
+  if (bf16)
+    for (auto& w : W) w = round_bf16(w);
+  const int dmax = F > H ? F : H;
+  std::vector<float> h(static_cast<size_t>(Ntot) * dmax), hn(static_cast<size_t>(Ntot) * H);
+  std::vector<float> z(static_cast<size_t>(Ntot) * H), sc_src(static_cast<size_t>(Ntot) * K),
+      sc_dst(static_cast<size_t>(Ntot) * K);
+  for (int64_t v = 0; v < Ntot; ++v)
+    for (int k = 0; k < F; ++k) h[v * F + k] = bf16 ? round_bf16(Xc[v * F + k]) : Xc[v * F + k];
+  std::vector<double> acc(H), u, wgt;
+  std::vector<int64_t> nb;
+  const float* Wl = W.data();
+  const float* al = att;
+  const float* bl = b_layers;
+  int d = F;
+  for (int l = 0; l < L; ++l) {
+    // z = W e' per node, then the two score terms per node and head
+    for (int64_t v = 0; v < Ntot; ++v) {
+      for (int j = 0; j < H; ++j) acc[j] = 0.0;
+      for (int k = 0; k < d; ++k) {
+        const double a = h[v * d + k];
+        const float* wrow = Wl + static_cast<size_t>(k) * H;
+        for (int j = 0; j < H; ++j) acc[j] += a * wrow[j];
+      }
+      for (int j = 0; j < H; ++j) z[v * H + j] = store(acc[j], bf16);
+      for (int k = 0; k < K; ++k) {
+        double ss = 0.0, tt = 0.0;
+        for (int c = k * Dh; c < (k + 1) * Dh; ++c) {
+          ss += static_cast<double>(al[c]) * z[v * H + c];
+          tt += static_cast<double>(al[H + c]) * z[v * H + c];
+        }
+        sc_src[v * K + k] = static_cast<float>(ss);
+        sc_dst[v * K + k] = static_cast<float>(tt);
+      }
+    }
+    for (int64_t v = 0; v < Ntot; ++v) {
+      nb.clear();
+      nb.push_back(v);
+      for (int e = in_rowptr[v]; e < in_rowptr[v + 1]; ++e) nb.push_back(in_col[e]);
+      for (int e = out_rowptr[v]; e < out_rowptr[v + 1]; ++e) nb.push_back(out_col[e]);
+      u.resize(nb.size());
+      wgt.resize(nb.size());
+      for (int k = 0; k < K; ++k) {
+        double m = -INFINITY;
+        for (size_t i = 0; i < nb.size(); ++i) {
+          double x = static_cast<double>(sc_src[v * K + k]) + static_cast<double>(sc_dst[nb[i] * K + k]);
+          x = x > 0.0 ? x : 0.2 * x;
+          u[i] = x;
+          if (x > m) m = x;
+        }
+        double den = 0.0;
+        for (size_t i = 0; i < nb.size(); ++i) {
+          wgt[i] = std::exp(u[i] - m);
+          den += wgt[i];
+        }
+        for (int c = k * Dh; c < (k + 1) * Dh; ++c) {
+          double o = 0.0;
+          for (size_t i = 0; i < nb.size(); ++i) o += wgt[i] / den * z[nb[i] * H + c];
+          o += bl[c];
+          hn[v * H + c] = store(o > 0.0 ? o : 0.0, bf16);
+        }
+      }
+    }
+    h.assign(hn.begin(), hn.end());
+    Wl += static_cast<size_t>(d) * H;
+    al += 2 * H;
+    bl += H;
+    d = H;
   }
+  if (h_last) std::memcpy(h_last, h.data(), static_cast<size_t>(Ntot) * H * sizeof(float));
+  readout_and_head(n_cand, node_off, h.data(), H, bf16, head, pred, readout);
 }
 
 }  // extern "C"

@@ -120,10 +120,17 @@ def gnn_forward(b: Batch, model, weights, bf16: Optional[bool] = None, want_hidd
     bl = np.ascontiguousarray(weights.biases, dtype=np.float32)
     hd = np.ascontiguousarray(weights.head, dtype=np.float32)
     Xc = np.ascontiguousarray(b.Xc, dtype=np.float32)
-    lib.orc_gnn_forward(C.c_int(b.n_cand), _p(b.node_off), _p(b.out_rowptr), _p(b.out_col),
-                        _p(b.in_rowptr), _p(b.in_col), _p(Xc), C.c_int(model.F), C.c_int(model.H),
-                        C.c_int(model.L), C.c_int(int(bf16)), _p(Wl), _p(bl), _p(hd),
-                        _p(pred), _p(h_last), _p(ro))
+    if getattr(model, "agg", "mean") == "attention":
+        at = np.ascontiguousarray(weights.att, dtype=np.float32)
+        lib.orc_gnn_forward_attn(C.c_int(b.n_cand), _p(b.node_off), _p(b.out_rowptr), _p(b.out_col),
+                                 _p(b.in_rowptr), _p(b.in_col), _p(Xc), C.c_int(model.F), C.c_int(model.H),
+                                 C.c_int(model.L), C.c_int(model.heads), C.c_int(int(bf16)), _p(Wl), _p(at), _p(bl),
+                                 _p(hd), _p(pred), _p(h_last), _p(ro))
+    else:
+        lib.orc_gnn_forward(C.c_int(b.n_cand), _p(b.node_off), _p(b.out_rowptr), _p(b.out_col),
+                            _p(b.in_rowptr), _p(b.in_col), _p(Xc), C.c_int(model.F), C.c_int(model.H),
+                            C.c_int(model.L), C.c_int(int(bf16)), _p(Wl), _p(bl), _p(hd),
+                            _p(pred), _p(h_last), _p(ro))
     if want_hidden:
         return pred, h_last[:b.ntot], ro[:b.n_cand]
     return pred

@@ -105,6 +105,8 @@ class ModelSpec:
     H: int
     L: int
     dtype: str              # "f32" | "bf16"
+    agg: str = "mean"       # "mean": in/out mean aggregation; "attention": K-head attention over N_i
+    heads: int = 1          # K (attention only); H must be a multiple of K
 
 
 @dataclass
@@ -112,10 +114,12 @@ class Weights:
     """fp32 master weights.  layers = concat over l of W^l row-major [3d, H]
     (row blocks: self, in-mean, out-mean); biases = concat of b^l [H];
     head = W1[H,H] | b1[H] | W2[H,H] | b2[H] | w3[H] | b3[1], W row-major
-    [in, out]."""
+    [in, out].  With attention aggregation W^l is [d, H] and att = concat over l
+    of a_src^l[H] | a_dst^l[H] (head k owns columns k*H/K .. (k+1)*H/K)."""
     layers: np.ndarray
     biases: np.ndarray
     head: np.ndarray
+    att: Optional[np.ndarray] = None
 
 
 @dataclass
@@ -432,18 +436,27 @@ def make_weights(model: ModelSpec, seed: int = 0, std: Optional[float] = None) -
     one stream.  std=None scales each tensor by 1/sqrt(fan_in) (keeps
     activations O(1) at any width); biases use the same std as their layer."""
     rng = Rng(seed, 7)
-    Ws, bs = [], []
+    Ws, bs, As = [], [], []
     for l in range(model.L):
         d = model.F if l == 0 else model.H
-        s = std if std is not None else 1.0 / math.sqrt(3 * d)
-        Ws.append(rng.normal(3 * d * model.H) * s)
-        bs.append(rng.normal(model.H) * s)
+        if model.agg == "attention":
+            # draw order per layer: W, a_src, a_dst, b
+            s = std if std is not None else 1.0 / math.sqrt(d)
+            Ws.append(rng.normal(d * model.H) * s)
+            sa = std if std is not None else 1.0 / math.sqrt(model.H // model.heads)
+            As.append(rng.normal(2 * model.H) * sa)
+            bs.append(rng.normal(model.H) * s)
+        else:
+            s = std if std is not None else 1.0 / math.sqrt(3 * d)
+            Ws.append(rng.normal(3 * d * model.H) * s)
+            bs.append(rng.normal(model.H) * s)
     H = model.H
     s = std if std is not None else 1.0 / math.sqrt(H)
     head = [rng.normal(H * H) * s, rng.normal(H) * s, rng.normal(H * H) * s, rng.normal(H) * s,
             rng.normal(H) * s, rng.normal(1) * s]
     return Weights(np.concatenate(Ws).astype(np.float32), np.concatenate(bs).astype(np.float32),
-                   np.concatenate(head).astype(np.float32))
+                   np.concatenate(head).astype(np.float32),
+                   np.concatenate(As).astype(np.float32) if As else None)
 
 
 # --------------------------------------------------------------------------
