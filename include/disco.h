@@ -69,6 +69,18 @@ typedef enum {
 
 typedef enum { DC_F32 = 0, DC_BF16 = 1 } dc_dtype;
 
+/* How a layer combines a node's neighbourhood (Sec. 3.3.1, first equation).
+ *   DC_AGG_MEAN       uniform coefficients: mean over predecessors and mean over successors,
+ *                     each with its own weight block next to the node's own (the default).
+ *   DC_AGG_ATTENTION  K heads with attention coefficients over N_i = (i, predecessors,
+ *                     successors).  The paper prints no formula for the coefficients; they
+ *                     are taken as in graph attention networks:
+ *                       z_j = W e'_j,  u_ij = LeakyReLU_0.2(a_src . z_i + a_dst . z_j) per head,
+ *                       gamma_ij = softmax over j in N_i,  e_i = ReLU(sum_j gamma_ij z_j + b),
+ *                     heads being contiguous blocks of H / heads columns.  A node that is both a
+ *                     predecessor and a successor of i is in N_i twice.                          */
+typedef enum { DC_AGG_MEAN = 0, DC_AGG_ATTENTION = 1 } dc_aggregator;
+
 /* Model shape and per-call capacities.
  *   F, H, L          input features, hidden width, number of message-passing layers
  *   dtype            DC_F32: fp32 storage and fp32 matrix arithmetic.
@@ -79,7 +91,9 @@ typedef enum { DC_F32 = 0, DC_BF16 = 1 } dc_dtype;
  *   max_base_nodes   bound on sum over candidates of base-graph node counts (= labels per call)
  *   max_base_edges   bound on sum over candidates of base-graph edge counts
  *   max_nodes        bound on contracted nodes per call; 0 means max_base_nodes
- *   max_edges        bound on contracted edges per call; 0 means max_base_edges           */
+ *   max_edges        bound on contracted edges per call; 0 means max_base_edges
+ *   aggregator       dc_aggregator; DC_AGG_ATTENTION needs H a power of two in [32, 512]
+ *   heads            K (attention only): a power of two with H / K >= 8; ignored for the mean */
 typedef struct {
   int32_t F, H, L;
   int32_t dtype;
@@ -88,6 +102,8 @@ typedef struct {
   int64_t max_base_edges;
   int64_t max_nodes;
   int64_t max_edges;
+  int32_t aggregator;
+  int32_t heads;
 } dc_config;
 
 /* A batch of contracted graphs, block diagonal: candidate c owns nodes
@@ -127,6 +143,16 @@ size_t dc_workspace_bytes(const dc_config* cfg);
  *             z1 = ReLU(r W1 + b1), z2 = ReLU(z1 W2 + b2), t = z2.w3 + b3.              */
 dc_status dc_set_weights(dc_ctx* ctx, const float* W_layers, const float* b_layers, const float* head,
                          void* stream);
+
+/* Weights of a context created with DC_AGG_ATTENTION (dc_set_weights is for DC_AGG_MEAN; each
+ * returns DC_ERR_INVALID_ARG on a context of the other kind).  Host fp32.
+ *   W_layers  concat over l of W^l, row-major [d, H], d = F for l = 0 else H.
+ *   att       concat over l of a_src^l [H] | a_dst^l [H]; head k owns columns [k H/K, (k+1) H/K).
+ *   b_layers  concat of b^l [H];  head as for dc_set_weights.
+ * On the bf16 path W and the head matrices are rounded to bfloat16, z = W e' is stored as
+ * bfloat16; scores, softmax and the weighted sums are fp32.                                  */
+dc_status dc_set_attention_weights(dc_ctx* ctx, const float* W_layers, const float* att, const float* b_layers,
+                                   const float* head, void* stream);
 
 /* Base graphs (set once, candidates refer to them by index).  All host pointers.
  *   g_node_off [n+1], g_edge_off [n+1]  node / edge offsets of the graphs

@@ -27,6 +27,8 @@ DC_ERR_HIP = 6
 DC_ERR_UNSUPPORTED = 7
 DC_F32 = 0
 DC_BF16 = 1
+DC_AGG_MEAN = 0
+DC_AGG_ATTENTION = 1
 STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "DC_ERR_BAD_PARTITION",
                 4: "DC_ERR_CAPACITY", 5: "DC_ERR_OOM", 6: "DC_ERR_HIP", 7: "DC_ERR_UNSUPPORTED"}
 
@@ -34,7 +36,8 @@ STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "
 class DcConfig(C.Structure):
     _fields_ = [("F", C.c_int32), ("H", C.c_int32), ("L", C.c_int32), ("dtype", C.c_int32),
                 ("max_cand", C.c_int64), ("max_base_nodes", C.c_int64), ("max_base_edges", C.c_int64),
-                ("max_nodes", C.c_int64), ("max_edges", C.c_int64)]
+                ("max_nodes", C.c_int64), ("max_edges", C.c_int64),
+                ("aggregator", C.c_int32), ("heads", C.c_int32)]
 
 
 class DcBatch(C.Structure):
@@ -66,6 +69,7 @@ def lib():
         L.dc_workspace_bytes.argtypes = [C.POINTER(DcConfig)]
         L.dc_workspace_bytes.restype = C.c_size_t
         L.dc_set_weights.argtypes = [vp, vp, vp, vp, vp]
+        L.dc_set_attention_weights.argtypes = [vp, vp, vp, vp, vp, vp]
         L.dc_set_base_graphs.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.dc_contract_graphs.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp]
         L.dc_gnn_forward.argtypes = [vp, C.POINTER(DcBatch), vp, vp]
@@ -76,7 +80,7 @@ def lib():
         L.dc_last_error.restype = C.c_char_p
         L.dc_profile_begin.argtypes = [vp]
         L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
-        for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_base_graphs", "dc_contract_graphs",
+        for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
                   "dc_gnn_forward", "dc_eval_candidates", "dc_check", "dc_last_totals", "dc_profile_begin",
                   "dc_profile_end"):
             getattr(L, n).restype = i32
@@ -101,6 +105,12 @@ def dc_destroy(ctx: int) -> int:
 
 def dc_set_weights(ctx, W_layers: np.ndarray, b_layers: np.ndarray, head: np.ndarray, stream: int = 0) -> int:
     return lib().dc_set_weights(ctx, W_layers.ctypes.data, b_layers.ctypes.data, head.ctypes.data, stream)
+
+
+def dc_set_attention_weights(ctx, W_layers: np.ndarray, att: np.ndarray, b_layers: np.ndarray, head: np.ndarray,
+                             stream: int = 0) -> int:
+    return lib().dc_set_attention_weights(ctx, W_layers.ctypes.data, att.ctypes.data, b_layers.ctypes.data,
+                                          head.ctypes.data, stream)
 
 
 def dc_set_base_graphs(ctx, n_graphs, g_node_off, g_edge_off, rowptr, col, X, stream: int = 0) -> int:
@@ -166,14 +176,16 @@ class Evaluator:
     """Owns one dc_ctx.  Methods move pointers across the C ABI; nothing is computed in Python."""
 
     def __init__(self, F: int, H: int, L: int, dtype: str, max_cand: int, max_base_nodes: int, max_base_edges: int,
-                 max_nodes: int = 0, max_edges: int = 0, device: str = "cuda:0"):
+                 max_nodes: int = 0, max_edges: int = 0, device: str = "cuda:0", agg: str = "mean", heads: int = 1):
         import torch
         self.torch = torch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = DcConfig(F, H, L, DC_BF16 if dtype == "bf16" else DC_F32, max_cand, max_base_nodes,
-                            max_base_edges, max_nodes, max_edges)
+                            max_base_edges, max_nodes, max_edges,
+                            DC_AGG_ATTENTION if agg == "attention" else DC_AGG_MEAN, heads)
         self.dtype = dtype
+        self.agg = agg
         st, h = dc_create(self.cfg)
         if st != DC_OK:
             raise DiscoError(st, "dc_create")
@@ -201,7 +213,11 @@ class Evaluator:
         W = np.ascontiguousarray(weights.layers, dtype=np.float32)
         b = np.ascontiguousarray(weights.biases, dtype=np.float32)
         hd = np.ascontiguousarray(weights.head, dtype=np.float32)
-        self._ok(dc_set_weights(self.ctx, W, b, hd, self._stream()), "dc_set_weights")
+        if self.agg == "attention":
+            at = np.ascontiguousarray(weights.att, dtype=np.float32)
+            self._ok(dc_set_attention_weights(self.ctx, W, at, b, hd, self._stream()), "dc_set_attention_weights")
+        else:
+            self._ok(dc_set_weights(self.ctx, W, b, hd, self._stream()), "dc_set_weights")
 
     def set_base_graphs(self, g_node_off, g_edge_off, rowptr, col, X):
         gno = np.ascontiguousarray(g_node_off, dtype=np.int32)
@@ -271,7 +287,8 @@ def evaluator_for(w, slack: float = 1.0, max_nodes: int = 0, max_edges: int = 0,
     nb = int(w.cand_off[-1])
     eb = int(sum(int(geo[b + 1] - geo[b]) for b in w.cand_graph))
     ev = Evaluator(w.model.F, w.model.H, w.model.L, w.model.dtype, max(w.n_cand, 1), max(int(nb * slack), 1),
-                   max(int(eb * slack), 1), max_nodes, max_edges, device)
+                   max(int(eb * slack), 1), max_nodes, max_edges, device, getattr(w.model, "agg", "mean"),
+                   getattr(w.model, "heads", 1))
     ev.set_base_graphs(w.g_node_off(), geo, w.cat_rowptr(), w.cat_col(), w.cat_X())
     ev.set_weights(w.weights)
     return ev

@@ -48,6 +48,8 @@ struct dc_ctx {
   void* W = nullptr;
   float* b = nullptr;
   float* head = nullptr;
+  float* att = nullptr;     // attention vectors (DC_AGG_ATTENTION only)
+  float* score[2] = {nullptr, nullptr};
   bool have_weights = false;
   // base graphs
   BaseGraphs bg{};
@@ -66,6 +68,7 @@ namespace {
 
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
                                              "fused_layer", "layer256", "layer256_d64", "aggregate_heavy", "build_desc",
+                                             "attention_project", "attention_scores", "attention_aggregate",
                                              "readout_head"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -130,7 +133,12 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   void* agg1 = a.take<char>((size_t)(k.NN + 1) * D * es);
   void* desc0 = a.take<char>((size_t)(k.NN + 1) * 16);
   void* desc1 = a.take<char>((size_t)(k.NN + 1) * 16);
+  const size_t nscore = cfg.aggregator == DC_AGG_ATTENTION ? (size_t)(k.NN + 1) * cfg.heads : 0;
+  float* score0 = a.take<float>(nscore);
+  float* score1 = a.take<float>(nscore);
   if (ctx) {
+    ctx->score[0] = score0;
+    ctx->score[1] = score1;
     ctx->status = status;
     ctx->totals = totals;
     ctx->tmp = t;
@@ -153,6 +161,11 @@ dc_status cfg_check(const dc_config* c, std::string* why) {
   if (!gnn_shape_supported(c->F, c->H, c->L)) {
     if (why) *why = "need F % 16 == 0, H % 32 == 0, F,H <= 512, L >= 1";
     return (c->F <= 0 || c->H <= 0 || c->L <= 0) ? DC_ERR_INVALID_ARG : DC_ERR_UNSUPPORTED;
+  }
+  if (c->aggregator != DC_AGG_MEAN && c->aggregator != DC_AGG_ATTENTION) return DC_ERR_INVALID_ARG;
+  if (c->aggregator == DC_AGG_ATTENTION && !attention_shape_supported(c->H, c->heads)) {
+    if (why) *why = "attention needs H a power of two in [32, 512] and heads a power of two with H / heads >= 8";
+    return c->heads <= 0 ? DC_ERR_INVALID_ARG : DC_ERR_UNSUPPORTED;
   }
   const long long lim = 2000000000LL;
   if (c->max_cand > lim || c->max_base_nodes + c->max_cand > lim || c->max_base_edges > lim) {
@@ -228,6 +241,12 @@ dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pr
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;
   g.allow_fused = ctx->allow_fused;
+  if (ctx->cfg.aggregator == DC_AGG_ATTENTION) {
+    g.heads = ctx->cfg.heads;
+    g.att = ctx->att;
+    g.score[0] = ctx->score[0];
+    g.score[1] = ctx->score[1];
+  }
   hipError_t e = launch_gnn_forward(g, ctx->prof.on ? &ctx->prof : nullptr, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "forward launch");
   return DC_OK;
@@ -340,7 +359,9 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 64 * sizeof(int), hipHostMallocDefault);
   const size_t es = cfg->dtype == DC_BF16 ? 2 : 4;
   const size_t HH = (size_t)cfg->H * cfg->H;
-  if (e == hipSuccess) e = hipMalloc(&ctx->W, packed_weight_elems(cfg->F, cfg->H, cfg->L) * es);
+  if (e == hipSuccess) e = hipMalloc(&ctx->W, packed_weight_elems(cfg->F, cfg->H, cfg->L, 3) * es);
+  if (e == hipSuccess && cfg->aggregator == DC_AGG_ATTENTION)
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->att), (size_t)cfg->L * 2 * cfg->H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->b), (size_t)cfg->L * cfg->H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->head), (2 * HH + 3 * cfg->H + 1) * sizeof(float));
   if (e != hipSuccess) {
@@ -361,23 +382,22 @@ dc_status dc_destroy(dc_ctx* ctx) {
   if (ctx->W) (void)hipFree(ctx->W);
   if (ctx->b) (void)hipFree(ctx->b);
   if (ctx->head) (void)hipFree(ctx->head);
+  if (ctx->att) (void)hipFree(ctx->att);
   if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
   if (ctx->slab) (void)hipFree(ctx->slab);
   delete ctx;
   return DC_OK;
 }
 
-dc_status dc_set_weights(dc_ctx* ctx, const float* W_layers, const float* b_layers, const float* head,
-                         void* stream) {
-  if (!ctx) return DC_ERR_INVALID_ARG;
-  if (!W_layers || !b_layers || !head) return fail(ctx, DC_ERR_INVALID_ARG, "null weight pointer");
-  hipStream_t s = static_cast<hipStream_t>(stream);
+static dc_status set_weights_common(dc_ctx* ctx, const float* W_layers, const float* att, const float* b_layers,
+                                    const float* head, hipStream_t s) {
   const dc_config& c = ctx->cfg;
   const int bf16 = c.dtype == DC_BF16;
+  const int nseg = c.aggregator == DC_AGG_ATTENTION ? 1 : 3;
   const size_t es = bf16 ? 2 : 4;
-  const size_t nW = packed_weight_elems(c.F, c.H, c.L);
+  const size_t nW = packed_weight_elems(c.F, c.H, c.L, nseg);
   std::vector<char> packed(nW * es);
-  pack_weights_host(W_layers, c.F, c.H, c.L, bf16, packed.data());
+  pack_weights_host(W_layers, c.F, c.H, c.L, nseg, bf16, packed.data());
   const size_t HH = (size_t)c.H * c.H;
   std::vector<float> hd(head, head + 2 * HH + 3 * c.H + 1);
   if (bf16) {
@@ -398,10 +418,30 @@ dc_status dc_set_weights(dc_ctx* ctx, const float* W_layers, const float* b_laye
   hipError_t e = hipMemcpyAsync(ctx->W, packed.data(), nW * es, hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->b, b_layers, (size_t)c.L * c.H * sizeof(float), hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->head, hd.data(), hd.size() * sizeof(float), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && att)
+    e = hipMemcpyAsync(ctx->att, att, (size_t)c.L * 2 * c.H * sizeof(float), hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);   // host staging buffers die at return
-  if (e != hipSuccess) return hip_fail(ctx, e, "dc_set_weights copy");
+  if (e != hipSuccess) return hip_fail(ctx, e, "weight copy");
   ctx->have_weights = true;
   return DC_OK;
+}
+
+dc_status dc_set_weights(dc_ctx* ctx, const float* W_layers, const float* b_layers, const float* head,
+                         void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!W_layers || !b_layers || !head) return fail(ctx, DC_ERR_INVALID_ARG, "null weight pointer");
+  if (ctx->cfg.aggregator != DC_AGG_MEAN)
+    return fail(ctx, DC_ERR_INVALID_ARG, "this context aggregates with attention: use dc_set_attention_weights");
+  return set_weights_common(ctx, W_layers, nullptr, b_layers, head, static_cast<hipStream_t>(stream));
+}
+
+dc_status dc_set_attention_weights(dc_ctx* ctx, const float* W_layers, const float* att, const float* b_layers,
+                                   const float* head, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!W_layers || !att || !b_layers || !head) return fail(ctx, DC_ERR_INVALID_ARG, "null weight pointer");
+  if (ctx->cfg.aggregator != DC_AGG_ATTENTION)
+    return fail(ctx, DC_ERR_INVALID_ARG, "this context aggregates with the mean: use dc_set_weights");
+  return set_weights_common(ctx, W_layers, att, b_layers, head, static_cast<hipStream_t>(stream));
 }
 
 dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_node_off, const int32_t* g_edge_off,

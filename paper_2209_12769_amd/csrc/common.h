@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamReadout, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -109,13 +109,22 @@ struct GnnArgs {
   const int* status;
   int n_cu;
   int allow_fused;      // 0 forces the separate aggregate + update kernels
+  // attention aggregation (heads > 0): W holds one [d, H] block per layer
+  int heads = 0;
+  const float* att = nullptr;   // per layer a_src[H] | a_dst[H]
+  float* score[2] = {nullptr, nullptr};   // per node and head: a_src . z, a_dst . z  [max_nodes, heads]
 };
 hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s);
-// Elements (of the storage dtype) of all layer matrices in device layout.
-size_t packed_weight_elems(int F, int H, int L);
+// Elements (of the storage dtype) of all layer matrices in device layout; nseg row blocks of
+// d rows per layer (3: self / predecessor mean / successor mean; 1: attention).
+size_t packed_weight_elems(int F, int H, int L, int nseg);
 // Host side: converts row-major fp32 W^l into the device layout of the dtype
 // (fp32: unchanged; bf16: [k/8][H][8] so that a lane's 8 consecutive k sit together).
-void pack_weights_host(const float* W_layers, int F, int H, int L, int bf16, void* dst);
+void pack_weights_host(const float* W_layers, int F, int H, int L, int nseg, int bf16, void* dst);
+// gnn_attention.hip: per-node score terms from z, then softmax-weighted sums over N_i
+bool attention_shape_supported(int H, int heads);
+hipError_t launch_attention_scores(const GnnArgs& a, const void* z, const float* att_l, hipStream_t s);
+hipError_t launch_attention_aggregate(const GnnArgs& a, const void* z, const float* bias, void* out, hipStream_t s);
 bool gnn_shape_supported(int F, int H, int L);
 // gnn_fused.hip: one layer with both neighbour means folded into the A-tile load (bf16).
 bool fused_layer_supported(int d, int H, int bf16);

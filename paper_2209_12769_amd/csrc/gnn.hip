@@ -110,9 +110,10 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const void* __restrict__
 //   fp32: A rows padded by one float, B rows padded to an odd multiple of 32.
 template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
-    const void* __restrict__ A0, const void* __restrict__ A1, const void* __restrict__ A2, int d,
+    const void* __restrict__ A0, const void* __restrict__ A1, const void* __restrict__ A2, int d, int nseg,
     const void* __restrict__ Wl, const float* __restrict__ bias, void* __restrict__ out, int H,
     const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  // nseg = 3: out = ReLU([A0 | A1 | A2] W + bias); nseg = 1 (bias == nullptr): out = A0 W
   if (status[0] != 0) return;
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
   const int ntot = node_off[C];
   const int nct = H / BN;
   const int ntiles = ((ntot + BM - 1) / BM) * nct;
-  const int K = 3 * d;
+  const int K = nseg * d;
 
   for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const int m0 = (tile / nct) * BM;
@@ -219,14 +220,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * WN + j * 32 + l32;
-      const float bj = bias[col];
+      const float bj = bias ? bias[col] : 0.f;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
           if (row < ntot) {
-            const float y = fmaxf(acc[i][j][v] + bj, 0.f);
+            const float y = bias ? fmaxf(acc[i][j][v] + bj, 0.f) : acc[i][j][v];
             if (kBf16) reinterpret_cast<u16*>(out)[(size_t)row * H + col] = to_bf16(y);
             else reinterpret_cast<float*>(out)[(size_t)row * H + col] = y;
           }
@@ -314,21 +315,33 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
 }
 
 template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
-void launch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, const void* Wl,
+void launch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
                    const float* bias, void* out, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  hipLaunchKernelGGL((update_kernel<kBf16, BM, BN, BK, WM, WN>), dim3(a.n_cu * 2), dim3(NT), 0, s, A0, A1, A2, d, Wl,
-                     bias, out, a.H, a.node_off, a.n_cand, a.status);
+  hipLaunchKernelGGL((update_kernel<kBf16, BM, BN, BK, WM, WN>), dim3(a.n_cu * 2), dim3(NT), 0, s, A0, A1, A2, d, nseg,
+                     Wl, bias, out, a.H, a.node_off, a.n_cand, a.status);
 }
 
 template <bool kBf16, int BK>
-void dispatch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, const void* Wl,
+void dispatch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
                      const float* bias, void* out, hipStream_t s) {
   const int H = a.H;
-  if (H % 256 == 0) launch_update<kBf16, 128, 256, BK, 64, 64>(a, A0, A1, A2, d, Wl, bias, out, s);
-  else if (H % 128 == 0) launch_update<kBf16, 128, 128, BK, 32, 64>(a, A0, A1, A2, d, Wl, bias, out, s);
-  else if (H % 64 == 0) launch_update<kBf16, 128, 64, BK, 32, 32>(a, A0, A1, A2, d, Wl, bias, out, s);
-  else launch_update<kBf16, 128, 32, BK, 32, 32>(a, A0, A1, A2, d, Wl, bias, out, s);
+  if (H % 256 == 0) launch_update<kBf16, 128, 256, BK, 64, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+  else if (H % 128 == 0) launch_update<kBf16, 128, 128, BK, 32, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+  else if (H % 64 == 0) launch_update<kBf16, 128, 64, BK, 32, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+  else launch_update<kBf16, 128, 32, BK, 32, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+}
+
+// [A0 | A1 | A2] W (nseg = 3) or A0 W (nseg = 1) with the chunk width the input width allows
+void run_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
+                const float* bias, void* out, hipStream_t s) {
+  if (a.bf16) {
+    if (d % 64 == 0) dispatch_update<true, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+    else dispatch_update<true, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+  } else {
+    if (d % 32 == 0) dispatch_update<false, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+    else dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+  }
 }
 
 }  // namespace
@@ -337,9 +350,9 @@ bool gnn_shape_supported(int F, int H, int L) {
   return F > 0 && H > 0 && L > 0 && F % 16 == 0 && H % 32 == 0 && H <= 512 && F <= 512;
 }
 
-size_t packed_weight_elems(int F, int H, int L) {
+size_t packed_weight_elems(int F, int H, int L, int nseg) {
   size_t n = 0;
-  for (int l = 0; l < L; ++l) n += (size_t)3 * (l == 0 ? F : H) * H;
+  for (int l = 0; l < L; ++l) n += (size_t)nseg * (l == 0 ? F : H) * H;
   return n;
 }
 
@@ -351,15 +364,15 @@ static unsigned short host_f2bf(float x) {
   return (unsigned short)(u >> 16);
 }
 
-void pack_weights_host(const float* W_layers, int F, int H, int L, int bf16, void* dst) {
+void pack_weights_host(const float* W_layers, int F, int H, int L, int nseg, int bf16, void* dst) {
   if (!bf16) {
-    memcpy(dst, W_layers, packed_weight_elems(F, H, L) * sizeof(float));
+    memcpy(dst, W_layers, packed_weight_elems(F, H, L, nseg) * sizeof(float));
     return;
   }
   unsigned short* o = static_cast<unsigned short*>(dst);
   const float* w = W_layers;
   for (int l = 0; l < L; ++l) {
-    const int K = 3 * (l == 0 ? F : H);
+    const int K = nseg * (l == 0 ? F : H);
     for (int k = 0; k < K; ++k)
       for (int n = 0; n < H; ++n) o[((size_t)(k / 8) * H + n) * 8 + (k % 8)] = host_f2bf(w[(size_t)k * H + n]);
     o += (size_t)K * H;
@@ -367,8 +380,43 @@ void pack_weights_host(const float* W_layers, int F, int H, int L, int bf16, voi
   }
 }
 
-hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
-  if (a.n_cand <= 0) return hipSuccess;
+namespace {
+
+// Layers with attention coefficients: z = h W (dense), the two score terms per node and
+// head, then the softmax-weighted sum over N_i with bias and ReLU.
+hipError_t attention_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const void** h_last) {
+  const void* hcur = a.Xc;
+  int d = a.F;
+  const size_t esz = a.bf16 ? 2 : 4;
+  const char* Wl = static_cast<const char*>(a.W);
+  const float* bl = a.b;
+  const float* al = a.att;
+  void* z = a.agg[0];
+  for (int l = 0; l < a.L; ++l) {
+    void* hnext = a.act[l & 1];
+    if (prof) prof->begin(kFamAttProject, s);
+    run_update(a, hcur, nullptr, nullptr, d, 1, Wl, nullptr, z, s);
+    if (prof) prof->end(s);
+    if (prof) prof->begin(kFamAttScores, s);
+    hipError_t e = launch_attention_scores(a, z, al, s);
+    if (prof) prof->end(s);
+    if (e != hipSuccess) return e;
+    if (prof) prof->begin(kFamAttAggregate, s);
+    e = launch_attention_aggregate(a, z, bl, hnext, s);
+    if (prof) prof->end(s);
+    if (e != hipSuccess) return e;
+    Wl += (size_t)d * a.H * esz;
+    bl += a.H;
+    al += 2 * a.H;
+    hcur = hnext;
+    d = a.H;
+  }
+  *h_last = hcur;
+  return hipGetLastError();
+}
+
+// Layers with uniform coefficients: mean over predecessors, mean over successors, dense update.
+hipError_t mean_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const void** h_last) {
   const void* hcur = a.Xc;
   int d = a.F;
   const size_t esz = a.bf16 ? 2 : 4;
@@ -402,13 +450,7 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
                            a.out_rowptr, a.out_col, a.agg[0], a.agg[1], a.node_off, a.n_cand, a.status);
       if (prof) prof->end(s);
       if (prof) prof->begin(kFamUpdate, s);
-      if (a.bf16) {
-        if (d % 64 == 0) dispatch_update<true, 64>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
-        else dispatch_update<true, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
-      } else {
-        if (d % 32 == 0) dispatch_update<false, 32>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
-        else dispatch_update<false, 16>(a, hcur, a.agg[0], a.agg[1], d, Wl, bl, hnext, s);
-      }
+      run_update(a, hcur, a.agg[0], a.agg[1], d, 3, Wl, bl, hnext, s);
       if (prof) prof->end(s);
     }
     Wl += (size_t)3 * d * a.H * esz;
@@ -416,6 +458,17 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
     hcur = hnext;
     d = a.H;
   }
+  *h_last = hcur;
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
+  if (a.n_cand <= 0) return hipSuccess;
+  const void* hcur = nullptr;
+  hipError_t e = a.heads > 0 ? attention_layers(a, prof, s, &hcur) : mean_layers(a, prof, s, &hcur);
+  if (e != hipSuccess) return e;
   if (prof) prof->begin(kFamReadout, s);
   if (a.bf16)
     hipLaunchKernelGGL(readout_head_kernel<true>, dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,

@@ -622,6 +622,13 @@ def random_labels(seed: int, n: int, n_groups: int, C: int = 1) -> np.ndarray:
     return out
 
 
+def with_attention(w: Workload, heads: int, seed: int = 0, std: Optional[float] = None) -> Workload:
+    """The same graphs and candidates evaluated by the attention variant of the estimator."""
+    m = ModelSpec(w.model.F, w.model.H, w.model.L, w.model.dtype, "attention", heads)
+    return Workload(w.name + "-attention", m, w.graphs, w.cand_graph, w.cand_off, w.group_id,
+                    make_weights(m, seed, std), w.note)
+
+
 def custom(name: str, model: ModelSpec, graphs: List[BaseGraph], labels_per_graph: List[np.ndarray],
            weights: Optional[Weights] = None, seed: int = 0, std: Optional[float] = None) -> Workload:
     return _pack(name, model, graphs, labels_per_graph, weights or make_weights(model, seed, std))
