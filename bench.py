@@ -32,6 +32,19 @@ def algorithmic_work(w, ntot, etot):
     C = w.n_cand
     base = sum(4 * (g.n + 1) + 4 * g.e + 4 * g.n * m.F for g in w.graphs)       # read once per batch
     contract = 4 * nb + 4 * nb + ntot * m.F * s + 2 * 4 * (ntot + C + etot) + base
+    if getattr(m, "agg", "mean") == "attention":
+        # per layer: z = h W (dense), score terms from z, weighted sums over N_i (z read once, h' written)
+        pf = pb = sb = ab = 0
+        d = m.F
+        for _ in range(m.L):
+            pf += 2 * ntot * d * m.H
+            pb += ntot * (d + m.H) * s + d * m.H * s
+            sb += ntot * m.H * s + 2 * 4 * ntot * m.heads
+            ab += 2 * ntot * m.H * s + 2 * 4 * (ntot + etot) + 4 * ntot * m.heads
+            d = m.H
+        return {"contract": {"bytes": contract}, "attention_project": {"flops": pf, "bytes": pb},
+                "attention_scores": {"bytes": sb}, "attention_aggregate": {"bytes": ab},
+                "readout_head": {"bytes": ntot * m.H * s}}
     agg_b, upd_f, upd_b = 0, 0, 0
     fus = {"fused_layer": [0, 0], "layer256": [0, 0], "layer256_d64": [0, 0]}
     d = m.F
@@ -93,6 +106,9 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--n-cand", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--aggregator", default="mean", choices=["mean", "attention"],
+                    help="mean: in/out mean aggregation (the headline path); attention: K-head attention coefficients")
+    ap.add_argument("--heads", type=int, default=4)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
                          "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -117,6 +133,8 @@ def main():
     from paper_2209_12769_amd import workloads as wl
 
     w = wl.make(args.workload, args.n_cand)
+    if args.aggregator == "attention":
+        w = wl.with_attention(w, args.heads)
     ev = B.evaluator_for(w)
     cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
     pred = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
@@ -142,6 +160,8 @@ def main():
     for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
                       ("fused_layer", "fused_layer"), ("layer256", "layer256"), ("layer256_d64", "layer256_d64"),
                       ("aggregate_heavy", "aggregate_heavy"), ("build_desc", "build_desc"),
+                      ("attention_project", "attention_project"), ("attention_scores", "attention_scores"),
+                      ("attention_aggregate", "attention_aggregate"),
                       ("readout_head", "readout_head")):
         ms_total, launches = fam[key]
         if launches == 0:
@@ -154,7 +174,7 @@ def main():
                 k["TFLOP/s"] = round(work[name]["flops"] / (per_step_ms * 1e-3) / 1e12, 2)
         kernels[name] = k
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-    if dom in ("update", "fused_layer", "layer256", "layer256_d64"):
+    if dom in ("update", "fused_layer", "layer256", "layer256_d64", "attention_project"):
         peak = PEAK_MFMA_TFLOPS[w.model.dtype]
         ach = kernels[dom].get("TFLOP/s", 0.0)
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
@@ -176,7 +196,8 @@ def main():
         "dtype": w.model.dtype, "data": "synthetic",
         "config": {"workload": w.name, "candidates": w.n_cand, "base_graphs": len(w.graphs),
                    "base_nodes": int(np.mean([g.n for g in w.graphs])), "contracted_nodes": ntot,
-                   "contracted_edges": etot, "F": w.model.F, "H": w.model.H, "L": w.model.L},
+                   "contracted_edges": etot, "F": w.model.F, "H": w.model.H, "L": w.model.L,
+                   "aggregator": args.aggregator, **({"heads": args.heads} if args.aggregator == "attention" else {})},
         "roofline": roof,
         "kernels": kernels,
     }

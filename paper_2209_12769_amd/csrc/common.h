@@ -136,6 +136,7 @@ bool layer256_supported(int d, int H, int bf16);
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s);
+hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, void* out, hipStream_t s);
 
 __global__ void reset_status_kernel(int* status);
 

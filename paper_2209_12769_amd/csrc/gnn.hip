@@ -395,7 +395,12 @@ hipError_t attention_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, con
   for (int l = 0; l < a.L; ++l) {
     void* hnext = a.act[l & 1];
     if (prof) prof->begin(kFamAttProject, s);
-    run_update(a, hcur, nullptr, nullptr, d, 1, Wl, nullptr, z, s);
+    if (a.allow_fused && layer256_supported(d, a.H, a.bf16)) {
+      hipError_t e = launch_dense256(hcur, d, a, Wl, z, s);
+      if (e != hipSuccess) return e;
+    } else {
+      run_update(a, hcur, nullptr, nullptr, d, 1, Wl, nullptr, z, s);
+    }
     if (prof) prof->end(s);
     if (prof) prof->begin(kFamAttScores, s);
     hipError_t e = launch_attention_scores(a, z, al, s);

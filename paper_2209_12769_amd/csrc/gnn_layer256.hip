@@ -38,11 +38,13 @@ constexpr int kU = 3;                       // neighbours gathered in-kernel per
 // (RQ = 1) and filed, two steps later, into a per-tile table, in time for its first use.
 // With DCH = 1 a direction is a single job: that job's four descriptors are requested
 // together (RQ = 4) and used directly when its rows are requested (DIRECT).
-template <int DCH>
+// DENSE: the plain product h W (K = D, every chunk the node's own row, no bias, no ReLU),
+// used for z = W e' of the attention variant; the data-moving waves then only keep step.
+template <int DCH, bool DENSE = false>
 struct Shape {
   static_assert(DCH == 4 || DCH == 1, "input widths 256 and 64");
   static constexpr int D = 64 * DCH;
-  static constexpr int NK = 3 * DCH;
+  static constexpr int NK = DENSE ? DCH : 3 * DCH;
   static constexpr bool DIRECT = DCH == 1;
   static constexpr int RQ = DIRECT ? 4 : 1;
   static constexpr unsigned ROWB = D * 2;     // bytes per row of h
@@ -326,9 +328,9 @@ struct MfmaConst {
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
 
-template <int DCH>
+template <int DCH, bool DENSE>
 __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
-  constexpr int NK = Shape<DCH>::NK;
+  constexpr int NK = Shape<DCH, DENSE>::NK;
   int n_req = 0;                            // requests of this step, in fours
   if (s + 2 >= 0) {
     const int J = s + 2;
@@ -352,13 +354,13 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
     }
     // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run; each wave moves
     // eight 1 KB pieces of it (chunk index clamped at the end: the count of loads is fixed).
-    // With three chunks in all (DCH = 1) chunk k always lands in ring slot k: the ring then
+    // With at most three chunks in all chunk k always lands in ring slot k: the ring then
     // holds the whole of W and only the first tile loads it.
     if (NK > 3 || J < NK) {
       n_req += 2;
       const int jn = min(J, S - 1);
       const char* wsrc = reinterpret_cast<const char*>(c.Wp) + (size_t)(jn % NK) * kBBytes;
-      const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
+      const unsigned ring = c.lds0 + kBOff + (unsigned)(NK > 3 ? J % 3 : kc) * kBBytes;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int piece = c.wave * 8 + i;   // c.wave is wave-uniform by construction (readfirstlane)
@@ -368,7 +370,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   }
   if (s >= 0) {
     const char* As = c.smem + (s % 3) * kABytes;
-    const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (s % 3) * kBBytes);
+    const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (NK > 3 ? s % 3 : s % NK) * kBBytes);
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       bf16x8 a[2], b[4];
@@ -400,6 +402,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
     // for a store to be acknowledged.
     const int ti = s / NK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
+    if (!DENSE) {
     float4 bq[4];
     {
       int cb = c.wn * 128 + 4 * c.lh;
@@ -434,6 +437,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(acc[i][j]));
+    }
     // ---- then bf16, wave-local staging, 16-byte row-contiguous stores
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -470,13 +474,13 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   }
 }
 
-template <int DCH>
+template <int DCH, bool DENSE>
 __global__ __launch_bounds__(kNT) void layer256_kernel(
     const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
     const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
     const float* __restrict__ bias, u16* __restrict__ out, const int* __restrict__ node_off, int C,
     const int* __restrict__ status) {
-  constexpr int NK = Shape<DCH>::NK, RQ = Shape<DCH>::RQ;
+  constexpr int NK = Shape<DCH, DENSE>::NK, RQ = Shape<DCH>::RQ;
   if (status[0] != 0) return;
   char* smem = dc_l256_smem;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -487,7 +491,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
   const int tpx = (ntiles + 7) >> 3;
   const int lim = min(tpx, ntiles - xcd * tpx);
   const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
-  const int S = nt_wg * NK;                 // steps of this workgroup (a multiple of 3)
+  const int S = nt_wg * NK;                 // steps of this workgroup (a multiple of 3 unless DENSE)
 
   if (S == 0) return;                       // no tile for this workgroup (uniform)
   // Both kinds of wave run S + 3 steps (s = -3 .. S-1) with one barrier per step.  Waves are
@@ -522,9 +526,11 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.wave = __builtin_amdgcn_readfirstlane(role_wave);   // scalar: the LDS base of a DMA load must be uniform
     __syncthreads();                          // step -3: only the data-moving waves work
     for (int s = -2; s < S; ++s) {
-      mfma_step<DCH>(s, S, acc, mc);
+      mfma_step<DCH, DENSE>(s, S, acc, mc);
       __syncthreads();
     }
+  } else if (DENSE) {
+    for (int s = -3; s < S; ++s) __syncthreads();            // nothing to gather: keep step with the barriers
   } else {
     // =========================== data-moving waves ====================================
     const int lt = role_wave * 64 + lane;
@@ -720,7 +726,7 @@ template <int DCH>
 hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out, Profiler* prof,
                         hipStream_t s) {
   static bool attr_done = false;
-  auto kern = layer256_kernel<DCH>;
+  auto kern = layer256_kernel<DCH, false>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -744,6 +750,34 @@ hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const f
 }
 
 }  // namespace
+
+namespace {
+
+template <int DCH>
+hipError_t launch_dense_shape(const void* h, const GnnArgs& a, const void* Wl, void* out, hipStream_t s) {
+  static bool attr_done = false;
+  auto kern = layer256_kernel<DCH, true>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int grid = ((a.n_cu + 7) / 8) * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, static_cast<const u16*>(h), nullptr, nullptr, nullptr,
+                     nullptr, static_cast<const u16*>(Wl), nullptr, static_cast<u16*>(out), a.node_off, a.n_cand,
+                     a.status);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// out = h W for H = 256, d = 256 or 64, bf16 (no bias, no activation)
+hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, void* out, hipStream_t s) {
+  if (d == 256) return launch_dense_shape<4>(h, a, Wl, out, s);
+  if (d == 64) return launch_dense_shape<1>(h, a, Wl, out, s);
+  return hipErrorInvalidValue;
+}
 
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s) {
