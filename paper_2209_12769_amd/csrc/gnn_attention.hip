@@ -87,9 +87,10 @@ __global__ __launch_bounds__(256) void attention_scores_kernel(const void* __res
 // the list (i, predecessors, successors) once, keeping a running maximum of the scores and
 // rescaling the partial sums when it grows (the usual single-pass softmax), fp32 throughout.
 // The group's lanes fetch up to LPR neighbour ids in one load and hand them round; rows and
-// score terms of four neighbours are in flight at a time.
+// score terms of four neighbours are in flight at a time.  Held to 64 registers so that eight
+// waves share a SIMD: the walk is a chain of dependent loads and only occupancy hides it.
 template <bool kBf16>
-__global__ __launch_bounds__(256) void attention_aggregate_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) void attention_aggregate_kernel(
     const void* __restrict__ z, int H, int K, const float* __restrict__ sc_src, const float* __restrict__ sc_dst,
     const float* __restrict__ bias, const int* __restrict__ in_rp, const int* __restrict__ in_ci,
     const int* __restrict__ out_rp, const int* __restrict__ out_ci, void* __restrict__ out,
@@ -99,14 +100,15 @@ __global__ __launch_bounds__(256) void attention_aggregate_kernel(
   const int LPR = H >> 3, LPH = LPR / K;
   const int lane = threadIdx.x & 63, sg = lane / LPR, ll = lane - sg * LPR, hb = sg * LPR;
   const int head = ll / LPH;
-  const int rows_per_wave = 64 / LPR;
-  const long long wave0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
-  float bq[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) bq[i] = bias[ll * 8 + i];
-  for (long long r0 = wave0 * rows_per_wave; r0 < ntot; r0 += nwaves * rows_per_wave) {
-    const long long v = r0 + sg;
+  const int rows_per_wave = 64 / LPR, rows_per_wg = rows_per_wave * (blockDim.x >> 6);
+  // Workgroups are dealt round-robin to the eight XCDs, each with its own L2: every XCD takes
+  // one contiguous eighth of the rows, so that the neighbours of its rows (a graph is a few
+  // hundred KB of z) are fetched into one L2 only.  The grid is a multiple of 8 workgroups.
+  const long long n_chunks = (ntot + rows_per_wg - 1) / rows_per_wg;
+  const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3, per_x = gridDim.x >> 3;
+  const long long c_begin = n_chunks * xcd / 8, c_end = n_chunks * (xcd + 1) / 8;
+  for (long long chunk = c_begin + jx; chunk < c_end; chunk += per_x) {
+    const long long v = chunk * rows_per_wg + (threadIdx.x >> 6) * rows_per_wave + sg;
     if (v >= ntot) continue;                     // whole lane groups drop out together
     const int is = in_rp[v], din = in_rp[v + 1] - is;
     const int os = out_rp[v], dout = out_rp[v + 1] - os;
@@ -148,8 +150,18 @@ __global__ __launch_bounds__(256) void attention_aggregate_kernel(
     }
     const float inv = 1.0f / den;                 // N_i holds at least i itself
     float y[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) y[i] = fmaxf(acc[i] * inv + bq[i], 0.f);
+    {
+      const float4 b0 = *reinterpret_cast<const float4*>(bias + ll * 8);        // read here, not kept across
+      const float4 b1 = *reinterpret_cast<const float4*>(bias + ll * 8 + 4);    // the walk: registers are scarce
+      y[0] = fmaxf(acc[0] * inv + b0.x, 0.f);
+      y[1] = fmaxf(acc[1] * inv + b0.y, 0.f);
+      y[2] = fmaxf(acc[2] * inv + b0.z, 0.f);
+      y[3] = fmaxf(acc[3] * inv + b0.w, 0.f);
+      y[4] = fmaxf(acc[4] * inv + b1.x, 0.f);
+      y[5] = fmaxf(acc[5] * inv + b1.y, 0.f);
+      y[6] = fmaxf(acc[6] * inv + b1.z, 0.f);
+      y[7] = fmaxf(acc[7] * inv + b1.w, 0.f);
+    }
     if constexpr (kBf16) {
       v4u o;
       o.x = pack_bf16x2(y[0], y[1]);
@@ -185,7 +197,7 @@ hipError_t launch_attention_scores(const GnnArgs& a, const void* z, const float*
 }
 
 hipError_t launch_attention_aggregate(const GnnArgs& a, const void* z, const float* bias, void* out, hipStream_t s) {
-  const dim3 grid(a.n_cu * 8), block(256);
+  const dim3 grid(a.n_cu * 8), block(256);      // 8 waves per SIMD: every workgroup resident from the start
   if (a.bf16)
     hipLaunchKernelGGL(attention_aggregate_kernel<true>, grid, block, 0, s, z, a.H, a.heads, a.score[0], a.score[1],
                        bias, a.in_rowptr, a.in_col, a.out_rowptr, a.out_col, out, a.node_off, a.n_cand, a.status);
