@@ -390,3 +390,38 @@ def test_fused_layer_matches_the_separate_kernels_bit_for_bit(B, monkeypatch):
         ev2.close()
         monkeypatch.delenv("DC_DISABLE_FUSED")
         assert np.array_equal(fused, plain), (name, np.abs(fused - plain).max())
+
+
+def test_eval_is_capturable_in_a_hip_graph_and_replays_identically(B):
+    """dc_eval_candidates enqueues kernels on the caller's stream only (no host round trip, no
+    allocation, no memset), so a caller may capture it; every replay, with eager work and
+    synchronisation in between, must reproduce the eager result bit for bit."""
+    import torch
+    w = wl.make("cfg2", 32)
+    ev = B.evaluator_for(w)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    pred = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
+    eager = ev.eval_candidates(cg, co, gid, pred).clone()
+    torch.cuda.synchronize()
+    assert ev.check() == B.DC_OK
+    side = torch.cuda.Stream(device=ev.device)
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        ev.eval_candidates(cg, co, gid, pred)             # warm-up on the capture stream
+        torch.cuda.current_stream().synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ev.eval_candidates(cg, co, gid, pred)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        pred.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(pred, eager), f"replay {rep}"
+        # eager work of the same context between replays
+        again = ev.eval_candidates(cg, co, gid).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager)
+    assert ev.check() == B.DC_OK
+    ev.close()
