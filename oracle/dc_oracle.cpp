@@ -36,6 +36,20 @@
 //    (i, predecessors ascending, successors ascending); a node that is both a
 //    predecessor and a successor counts twice.
 //
+//  * End-to-end time of a candidate module by list scheduling (orc_simulate, Sec. 3.4):
+//    computation ops run one at a time on one device in the order of a FIFO ready queue
+//    (an op enters the tail when its last dependency clears; it starts when the device is
+//    free and its predecessors are done); all-reduce instructions run one at a time on a
+//    communication channel, in the order in which their tensors are produced, each
+//    starting when its tensor is produced (all its predecessors done) and the channel is
+//    clear, for T = C x + D (Sec. 3.1, Profiler) with x the tensor size; they overlap with
+//    computation.  The result is the later of the two ends.  Choices of this build where
+//    the text is silent: the queue starts with the source ops in ascending index; an
+//    all-reduce is put on the channel the moment its last predecessor is processed (before
+//    the next op is taken from the queue), ties in ascending index; successors of a node
+//    are released in ascending index; a module whose graph has a cycle (an invalid fusion)
+//    costs +infinity.  All arithmetic in fp64.
+//
 // Numerics: values are stored as fp32, every sum and dot product is
 // accumulated in fp64 and rounded once.  With bf16 != 0 the storage points
 // that the bf16 device path rounds (contracted features, all activations,
@@ -53,6 +67,10 @@
 // a dense masked-softmax float64 formulation on small graphs, a single-node graph,
 // invariance to a shift of all scores of a node, and one hand-worked example;
 // that gamma has this form in the paper's own code: parity unpinned.
+// Simulator: a chain (sum of times), ops only (sum of times whatever the graph), one
+// all-reduce behind a chain, two buckets that queue on the channel, overlap of
+// communication with computation, the ring closed form for C, a brute-force event
+// simulation on random DAGs, cyclic graphs, and one hand-worked example.
 #include <cstdint>
 #include <cstring>
 #include <cmath>
@@ -390,5 +408,54 @@ void orc_gnn_forward_attn(int n_cand, const int32_t* node_off,
   if (h_last) std::memcpy(h_last, h.data(), static_cast<size_t>(Ntot) * H * sizeof(float));
   readout_and_head(n_cand, node_off, h.data(), H, bf16, head, pred, readout);
 }
+
+// List-scheduling estimate of the per-iteration time of each candidate module (see the
+// header).  op_time[v]: execution time of computation node v; ar_size[v]: tensor size of
+// all-reduce node v, negative for computation nodes.  cost[c] = +inf if graph c has a cycle.
+void orc_simulate(int n_cand, const int32_t* node_off,
+                  const int32_t* out_rowptr, const int32_t* out_col,
+                  const int32_t* in_rowptr, const int32_t* /*in_col*/,
+                  const float* op_time, const float* ar_size, float ar_c, float ar_d, float* cost) {
+  std::vector<int> indeg;
+  std::vector<double> ready;
+  std::vector<int64_t> q, aq;
+  for (int c = 0; c < n_cand; ++c) {
+    const int64_t n0 = node_off[c], n1 = node_off[c + 1], G = n1 - n0;
+    indeg.assign(G, 0);
+    ready.assign(G, 0.0);
+    q.clear();
+    aq.clear();
+    for (int64_t v = 0; v < G; ++v) {
+      indeg[v] = in_rowptr[n0 + v + 1] - in_rowptr[n0 + v];
+      if (indeg[v] == 0) (ar_size[n0 + v] >= 0.0f ? aq : q).push_back(v);
+    }
+    size_t qh = 0, ah = 0;
+    int64_t processed = 0;
+    double dev = 0.0, chan = 0.0;
+    while (ah < aq.size() || qh < q.size()) {
+      int64_t u;
+      double done;
+      if (ah < aq.size()) {               // tensors already produced go on the channel first
+        u = aq[ah++];
+        const double start = ready[u] > chan ? ready[u] : chan;
+        done = start + (static_cast<double>(ar_c) * static_cast<double>(ar_size[n0 + u]) + static_cast<double>(ar_d));
+        chan = done;
+      } else {
+        u = q[qh++];
+        const double start = ready[u] > dev ? ready[u] : dev;
+        done = start + static_cast<double>(op_time[n0 + u]);
+        dev = done;
+      }
+      ++processed;
+      for (int e = out_rowptr[n0 + u]; e < out_rowptr[n0 + u + 1]; ++e) {
+        const int64_t w = out_col[e] - n0;
+        if (done > ready[w]) ready[w] = done;
+        if (--indeg[w] == 0) (ar_size[n0 + w] >= 0.0f ? aq : q).push_back(w);
+      }
+    }
+    cost[c] = processed == G ? static_cast<float>(dev > chan ? dev : chan) : INFINITY;
+  }
+}
+
 
 }  // extern "C"

@@ -35,6 +35,7 @@ def _load():
         _lib = C.CDLL(_SO)
         _lib.orc_contract_batch.restype = C.c_int
         _lib.orc_gnn_forward.restype = None
+        _lib.orc_simulate.restype = None
         _lib.orc_round_bf16.restype = None
     return _lib
 
@@ -134,6 +135,18 @@ def gnn_forward(b: Batch, model, weights, bf16: Optional[bool] = None, want_hidd
     if want_hidden:
         return pred, h_last[:b.ntot], ro[:b.n_cand]
     return pred
+
+
+def simulate(b: Batch, op_time: np.ndarray, ar_size: np.ndarray, ar_c: float, ar_d: float) -> np.ndarray:
+    """End-to-end time per candidate by list scheduling on one device plus a serial all-reduce
+    channel; +inf where the contracted graph has a cycle."""
+    lib = _load()
+    cost = np.zeros(b.n_cand, np.float32)
+    t = np.ascontiguousarray(op_time, dtype=np.float32)
+    x = np.ascontiguousarray(ar_size, dtype=np.float32)
+    lib.orc_simulate(C.c_int(b.n_cand), _p(b.node_off), _p(b.out_rowptr), _p(b.out_col), _p(b.in_rowptr),
+                     _p(b.in_col), _p(t), _p(x), C.c_float(ar_c), C.c_float(ar_d), _p(cost))
+    return cost
 
 
 def evaluate(w, bf16: Optional[bool] = None) -> np.ndarray:
