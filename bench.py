@@ -98,6 +98,52 @@ def cpu_baseline(w, seconds_target=15.0):
             "sample": f"{n} of {w.n_cand} candidates of {w.name}, evenly spaced, contract+forward, {dt:.1f} s"}
 
 
+def simulate_bench(args, w, B, torch):
+    """Times dc_simulate alone: the batch is contracted once, then K simulator passes."""
+    ev = B.evaluator_for(w)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    nb = int(w.cand_off[-1])
+    geo = w.g_edge_off()
+    eb = int(sum(int(geo[b + 1] - geo[b]) for b in w.cand_graph))
+    batch = ev.alloc_batch(w.n_cand, nb, nb, eb)
+    ev.contract_graphs(cg, co, gid, batch)
+    ntot, etot = ev.last_totals()
+    Xc = batch.Xc[:ntot].float()
+    is_ar = Xc[:, 1] > 0
+    ar_size = torch.where(is_ar, Xc[:, 0], torch.full_like(Xc[:, 0], -1.0)).contiguous()
+    op_time = torch.where(is_ar, torch.zeros_like(Xc[:, 2]), 0.05 + Xc[:, 2]).contiguous()
+    cost = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
+    for _ in range(args.warmup):
+        ev.simulate(batch, op_time, ar_size, 0.02, 0.01, cost)
+    torch.cuda.synchronize()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev.simulate(batch, op_time, ar_size, 0.02, 0.01, cost)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out = {"metric": "fusion candidates simulated/sec (list scheduling + all-reduce channel) on 1 MI355X",
+           "value": round(w.n_cand * args.steps / dt, 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": w.name, "candidates": w.n_cand, "contracted_nodes": ntot, "contracted_edges": etot,
+                      "finite": int(torch.isfinite(cost).sum().item())}}
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        n = min(w.n_cand, 256)
+        sub = w.subset(np.linspace(0, w.n_cand - 1, n).astype(np.int64))
+        ref = orc.contract(sub, False)
+        ar = np.where(ref.Xc[:, 1] > 0, ref.Xc[:, 0], -1.0).astype(np.float32)
+        tt = np.where(ref.Xc[:, 1] > 0, 0.0, 0.05 + ref.Xc[:, 2]).astype(np.float32)
+        t0 = time.perf_counter()
+        orc.simulate(ref, tt, ar, 0.02, 0.01)
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n / cdt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{n} of {w.n_cand} candidates, simulator only, {cdt:.2f} s"}
+    ev.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +155,9 @@ def main():
     ap.add_argument("--aggregator", default="mean", choices=["mean", "attention"],
                     help="mean: in/out mean aggregation (the headline path); attention: K-head attention coefficients")
     ap.add_argument("--heads", type=int, default=4)
+    ap.add_argument("--simulate", action="store_true",
+                    help="instead of the estimator, time the list-scheduling simulator (dc_simulate) on the "
+                         "contracted batch; per-node times and tensor sizes are synthetic (from the features)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
                          "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -133,6 +182,9 @@ def main():
     from paper_2209_12769_amd import workloads as wl
 
     w = wl.make(args.workload, args.n_cand)
+    if args.simulate:
+        simulate_bench(args, w, B, torch)
+        return
     if args.aggregator == "attention":
         w = wl.with_attention(w, args.heads)
     ev = B.evaluator_for(w)

@@ -181,6 +181,28 @@ dc_status dc_contract_graphs(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
  * pred dev [n_cand] fp32: predicted per-iteration time per candidate.            */
 dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* stream);
 
+/* End-to-end time of each candidate module by list scheduling (Sec. 3.4): computation nodes
+ * run one at a time on one device in FIFO order of a ready queue (a node enters the tail when
+ * its last dependency clears and starts when the device is free and its predecessors are
+ * done); all-reduce nodes run one at a time on a communication channel in the order in
+ * which their tensors are produced, each for T = ar_c * size + ar_d (Sec. 3.1, Profiler),
+ * overlapping with computation; the result is the later of the two ends.  Where the text is
+ * silent: the queue starts with the source nodes in ascending index; an all-reduce goes on
+ * the channel the moment its last predecessor is processed, before the next node is taken,
+ * ties in ascending index; successors are released in ascending index.
+ *   in        a batch as produced by dc_contract_graphs (validated on the device as for
+ *             dc_gnn_forward; Xc and new_id are not read)
+ *   op_time   dev [node_off[n_cand]] fp32: execution time of each computation node (profiled,
+ *             or predicted by an estimator for fused ops); ignored for all-reduce nodes
+ *   ar_size   dev [node_off[n_cand]] fp32: tensor size of each all-reduce node; negative marks
+ *             a computation node
+ *   cost      dev [n_cand] fp32; +infinity for a module whose graph has a cycle (an invalid
+ *             fusion).  Times are accumulated in fp64 in the order the rules fix.
+ * Needs dc_set_base_graphs (their sizes bound the scratch); no weights.  A graph larger than
+ * every base graph of the context is reported by dc_check as DC_ERR_CAPACITY.            */
+dc_status dc_simulate(dc_ctx* ctx, const dc_batch* in, const float* op_time, const float* ar_size, float ar_c,
+                      float ar_d, float* cost, void* stream);
+
 /* dc_contract_graphs into context-owned buffers followed by dc_gnn_forward. */
 dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
                              const int32_t* group_id, float* pred, void* stream);

@@ -74,6 +74,7 @@ def lib():
         L.dc_contract_graphs.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp]
         L.dc_gnn_forward.argtypes = [vp, C.POINTER(DcBatch), vp, vp]
         L.dc_eval_candidates.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.dc_simulate.argtypes = [vp, C.POINTER(DcBatch), vp, vp, C.c_float, C.c_float, vp, vp]
         L.dc_check.argtypes = [vp, vp]
         L.dc_last_totals.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_last_error.argtypes = [vp]
@@ -81,7 +82,7 @@ def lib():
         L.dc_profile_begin.argtypes = [vp]
         L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
         for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
-                  "dc_gnn_forward", "dc_eval_candidates", "dc_check", "dc_last_totals", "dc_profile_begin",
+                  "dc_gnn_forward", "dc_eval_candidates", "dc_simulate", "dc_check", "dc_last_totals", "dc_profile_begin",
                   "dc_profile_end"):
             getattr(L, n).restype = i32
         _lib = L
@@ -128,6 +129,11 @@ def dc_gnn_forward(ctx, batch: DcBatch, pred_ptr, stream: int = 0) -> int:
 
 def dc_eval_candidates(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, pred_ptr, stream: int = 0) -> int:
     return lib().dc_eval_candidates(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, pred_ptr, stream)
+
+
+def dc_simulate(ctx, batch: DcBatch, op_time_ptr, ar_size_ptr, ar_c: float, ar_d: float, cost_ptr,
+                stream: int = 0) -> int:
+    return lib().dc_simulate(ctx, C.byref(batch), op_time_ptr, ar_size_ptr, ar_c, ar_d, cost_ptr, stream)
 
 
 def dc_check(ctx, stream: int = 0) -> int:
@@ -257,6 +263,13 @@ class Evaluator:
             pred = self.torch.empty(max(batch.c.n_cand, 1), dtype=self.torch.float32, device=self.device)
         self._ok(dc_gnn_forward(self.ctx, batch.c, pred.data_ptr(), self._stream()), "dc_gnn_forward")
         return pred[:batch.c.n_cand]
+
+    def simulate(self, batch: DeviceBatch, op_time, ar_size, ar_c: float, ar_d: float, cost=None):
+        if cost is None:
+            cost = self.torch.empty(max(batch.c.n_cand, 1), dtype=self.torch.float32, device=self.device)
+        self._ok(dc_simulate(self.ctx, batch.c, op_time.data_ptr(), ar_size.data_ptr(), ar_c, ar_d,
+                             cost.data_ptr(), self._stream()), "dc_simulate")
+        return cost[:batch.c.n_cand]
 
     def eval_candidates(self, cand_graph, cand_off, group_id, pred=None):
         n_cand = int(cand_graph.numel())

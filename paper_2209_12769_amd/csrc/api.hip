@@ -59,6 +59,9 @@ struct dc_ctx {
   char* slab = nullptr;
   size_t slab_stride = 0;
   int slab_wgs = 0;
+  char* sim_scratch = nullptr;   // slices for modules the simulator cannot hold in LDS
+  size_t sim_stride = 0;
+  int sim_slices = 0;
   int allow_fused = 1;
   Profiler prof;
   std::string err;
@@ -69,9 +72,11 @@ namespace {
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
                                              "fused_layer", "layer256", "layer256_d64", "aggregate_heavy", "build_desc",
                                              "attention_project", "attention_scores", "attention_aggregate",
-                                             "readout_head"};
+                                             "readout_head", "simulate"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+constexpr int kSimLdsBytes = 80 * 1024;   // two simulator waves per CU
 
 struct Arena {
   size_t off = 0;
@@ -385,6 +390,7 @@ dc_status dc_destroy(dc_ctx* ctx) {
   if (ctx->att) (void)hipFree(ctx->att);
   if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
   if (ctx->slab) (void)hipFree(ctx->slab);
+  if (ctx->sim_scratch) (void)hipFree(ctx->sim_scratch);
   delete ctx;
   return DC_OK;
 }
@@ -526,14 +532,29 @@ dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_nod
     slab_wgs = ctx->n_cu * 2;
     e = hipMalloc(reinterpret_cast<void**>(&slab), slab_stride * slab_wgs);
   }
+  // the simulator keeps a module in LDS if it fits kSimLdsBytes; a contracted graph is never
+  // larger than its base graph, so slices of the largest base graph serve all the others
+  char* sim = nullptr;
+  size_t sim_stride = 0;
+  int sim_slices = 0;
+  if (e == hipSuccess && simulate_scratch_bytes(max_gn, max_ge, 1) > (size_t)kSimLdsBytes) {
+    sim_stride = al(simulate_scratch_bytes(max_gn, max_ge, 1));
+    sim_slices = ctx->n_cu * 4;
+    e = hipMalloc(reinterpret_cast<void**>(&sim), sim_stride * sim_slices);
+  }
   if (e != hipSuccess) {
     (void)hipGetLastError();
     (void)hipFree(mem);
+    if (slab) (void)hipFree(slab);
     return hip_fail(ctx, e, "dc_set_base_graphs copy");
   }
   (void)hipDeviceSynchronize();   // earlier calls may still read the old graphs
   if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
   if (ctx->slab) (void)hipFree(ctx->slab);
+  if (ctx->sim_scratch) (void)hipFree(ctx->sim_scratch);
+  ctx->sim_scratch = sim;
+  ctx->sim_stride = sim_stride;
+  ctx->sim_slices = sim_slices;
   ctx->bg_mem = mem;
   ctx->slab = slab;
   ctx->slab_stride = slab_stride;
@@ -612,6 +633,45 @@ dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* str
   v.cap_nodes = in->cap_nodes;
   v.cap_edges = in->cap_edges;
   return do_forward(ctx, in->n_cand, v, pred, s);
+}
+
+dc_status dc_simulate(dc_ctx* ctx, const dc_batch* in, const float* op_time, const float* ar_size, float ar_c,
+                      float ar_d, float* cost, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!in || in->n_cand < 0) return fail(ctx, DC_ERR_INVALID_ARG, "null batch or negative count");
+  if (!ctx->have_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_base_graphs has not been called");
+  if (in->n_cand > ctx->cfg.max_cand) return fail(ctx, DC_ERR_CAPACITY, "n_cand exceeds max_cand");
+  if (in->n_cand == 0) return DC_OK;
+  if (!cost || !op_time || !ar_size || !in->node_off || !in->out_rowptr || !in->out_col || !in->in_rowptr ||
+      !in->in_col)
+    return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  const Caps k = caps_of(ctx->cfg);
+  hipLaunchKernelGGL(check_batch_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, s, in->node_off, in->n_cand,
+                     (long long)(in->cap_nodes < k.NN ? in->cap_nodes : k.NN), (long long)in->cap_edges,
+                     in->out_rowptr, in->out_col, in->in_rowptr, in->in_col, ctx->status);
+  SimArgs a;
+  a.n_cand = in->n_cand;
+  a.node_off = in->node_off;
+  a.out_rowptr = in->out_rowptr;
+  a.out_col = in->out_col;
+  a.in_rowptr = in->in_rowptr;
+  a.op_time = op_time;
+  a.ar_size = ar_size;
+  a.ar_c = ar_c;
+  a.ar_d = ar_d;
+  a.cost = cost;
+  a.lds_bytes = kSimLdsBytes;
+  a.scratch = ctx->sim_scratch;
+  a.scratch_stride = ctx->sim_stride;
+  a.n_slices = ctx->sim_slices;
+  a.status = ctx->status;
+  if (ctx->prof.on) ctx->prof.begin(kFamSimulate, s);
+  hipError_t e = launch_simulate(a, s);
+  if (ctx->prof.on) ctx->prof.end(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "simulator launch");
+  return DC_OK;
 }
 
 dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,

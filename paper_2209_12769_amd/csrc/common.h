@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamSimulate, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -137,6 +137,26 @@ hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s);
 hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, void* out, hipStream_t s);
+
+// simulate.hip: list-scheduling estimate of the end-to-end time of each candidate module
+struct SimArgs {
+  int n_cand;
+  const int* node_off;
+  const int* out_rowptr;
+  const int* out_col;
+  const int* in_rowptr;
+  const float* op_time;     // [Ntot] execution time of computation nodes
+  const float* ar_size;     // [Ntot] tensor size of all-reduce nodes, negative for computation nodes
+  float ar_c, ar_d;         // T = ar_c * size + ar_d
+  float* cost;              // [n_cand]
+  int lds_bytes;            // LDS per wave for modules walked on chip
+  char* scratch;            // slices of global memory for the others
+  size_t scratch_stride;
+  int n_slices;
+  int* status;
+};
+size_t simulate_scratch_bytes(long long max_graph_nodes, long long max_graph_edges, int n_slices);
+hipError_t launch_simulate(const SimArgs& a, hipStream_t s);
 
 __global__ void reset_status_kernel(int* status);
 

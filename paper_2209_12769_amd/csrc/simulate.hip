@@ -1,0 +1,168 @@
+// End-to-end time of a candidate module by list scheduling (Sec. 3.4; gfx950).
+//
+// Computation ops run one at a time on one device in the order of a FIFO ready queue (an
+// op enters the tail when its last dependency clears; it starts when the device is free
+// and its predecessors are done).  All-reduce instructions run one at a time on a
+// communication channel, in the order in which their tensors are produced, each starting
+// when its tensor is produced and the channel is clear, for T = C x + D (Sec. 3.1,
+// Profiler); they overlap with computation.  The result is the later of the two ends.
+// Where the text is silent: the queue starts with the source ops in ascending index; an
+// all-reduce goes on the channel the moment its last predecessor is processed, before the
+// next op is taken, ties in ascending index; successors are released in ascending index;
+// a module whose graph has a cycle (an invalid fusion) costs +infinity.
+//
+// The walk over one module is a serial chain, so the batch supplies the parallelism: one
+// wave per candidate, with the whole module (successor lists, durations, dependency
+// counters, ready times, both queues) in LDS; the lanes release the successors of the
+// current node together (lists are duplicate free, so no two lanes touch one node) and
+// append the newly ready ones in lane order = ascending index.  Modules too large for LDS
+// keep the same arrays in a slice of global memory.  Times are fp64, added in the order
+// the rules fix, so the result does not depend on the implementation.
+#include <math.h>
+
+#include "common.h"
+
+namespace dc {
+namespace {
+
+constexpr int kAr = 1 << 30;    // flag in the dependency counter: the node is an all-reduce
+
+__host__ __device__ inline size_t sim_bytes(long long G, long long E) {
+  // ready[G] f64 | dur[G] f64 | dep[G] i32 | q[G] i32 | aq[G] i32 | rp[G+1] i32 | ci[E] u16 (padded to 8 bytes)
+  return (size_t)G * (8 + 8 + 4 + 4 + 4) + (size_t)(G + 1) * 4 + (((size_t)E * 2 + 7) & ~(size_t)7) + 8;
+}
+
+extern __shared__ __attribute__((aligned(16))) char dc_sim_smem[];
+
+template <bool kLds>
+__global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ node_off,
+                                                       const int* __restrict__ out_rp, const int* __restrict__ out_ci,
+                                                       const int* __restrict__ in_rp,
+                                                       const float* __restrict__ op_time,
+                                                       const float* __restrict__ ar_size, int C, float ar_c,
+                                                       float ar_d, float* __restrict__ cost, char* gscratch,
+                                                       size_t gstride, int lds_bytes, int* status) {
+  if (status[0] != 0) return;
+  const int lane = threadIdx.x;
+  for (int c = blockIdx.x; c < C; c += gridDim.x) {
+    const int n0 = node_off[c], G = node_off[c + 1] - n0;
+    const int e0 = out_rp[n0], E = out_rp[n0 + G] - e0;
+    const bool fits = sim_bytes(G, E) <= (size_t)lds_bytes;
+    if (fits != kLds) continue;
+    if (!kLds && sim_bytes(G, E) > gstride) {       // larger than any base graph of this context
+      if (lane == 0) {
+        set_error(status, (int)DC_ERR_CAPACITY);
+        cost[c] = INFINITY;
+      }
+      continue;
+    }
+    char* base = kLds ? dc_sim_smem : gscratch + (size_t)blockIdx.x * gstride;
+    double* ready = reinterpret_cast<double*>(base);
+    double* dur = ready + G;
+    int* dep = reinterpret_cast<int*>(dur + G);
+    int* q = dep + G;
+    int* aq = q + G;
+    int* rp = aq + G;
+    unsigned short* ci = reinterpret_cast<unsigned short*>(rp + G + 1);
+
+    // ---- load the module
+    for (int v = lane; v < G; v += 64) {
+      const float x = ar_size[n0 + v];
+      const bool ar = x >= 0.0f;
+      ready[v] = 0.0;
+      dur[v] = ar ? (double)ar_c * (double)x + (double)ar_d : (double)op_time[n0 + v];
+      dep[v] = (in_rp[n0 + v + 1] - in_rp[n0 + v]) | (ar ? kAr : 0);
+      rp[v] = out_rp[n0 + v] - e0;
+    }
+    if (lane == 0) rp[G] = E;
+    for (int k = lane; k < E; k += 64) ci[k] = (unsigned short)(out_ci[e0 + k] - n0);
+    __syncthreads();                      // one wave: orders the memory operations above
+
+    // ---- sources, in ascending index, onto the two queues
+    int qt = 0, at = 0;                   // tails (wave-uniform)
+    for (int v0 = 0; v0 < G; v0 += 64) {
+      const int v = v0 + lane;
+      const int d = v < G ? dep[v] : 1;
+      const bool src_op = d == 0, src_ar = d == kAr;
+      const unsigned long long mo = __ballot(src_op), ma = __ballot(src_ar);
+      const unsigned long long below = (1ull << lane) - 1ull;
+      if (src_op) q[qt + __popcll(mo & below)] = v;
+      if (src_ar) aq[at + __popcll(ma & below)] = v;
+      qt += __popcll(mo);
+      at += __popcll(ma);
+    }
+    __syncthreads();
+
+    // ---- the walk
+    int qh = 0, ah = 0, processed = 0;
+    double dev = 0.0, chan = 0.0;
+    while (ah < at || qh < qt) {
+      int u;
+      double done;
+      if (ah < at) {                      // tensors already produced go on the channel first
+        u = aq[ah++];
+        const double r = ready[u];
+        done = (r > chan ? r : chan) + dur[u];
+        chan = done;
+      } else {
+        u = q[qh++];
+        const double r = ready[u];
+        done = (r > dev ? r : dev) + dur[u];
+        dev = done;
+      }
+      ++processed;
+      const int s = rp[u], e = rp[u + 1];
+      for (int k0 = s; k0 < e; k0 += 64) {
+        const int k = k0 + lane;
+        bool new_op = false, new_ar = false;
+        int w = 0;
+        if (k < e) {
+          w = ci[k];
+          if (done > ready[w]) ready[w] = done;
+          const int d = dep[w] - 1;
+          dep[w] = d;
+          new_op = d == 0;
+          new_ar = d == kAr;
+        }
+        const unsigned long long mo = __ballot(new_op), ma = __ballot(new_ar);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (new_op) q[qt + __popcll(mo & below)] = w;
+        if (new_ar) aq[at + __popcll(ma & below)] = w;
+        qt += __popcll(mo);
+        at += __popcll(ma);
+      }
+      __syncthreads();                    // the releases are visible before the next node is taken
+    }
+    if (lane == 0) cost[c] = processed == G ? (float)(dev > chan ? dev : chan) : INFINITY;
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+size_t simulate_scratch_bytes(long long max_graph_nodes, long long max_graph_edges, int n_slices) {
+  return sim_bytes(max_graph_nodes, max_graph_edges) * (size_t)n_slices;
+}
+
+hipError_t launch_simulate(const SimArgs& a, hipStream_t s) {
+  if (a.n_cand <= 0) return hipSuccess;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&simulate_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, a.lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  // modules that fit in LDS: one wave each, as many workgroups as there are candidates
+  hipLaunchKernelGGL(simulate_kernel<true>, dim3(a.n_cand), dim3(64), a.lds_bytes, s, a.node_off, a.out_rowptr,
+                     a.out_col, a.in_rowptr, a.op_time, a.ar_size, a.n_cand, a.ar_c, a.ar_d, a.cost, nullptr, (size_t)0,
+                     a.lds_bytes, a.status);
+  // the others walk in slices of global memory (a persistent grid of n_slices waves)
+  if (a.n_slices > 0)
+    hipLaunchKernelGGL(simulate_kernel<false>, dim3(a.n_slices), dim3(64), 0, s, a.node_off, a.out_rowptr, a.out_col,
+                       a.in_rowptr, a.op_time, a.ar_size, a.n_cand, a.ar_c, a.ar_d, a.cost, a.scratch, a.scratch_stride,
+                       a.lds_bytes, a.status);
+  return hipGetLastError();
+}
+
+}  // namespace dc
