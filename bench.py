@@ -130,16 +130,15 @@ def simulate_bench(args, w, B, torch):
                       "finite": int(torch.isfinite(cost).sum().item())}}
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
-        n = min(w.n_cand, 256)
-        sub = w.subset(np.linspace(0, w.n_cand - 1, n).astype(np.int64))
-        ref = orc.contract(sub, False)
+        n = w.n_cand                          # the simulator is cheap on the CPU: time the whole batch
+        ref = orc.contract(w, False)
         ar = np.where(ref.Xc[:, 1] > 0, ref.Xc[:, 0], -1.0).astype(np.float32)
         tt = np.where(ref.Xc[:, 1] > 0, 0.0, 0.05 + ref.Xc[:, 2]).astype(np.float32)
         t0 = time.perf_counter()
         orc.simulate(ref, tt, ar, 0.02, 0.01)
         cdt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": n / cdt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
-                               "sample": f"{n} of {w.n_cand} candidates, simulator only, {cdt:.2f} s"}
+                               "sample": f"all {n} candidates, simulator only (contraction not timed), {cdt:.3f} s"}
     ev.close()
     print(json.dumps(out), flush=True)
 

@@ -28,11 +28,20 @@ namespace {
 constexpr int kAr = 1 << 30;    // flag in the dependency counter: the node is an all-reduce
 
 __host__ __device__ inline size_t sim_bytes(long long G, long long E) {
-  // ready[G] f64 | dur[G] f64 | dep[G] i32 | q[G] i32 | aq[G] i32 | rp[G+1] i32 | ci[E] u16 (padded to 8 bytes)
-  return (size_t)G * (8 + 8 + 4 + 4 + 4) + (size_t)(G + 1) * 4 + (((size_t)E * 2 + 7) & ~(size_t)7) + 8;
+  // ready[G] f64 | val[G] f32 | dep[G] i32 | queue[G] i32 | rp[G+1] i32 | ci[E] u16 (padded to 8 bytes)
+  return (size_t)G * (8 + 4 + 4 + 4) + (size_t)(G + 1) * 4 + (((size_t)E * 2 + 7) & ~(size_t)7) + 8;
 }
 
 extern __shared__ __attribute__((aligned(16))) char dc_sim_smem[];
+
+// The workgroup is one wave.  LDS operations of a wave are carried out in issue order, so
+// between a lane's write and another lane's later read only the compiler has to be kept from
+// reordering; global memory needs the writes to have completed.
+template <bool kLds>
+__device__ __forceinline__ void sync_wave() {
+  if (kLds) __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  else __syncthreads();
+}
 
 template <bool kLds>
 __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ node_off,
@@ -41,14 +50,16 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
                                                        const float* __restrict__ op_time,
                                                        const float* __restrict__ ar_size, int C, float ar_c,
                                                        float ar_d, float* __restrict__ cost, char* gscratch,
-                                                       size_t gstride, int lds_bytes, int* status) {
+                                                       size_t gstride, int lds_lo, int lds_hi, int* status) {
+  // kLds: this launch walks the modules whose arrays need more than lds_lo and at most lds_hi
+  // bytes (its LDS allocation); !kLds: those that need more than lds_hi, in global memory
   if (status[0] != 0) return;
   const int lane = threadIdx.x;
   for (int c = blockIdx.x; c < C; c += gridDim.x) {
     const int n0 = node_off[c], G = node_off[c + 1] - n0;
     const int e0 = out_rp[n0], E = out_rp[n0 + G] - e0;
-    const bool fits = sim_bytes(G, E) <= (size_t)lds_bytes;
-    if (fits != kLds) continue;
+    const size_t need = sim_bytes(G, E);
+    if (kLds ? (need <= (size_t)lds_lo || need > (size_t)lds_hi) : need <= (size_t)lds_hi) continue;
     if (!kLds && sim_bytes(G, E) > gstride) {       // larger than any base graph of this context
       if (lane == 0) {
         set_error(status, (int)DC_ERR_CAPACITY);
@@ -58,40 +69,40 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
     }
     char* base = kLds ? dc_sim_smem : gscratch + (size_t)blockIdx.x * gstride;
     double* ready = reinterpret_cast<double*>(base);
-    double* dur = ready + G;
-    int* dep = reinterpret_cast<int*>(dur + G);
-    int* q = dep + G;
-    int* aq = q + G;
-    int* rp = aq + G;
+    float* val = reinterpret_cast<float*>(ready + G);      // execution time, or tensor size of an all-reduce
+    int* dep = reinterpret_cast<int*>(val + G);
+    int* qu = dep + G;       // every node is queued once: ops fill it from the front, all-reduces from the back
+    int* rp = qu + G;
     unsigned short* ci = reinterpret_cast<unsigned short*>(rp + G + 1);
+    const double dc = (double)ar_c, dd = (double)ar_d;
 
     // ---- load the module
     for (int v = lane; v < G; v += 64) {
       const float x = ar_size[n0 + v];
       const bool ar = x >= 0.0f;
       ready[v] = 0.0;
-      dur[v] = ar ? (double)ar_c * (double)x + (double)ar_d : (double)op_time[n0 + v];
+      val[v] = ar ? x : op_time[n0 + v];
       dep[v] = (in_rp[n0 + v + 1] - in_rp[n0 + v]) | (ar ? kAr : 0);
       rp[v] = out_rp[n0 + v] - e0;
     }
     if (lane == 0) rp[G] = E;
     for (int k = lane; k < E; k += 64) ci[k] = (unsigned short)(out_ci[e0 + k] - n0);
-    __syncthreads();                      // one wave: orders the memory operations above
+    sync_wave<kLds>();
 
     // ---- sources, in ascending index, onto the two queues
-    int qt = 0, at = 0;                   // tails (wave-uniform)
+    int qt = 0, at = 0;                   // entries queued so far (wave-uniform)
     for (int v0 = 0; v0 < G; v0 += 64) {
       const int v = v0 + lane;
       const int d = v < G ? dep[v] : 1;
       const bool src_op = d == 0, src_ar = d == kAr;
       const unsigned long long mo = __ballot(src_op), ma = __ballot(src_ar);
       const unsigned long long below = (1ull << lane) - 1ull;
-      if (src_op) q[qt + __popcll(mo & below)] = v;
-      if (src_ar) aq[at + __popcll(ma & below)] = v;
+      if (src_op) qu[qt + __popcll(mo & below)] = v;
+      if (src_ar) qu[G - 1 - (at + __popcll(ma & below))] = v;
       qt += __popcll(mo);
       at += __popcll(ma);
     }
-    __syncthreads();
+    sync_wave<kLds>();
 
     // ---- the walk
     int qh = 0, ah = 0, processed = 0;
@@ -100,14 +111,14 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
       int u;
       double done;
       if (ah < at) {                      // tensors already produced go on the channel first
-        u = aq[ah++];
+        u = qu[G - 1 - ah++];
         const double r = ready[u];
-        done = (r > chan ? r : chan) + dur[u];
+        done = (r > chan ? r : chan) + (dc * (double)val[u] + dd);
         chan = done;
       } else {
-        u = q[qh++];
+        u = qu[qh++];
         const double r = ready[u];
-        done = (r > dev ? r : dev) + dur[u];
+        done = (r > dev ? r : dev) + (double)val[u];
         dev = done;
       }
       ++processed;
@@ -126,15 +137,15 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
         }
         const unsigned long long mo = __ballot(new_op), ma = __ballot(new_ar);
         const unsigned long long below = (1ull << lane) - 1ull;
-        if (new_op) q[qt + __popcll(mo & below)] = w;
-        if (new_ar) aq[at + __popcll(ma & below)] = w;
+        if (new_op) qu[qt + __popcll(mo & below)] = w;
+        if (new_ar) qu[G - 1 - (at + __popcll(ma & below))] = w;
         qt += __popcll(mo);
         at += __popcll(ma);
       }
-      __syncthreads();                    // the releases are visible before the next node is taken
+      sync_wave<kLds>();                  // the releases are visible before the next node is taken
     }
     if (lane == 0) cost[c] = processed == G ? (float)(dev > chan ? dev : chan) : INFINITY;
-    __syncthreads();
+    sync_wave<kLds>();
   }
 }
 
@@ -146,6 +157,10 @@ size_t simulate_scratch_bytes(long long max_graph_nodes, long long max_graph_edg
 
 hipError_t launch_simulate(const SimArgs& a, hipStream_t s) {
   if (a.n_cand <= 0) return hipSuccess;
+  // Modules are walked on chip in four launches by size class, each with just the LDS its class
+  // needs (10, 5, 3 or 2 waves per CU); a workgroup whose candidate belongs to another class
+  // returns at once.  The rest walk in slices of global memory (a persistent grid).
+  const int classes[5] = {0, 16 * 1024, 32 * 1024, 53 * 1024, a.lds_bytes};
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&simulate_kernel<true>),
@@ -153,15 +168,14 @@ hipError_t launch_simulate(const SimArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  // modules that fit in LDS: one wave each, as many workgroups as there are candidates
-  hipLaunchKernelGGL(simulate_kernel<true>, dim3(a.n_cand), dim3(64), a.lds_bytes, s, a.node_off, a.out_rowptr,
-                     a.out_col, a.in_rowptr, a.op_time, a.ar_size, a.n_cand, a.ar_c, a.ar_d, a.cost, nullptr, (size_t)0,
-                     a.lds_bytes, a.status);
-  // the others walk in slices of global memory (a persistent grid of n_slices waves)
+  for (int k = 0; k < 4; ++k)
+    hipLaunchKernelGGL(simulate_kernel<true>, dim3(a.n_cand), dim3(64), classes[k + 1], s, a.node_off, a.out_rowptr,
+                       a.out_col, a.in_rowptr, a.op_time, a.ar_size, a.n_cand, a.ar_c, a.ar_d, a.cost, nullptr,
+                       (size_t)0, classes[k], classes[k + 1], a.status);
   if (a.n_slices > 0)
     hipLaunchKernelGGL(simulate_kernel<false>, dim3(a.n_slices), dim3(64), 0, s, a.node_off, a.out_rowptr, a.out_col,
                        a.in_rowptr, a.op_time, a.ar_size, a.n_cand, a.ar_c, a.ar_d, a.cost, a.scratch, a.scratch_stride,
-                       a.lds_bytes, a.status);
+                       0, a.lds_bytes, a.status);
   return hipGetLastError();
 }
 

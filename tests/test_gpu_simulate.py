@@ -81,15 +81,21 @@ def test_cycles_give_infinity_and_large_graphs_use_the_global_path(B):
     got, st = run(B, w, ref, op_time, ar_size, 0.25, 0.05)
     assert st == B.DC_OK
     assert np.array_equal(got, want)
-    # contracted graphs of a few thousand nodes do not fit the 80 KB a wave has on chip: same
-    # result through slices of global memory
-    big = wl.make("cfg5", 6, n_graphs=3)
+    # a contracted graph of several thousand nodes does not fit the 80 KB a wave has on chip: same
+    # result through slices of global memory (identity and coarse partitions of a 5000-node DAG)
+    gb = wl.random_dag(23, 5000, 0.0006, 16)
+    labsb = np.concatenate([np.arange(gb.n, dtype=np.int32).reshape(1, -1), wl.random_labels(24, gb.n, 4000, C=1),
+                            wl.random_labels(25, gb.n, 900, C=1)])
+    big = wl.custom("sim-big", wl.ModelSpec(16, 32, 1, "f32"), [gb], [labsb], seed=1)
     refb = orc.contract(big, False)
-    need = [32 * int(refb.node_off[c + 1] - refb.node_off[c]) + 2 * int(refb.edge_off[c + 1] - refb.edge_off[c])
+    need = [24 * int(refb.node_off[c + 1] - refb.node_off[c]) + 2 * int(refb.edge_off[c + 1] - refb.edge_off[c])
             for c in range(big.n_cand)]
     assert max(need) > 80 * 1024 > min(need)
-    t2, x2 = times_of(refb, big.model.F)
+    rng = wl.Rng(6, 11)
+    t2 = (rng.uniform(refb.ntot) + 0.1).astype(np.float32)
+    x2 = np.where(rng.uniform(refb.ntot) < 0.15, rng.uniform(refb.ntot) * 8, -1.0).astype(np.float32)
     wantb = orc.simulate(refb, t2, x2, 0.1, 0.02)
+    assert np.isfinite(wantb).any()
     gotb, st = run(B, big, refb, t2, x2, 0.1, 0.02)
     assert st == B.DC_OK
     assert np.array_equal(gotb, wantb)
