@@ -50,6 +50,14 @@
 //    are released in ascending index; a module whose graph has a cycle (an invalid fusion)
 //    costs +infinity.  All arithmetic in fp64.
 //
+//  * Cost(H) as the paper composes it (Sec. 3.1, Simulator; Sec. 3.3; Sec. 3.4): the
+//    estimator is applied to every fused op, i.e. to the subgraph of its original ops with
+//    the dependencies among them (orc_fused_op_batch builds these subgraphs, the forward
+//    pass above runs on them as a batch of small graphs); single ops take their profiled
+//    time, a (fused) gradient tensor the sum of its members' sizes (orc_module_times);
+//    orc_simulate then gives the end-to-end time.  Choices of this build: an estimate is
+//    clamped at zero; a group that mixes ops and tensors gets an infinite time.
+//
 // Numerics: values are stored as fp32, every sum and dot product is
 // accumulated in fp64 and rounded once.  With bf16 != 0 the storage points
 // that the bf16 device path rounds (contracted features, all activations,
@@ -71,6 +79,11 @@
 // all-reduce behind a chain, two buckets that queue on the channel, overlap of
 // communication with computation, the ring closed form for C, a brute-force event
 // simulation on random DAGs, cyclic graphs, and one hand-worked example.
+// Cost composition: the all-singleton partition (profiled data only), every fused op
+// rebuilt on its own from a dense adjacency restricted to its members and evaluated by the
+// dense float64 forward pass, closed forms with a constant estimator (bias-only head), the
+// clamp, a fused tensor behind one op, mixed groups, label-bijection invariance, and one
+// hand-worked example.
 #include <cstdint>
 #include <cstring>
 #include <cmath>
@@ -457,5 +470,137 @@ void orc_simulate(int n_cand, const int32_t* node_off,
   }
 }
 
+// The fused ops of every candidate as a batch of small graphs (Sec. 3.3: a fused op is the
+// subgraph of the model graph whose nodes are its original ops and whose edges are the
+// dependencies among them; the estimator predicts its execution time from that subgraph).
+// A contracted node is a fused op when it has at least two members and all of them are
+// computation ops (ar_size_base < 0).  Order: candidates ascending, within a candidate
+// contracted nodes ascending; the rows of a fused op are its members in ascending base
+// index with their own feature rows (rounded like every stored feature); its edges are the
+// base edges with both ends in the group, 0/1 adjacency, lists ascending.  Layout as for
+// orc_contract_batch with one graph per fused op.  fo_cnode[k] is the contracted node
+// (global number) of fused op k, fo_member[r] the base node (local number) of row r.
+// new_id / c_node_off are the outputs of orc_contract_batch for the same candidates.
+// Returns the number of fused ops, or -4 when a capacity is exceeded.
+int64_t orc_fused_op_batch(const int32_t* g_node_off, const int32_t* g_edge_off, const int32_t* rowptr,
+                           const int32_t* col, const float* X, int F, const float* ar_size_base, int n_cand,
+                           const int32_t* cand_graph, const int64_t* cand_off, const int32_t* new_id,
+                           const int32_t* c_node_off, int bf16, int64_t cap_graphs, int64_t cap_nodes,
+                           int64_t cap_edges, int32_t* fo_node_off, int32_t* fo_edge_off, int32_t* fo_cnode,
+                           int32_t* fo_member, int32_t* out_rowptr, int32_t* out_col, int32_t* in_rowptr,
+                           int32_t* in_col, float* Xf) {
+  int64_t K = 0, nt = 0, et = 0;
+  fo_node_off[0] = 0;
+  fo_edge_off[0] = 0;
+  for (int c = 0; c < n_cand; ++c) {
+    const int b = cand_graph[c];
+    const int n = g_node_off[b + 1] - g_node_off[b];
+    const int32_t* rp = rowptr + g_node_off[b] + b;
+    const int32_t* ci = col + g_edge_off[b];
+    const int32_t* nid = new_id + cand_off[c];
+    const int G = c_node_off[c + 1] - c_node_off[c];
+    std::vector<std::vector<int32_t>> members(G);
+    for (int v = 0; v < n; ++v) members[nid[v]].push_back(v);      // ascending by construction
+    for (int g = 0; g < G; ++g) {
+      const std::vector<int32_t>& m = members[g];
+      bool ops_only = true;
+      for (int32_t v : m) ops_only = ops_only && ar_size_base[g_node_off[b] + v] < 0.0f;
+      if (m.size() < 2 || !ops_only) continue;
+      std::set<std::pair<int32_t, int32_t>> fwd, bwd;             // (row, neighbour) in member positions
+      for (size_t i = 0; i < m.size(); ++i)
+        for (int e = rp[m[i]]; e < rp[m[i] + 1]; ++e) {
+          const int32_t w = ci[e];
+          if (nid[w] != g || w == m[i]) continue;
+          size_t j = 0;
+          while (m[j] != w) ++j;
+          fwd.insert({static_cast<int32_t>(i), static_cast<int32_t>(j)});
+          bwd.insert({static_cast<int32_t>(j), static_cast<int32_t>(i)});
+        }
+      const int64_t sz = static_cast<int64_t>(m.size()), E = static_cast<int64_t>(fwd.size());
+      if (K + 1 > cap_graphs || nt + sz > cap_nodes || et + E > cap_edges) return -4;
+      std::vector<int32_t> orp(sz + 1, 0), irp(sz + 1, 0);
+      int64_t k = 0;
+      for (const auto& p : fwd) {
+        orp[p.first + 1] += 1;
+        out_col[et + k++] = static_cast<int32_t>(nt + p.second);
+      }
+      k = 0;
+      for (const auto& p : bwd) {
+        irp[p.first + 1] += 1;
+        in_col[et + k++] = static_cast<int32_t>(nt + p.second);
+      }
+      for (int64_t i = 0; i < sz; ++i) {
+        orp[i + 1] += orp[i];
+        irp[i + 1] += irp[i];
+        out_rowptr[nt + i] = static_cast<int32_t>(et + orp[i]);
+        in_rowptr[nt + i] = static_cast<int32_t>(et + irp[i]);
+        fo_member[nt + i] = m[i];
+        for (int f = 0; f < F; ++f)
+          Xf[static_cast<size_t>(nt + i) * F + f] =
+              store(static_cast<double>(X[static_cast<size_t>(g_node_off[b] + m[i]) * F + f]), bf16);
+      }
+      fo_cnode[K] = c_node_off[c] + g;
+      nt += sz;
+      et += E;
+      ++K;
+      fo_node_off[K] = static_cast<int32_t>(nt);
+      fo_edge_off[K] = static_cast<int32_t>(et);
+    }
+  }
+  out_rowptr[nt] = static_cast<int32_t>(et);
+  in_rowptr[nt] = static_cast<int32_t>(et);
+  return K;
+}
+
+// What the simulator is given for every node of the candidate modules (Sec. 3.1, Simulator:
+// profiled data for individual ops, the estimator for fused ops, the linear model for
+// all-reduce instructions on the size of the - possibly fused - tensor; Sec. 2.3: the size of
+// a fused tensor is the sum of its members' sizes).  Per contracted node:
+//   all members all-reduce tensors: ar_size = sum of their sizes (fp64, ascending member
+//                                   index, rounded once), op_time = 0 (unused)
+//   one op:                         op_time = its profiled time, ar_size = -1
+//   two or more ops:                op_time = max(0, estimator output) (the regression network
+//                                   ends in a ReLU, Sec. 3.3.2: a time is never negative),
+//                                   taken from fo_pred through fo_cnode; ar_size = -1
+//   ops and tensors mixed:          not a fusion the strategies produce (Sec. 3.2): op_time =
+//                                   +infinity, which makes the module cost +infinity
+void orc_module_times(const int32_t* g_node_off, const float* op_time_base, const float* ar_size_base, int n_cand,
+                      const int32_t* cand_graph, const int64_t* cand_off, const int32_t* new_id,
+                      const int32_t* c_node_off, int64_t K, const int32_t* fo_cnode, const float* fo_pred,
+                      float* op_time, float* ar_size) {
+  for (int c = 0; c < n_cand; ++c) {
+    const int b = cand_graph[c];
+    const int n = g_node_off[b + 1] - g_node_off[b];
+    const int32_t* nid = new_id + cand_off[c];
+    const int G = c_node_off[c + 1] - c_node_off[c];
+    std::vector<int> n_op(G, 0), n_ar(G, 0);
+    std::vector<double> size_sum(G, 0.0);
+    std::vector<float> single(G, 0.0f);
+    for (int v = 0; v < n; ++v) {
+      const float x = ar_size_base[g_node_off[b] + v];
+      if (x >= 0.0f) {
+        n_ar[nid[v]] += 1;
+        size_sum[nid[v]] += static_cast<double>(x);
+      } else {
+        n_op[nid[v]] += 1;
+        single[nid[v]] = op_time_base[g_node_off[b] + v];
+      }
+    }
+    for (int g = 0; g < G; ++g) {
+      const int64_t o = c_node_off[c] + g;
+      if (n_op[g] == 0) {
+        op_time[o] = 0.0f;
+        ar_size[o] = static_cast<float>(size_sum[g]);
+      } else if (n_ar[g] == 0) {
+        op_time[o] = n_op[g] == 1 ? single[g] : 0.0f;      // fused ops are filled in below
+        ar_size[o] = -1.0f;
+      } else {
+        op_time[o] = INFINITY;
+        ar_size[o] = -1.0f;
+      }
+    }
+  }
+  for (int64_t k = 0; k < K; ++k) op_time[fo_cnode[k]] = fo_pred[k] > 0.0f ? fo_pred[k] : 0.0f;
+}
 
 }  // extern "C"

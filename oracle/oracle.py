@@ -36,6 +36,8 @@ def _load():
         _lib.orc_contract_batch.restype = C.c_int
         _lib.orc_gnn_forward.restype = None
         _lib.orc_simulate.restype = None
+        _lib.orc_fused_op_batch.restype = C.c_int64
+        _lib.orc_module_times.restype = None
         _lib.orc_round_bf16.restype = None
     return _lib
 
@@ -147,6 +149,78 @@ def simulate(b: Batch, op_time: np.ndarray, ar_size: np.ndarray, ar_c: float, ar
     lib.orc_simulate(C.c_int(b.n_cand), _p(b.node_off), _p(b.out_rowptr), _p(b.out_col), _p(b.in_rowptr),
                      _p(b.in_col), _p(t), _p(x), C.c_float(ar_c), C.c_float(ar_d), _p(cost))
     return cost
+
+
+def fused_ops(w, b: Batch, ar_size_base: np.ndarray, bf16: Optional[bool] = None):
+    """The fused ops (groups of two or more computation ops) of every candidate of `w`, each
+    as the subgraph of its members: returns (batch with one graph per fused op, contracted
+    node of each fused op, base node of each row).  `b` is contract(w)."""
+    lib = _load()
+    if bf16 is None:
+        bf16 = w.model.dtype == "bf16"
+    F = w.model.F
+    gno, geo = w.g_node_off(), w.g_edge_off()
+    rowptr, col, X = w.cat_rowptr(), w.cat_col(), w.cat_X()
+    cand_graph = np.ascontiguousarray(w.cand_graph, dtype=np.int32)
+    cand_off = np.ascontiguousarray(w.cand_off, dtype=np.int64)
+    x = np.ascontiguousarray(ar_size_base, dtype=np.float32)
+    cap_n = int(cand_off[-1])
+    cap_g = cap_n // 2 + 1
+    cap_e = int(sum(int(geo[g + 1] - geo[g]) for g in cand_graph))
+    node_off = np.zeros(cap_g + 1, np.int32)
+    edge_off = np.zeros(cap_g + 1, np.int32)
+    cnode = np.zeros(cap_g, np.int32)
+    member = np.zeros(max(cap_n, 1), np.int32)
+    orp = np.zeros(cap_n + 1, np.int32)
+    irp = np.zeros(cap_n + 1, np.int32)
+    oc = np.zeros(max(cap_e, 1), np.int32)
+    ic = np.zeros(max(cap_e, 1), np.int32)
+    Xf = np.zeros((max(cap_n, 1), F), np.float32)
+    new_id = np.ascontiguousarray(b.new_id, dtype=np.int32)
+    K = lib.orc_fused_op_batch(_p(gno), _p(geo), _p(rowptr), _p(col), _p(X), C.c_int(F), _p(x), C.c_int(w.n_cand),
+                               _p(cand_graph), _p(cand_off), _p(new_id), _p(b.node_off), C.c_int(int(bf16)),
+                               C.c_int64(cap_g), C.c_int64(cap_n), C.c_int64(cap_e), _p(node_off), _p(edge_off),
+                               _p(cnode), _p(member), _p(orp), _p(oc), _p(irp), _p(ic), _p(Xf))
+    if K < 0:
+        raise ValueError(f"oracle fused-op extraction failed with status {K}")
+    K = int(K)
+    nt, et = int(node_off[K]), int(edge_off[K])
+    fo = Batch(K, F, node_off[:K + 1], edge_off[:K + 1], member[:nt], orp[:nt + 1], oc[:et], irp[:nt + 1], ic[:et],
+               Xf[:nt], np.diff(node_off[:K + 1]).astype(np.int32))
+    return fo, cnode[:K], member[:nt]
+
+
+def module_times(w, b: Batch, op_time_base: np.ndarray, ar_size_base: np.ndarray, bf16: Optional[bool] = None,
+                 want_fused: bool = False):
+    """Per node of the contracted batch `b` = contract(w): execution time (profiled for single
+    ops, estimated for fused ops, clamped at zero) and all-reduce tensor size (sum over the
+    members of a bucket; negative for computation nodes)."""
+    lib = _load()
+    fo, cnode, _ = fused_ops(w, b, ar_size_base, bf16)
+    fo_pred = gnn_forward(fo, w.model, w.weights, bf16) if fo.n_cand > 0 else np.zeros(0, np.float32)
+    t = np.ascontiguousarray(op_time_base, dtype=np.float32)
+    x = np.ascontiguousarray(ar_size_base, dtype=np.float32)
+    cand_graph = np.ascontiguousarray(w.cand_graph, dtype=np.int32)
+    cand_off = np.ascontiguousarray(w.cand_off, dtype=np.int64)
+    new_id = np.ascontiguousarray(b.new_id, dtype=np.int32)
+    gno = w.g_node_off()
+    op_time = np.zeros(max(b.ntot, 1), np.float32)
+    ar_size = np.zeros(max(b.ntot, 1), np.float32)
+    cn = np.ascontiguousarray(cnode, dtype=np.int32)
+    fp = np.ascontiguousarray(fo_pred, dtype=np.float32)
+    lib.orc_module_times(_p(gno), _p(t), _p(x), C.c_int(w.n_cand), _p(cand_graph), _p(cand_off), _p(new_id),
+                         _p(b.node_off), C.c_int64(fo.n_cand), _p(cn), _p(fp), _p(op_time), _p(ar_size))
+    if want_fused:
+        return op_time[:b.ntot], ar_size[:b.ntot], fo, cnode, fo_pred
+    return op_time[:b.ntot], ar_size[:b.ntot]
+
+
+def cost(w, op_time_base: np.ndarray, ar_size_base: np.ndarray, ar_c: float, ar_d: float,
+         bf16: Optional[bool] = None) -> np.ndarray:
+    """Cost(H) per candidate: contraction, times of all nodes of the module, list scheduling."""
+    b = contract(w, bf16)
+    op_time, ar_size = module_times(w, b, op_time_base, ar_size_base, bf16)
+    return simulate(b, op_time, ar_size, ar_c, ar_d)
 
 
 def evaluate(w, bf16: Optional[bool] = None) -> np.ndarray:

@@ -629,6 +629,19 @@ def with_attention(w: Workload, heads: int, seed: int = 0, std: Optional[float] 
                     make_weights(m, seed, std), w.note)
 
 
+def profile_of(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
+    """Stand-in for the profiler's records (Sec. 3.1) over all base nodes, concatenated like
+    the features: (op_time, ar_size).  An op's execution time is 0.05 + feature column 2; an
+    all-reduce node's tensor size is feature column 0 (MiB in cfg2-cfg5); ar_size is -1 for
+    ops and op_time is 0 for all-reduce nodes."""
+    t, x = [], []
+    for g in w.graphs:
+        is_ar = np.arange(g.n) >= g.n_op
+        t.append(np.where(is_ar, 0.0, 0.05 + g.X[:, 2]).astype(np.float32))
+        x.append(np.where(is_ar, g.X[:, 0], -1.0).astype(np.float32))
+    return np.concatenate(t), np.concatenate(x)
+
+
 def custom(name: str, model: ModelSpec, graphs: List[BaseGraph], labels_per_graph: List[np.ndarray],
            weights: Optional[Weights] = None, seed: int = 0, std: Optional[float] = None) -> Workload:
     return _pack(name, model, graphs, labels_per_graph, weights or make_weights(model, seed, std))

@@ -1,0 +1,179 @@
+"""Pins for the CPU oracle's composition of Cost(H) (Secs. 3.1, 3.3, 3.4; no GPU): fused ops
+extracted as subgraphs, estimated by the forward pass, single ops from the profile, fused
+tensors by summed size, then the list-scheduling simulator."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2209_12769_amd import workloads as wl
+from test_oracle_gnn import _dense_forward
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def graph_of(n, n_op, edges, X):
+    src = np.array([e[0] for e in edges], np.int64)
+    dst = np.array([e[1] for e in edges], np.int64)
+    rp, ci = wl._csr_from_edges(n, src, dst)
+    return wl.BaseGraph(n, n_op, rp, ci, np.asarray(X, np.float32))
+
+
+def constant_estimator(model, value):
+    """Weights under which every fused op is predicted `value`: zero matrices, head bias = value."""
+    wt = wl.make_weights(model, 0)
+    return wl.Weights(np.zeros_like(wt.layers), np.zeros_like(wt.biases),
+                      np.concatenate([np.zeros(wt.head.size - 1, np.float32), [np.float32(value)]]))
+
+
+def random_case(seed, n=14, n_ar=4, n_groups=7, C=3):
+    """Random DAG on n ops plus n_ar all-reduce sinks; arbitrary labels on the ops, runs on the tensors."""
+    g0 = wl.random_dag(seed, n, 0.3, 16)
+    rng = wl.Rng(seed, 11)
+    src = list(np.repeat(np.arange(n), np.diff(g0.rowptr))) + [int(v) for v in rng.integers(0, n - 1, n_ar)]
+    dst = list(g0.col) + list(range(n, n + n_ar))
+    X = rng.uniform((n + n_ar) * 16).reshape(n + n_ar, 16).astype(np.float32)
+    g = graph_of(n + n_ar, n, list(zip(src, dst)), X)
+    labs = np.empty((C, n + n_ar), np.int32)
+    labs[:, :n] = wl.random_labels(seed, n, n_groups, C)
+    for c in range(C):
+        run = np.cumsum(rng.uniform(n_ar) < 0.5)
+        labs[c, n:] = n + run - run[0]              # labels >= n: never shared with an op
+    model = wl.ModelSpec(16, 32, 2, "f32")
+    w = wl.custom("cost", model, [g], [labs], seed=seed, std=0.3)
+    w.weights.head[-1] += 1.0                       # most estimates positive
+    return w
+
+
+def test_all_singletons_use_profiled_data_only():
+    w = wl.make("cfg2", 1)
+    n = w.graphs[0].n
+    w = wl.custom("id", w.model, w.graphs, [np.arange(n, dtype=np.int32).reshape(1, n)])
+    t, x = wl.profile_of(w)
+    b = orc.contract(w)
+    fo, cnode, _ = orc.fused_ops(w, b, x)
+    assert fo.n_cand == 0 and fo.ntot == 0
+    op_time, ar_size = orc.module_times(w, b, t, x)
+    np.testing.assert_array_equal(op_time, t)
+    np.testing.assert_array_equal(ar_size, x)
+    np.testing.assert_array_equal(orc.cost(w, t, x, 0.02, 0.01), orc.simulate(b, t, x, 0.02, 0.01))
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_every_fused_op_rebuilt_from_a_dense_adjacency(seed):
+    w = random_case(seed)
+    g = w.graphs[0]
+    t, x = wl.profile_of(w)
+    b = orc.contract(w)
+    op_time, ar_size, fo, cnode, fo_pred = orc.module_times(w, b, t, x, want_fused=True)
+    A = np.zeros((g.n, g.n))
+    for u in range(g.n):
+        A[u, g.col[g.rowptr[u]:g.rowptr[u + 1]]] = 1
+    seen = 0
+    for c in range(w.n_cand):
+        lab = w.group_id[w.cand_off[c]:w.cand_off[c + 1]]
+        nid = b.new_id[w.cand_off[c]:w.cand_off[c + 1]]
+        for l in np.unique(lab):
+            mem = np.nonzero(lab == l)[0]
+            node = int(b.node_off[c] + nid[mem[0]])
+            if np.all(mem >= g.n_op):                                   # a bucket of tensors
+                assert ar_size[node] == np.float32(np.sum(x[mem].astype(np.float64)))
+                continue
+            assert np.all(mem < g.n_op)
+            assert ar_size[node] == -1.0
+            if len(mem) == 1:
+                assert op_time[node] == t[mem[0]]
+                continue
+            k = int(np.nonzero(cnode == node)[0][0])
+            ref, _, _ = _dense_forward(A[np.ix_(mem, mem)], g.X[mem], w.model, w.weights)
+            assert abs(fo_pred[k] - ref) <= 2e-6 * max(1.0, abs(ref))
+            assert abs(op_time[node] - max(ref, 0.0)) <= 2e-6 * max(1.0, abs(ref))
+            np.testing.assert_array_equal(fo.new_id[fo.node_off[k]:fo.node_off[k + 1]], mem)
+            seen += 1
+    assert seen == fo.n_cand and seen > 0
+    assert np.all(np.diff(cnode) > 0)                                   # candidates, then nodes, ascending
+
+
+def test_constant_estimator_on_a_chain_gives_a_closed_form():
+    # chain of 8 ops, labels fuse (0,1,2) and (5,6): 8 - 5 = 3 single ops + 2 fused ops at 2.5 each
+    n = 8
+    X = np.zeros((n, 16), np.float32)
+    X[:, 2] = np.arange(1, n + 1)
+    g = graph_of(n, n, [(i, i + 1) for i in range(n - 1)], X)
+    model = wl.ModelSpec(16, 32, 2, "f32")
+    lab = np.array([[0, 0, 0, 3, 4, 5, 5, 7]], np.int32)
+    w = wl.custom("chain", model, [g], [lab], weights=constant_estimator(model, 2.5))
+    t, x = wl.profile_of(w)
+    expect = float(t[3] + t[4] + t[7]) + 2 * 2.5
+    assert orc.cost(w, t, x, 0.0, 0.0)[0] == np.float32(expect)
+
+
+def test_a_negative_estimate_counts_as_zero():
+    n = 4
+    X = np.zeros((n, 16), np.float32)
+    g = graph_of(n, n, [(0, 1), (1, 2), (2, 3)], X)
+    model = wl.ModelSpec(16, 32, 1, "f32")
+    w = wl.custom("neg", model, [g], [np.array([[0, 0, 2, 3]], np.int32)], weights=constant_estimator(model, -3.0))
+    t, x = wl.profile_of(w)
+    b = orc.contract(w)
+    op_time, _, fo, _, fo_pred = orc.module_times(w, b, t, x, want_fused=True)
+    assert fo.n_cand == 1 and fo_pred[0] == -3.0 and op_time[0] == 0.0
+    assert orc.cost(w, t, x, 0.0, 0.0)[0] == np.float32(float(t[2]) + float(t[3]))
+
+
+def test_a_fused_tensor_is_sent_once_with_the_summed_size():
+    # one op feeding three tensors; fused they cost C (x1 + x2 + x3) + D once, separately three times D
+    X = np.zeros((4, 16), np.float32)
+    X[0, 2] = 0.95
+    X[1:, 0] = [1.5, 2.25, 4.0]
+    g = graph_of(4, 1, [(0, 1), (0, 2), (0, 3)], X)
+    model = wl.ModelSpec(16, 32, 1, "f32")
+    fused = wl.custom("b", model, [g], [np.array([[0, 1, 1, 1]], np.int32)])
+    apart = wl.custom("s", model, [g], [np.array([[0, 1, 2, 3]], np.int32)])
+    t, x = wl.profile_of(fused)
+    C, D = 0.5, 0.125
+    assert orc.cost(fused, t, x, C, D)[0] == np.float32(1.0 + C * 7.75 + D)
+    assert orc.cost(apart, t, x, C, D)[0] == np.float32(1.0 + C * 7.75 + 3 * D)
+
+
+def test_a_group_mixing_ops_and_tensors_costs_infinity():
+    X = np.zeros((3, 16), np.float32)
+    g = graph_of(3, 2, [(0, 1), (1, 2)], X)
+    model = wl.ModelSpec(16, 32, 1, "f32")
+    w = wl.custom("mix", model, [g], [np.array([[0, 1, 1], [0, 1, 2]], np.int32)])
+    t, x = wl.profile_of(w)
+    c = orc.cost(w, t, x, 0.1, 0.1)
+    assert np.isinf(c[0]) and np.isfinite(c[1])
+
+
+def test_label_bijection_leaves_the_cost_unchanged():
+    w = random_case(9)
+    n = w.graphs[0].n
+    perm = wl.Rng(3, 5).permutation(n).astype(np.int32)
+    w2 = wl.custom("perm", w.model, w.graphs, [perm[w.group_id].reshape(w.n_cand, n)], weights=w.weights)
+    t, x = wl.profile_of(w)
+    np.testing.assert_array_equal(orc.cost(w, t, x, 0.02, 0.01), orc.cost(w2, t, x, 0.02, 0.01))
+
+
+def test_hand_worked_example():
+    rec = {}
+    with open(os.path.join(GOLD, "cost_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, *v = line.split()
+            rec[k] = [float(z) for z in v]
+    n, n_op = int(rec["n"][0]), int(rec["n_op"][0])
+    e = [int(z) for z in rec["edges"]]
+    t = np.array(rec["op_time"], np.float32)
+    x = np.array(rec["ar_size"], np.float32)
+    g = graph_of(n, n_op, list(zip(e[0::2], e[1::2])), t.reshape(n, 1))
+    model = wl.ModelSpec(1, 1, 1, "f32")
+    wt = wl.Weights(np.array(rec["layer_w"], np.float32), np.array(rec["layer_b"], np.float32),
+                    np.array(rec["head"], np.float32))
+    w = wl.custom("gold", model, [g], [np.array(rec["labels"], np.int32).reshape(1, n)], weights=wt)
+    b = orc.contract(w)
+    _, _, fo, _, fo_pred = orc.module_times(w, b, t, x, want_fused=True)
+    np.testing.assert_array_equal(fo_pred, np.array(rec["fused_op_time"], np.float32))
+    assert orc.cost(w, t, x, rec["c"][0], rec["d"][0])[0] == np.float32(rec["cost"][0])
