@@ -21,7 +21,12 @@
  *                       encoding); a sum over all nodes of each graph
  *                       (Sec. 3.3.1, second equation); fully connected layers
  *                       with ReLU and a scalar output (Sec. 3.3.2).
- *   dc_eval_candidates  = contract + forward: the batched Cost() call.
+ *   dc_eval_candidates  = contract + forward: one estimate per candidate module.
+ *   dc_simulate         list scheduling of the candidate modules (Sec. 3.4).
+ *   dc_cost_candidates  Cost(H') as the paper composes it (Sec. 3.1, Simulator): the
+ *                       estimator on every fused op, profiled times for single ops,
+ *                       the linear model for (fused) all-reduce tensors, then
+ *                       dc_simulate.
  *
  * Conventions
  *  - Every call returns a dc_status; nothing throws or aborts.
@@ -202,6 +207,42 @@ dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* str
  * every base graph of the context is reported by dc_check as DC_ERR_CAPACITY.            */
 dc_status dc_simulate(dc_ctx* ctx, const dc_batch* in, const float* op_time, const float* ar_size, float ar_c,
                       float ar_d, float* cost, void* stream);
+
+/* Profiled data of the base graphs (Sec. 3.1, Profiler), host fp32 arrays over all base nodes in
+ * the order of X in dc_set_base_graphs:
+ *   op_time  execution time of each individual op (ignored for all-reduce nodes)
+ *   ar_size  tensor size of each gradient all-reduce node; negative marks a computation op
+ * Allocates the scratch of the cost path (about 40 bytes per base node and candidate slot plus
+ * a feature copy) and must follow dc_set_base_graphs; a later dc_set_base_graphs discards it.
+ * The cost path needs every base row strictly ascending (DC_ERR_BAD_GRAPH otherwise) and a
+ * context created with max_nodes = max_edges = 0 (DC_ERR_CAPACITY otherwise).            */
+dc_status dc_set_profile(dc_ctx* ctx, const float* op_time, const float* ar_size, void* stream);
+
+/* Contracts the candidates into *out (as dc_contract_graphs) and gives every node of the
+ * contracted batch what the simulator needs (Sec. 3.1, Simulator; Sec. 3.3):
+ *   a group of two or more ops     the estimator's prediction for the fused op, i.e. for the
+ *                                  subgraph of its members (ascending base index, their own
+ *                                  features, the base edges with both ends in the group):
+ *                                  layers, sum over the members, regression network; the
+ *                                  result is clamped at zero (Sec. 3.3.2: the network ends in a ReLU)
+ *   a single op                    its profiled time
+ *   a group of all-reduce tensors  ar_size = sum of the members' sizes (Sec. 2.3; fp64 in
+ *                                  ascending member order, rounded once), op_time = 0
+ *   ops and tensors mixed          op_time = +infinity (no strategy of Sec. 3.2 produces it)
+ * op_time, ar_size: dev [out->cap_nodes] fp32; ar_size is negative for computation nodes.
+ * On the bf16 path the sums over members and the two hidden layers of the regression network
+ * are stored as bfloat16 (they are inputs of MFMA GEMMs).                                   */
+dc_status dc_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                          const int32_t* group_id, dc_batch* out, float* op_time, float* ar_size, void* stream);
+
+/* Cost(H') of every candidate: dc_module_times into context-owned buffers followed by
+ * dc_simulate with T = ar_c * size + ar_d.  cost dev [n_cand] fp32.                      */
+dc_status dc_cost_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                             const int32_t* group_id, float ar_c, float ar_d, float* cost, void* stream);
+
+/* After a synchronised dc_module_times / dc_cost_candidates: how many fused ops the estimator
+ * ran on, their member rows and the edges inside them.  Synchronises `stream`.            */
+dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, int64_t* n_edges, void* stream);
 
 /* dc_contract_graphs into context-owned buffers followed by dc_gnn_forward. */
 dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,

@@ -75,6 +75,10 @@ def lib():
         L.dc_gnn_forward.argtypes = [vp, C.POINTER(DcBatch), vp, vp]
         L.dc_eval_candidates.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.dc_simulate.argtypes = [vp, C.POINTER(DcBatch), vp, vp, C.c_float, C.c_float, vp, vp]
+        L.dc_set_profile.argtypes = [vp, vp, vp, vp]
+        L.dc_module_times.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp, vp, vp]
+        L.dc_cost_candidates.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp]
+        L.dc_last_fused_ops.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_check.argtypes = [vp, vp]
         L.dc_last_totals.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_last_error.argtypes = [vp]
@@ -83,7 +87,7 @@ def lib():
         L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
         for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
                   "dc_gnn_forward", "dc_eval_candidates", "dc_simulate", "dc_check", "dc_last_totals", "dc_profile_begin",
-                  "dc_profile_end"):
+                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops"):
             getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -136,6 +140,28 @@ def dc_simulate(ctx, batch: DcBatch, op_time_ptr, ar_size_ptr, ar_c: float, ar_d
     return lib().dc_simulate(ctx, C.byref(batch), op_time_ptr, ar_size_ptr, ar_c, ar_d, cost_ptr, stream)
 
 
+def dc_set_profile(ctx, op_time: np.ndarray, ar_size: np.ndarray, stream: int = 0) -> int:
+    return lib().dc_set_profile(ctx, op_time.ctypes.data, ar_size.ctypes.data, stream)
+
+
+def dc_module_times(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, batch: DcBatch, op_time_ptr, ar_size_ptr,
+                    stream: int = 0) -> int:
+    return lib().dc_module_times(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, C.byref(batch), op_time_ptr,
+                                 ar_size_ptr, stream)
+
+
+def dc_cost_candidates(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, ar_c: float, ar_d: float, cost_ptr,
+                       stream: int = 0) -> int:
+    return lib().dc_cost_candidates(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, ar_c, ar_d, cost_ptr,
+                                    stream)
+
+
+def dc_last_fused_ops(ctx, stream: int = 0) -> Tuple[int, int, int, int]:
+    k, m, e = C.c_int64(), C.c_int64(), C.c_int64()
+    st = lib().dc_last_fused_ops(ctx, C.byref(k), C.byref(m), C.byref(e), stream)
+    return st, k.value, m.value, e.value
+
+
 def dc_check(ctx, stream: int = 0) -> int:
     return lib().dc_check(ctx, stream)
 
@@ -155,7 +181,7 @@ def dc_profile_begin(ctx) -> int:
 
 
 def dc_profile_end(ctx) -> Dict[str, Tuple[float, int]]:
-    cap = 16
+    cap = 32
     names = (C.c_char_p * cap)()
     ms = (C.c_float * cap)()
     cnt = (C.c_int32 * cap)()
@@ -278,6 +304,35 @@ class Evaluator:
         self._ok(dc_eval_candidates(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(),
                                     group_id.data_ptr(), pred.data_ptr(), self._stream()), "dc_eval_candidates")
         return pred[:n_cand]
+
+    def set_profile(self, op_time: np.ndarray, ar_size: np.ndarray):
+        t = np.ascontiguousarray(op_time, dtype=np.float32)
+        x = np.ascontiguousarray(ar_size, dtype=np.float32)
+        self._ok(dc_set_profile(self.ctx, t, x, self._stream()), "dc_set_profile")
+
+    def module_times(self, cand_graph, cand_off, group_id, batch: DeviceBatch, op_time=None, ar_size=None):
+        n_cand = int(cand_graph.numel())
+        f32 = dict(dtype=self.torch.float32, device=self.device)
+        if op_time is None:
+            op_time = self.torch.empty(max(batch.c.cap_nodes, 1), **f32)
+        if ar_size is None:
+            ar_size = self.torch.empty(max(batch.c.cap_nodes, 1), **f32)
+        self._ok(dc_module_times(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(), group_id.data_ptr(),
+                                 batch.c, op_time.data_ptr(), ar_size.data_ptr(), self._stream()), "dc_module_times")
+        return op_time, ar_size
+
+    def cost_candidates(self, cand_graph, cand_off, group_id, ar_c: float, ar_d: float, cost=None):
+        n_cand = int(cand_graph.numel())
+        if cost is None:
+            cost = self.torch.empty(max(n_cand, 1), dtype=self.torch.float32, device=self.device)
+        self._ok(dc_cost_candidates(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(), group_id.data_ptr(),
+                                    ar_c, ar_d, cost.data_ptr(), self._stream()), "dc_cost_candidates")
+        return cost[:n_cand]
+
+    def last_fused_ops(self) -> Tuple[int, int, int]:
+        st, k, m, e = dc_last_fused_ops(self.ctx, self._stream())
+        self._ok(st, "dc_last_fused_ops")
+        return k, m, e
 
     def check(self) -> int:
         return dc_check(self.ctx, self._stream())

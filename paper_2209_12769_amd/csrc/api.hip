@@ -62,6 +62,16 @@ struct dc_ctx {
   char* sim_scratch = nullptr;   // slices for modules the simulator cannot hold in LDS
   size_t sim_stride = 0;
   int sim_slices = 0;
+  // Cost(H) path: profiled data, the batch of fused-op subgraphs and per-node times (dc_set_profile)
+  bool bg_canonical = false;     // every base row strictly ascending, no self loop
+  long long bg_nodes = 0;
+  char* cost_mem = nullptr;
+  FusedOpsArgs fo{};             // the pointers that do not change from call to call
+  float* m_op_time = nullptr;    // [max_nodes] per contracted node, for dc_cost_candidates
+  float* m_ar_size = nullptr;
+  float* fo_pred = nullptr;      // raw estimate of each fused op of the last call
+  void* headW = nullptr;         // W1 | W2 of the regression network in the layer kernels' layout
+  bool have_profile = false;
   int allow_fused = 1;
   Profiler prof;
   std::string err;
@@ -72,7 +82,7 @@ namespace {
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
                                              "fused_layer", "layer256", "layer256_d64", "aggregate_heavy", "build_desc",
                                              "attention_project", "attention_scores", "attention_aggregate",
-                                             "readout_head", "simulate"};
+                                             "readout_head", "simulate", "fused_op_extract", "fused_op_head"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -220,7 +230,16 @@ dc_status do_contract(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, co
   return DC_OK;
 }
 
+GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred);
+
 dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred, hipStream_t s) {
+  const GnnArgs g = gnn_args(ctx, n_cand, in, pred);
+  hipError_t e = launch_gnn_forward(g, ctx->prof.on ? &ctx->prof : nullptr, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "forward launch");
+  return DC_OK;
+}
+
+GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) {
   GnnArgs g;
   g.n_cand = n_cand;
   g.node_off = in.node_off;
@@ -252,8 +271,74 @@ dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pr
     g.score[0] = ctx->score[0];
     g.score[1] = ctx->score[1];
   }
-  hipError_t e = launch_gnn_forward(g, ctx->prof.on ? &ctx->prof : nullptr, s);
-  if (e != hipSuccess) return hip_fail(ctx, e, "forward launch");
+  return g;
+}
+
+dc_status do_simulate(dc_ctx* ctx, int32_t n_cand, const BatchView& in, const float* op_time, const float* ar_size,
+                      float ar_c, float ar_d, float* cost, hipStream_t s) {
+  SimArgs a;
+  a.n_cand = n_cand;
+  a.node_off = in.node_off;
+  a.out_rowptr = in.out_rowptr;
+  a.out_col = in.out_col;
+  a.in_rowptr = in.in_rowptr;
+  a.op_time = op_time;
+  a.ar_size = ar_size;
+  a.ar_c = ar_c;
+  a.ar_d = ar_d;
+  a.cost = cost;
+  a.lds_bytes = kSimLdsBytes;
+  a.scratch = ctx->sim_scratch;
+  a.scratch_stride = ctx->sim_stride;
+  a.n_slices = ctx->sim_slices;
+  a.status = ctx->status;
+  if (ctx->prof.on) ctx->prof.begin(kFamSimulate, s);
+  hipError_t e = launch_simulate(a, s);
+  if (ctx->prof.on) ctx->prof.end(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "simulator launch");
+  return DC_OK;
+}
+
+// After a contraction into `cb`: the batch of fused-op subgraphs, the estimator on it, and the
+// time / tensor size of every node of the contracted batch.
+dc_status do_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                          const BatchView& cb, float* op_time, float* ar_size, hipStream_t s) {
+  Profiler* prof = ctx->prof.on ? &ctx->prof : nullptr;
+  FusedOpsArgs a = ctx->fo;
+  a.bg = ctx->bg;
+  a.n_cand = n_cand;
+  a.cand_graph = cand_graph;
+  a.cand_off = cand_off;
+  a.members = ctx->tmp.members;
+  a.mstart = ctx->tmp.mstart;
+  a.Gc = ctx->tmp.Gc;
+  a.new_id = cb.new_id;
+  a.c_node_off = cb.node_off;
+  a.op_time = op_time;
+  a.ar_size = ar_size;
+  hipError_t e = launch_fused_op_extract(a, prof, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fused-op extraction launch");
+  // the layer kernels only need the total row count: the batch is handed over as one graph
+  GnnArgs g = gnn_args(ctx, 1, a.fb, nullptr);
+  g.node_off = a.totals;
+  const void* h_last = nullptr;
+  e = launch_gnn_layers(g, prof, s, &h_last);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fused-op forward launch");
+  const size_t es = ctx->cfg.dtype == DC_BF16 ? 2 : 4;
+  const size_t HH = (size_t)ctx->cfg.H * ctx->cfg.H;
+  const int H = ctx->cfg.H;
+  if (prof) prof->begin(kFamFusedHead, s);
+  void* R = ctx->agg[0];
+  void* Z1 = ctx->agg[1];
+  void* Z2 = ctx->agg[0];
+  e = launch_fused_op_readout(a, h_last, R, s);
+  GnnArgs gh = g;
+  gh.node_off = a.totals + 2;               // rows = fused ops
+  launch_dense_bias_relu(gh, R, H, ctx->headW, ctx->head + HH, Z1, s);
+  launch_dense_bias_relu(gh, Z1, H, static_cast<char*>(ctx->headW) + HH * es, ctx->head + 2 * HH + H, Z2, s);
+  if (e == hipSuccess) e = launch_fused_op_times(a, Z2, ctx->head + 2 * HH + 2 * H, ctx->fo_pred, s);
+  if (prof) prof->end(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fused-op head launch");
   return DC_OK;
 }
 
@@ -369,6 +454,7 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
     e = hipMalloc(reinterpret_cast<void**>(&ctx->att), (size_t)cfg->L * 2 * cfg->H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->b), (size_t)cfg->L * cfg->H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->head), (2 * HH + 3 * cfg->H + 1) * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&ctx->headW, 2 * HH * es);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     dc_destroy(ctx);
@@ -388,6 +474,8 @@ dc_status dc_destroy(dc_ctx* ctx) {
   if (ctx->b) (void)hipFree(ctx->b);
   if (ctx->head) (void)hipFree(ctx->head);
   if (ctx->att) (void)hipFree(ctx->att);
+  if (ctx->headW) (void)hipFree(ctx->headW);
+  if (ctx->cost_mem) (void)hipFree(ctx->cost_mem);
   if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
   if (ctx->slab) (void)hipFree(ctx->slab);
   if (ctx->sim_scratch) (void)hipFree(ctx->sim_scratch);
@@ -421,7 +509,12 @@ static dc_status set_weights_common(dc_ctx* ctx, const float* W_layers, const fl
     for (size_t i = 0; i < HH; ++i) hd[HH + c.H + i] = rnd(hd[HH + c.H + i]);
     for (int i = 0; i < c.H; ++i) hd[2 * HH + 2 * c.H + i] = rnd(hd[2 * HH + 2 * c.H + i]);
   }
+  // W1 and W2 once more in the layout of a layer block: the fused-op path runs them as GEMMs
+  std::vector<char> hw(2 * HH * es);
+  pack_weights_host(head, c.H, c.H, 1, 1, bf16, hw.data());
+  pack_weights_host(head + HH + c.H, c.H, c.H, 1, 1, bf16, hw.data() + HH * es);
   hipError_t e = hipMemcpyAsync(ctx->W, packed.data(), nW * es, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(ctx->headW, hw.data(), hw.size(), hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->b, b_layers, (size_t)c.L * c.H * sizeof(float), hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->head, hd.data(), hd.size() * sizeof(float), hipMemcpyHostToDevice, s);
   if (e == hipSuccess && att)
@@ -458,6 +551,7 @@ dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_nod
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (g_node_off[0] != 0 || g_edge_off[0] != 0) return fail(ctx, DC_ERR_BAD_GRAPH, "offsets must start at 0");
   int max_gn = 0, max_ge = 0, min_need = INT32_MAX;
+  bool canonical = true;
   for (int b = 0; b < n_graphs; ++b) {
     const long long n = (long long)g_node_off[b + 1] - g_node_off[b];
     const long long e = (long long)g_edge_off[b + 1] - g_edge_off[b];
@@ -471,6 +565,9 @@ dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_nod
     const int32_t* ci = col + g_edge_off[b];
     for (long long k = 0; k < e; ++k)
       if (ci[k] < 0 || ci[k] >= n) return fail(ctx, DC_ERR_BAD_GRAPH, "col out of range");
+    for (long long v = 0; v < n && canonical; ++v)
+      for (long long k = rp[v]; k < rp[v + 1]; ++k)
+        if (ci[k] == v || (k > rp[v] && ci[k] <= ci[k - 1])) canonical = false;
     if (n > max_gn) max_gn = (int)n;
     if (e > max_ge) max_ge = (int)e;
     const int need = contract_working_set_bytes((int)n, (int)e);
@@ -571,6 +668,11 @@ dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_nod
   ctx->max_ge = max_ge;
   ctx->min_need = min_need;
   ctx->have_graphs = true;
+  ctx->bg_canonical = canonical;
+  ctx->bg_nodes = NT;
+  if (ctx->cost_mem) (void)hipFree(ctx->cost_mem);   // the profile belongs to the graphs it was recorded on
+  ctx->cost_mem = nullptr;
+  ctx->have_profile = false;
   return DC_OK;
 }
 
@@ -651,27 +753,13 @@ dc_status dc_simulate(dc_ctx* ctx, const dc_batch* in, const float* op_time, con
   hipLaunchKernelGGL(check_batch_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, s, in->node_off, in->n_cand,
                      (long long)(in->cap_nodes < k.NN ? in->cap_nodes : k.NN), (long long)in->cap_edges,
                      in->out_rowptr, in->out_col, in->in_rowptr, in->in_col, ctx->status);
-  SimArgs a;
-  a.n_cand = in->n_cand;
-  a.node_off = in->node_off;
-  a.out_rowptr = in->out_rowptr;
-  a.out_col = in->out_col;
-  a.in_rowptr = in->in_rowptr;
-  a.op_time = op_time;
-  a.ar_size = ar_size;
-  a.ar_c = ar_c;
-  a.ar_d = ar_d;
-  a.cost = cost;
-  a.lds_bytes = kSimLdsBytes;
-  a.scratch = ctx->sim_scratch;
-  a.scratch_stride = ctx->sim_stride;
-  a.n_slices = ctx->sim_slices;
-  a.status = ctx->status;
-  if (ctx->prof.on) ctx->prof.begin(kFamSimulate, s);
-  hipError_t e = launch_simulate(a, s);
-  if (ctx->prof.on) ctx->prof.end(s);
-  if (e != hipSuccess) return hip_fail(ctx, e, "simulator launch");
-  return DC_OK;
+  BatchView v{};
+  v.node_off = in->node_off;
+  v.out_rowptr = in->out_rowptr;
+  v.out_col = in->out_col;
+  v.in_rowptr = in->in_rowptr;
+  v.in_col = in->in_col;
+  return do_simulate(ctx, in->n_cand, v, op_time, ar_size, ar_c, ar_d, cost, s);
 }
 
 dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
@@ -688,6 +776,136 @@ dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
   dc_status st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s);
   if (st != DC_OK) return st;
   return do_forward(ctx, n_cand, ctx->ib, pred, s);
+}
+
+dc_status dc_set_profile(dc_ctx* ctx, const float* op_time, const float* ar_size, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!op_time || !ar_size) return fail(ctx, DC_ERR_INVALID_ARG, "null profile array");
+  if (!ctx->have_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_base_graphs has not been called");
+  if (!ctx->bg_canonical)
+    return fail(ctx, DC_ERR_BAD_GRAPH, "the cost path needs base rows strictly ascending (no duplicates, no self loops)");
+  const Caps k = caps_of(ctx->cfg);
+  if (k.NN < k.NB || k.NE < k.EB)
+    return fail(ctx, DC_ERR_CAPACITY, "the cost path runs the estimator on up to max_base_nodes rows: create the "
+                                      "context with max_nodes = 0 and max_edges = 0");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t es = ctx->cfg.dtype == DC_BF16 ? 2 : 4;
+  const long long NT = ctx->bg_nodes;
+  const long long cap_ops = k.NB / 2 + 1;
+  FusedOpsArgs f{};
+  float *tb = nullptr, *xb = nullptr, *mt = nullptr, *mx = nullptr, *fp = nullptr;
+  size_t bytes = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    Arena a;
+    a.base = pass ? ctx->cost_mem : nullptr;
+    tb = a.take<float>(NT + 1);
+    xb = a.take<float>(NT + 1);
+    f.gfm = a.take<int>(k.NB + k.C + 1);
+    f.gfk = a.take<int>(k.NB + k.C + 1);
+    f.dgo = a.take<int>(k.NB + k.C + 1);
+    f.dgi = a.take<int>(k.NB + k.C + 1);
+    f.cnt = a.take<int>(3 * (k.C + 1));
+    f.totals = a.take<int>(64);
+    f.fb.node_off = a.take<int>(cap_ops + 1);
+    f.fb.edge_off = a.take<int>(cap_ops + 1);
+    f.fo_cnode = a.take<int>(cap_ops + 1);
+    f.fb.new_id = a.take<int>(k.NB + 1);
+    f.fb.out_rowptr = a.take<int>(k.NB + 1);
+    f.fb.in_rowptr = a.take<int>(k.NB + 1);
+    f.fb.out_col = a.take<int>(k.EB + 1);
+    f.fb.in_col = a.take<int>(k.EB + 1);
+    f.fb.Xc = a.take<char>((size_t)(k.NB + 1) * ctx->cfg.F * es);
+    mt = a.take<float>(k.NN + 1);
+    mx = a.take<float>(k.NN + 1);
+    fp = a.take<float>(cap_ops + 1);
+    bytes = a.off;
+    if (pass == 0) {
+      (void)hipDeviceSynchronize();   // earlier calls may still use the old block
+      if (ctx->cost_mem) (void)hipFree(ctx->cost_mem);
+      ctx->cost_mem = nullptr;
+      ctx->have_profile = false;
+      if (hipMalloc(reinterpret_cast<void**>(&ctx->cost_mem), bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->cost_mem = nullptr;
+        return fail(ctx, DC_ERR_OOM, "cost path allocation failed");
+      }
+    }
+  }
+  f.fb.cap_nodes = k.NB;
+  f.fb.cap_edges = k.EB;
+  f.cap_ops = cap_ops;
+  f.cap_rows = k.NB;
+  f.cap_edges = k.EB;
+  f.op_time_base = tb;
+  f.ar_size_base = xb;
+  f.F = ctx->cfg.F;
+  f.H = ctx->cfg.H;
+  f.bf16 = ctx->cfg.dtype == DC_BF16;
+  f.status = ctx->status;
+  f.n_cu = ctx->n_cu;
+  hipError_t e = hipMemsetAsync(f.totals, 0, 64 * sizeof(int), s);
+  if (e == hipSuccess && NT > 0) e = hipMemcpyAsync(tb, op_time, (size_t)NT * sizeof(float), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && NT > 0) e = hipMemcpyAsync(xb, ar_size, (size_t)NT * sizeof(float), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "dc_set_profile copy");
+  ctx->fo = f;
+  ctx->m_op_time = mt;
+  ctx->m_ar_size = mx;
+  ctx->fo_pred = fp;
+  ctx->have_profile = true;
+  return DC_OK;
+}
+
+static dc_status cost_call_check(dc_ctx* ctx, int32_t n_cand) {
+  if (n_cand < 0) return fail(ctx, DC_ERR_INVALID_ARG, "negative count");
+  if (!ctx->have_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_base_graphs has not been called");
+  if (!ctx->have_weights) return fail(ctx, DC_ERR_INVALID_ARG, "the estimator weights have not been set");
+  if (!ctx->have_profile) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_profile has not been called");
+  if (n_cand > ctx->cfg.max_cand) return fail(ctx, DC_ERR_CAPACITY, "n_cand exceeds max_cand");
+  return DC_OK;
+}
+
+dc_status dc_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                          const int32_t* group_id, dc_batch* out, float* op_time, float* ar_size, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  dc_status st = cost_call_check(ctx, n_cand);
+  if (st != DC_OK) return st;
+  if (n_cand > 0 && (!op_time || !ar_size)) return fail(ctx, DC_ERR_INVALID_ARG, "null output array");
+  st = dc_contract_graphs(ctx, n_cand, cand_graph, cand_off, group_id, out, stream);
+  if (st != DC_OK || n_cand == 0) return st;
+  BatchView v{};
+  v.node_off = out->node_off;
+  v.new_id = out->new_id;
+  return do_module_times(ctx, n_cand, cand_graph, cand_off, v, op_time, ar_size, static_cast<hipStream_t>(stream));
+}
+
+dc_status dc_cost_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                             const int32_t* group_id, float ar_c, float ar_d, float* cost, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  dc_status st = cost_call_check(ctx, n_cand);
+  if (st != DC_OK) return st;
+  if (n_cand == 0) return DC_OK;
+  if (!cand_graph || !cand_off || !group_id || !cost) return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s);
+  if (st != DC_OK) return st;
+  st = do_module_times(ctx, n_cand, cand_graph, cand_off, ctx->ib, ctx->m_op_time, ctx->m_ar_size, s);
+  if (st != DC_OK) return st;
+  return do_simulate(ctx, n_cand, ctx->ib, ctx->m_op_time, ctx->m_ar_size, ar_c, ar_d, cost, s);
+}
+
+dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, int64_t* n_edges, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!ctx->have_profile) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_profile has not been called");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(ctx->h_pinned + 8, ctx->fo.totals, 8 * sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "dc_last_fused_ops");
+  if (n_rows) *n_rows = ctx->h_pinned[8 + 1];
+  if (n_fused_ops) *n_fused_ops = ctx->h_pinned[8 + 3];
+  if (n_edges) *n_edges = ctx->h_pinned[8 + 4];
+  return DC_OK;
 }
 
 dc_status dc_check(dc_ctx* ctx, void* stream) {

@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamSimulate, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamSimulate, kFamFusedOps, kFamFusedHead, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -115,6 +115,11 @@ struct GnnArgs {
   float* score[2] = {nullptr, nullptr};   // per node and head: a_src . z, a_dst . z  [max_nodes, heads]
 };
 hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s);
+// The message-passing layers alone; *h_last receives the final embeddings [node_off[n_cand], H].
+hipError_t launch_gnn_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const void** h_last);
+// out = ReLU(A Wp + bias) for the node_off[n_cand] rows of A [rows, d]; Wp in the device layout of one layer block.
+void launch_dense_bias_relu(const GnnArgs& a, const void* A, int d, const void* Wp, const float* bias, void* out,
+                            hipStream_t s);
 // Elements (of the storage dtype) of all layer matrices in device layout; nseg row blocks of
 // d rows per layer (3: self / predecessor mean / successor mean; 1: attention).
 size_t packed_weight_elems(int F, int H, int L, int nseg);
@@ -158,6 +163,41 @@ struct SimArgs {
 size_t simulate_scratch_bytes(long long max_graph_nodes, long long max_graph_edges, int n_slices);
 hipError_t launch_simulate(const SimArgs& a, hipStream_t s);
 
+// fused_ops.hip: the batch of fused-op subgraphs of the candidates just contracted, and the
+// per-node times the simulator takes
+struct FusedOpsArgs {
+  BaseGraphs bg;
+  const float* op_time_base;   // [sum N_b] profiled time of each op
+  const float* ar_size_base;   // [sum N_b] tensor size of each all-reduce node, negative for ops
+  int n_cand;
+  const int* cand_graph;
+  const int* cand_off;
+  const int* members;          // left by the contraction: base nodes grouped by contracted node
+  const int* mstart;           // start of each group in members (slot cand_off[c] + c)
+  const int* Gc;               // contracted node count per candidate
+  const int* new_id;           // contracted node (local) of each base node
+  const int* c_node_off;       // [C+1] contracted node offsets
+  // scratch, slot cand_off[c] + c with one extra entry per candidate
+  int* gfm;                    // per group: rows of fused ops before it (local)
+  int* gfk;                    // per group: fused ops before it (local)
+  int* dgo;                    // per member position: edges inside groups before it, successors
+  int* dgi;                    // the same, predecessors
+  int* cnt;                    // [3][C+1] fused ops / rows / edges per candidate, scanned in place
+  int* totals;                 // {0, rows} {0, fused ops} edges
+  BatchView fb;                // one graph per fused op; new_id holds the base node of each row
+  int* fo_cnode;               // contracted node (global) of each fused op
+  long long cap_ops, cap_rows, cap_edges;
+  float* op_time;              // [contracted nodes] out
+  float* ar_size;              // [contracted nodes] out
+  int F, H, bf16;
+  int* status;
+  int n_cu;
+};
+hipError_t launch_fused_op_extract(const FusedOpsArgs& a, Profiler* prof, hipStream_t s);
+hipError_t launch_fused_op_readout(const FusedOpsArgs& a, const void* h_last, void* R, hipStream_t s);
+hipError_t launch_fused_op_times(const FusedOpsArgs& a, const void* Z2, const float* w3b3, float* fo_pred,
+                                 hipStream_t s);
+
 __global__ void reset_status_kernel(int* status);
 
 // fp32 -> bf16, round to nearest even, in hardware (v_cvt_pk_bf16_f32): a in the low half
@@ -186,6 +226,44 @@ __device__ __forceinline__ void bf16_pair_add(float& lo, float& hi, unsigned x, 
   const bf16x2_t v = __builtin_bit_cast(bf16x2_t, x);
   lo = __builtin_amdgcn_fdot2_f32_bf16(v, __builtin_bit_cast(bf16x2_t, one), lo, false);
   hi = __builtin_amdgcn_fdot2_f32_bf16(v, __builtin_bit_cast(bf16x2_t, one << 16), hi, false);
+}
+
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int y = __shfl_up(x, o, 64);
+    if (lane >= o) x += y;
+  }
+  return x;
+}
+
+// Exclusive scan of in[0..n) into out[0..n) (may alias) by the whole workgroup;
+// returns the total.  Each thread owns a contiguous chunk.  Ends with a barrier.
+__device__ __forceinline__ int block_exscan(const int* in, int* out, int n, int* wsum) {
+  const int t = threadIdx.x, T = blockDim.x;
+  const int K = (n + T - 1) / T;
+  const int lo = min(t * K, n), hi = min(lo + K, n);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += in[i];
+  const int inc = wave_incl_scan(s);
+  if ((t & 63) == 63) wsum[t >> 6] = inc;
+  __syncthreads();
+  int woff = 0, total = 0;
+  const int nw = T >> 6;
+  for (int i = 0; i < nw; ++i) {
+    int x = wsum[i];
+    if (i < (t >> 6)) woff += x;
+    total += x;
+  }
+  int run = woff + inc - s;
+  for (int i = lo; i < hi; ++i) {
+    int x = in[i];
+    out[i] = run;
+    run += x;
+  }
+  __syncthreads();
+  return total;
 }
 
 static inline __host__ __device__ int ceil_div(int a, int b) { return (a + b - 1) / b; }

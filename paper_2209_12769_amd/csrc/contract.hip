@@ -50,44 +50,6 @@ __host__ __device__ inline Slab slab_layout(int N, int E) {
   return s;
 }
 
-__device__ __forceinline__ int wave_incl_scan(int x) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int y = __shfl_up(x, o, 64);
-    if (lane >= o) x += y;
-  }
-  return x;
-}
-
-// Exclusive scan of in[0..n) into out[0..n) (may alias) by the whole workgroup;
-// returns the total.  Each thread owns a contiguous chunk.  Ends with a barrier.
-__device__ __forceinline__ int block_exscan(const int* in, int* out, int n, int* wsum) {
-  const int t = threadIdx.x, T = blockDim.x;
-  const int K = (n + T - 1) / T;
-  const int lo = min(t * K, n), hi = min(lo + K, n);
-  int s = 0;
-  for (int i = lo; i < hi; ++i) s += in[i];
-  const int inc = wave_incl_scan(s);
-  if ((t & 63) == 63) wsum[t >> 6] = inc;
-  __syncthreads();
-  int woff = 0, total = 0;
-  const int nw = T >> 6;
-  for (int i = 0; i < nw; ++i) {
-    int x = wsum[i];
-    if (i < (t >> 6)) woff += x;
-    total += x;
-  }
-  int run = woff + inc - s;
-  for (int i = lo; i < hi; ++i) {
-    int x = in[i];
-    out[i] = run;
-    run += x;
-  }
-  __syncthreads();
-  return total;
-}
-
 // Short lists (up to 16 entries) are sorted by one thread each, in registers, with a
 // fixed compare-exchange network (Batcher's odd-even merge sort): no dependent chain
 // through memory, and the same instruction stream for every lane.  Unused places hold

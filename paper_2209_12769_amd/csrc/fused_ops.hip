@@ -1,0 +1,361 @@
+// Times of the nodes of a candidate module, as the simulator needs them (gfx950).
+//
+// The cost model of the paper is a composition (Sec. 3.1, Simulator): profiled data for
+// individual ops, the GNN estimator for fused ops, a linear model on the tensor size for
+// all-reduce instructions.  A fused op is the subgraph of its original ops with the
+// dependencies among them (Sec. 3.3), so the estimator runs on a batch with one small graph
+// per fused op.  The kernels here build that batch from what the contraction leaves behind
+// (members grouped by contracted node, ascending), and afterwards turn the estimator's
+// embeddings into times:
+//
+//   fo_count_kernel   per candidate: classifies every contracted node (bucket of tensors /
+//                     single op / fused op / mixture), writes the times that need no
+//                     estimator, counts fused ops, their rows and their internal edges
+//   fo_scan_kernel    offsets of every candidate's share of the fused-op batch
+//   fo_fill_kernel    writes the batch: one graph per fused op, rows = members in ascending
+//                     base index with their own features, edges = base edges inside the group
+//   fo_readout_kernel sum of the final embeddings over the rows of each fused op
+//                     (Sec. 3.3.1, second equation), fp64 accumulation in row order
+//   (two dense layers with bias and ReLU on those sums run in the layer kernels' GEMM)
+//   fo_time_kernel    last layer of the regression network (Sec. 3.3.2), clamped at zero,
+//                     scattered to the fused op's node of the module
+//
+// Per contracted node: all members tensors: size = sum of the members' sizes (Sec. 2.3), fp64
+// in ascending member order, rounded once; one op: its profiled time; two or more ops: the
+// estimate; ops and tensors mixed: +infinity (no strategy of Sec. 3.2 produces it).
+// Base rows must be strictly ascending (no duplicates, no self loops): the count of edges
+// inside a group is then exact without sorting.
+#include <math.h>
+
+#include "common.h"
+
+namespace dc {
+namespace {
+
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
+  __shared__ int wsum[8];
+  if (a.status[0] != 0) return;
+  const int c = blockIdx.x, t = threadIdx.x, T = blockDim.x;
+  const int b = a.cand_graph[c];
+  const int coff = a.cand_off[c], N = a.cand_off[c + 1] - coff, nslot = coff + c;
+  const int G = a.Gc[c], gb = a.bg.gno[b], n0 = a.c_node_off[c];
+  const int* ms = a.mstart + nslot;
+  const int* mem = a.members + coff;
+  const int* nid = a.new_id + coff;
+  const float* tb = a.op_time_base + gb;
+  const float* xb = a.ar_size_base + gb;
+  int* gfm = a.gfm + nslot;
+  int* gfk = a.gfk + nslot;
+  for (int g = t; g < G; g += T) {
+    const int s = ms[g], e = ms[g + 1], n = e - s;
+    int n_ar = 0;
+    double size = 0.0;
+    for (int m = s; m < e; ++m) {
+      const float x = xb[mem[m]];
+      if (x >= 0.0f) {
+        ++n_ar;
+        size += (double)x;
+      }
+    }
+    const bool fused = n_ar == 0 && n >= 2;
+    float ot, as;
+    if (n_ar == n) {
+      ot = 0.0f;
+      as = (float)size;
+    } else if (n_ar == 0) {
+      ot = n == 1 ? tb[mem[s]] : 0.0f;      // a fused op's time is written by fo_time_kernel
+      as = -1.0f;
+    } else {
+      ot = INFINITY;
+      as = -1.0f;
+    }
+    a.op_time[n0 + g] = ot;
+    a.ar_size[n0 + g] = as;
+    gfm[g] = fused ? n : 0;
+    gfk[g] = fused ? 1 : 0;
+  }
+  __syncthreads();
+  const int Mc = block_exscan(gfm, gfm, G, wsum);
+  const int Kc = block_exscan(gfk, gfk, G, wsum);
+  if (t == 0) {
+    gfm[G] = Mc;
+    gfk[G] = Kc;
+  }
+  __syncthreads();
+  // edges inside a group, per member (in member order), both directions
+  const int* rp = a.bg.rowptr + gb + b;
+  const int* ci = a.bg.col + a.bg.geo[b];
+  const int* crp = a.bg.crowptr + gb + b;
+  const int* cci = a.bg.ccol + a.bg.geo[b];
+  int* dgo = a.dgo + nslot;
+  int* dgi = a.dgi + nslot;
+  for (int i = t; i < N; i += T) {
+    const int u = mem[i], g = nid[u];
+    int no = 0, ni = 0;
+    if (gfm[g + 1] != gfm[g]) {
+      for (int k = rp[u]; k < rp[u + 1]; ++k) no += nid[ci[k]] == g;
+      for (int k = crp[u]; k < crp[u + 1]; ++k) ni += nid[cci[k]] == g;
+    }
+    dgo[i] = no;
+    dgi[i] = ni;
+  }
+  __syncthreads();
+  const int Eo = block_exscan(dgo, dgo, N, wsum);
+  const int Ei = block_exscan(dgi, dgi, N, wsum);
+  if (t == 0) {
+    dgo[N] = Eo;
+    dgi[N] = Ei;
+    a.cnt[c] = Kc;
+    a.cnt[a.n_cand + 1 + c] = Mc;
+    a.cnt[2 * (a.n_cand + 1) + c] = Eo;
+    if (Eo != Ei) set_error(a.status, (int)DC_ERR_BAD_GRAPH);
+  }
+}
+
+__global__ __launch_bounds__(1024) void fo_scan_kernel(FusedOpsArgs a) {
+  __shared__ int wsum[16];
+  if (a.status[0] != 0) return;
+  const int C = a.n_cand;
+  int* cK = a.cnt;
+  int* cM = a.cnt + (C + 1);
+  int* cE = a.cnt + 2 * (C + 1);
+  const int K = block_exscan(cK, cK, C, wsum);
+  const int M = block_exscan(cM, cM, C, wsum);
+  const int E = block_exscan(cE, cE, C, wsum);
+  if (threadIdx.x == 0) {
+    cK[C] = K;
+    cM[C] = M;
+    cE[C] = E;
+    if (K > a.cap_ops || M > a.cap_rows || E > a.cap_edges) {
+      set_error(a.status, (int)DC_ERR_CAPACITY);
+      a.totals[1] = 0;
+      a.totals[3] = 0;
+      return;
+    }
+    a.totals[0] = 0;       // {0, rows}: offsets of the whole batch as one graph, for the layer kernels
+    a.totals[1] = M;
+    a.totals[2] = 0;       // {0, fused ops}: the same for the dense layers of the regression network
+    a.totals[3] = K;
+    a.totals[4] = E;
+    a.fb.node_off[K] = M;
+    a.fb.edge_off[K] = E;
+    a.fb.out_rowptr[M] = E;
+    a.fb.in_rowptr[M] = E;
+  }
+}
+
+// position of w in the ascending list m[0..n)
+__device__ __forceinline__ int rank_in(const int* m, int n, int w) {
+  int lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (m[mid] <= w) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <bool kBf16>
+__global__ __launch_bounds__(256) void fo_fill_kernel(FusedOpsArgs a) {
+  if (a.status[0] != 0) return;
+  const int c = blockIdx.x, t = threadIdx.x, T = blockDim.x, C = a.n_cand;
+  const int b = a.cand_graph[c];
+  const int coff = a.cand_off[c], N = a.cand_off[c + 1] - coff, nslot = coff + c;
+  const int G = a.Gc[c], gb = a.bg.gno[b], n0 = a.c_node_off[c];
+  const int k0 = a.cnt[c], m0 = a.cnt[C + 1 + c], e0 = a.cnt[2 * (C + 1) + c];
+  const int Mc = a.cnt[C + 1 + c + 1] - m0;
+  const int* ms = a.mstart + nslot;
+  const int* mem = a.members + coff;
+  const int* nid = a.new_id + coff;
+  const int* gfm = a.gfm + nslot;
+  const int* gfk = a.gfk + nslot;
+  const int* dgo = a.dgo + nslot;
+  const int* dgi = a.dgi + nslot;
+  for (int g = t; g < G; g += T) {
+    if (gfm[g + 1] == gfm[g]) continue;
+    const int k = k0 + gfk[g];
+    a.fb.node_off[k] = m0 + gfm[g];
+    a.fb.edge_off[k] = e0 + dgo[ms[g]];
+    a.fo_cnode[k] = n0 + g;
+  }
+  const int* rp = a.bg.rowptr + gb + b;
+  const int* ci = a.bg.col + a.bg.geo[b];
+  const int* crp = a.bg.crowptr + gb + b;
+  const int* cci = a.bg.ccol + a.bg.geo[b];
+  for (int i = t; i < N; i += T) {
+    const int u = mem[i], g = nid[u];
+    if (gfm[g + 1] == gfm[g]) continue;
+    const int s = ms[g], n = ms[g + 1] - s;
+    const int first = m0 + gfm[g];            // row of the group's first member
+    const int row = first + (i - s);
+    a.fb.new_id[row] = u;
+    int ko = e0 + dgo[i], ki = e0 + dgi[i];
+    a.fb.out_rowptr[row] = ko;
+    a.fb.in_rowptr[row] = ki;
+    for (int k = rp[u]; k < rp[u + 1]; ++k) {
+      const int w = ci[k];
+      if (nid[w] == g) a.fb.out_col[ko++] = first + rank_in(mem + s, n, w);
+    }
+    for (int k = crp[u]; k < crp[u + 1]; ++k) {
+      const int w = cci[k];
+      if (nid[w] == g) a.fb.in_col[ki++] = first + rank_in(mem + s, n, w);
+    }
+  }
+  __syncthreads();          // fb.new_id of this candidate's rows is complete
+  const int q = a.F >> 2;
+  const float4* X4 = reinterpret_cast<const float4*>(a.bg.X) + (size_t)gb * q;
+  for (int i = t; i < Mc * q; i += T) {
+    const int r = i / q, f = i - r * q;
+    const size_t row = (size_t)(m0 + r);
+    const float4 x = X4[(size_t)a.fb.new_id[row] * q + f];
+    if (kBf16) {
+      uint2 p;
+      p.x = pack_bf16x2(x.x, x.y);
+      p.y = pack_bf16x2(x.z, x.w);
+      reinterpret_cast<uint2*>(a.fb.Xc)[row * q + f] = p;
+    } else {
+      reinterpret_cast<float4*>(a.fb.Xc)[row * q + f] = x;
+    }
+  }
+}
+
+template <bool kBf16>
+__device__ __forceinline__ void load8(const void* base, size_t row, int H, int ll, float (&x)[8]) {
+  if constexpr (kBf16) {
+    const v4u r = reinterpret_cast<const v4u*>(base)[row * (size_t)(H >> 3) + ll];
+    x[0] = __uint_as_float(r.x << 16);
+    x[1] = __uint_as_float(r.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(r.y << 16);
+    x[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(r.z << 16);
+    x[5] = __uint_as_float(r.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(r.w << 16);
+    x[7] = __uint_as_float(r.w & 0xFFFF0000u);
+  } else {
+    const float4* p = reinterpret_cast<const float4*>(base) + row * (size_t)(H >> 2) + 2 * ll;
+    const float4 u = p[0], v = p[1];
+    x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+    x[4] = v.x; x[5] = v.y; x[6] = v.z; x[7] = v.w;
+  }
+}
+
+// r_k = sum over the rows of fused op k of the final embeddings.  H / 8 lanes per fused op,
+// eight columns each; the rows of a fused op are contiguous, two of them in flight.
+template <bool kBf16>
+__global__ __launch_bounds__(256) void fo_readout_kernel(const void* __restrict__ h, int H,
+                                                          const int* __restrict__ node_off,
+                                                          const int* __restrict__ totals, void* __restrict__ R,
+                                                          const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int K = totals[3];
+  const int LPR = H >> 3, per_wave = 64 / LPR;
+  const int lane = threadIdx.x & 63, sg = lane / LPR, ll = lane - sg * LPR;
+  if (sg >= per_wave) return;
+  const long long wave0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
+  for (long long k = wave0 * per_wave + sg; k < K; k += nwaves * per_wave) {
+    const int p0 = node_off[k], p1 = node_off[k + 1];
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int p = p0;
+    for (; p + 1 < p1; p += 2) {
+      float x[8], y[8];
+      load8<kBf16>(h, (size_t)p, H, ll, x);
+      load8<kBf16>(h, (size_t)p + 1, H, ll, y);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = (acc[i] + (double)x[i]) + (double)y[i];
+    }
+    if (p < p1) {
+      float x[8];
+      load8<kBf16>(h, (size_t)p, H, ll, x);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += (double)x[i];
+    }
+    if constexpr (kBf16) {
+      v4u o;
+      o.x = pack_bf16x2((float)acc[0], (float)acc[1]);
+      o.y = pack_bf16x2((float)acc[2], (float)acc[3]);
+      o.z = pack_bf16x2((float)acc[4], (float)acc[5]);
+      o.w = pack_bf16x2((float)acc[6], (float)acc[7]);
+      reinterpret_cast<v4u*>(R)[(size_t)k * LPR + ll] = o;
+    } else {
+      float4* o = reinterpret_cast<float4*>(R) + (size_t)k * (H >> 2) + 2 * ll;
+      o[0] = make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]);
+      o[1] = make_float4((float)acc[4], (float)acc[5], (float)acc[6], (float)acc[7]);
+    }
+  }
+}
+
+// t_k = max(0, z2_k . w3 + b3) -> op_time of the fused op's node; the raw value also goes to
+// fo_pred when that is not null.  fp64 accumulation, lanes added in ascending order.
+template <bool kBf16>
+__global__ __launch_bounds__(256) void fo_time_kernel(const void* __restrict__ Z, int H,
+                                                       const float* __restrict__ w3b3,
+                                                       const int* __restrict__ fo_cnode,
+                                                       const int* __restrict__ totals, float* __restrict__ op_time,
+                                                       float* __restrict__ fo_pred, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int K = totals[3];
+  const int LPR = H >> 3, per_wave = 64 / LPR;
+  const int lane = threadIdx.x & 63, sg = lane / LPR, ll = lane - sg * LPR, hb = sg * LPR;
+  const bool active = sg < per_wave;
+  const long long wave0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
+  float w[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) w[i] = active ? w3b3[ll * 8 + i] : 0.0f;
+  const double b3 = (double)w3b3[H];
+  for (long long k0 = wave0 * per_wave; k0 < K; k0 += nwaves * per_wave) {      // wave-uniform trip count
+    const long long k = k0 + sg;
+    double part = 0.0;
+    if (active && k < K) {
+      float x[8];
+      load8<kBf16>(Z, (size_t)k, H, ll, x);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part += (double)x[i] * (double)w[i];
+    }
+    double sum = b3;
+    for (int j = 0; j < LPR; ++j) sum += __shfl(part, (hb + j) & 63, 64);
+    if (active && k < K && ll == 0) {
+      const float tk = (float)sum;
+      op_time[fo_cnode[k]] = tk > 0.0f ? tk : 0.0f;
+      if (fo_pred) fo_pred[k] = tk;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_fused_op_extract(const FusedOpsArgs& a, Profiler* prof, hipStream_t s) {
+  if (a.n_cand <= 0) return hipSuccess;
+  if (prof) prof->begin(kFamFusedOps, s);
+  hipLaunchKernelGGL(fo_count_kernel, dim3(a.n_cand), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(fo_scan_kernel, dim3(1), dim3(1024), 0, s, a);
+  if (a.bf16) hipLaunchKernelGGL(fo_fill_kernel<true>, dim3(a.n_cand), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(fo_fill_kernel<false>, dim3(a.n_cand), dim3(256), 0, s, a);
+  if (prof) prof->end(s);
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_op_readout(const FusedOpsArgs& a, const void* h_last, void* R, hipStream_t s) {
+  const dim3 grid(a.n_cu * 8), block(256);
+  if (a.bf16)
+    hipLaunchKernelGGL(fo_readout_kernel<true>, grid, block, 0, s, h_last, a.H, a.fb.node_off, a.totals, R, a.status);
+  else
+    hipLaunchKernelGGL(fo_readout_kernel<false>, grid, block, 0, s, h_last, a.H, a.fb.node_off, a.totals, R, a.status);
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_op_times(const FusedOpsArgs& a, const void* Z2, const float* w3b3, float* fo_pred,
+                                 hipStream_t s) {
+  const dim3 grid(a.n_cu * 8), block(256);
+  if (a.bf16)
+    hipLaunchKernelGGL(fo_time_kernel<true>, grid, block, 0, s, Z2, a.H, w3b3, a.fo_cnode, a.totals, a.op_time,
+                       fo_pred, a.status);
+  else
+    hipLaunchKernelGGL(fo_time_kernel<false>, grid, block, 0, s, Z2, a.H, w3b3, a.fo_cnode, a.totals, a.op_time,
+                       fo_pred, a.status);
+  return hipGetLastError();
+}
+
+}  // namespace dc

@@ -469,10 +469,19 @@ hipError_t mean_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const vo
 
 }  // namespace
 
+hipError_t launch_gnn_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const void** h_last) {
+  return a.heads > 0 ? attention_layers(a, prof, s, h_last) : mean_layers(a, prof, s, h_last);
+}
+
+void launch_dense_bias_relu(const GnnArgs& a, const void* A, int d, const void* Wp, const float* bias, void* out,
+                            hipStream_t s) {
+  run_update(a, A, nullptr, nullptr, d, 1, Wp, bias, out, s);
+}
+
 hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   if (a.n_cand <= 0) return hipSuccess;
   const void* hcur = nullptr;
-  hipError_t e = a.heads > 0 ? attention_layers(a, prof, s, &hcur) : mean_layers(a, prof, s, &hcur);
+  hipError_t e = launch_gnn_layers(a, prof, s, &hcur);
   if (e != hipSuccess) return e;
   if (prof) prof->begin(kFamReadout, s);
   if (a.bf16)

@@ -1,0 +1,246 @@
+"""GPU parity of the Cost(H) composition (Secs. 3.1, 3.3, 3.4) against the CPU oracle, through
+the C ABI: times and tensor sizes of every node of the candidate modules (dc_module_times) and
+the end-to-end time (dc_cost_candidates).
+
+Tensor sizes, profiled times and the classification of every node are exact; the estimate of a
+fused op is floating point (rel 1e-5 fp32, 2e-2 bf16, measured against max(|estimate|, 1e-3 of
+the median estimate)).  The schedule's order does not depend on the durations, so the cost is a
+fixed max-plus expression of them and inherits their relative tolerance."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2209_12769_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_12769_amd import binding
+    binding.lib()
+    return binding
+
+
+def positive(w):
+    """The same workload with the last bias of the regression network raised by one, so that
+    most estimates are positive and the clamp at zero does not hide them."""
+    wt = w.weights
+    head = wt.head.copy()
+    head[-1] += 1.0
+    return wl.Workload(w.name, w.model, w.graphs, w.cand_graph, w.cand_off, w.group_id,
+                       wl.Weights(wt.layers, wt.biases, head, wt.att), w.note)
+
+
+def sizes(w):
+    nb = int(w.cand_off[-1])
+    geo = w.g_edge_off()
+    eb = int(sum(int(geo[b + 1] - geo[b]) for b in w.cand_graph))
+    return nb, eb
+
+
+def gpu_module_times(B, w, t, x):
+    ev = B.evaluator_for(w)
+    ev.set_profile(t, x)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    nb, eb = sizes(w)
+    batch = ev.alloc_batch(w.n_cand, nb, nb, eb)
+    op_time, ar_size = ev.module_times(cg, co, gid, batch)
+    st = ev.check()
+    ntot, _ = ev.last_totals()
+    counts = ev.last_fused_ops()
+    out = (op_time[:ntot].cpu().numpy(), ar_size[:ntot].cpu().numpy(), batch.node_off.cpu().numpy(), counts, st)
+    ev.close()
+    return out
+
+
+def gpu_cost(B, w, t, x, c, d):
+    ev = B.evaluator_for(w)
+    ev.set_profile(t, x)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    cost = ev.cost_candidates(cg, co, gid, c, d).cpu().numpy()
+    st = ev.check()
+    again = ev.cost_candidates(cg, co, gid, c, d).cpu().numpy()
+    assert np.array_equal(cost, again, equal_nan=True)
+    ev.close()
+    return cost, st
+
+
+def check_times(w, got_t, got_x, ref_b, t, x):
+    want_t, want_x, fo, cnode, fo_pred = orc.module_times(w, ref_b, t, x, want_fused=True)
+    assert np.array_equal(got_x, want_x)
+    fused = np.zeros(ref_b.ntot, bool)
+    fused[cnode] = True
+    assert np.array_equal(got_t[~fused], want_t[~fused])
+    if fo.n_cand:
+        floor = 1e-3 * float(np.median(np.abs(fo_pred)))
+        scale = np.maximum(np.abs(fo_pred), floor)
+        err = np.abs(got_t[cnode] - want_t[cnode]) / scale
+        assert err.max() <= TOL[w.model.dtype], (w.name, err.max(), int(err.argmax()))
+        return float(err.max()), fo, fo_pred
+    return 0.0, fo, fo_pred
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 5), ("cfg2", 48), ("cfg3", 40), ("cfg4", 12), ("cfg5", 12)])
+def test_module_times_of_the_configurations(B, name, n):
+    w = positive(wl.make(name, n, n_graphs=12) if name == "cfg5" else wl.make(name, n))
+    t, x = wl.profile_of(w)
+    ref_b = orc.contract(w)
+    got_t, got_x, node_off, counts, st = gpu_module_times(B, w, t, x)
+    assert st == B.DC_OK
+    assert np.array_equal(node_off, ref_b.node_off)
+    err, fo, fo_pred = check_times(w, got_t, got_x, ref_b, t, x)
+    assert counts == (fo.n_cand, fo.ntot, fo.etot)
+    assert np.mean(fo_pred > 0) > 0.5
+    print(f"[module_times] {name} C={n}: {fo.n_cand} fused ops, {fo.ntot} rows, {fo.etot} edges, "
+          f"max rel err {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 5), ("cfg2", 48), ("cfg3", 40), ("cfg4", 12)])
+def test_cost_of_the_configurations(B, name, n):
+    w = positive(wl.make(name, n))
+    t, x = wl.profile_of(w)
+    for c, d in ((0.02, 0.01), (0.5, 0.3)):
+        want = orc.cost(w, t, x, c, d)
+        got, st = gpu_cost(B, w, t, x, c, d)
+        assert st == B.DC_OK
+        assert np.all(np.isfinite(want)) and np.all(np.isfinite(got))
+        err = np.abs(got - want) / np.abs(want)
+        assert err.max() <= TOL[w.model.dtype], (name, c, d, err.max())
+    print(f"[cost] {name} C={n}: cost {want.min():.3f} .. {want.max():.3f}, max rel err {err.max():.2e}", flush=True)
+
+
+def test_cost_is_the_simulator_on_the_module_times(B):
+    import torch
+    w = positive(wl.make("cfg3", 24))
+    t, x = wl.profile_of(w)
+    ev = B.evaluator_for(w)
+    ev.set_profile(t, x)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    nb, eb = sizes(w)
+    batch = ev.alloc_batch(w.n_cand, nb, nb, eb)
+    op_time, ar_size = ev.module_times(cg, co, gid, batch)
+    two_step = ev.simulate(batch, op_time, ar_size, 0.02, 0.01).cpu().numpy()
+    one_call = ev.cost_candidates(cg, co, gid, 0.02, 0.01).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    assert np.array_equal(two_step, one_call)
+    # and the simulator's own parity: the oracle on the device's times gives the same bits
+    ref_b = orc.contract(w)
+    ntot = ref_b.ntot
+    want = orc.simulate(ref_b, op_time[:ntot].cpu().numpy(), ar_size[:ntot].cpu().numpy(), 0.02, 0.01)
+    assert np.array_equal(one_call, want)
+    ev.close()
+
+
+def test_attention_estimator(B):
+    w = positive(wl.with_attention(wl.make("cfg3", 16), 4))
+    t, x = wl.profile_of(w)
+    ref_b = orc.contract(w)
+    got_t, got_x, _, _, st = gpu_module_times(B, w, t, x)
+    assert st == B.DC_OK
+    err, fo, _ = check_times(w, got_t, got_x, ref_b, t, x)
+    want = orc.cost(w, t, x, 0.02, 0.01)
+    got, st = gpu_cost(B, w, t, x, 0.02, 0.01)
+    assert st == B.DC_OK and np.max(np.abs(got - want) / np.abs(want)) <= TOL["bf16"]
+    print(f"[module_times] attention: {fo.n_cand} fused ops, max rel err {err:.2e}", flush=True)
+
+
+def edge_case_workload(dtype):
+    """One random DAG of 300 ops and 12 tensors with: the all-singleton partition (no fused op),
+    all ops in one group, one group that mixes an op with a tensor, arbitrary labels (cyclic
+    quotients), and all tensors in one bucket."""
+    n_op, n_ar = 300, 12
+    g0 = wl.random_dag(77, n_op, 0.02, 32)
+    rng = wl.Rng(77, 11)
+    src = np.concatenate([np.repeat(np.arange(n_op), np.diff(g0.rowptr)), rng.integers(0, n_op - 1, n_ar)])
+    dst = np.concatenate([g0.col, n_op + np.arange(n_ar)])
+    rp, ci = wl._csr_from_edges(n_op + n_ar, src, dst)
+    n = n_op + n_ar
+    g = wl.BaseGraph(n, n_op, rp, ci, rng.uniform(n * 32).reshape(n, 32).astype(np.float32))
+    labs = np.empty((6, n), np.int32)
+    labs[0] = np.arange(n)
+    labs[1] = np.arange(n)
+    labs[1, :n_op] = 0
+    labs[2] = np.arange(n)
+    labs[2, n_op] = 5
+    labs[3, :n_op] = wl.random_labels(5, n_op, 40, 1)[0]
+    labs[3, n_op:] = np.arange(n_op, n)
+    labs[4, :n_op] = wl.random_labels(6, n_op, 150, 1)[0]
+    labs[4, n_op:] = n_op
+    labs[5] = np.arange(n)
+    labs[5, n_op:] = n - 1
+    return positive(wl.custom("edge", wl.ModelSpec(32, 64, 2, dtype), [g], [labs], seed=3))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_edge_cases(B, dtype):
+    w = edge_case_workload(dtype)
+    t, x = wl.profile_of(w)
+    ref_b = orc.contract(w)
+    got_t, got_x, _, counts, st = gpu_module_times(B, w, t, x)
+    assert st == B.DC_OK
+    # the sum over 300 member rows is rounded to bf16 before the regression network: same bound
+    check_times(w, got_t, got_x, ref_b, t, x)
+    want = orc.cost(w, t, x, 0.1, 0.05)
+    got, st = gpu_cost(B, w, t, x, 0.1, 0.05)
+    assert st == B.DC_OK
+    assert np.array_equal(np.isinf(got), np.isinf(want))
+    assert np.isinf(want[2]) and np.isfinite(want[0]) and np.isfinite(want[5])
+    fin = np.isfinite(want)
+    assert np.max(np.abs(got[fin] - want[fin]) / np.abs(want[fin])) <= TOL[dtype]
+    assert got[0] == want[0]                 # no estimator involved: exact
+    assert got[5] == want[5]
+
+
+def test_no_fused_op_at_all(B):
+    w = wl.make("cfg2", 3)
+    n = w.graphs[0].n
+    w = wl.custom("id", w.model, w.graphs, [np.tile(np.arange(n, dtype=np.int32), (3, 1))])
+    t, x = wl.profile_of(w)
+    got_t, got_x, _, counts, st = gpu_module_times(B, w, t, x)
+    assert st == B.DC_OK and counts == (0, 0, 0)
+    assert np.array_equal(got_t, np.tile(t, 3)) and np.array_equal(got_x, np.tile(x, 3))
+    got, st = gpu_cost(B, w, t, x, 0.02, 0.01)
+    assert st == B.DC_OK and np.array_equal(got, orc.cost(w, t, x, 0.02, 0.01))
+
+
+def test_call_order_and_limits(B):
+    w = wl.make("cfg1", 2)
+    t, x = wl.profile_of(w)
+    ev = B.evaluator_for(w)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    with pytest.raises(B.DiscoError) as e:
+        ev.cost_candidates(cg, co, gid, 0.1, 0.1)
+    assert e.value.status == B.DC_ERR_INVALID_ARG          # no profile yet
+    ev.set_profile(t, x)
+    ev.cost_candidates(cg, co, gid, 0.1, 0.1)
+    assert ev.check() == B.DC_OK
+    ev.set_base_graphs(w.g_node_off(), w.g_edge_off(), w.cat_rowptr(), w.cat_col(), w.cat_X())
+    with pytest.raises(B.DiscoError) as e:                 # new graphs discard the profile
+        ev.cost_candidates(cg, co, gid, 0.1, 0.1)
+    assert e.value.status == B.DC_ERR_INVALID_ARG
+    ev.close()
+    # a context whose estimator scratch is smaller than the base graphs cannot take the cost path
+    small = B.evaluator_for(w, max_nodes=40, max_edges=100)
+    with pytest.raises(B.DiscoError) as e:
+        small.set_profile(t, x)
+    assert e.value.status == B.DC_ERR_CAPACITY
+    small.close()
+    # rows that are not strictly ascending
+    g = w.graphs[0]
+    col = g.col.copy()
+    u = int(np.argmax(np.diff(g.rowptr) >= 2))
+    s = g.rowptr[u]
+    col[s], col[s + 1] = col[s + 1], col[s]
+    w2 = wl.custom("unsorted", w.model, [wl.BaseGraph(g.n, g.n_op, g.rowptr, col, g.X)],
+                   [w.group_id.reshape(w.n_cand, g.n)])
+    ev = B.evaluator_for(w2)
+    with pytest.raises(B.DiscoError) as e:
+        ev.set_profile(t, x)
+    assert e.value.status == B.DC_ERR_BAD_GRAPH
+    ev.close()
