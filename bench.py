@@ -143,6 +143,79 @@ def simulate_bench(args, w, B, torch):
     print(json.dumps(out), flush=True)
 
 
+def cost_bench(args, w, B, torch):
+    """Times dc_cost_candidates: contraction, the estimator on every fused op, per-node times,
+    list scheduling.  Profiled data are synthetic (workloads.profile_of)."""
+    from paper_2209_12769_amd import workloads as wl
+    t_base, x_base = wl.profile_of(w)
+    ev = B.evaluator_for(w)
+    ev.set_profile(t_base, x_base)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    cost = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
+    ar_c, ar_d = 0.02, 0.01
+    for _ in range(args.warmup):
+        ev.cost_candidates(cg, co, gid, ar_c, ar_d, cost)
+    torch.cuda.synchronize()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    ntot, etot = ev.last_totals()
+    K, M, E = ev.last_fused_ops()
+    ev.profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev.cost_candidates(cg, co, gid, ar_c, ar_d, cost)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fam = ev.profile_end()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    work = algorithmic_work(w, M, E)          # the layer kernels run on the fused-op batch
+    m = w.model
+    s = 2 if m.dtype == "bf16" else 4
+    work["fused_op_head"] = {"flops": 2 * 2 * K * m.H * m.H, "bytes": M * m.H * s + 5 * K * m.H * s}
+    kernels = {}
+    for name, (ms_total, launches) in fam.items():
+        if launches == 0:
+            continue
+        per = ms_total / args.steps
+        k = {"ms_per_step": round(per, 4), "launches_per_step": launches / args.steps}
+        if per > 0 and name in work and work[name].get("bytes"):
+            k["GB/s"] = round(work[name]["bytes"] / (per * 1e-3) / 1e9, 1)
+        if per > 0 and name in work and work[name].get("flops"):
+            k["TFLOP/s"] = round(work[name]["flops"] / (per * 1e-3) / 1e12, 2)
+        kernels[name] = k
+    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    if "TFLOP/s" in kernels[dom]:
+        peak = PEAK_MFMA_TFLOPS[m.dtype]
+        ach = kernels[dom]["TFLOP/s"]
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": round(ach / peak, 4), "traffic": None}
+    else:
+        ach = kernels[dom].get("GB/s", 0.0)
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    roof["avg_launch_ms"] = round(kernels[dom]["ms_per_step"] / max(kernels[dom]["launches_per_step"], 1), 4)
+    out = {"metric": "fusion candidates costed/sec (contraction + estimator on every fused op + list scheduling) "
+                     "on 1 MI355X",
+           "value": round(w.n_cand * args.steps / dt, 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": m.dtype, "data": "synthetic",
+           "config": {"workload": w.name, "candidates": w.n_cand, "contracted_nodes": ntot, "contracted_edges": etot,
+                      "fused_ops": K, "fused_op_rows": M, "fused_op_edges": E, "F": m.F, "H": m.H, "L": m.L,
+                      "finite": int(torch.isfinite(cost).sum().item())},
+           "roofline": roof, "kernels": kernels}
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        n = min(w.n_cand, 6 if w.name in ("cfg4", "cfg5") else 32)
+        sub = w.subset(np.linspace(0, w.n_cand - 1, n).astype(np.int64))
+        t0 = time.perf_counter()
+        orc.cost(sub, t_base, x_base, ar_c, ar_d)
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n / cdt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{n} of {w.n_cand} candidates of {w.name}, evenly spaced, {cdt:.1f} s"}
+    ev.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,6 +230,9 @@ def main():
     ap.add_argument("--simulate", action="store_true",
                     help="instead of the estimator, time the list-scheduling simulator (dc_simulate) on the "
                          "contracted batch; per-node times and tensor sizes are synthetic (from the features)")
+    ap.add_argument("--cost", action="store_true",
+                    help="instead of one estimate per module, time Cost(H) as the paper composes it "
+                         "(dc_cost_candidates): estimator on every fused op, profiled single ops, simulator")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
                          "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -186,6 +262,9 @@ def main():
         return
     if args.aggregator == "attention":
         w = wl.with_attention(w, args.heads)
+    if args.cost:
+        cost_bench(args, w, B, torch)
+        return
     ev = B.evaluator_for(w)
     cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
     pred = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)

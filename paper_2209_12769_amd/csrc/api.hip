@@ -321,6 +321,7 @@ dc_status do_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph
   // the layer kernels only need the total row count: the batch is handed over as one graph
   GnnArgs g = gnn_args(ctx, 1, a.fb, nullptr);
   g.node_off = a.totals;
+  g.gather_slots = 1;                       // the members of a fused op have few dependencies among them
   const void* h_last = nullptr;
   e = launch_gnn_layers(g, prof, s, &h_last);
   if (e != hipSuccess) return hip_fail(ctx, e, "fused-op forward launch");

@@ -109,6 +109,7 @@ struct GnnArgs {
   const int* status;
   int n_cu;
   int allow_fused;      // 0 forces the separate aggregate + update kernels
+  int gather_slots = 3; // 1: nearly every neighbour list has at most one entry (batches of fused-op subgraphs)
   // attention aggregation (heads > 0): W holds one [d, H] block per layer
   int heads = 0;
   const float* att = nullptr;   // per layer a_src[H] | a_dst[H]
@@ -141,7 +142,8 @@ bool layer256_supported(int d, int H, int bf16);
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s);
-hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, void* out, hipStream_t s);
+hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                           hipStream_t s);
 
 // simulate.hip: list-scheduling estimate of the end-to-end time of each candidate module
 struct SimArgs {

@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void fo_readout_kernel(const void* __restrict_
 }
 
 // t_k = max(0, z2_k . w3 + b3) -> op_time of the fused op's node; the raw value also goes to
-// fo_pred when that is not null.  fp64 accumulation, lanes added in ascending order.
+// fo_pred when that is not null.  fp64 accumulation in a fixed order.
 template <bool kBf16>
 __global__ __launch_bounds__(256) void fo_time_kernel(const void* __restrict__ Z, int H,
                                                        const float* __restrict__ w3b3,
@@ -315,7 +315,12 @@ __global__ __launch_bounds__(256) void fo_time_kernel(const void* __restrict__ Z
       for (int i = 0; i < 8; ++i) part += (double)x[i] * (double)w[i];
     }
     double sum = b3;
-    for (int j = 0; j < LPR; ++j) sum += __shfl(part, (hb + j) & 63, 64);
+    if ((LPR & (LPR - 1)) == 0) {            // the lanes of a fused op are adjacent and LPR-aligned
+      for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o, 64);
+      sum += part;
+    } else {
+      for (int j = 0; j < LPR; ++j) sum += __shfl(part, (hb + j) & 63, 64);
+    }
     if (active && k < K && ll == 0) {
       const float tk = (float)sum;
       op_time[fo_cnode[k]] = tk > 0.0f ? tk : 0.0f;

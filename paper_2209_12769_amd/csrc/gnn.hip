@@ -396,7 +396,7 @@ hipError_t attention_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, con
     void* hnext = a.act[l & 1];
     if (prof) prof->begin(kFamAttProject, s);
     if (a.allow_fused && layer256_supported(d, a.H, a.bf16)) {
-      hipError_t e = launch_dense256(hcur, d, a, Wl, z, s);
+      hipError_t e = launch_dense256(hcur, d, a, Wl, nullptr, z, s);
       if (e != hipSuccess) return e;
     } else {
       run_update(a, hcur, nullptr, nullptr, d, 1, Wl, nullptr, z, s);
@@ -475,6 +475,8 @@ hipError_t launch_gnn_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, co
 
 void launch_dense_bias_relu(const GnnArgs& a, const void* A, int d, const void* Wp, const float* bias, void* out,
                             hipStream_t s) {
+  if (a.allow_fused && layer256_supported(d, a.H, a.bf16) && launch_dense256(A, d, a, Wp, bias, out, s) == hipSuccess)
+    return;
   run_update(a, A, nullptr, nullptr, d, 1, Wp, bias, out, s);
 }
 

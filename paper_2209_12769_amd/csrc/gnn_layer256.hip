@@ -7,10 +7,10 @@
 // 64 x 128 block of the 128 x 256 output tile, reads its A/B fragments from LDS
 // and prefetches the next B chunk of W.  Waves 4-7 only move data: per K chunk
 // of 64 columns each lane owns four (row, 16-byte column) items; it issues the
-// loads of chunk j+2 (the node's own row, or up to kU neighbour rows), then
+// loads of chunk j+2 (the node's own row, or up to U neighbour rows), then
 // reduces chunk j+1 (issued one step earlier) in fp32 in ascending neighbour
 // order, scales by 1/deg, rounds to bf16 and writes the A chunk into the LDS set
-// the MFMA waves read in the next step.  Rows with more than kU neighbours get
+// the MFMA waves read in the next step.  Rows with more than U neighbours get
 // their mean from a pre-pass (aggregate_heavy) so that no lane ever walks a long
 // neighbour list inside this kernel.  All waves meet at one barrier per step;
 // the step sequence runs across tiles, so loads for the next tile are in flight
@@ -31,7 +31,11 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kBM = 128, kBN = 256, kBK = 64;
 constexpr int kNT = 512;
-constexpr int kU = 3;                       // neighbours gathered in-kernel per row and direction
+constexpr int kU = 3;                       // neighbours gathered in-kernel per row and direction, at most
+// The kernels are built for U = 3 slots (candidate modules: 2.4 neighbours per row and
+// direction on average) and for U = 1 (batches of small sparse graphs such as fused-op
+// subgraphs, where almost every list has at most one entry): a slot costs a vector-memory
+// instruction per eight rows whether it is used or not.
 // Shape constants for input width D = 64 * DCH: K = 3 D in chunks of 64 columns, the first
 // DCH of them the node's own row.  A lane needs eight gather descriptors per tile (two
 // directions x four items).  With DCH = 4 each serves four jobs: one is requested per step
@@ -145,7 +149,7 @@ __device__ __forceinline__ void wait_vm_times4(int n4) {
 // reduce job s+1 (stage (Q+1)%3, requested two steps ago) into its LDS ring slot.  The first
 // DCH jobs of a tile are the node's own rows: those go from global memory straight into
 // LDS (issued by the MFMA waves) and cost this wave nothing.  A gather job issues exactly
-// 4 x kU row loads and every step exactly RQ descriptor loads, with no branch around a
+// 4 x U row loads and every step exactly RQ descriptor loads, with no branch around a
 // single vector load, so the in-order load counter says how many newer loads may still be
 // in flight when an older one is needed.
 // Row addresses are 32-bit byte offsets from a per-tile base row: a graph has fewer
@@ -164,18 +168,21 @@ struct MoverConst {
 template <int DCH>
 __device__ __forceinline__ int is_gather(int J, int S) { return (min(J, S - 1) % Shape<DCH>::NK) >= DCH; }
 
-// s_waitcnt vmcnt(BASE + 12 * n), n in 0..2, chosen at run time (wave-uniform)
-template <int BASE>
+// s_waitcnt vmcnt(BASE + PER * n), n in 0..2, chosen at run time (wave-uniform)
+template <int BASE, int PER>
 __device__ __forceinline__ void wait_vm_sel(int n) {
-  if (n == 2) wait_vm<BASE + 24>();
-  else if (n == 1) wait_vm<BASE + 12>();
+  if (n == 2) wait_vm<BASE + 2 * PER>();
+  else if (n == 1) wait_vm<BASE + PER>();
   else wait_vm<BASE>();
 }
 // Names registers as operands of an empty statement placed after a wait, so that no use of
 // them can be scheduled before it.
-__device__ __forceinline__ void pin(v4u (&a)[4][kU]) {
+__device__ __forceinline__ void pin(v4u (&a)[4][3]) {
   asm volatile("" : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]),
                     "+v"(a[2][0]), "+v"(a[2][1]), "+v"(a[2][2]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(a[3][2]));
+}
+__device__ __forceinline__ void pin(v4u (&a)[4][1]) {
+  asm volatile("" : "+v"(a[0][0]), "+v"(a[1][0]), "+v"(a[2][0]), "+v"(a[3][0]));
 }
 __device__ __forceinline__ void pin(v4i& d) { asm volatile("" : "+v"(d)); }
 
@@ -200,10 +207,11 @@ __device__ __forceinline__ const v4i* desc_addr(const MoverConst& c, int m, int 
 
 // Q = (s + 3) % 3 is the register stage that receives job s+3; job s+1 sits in stage
 // (Q + 1) % 3 and job s+2 (in flight) in stage (Q + 2) % 3.
-template <int DCH, int Q>
-__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], int (&sdeg)[3][4],
-                                           unsigned (&off)[2][4][kU], int (&dgs)[2][4],
+template <int DCH, int Q, int U>
+__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][U], int (&sdeg)[3][4],
+                                           unsigned (&off)[2][4][U], int (&dgs)[2][4],
                                            v4i (&dq)[3][Shape<DCH>::RQ], const MoverConst c) {
+  static_assert(U == 1 || U == 3, "one or three slots");
   constexpr int NK = Shape<DCH>::NK, RQ = Shape<DCH>::RQ;
   constexpr unsigned kRowBytes = Shape<DCH>::ROWB;
   constexpr int QC = (Q + 1) % 3;
@@ -217,7 +225,7 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
     // The descriptors requested two steps ago are needed now.  Newer than the last of them:
     // the row loads of its own step (job s+1) and all of the next step (its descriptors and
     // job s+2).
-    wait_vm_sel<RQ>(g1 + g2);
+    wait_vm_sel<RQ, 4 * U>(g1 + g2);
 #pragma unroll
     for (int r = 0; r < RQ; ++r) pin(dq[QC][r]);
     if (!Shape<DCH>::DIRECT) {
@@ -227,7 +235,7 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
       const unsigned f1 = (unsigned)(dd.y - base_row) * kRowBytes + colb;
       const unsigned f2 = (unsigned)(dd.z - base_row) * kRowBytes + colb;
       const int fd = dd.w;
-#define DC_FILE(dd_, ii_) { off[dd_][ii_][0] = f0; off[dd_][ii_][1] = f1; off[dd_][ii_][2] = f2; dgs[dd_][ii_] = fd; }
+#define DC_FILE(dd_, ii_) { off[dd_][ii_][0] = f0; if constexpr (U == 3) { off[dd_][ii_][U - 2] = f1; off[dd_][ii_][U - 1] = f2; } dgs[dd_][ii_] = fd; }
       switch (kc) {
         case 0: DC_FILE(0, 0) break;
         case 1: DC_FILE(0, 1) break;
@@ -259,7 +267,7 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
     // and this step's descriptors.
     const bool reduce = s + 1 >= 0 && s + 1 < S && g1;
     if (reduce) {
-      wait_vm_sel<2 * RQ>(g2);
+      wait_vm_sel<2 * RQ, 4 * U>(g2);
       pin(ax[QC]);
     }
     const int seg = kc / DCH;
@@ -271,24 +279,31 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
     for (int i = 0; i < 4; ++i) {
       if (reduce) {
         const int dg = sdeg[QC][i];
-        // branch-free mean in ascending neighbour order: slot u counts iff u < deg
-        const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
-        const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
-        const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][1], x2 = ax[QC][i][2];
         v4u o;
+        if constexpr (U == 3) {
+          // branch-free mean in ascending neighbour order: slot u counts iff u < deg
+          const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
+          const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
+          const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][U - 2], x2 = ax[QC][i][U - 1];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float lo = __uint_as_float(x0[w] << 16);
-          float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
-          bf16_pair_add(lo, hi, x1[w], k1);
-          bf16_pair_add(lo, hi, x2[w], k2);
-          o[w] = pack_bf16x2(lo * sc, hi * sc);
+          for (int w = 0; w < 4; ++w) {
+            float lo = __uint_as_float(x0[w] << 16);
+            float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
+            bf16_pair_add(lo, hi, x1[w], k1);
+            bf16_pair_add(lo, hi, x2[w], k2);
+            o[w] = pack_bf16x2(lo * sc, hi * sc);
+          }
+          o = dg > U ? x0 : o;                // pre-pass rows: slot 0 is the finished mean
+        } else {
+          // one slot: the mean of a single neighbour is that neighbour's row, longer lists
+          // bring their finished mean, an empty list gives zero
+          const v4u x0 = ax[QC][i][0];
+          o = dg > 0 ? x0 : v4u{0u, 0u, 0u, 0u};
         }
-        o = dg > kU ? x0 : o;                 // pre-pass rows: slot 0 is the finished mean
         *reinterpret_cast<v4u*>(dst + 32 * i * kARow) = o;    // rows ar + 32 i share the swizzle of row ar
       }
       if (g3) {
-        unsigned g0, ga, gb;
+        unsigned g0, ga = 0u, gb = 0u;
         int dg;
         if (Shape<DCH>::DIRECT) {
           g0 = (unsigned)(dnow[i].x - base_row) * kRowBytes + colb;
@@ -297,17 +312,21 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][kU], in
           dg = dnow[i].w;
         } else {
           g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
-          ga = seg == 2 ? off[1][i][1] : off[0][i][1];
-          gb = seg == 2 ? off[1][i][2] : off[0][i][2];
+          if constexpr (U == 3) {
+            ga = seg == 2 ? off[1][i][U - 2] : off[0][i][U - 2];
+            gb = seg == 2 ? off[1][i][U - 1] : off[0][i][U - 1];
+          }
           dg = seg == 2 ? dgs[1][i] : dgs[0][i];
         }
         sdeg[Q][i] = dg;                      // travels with the rows: the filed copy may be replaced before they are reduced
-        // rows left to the pre-pass have all three offsets on the row itself (see build_desc):
+        // rows left to the pre-pass have all their offsets on the row itself (see build_desc):
         // slot 0 then reads the row's finished mean from the pre-pass buffer
-        const char* b0 = dg > kU ? pb : hb;
+        const char* b0 = dg > U ? pb : hb;
         ax[Q][i][0] = load16_async(b0 + (g0 + kcoff));
-        ax[Q][i][1] = load16_async(hb, ga + kcoff);
-        ax[Q][i][2] = load16_async(hb, gb + kcoff);
+        if constexpr (U == 3) {
+          ax[Q][i][U - 2] = load16_async(hb, ga + kcoff);
+          ax[Q][i][U - 1] = load16_async(hb, gb + kcoff);
+        }
       }
     }
   }
@@ -402,7 +421,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
     // for a store to be acknowledged.
     const int ti = s / NK;
     const int m0 = (c.tile0 + ti * c.per) * kBM;
-    if (!DENSE) {
+    if (!DENSE || c.bias != nullptr) {     // the plain product takes a bias (then also the ReLU) or none
     float4 bq[4];
     {
       int cb = c.wn * 128 + 4 * c.lh;
@@ -474,7 +493,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   }
 }
 
-template <int DCH, bool DENSE>
+template <int DCH, bool DENSE, int U = kU>
 __global__ __launch_bounds__(kNT) void layer256_kernel(
     const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
     const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
@@ -534,9 +553,9 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
   } else {
     // =========================== data-moving waves ====================================
     const int lt = role_wave * 64 + lane;
-    unsigned off[2][4][kU];                  // byte offsets of the gathered rows [direction][item][slot]
+    unsigned off[2][4][U];                   // byte offsets of the gathered rows [direction][item][slot]
     int dgs[2][4];                           // degrees [direction][item]
-    v4u ax[3][4][kU];                        // rows in flight [stage][item][slot]
+    v4u ax[3][4][U];                         // rows in flight [stage][item][slot]
     int sdeg[3][4];                          // their degrees
     v4i dq[3][RQ];                           // descriptors in flight
 #pragma unroll
@@ -546,7 +565,7 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
 #pragma unroll
       for (int q = 0; q < 3; ++q) sdeg[q][i] = 0;
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
+      for (int u = 0; u < U; ++u) {
         off[0][i][u] = 0u;
         off[1][i][u] = 0u;
         ax[0][i][u] = v4u{0u, 0u, 0u, 0u};
@@ -581,24 +600,24 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     __builtin_amdgcn_s_waitcnt(0);           // nothing of the set-up may still be in flight
 
     for (int s = -3; s < S; s += 3) {        // S + 3 is a multiple of 3
-      mover_step<DCH, 0>(s, S, ax, sdeg, off, dgs, dq, mc);
+      mover_step<DCH, 0, U>(s, S, ax, sdeg, off, dgs, dq, mc);
       __syncthreads();
-      mover_step<DCH, 1>(s + 1, S, ax, sdeg, off, dgs, dq, mc);
+      mover_step<DCH, 1, U>(s + 1, S, ax, sdeg, off, dgs, dq, mc);
       __syncthreads();
-      mover_step<DCH, 2>(s + 2, S, ax, sdeg, off, dgs, dq, mc);
+      mover_step<DCH, 2, U>(s + 2, S, ax, sdeg, off, dgs, dq, mc);
       __syncthreads();
     }
   }
 }
 
-// One gather descriptor per node and direction: the first kU neighbours (unused slots
+// One gather descriptor per node and direction: the first `slots` neighbours (unused slots
 // and rows left to the pre-pass point at the node itself, always a valid row) and the
 // degree.  Depends only on the graphs, so it is built once per forward pass.
 __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__ in_rp, const int* __restrict__ in_ci,
                                                           const int* __restrict__ out_rp,
                                                           const int* __restrict__ out_ci, v4i* __restrict__ desc_in,
                                                           v4i* __restrict__ desc_out,
-                                                          const int* __restrict__ node_off, int C,
+                                                          const int* __restrict__ node_off, int C, int slots,
                                                           const int* __restrict__ status) {
   if (status[0] != 0) return;
   const long long ntot = node_off[C];
@@ -610,7 +629,7 @@ __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__
     const int* ci = dir ? out_ci : in_ci;
     const int s = rp[v], dg = rp[v + 1] - s;
     v4i d = v4i{v, v, v, dg};          // rows left to the pre-pass (and empty lists) point at the row itself
-    if (dg <= kU && dg > 0) {
+    if (dg <= slots && dg > 0) {
       d.x = ci[s];                     // unused slots repeat the first neighbour: same cache line, never summed
       d.y = dg > 1 ? ci[s + 1] : d.x;
       d.z = dg > 2 ? ci[s + 2] : d.x;
@@ -619,7 +638,7 @@ __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__
   }
 }
 
-// Means of rows with more than kU neighbours (both directions), written at the rows'
+// Means of rows with more than `slots` neighbours (both directions), written at the rows'
 // own positions in h_in / h_out; all other rows are left untouched.  Each thread tests
 // one (row, direction) pair; the pairs that qualify are then served by the wave, 64 / LPR
 // at a time, LPR = D / 8 lanes (16 bytes each) per row.  The grid must be a multiple of
@@ -631,7 +650,7 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
                                                                const int* __restrict__ out_rp,
                                                                const int* __restrict__ out_ci, u16* __restrict__ h_in,
                                                                u16* __restrict__ h_out,
-                                                               const int* __restrict__ node_off, int C,
+                                                               const int* __restrict__ node_off, int C, int slots,
                                                                const int* __restrict__ status) {
   constexpr int NSG = 64 / LPR;              // pairs served at a time
   if (status[0] != 0) return;
@@ -656,7 +675,7 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
       s = rp[v];
       e = rp[v + 1];
     }
-    unsigned long long todo = __ballot(e - s > kU);
+    unsigned long long todo = __ballot(e - s > slots);
     while (todo) {
       // lane group g takes the g-th lowest pending pair (if there is one)
       int src = -1;
@@ -679,7 +698,7 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
           const int nb = min(LPR, deg - b0);
           const int mine = ll < nb ? ci[ms + b0 + ll] : 0;
           int k = 0;
-          if (b0 == 0) {                        // a pair here has more than kU >= 1 neighbours
+          if (b0 == 0) {                        // a pair here has more than slots >= 1 neighbours
             set8(a8, h4[(size_t)__shfl(mine, hb, 64) * LPR + ll]);
             k = 1;
           }
@@ -712,21 +731,22 @@ __global__ __launch_bounds__(256) void aggregate_heavy_kernel(const u16* __restr
 bool layer256_supported(int d, int H, int bf16) { return bf16 && H == kBN && (d == 256 || d == 64); }
 
 static_assert(kU == 3, "a descriptor holds three neighbour ids and the degree");
+static int slots_of(const GnnArgs& a) { return a.gather_slots == 1 ? 1 : kU; }
 
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(build_desc_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
                      a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.node_off, a.n_cand,
-                     a.status);
+                     slots_of(a), a.status);
   return hipGetLastError();
 }
 
 namespace {
 
-template <int DCH>
+template <int DCH, int U>
 hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out, Profiler* prof,
                         hipStream_t s) {
   static bool attr_done = false;
-  auto kern = layer256_kernel<DCH, false>;
+  auto kern = layer256_kernel<DCH, false, U>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -737,7 +757,7 @@ hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const f
   if (prof) prof->begin(kFamHeavy, s);
   hipLaunchKernelGGL(aggregate_heavy_kernel<8 * DCH>, dim3(a.n_cu * 8), dim3(256), 0, s, hh, a.in_rowptr, a.in_col,
                      a.out_rowptr, a.out_col, static_cast<u16*>(a.agg[0]), static_cast<u16*>(a.agg[1]), a.node_off,
-                     a.n_cand, a.status);
+                     a.n_cand, U, a.status);
   if (prof) prof->end(s);
   if (prof) prof->begin(DCH == 4 ? kFamLayer256 : kFamLayer64, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
@@ -754,7 +774,8 @@ hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const f
 namespace {
 
 template <int DCH>
-hipError_t launch_dense_shape(const void* h, const GnnArgs& a, const void* Wl, void* out, hipStream_t s) {
+hipError_t launch_dense_shape(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                              hipStream_t s) {
   static bool attr_done = false;
   auto kern = layer256_kernel<DCH, true>;
   if (!attr_done) {
@@ -765,24 +786,26 @@ hipError_t launch_dense_shape(const void* h, const GnnArgs& a, const void* Wl, v
   }
   const int grid = ((a.n_cu + 7) / 8) * 8;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, static_cast<const u16*>(h), nullptr, nullptr, nullptr,
-                     nullptr, static_cast<const u16*>(Wl), nullptr, static_cast<u16*>(out), a.node_off, a.n_cand,
+                     nullptr, static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand,
                      a.status);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// out = h W for H = 256, d = 256 or 64, bf16 (no bias, no activation)
-hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, void* out, hipStream_t s) {
-  if (d == 256) return launch_dense_shape<4>(h, a, Wl, out, s);
-  if (d == 64) return launch_dense_shape<1>(h, a, Wl, out, s);
+// out = h W (bias == nullptr) or ReLU(h W + bias) for H = 256, d = 256 or 64, bf16
+hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                           hipStream_t s) {
+  if (d == 256) return launch_dense_shape<4>(h, a, Wl, bias, out, s);
+  if (d == 64) return launch_dense_shape<1>(h, a, Wl, bias, out, s);
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s) {
-  if (d == 256) return launch_shape<4>(h, a, Wl, bias, out, prof, s);
-  if (d == 64) return launch_shape<1>(h, a, Wl, bias, out, prof, s);
+  const bool sparse = slots_of(a) == 1;
+  if (d == 256) return sparse ? launch_shape<4, 1>(h, a, Wl, bias, out, prof, s) : launch_shape<4, kU>(h, a, Wl, bias, out, prof, s);
+  if (d == 64) return sparse ? launch_shape<1, 1>(h, a, Wl, bias, out, prof, s) : launch_shape<1, kU>(h, a, Wl, bias, out, prof, s);
   return hipErrorInvalidValue;
 }
 
