@@ -62,6 +62,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2209_12769_amd.build)")
+        # torch first: the process must hold one HIP runtime, the one that owns the tensors whose pointers
+        # cross this boundary; loaded afterwards, libdisco.so binds to it instead of bringing a second copy
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i32, fp = C.c_void_p, C.c_int32, C.POINTER(C.c_float)
         L.dc_create.argtypes = [C.POINTER(vp), C.POINTER(DcConfig)]
