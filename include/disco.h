@@ -244,6 +244,46 @@ dc_status dc_cost_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
  * ran on, their member rows and the edges inside them.  Synchronises `stream`.            */
 dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, int64_t* n_edges, void* stream);
 
+/* Backtracking search over fusion strategies (Alg. 1, Sec. 4) with dc_cost_candidates as Cost().
+ * A strategy is a labelling of the nodes of base graph `graph`; the search starts from the
+ * all-singleton labelling H_in with H_opt = H_in.  Per step up to `parents` entries leave the
+ * priority queue (ascending cost, oldest first); each gets one child per optimisation method:
+ *   op fusion      n = Random(0, beta) times: a dependency u -> v between two computation ops of
+ *                  the base module is drawn uniformly; if its ends are in different groups, the
+ *                  group of u joins the group of v                        (Sec. 4, method (i))
+ *   tensor fusion  n times: an all-reduce node a and a side are drawn uniformly; the nearest
+ *                  bucket on that side in production order joins a's      (Sec. 4, method (iii))
+ * (method (ii) duplicates an op; a labelling cannot express that).  The children of a step are
+ * costed together and then handled in order: a child with a finite cost (a cyclic module costs
+ * +infinity) replaces H_opt when cheaper, which restarts the counter of unchanged evaluations,
+ * otherwise the counter grows; it is enqueued when Cost(H') <= alpha * Cost(H_opt).  The search
+ * ends when the queue is empty, when the counter has reached max_unchanged (checked between
+ * steps) or after max_steps steps.  parents = 1 is the loop as the paper prints it.  A queue
+ * above max_queue entries drops its most expensive ones.
+ * Draws: key = mix(seed ^ mix(step * 2^32 + child)), draw d = mix(key + d * 0xD1342543DE82EF95),
+ * mix = the output function of splitmix64; draw 0 mod (beta + 1) is n, draws 1.. mod the number
+ * of choices pick the applications (tensor fusion takes the side from bit 32 of its draw).
+ * Needs dc_set_profile and capacities for 2 * parents candidates of this graph per call.
+ * labels_opt: host [N] out (may be NULL); res: host out.  Allocates its own device buffers
+ * ((max_queue + 4 * parents) * N labels) for the duration of the call and synchronises `stream`
+ * once per step.                                                                            */
+typedef struct {
+  float alpha;           /* >= 1 */
+  int32_t beta;          /* >= 0 */
+  int32_t max_unchanged; /* the paper uses 1000 */
+  int32_t parents;       /* >= 1 */
+  int32_t max_queue;     /* >= 1 */
+  int64_t max_steps;
+  uint64_t seed;
+  float ar_c, ar_d;      /* T = ar_c * size + ar_d */
+} dc_search_params;
+typedef struct {
+  float cost_in, cost_opt;
+  int64_t steps, evaluated, valid, enqueued, improved, queued, unchanged;
+} dc_search_result;
+dc_status dc_search(dc_ctx* ctx, int32_t graph, const dc_search_params* params, int32_t* labels_opt,
+                    dc_search_result* res, void* stream);
+
 /* dc_contract_graphs into context-owned buffers followed by dc_gnn_forward. */
 dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
                              const int32_t* group_id, float* pred, void* stream);

@@ -47,6 +47,18 @@ class DcBatch(C.Structure):
                 ("in_col", C.c_void_p), ("Xc", C.c_void_p)]
 
 
+class DcSearchParams(C.Structure):
+    _fields_ = [("alpha", C.c_float), ("beta", C.c_int32), ("max_unchanged", C.c_int32), ("parents", C.c_int32),
+                ("max_queue", C.c_int32), ("max_steps", C.c_int64), ("seed", C.c_uint64),
+                ("ar_c", C.c_float), ("ar_d", C.c_float)]
+
+
+class DcSearchResult(C.Structure):
+    _fields_ = [("cost_in", C.c_float), ("cost_opt", C.c_float), ("steps", C.c_int64), ("evaluated", C.c_int64),
+                ("valid", C.c_int64), ("enqueued", C.c_int64), ("improved", C.c_int64), ("queued", C.c_int64),
+                ("unchanged", C.c_int64)]
+
+
 class DiscoError(RuntimeError):
     def __init__(self, status: int, detail: str = ""):
         self.status = status
@@ -82,6 +94,7 @@ def lib():
         L.dc_module_times.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp, vp, vp]
         L.dc_cost_candidates.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp]
         L.dc_last_fused_ops.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
+        L.dc_search.argtypes = [vp, i32, C.POINTER(DcSearchParams), vp, C.POINTER(DcSearchResult), vp]
         L.dc_check.argtypes = [vp, vp]
         L.dc_last_totals.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_last_error.argtypes = [vp]
@@ -90,7 +103,7 @@ def lib():
         L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
         for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
                   "dc_gnn_forward", "dc_eval_candidates", "dc_simulate", "dc_check", "dc_last_totals", "dc_profile_begin",
-                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops"):
+                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops", "dc_search"):
             getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -163,6 +176,12 @@ def dc_last_fused_ops(ctx, stream: int = 0) -> Tuple[int, int, int, int]:
     k, m, e = C.c_int64(), C.c_int64(), C.c_int64()
     st = lib().dc_last_fused_ops(ctx, C.byref(k), C.byref(m), C.byref(e), stream)
     return st, k.value, m.value, e.value
+
+
+def dc_search(ctx, graph: int, params: DcSearchParams, labels_opt: Optional[np.ndarray], res: DcSearchResult,
+              stream: int = 0) -> int:
+    return lib().dc_search(ctx, graph, C.byref(params), None if labels_opt is None else labels_opt.ctypes.data,
+                           C.byref(res), stream)
 
 
 def dc_check(ctx, stream: int = 0) -> int:
@@ -331,6 +350,15 @@ class Evaluator:
         self._ok(dc_cost_candidates(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(), group_id.data_ptr(),
                                     ar_c, ar_d, cost.data_ptr(), self._stream()), "dc_cost_candidates")
         return cost[:n_cand]
+
+    def search(self, graph: int, n_nodes: int, alpha: float, beta: int, seed: int, ar_c: float, ar_d: float,
+               max_unchanged: int = 1000, parents: int = 1, max_steps: int = 1 << 40, max_queue: int = 4096):
+        """Alg. 1 on base graph `graph`; returns (labels_opt, DcSearchResult)."""
+        p = DcSearchParams(alpha, beta, max_unchanged, parents, max_queue, max_steps, seed, ar_c, ar_d)
+        r = DcSearchResult()
+        labels = np.zeros(n_nodes, np.int32)
+        self._ok(dc_search(self.ctx, graph, p, labels, r, self._stream()), "dc_search")
+        return labels, r
 
     def last_fused_ops(self) -> Tuple[int, int, int]:
         st, k, m, e = dc_last_fused_ops(self.ctx, self._stream())

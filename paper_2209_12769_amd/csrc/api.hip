@@ -72,6 +72,7 @@ struct dc_ctx {
   float* fo_pred = nullptr;      // raw estimate of each fused op of the last call
   void* headW = nullptr;         // W1 | W2 of the regression network in the layer kernels' layout
   bool have_profile = false;
+  std::vector<int> h_gno, h_geo;   // host copies of the base graphs' offsets
   int allow_fused = 1;
   Profiler prof;
   std::string err;
@@ -671,6 +672,8 @@ dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_nod
   ctx->have_graphs = true;
   ctx->bg_canonical = canonical;
   ctx->bg_nodes = NT;
+  ctx->h_gno.assign(g_node_off, g_node_off + n_graphs + 1);
+  ctx->h_geo.assign(g_edge_off, g_edge_off + n_graphs + 1);
   if (ctx->cost_mem) (void)hipFree(ctx->cost_mem);   // the profile belongs to the graphs it was recorded on
   ctx->cost_mem = nullptr;
   ctx->have_profile = false;
@@ -894,6 +897,31 @@ dc_status dc_cost_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
   st = do_module_times(ctx, n_cand, cand_graph, cand_off, ctx->ib, ctx->m_op_time, ctx->m_ar_size, s);
   if (st != DC_OK) return st;
   return do_simulate(ctx, n_cand, ctx->ib, ctx->m_op_time, ctx->m_ar_size, ar_c, ar_d, cost, s);
+}
+
+dc_status dc_search(dc_ctx* ctx, int32_t graph, const dc_search_params* params, int32_t* labels_opt,
+                    dc_search_result* res, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!params) return fail(ctx, DC_ERR_INVALID_ARG, "null parameters");
+  dc_status st = cost_call_check(ctx, 0);
+  if (st != DC_OK) return st;
+  const dc_search_params& p = *params;
+  if (graph < 0 || graph >= ctx->bg.n_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "graph index out of range");
+  if (!(p.alpha >= 1.0f) || p.beta < 0 || p.max_unchanged < 0 || p.parents < 1 || p.max_queue < 1 || p.max_steps < 0)
+    return fail(ctx, DC_ERR_INVALID_ARG, "need alpha >= 1, beta >= 0, parents >= 1, max_queue >= 1");
+  SearchView g;
+  g.n = ctx->h_gno[graph + 1] - ctx->h_gno[graph];
+  g.e = ctx->h_geo[graph + 1] - ctx->h_geo[graph];
+  g.rowptr = ctx->bg.rowptr + ctx->h_gno[graph] + graph;
+  g.col = ctx->bg.col + ctx->h_geo[graph];
+  g.ar_size = ctx->fo.ar_size_base + ctx->h_gno[graph];
+  const long long kids = 2LL * p.parents;
+  if (kids > ctx->cfg.max_cand || kids * g.n > ctx->cfg.max_base_nodes || kids * g.e > ctx->cfg.max_base_edges)
+    return fail(ctx, DC_ERR_CAPACITY, "the context must hold 2 * parents candidates of this graph per call");
+  if (g.n == 0) return fail(ctx, DC_ERR_INVALID_ARG, "empty graph");
+  st = run_search(ctx, g, graph, p, labels_opt, res, static_cast<hipStream_t>(stream));
+  if (st != DC_OK && ctx->err.empty()) ctx->err = "search failed";
+  return st;
 }
 
 dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, int64_t* n_edges, void* stream) {

@@ -200,6 +200,16 @@ hipError_t launch_fused_op_readout(const FusedOpsArgs& a, const void* h_last, vo
 hipError_t launch_fused_op_times(const FusedOpsArgs& a, const void* Z2, const float* w3b3, float* fo_pred,
                                  hipStream_t s);
 
+// search.hip: the backtracking search driver; it sees one base graph and calls the public cost entry point
+struct SearchView {
+  const int* rowptr;     // device, N + 1 local entries
+  const int* col;        // device, local node numbers
+  const float* ar_size;  // device [N], negative for computation ops
+  int n, e;
+};
+dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_search_params& p, int32_t* labels_opt,
+                     dc_search_result* res, hipStream_t s);
+
 __global__ void reset_status_kernel(int* status);
 
 // fp32 -> bf16, round to nearest even, in hardware (v_cvt_pk_bf16_f32): a in the low half
