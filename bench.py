@@ -216,6 +216,40 @@ def cost_bench(args, w, B, torch):
     print(json.dumps(out), flush=True)
 
 
+def search_bench(args, w, B, torch):
+    """Times dc_search (Alg. 1 with batched steps) on the workload's first base graph: every step mutates
+    `parents` queue entries twice on the device, costs the children in one dc_cost_candidates call and
+    updates the queue on the host.  A step here is one search step; value = candidates costed per second."""
+    from paper_2209_12769_amd import workloads as wl
+    g = w.graphs[0]
+    P = max(1, (args.n_cand or 4096) // 2)
+    ident = np.tile(np.arange(g.n, dtype=np.int32), (2 * P, 1))
+    wt = w.weights
+    wt.head[-1] += 1.0
+    ws = wl.custom(w.name, w.model, [g], [ident], weights=wt)
+    t_base, x_base = wl.profile_of(ws)
+    ev = B.evaluator_for(ws)
+    ev.set_profile(t_base, x_base)
+    kw = dict(alpha=1.05, beta=16, seed=1, ar_c=0.02, ar_d=0.01, max_unchanged=1 << 30, parents=P, max_queue=4 * P)
+    ev.search(0, g.n, max_steps=args.warmup, **kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    labels, r = ev.search(0, g.n, max_steps=args.steps, **kw)
+    dt = time.perf_counter() - t0
+    out = {"metric": "fusion candidates generated and costed/sec inside the backtracking search (Alg. 1) on 1 MI355X",
+           "value": round(r.evaluated / dt, 1), "unit": "candidates/s", "n_gpus": 1, "steps": int(r.steps),
+           "warmup": args.warmup, "ms_per_step": round(dt / max(r.steps, 1) * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": w.model.dtype, "data": "synthetic",
+           "config": {"workload": w.name, "base_nodes": g.n, "parents_per_step": P, "alpha": 1.05, "beta": 16,
+                      "evaluated": int(r.evaluated), "valid": int(r.valid), "enqueued": int(r.enqueued),
+                      "improved": int(r.improved), "cost_in": r.cost_in, "cost_opt": r.cost_opt,
+                      "groups_opt": int(len(np.unique(labels))),
+                      "note": "includes the set-up of the call (first cost of H_in, buffers) and one stream "
+                              "synchronisation per step"}}
+    ev.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -233,6 +267,9 @@ def main():
     ap.add_argument("--cost", action="store_true",
                     help="instead of one estimate per module, time Cost(H) as the paper composes it "
                          "(dc_cost_candidates): estimator on every fused op, profiled single ops, simulator")
+    ap.add_argument("--search", action="store_true",
+                    help="time the backtracking search (dc_search) on the workload's base graph; "
+                         "--n-cand children per step, --steps search steps")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
                          "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -256,7 +293,7 @@ def main():
     from paper_2209_12769_amd import binding as B
     from paper_2209_12769_amd import workloads as wl
 
-    w = wl.make(args.workload, args.n_cand)
+    w = wl.make(args.workload, 1 if args.search else args.n_cand)
     if args.simulate:
         simulate_bench(args, w, B, torch)
         return
@@ -264,6 +301,9 @@ def main():
         w = wl.with_attention(w, args.heads)
     if args.cost:
         cost_bench(args, w, B, torch)
+        return
+    if args.search:
+        search_bench(args, w, B, torch)
         return
     ev = B.evaluator_for(w)
     cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)

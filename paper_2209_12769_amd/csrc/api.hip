@@ -638,7 +638,10 @@ dc_status dc_set_base_graphs(dc_ctx* ctx, int32_t n_graphs, const int32_t* g_nod
   int sim_slices = 0;
   if (e == hipSuccess && simulate_scratch_bytes(max_gn, max_ge, 1) > (size_t)kSimLdsBytes) {
     sim_stride = al(simulate_scratch_bytes(max_gn, max_ge, 1));
-    sim_slices = ctx->n_cu * 4;
+    // one wave per slice; many waves per CU hide the latency of the walk (up to 2 GB of slices)
+    sim_slices = ctx->n_cu * 16;
+    const size_t fit = ((size_t)2 << 30) / sim_stride;
+    if ((size_t)sim_slices > fit) sim_slices = (int)(fit > (size_t)ctx->n_cu ? fit : (size_t)ctx->n_cu);
     e = hipMalloc(reinterpret_cast<void**>(&sim), sim_stride * sim_slices);
   }
   if (e != hipSuccess) {

@@ -90,6 +90,14 @@ __global__ __launch_bounds__(256) void mutate_kernel(const int* __restrict__ poo
   for (int v = t; v < N; v += T) dst[v] = lab[v];
 }
 
+// Copies the children that were kept into their pool slots: pair i = (child, slot).
+__global__ __launch_bounds__(256) void keep_kernel(const int* __restrict__ children, int* __restrict__ pool, int N,
+                                                    const int* __restrict__ pairs) {
+  const int* src = children + (size_t)pairs[2 * blockIdx.x] * N;
+  int* dst = pool + (size_t)pairs[2 * blockIdx.x + 1] * N;
+  for (int v = threadIdx.x; v < N; v += blockDim.x) dst[v] = src[v];
+}
+
 __global__ void iota_kernel(int* p, int n, int mul) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = i * mul;
@@ -148,16 +156,20 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
   int* pool = mem.take<int>((size_t)slots * N, &e);
   int* children = mem.take<int>((size_t)C * N, &e);
   int* d_parent = mem.take<int>(P, &e);
+  int* d_pairs = mem.take<int>(2 * (size_t)(C + 1), &e);
   int* cand_graph = mem.take<int>(C, &e);
   int* cand_off = mem.take<int>(C + 1, &e);
   float* d_cost = mem.take<float>(C, &e);
-  if (e == hipSuccess) e = hipHostMalloc(&mem.pinned, (size_t)C * sizeof(float) + (size_t)P * sizeof(int), hipHostMallocDefault);
+  if (e == hipSuccess)
+    e = hipHostMalloc(&mem.pinned, (size_t)C * sizeof(float) + ((size_t)P + 2 * (size_t)(C + 1)) * sizeof(int),
+                      hipHostMallocDefault);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     return e == hipErrorOutOfMemory ? DC_ERR_OOM : DC_ERR_HIP;
   }
   float* h_cost = static_cast<float*>(mem.pinned);
   int* h_parent = reinterpret_cast<int*>(h_cost + C);
+  int* h_pairs = h_parent + P;
   if (!esrc.empty()) {
     e = hipMemcpyAsync(d_esrc, esrc.data(), esrc.size() * sizeof(int), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemcpyAsync(d_edst, edst.data(), edst.size() * sizeof(int), hipMemcpyHostToDevice, s);
@@ -207,6 +219,10 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
     if (hipGetLastError() != hipSuccess) return DC_ERR_HIP;
     st = cost_of(children, nc);
     if (st != DC_OK) return st;
+    // decisions first, on the host; the label vectors that are kept move afterwards in one launch.
+    // A slot that is given up within the step (queue full) may be handed out again: its earlier
+    // pair is then dropped, so that no two pairs write one slot.
+    int n_pairs = 0, best_child = -1;
     for (int j = 0; j < nc; ++j) {
       const float c = h_cost[j];
       ++evaluated;
@@ -216,8 +232,7 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
         cost_opt = c;
         ++improved;
         unchanged = 0;
-        if (hipMemcpyAsync(pool, children + (size_t)j * N, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s) != hipSuccess)
-          return DC_ERR_HIP;
+        best_child = j;
       } else {
         ++unchanged;
       }
@@ -225,17 +240,38 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
         if (free_slots.empty()) {            // the queue is full: its most expensive entry makes room
           if (queue.empty()) return DC_ERR_CAPACITY;
           auto last = std::prev(queue.end());
-          free_slots.push_back(std::get<2>(*last));
+          const int gone = std::get<2>(*last);
+          for (int i = 0; i < n_pairs; ++i)
+            if (h_pairs[2 * i + 1] == gone) {
+              h_pairs[2 * i] = h_pairs[2 * (n_pairs - 1)];
+              h_pairs[2 * i + 1] = h_pairs[2 * (n_pairs - 1) + 1];
+              --n_pairs;
+              break;
+            }
+          free_slots.push_back(gone);
           queue.erase(last);
         }
         const int slot = free_slots.back();
         free_slots.pop_back();
-        if (hipMemcpyAsync(pool + (size_t)slot * N, children + (size_t)j * N, (size_t)N * sizeof(int),
-                           hipMemcpyDeviceToDevice, s) != hipSuccess)
-          return DC_ERR_HIP;
+        h_pairs[2 * n_pairs] = j;
+        h_pairs[2 * n_pairs + 1] = slot;
+        ++n_pairs;
         queue.insert(Entry(c, next_id++, slot));
         ++enqueued;
       }
+    }
+    if (best_child >= 0) {                   // slot 0 holds H_opt
+      h_pairs[2 * n_pairs] = best_child;
+      h_pairs[2 * n_pairs + 1] = 0;
+      ++n_pairs;
+    }
+    if (n_pairs > 0) {
+      if (hipMemcpyAsync(d_pairs, h_pairs, 2 * (size_t)n_pairs * sizeof(int), hipMemcpyHostToDevice, s) != hipSuccess)
+        return DC_ERR_HIP;
+      hipLaunchKernelGGL(keep_kernel, dim3(n_pairs), dim3(256), 0, s, children, pool, N, d_pairs);
+      if (hipGetLastError() != hipSuccess) return DC_ERR_HIP;
+      // h_pairs is reused next step: the copy above must have been taken before then; the next
+      // step synchronises on its costs before it writes h_pairs again
     }
     for (int i = 0; i < np; ++i) free_slots.push_back(used[i]);
     while ((long long)queue.size() > (long long)p.max_queue) {
