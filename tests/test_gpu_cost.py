@@ -137,6 +137,21 @@ def test_cost_is_the_simulator_on_the_module_times(B):
     ev.close()
 
 
+@pytest.mark.timeout(300)
+def test_full_size_batch_sampled_and_deterministic(B):
+    # the launch `bench.py --cost` times: 4096 candidates of cfg4 through dc_cost_candidates; sampled
+    # candidates against the oracle, the whole vector against a second run (inside gpu_cost)
+    w = positive(wl.make("cfg4", 4096))
+    t, x = wl.profile_of(w)
+    got, st = gpu_cost(B, w, t, x, 0.02, 0.01)
+    assert st == B.DC_OK and np.isfinite(got).all()
+    sample = [0, 1777, 4095]
+    want = orc.cost(w.subset(sample), t, x, 0.02, 0.01)
+    err = np.abs(got[sample] - want) / np.abs(want)
+    print(f"[cost full size] sampled max rel err {err.max():.2e}", flush=True)
+    assert err.max() <= TOL["bf16"]
+
+
 def test_attention_estimator(B):
     w = positive(wl.with_attention(wl.make("cfg3", 16), 4))
     t, x = wl.profile_of(w)
