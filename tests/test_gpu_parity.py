@@ -212,6 +212,54 @@ def test_full_size_bulk_batch_sampled_and_deterministic(B):
     ev.close()
 
 
+def largest_graph(F):
+    """A base graph at the documented limit of 65535 nodes: 64000 ops with 1-3 dependencies to ops up
+    to 40 places ahead plus a few long ones, and 1535 all-reduce sinks."""
+    n_op, n = 64000, 65535
+    rng = wl.Rng(4242, 0)
+    deg = rng.integers(1, 3, n_op)
+    src = np.repeat(np.arange(n_op), deg)
+    dst = np.minimum(src + rng.integers(1, 40, src.size), n_op - 1)
+    far = rng.integers(0, n_op - 2, 2000)
+    src = np.concatenate([src, far, rng.integers(0, n_op - 1, n - n_op)])
+    dst = np.concatenate([dst, np.minimum(far + rng.integers(1000, 30000, 2000), n_op - 1), np.arange(n_op, n)])
+    rp, ci = wl._csr_from_edges(n, src, dst)
+    X = rng.uniform(n * F).reshape(n, F).astype(np.float32)
+    X[:n_op, 1] = 0.0
+    X[n_op:, 1] = 1.0
+    return wl.BaseGraph(n, n_op, rp, ci, X)
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("dtype,H,L", [("f32", 32, 2), ("bf16", 256, 1)])
+def test_largest_base_graph(B, dtype, H, L):
+    # 65535 nodes: 16-bit node ids at their limit, working set in global memory, and (bf16, H = 256)
+    # the bulk layer kernel's 32-bit row offsets at the largest distance a graph allows
+    F = 64 if H == 256 else 16
+    g = largest_graph(F)
+    rng = wl.Rng(4242, 9)
+    labs = np.empty((3, g.n), np.int32)
+    labs[0] = np.arange(g.n)
+    labs[1] = wl._interval_partitions(rng, g, 1, ("uniform", 6), ("uniform", 30), False)[0]
+    labs[2] = labs[1]
+    labs[2, :100] = labs[2, 0]                                         # one group of 100 at the front
+    w = wl.custom("largest", wl.ModelSpec(F, H, L, dtype), [g], [labs], seed=8)
+    ev, batch, ref = check_contraction(B, w)
+    assert ref.node_off[1] == g.n
+    check_forward(B, w, ev, batch, ref)
+    # the simulator on the same batch (its modules walk in global memory): bit for bit
+    is_ar = ref.Xc[:, 1] > 0
+    ar_size = np.where(is_ar, ref.Xc[:, 0], -1.0).astype(np.float32)
+    op_time = np.where(is_ar, 0.0, 0.05 + ref.Xc[:, 2]).astype(np.float32)
+    import torch
+    cost = ev.simulate(batch, torch.from_numpy(op_time).to(ev.device), torch.from_numpy(ar_size).to(ev.device),
+                       0.02, 0.01).cpu().numpy()
+    assert ev.check() == B.DC_OK
+    want = orc.simulate(ref, op_time, ar_size, 0.02, 0.01)
+    assert np.array_equal(cost, want) and np.isfinite(want).all()
+    ev.close()
+
+
 def test_identity_and_single_group(B):
     g = wl.random_dag(21, 500, 0.01, 32)
     labs = np.stack([np.arange(g.n, dtype=np.int32), np.full(g.n, 7, np.int32),
