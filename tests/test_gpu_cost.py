@@ -152,6 +152,41 @@ def test_full_size_batch_sampled_and_deterministic(B):
     assert err.max() <= TOL["bf16"]
 
 
+def test_cost_is_capturable_in_a_hip_graph_and_replays_identically(B):
+    """dc_cost_candidates only enqueues kernels on the caller's stream (the sizes of the fused-op batch stay
+    on the device), so it can be captured; every replay must reproduce the eager costs bit for bit."""
+    import torch
+    w = positive(wl.make("cfg3", 24))
+    t, x = wl.profile_of(w)
+    ev = B.evaluator_for(w)
+    ev.set_profile(t, x)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    cost = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
+    eager = ev.cost_candidates(cg, co, gid, 0.02, 0.01, cost).clone()
+    torch.cuda.synchronize()
+    assert ev.check() == B.DC_OK
+    side = torch.cuda.Stream(device=ev.device)
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        ev.cost_candidates(cg, co, gid, 0.02, 0.01, cost)           # warm-up on the capture stream
+        torch.cuda.current_stream().synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ev.cost_candidates(cg, co, gid, 0.02, 0.01, cost)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        cost.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cost, eager), f"replay {rep}"
+        again = ev.cost_candidates(cg, co, gid, 0.02, 0.01).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager)
+    assert ev.check() == B.DC_OK
+    ev.close()
+
+
 def test_attention_estimator(B):
     w = positive(wl.with_attention(wl.make("cfg3", 16), 4))
     t, x = wl.profile_of(w)
