@@ -109,6 +109,22 @@ def test_result_with_a_real_estimator_stands_on_its_own(B, name, tol):
     print(f"[search] {name} real estimator: cost {r.cost_in:.4f} -> {r.cost_opt:.4f} in {r.steps} steps", flush=True)
 
 
+@pytest.mark.timeout(300)
+def test_largest_base_graph(B):
+    # 65535 nodes: the mutation kernel keeps 128 KB of labels in LDS, the modules walk in global memory
+    from test_gpu_parity import largest_graph
+    g = largest_graph(16)
+    model = wl.ModelSpec(16, 32, 1, "f32")
+    wt = constant_estimator(model, 0.03)
+    base = wl.custom("largest", model, [g], [np.arange(g.n, dtype=np.int32).reshape(1, g.n)], weights=wt)
+    t, x = wl.profile_of(base)
+    kw = dict(alpha=1.01, beta=40, seed=4, max_unchanged=1000, max_steps=4)
+    ref = osr.search(g, oracle_cost_fn(g, model, wt, t, x, 0.02, 0.01), parents=2, **kw)
+    labels, r = gpu_search(B, g, model, wt, t, x, 2, ar_c=0.02, ar_d=0.01, **kw)
+    same_run(r, ref, labels, "largest")
+    assert r.evaluated >= 8 and r.valid >= 1
+
+
 def test_bad_arguments(B):
     base = wl.make("cfg1", 2)
     t, x = wl.profile_of(base)
