@@ -278,12 +278,17 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][U], int
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (reduce) {
-        const int dg = sdeg[QC][i];
+        // slots of the row that count (0..3; a row left to the pre-pass has one: its finished mean)
+        const int ns = sdeg[QC][i] & 3;
         v4u o;
         if constexpr (U == 3) {
-          // branch-free mean in ascending neighbour order: slot u counts iff u < deg
-          const unsigned k1 = dg > 1 ? 0x3F80u : 0u, k2 = dg > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
-          const float sc = dg == 1 ? 1.0f : (dg == 2 ? 0.5f : (dg == 3 ? (1.0f / 3.0f) : 0.0f));
+          // branch-free mean in ascending neighbour order: slot u counts iff u < ns; the scale is
+          // picked as a bit pattern so that the choice stays a chain of selects
+          const unsigned k1 = ns > 1 ? 0x3F80u : 0u, k2 = ns > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
+          unsigned scb = ns == 1 ? 0x3F800000u : 0u;
+          scb = ns == 2 ? 0x3F000000u : scb;
+          scb = ns == 3 ? 0x3EAAAAABu : scb;                                        // 1/3 rounded to nearest
+          const float sc = __uint_as_float(scb);
           const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][U - 2], x2 = ax[QC][i][U - 1];
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
@@ -291,14 +296,13 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][U], int
             float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
             bf16_pair_add(lo, hi, x1[w], k1);
             bf16_pair_add(lo, hi, x2[w], k2);
-            o[w] = pack_bf16x2(lo * sc, hi * sc);
+            o[w] = pack_bf16x2(lo * sc, hi * sc);     // one slot: x * 1.0 repacks to the same bf16 values
           }
-          o = dg > U ? x0 : o;                // pre-pass rows: slot 0 is the finished mean
         } else {
           // one slot: the mean of a single neighbour is that neighbour's row, longer lists
           // bring their finished mean, an empty list gives zero
           const v4u x0 = ax[QC][i][0];
-          o = dg > 0 ? x0 : v4u{0u, 0u, 0u, 0u};
+          o = ns > 0 ? x0 : v4u{0u, 0u, 0u, 0u};
         }
         *reinterpret_cast<v4u*>(dst + 32 * i * kARow) = o;    // rows ar + 32 i share the swizzle of row ar
       }
@@ -319,9 +323,9 @@ __device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][U], int
           dg = seg == 2 ? dgs[1][i] : dgs[0][i];
         }
         sdeg[Q][i] = dg;                      // travels with the rows: the filed copy may be replaced before they are reduced
-        // rows left to the pre-pass have all their offsets on the row itself (see build_desc):
-        // slot 0 then reads the row's finished mean from the pre-pass buffer
-        const char* b0 = dg > U ? pb : hb;
+        // rows left to the pre-pass (code above 3) have all their offsets on the row itself (see
+        // build_desc): slot 0 then reads the row's finished mean from the pre-pass buffer
+        const char* b0 = dg > 3 ? pb : hb;
         ax[Q][i][0] = load16_async(b0 + (g0 + kcoff));
         if constexpr (U == 3) {
           ax[Q][i][U - 2] = load16_async(hb, ga + kcoff);
@@ -611,8 +615,9 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
 }
 
 // One gather descriptor per node and direction: the first `slots` neighbours (unused slots
-// and rows left to the pre-pass point at the node itself, always a valid row) and the
-// degree.  Depends only on the graphs, so it is built once per forward pass.
+// and rows left to the pre-pass point at the node itself, always a valid row) and a code:
+// the number of slots that count, or 5 for a row left to the pre-pass.  Depends only on the
+// graphs, so it is built once per forward pass.
 __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__ in_rp, const int* __restrict__ in_ci,
                                                           const int* __restrict__ out_rp,
                                                           const int* __restrict__ out_ci, v4i* __restrict__ desc_in,
@@ -628,7 +633,9 @@ __global__ __launch_bounds__(256) void build_desc_kernel(const int* __restrict__
     const int* rp = dir ? out_rp : in_rp;
     const int* ci = dir ? out_ci : in_ci;
     const int s = rp[v], dg = rp[v + 1] - s;
-    v4i d = v4i{v, v, v, dg};          // rows left to the pre-pass (and empty lists) point at the row itself
+    // last word: the number of slots that count (0..3), plus 4 for a row left to the pre-pass (which
+    // has one slot: its finished mean); such rows and empty lists point at the row itself
+    v4i d = v4i{v, v, v, dg > slots ? 5 : dg};
     if (dg <= slots && dg > 0) {
       d.x = ci[s];                     // unused slots repeat the first neighbour: same cache line, never summed
       d.y = dg > 1 ? ci[s + 1] : d.x;
