@@ -645,3 +645,70 @@ def profile_of(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
 def custom(name: str, model: ModelSpec, graphs: List[BaseGraph], labels_per_graph: List[np.ndarray],
            weights: Optional[Weights] = None, seed: int = 0, std: Optional[float] = None) -> Workload:
     return _pack(name, model, graphs, labels_per_graph, weights or make_weights(model, seed, std))
+
+
+# --------------------------------------------------------------------------
+# training samples of the fused-op estimator
+# --------------------------------------------------------------------------
+def training_labels(g: BaseGraph, seed: int, C: int, kmax: int = 48, cover: float = 0.6) -> np.ndarray:
+    """Labelings [C, n] whose groups of two or more ops are training samples drawn the way
+    Sec. 5.1 describes (Fused Op Estimator): a random op is fused with one of its
+    predecessors, and the fused op again with one of its predecessors, k times; k is
+    log-uniform in [1, kmax] and growth stops early when no free predecessor is left (the
+    paper draws far larger counts than a module has ops; the same early stop applies there).
+    Samples of one labeling are disjoint; seeds are drawn until `cover` of the ops are used.
+    All-reduce nodes stay single."""
+    rng = Rng(seed, 21)
+    n, n_op = g.n, g.n_op
+    crp = np.zeros(n + 1, np.int64)
+    src = np.repeat(np.arange(n), np.diff(g.rowptr))
+    np.add.at(crp, g.col + 1, 1)
+    crp = np.cumsum(crp)
+    order = np.argsort(g.col, kind="stable")
+    pred = src[order]
+    out = np.empty((C, n), np.int32)
+    for c in range(C):
+        lab = np.arange(n, dtype=np.int32)
+        used = np.zeros(n, bool)
+        used[n_op:] = True
+        tries = rng.permutation(n_op)
+        ks = np.exp(rng.uniform(n_op) * math.log(kmax)).astype(np.int64)
+        pick = rng.u64(n_op * 4)
+        pi, covered = 0, 0
+        for i, s0 in enumerate(tries):
+            if covered >= cover * n_op:
+                break
+            if used[s0]:
+                continue
+            members, frontier = [int(s0)], [int(p) for p in pred[crp[s0]:crp[s0 + 1]] if not used[p]]
+            used[s0] = True
+            for _ in range(int(ks[i])):
+                frontier = [p for p in frontier if not used[p]]
+                if not frontier:
+                    break
+                p = frontier[int(pick[pi % pick.size] % np.uint64(len(frontier)))]
+                pi += 1
+                used[p] = True
+                members.append(p)
+                frontier += [int(q) for q in pred[crp[p]:crp[p + 1]] if not used[q]]
+            if len(members) >= 2:
+                lab[members] = min(members)
+                covered += len(members)
+        out[c] = lab
+    return out
+
+
+def synthetic_fused_times(node_off: np.ndarray, base_node: np.ndarray, op_time: np.ndarray,
+                          seed: int = 0) -> np.ndarray:
+    """Stand-in for profiled fused-op times (Sec. 3.3.3 trains on profiled ones): the members'
+    own times summed, scaled by a fusion gain that grows with the number of members and by
+    +-10 % seeded noise.  Positive for every fused op.  node_off [K+1] and base_node [rows]
+    describe the batch of fused-op subgraphs (concatenated base numbering)."""
+    K = node_off.size - 1
+    cnt = np.diff(node_off.astype(np.int64))
+    own = np.asarray(op_time, np.float64)[np.asarray(base_node[:int(node_off[-1])], np.int64)]
+    s = np.zeros(K)
+    np.add.at(s, np.repeat(np.arange(K), cnt), own)
+    gain = 0.55 + 0.45 / np.sqrt(np.maximum(cnt, 1))
+    noise = 0.9 + 0.2 * Rng(seed, 22).uniform(max(K, 1))[:K]
+    return np.maximum(s * gain * noise, 1e-3).astype(np.float32)
