@@ -27,6 +27,8 @@
  *                       estimator on every fused op, profiled times for single ops,
  *                       the linear model for (fused) all-reduce tensors, then
  *                       dc_simulate.
+ *   dc_train_step       one step of the estimator's supervised training on a batch of
+ *                       fused ops with profiled times (Sec. 3.3.3: loss of Eq. (1), Adam).
  *
  * Conventions
  *  - Every call returns a dc_status; nothing throws or aborts.
@@ -283,6 +285,62 @@ typedef struct {
 } dc_search_result;
 dc_status dc_search(dc_ctx* ctx, int32_t graph, const dc_search_params* params, int32_t* labels_opt,
                     dc_search_result* res, void* stream);
+
+/* ---- Training of the estimator (Sec. 3.3.3; samples as in Sec. 5.1, Fused Op Estimator) ----
+ *
+ * The graph layers and the regression network are trained together on a set G of fused ops
+ * with profiled times y', by Adam on the loss of Eq. (1).  Eq. (1) as printed has no minimum
+ * at a perfect fit; it is taken as the mean squared difference of the logarithms,
+ *     L = 1/|G| sum_g (log max(y_g, floor) - log y'_g)^2 ,
+ * where y_g is the raw output z2.w3 + b3 of the regression network and a sample with
+ * y_g <= floor contributes its loss but no gradient.  Training needs a DC_F32, DC_AGG_MEAN
+ * context whose weights have been set; it updates those weights in place, so every later
+ * dc_gnn_forward / dc_eval_candidates / dc_cost_candidates runs the trained estimator.
+ * Arithmetic: fp32 storage and fp32 MFMA accumulation; the sums over the ops of a fused op, the
+ * per-sample loss terms and their total are formed in fp64.                                    */
+typedef struct {
+  float lr, beta1, beta2, eps; /* Adam: m = b1 m + (1-b1) g, v = b2 v + (1-b2) g^2,
+                                  theta -= lr (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps), t from 1 */
+  float floor;                 /* > 0                                                                */
+  int64_t max_samples;         /* graphs per batch                                                   */
+  int64_t max_rows;            /* rows per batch, at most the context's max_nodes                    */
+} dc_train_params;
+
+/* Number of fp32 parameters, in the order W_layers | b_layers | head of dc_set_weights. */
+int64_t dc_num_params(const dc_ctx* ctx);
+
+/* Allocates the training buffers (device; about (L + 6) * max_rows * H * 4 bytes), clears both
+ * moment vectors and the step count.  May be called again to restart or to change the sizes. */
+dc_status dc_train_begin(dc_ctx* ctx, const dc_train_params* params, void* stream);
+
+/* The training set of a list of labelings: contraction as in dc_contract_graphs, then every
+ * group of two or more computation ops becomes one graph of `out` (rows = its members in
+ * ascending base index with their own features, edges = the base edges with both ends in the
+ * group), ordered by candidate and then by contracted node.  out->new_id receives the base
+ * node (concatenated numbering) of each row; out->node_off / edge_off need cap_nodes / 2 + 2
+ * entries.  Needs dc_set_profile (it tells ops from all-reduce nodes).  Synchronises `stream`
+ * and sets out->n_cand to the number of graphs written.                                        */
+dc_status dc_fused_op_batch(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                            const int32_t* group_id, dc_batch* out, void* stream);
+
+/* Forward pass, loss and its gradient over one batch of sample graphs (any dc_batch: the
+ * output of dc_fused_op_batch or of dc_contract_graphs).  All pointers device memory.
+ *   target  [in->n_cand] profiled times, > 0
+ *   loss    [1]
+ *   pred    [in->n_cand] raw estimates y_g, or null
+ *   grad    [dc_num_params] in the order of dc_num_params, or null
+ * Nothing is updated.  Needs dc_train_begin.  No host synchronisation.                        */
+dc_status dc_loss_gradients(dc_ctx* ctx, const dc_batch* in, const float* target, float* loss, float* pred,
+                            float* grad, void* stream);
+
+/* One training step: dc_loss_gradients followed by one Adam update of all parameters in place.
+ * An empty batch (n_cand = 0) leaves everything as it is and reports a loss of 0.
+ * No host synchronisation: steps may be queued back to back on one stream.                     */
+dc_status dc_train_step(dc_ctx* ctx, const dc_batch* in, const float* target, float* loss, void* stream);
+
+/* Copies the current weights to host arrays laid out as for dc_set_weights (DC_F32 contexts).
+ * Synchronises `stream`.                                                                       */
+dc_status dc_get_weights(dc_ctx* ctx, float* W_layers, float* b_layers, float* head, void* stream);
 
 /* dc_contract_graphs into context-owned buffers followed by dc_gnn_forward. */
 dc_status dc_eval_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,

@@ -21,7 +21,10 @@ The gradient is the hand-derived reverse pass of exactly these formulas, one sta
 formula, with no fusion or reordering.  Pins (tests/test_oracle_train.py): central finite
 differences of the loss for every parameter tensor, reverse-mode differentiation of an
 independently written forward pass by a library (torch.autograd, fp64), closed forms of the
-loss, the library's Adam, and the constant-gradient closed form of Adam.
+loss, the library's Adam, and the constant-gradient closed form of Adam.  Where a pre-activation
+is closer to zero than single precision resolves, a single-precision pass may take the ReLU
+derivative from either side; undecided_units() lists such units and the `flip` argument takes the
+other side, pinned by moving a unit just across zero.
 
 Nothing in the product package imports this module, and it shares no code with the HIP path.
 """
@@ -118,8 +121,30 @@ def loss_of(y: np.ndarray, target: np.ndarray, floor: float) -> float:
     return float(np.mean(d * d))
 
 
-def loss_and_gradients(batch, target: np.ndarray, p: Params, floor: float = 1e-6):
-    """(loss, y, gradient as Params) of Eq. (1) over the batch."""
+def undecided_units(batch, p: Params, rel: float):
+    """Units (layer, row, column) whose pre-activation lies within rel * (largest magnitude in
+    that layer) of zero, top layer first; the two hidden layers of the regression network count
+    as layers L (z1) and L + 1 (z2), their rows are samples.  An fp32 forward pass cannot tell
+    which side of zero such a unit is on, so its ReLU derivative may legitimately be taken either
+    way; loss_and_gradients(flip=...) gives the other choice."""
+    _, c = forward(batch, p)
+    out = []
+    L = len(p.W)
+    for l, Z in ((L + 1, c["z1"] @ p.W2 + p.b2), (L, c["r"] @ p.W1 + p.b1)):
+        if Z.size:
+            r, j = np.nonzero(np.abs(Z) < rel * np.abs(Z).max())
+            out += [(l, int(a), int(b)) for a, b in zip(r, j)]
+    for l in range(L - 1, -1, -1):
+        Z = np.concatenate([c["hs"][l], c["mps"][l], c["mss"][l]], axis=1) @ p.W[l] + p.b[l]
+        r, j = np.nonzero(np.abs(Z) < rel * np.abs(Z).max())
+        out += [(l, int(a), int(b)) for a, b in zip(r, j)]
+    return out
+
+
+def loss_and_gradients(batch, target: np.ndarray, p: Params, floor: float = 1e-6, flip=()):
+    """(loss, y, gradient as Params) of Eq. (1) over the batch.  `flip` lists units (layer, row,
+    column) whose ReLU derivative is taken from the other side of zero (see undecided_units);
+    the forward values are not touched."""
     y, c = forward(batch, p)
     B, n = batch.n_cand, batch.ntot
     t = np.asarray(target, np.float64)
@@ -128,18 +153,24 @@ def loss_and_gradients(batch, target: np.ndarray, p: Params, floor: float = 1e-6
     yc = np.maximum(y, floor)
     dy = np.where(y > floor, 2.0 / max(B, 1) * (np.log(yc) - np.log(t)) / yc, 0.0)
     # regression network
+    L = len(p.W)
+    on2, on1 = c["z2"] > 0, c["z1"] > 0
+    for (fl, fr, fc) in flip:
+        if fl == L + 1:
+            on2[fr, fc] = not on2[fr, fc]
+        elif fl == L:
+            on1[fr, fc] = not on1[fr, fc]
     gw3 = c["z2"].T @ dy
     gb3 = np.array([dy.sum()])
-    dz2 = np.outer(dy, p.w3) * (c["z2"] > 0)
+    dz2 = np.outer(dy, p.w3) * on2
     gW2 = c["z1"].T @ dz2
     gb2 = dz2.sum(axis=0)
-    dz1 = (dz2 @ p.W2.T) * (c["z1"] > 0)
+    dz1 = (dz2 @ p.W2.T) * on1
     gW1 = c["r"].T @ dz1
     gb1 = dz1.sum(axis=0)
     dr = dz1 @ p.W1.T
     # the sum over the ops of a fused op hands its gradient to every one of them
     G = dr[c["gid"]]
-    L = len(p.W)
     gW: List[Optional[np.ndarray]] = [None] * L
     gb: List[Optional[np.ndarray]] = [None] * L
     pin, pout = c["pin"], c["pout"]
@@ -148,7 +179,11 @@ def loss_and_gradients(batch, target: np.ndarray, p: Params, floor: float = 1e-6
     for l in range(L - 1, -1, -1):
         h, hn = c["hs"][l], c["hs"][l + 1]
         d = h.shape[1]
-        dZ = G * (hn > 0)
+        on = hn > 0
+        for (fl, fr, fc) in flip:
+            if fl == l:
+                on[fr, fc] = not on[fr, fc]
+        dZ = G * on
         A = np.concatenate([h, c["mps"][l], c["mss"][l]], axis=1)
         gW[l] = A.T @ dZ
         gb[l] = dZ.sum(axis=0)

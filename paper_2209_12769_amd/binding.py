@@ -59,6 +59,11 @@ class DcSearchResult(C.Structure):
                 ("unchanged", C.c_int64)]
 
 
+class DcTrainParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("floor", C.c_float), ("max_samples", C.c_int64), ("max_rows", C.c_int64)]
+
+
 class DiscoError(RuntimeError):
     def __init__(self, status: int, detail: str = ""):
         self.status = status
@@ -95,6 +100,13 @@ def lib():
         L.dc_cost_candidates.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp]
         L.dc_last_fused_ops.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_search.argtypes = [vp, i32, C.POINTER(DcSearchParams), vp, C.POINTER(DcSearchResult), vp]
+        L.dc_num_params.argtypes = [vp]
+        L.dc_num_params.restype = C.c_int64
+        L.dc_train_begin.argtypes = [vp, C.POINTER(DcTrainParams), vp]
+        L.dc_fused_op_batch.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp]
+        L.dc_loss_gradients.argtypes = [vp, C.POINTER(DcBatch), vp, vp, vp, vp, vp]
+        L.dc_train_step.argtypes = [vp, C.POINTER(DcBatch), vp, vp, vp]
+        L.dc_get_weights.argtypes = [vp, vp, vp, vp, vp]
         L.dc_check.argtypes = [vp, vp]
         L.dc_last_totals.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_last_error.argtypes = [vp]
@@ -103,7 +115,8 @@ def lib():
         L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
         for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
                   "dc_gnn_forward", "dc_eval_candidates", "dc_simulate", "dc_check", "dc_last_totals", "dc_profile_begin",
-                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops", "dc_search"):
+                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops", "dc_search",
+                  "dc_train_begin", "dc_fused_op_batch", "dc_loss_gradients", "dc_train_step", "dc_get_weights"):
             getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -182,6 +195,30 @@ def dc_search(ctx, graph: int, params: DcSearchParams, labels_opt: Optional[np.n
               stream: int = 0) -> int:
     return lib().dc_search(ctx, graph, C.byref(params), None if labels_opt is None else labels_opt.ctypes.data,
                            C.byref(res), stream)
+
+
+def dc_num_params(ctx) -> int:
+    return int(lib().dc_num_params(ctx))
+
+
+def dc_train_begin(ctx, params: DcTrainParams, stream: int = 0) -> int:
+    return lib().dc_train_begin(ctx, C.byref(params), stream)
+
+
+def dc_fused_op_batch(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, batch: DcBatch, stream: int = 0) -> int:
+    return lib().dc_fused_op_batch(ctx, n_cand, cand_graph_ptr, cand_off_ptr, group_id_ptr, C.byref(batch), stream)
+
+
+def dc_loss_gradients(ctx, batch: DcBatch, target_ptr, loss_ptr, pred_ptr, grad_ptr, stream: int = 0) -> int:
+    return lib().dc_loss_gradients(ctx, C.byref(batch), target_ptr, loss_ptr, pred_ptr, grad_ptr, stream)
+
+
+def dc_train_step(ctx, batch: DcBatch, target_ptr, loss_ptr, stream: int = 0) -> int:
+    return lib().dc_train_step(ctx, C.byref(batch), target_ptr, loss_ptr, stream)
+
+
+def dc_get_weights(ctx, W_layers: np.ndarray, b_layers: np.ndarray, head: np.ndarray, stream: int = 0) -> int:
+    return lib().dc_get_weights(ctx, W_layers.ctypes.data, b_layers.ctypes.data, head.ctypes.data, stream)
 
 
 def dc_check(ctx, stream: int = 0) -> int:
@@ -359,6 +396,47 @@ class Evaluator:
         labels = np.zeros(n_nodes, np.int32)
         self._ok(dc_search(self.ctx, graph, p, labels, r, self._stream()), "dc_search")
         return labels, r
+
+    # ---- training of the estimator ----
+    def num_params(self) -> int:
+        return dc_num_params(self.ctx)
+
+    def train_begin(self, lr: float, max_samples: int, max_rows: int, beta1: float = 0.9, beta2: float = 0.999,
+                    eps: float = 1e-8, floor: float = 1e-6):
+        p = DcTrainParams(lr, beta1, beta2, eps, floor, max_samples, max_rows)
+        self._ok(dc_train_begin(self.ctx, p, self._stream()), "dc_train_begin")
+
+    def fused_op_batch(self, cand_graph, cand_off, group_id, batch: DeviceBatch) -> DeviceBatch:
+        n_cand = int(cand_graph.numel())
+        self._ok(dc_fused_op_batch(self.ctx, n_cand, cand_graph.data_ptr(), cand_off.data_ptr(), group_id.data_ptr(),
+                                   batch.c, self._stream()), "dc_fused_op_batch")
+        return batch
+
+    def loss_gradients(self, batch: DeviceBatch, target, want_grad: bool = True):
+        """(loss [1], pred [n], grad [num_params] or None), device tensors."""
+        f32 = dict(dtype=self.torch.float32, device=self.device)
+        loss = self.torch.empty(1, **f32)
+        pred = self.torch.empty(max(batch.c.n_cand, 1), **f32)
+        grad = self.torch.empty(max(self.num_params(), 1), **f32) if want_grad else None
+        self._ok(dc_loss_gradients(self.ctx, batch.c, target.data_ptr(), loss.data_ptr(), pred.data_ptr(),
+                                   grad.data_ptr() if want_grad else None, self._stream()), "dc_loss_gradients")
+        return loss, pred[:batch.c.n_cand], grad
+
+    def train_step(self, batch: DeviceBatch, target, loss=None):
+        if loss is None:
+            loss = self.torch.empty(1, dtype=self.torch.float32, device=self.device)
+        self._ok(dc_train_step(self.ctx, batch.c, target.data_ptr(), loss.data_ptr(), self._stream()), "dc_train_step")
+        return loss
+
+    def get_weights(self):
+        """(W_layers, b_layers, head) as host fp32 arrays in the layout of dc_set_weights."""
+        c = self.cfg
+        nW = sum(3 * (c.F if l == 0 else c.H) * c.H for l in range(c.L))
+        W = np.empty(nW, np.float32)
+        b = np.empty(c.L * c.H, np.float32)
+        hd = np.empty(2 * c.H * c.H + 3 * c.H + 1, np.float32)
+        self._ok(dc_get_weights(self.ctx, W, b, hd, self._stream()), "dc_get_weights")
+        return W, b, hd
 
     def last_fused_ops(self) -> Tuple[int, int, int]:
         st, k, m, e = dc_last_fused_ops(self.ctx, self._stream())

@@ -1,4 +1,5 @@
 // C ABI of libdisco: context, argument checks, memory, launches (gfx950 only).
+#include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -74,6 +75,14 @@ struct dc_ctx {
   bool have_profile = false;
   std::vector<int> h_gno, h_geo;   // host copies of the base graphs' offsets
   int allow_fused = 1;
+  // training (dc_train_begin)
+  bool training = false;
+  dc_train_params tp{};
+  long long train_t = 0;         // Adam steps taken
+  char* train_mem = nullptr;
+  TrainPass tb{};                // the buffers of a pass
+  float* adam_m = nullptr;
+  float* adam_v = nullptr;
   Profiler prof;
   std::string err;
 };
@@ -481,6 +490,7 @@ dc_status dc_destroy(dc_ctx* ctx) {
   if (ctx->bg_mem) (void)hipFree(ctx->bg_mem);
   if (ctx->slab) (void)hipFree(ctx->slab);
   if (ctx->sim_scratch) (void)hipFree(ctx->sim_scratch);
+  if (ctx->train_mem) (void)hipFree(ctx->train_mem);
   delete ctx;
   return DC_OK;
 }
@@ -938,6 +948,267 @@ dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, 
   if (n_fused_ops) *n_fused_ops = ctx->h_pinned[8 + 3];
   if (n_edges) *n_edges = ctx->h_pinned[8 + 4];
   return DC_OK;
+}
+
+// ---------------------------------------------------------------------------
+// training of the estimator
+// ---------------------------------------------------------------------------
+namespace {
+__global__ void zero_kernel(float* p, long long n) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+    p[i] = 0.f;
+}
+
+size_t n_layer_weights(const dc_config& c) { return packed_weight_elems(c.F, c.H, c.L, 3); }
+size_t n_head_params(const dc_config& c) { return 2 * (size_t)c.H * c.H + 3 * (size_t)c.H + 1; }
+
+dc_status train_ready(dc_ctx* ctx, const dc_batch* in) {
+  if (!ctx->training) return fail(ctx, DC_ERR_INVALID_ARG, "dc_train_begin has not been called");
+  if (!in || in->n_cand < 0) return fail(ctx, DC_ERR_INVALID_ARG, "null batch or negative count");
+  if (in->n_cand > ctx->tp.max_samples) return fail(ctx, DC_ERR_CAPACITY, "the batch has more graphs than max_samples");
+  return DC_OK;
+}
+
+// forward, loss and (with a gradient vector) the reverse pass over one batch
+dc_status train_pass(dc_ctx* ctx, const dc_batch* in, const float* target, float* loss, float* pred, float* grad,
+                     hipStream_t s) {
+  if (!target || !loss || !in->node_off || !in->out_rowptr || !in->out_col || !in->in_rowptr || !in->in_col || !in->Xc)
+    return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  const long long cap = in->cap_nodes < ctx->tp.max_rows ? in->cap_nodes : ctx->tp.max_rows;
+  hipLaunchKernelGGL(check_batch_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, s, in->node_off, in->n_cand, cap,
+                     (long long)in->cap_edges, in->out_rowptr, in->out_col, in->in_rowptr, in->in_col, ctx->status);
+  TrainPass t = ctx->tb;
+  t.n_samples = in->n_cand;
+  t.node_off = in->node_off;
+  t.out_rowptr = in->out_rowptr;
+  t.out_col = in->out_col;
+  t.in_rowptr = in->in_rowptr;
+  t.in_col = in->in_col;
+  t.X = static_cast<const float*>(in->Xc);
+  t.target = target;
+  t.W = static_cast<const float*>(ctx->W);
+  t.b = ctx->b;
+  t.head = ctx->head;
+  t.grad = grad;
+  t.loss = loss;
+  t.pred = pred;
+  hipError_t e = launch_train_pass(t, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "training pass launch");
+  return DC_OK;
+}
+}  // namespace
+
+int64_t dc_num_params(const dc_ctx* ctx) {
+  if (!ctx || ctx->cfg.aggregator != DC_AGG_MEAN) return 0;
+  return (int64_t)(n_layer_weights(ctx->cfg) + (size_t)ctx->cfg.L * ctx->cfg.H + n_head_params(ctx->cfg));
+}
+
+dc_status dc_train_begin(dc_ctx* ctx, const dc_train_params* params, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!params) return fail(ctx, DC_ERR_INVALID_ARG, "null parameters");
+  const dc_config& c = ctx->cfg;
+  if (c.dtype != DC_F32 || c.aggregator != DC_AGG_MEAN)
+    return fail(ctx, DC_ERR_UNSUPPORTED, "training needs a DC_F32 context with DC_AGG_MEAN");
+  if (!ctx->have_weights) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_weights has not been called");
+  const dc_train_params& p = *params;
+  if (!(p.lr >= 0.f) || !(p.beta1 >= 0.f && p.beta1 < 1.f) || !(p.beta2 >= 0.f && p.beta2 < 1.f) || !(p.eps > 0.f) ||
+      !(p.floor > 0.f))
+    return fail(ctx, DC_ERR_INVALID_ARG, "need lr >= 0, 0 <= beta < 1, eps > 0, floor > 0");
+  const Caps k = caps_of(c);
+  if (p.max_samples < 1 || p.max_rows < 1) return fail(ctx, DC_ERR_INVALID_ARG, "max_samples and max_rows must be positive");
+  if (p.max_rows > k.NN) return fail(ctx, DC_ERR_CAPACITY, "max_rows exceeds the context's max_nodes");
+  if (p.max_samples > INT32_MAX / 2 || p.max_rows * 3 * (long long)c.H > (1LL << 40))
+    return fail(ctx, DC_ERR_CAPACITY, "training batch too large");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipStreamSynchronize(s);
+  if (ctx->train_mem) (void)hipFree(ctx->train_mem);
+  ctx->train_mem = nullptr;
+  ctx->training = false;
+  const size_t R = (size_t)p.max_rows, B = (size_t)p.max_samples, H = (size_t)c.H;
+  const size_t dmax = (size_t)(c.F > c.H ? c.F : c.H);
+  const size_t P = (size_t)dc_num_params(ctx);
+  const int S = train_slabs(ctx->n_cu, c.F, c.H);
+  TrainPass t{};
+  float *m = nullptr, *v = nullptr;
+  for (int pass = 0; pass < 2; ++pass) {
+    Arena a;
+    a.base = pass ? ctx->train_mem : nullptr;
+    t.hs = a.take<float>((size_t)c.L * R * H);
+    t.dA = a.take<float>(R * 3 * H);
+    t.R = a.take<float>(B * H);
+    t.Z1 = a.take<float>(B * H);
+    t.Z2 = a.take<float>(B * H);
+    t.dZ2 = a.take<float>(B * H);
+    t.dZ1 = a.take<float>(B * H);
+    t.dR = a.take<float>(B * H);
+    t.y = a.take<float>(B);
+    t.dy = a.take<float>(B);
+    t.lterm = a.take<double>(B);
+    t.gid = a.take<int>(R);
+    t.cnt = a.take<int>(2);
+    t.WT = a.take<float>(3 * H * H);
+    t.part = a.take<float>((size_t)S * (3 * dmax * H + H));
+    t.grad = a.take<float>(P);
+    m = a.take<float>(P);
+    v = a.take<float>(P);
+    if (!pass) {
+      hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->train_mem), a.off);
+      if (e != hipSuccess) {
+        ctx->train_mem = nullptr;
+        return hip_fail(ctx, e, "training buffers");
+      }
+    }
+  }
+  t.F = c.F;
+  t.H = c.H;
+  t.L = c.L;
+  t.floor = p.floor;
+  t.mp = static_cast<float*>(ctx->agg[0]);
+  t.ms = static_cast<float*>(ctx->agg[1]);
+  t.dZ[0] = static_cast<float*>(ctx->act[0]);
+  t.dZ[1] = static_cast<float*>(ctx->act[1]);
+  t.slabs = S;
+  t.max_rows = p.max_rows;
+  t.status = ctx->status;
+  t.n_cu = ctx->n_cu;
+  ctx->tb = t;
+  ctx->adam_m = m;
+  ctx->adam_v = v;
+  ctx->tp = p;
+  ctx->train_t = 0;
+  hipLaunchKernelGGL(zero_kernel, dim3(256), dim3(256), 0, s, m, (long long)P);
+  hipLaunchKernelGGL(zero_kernel, dim3(256), dim3(256), 0, s, v, (long long)P);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e, "training state");
+  ctx->training = true;
+  return DC_OK;
+}
+
+dc_status dc_fused_op_batch(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
+                            const int32_t* group_id, dc_batch* out, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  dc_status st = cost_call_check(ctx, n_cand);
+  if (st != DC_OK) return st;
+  if (!out) return fail(ctx, DC_ERR_INVALID_ARG, "null batch");
+  if (!out->node_off || !out->edge_off || !out->new_id || !out->out_rowptr || !out->out_col || !out->in_rowptr ||
+      !out->in_col || !out->Xc || out->cap_nodes < 0 || out->cap_edges < 0)
+    return fail(ctx, DC_ERR_INVALID_ARG, "dc_batch has a null array or negative capacity");
+  out->n_cand = 0;
+  if (n_cand == 0) return DC_OK;
+  if (!cand_graph || !cand_off || !group_id) return fail(ctx, DC_ERR_INVALID_ARG, "null candidate array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
+  st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s);
+  if (st != DC_OK) return st;
+  Profiler* prof = ctx->prof.on ? &ctx->prof : nullptr;
+  FusedOpsArgs a = ctx->fo;
+  a.bg = ctx->bg;
+  a.n_cand = n_cand;
+  a.cand_graph = cand_graph;
+  a.cand_off = cand_off;
+  a.members = ctx->tmp.members;
+  a.mstart = ctx->tmp.mstart;
+  a.Gc = ctx->tmp.Gc;
+  a.new_id = ctx->ib.new_id;
+  a.c_node_off = ctx->ib.node_off;
+  a.op_time = ctx->m_op_time;
+  a.ar_size = ctx->m_ar_size;
+  // the batch goes to the caller's arrays, within the caller's capacities
+  a.fb.node_off = out->node_off;
+  a.fb.edge_off = out->edge_off;
+  a.fb.new_id = out->new_id;
+  a.fb.out_rowptr = out->out_rowptr;
+  a.fb.out_col = out->out_col;
+  a.fb.in_rowptr = out->in_rowptr;
+  a.fb.in_col = out->in_col;
+  a.fb.Xc = out->Xc;
+  a.fb.cap_nodes = out->cap_nodes;
+  a.fb.cap_edges = out->cap_edges;
+  if (out->cap_nodes < a.cap_rows) a.cap_rows = out->cap_nodes;
+  if (out->cap_edges < a.cap_edges) a.cap_edges = out->cap_edges;
+  if (out->cap_nodes / 2 + 1 < a.cap_ops) a.cap_ops = out->cap_nodes / 2 + 1;
+  hipError_t e = launch_fused_op_extract(a, prof, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fused-op extraction launch");
+  int64_t K = 0;
+  st = dc_last_fused_ops(ctx, &K, nullptr, nullptr, stream);
+  if (st != DC_OK) return st;
+  st = dc_check(ctx, stream);
+  if (st != DC_OK) return st;
+  out->n_cand = (int32_t)K;
+  return DC_OK;
+}
+
+dc_status dc_loss_gradients(dc_ctx* ctx, const dc_batch* in, const float* target, float* loss, float* pred,
+                            float* grad, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  dc_status st = train_ready(ctx, in);
+  if (st != DC_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!loss) return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  if (in->n_cand == 0) {
+    hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(64), 0, s, loss, 1LL);
+    if (grad) hipLaunchKernelGGL(zero_kernel, dim3(256), dim3(256), 0, s, grad, (long long)dc_num_params(ctx));
+    return DC_OK;
+  }
+  // the reverse pass writes the context's gradient vector; a caller's array receives a copy
+  st = train_pass(ctx, in, target, loss, pred, grad ? ctx->tb.grad : nullptr, s);
+  if (st != DC_OK || !grad) return st;
+  hipError_t e = hipMemcpyAsync(grad, ctx->tb.grad, (size_t)dc_num_params(ctx) * sizeof(float),
+                                hipMemcpyDeviceToDevice, s);
+  return e == hipSuccess ? DC_OK : hip_fail(ctx, e, "gradient copy");
+}
+
+dc_status dc_train_step(dc_ctx* ctx, const dc_batch* in, const float* target, float* loss, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  dc_status st = train_ready(ctx, in);
+  if (st != DC_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!loss) return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  if (in->n_cand == 0) {
+    hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(64), 0, s, loss, 1LL);
+    return DC_OK;
+  }
+  st = train_pass(ctx, in, target, loss, nullptr, ctx->tb.grad, s);
+  if (st != DC_OK) return st;
+  const dc_config& c = ctx->cfg;
+  const dc_train_params& p = ctx->tp;
+  const long long tstep = ++ctx->train_t;
+  const double c1 = 1.0 / (1.0 - pow((double)p.beta1, (double)tstep));
+  const double c2 = 1.0 / (1.0 - pow((double)p.beta2, (double)tstep));
+  const long long nW = (long long)n_layer_weights(c), nb = (long long)c.L * c.H, nh = (long long)n_head_params(c);
+  const float* g = ctx->tb.grad;
+  hipError_t e = launch_adam(static_cast<float*>(ctx->W), g, ctx->adam_m, ctx->adam_v, nW, p.lr, p.beta1, p.beta2,
+                             p.eps, c1, c2, ctx->status, s);
+  if (e == hipSuccess)
+    e = launch_adam(ctx->b, g + nW, ctx->adam_m + nW, ctx->adam_v + nW, nb, p.lr, p.beta1, p.beta2, p.eps, c1, c2,
+                    ctx->status, s);
+  if (e == hipSuccess)
+    e = launch_adam(ctx->head, g + nW + nb, ctx->adam_m + nW + nb, ctx->adam_v + nW + nb, nh, p.lr, p.beta1, p.beta2,
+                    p.eps, c1, c2, ctx->status, s);
+  // the copy of W1 | W2 that the fused-op path multiplies with (same layout in fp32)
+  const size_t HH = (size_t)c.H * c.H;
+  if (e == hipSuccess) e = hipMemcpyAsync(ctx->headW, ctx->head, HH * sizeof(float), hipMemcpyDeviceToDevice, s);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(static_cast<float*>(ctx->headW) + HH, ctx->head + HH + c.H, HH * sizeof(float),
+                       hipMemcpyDeviceToDevice, s);
+  return e == hipSuccess ? DC_OK : hip_fail(ctx, e, "optimiser step");
+}
+
+dc_status dc_get_weights(dc_ctx* ctx, float* W_layers, float* b_layers, float* head, void* stream) {
+  if (!ctx) return DC_ERR_INVALID_ARG;
+  if (!W_layers || !b_layers || !head) return fail(ctx, DC_ERR_INVALID_ARG, "null array");
+  const dc_config& c = ctx->cfg;
+  if (c.dtype != DC_F32 || c.aggregator != DC_AGG_MEAN)
+    return fail(ctx, DC_ERR_UNSUPPORTED, "dc_get_weights needs a DC_F32 context with DC_AGG_MEAN");
+  if (!ctx->have_weights) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_weights has not been called");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(W_layers, ctx->W, n_layer_weights(c) * sizeof(float), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(b_layers, ctx->b, (size_t)c.L * c.H * sizeof(float), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(head, ctx->head, n_head_params(c) * sizeof(float), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  return e == hipSuccess ? DC_OK : hip_fail(ctx, e, "dc_get_weights");
 }
 
 dc_status dc_check(dc_ctx* ctx, void* stream) {

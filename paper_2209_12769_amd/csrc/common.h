@@ -121,6 +121,12 @@ hipError_t launch_gnn_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, co
 // out = ReLU(A Wp + bias) for the node_off[n_cand] rows of A [rows, d]; Wp in the device layout of one layer block.
 void launch_dense_bias_relu(const GnnArgs& a, const void* A, int d, const void* Wp, const float* bias, void* out,
                             hipStream_t s);
+// The two neighbour means of every row of h [rows, d] (separate kernel; any d that is a multiple of 16 bytes).
+void launch_mean_aggregate(const GnnArgs& a, const void* h, int d, void* h_in, void* h_out, hipStream_t s);
+// out [rows, a.H] = [A0 | A1 | A2] Wl (nseg = 3) or A0 Wl (nseg = 1), rows = a.node_off[a.n_cand]; with a bias
+// the result is ReLU(. + bias), without one it is stored as it is.  a.H must be a multiple of 32.
+void launch_dense_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg,
+                         const void* Wl, const float* bias, void* out, hipStream_t s);
 // Elements (of the storage dtype) of all layer matrices in device layout; nseg row blocks of
 // d rows per layer (3: self / predecessor mean / successor mean; 1: attention).
 size_t packed_weight_elems(int F, int H, int L, int nseg);
@@ -209,6 +215,56 @@ struct SearchView {
 };
 dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_search_params& p, int32_t* labels_opt,
                      dc_search_result* res, hipStream_t s);
+
+// train.hip: one pass of supervised training of the estimator (fp32): forward with kept activations,
+// loss, reverse pass into one gradient vector laid out W_layers | b_layers | head; Adam.
+struct TrainPass {
+  // the batch of sample graphs
+  int n_samples;               // host-known number of graphs
+  const int* node_off;         // [n_samples + 1]
+  const int* out_rowptr;
+  const int* out_col;
+  const int* in_rowptr;
+  const int* in_col;
+  const float* X;              // [rows, F]
+  const float* target;         // [n_samples]
+  // parameters (row-major fp32)
+  const float* W;
+  const float* b;
+  const float* head;
+  int F, H, L;
+  float floor;
+  // buffers
+  float* hs;                   // [L][max_rows, H] activations after each layer
+  float* mp;                   // [max_rows, max(F,H)] predecessor mean of the layer at hand
+  float* ms;                   // successor mean
+  float* dZ[2];                // [max_rows, H] gradient at the pre-activations, ping-pong
+  float* dA;                   // [max_rows, 3H]
+  float* R;                    // [max_samples, H] each: R, Z1, Z2, dZ2, dZ1, dR
+  float* Z1;
+  float* Z2;
+  float* dZ2;
+  float* dZ1;
+  float* dR;
+  float* y;                    // [max_samples]
+  float* dy;
+  double* lterm;               // [max_samples] per-sample loss terms
+  int* gid;                    // [max_rows] sample of each row
+  int* cnt;                    // {0, n_samples}
+  float* WT;                   // [H, 3H] transposed matrix of the layer at hand
+  float* part;                 // [slabs][3 max(F,H) H + H] partial sums of the weight gradients
+  int slabs;
+  long long max_rows;
+  float* grad;                 // [n_params]
+  float* loss;                 // [1]
+  float* pred;                 // [n_samples] or null
+  int* status;
+  int n_cu;
+};
+hipError_t launch_train_pass(const TrainPass& t, hipStream_t s);
+int train_slabs(int n_cu, int F, int H);
+hipError_t launch_adam(float* theta, const float* grad, float* m, float* v, long long n, float lr, float beta1,
+                       float beta2, float eps, double c1, double c2, const int* status, hipStream_t s);
 
 __global__ void reset_status_kernel(int* status);
 

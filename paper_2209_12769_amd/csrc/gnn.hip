@@ -473,6 +473,20 @@ hipError_t launch_gnn_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, co
   return a.heads > 0 ? attention_layers(a, prof, s, h_last) : mean_layers(a, prof, s, h_last);
 }
 
+void launch_mean_aggregate(const GnnArgs& a, const void* h, int d, void* h_in, void* h_out, hipStream_t s) {
+  if (a.bf16)
+    hipLaunchKernelGGL(aggregate_kernel<true>, dim3(a.n_cu * 8), dim3(256), 0, s, h, d, a.in_rowptr, a.in_col,
+                       a.out_rowptr, a.out_col, h_in, h_out, a.node_off, a.n_cand, a.status);
+  else
+    hipLaunchKernelGGL(aggregate_kernel<false>, dim3(a.n_cu * 8), dim3(256), 0, s, h, d, a.in_rowptr, a.in_col,
+                       a.out_rowptr, a.out_col, h_in, h_out, a.node_off, a.n_cand, a.status);
+}
+
+void launch_dense_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg,
+                         const void* Wl, const float* bias, void* out, hipStream_t s) {
+  run_update(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+}
+
 void launch_dense_bias_relu(const GnnArgs& a, const void* A, int d, const void* Wp, const float* bias, void* out,
                             hipStream_t s) {
   if (a.allow_fused && layer256_supported(d, a.H, a.bf16) && launch_dense256(A, d, a, Wp, bias, out, s) == hipSuccess)

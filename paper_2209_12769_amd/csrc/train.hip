@@ -1,0 +1,517 @@
+// Supervised training of the fused-op estimator (Sec. 3.3.3) on gfx950, fp32.
+//
+// One pass = forward with the activations of every layer kept, the loss of Eq. (1) read as the
+// mean squared difference of logarithms, and the reverse pass of exactly the forward formulas:
+//     y = z2.w3 + b3,  z2 = ReLU(z1 W2 + b2),  z1 = ReLU(r W1 + b1),  r = sum of h_L over the
+//     ops of the fused op (Secs. 3.3.1, 3.3.2),
+//     h_{l+1} = ReLU([h_l | mean over predecessors | mean over successors] W_l + b_l).
+// Dense products run on the fp32 matrix cores (32x32x2): forward and the data gradients through the
+// layer update kernel, the weight gradients through wgrad_kernel below, whose contraction
+// index is the row of the batch (transposed-A product, split over slabs of rows, partial
+// results reduced in a fixed order, so a pass is bit-reproducible).  Everything else is
+// bandwidth-bound and done by plain grid-stride kernels.  Adam as published by Kingma & Ba.
+#include "common.h"
+
+namespace dc {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---- sample of each row: largest g with node_off[g] <= v (graphs may be empty) ----
+__global__ __launch_bounds__(256) void gid_kernel(const int* __restrict__ node_off, int B, int* __restrict__ gid,
+                                                  const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const long long ntot = node_off[B];
+  for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < ntot;
+       v += (long long)gridDim.x * blockDim.x) {
+    int lo = 0, hi = B;                 // invariant: node_off[lo] <= v < node_off[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (node_off[mid] <= v) lo = mid; else hi = mid;
+    }
+    gid[v] = lo;
+  }
+}
+
+// ---- r[g] = sum over the rows of graph g, fp64 in ascending row order ----
+__global__ __launch_bounds__(256) void readout_kernel(const float* __restrict__ h, int H,
+                                                      const int* __restrict__ node_off, int B,
+                                                      float* __restrict__ R, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int cpr = H / 4;
+  const long long total = (long long)B * cpr;
+  const float4* __restrict__ h4 = reinterpret_cast<const float4*>(h);
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const int g = (int)(idx / cpr), ch = (int)(idx - (long long)g * cpr);
+    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    for (int v = node_off[g]; v < node_off[g + 1]; ++v) {
+      const float4 x = h4[(size_t)v * cpr + ch];
+      a0 += x.x; a1 += x.y; a2 += x.z; a3 += x.w;
+    }
+    reinterpret_cast<float4*>(R)[idx] = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
+  }
+}
+
+// ---- per sample: y, the loss term and dL/dy; one wave per sample ----
+__global__ __launch_bounds__(256) void loss_kernel(const float* __restrict__ Z2, int H, const float* __restrict__ w3b3,
+                                                   const float* __restrict__ target, int B, float floor_,
+                                                   float* __restrict__ y, float* __restrict__ dy,
+                                                   double* __restrict__ lterm, float* __restrict__ pred,
+                                                   const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int lane = threadIdx.x & 63;
+  const int wpb = blockDim.x >> 6;
+  for (int g = blockIdx.x * wpb + (threadIdx.x >> 6); g < B; g += gridDim.x * wpb) {
+    double s = 0.0;
+    for (int j = lane; j < H; j += 64) s += (double)Z2[(size_t)g * H + j] * (double)w3b3[j];
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) {
+      const float yf = (float)(s + (double)w3b3[H]);
+      const double yc = yf > floor_ ? (double)yf : (double)floor_;
+      const double dl = log(yc) - log((double)target[g]);
+      y[g] = yf;
+      if (pred) pred[g] = yf;
+      lterm[g] = dl * dl;
+      dy[g] = yf > floor_ ? (float)(2.0 / (double)B * dl / yc) : 0.f;
+    }
+  }
+}
+
+// ---- loss = mean of the terms; one workgroup, fixed order ----
+__global__ __launch_bounds__(1024) void loss_reduce_kernel(const double* __restrict__ lterm, int B,
+                                                           float* __restrict__ loss,
+                                                           const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  __shared__ double red[1024];
+  double s = 0.0;
+  for (int g = threadIdx.x; g < B; g += 1024) s += lterm[g];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = B > 0 ? (float)(red[0] / (double)B) : 0.f;
+}
+
+// ---- dz2[g][j] = dy[g] w3[j] where z2 > 0 ----
+__global__ __launch_bounds__(256) void dz2_kernel(const float* __restrict__ Z2, const float* __restrict__ dy,
+                                                  const float* __restrict__ w3, int H, int B,
+                                                  float* __restrict__ dZ2, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const long long total = (long long)B * H;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int g = (int)(i / H), j = (int)(i - (long long)g * H);
+    dZ2[i] = Z2[i] > 0.f ? dy[g] * w3[j] : 0.f;
+  }
+}
+
+// ---- x = 0 where the activation is not positive (ReLU'), rows from a device count ----
+__global__ __launch_bounds__(256) void relu_mask_kernel(float* __restrict__ x, const float* __restrict__ act,
+                                                        const int* __restrict__ nrows, int H,
+                                                        const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const long long total = (long long)nrows[0] * H;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x)
+    if (!(act[i] > 0.f)) x[i] = 0.f;
+}
+
+// ---- gradient at the last layer's pre-activations: every op of a fused op receives dr ----
+__global__ __launch_bounds__(256) void top_kernel(const float* __restrict__ dR, const int* __restrict__ gid,
+                                                  const float* __restrict__ hL, const int* __restrict__ nrows, int H,
+                                                  float* __restrict__ dZ, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int cpr = H / 4;
+  const long long total = (long long)nrows[0] * cpr;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const long long v = i / cpr;
+    const int ch = (int)(i - v * cpr);
+    const float4 g = reinterpret_cast<const float4*>(dR)[(size_t)gid[v] * cpr + ch];
+    const float4 a = reinterpret_cast<const float4*>(hL)[i];
+    reinterpret_cast<float4*>(dZ)[i] = make_float4(a.x > 0.f ? g.x : 0.f, a.y > 0.f ? g.y : 0.f,
+                                                   a.z > 0.f ? g.z : 0.f, a.w > 0.f ? g.w : 0.f);
+  }
+}
+
+// ---- WT [N, M] = transpose of W [M, N] ----
+__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ W, int M, int N,
+                                                        float* __restrict__ WT, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const int tm = (M + 31) / 32, tn = (N + 31) / 32;
+  for (int t = blockIdx.x; t < tm * tn; t += gridDim.x) {
+    const int m0 = (t / tn) * 32, n0 = (t % tn) * 32;
+    for (int r = ty; r < 32; r += 8)
+      tile[r][tx] = (m0 + r < M && n0 + tx < N) ? W[(size_t)(m0 + r) * N + n0 + tx] : 0.f;
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8)
+      if (n0 + r < N && m0 + tx < M) WT[(size_t)(n0 + r) * M + m0 + tx] = tile[tx][r];
+    __syncthreads();
+  }
+}
+
+// ---- reverse of the two neighbour means, plus the node's own block, then ReLU' of the layer below ----
+// dA [rows, 3d] = dZ W^T holds per row v the gradient at [h[v] | mean over pred(v) | mean over succ(v)].
+// h[u] enters the predecessor mean of each successor v with weight 1/indeg(v), and the successor
+// mean of each predecessor v with weight 1/outdeg(v).
+__global__ __launch_bounds__(256) void gather_back_kernel(const float* __restrict__ dA, int d,
+                                                          const int* __restrict__ in_rp, const int* __restrict__ in_ci,
+                                                          const int* __restrict__ out_rp,
+                                                          const int* __restrict__ out_ci,
+                                                          const float* __restrict__ h, const int* __restrict__ nrows,
+                                                          float* __restrict__ dZ, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int cpr = d / 4;
+  const long long total = (long long)nrows[0] * cpr;
+  const float4* __restrict__ A4 = reinterpret_cast<const float4*>(dA);
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const long long u = i / cpr;
+    const int ch = (int)(i - u * cpr);
+    float4 acc = A4[(size_t)u * 3 * cpr + ch];
+    for (int k = out_rp[u]; k < out_rp[u + 1]; ++k) {
+      const int v = out_ci[k];
+      const float sc = 1.0f / (float)(in_rp[v + 1] - in_rp[v]);
+      const float4 x = A4[(size_t)v * 3 * cpr + cpr + ch];
+      acc.x += x.x * sc; acc.y += x.y * sc; acc.z += x.z * sc; acc.w += x.w * sc;
+    }
+    for (int k = in_rp[u]; k < in_rp[u + 1]; ++k) {
+      const int v = in_ci[k];
+      const float sc = 1.0f / (float)(out_rp[v + 1] - out_rp[v]);
+      const float4 x = A4[(size_t)v * 3 * cpr + 2 * cpr + ch];
+      acc.x += x.x * sc; acc.y += x.y * sc; acc.z += x.z * sc; acc.w += x.w * sc;
+    }
+    const float4 a = reinterpret_cast<const float4*>(h)[i];
+    reinterpret_cast<float4*>(dZ)[i] = make_float4(a.x > 0.f ? acc.x : 0.f, a.y > 0.f ? acc.y : 0.f,
+                                                   a.z > 0.f ? acc.z : 0.f, a.w > 0.f ? acc.w : 0.f);
+  }
+}
+
+// ---- weight gradients: C [M, N] = sum over rows r of A[r][:]^T B[r][:], M = nseg * d ----
+// One workgroup = one 128 x 128 tile of C over one slab of rows; 4 waves of 64 x 64.  The
+// contraction index is the batch row, so both MFMA operands are read straight from global memory
+// with 32 consecutive lanes on 32 consecutive columns of one row (lanes 32..63: the next row).
+// The column sums of B (bias gradients) ride along in the waves of the first row of tiles.
+constexpr int kWT = 128;
+__global__ __launch_bounds__(256) void wgrad_kernel(const float* __restrict__ A0, const float* __restrict__ A1,
+                                                    const float* __restrict__ A2, int d, int nseg,
+                                                    const float* __restrict__ Bm, int ldb, int N,
+                                                    const int* __restrict__ nrows, float* __restrict__ part,
+                                                    long long part_stride, int S, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int M = nseg * d;
+  const int tiles_n = (N + kWT - 1) / kWT, tiles_m = (M + kWT - 1) / kWT;
+  const int ntile = tiles_m * tiles_n;
+  const int tile = blockIdx.x % ntile, slab = blockIdx.x / ntile;
+  if (slab >= S) return;
+  const int m0 = (tile / tiles_n) * kWT, n0 = (tile % tiles_n) * kWT;
+  const int rows = nrows[0];
+  const int per = (((rows + S - 1) / S) + 1) & ~1;
+  const long long r0 = (long long)slab * per;
+  const long long r1 = r0 + per < rows ? r0 + per : rows;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lh = lane >> 5;
+
+  const float* ap[2];
+  const float* bp[2];
+  bool av[2], bv[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = m0 + wm * 64 + i * 32 + l32;
+    av[i] = m < M;
+    const int mm = av[i] ? m : 0;
+    const int seg = mm / d;
+    ap[i] = (seg == 0 ? A0 : (seg == 1 ? A1 : A2)) + (mm - seg * d);
+    const int n = n0 + wn * 64 + i * 32 + l32;
+    bv[i] = n < N;
+    bp[i] = Bm + (bv[i] ? n : 0);
+  }
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  float bsum[2] = {0.f, 0.f};
+
+  // pairs of rows (lane half lh takes row 2*it + lh); an odd last row is taken by half 0 alone
+  const int npair = r1 > r0 ? (int)((r1 - r0) >> 1) : 0;
+  const size_t sa = (size_t)d, sb = (size_t)ldb;
+  const float* pa[2] = {ap[0] + (size_t)(r0 + lh) * sa, ap[1] + (size_t)(r0 + lh) * sa};
+  const float* pb[2] = {bp[0] + (size_t)(r0 + lh) * sb, bp[1] + (size_t)(r0 + lh) * sb};
+  if (npair > 0) {
+    // software pipeline: the loads of the next kU pairs are in flight while this chunk multiplies;
+    // positions past the end re-read the last pair (in bounds) and are zeroed where they are used
+    constexpr int kU = 8;
+    float ca[kU][2], cb[kU][2];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const size_t k = (size_t)(u < npair ? u : npair - 1) * 2;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        ca[u][i] = pa[i][k * sa];
+        cb[u][i] = pb[i][k * sb];
+      }
+    }
+    for (int base = 0; base < npair; base += kU) {
+      float na[kU][2], nb[kU][2];
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int it = base + kU + u;
+        const size_t k = (size_t)(it < npair ? it : npair - 1) * 2;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          na[u][i] = pa[i][k * sa];
+          nb[u][i] = pb[i][k * sb];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of this chunk's products
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const bool in = base + u < npair;
+        float a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          a[i] = (in && av[i]) ? ca[u][i] : 0.f;
+          b[i] = (in && bv[i]) ? cb[u][i] : 0.f;
+          bsum[i] += b[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < kU; ++u)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          ca[u][i] = na[u][i];
+          cb[u][i] = nb[u][i];
+        }
+    }
+  }
+  if (r1 > r0 && ((r1 - r0) & 1)) {
+    const size_t rl = (size_t)(r1 - 1);
+    float a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const float x = ap[i][rl * sa];
+      a[i] = (lh == 0 && av[i]) ? x : 0.f;
+      const float y = bp[i][rl * sb];
+      b[i] = (lh == 0 && bv[i]) ? y : 0.f;
+      bsum[i] += b[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+
+  float* P = part + (size_t)slab * (size_t)part_stride;
+  // accumulator register v of lane (l32, lh) holds row 8*(v/4) + 4*lh + (v%4), column l32 of its 32 x 32 block
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = n0 + wn * 64 + j * 32 + l32;
+    if (n >= N) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        if (m < M) P[(size_t)m * N + n] = acc[i][j][v];
+      }
+  }
+  if (m0 == 0 && wm == 0) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float tot = bsum[j] + __shfl_xor(bsum[j], 32, 64);
+      const int n = n0 + wn * 64 + j * 32 + l32;
+      if (lh == 0 && n < N) P[(size_t)M * N + n] = tot;
+    }
+  }
+}
+
+// gW [M*N] and gb [N] = sums of the slabs' partial results, fp64, ascending slab order
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part, long long part_stride,
+                                                           int S, long long MN, int N, float* __restrict__ gW,
+                                                           float* __restrict__ gb, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const long long total = MN + (gb ? N : 0);
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    double s = 0.0;
+    for (int k = 0; k < S; ++k) s += (double)part[(size_t)k * (size_t)part_stride + i];
+    if (i < MN) gW[i] = (float)s; else gb[i - MN] = (float)s;
+  }
+}
+
+__global__ void set_count_kernel(int* cnt, int n) {
+  cnt[0] = 0;
+  cnt[1] = n;
+}
+
+__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, const float* __restrict__ g,
+                                                   float* __restrict__ m, float* __restrict__ v, long long n,
+                                                   float lr, float beta1, float beta2, float eps, float c1, float c2,
+                                                   const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (long long)gridDim.x * blockDim.x) {
+    const float gi = g[i];
+    const float mi = beta1 * m[i] + (1.f - beta1) * gi;
+    const float vi = beta2 * v[i] + (1.f - beta2) * gi * gi;
+    m[i] = mi;
+    v[i] = vi;
+    theta[i] -= lr * (mi * c1) / (sqrtf(vi * c2) + eps);      // c1 = 1/(1-beta1^t), c2 = 1/(1-beta2^t)
+  }
+}
+
+int grid_for(long long items, int n_cu) {
+  long long g = (items + 255) / 256;
+  const long long cap = (long long)n_cu * 16;
+  if (g > cap) g = cap;
+  return g < 1 ? 1 : (int)g;
+}
+
+// C = sum over rows of [A0|A1|A2]^T B into gW (and column sums of B into gb)
+void weight_gradient(const TrainPass& t, const float* A0, const float* A1, const float* A2, int d, int nseg,
+                     const float* Bm, int ldb, int N, const int* nrows, float* gW, float* gb, hipStream_t s) {
+  const int M = nseg * d;
+  const int ntile = ((M + kWT - 1) / kWT) * ((N + kWT - 1) / kWT);
+  const long long stride = (long long)M * N + N;
+  hipLaunchKernelGGL(wgrad_kernel, dim3(ntile * t.slabs), dim3(256), 0, s, A0, A1, A2, d, nseg, Bm, ldb, N, nrows,
+                     t.part, stride, t.slabs, t.status);
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(stride, t.n_cu)), dim3(256), 0, s, t.part, stride, t.slabs,
+                     (long long)M * N, N, gW, gb, t.status);
+}
+
+}  // namespace
+
+int train_slabs(int n_cu, int F, int H) {
+  // enough slabs that the smallest product of a pass still covers the chip twice
+  (void)F;
+  const int ntile = ((H + kWT - 1) / kWT) * ((H + kWT - 1) / kWT);
+  int S = (2 * n_cu + ntile - 1) / ntile;
+  if (S > 128) S = 128;
+  return S < 1 ? 1 : S;
+}
+
+hipError_t launch_train_pass(const TrainPass& t, hipStream_t s) {
+  const int B = t.n_samples, H = t.H, F = t.F, L = t.L;
+  const size_t HH = (size_t)H * H;
+  const int* nrows = t.node_off + B;          // device-resident row count
+  GnnArgs g{};
+  g.n_cand = B;
+  g.node_off = t.node_off;
+  g.out_rowptr = t.out_rowptr;
+  g.out_col = t.out_col;
+  g.in_rowptr = t.in_rowptr;
+  g.in_col = t.in_col;
+  g.H = H;
+  g.bf16 = 0;
+  g.status = t.status;
+  g.n_cu = t.n_cu;
+  GnnArgs gh = g;                              // the regression network: one row per sample
+  gh.n_cand = 1;
+  gh.node_off = t.cnt;
+  const long long rows_cap = t.max_rows;
+  const float* W1 = t.head;
+  const float* b1 = W1 + HH;
+  const float* W2 = b1 + H;
+  const float* b2 = W2 + HH;
+  const float* w3 = b2 + H;                    // followed by b3
+  // gradient vector: W_layers | b_layers | W1 b1 W2 b2 w3 b3
+  size_t nW = 0;
+  for (int l = 0; l < L; ++l) nW += (size_t)3 * (l == 0 ? F : H) * H;
+  float* gWl = t.grad;
+  float* gbl = t.grad + nW;
+  float* gW1 = gbl + (size_t)L * H;
+  float* gb1 = gW1 + HH;
+  float* gW2 = gb1 + H;
+  float* gb2 = gW2 + HH;
+  float* gw3 = gb2 + H;
+  float* gb3 = gw3 + H;
+
+  hipLaunchKernelGGL(set_count_kernel, dim3(1), dim3(1), 0, s, t.cnt, B);
+  hipLaunchKernelGGL(gid_kernel, dim3(grid_for(rows_cap, t.n_cu)), dim3(256), 0, s, t.node_off, B, t.gid, t.status);
+
+  // ---- forward, every layer's output kept ----
+  const float* hcur = t.X;
+  int d = F;
+  const float* Wl = t.W;
+  const float* bl = t.b;
+  for (int l = 0; l < L; ++l) {
+    float* hn = t.hs + (size_t)l * rows_cap * H;
+    launch_mean_aggregate(g, hcur, d, t.mp, t.ms, s);
+    launch_dense_update(g, hcur, t.mp, t.ms, d, 3, Wl, bl, hn, s);
+    Wl += (size_t)3 * d * H;
+    bl += H;
+    hcur = hn;
+    d = H;
+  }
+  hipLaunchKernelGGL(readout_kernel, dim3(grid_for((long long)B * (H / 4), t.n_cu)), dim3(256), 0, s, hcur, H,
+                     t.node_off, B, t.R, t.status);
+  launch_dense_update(gh, t.R, nullptr, nullptr, H, 1, W1, b1, t.Z1, s);
+  launch_dense_update(gh, t.Z1, nullptr, nullptr, H, 1, W2, b2, t.Z2, s);
+  hipLaunchKernelGGL(loss_kernel, dim3(grid_for((long long)B * 64, t.n_cu)), dim3(256), 0, s, t.Z2, H, w3, t.target, B,
+                     t.floor, t.y, t.dy, t.lterm, t.pred, t.status);
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, t.lterm, B, t.loss, t.status);
+  if (!t.grad) return hipGetLastError();
+
+  // ---- regression network, reverse ----
+  const int* nB = t.cnt + 1;
+  weight_gradient(t, t.Z2, nullptr, nullptr, H, 1, t.dy, 1, 1, nB, gw3, gb3, s);
+  hipLaunchKernelGGL(dz2_kernel, dim3(grid_for((long long)B * H, t.n_cu)), dim3(256), 0, s, t.Z2, t.dy, w3, H, B,
+                     t.dZ2, t.status);
+  weight_gradient(t, t.Z1, nullptr, nullptr, H, 1, t.dZ2, H, H, nB, gW2, gb2, s);
+  hipLaunchKernelGGL(transpose_kernel, dim3(64), dim3(256), 0, s, W2, H, H, t.WT, t.status);
+  launch_dense_update(gh, t.dZ2, nullptr, nullptr, H, 1, t.WT, nullptr, t.dZ1, s);
+  hipLaunchKernelGGL(relu_mask_kernel, dim3(grid_for((long long)B * H, t.n_cu)), dim3(256), 0, s, t.dZ1, t.Z1, nB, H,
+                     t.status);
+  weight_gradient(t, t.R, nullptr, nullptr, H, 1, t.dZ1, H, H, nB, gW1, gb1, s);
+  hipLaunchKernelGGL(transpose_kernel, dim3(64), dim3(256), 0, s, W1, H, H, t.WT, t.status);
+  launch_dense_update(gh, t.dZ1, nullptr, nullptr, H, 1, t.WT, nullptr, t.dR, s);
+
+  // ---- graph layers, reverse ----
+  float* dZ = t.dZ[0];
+  float* dZn = t.dZ[1];
+  hipLaunchKernelGGL(top_kernel, dim3(grid_for(rows_cap * (H / 4), t.n_cu)), dim3(256), 0, s, t.dR, t.gid, hcur, nrows,
+                     H, dZ, t.status);
+  GnnArgs g3 = g;
+  g3.H = 3 * H;                                // dA = dZ W^T is [rows, 3H] for the layers above the first
+  for (int l = L - 1; l >= 0; --l) {
+    const int dl = l == 0 ? F : H;
+    const float* hl = l == 0 ? t.X : t.hs + (size_t)(l - 1) * rows_cap * H;
+    size_t woff = 0;
+    for (int k = 0; k < l; ++k) woff += (size_t)3 * (k == 0 ? F : H) * H;
+    launch_mean_aggregate(g, hl, dl, t.mp, t.ms, s);
+    weight_gradient(t, hl, t.mp, t.ms, dl, 3, dZ, H, H, nrows, gWl + woff, gbl + (size_t)l * H, s);
+    if (l == 0) break;
+    hipLaunchKernelGGL(transpose_kernel, dim3(128), dim3(256), 0, s, t.W + woff, 3 * H, H, t.WT, t.status);
+    launch_dense_update(g3, dZ, nullptr, nullptr, H, 1, t.WT, nullptr, t.dA, s);
+    hipLaunchKernelGGL(gather_back_kernel, dim3(grid_for(rows_cap * (H / 4), t.n_cu)), dim3(256), 0, s, t.dA, H,
+                       t.in_rowptr, t.in_col, t.out_rowptr, t.out_col, hl, nrows, dZn, t.status);
+    float* tmp = dZ;
+    dZ = dZn;
+    dZn = tmp;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_adam(float* theta, const float* grad, float* m, float* v, long long n, float lr, float beta1,
+                       float beta2, float eps, double c1, double c2, const int* status, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(adam_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, theta, grad, m, v, n, lr, beta1, beta2,
+                     eps, (float)c1, (float)c2, status);
+  return hipGetLastError();
+}
+
+}  // namespace dc

@@ -1,0 +1,319 @@
+"""GPU parity of estimator training (Sec. 3.3.3: loss of Eq. (1), Adam) against the fp64 CPU oracle,
+through the C ABI: the training set extracted from labelings (dc_fused_op_batch, exact), loss,
+estimates and the gradient of every parameter tensor (dc_loss_gradients), and the weights after
+several Adam steps (dc_train_step, dc_get_weights).
+
+Tolerances.  The GPU pass is fp32 with fp32 MFMA accumulation; a gradient entry is a sum over all
+rows of the batch, so its error scales with the magnitude of the tensor it belongs to, not with its
+own: |g_gpu - g_oracle| <= 1e-5 * max|g_oracle| per tensor (measured: about 1e-7).  The ReLU
+derivative is a binary decision taken from a floating-point value: for the few units whose fp64
+pre-activation is within 2e-6 (relative to the layer) of zero, which fp32 cannot place, the oracle's
+gradient is taken with the unit on the side that matches (oracle_gradient_like); every other
+decision is the oracle's own.  Loss and estimates: rel 1e-5 like the fp32 forward pass.  Adam divides by sqrt(v):
+an entry whose gradient is far below its tensor's scale may move by up to lr per step in either
+direction, so weights are compared entrywise to lr-fractions: |dtheta| <= 0.02 * lr * steps for
+entries with a well-conditioned gradient and <= lr * steps for all."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from oracle import train as ot
+from paper_2209_12769_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2209_12769_amd import binding
+    binding.lib()
+    return binding
+
+
+def sizes(w):
+    nb = int(w.cand_off[-1])
+    geo = w.g_edge_off()
+    return nb, int(sum(int(geo[b + 1] - geo[b]) for b in w.cand_graph))
+
+
+def sample_workload(name, seed, C, F_H_L, kmax=24):
+    """Labelings of a benchmark-shaped module whose fused groups are the training samples."""
+    base = wl.make(name, 1)
+    H, L = F_H_L
+    model = wl.ModelSpec(base.model.F, H, L, "f32")
+    w = wl.custom("train-" + name, model, base.graphs, [wl.training_labels(base.graphs[0], seed, C, kmax=kmax)],
+                  seed=seed)
+    w.weights.head[-1] += 1.0
+    return w
+
+
+def contracted_workload(seed, F=16, H=32, L=2, n=40, C=6):
+    g = wl.random_dag(seed, n, 0.15, F)
+    model = wl.ModelSpec(F, H, L, "f32")
+    w = wl.custom("train-rand", model, [g], [wl.random_labels(seed, n, 12, C)], seed=seed, std=0.25)
+    w.weights.head[-1] += 2.0
+    return w
+
+
+def trainer_for(B, w):
+    """An evaluator that can hold every fused op of `w` as a graph of its own."""
+    nb, eb = sizes(w)
+    ev = B.Evaluator(w.model.F, w.model.H, w.model.L, "f32", nb // 2 + 1, nb, eb)
+    ev.set_base_graphs(w.g_node_off(), w.g_edge_off(), w.cat_rowptr(), w.cat_col(), w.cat_X())
+    ev.set_weights(w.weights)
+    return ev
+
+
+def gpu_fused_batch(B, w):
+    ev = trainer_for(B, w)
+    t, x = wl.profile_of(w)
+    ev.set_profile(t, x)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    nb, eb = sizes(w)
+    batch = ev.alloc_batch(nb // 2 + 1, nb, nb, eb)
+    ev.fused_op_batch(cg, co, gid, batch)
+    return ev, batch
+
+
+def oracle_fused_batch(w):
+    t, x = wl.profile_of(w)
+    fo, _, member = orc.fused_ops(w, orc.contract(w), x)
+    return fo, member, wl.synthetic_fused_times(fo.node_off, member, t, 5)
+
+
+def tensor_slices(model):
+    o, out = 0, []
+    for shp in ot.Params.shapes(model.F, model.H, model.L):
+        n = int(np.prod(shp))
+        out.append(slice(o, o + n))
+        o += n
+    return out
+
+
+def check_gradient(g_gpu, g_orc, model, tol=1e-5):
+    worst = 0.0
+    for sl in tensor_slices(model):
+        scale = np.abs(g_orc[sl]).max()
+        err = np.abs(g_gpu[sl].astype(np.float64) - g_orc[sl]).max()
+        if scale == 0.0:
+            assert err == 0.0
+            continue
+        worst = max(worst, err / scale)
+        assert err <= tol * scale, (sl, err, scale)
+    return worst
+
+
+def oracle_gradient_like(ob, target, p, model, g_gpu, rel=2e-6):
+    """The oracle's gradient, with each ReLU unit that single precision cannot place (fp64
+    pre-activation within `rel` of zero, relative to its layer) taken from the side that matches the
+    GPU's gradient better; every other unit is the oracle's own decision.  Returns (loss, y, flat
+    gradient, undecided units, units taken from the other side)."""
+    loss, y, g = ot.loss_and_gradients(ob, target, p)
+    g = g.flat()
+    slices = tensor_slices(model)
+
+    def badness(a):
+        return max(np.abs(g_gpu[sl] - a[sl]).max() / max(np.abs(a[sl]).max(), 1e-300) for sl in slices)
+
+    cands = ot.undecided_units(ob, p, rel)
+    flip, cur = [], badness(g)
+    for u in cands:
+        if cur < 1e-6:
+            break
+        _, _, gt = ot.loss_and_gradients(ob, target, p, flip=flip + [u])
+        gt = gt.flat()
+        bt = badness(gt)
+        if bt < 0.7 * cur:
+            flip, g, cur = flip + [u], gt, bt
+    return loss, y, g, cands, flip
+
+
+def test_fused_op_batch_is_exact(B):
+    w = sample_workload("cfg2", 3, 4, (32, 2))
+    ev, batch = gpu_fused_batch(B, w)
+    fo, member, _ = oracle_fused_batch(w)
+    K, nt, et = fo.n_cand, fo.ntot, fo.etot
+    assert batch.c.n_cand == K and K > 50
+    assert ev.last_fused_ops() == (K, nt, et)
+    np.testing.assert_array_equal(batch.node_off[:K + 1].cpu().numpy(), fo.node_off)
+    np.testing.assert_array_equal(batch.edge_off[:K + 1].cpu().numpy(), fo.edge_off)
+    np.testing.assert_array_equal(batch.new_id[:nt].cpu().numpy(), member)
+    np.testing.assert_array_equal(batch.out_rowptr[:nt + 1].cpu().numpy(), fo.out_rowptr)
+    np.testing.assert_array_equal(batch.in_rowptr[:nt + 1].cpu().numpy(), fo.in_rowptr)
+    np.testing.assert_array_equal(batch.out_col[:et].cpu().numpy(), fo.out_col)
+    np.testing.assert_array_equal(batch.in_col[:et].cpu().numpy(), fo.in_col)
+    np.testing.assert_array_equal(batch.Xc[:nt].cpu().numpy(), fo.Xc)
+    ev.close()
+
+
+@pytest.mark.parametrize("case", ["contracted", "cfg2-H64", "cfg3-H256", "cfg2-H96"])
+def test_loss_estimates_and_gradient(B, case):
+    import torch
+    if case == "contracted":
+        # arbitrary contracted graphs with long neighbour lists in both directions
+        w = contracted_workload(11)
+        ev = B.evaluator_for(w)
+        cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+        nb, eb = sizes(w)
+        batch = ev.contract_graphs(cg, co, gid, ev.alloc_batch(w.n_cand, nb, nb, eb))
+        ob = orc.contract(w)
+        target = np.random.default_rng(1).uniform(0.5, 4.0, ob.n_cand).astype(np.float32)
+    else:
+        name, hh = case.split("-H")
+        # H = 256, four layers: several 128-wide tiles and slabs with ragged ends; H = 96: partial tiles
+        w = sample_workload(name, 7, 3 if hh == "256" else 2, (int(hh), 4 if hh == "256" else 3))
+        ev, batch = gpu_fused_batch(B, w)
+        ob, _, target = oracle_fused_batch(w)
+    model = w.model
+    p = ot.Params.from_weights(w.weights, model.F, model.H, model.L)
+    loss_o, y_o, g_o = ot.loss_and_gradients(ob, target, p)
+    assert (y_o > 1e-6).mean() > 0.5                   # most samples carry a gradient
+    ev.train_begin(1e-3, max(batch.c.n_cand, 1), max(ob.ntot, 1))
+    tg = torch.from_numpy(target).to(ev.device)
+    loss, pred, grad = ev.loss_gradients(batch, tg)
+    assert ev.check() == 0
+    scale = np.abs(y_o).max()
+    np.testing.assert_allclose(pred.cpu().numpy(), y_o, rtol=1e-5, atol=1e-5 * scale)
+    assert float(loss.cpu()[0]) == pytest.approx(loss_o, rel=2e-5)
+    g_gpu = grad.cpu().numpy().astype(np.float64)
+    assert g_gpu.size == ev.num_params() == g_o.flat().size
+    _, _, g_ref, undecided, flipped = oracle_gradient_like(ob, target, p, model, g_gpu)
+    worst = check_gradient(g_gpu, g_ref, model)
+    print(f"{case}: samples {ob.n_cand}, rows {ob.ntot}, worst gradient error / tensor scale {worst:.2e}; "
+          f"{len(undecided)} ReLU units within 2e-6 of zero, {len(flipped)} taken from the other side")
+    # the pass is bit-reproducible
+    _, _, grad2 = ev.loss_gradients(batch, tg)
+    assert torch.equal(grad, grad2)
+    ev.close()
+
+
+def test_adam_steps_and_trained_forward(B):
+    import torch
+    w = sample_workload("cfg2", 5, 2, (64, 3))
+    ev, batch = gpu_fused_batch(B, w)
+    ob, _, target = oracle_fused_batch(w)
+    model = w.model
+    lr, steps = 1e-3, 4
+    p0 = ot.Params.from_weights(w.weights, model.F, model.H, model.L)
+    targets = [target * (1.0 + 0.1 * k) for k in range(steps)]        # a different regression problem each step
+    p_o, losses_o = ot.train([ob] * steps, targets, p0, model.F, model.H, model.L, lr=lr)
+    ev.train_begin(lr, batch.c.n_cand, ob.ntot)
+    losses = []
+    for k in range(steps):
+        losses.append(ev.train_step(batch, torch.from_numpy(targets[k].astype(np.float32)).to(ev.device)))
+    assert ev.check() == 0
+    np.testing.assert_allclose([float(x.cpu()[0]) for x in losses], losses_o, rtol=1e-4)
+    Wg, bg, hg = ev.get_weights()
+    th_g = np.concatenate([Wg, bg, hg]).astype(np.float64)
+    th_o, th_0 = p_o.flat(), p0.flat()
+    assert np.abs(th_o - th_0).max() > 0.5 * lr * steps               # the optimiser moved the weights
+    d = np.abs(th_g - th_o)
+    assert d.max() <= lr * steps * 1.01
+    # entries whose gradient is not tiny next to its tensor: tight agreement
+    _, _, g0 = ot.loss_and_gradients(ob, targets[0], p0)
+    g0 = g0.flat()
+    well = np.zeros(g0.size, bool)
+    for sl in tensor_slices(model):
+        well[sl] = np.abs(g0[sl]) > 1e-2 * np.abs(g0[sl]).max()
+    assert well.sum() > 100
+    assert d[well].max() <= 0.02 * lr * steps, d[well].max()
+    # the forward entry point now runs the trained estimator
+    pred = ev.gnn_forward(batch).cpu().numpy()
+    y_o, _ = ot.forward(ob, p_o)
+    np.testing.assert_allclose(pred, y_o, rtol=2e-3, atol=2e-3 * np.abs(y_o).max())
+    y_0, _ = ot.forward(ob, p0)
+    assert np.abs(pred - y_0).max() > 10 * np.abs(pred - y_o).max()   # and not the initial one
+    ev.close()
+
+
+def test_whole_batch_gradient_is_the_weighted_sum_of_its_parts(B):
+    """Holds at any size: the loss is a mean over samples, so the gradient of a batch is the
+    sample-weighted mean of the gradients of the labelings it is made of."""
+    import torch
+    w = sample_workload("cfg3", 2, 6, (128, 3))
+    ev = trainer_for(B, w)
+    t, x = wl.profile_of(w)
+    ev.set_profile(t, x)
+    nb, eb = sizes(w)
+    ev.train_begin(1e-3, nb // 2 + 1, nb)
+    n = w.graphs[0].n
+
+    def run(sub, given):
+        cg, co, gid = ev.to_device(sub.cand_graph), ev.to_device(sub.cand_off), ev.to_device(sub.group_id)
+        batch = ev.fused_op_batch(cg, co, gid, ev.alloc_batch(nb // 2 + 1, nb, nb, eb))
+        K = batch.c.n_cand
+        if given is None:
+            tg = wl.synthetic_fused_times(batch.node_off[:K + 1].cpu().numpy(), batch.new_id.cpu().numpy(), t, 0)
+        else:
+            tg = given[0][given[1]:given[1] + K]
+        _, _, grad = ev.loss_gradients(batch, torch.from_numpy(tg).to(ev.device))
+        return K, grad.cpu().numpy().astype(np.float64), tg
+
+    K_all, g_all, tg_all = run(w, None)
+    acc = np.zeros_like(g_all)
+    off = 0
+    for c in range(w.n_cand):
+        K, g, _ = run(w.subset([c]), (tg_all, off))
+        acc += K * g
+        off += K
+    assert off == K_all
+    assert ev.check() == 0
+    acc /= K_all
+    for sl in tensor_slices(w.model):
+        scale = np.abs(g_all[sl]).max()
+        assert np.abs(acc[sl] - g_all[sl]).max() <= 1e-4 * scale
+    ev.close()
+
+
+def test_edge_cases_and_errors(B):
+    import torch
+    w = sample_workload("cfg2", 1, 1, (32, 2))
+    ev, batch = gpu_fused_batch(B, w)
+    ob, _, target = oracle_fused_batch(w)
+    K = batch.c.n_cand
+    tg = torch.from_numpy(target).to(ev.device)
+    # before dc_train_begin
+    loss = torch.zeros(1, device=ev.device)
+    assert B.dc_train_step(ev.ctx, batch.c, tg.data_ptr(), loss.data_ptr(), 0) == 1
+    ev.train_begin(1e-2, K, ob.ntot)
+    W0, b0, h0 = ev.get_weights()
+    # an empty batch: loss 0, nothing moves
+    empty = ev.alloc_batch(1, 1, 1, 1)
+    empty.c.n_cand = 0
+    l0 = ev.train_step(empty, tg)
+    assert float(l0.cpu()[0]) == 0.0
+    W1, b1, h1 = ev.get_weights()
+    assert np.array_equal(W0, W1) and np.array_equal(b0, b1) and np.array_equal(h0, h1)
+    # every estimate below the floor: the loss is the floor's, the gradient is exactly zero, Adam stays put
+    hd = w.weights.head.copy()
+    hd[-1] = -1e4
+    ev.set_weights(wl.Weights(w.weights.layers, w.weights.biases, hd))
+    lossf, pred, grad = ev.loss_gradients(batch, tg)
+    assert (pred.cpu().numpy() < 0).all()
+    assert float(lossf.cpu()[0]) == pytest.approx(np.mean((np.log(1e-6) - np.log(target.astype(np.float64))) ** 2),
+                                                  rel=1e-6)
+    assert not grad.cpu().numpy().any()
+    ev.train_step(batch, tg)
+    W2, b2, h2 = ev.get_weights()
+    assert np.array_equal(W2, w.weights.layers) and np.array_equal(h2, hd)
+    # more samples than max_samples: refused on the host
+    ev.train_begin(1e-2, K - 1, ob.ntot)
+    assert B.dc_train_step(ev.ctx, batch.c, tg.data_ptr(), loss.data_ptr(), 0) == 4
+    # more rows than max_rows: found on the device, nothing is written
+    ev.set_weights(w.weights)
+    ev.train_begin(1e-2, K, ob.ntot - 1)
+    ev.train_step(batch, tg)
+    assert ev.check() == 4
+    W3, _, _ = ev.get_weights()
+    assert np.array_equal(W3, w.weights.layers)
+    ev.close()
+    # training is fp32 with the mean aggregator only
+    wb = wl.make("cfg1", 2)
+    m = wl.ModelSpec(wb.model.F, wb.model.H, wb.model.L, "bf16")
+    evb = B.evaluator_for(wl.Workload(wb.name, m, wb.graphs, wb.cand_graph, wb.cand_off, wb.group_id, wb.weights))
+    p = B.DcTrainParams(1e-3, 0.9, 0.999, 1e-8, 1e-6, 4, 64)
+    assert B.dc_train_begin(evb.ctx, p, 0) == 7
+    evb.close()

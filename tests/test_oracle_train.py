@@ -141,6 +141,28 @@ def test_sample_below_floor_has_loss_but_no_gradient():
     assert not g.flat().any()
 
 
+def test_flipped_unit_is_the_derivative_from_the_other_side():
+    # put one pre-activation a hair above zero, then a hair below: the gradient just below equals
+    # the gradient just above with that unit's ReLU derivative flipped, and the two differ clearly
+    b, p, target, model = tiny_case(4)
+    l, row, col = 1, 3, 2
+    _, c = ot.forward(b, p)
+    Z = np.concatenate([c["hs"][l], c["mps"][l], c["mss"][l]], axis=1) @ p.W[l] + p.b[l]
+    # moving the bias moves the whole column; the probed unit is the only one that crosses zero
+    others = np.delete(Z[:, col], row)
+    assert np.abs(others - Z[row, col]).min() > 1e-6
+    base = p.b[l][col] - Z[row, col]
+    p.b[l][col] = base + 1e-11
+    assert ot.undecided_units(b, p, 1e-9) == [(l, row, col)]
+    _, _, g_above = ot.loss_and_gradients(b, target, p)
+    _, _, g_above_flipped = ot.loss_and_gradients(b, target, p, flip=[(l, row, col)])
+    p.b[l][col] = base - 1e-11
+    _, _, g_below = ot.loss_and_gradients(b, target, p)
+    scale = np.abs(g_below.flat()).max()
+    assert np.abs(g_above_flipped.flat() - g_below.flat()).max() < 1e-8 * scale
+    assert np.abs(g_above.flat() - g_below.flat()).max() > 1e-4 * scale
+
+
 def test_adam_constant_gradient_closed_form():
     # with the same gradient at every step the bias-corrected moments are g and g^2: each step
     # moves by lr * g / (|g| + eps), whatever the betas
