@@ -251,6 +251,103 @@ def search_bench(args, w, B, torch):
     print(json.dumps(out), flush=True)
 
 
+def train_bench(args, w, B, torch):
+    """Times dc_train_step (Sec. 3.3.3): forward with kept activations, loss of Eq. (1), reverse pass and one
+    Adam update over one resident batch of fused-op samples.  The samples are drawn the way Sec. 5.1 describes
+    (workloads.training_labels) on the workload's base graph; the profiled times they are fitted to are
+    synthetic (workloads.synthetic_fused_times).  fp32."""
+    from paper_2209_12769_amd import workloads as wl
+    g = w.graphs[0]
+    C = args.n_cand or 128
+    model = wl.ModelSpec(w.model.F, w.model.H, w.model.L, "f32")
+    ws = wl.custom(w.name + "-train", model, [g], [wl.training_labels(g, 1, C)], seed=0)
+    ws.weights.head[-1] += 1.0
+    nb = int(ws.cand_off[-1])
+    eb = g.e * C
+    ev = B.Evaluator(model.F, model.H, model.L, "f32", nb // 2 + 1, nb, eb)
+    ev.set_base_graphs(ws.g_node_off(), ws.g_edge_off(), ws.cat_rowptr(), ws.cat_col(), ws.cat_X())
+    ev.set_weights(ws.weights)
+    t_base, x_base = wl.profile_of(ws)
+    ev.set_profile(t_base, x_base)
+    cg, co, gid = ev.to_device(ws.cand_graph), ev.to_device(ws.cand_off), ev.to_device(ws.group_id)
+    batch = ev.fused_op_batch(cg, co, gid, ev.alloc_batch(nb // 2 + 1, nb, nb, eb))
+    K, M, E = ev.last_fused_ops()
+    target_h = wl.synthetic_fused_times(batch.node_off[:K + 1].cpu().numpy(), batch.new_id[:M].cpu().numpy(), t_base)
+    target = torch.from_numpy(target_h).to(ev.device)
+    ev.train_begin(1e-4, K, M)
+    loss = torch.empty(1, dtype=torch.float32, device=ev.device)
+    first = None
+    for _ in range(args.warmup):
+        ev.train_step(batch, target, loss)
+        if first is None:
+            first = float(loss.cpu()[0])
+    torch.cuda.synchronize()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    ev.profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev.train_step(batch, target, loss)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fam = ev.profile_end()
+    assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
+    F, H, L = model.F, model.H, model.L
+    dims = [F] + [H] * (L - 1)
+    gemm = sum(2 * M * 3 * d * H for d in dims)                     # one product with every layer's [3d, H] matrix
+    work = {"train_update": {"flops": gemm, "bytes": sum(M * (3 * d + H) * 4 for d in dims)},
+            "train_wgrad": {"flops": gemm, "bytes": sum(M * (3 * d + H) * 4 for d in dims)},
+            "train_dgrad": {"flops": 2 * M * 3 * H * H * (L - 1), "bytes": (L - 1) * M * 4 * H * 4},
+            "train_aggregate": {"bytes": sum(2 * (M + 2 * E) * d * 4 for d in dims) + sum(2 * M * d * 4 for d in dims)},
+            "train_gather_back": {"bytes": (L - 1) * ((M + 2 * E) * H * 4 + 2 * M * H * 4)}}
+    kernels = {}
+    for name, (ms_total, launches) in fam.items():
+        if launches == 0:
+            continue
+        per = ms_total / args.steps
+        k = {"ms_per_step": round(per, 4), "launches_per_step": launches / args.steps}
+        if per > 0 and name in work and work[name].get("bytes"):
+            k["GB/s"] = round(work[name]["bytes"] / (per * 1e-3) / 1e9, 1)
+        if per > 0 and name in work and work[name].get("flops"):
+            k["TFLOP/s"] = round(work[name]["flops"] / (per * 1e-3) / 1e12, 2)
+        kernels[name] = k
+    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    if "TFLOP/s" in kernels[dom]:
+        ach = kernels[dom]["TFLOP/s"]
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS["f32"], "unit": "TFLOP/s",
+                "frac": round(ach / PEAK_MFMA_TFLOPS["f32"], 4), "traffic": read_traffic(w.name + "_train", dom)}
+    else:
+        ach = kernels[dom].get("GB/s", 0.0)
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": read_traffic(w.name + "_train", dom)}
+    roof["avg_launch_ms"] = round(kernels[dom]["ms_per_step"] / max(kernels[dom]["launches_per_step"], 1), 4)
+    out = {"metric": "fused-op samples trained/sec (forward + loss + reverse pass + Adam) on 1 MI355X",
+           "value": round(K * args.steps / dt, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": ws.name, "labelings": C, "samples": K, "rows": M, "edges": E, "F": F, "H": H, "L": L,
+                      "params": ev.num_params(), "loss_first": first, "loss_last": float(loss.cpu()[0])},
+           "roofline": roof, "kernels": kernels}
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        from oracle import train as ot
+        from threadpoolctl import threadpool_info
+        n = min(C, 128)               # about 15 s of numpy
+        sub = wl.custom("s", model, [g], [ws.group_id.reshape(C, g.n)[:n]], weights=ws.weights)
+        fo, _, member = orc.fused_ops(sub, orc.contract(sub), x_base)
+        tg = wl.synthetic_fused_times(fo.node_off, member, t_base)
+        p0 = ot.Params.from_weights(ws.weights, F, H, L)
+        t0 = time.perf_counter()
+        ot.train([fo], [tg], p0, F, H, L, lr=1e-4)
+        cdt = time.perf_counter() - t0
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        out["cpu_baseline"] = {"value": fo.n_cand / cdt, "unit": "samples/s", "cores": threads, "kind": "oracle",
+                               "sample": f"one training step on the {fo.n_cand} samples ({fo.ntot} rows) of the first "
+                                         f"{n} of {C} labelings, {cdt:.1f} s"}
+    ev.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -271,6 +368,9 @@ def main():
     ap.add_argument("--search", action="store_true",
                     help="time the backtracking search (dc_search) on the workload's base graph; "
                          "--n-cand children per step, --steps search steps")
+    ap.add_argument("--train", action="store_true",
+                    help="time dc_train_step (estimator training, fp32) on samples drawn on the workload's base "
+                         "graph; --n-cand = number of labelings the samples are drawn from")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
                          "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -294,7 +394,10 @@ def main():
     from paper_2209_12769_amd import binding as B
     from paper_2209_12769_amd import workloads as wl
 
-    w = wl.make(args.workload, 1 if args.search else args.n_cand)
+    w = wl.make(args.workload, 1 if (args.search or args.train) else args.n_cand)
+    if args.train:
+        train_bench(args, w, B, torch)
+        return
     if args.simulate:
         simulate_bench(args, w, B, torch)
         return

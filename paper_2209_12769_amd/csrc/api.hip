@@ -92,7 +92,9 @@ namespace {
 const char* const kFamilyNames[kFamCount] = {"prep_scan", "contract", "finalize", "aggregate", "update",
                                              "fused_layer", "layer256", "layer256_d64", "aggregate_heavy", "build_desc",
                                              "attention_project", "attention_scores", "attention_aggregate",
-                                             "readout_head", "simulate", "fused_op_extract", "fused_op_head"};
+                                             "readout_head", "simulate", "fused_op_extract", "fused_op_head",
+                                             "train_aggregate", "train_update", "train_head", "train_wgrad",
+                                             "train_dgrad", "train_gather_back", "train_adam"};
 
 size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -993,7 +995,7 @@ dc_status train_pass(dc_ctx* ctx, const dc_batch* in, const float* target, float
   t.grad = grad;
   t.loss = loss;
   t.pred = pred;
-  hipError_t e = launch_train_pass(t, s);
+  hipError_t e = launch_train_pass(t, ctx->prof.on ? &ctx->prof : nullptr, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "training pass launch");
   return DC_OK;
 }
@@ -1178,6 +1180,7 @@ dc_status dc_train_step(dc_ctx* ctx, const dc_batch* in, const float* target, fl
   const double c2 = 1.0 / (1.0 - pow((double)p.beta2, (double)tstep));
   const long long nW = (long long)n_layer_weights(c), nb = (long long)c.L * c.H, nh = (long long)n_head_params(c);
   const float* g = ctx->tb.grad;
+  if (ctx->prof.on) ctx->prof.begin(kFamTrainAdam, s);
   hipError_t e = launch_adam(static_cast<float*>(ctx->W), g, ctx->adam_m, ctx->adam_v, nW, p.lr, p.beta1, p.beta2,
                              p.eps, c1, c2, ctx->status, s);
   if (e == hipSuccess)
@@ -1186,6 +1189,7 @@ dc_status dc_train_step(dc_ctx* ctx, const dc_batch* in, const float* target, fl
   if (e == hipSuccess)
     e = launch_adam(ctx->head, g + nW + nb, ctx->adam_m + nW + nb, ctx->adam_v + nW + nb, nh, p.lr, p.beta1, p.beta2,
                     p.eps, c1, c2, ctx->status, s);
+  if (ctx->prof.on) ctx->prof.end(s);
   // the copy of W1 | W2 that the fused-op path multiplies with (same layout in fp32)
   const size_t HH = (size_t)c.H * c.H;
   if (e == hipSuccess) e = hipMemcpyAsync(ctx->headW, ctx->head, HH * sizeof(float), hipMemcpyDeviceToDevice, s);

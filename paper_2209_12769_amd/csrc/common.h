@@ -55,7 +55,7 @@ struct BatchView {
 };
 
 // Optional per-kernel timing with HIP events on the launch stream.
-enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamSimulate, kFamFusedOps, kFamFusedHead, kFamCount };
+enum Family { kFamPrep = 0, kFamContract, kFamFinalize, kFamAggregate, kFamUpdate, kFamFused, kFamLayer256, kFamLayer64, kFamHeavy, kFamDesc, kFamAttProject, kFamAttScores, kFamAttAggregate, kFamReadout, kFamSimulate, kFamFusedOps, kFamFusedHead, kFamTrainAggregate, kFamTrainUpdate, kFamTrainHead, kFamTrainWgrad, kFamTrainDgrad, kFamTrainGatherBack, kFamTrainAdam, kFamCount };
 struct Profiler {
   bool on = false;
   static constexpr int kCap = 4096;
@@ -261,7 +261,7 @@ struct TrainPass {
   int* status;
   int n_cu;
 };
-hipError_t launch_train_pass(const TrainPass& t, hipStream_t s);
+hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s);
 int train_slabs(int n_cu, int F, int H);
 hipError_t launch_adam(float* theta, const float* grad, float* m, float* v, long long n, float lr, float beta1,
                        float beta2, float eps, double c1, double c2, const int* status, hipStream_t s);

@@ -404,7 +404,9 @@ int train_slabs(int n_cu, int F, int H) {
   return S < 1 ? 1 : S;
 }
 
-hipError_t launch_train_pass(const TrainPass& t, hipStream_t s) {
+hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s) {
+  auto begin = [&](int fam) { if (prof) prof->begin(fam, s); };
+  auto end = [&]() { if (prof) prof->end(s); };
   const int B = t.n_samples, H = t.H, F = t.F, L = t.L;
   const size_t HH = (size_t)H * H;
   const int* nrows = t.node_off + B;          // device-resident row count
@@ -450,13 +452,18 @@ hipError_t launch_train_pass(const TrainPass& t, hipStream_t s) {
   const float* bl = t.b;
   for (int l = 0; l < L; ++l) {
     float* hn = t.hs + (size_t)l * rows_cap * H;
+    begin(kFamTrainAggregate);
     launch_mean_aggregate(g, hcur, d, t.mp, t.ms, s);
+    end();
+    begin(kFamTrainUpdate);
     launch_dense_update(g, hcur, t.mp, t.ms, d, 3, Wl, bl, hn, s);
+    end();
     Wl += (size_t)3 * d * H;
     bl += H;
     hcur = hn;
     d = H;
   }
+  begin(kFamTrainHead);
   hipLaunchKernelGGL(readout_kernel, dim3(grid_for((long long)B * (H / 4), t.n_cu)), dim3(256), 0, s, hcur, H,
                      t.node_off, B, t.R, t.status);
   launch_dense_update(gh, t.R, nullptr, nullptr, H, 1, W1, b1, t.Z1, s);
@@ -464,7 +471,10 @@ hipError_t launch_train_pass(const TrainPass& t, hipStream_t s) {
   hipLaunchKernelGGL(loss_kernel, dim3(grid_for((long long)B * 64, t.n_cu)), dim3(256), 0, s, t.Z2, H, w3, t.target, B,
                      t.floor, t.y, t.dy, t.lterm, t.pred, t.status);
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, t.lterm, B, t.loss, t.status);
-  if (!t.grad) return hipGetLastError();
+  if (!t.grad) {
+    end();
+    return hipGetLastError();
+  }
 
   // ---- regression network, reverse ----
   const int* nB = t.cnt + 1;
@@ -485,6 +495,7 @@ hipError_t launch_train_pass(const TrainPass& t, hipStream_t s) {
   float* dZn = t.dZ[1];
   hipLaunchKernelGGL(top_kernel, dim3(grid_for(rows_cap * (H / 4), t.n_cu)), dim3(256), 0, s, t.dR, t.gid, hcur, nrows,
                      H, dZ, t.status);
+  end();
   GnnArgs g3 = g;
   g3.H = 3 * H;                                // dA = dZ W^T is [rows, 3H] for the layers above the first
   for (int l = L - 1; l >= 0; --l) {
@@ -492,13 +503,21 @@ hipError_t launch_train_pass(const TrainPass& t, hipStream_t s) {
     const float* hl = l == 0 ? t.X : t.hs + (size_t)(l - 1) * rows_cap * H;
     size_t woff = 0;
     for (int k = 0; k < l; ++k) woff += (size_t)3 * (k == 0 ? F : H) * H;
+    begin(kFamTrainAggregate);
     launch_mean_aggregate(g, hl, dl, t.mp, t.ms, s);
+    end();
+    begin(kFamTrainWgrad);
     weight_gradient(t, hl, t.mp, t.ms, dl, 3, dZ, H, H, nrows, gWl + woff, gbl + (size_t)l * H, s);
+    end();
     if (l == 0) break;
+    begin(kFamTrainDgrad);
     hipLaunchKernelGGL(transpose_kernel, dim3(128), dim3(256), 0, s, t.W + woff, 3 * H, H, t.WT, t.status);
     launch_dense_update(g3, dZ, nullptr, nullptr, H, 1, t.WT, nullptr, t.dA, s);
+    end();
+    begin(kFamTrainGatherBack);
     hipLaunchKernelGGL(gather_back_kernel, dim3(grid_for(rows_cap * (H / 4), t.n_cu)), dim3(256), 0, s, t.dA, H,
                        t.in_rowptr, t.in_col, t.out_rowptr, t.out_col, hl, nrows, dZn, t.status);
+    end();
     float* tmp = dZ;
     dZ = dZn;
     dZn = tmp;
