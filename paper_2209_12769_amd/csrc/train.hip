@@ -207,7 +207,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const float* __restrict__ A0
   const int M = nseg * d;
   const int tiles_n = (N + kWT - 1) / kWT, tiles_m = (M + kWT - 1) / kWT;
   const int ntile = tiles_m * tiles_n;
-  const int tile = blockIdx.x % ntile, slab = blockIdx.x / ntile;
+  // Workgroups go round-robin to the 8 XCDs, each with an L2 of its own: workgroup b becomes work
+  // item (b % 8) * (grid / 8) + b / 8, so that the tiles of one slab, which read the same rows, run
+  // on one XCD (the grid is ntile * S with S a multiple of 8).
+  const int per_xcd = gridDim.x >> 3;
+  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int tile = item % ntile, slab = item / ntile;
   if (slab >= S) return;
   const int m0 = (tile / tiles_n) * kWT, n0 = (tile % tiles_n) * kWT;
   const int rows = nrows[0];
@@ -400,8 +405,9 @@ int train_slabs(int n_cu, int F, int H) {
   (void)F;
   const int ntile = ((H + kWT - 1) / kWT) * ((H + kWT - 1) / kWT);
   int S = (2 * n_cu + ntile - 1) / ntile;
+  S = (S + 7) & ~7;                       // the tile-to-XCD mapping of wgrad_kernel needs a multiple of 8
   if (S > 128) S = 128;
-  return S < 1 ? 1 : S;
+  return S;
 }
 
 hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s) {

@@ -317,3 +317,69 @@ def test_edge_cases_and_errors(B):
     p = B.DcTrainParams(1e-3, 0.9, 0.999, 1e-8, 1e-6, 4, 64)
     assert B.dc_train_begin(evb.ctx, p, 0) == 7
     evb.close()
+
+
+def test_bench_size_batch(B):
+    """The batch bench.py --train times (cfg4's base graph, 128 labelings, ~53 k samples, ~474 k rows, H = 256,
+    L = 4), in the same launch configuration.  Estimates and loss terms of sampled labelings against the
+    oracle run on those labelings alone (a sample's estimate does not depend on the rest of the batch); the
+    gradient through the property that holds at any size, full = sample-weighted mean of the parts, with the
+    sampled parts themselves checked against the oracle."""
+    import torch
+    base = wl.make("cfg4", 1)
+    g = base.graphs[0]
+    C = 128
+    model = wl.ModelSpec(base.model.F, base.model.H, base.model.L, "f32")
+    w = wl.custom("cfg4-train", model, [g], [wl.training_labels(g, 1, C)], seed=0)
+    w.weights.head[-1] += 1.0
+    ev = trainer_for(B, w)
+    t, x = wl.profile_of(w)
+    ev.set_profile(t, x)
+    nb, eb = sizes(w)
+    cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+    batch = ev.fused_op_batch(cg, co, gid, ev.alloc_batch(nb // 2 + 1, nb, nb, eb))
+    K, M, E = ev.last_fused_ops()
+    assert K > 50000 and M > 450000
+    node_off = batch.node_off[:K + 1].cpu().numpy()
+    target = wl.synthetic_fused_times(node_off, batch.new_id[:M].cpu().numpy(), t)
+    ev.train_begin(1e-4, K, M)
+    tg = torch.from_numpy(target).to(ev.device)
+    loss, pred, grad = ev.loss_gradients(batch, tg)
+    assert ev.check() == 0
+    pred, g_full = pred.cpu().numpy(), grad.cpu().numpy().astype(np.float64)
+    # samples per labeling, in batch order (candidate by candidate): its groups of two or more ops
+    labs = w.group_id.reshape(C, g.n)
+    counts = np.array([(np.unique(labs[c], return_counts=True)[1] >= 2).sum() for c in range(C)])
+    offs = np.concatenate([[0], np.cumsum(counts)])
+    assert offs[-1] == K
+    p = ot.Params.from_weights(w.weights, model.F, model.H, model.L)
+    part_batch = ev.alloc_batch(nb // 2 + 1, nb, nb, eb)
+    acc = np.zeros_like(g_full)
+    lsum = 0.0
+    for c in range(C):
+        sub = w.subset([c])
+        pb = ev.fused_op_batch(ev.to_device(sub.cand_graph), ev.to_device(sub.cand_off), ev.to_device(sub.group_id),
+                               part_batch)
+        Kc = pb.c.n_cand
+        assert Kc == counts[c]
+        tc = torch.from_numpy(target[offs[c]:offs[c + 1]]).to(ev.device)
+        lc, pc, gc = ev.loss_gradients(pb, tc)
+        gc = gc.cpu().numpy().astype(np.float64)
+        acc += Kc * gc
+        lsum += Kc * float(lc.cpu()[0])
+        # the same sample gives the same estimate whatever batch it sits in
+        np.testing.assert_allclose(pc.cpu().numpy(), pred[offs[c]:offs[c + 1]], rtol=1e-6, atol=1e-6)
+        if c in (0, 77):
+            fo, member, _ = (lambda s: (orc.fused_ops(s, orc.contract(s), x)))(sub)
+            assert fo.n_cand == Kc
+            lo, yo, _ = ot.loss_and_gradients(fo, target[offs[c]:offs[c + 1]], p)
+            np.testing.assert_allclose(pred[offs[c]:offs[c + 1]], yo, rtol=1e-5, atol=1e-5 * np.abs(yo).max())
+            assert float(lc.cpu()[0]) == pytest.approx(lo, rel=2e-5)
+            _, _, g_ref, _, _ = oracle_gradient_like(fo, target[offs[c]:offs[c + 1]], p, model, gc)
+            check_gradient(gc, g_ref, model)
+    assert ev.check() == 0
+    assert float(loss.cpu()[0]) == pytest.approx(lsum / K, rel=1e-5)
+    acc /= K
+    for sl in tensor_slices(model):
+        assert np.abs(acc[sl] - g_full[sl]).max() <= 1e-5 * np.abs(g_full[sl]).max()
+    ev.close()
