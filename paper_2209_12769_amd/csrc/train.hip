@@ -193,19 +193,25 @@ __global__ __launch_bounds__(256) void gather_back_kernel(const float* __restric
 }
 
 // ---- weight gradients: C [M, N] = sum over rows r of A[r][:]^T B[r][:], M = nseg * d ----
-// One workgroup = one 128 x 128 tile of C over one slab of rows; 4 waves of 64 x 64.  The
-// contraction index is the batch row, so both MFMA operands are read straight from global memory
-// with 32 consecutive lanes on 32 consecutive columns of one row (lanes 32..63: the next row).
-// The column sums of B (bias gradients) ride along in the waves of the first row of tiles.
-constexpr int kWT = 128;
-__global__ __launch_bounds__(256) void wgrad_kernel(const float* __restrict__ A0, const float* __restrict__ A1,
+// One workgroup = one 256 x 128 tile of C over one slab of rows; 8 waves of 64 x 64 (4 accumulator
+// blocks of 32 x 32 each; four waves per SIMD at two workgroups per CU).  The contraction index is the batch row: chunks of 16 rows of both
+// operands are staged in LDS exactly as they lie in memory (row-major, 16-byte loads, each line read
+// once per workgroup), double-buffered, with the next chunk's global loads in flight while the
+// current one multiplies.  An MFMA block is free to take any 32 columns: block i of a wave takes
+// columns 2*l + i of its 64 (l = lane mod 32), so one 8-byte LDS read feeds a lane's two A operands
+// and another its two B operands.  The column sums of B (bias gradients) ride
+// along in the waves of the first row of tiles.
+constexpr int kTM = 256, kTN = 128, kRC = 16;
+__global__ __launch_bounds__(512) void wgrad_kernel(const float* __restrict__ A0, const float* __restrict__ A1,
                                                     const float* __restrict__ A2, int d, int nseg,
                                                     const float* __restrict__ Bm, int ldb, int N,
                                                     const int* __restrict__ nrows, float* __restrict__ part,
                                                     long long part_stride, int S, const int* __restrict__ status) {
   if (status[0] != 0) return;
+  __shared__ __attribute__((aligned(16))) float As[2][kRC][kTM];
+  __shared__ __attribute__((aligned(16))) float Bs[2][kRC][kTN];
   const int M = nseg * d;
-  const int tiles_n = (N + kWT - 1) / kWT, tiles_m = (M + kWT - 1) / kWT;
+  const int tiles_n = (N + kTN - 1) / kTN, tiles_m = (M + kTM - 1) / kTM;
   const int ntile = tiles_m * tiles_n;
   // Workgroups go round-robin to the 8 XCDs, each with an L2 of its own: workgroup b becomes work
   // item (b % 8) * (grid / 8) + b / 8, so that the tiles of one slab, which read the same rows, run
@@ -214,28 +220,54 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const float* __restrict__ A0
   const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   const int tile = item % ntile, slab = item / ntile;
   if (slab >= S) return;
-  const int m0 = (tile / tiles_n) * kWT, n0 = (tile % tiles_n) * kWT;
+  const int m0 = (tile / tiles_n) * kTM, n0 = (tile % tiles_n) * kTN;
   const int rows = nrows[0];
-  const int per = (((rows + S - 1) / S) + 1) & ~1;
+  const int per = (rows + S - 1) / S;
   const long long r0 = (long long)slab * per;
   const long long r1 = r0 + per < rows ? r0 + per : rows;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lh = lane >> 5;
 
-  const float* ap[2];
-  const float* bp[2];
-  bool av[2], bv[2];
+  // loader roles: A rows arow + 8u (u < 2), 4 columns from am; B row brow, 4 columns from bn
+  const int ac4 = t & 63, arow = t >> 6;                 // arow 0..7
+  const int am = m0 + ac4 * 4;
+  const bool aok = am < M;                               // M is a multiple of 4: all four columns or none
+  const int aseg = aok ? am / d : 0;
+  const float* pa = (aseg == 0 ? A0 : (aseg == 1 ? A1 : A2)) + (aok ? am - aseg * d : 0);
+  const int bc4 = t & 31, brow = t >> 5;                 // brow 0..15
+  const int bn = n0 + bc4 * 4;
+  const bool bvec = (N & 3) == 0 && (ldb & 3) == 0;      // 16-byte loads of B are possible
+  float4 ra[2], rb[1];
+  auto fetch = [&](long long rbase) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = m0 + wm * 64 + i * 32 + l32;
-    av[i] = m < M;
-    const int mm = av[i] ? m : 0;
-    const int seg = mm / d;
-    ap[i] = (seg == 0 ? A0 : (seg == 1 ? A1 : A2)) + (mm - seg * d);
-    const int n = n0 + wn * 64 + i * 32 + l32;
-    bv[i] = n < N;
-    bp[i] = Bm + (bv[i] ? n : 0);
-  }
+    for (int u = 0; u < 2; ++u) {
+      const long long r = rbase + arow + 8 * u;
+      ra[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (aok && r < r1) ra[u] = *reinterpret_cast<const float4*>(pa + (size_t)r * d);
+    }
+#pragma unroll
+    for (int u = 0; u < 1; ++u) {
+      const long long r = rbase + brow;
+      rb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < r1) {
+        const float* q = Bm + (size_t)r * ldb;
+        if (bvec) {
+          if (bn < N) rb[u] = *reinterpret_cast<const float4*>(q + bn);
+        } else {
+          if (bn < N) rb[u].x = q[bn];
+          if (bn + 1 < N) rb[u].y = q[bn + 1];
+          if (bn + 2 < N) rb[u].z = q[bn + 2];
+          if (bn + 3 < N) rb[u].w = q[bn + 3];
+        }
+      }
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) *reinterpret_cast<float4*>(&As[buf][arow + 8 * u][ac4 * 4]) = ra[u];
+    *reinterpret_cast<float4*>(&Bs[buf][brow][bc4 * 4]) = rb[0];
+  };
+
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -245,92 +277,46 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const float* __restrict__ A0
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   float bsum[2] = {0.f, 0.f};
 
-  // pairs of rows (lane half lh takes row 2*it + lh); an odd last row is taken by half 0 alone
-  const int npair = r1 > r0 ? (int)((r1 - r0) >> 1) : 0;
-  const size_t sa = (size_t)d, sb = (size_t)ldb;
-  const float* pa[2] = {ap[0] + (size_t)(r0 + lh) * sa, ap[1] + (size_t)(r0 + lh) * sa};
-  const float* pb[2] = {bp[0] + (size_t)(r0 + lh) * sb, bp[1] + (size_t)(r0 + lh) * sb};
-  if (npair > 0) {
-    // software pipeline: the loads of the next kU pairs are in flight while this chunk multiplies;
-    // positions past the end re-read the last pair (in bounds) and are zeroed where they are used
-    constexpr int kU = 8;
-    float ca[kU][2], cb[kU][2];
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      const size_t k = (size_t)(u < npair ? u : npair - 1) * 2;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        ca[u][i] = pa[i][k * sa];
-        cb[u][i] = pb[i][k * sb];
-      }
-    }
-    for (int base = 0; base < npair; base += kU) {
-      float na[kU][2], nb[kU][2];
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int it = base + kU + u;
-        const size_t k = (size_t)(it < npair ? it : npair - 1) * 2;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          na[u][i] = pa[i][k * sa];
-          nb[u][i] = pb[i][k * sb];
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of this chunk's products
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const bool in = base + u < npair;
-        float a[2], b[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          a[i] = (in && av[i]) ? ca[u][i] : 0.f;
-          b[i] = (in && bv[i]) ? cb[u][i] : 0.f;
-          bsum[i] += b[i];
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < kU; ++u)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          ca[u][i] = na[u][i];
-          cb[u][i] = nb[u][i];
-        }
-    }
+  const int nchunk = r1 > r0 ? (int)((r1 - r0 + kRC - 1) / kRC) : 0;       // the same for the whole workgroup
+  if (nchunk > 0) {
+    fetch(r0);
+    stash(0);
   }
-  if (r1 > r0 && ((r1 - r0) & 1)) {
-    const size_t rl = (size_t)(r1 - 1);
-    float a[2], b[2];
+  __syncthreads();
+  for (int c = 0; c < nchunk; ++c) {
+    const int buf = c & 1;
+    if (c + 1 < nchunk) fetch(r0 + (long long)(c + 1) * kRC);
+    __builtin_amdgcn_sched_barrier(0);       // keep the global loads ahead of this chunk's products
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const float x = ap[i][rl * sa];
-      a[i] = (lh == 0 && av[i]) ? x : 0.f;
-      const float y = bp[i][rl * sb];
-      b[i] = (lh == 0 && bv[i]) ? y : 0.f;
-      bsum[i] += b[i];
+    for (int ks = 0; ks < kRC / 2; ++ks) {
+      const float2 a2 = *reinterpret_cast<const float2*>(&As[buf][2 * ks + lh][wm * 64 + l32 * 2]);
+      const float2 b2 = *reinterpret_cast<const float2*>(&Bs[buf][2 * ks + lh][wn * 64 + l32 * 2]);
+      const float a[2] = {a2.x, a2.y};
+      const float b[2] = {b2.x, b2.y};
+      bsum[0] += b2.x;
+      bsum[1] += b2.y;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (c + 1 < nchunk) stash(buf ^ 1);      // last read one iteration ago, before that iteration's barrier
+    __syncthreads();
   }
 
   float* P = part + (size_t)slab * (size_t)part_stride;
-  // accumulator register v of lane (l32, lh) holds row 8*(v/4) + 4*lh + (v%4), column l32 of its 32 x 32 block
+  // accumulator register v of lane (l32, lh) holds row 8*(v/4) + 4*lh + (v%4), column l32 of its 32 x 32
+  // block; block (i, j) row R is tile column 2R + i of the wave's 64, block column l is 2l + j of its 64
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + l32;
+    const int n = n0 + wn * 64 + l32 * 2 + j;
     if (n >= N) continue;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        const int m = m0 + wm * 64 + (8 * (v >> 2) + 4 * lh + (v & 3)) * 2 + i;
         if (m < M) P[(size_t)m * N + n] = acc[i][j][v];
       }
   }
@@ -338,7 +324,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const float* __restrict__ A0
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const float tot = bsum[j] + __shfl_xor(bsum[j], 32, 64);
-      const int n = n0 + wn * 64 + j * 32 + l32;
+      const int n = n0 + wn * 64 + l32 * 2 + j;
       if (lh == 0 && n < N) P[(size_t)M * N + n] = tot;
     }
   }
@@ -386,28 +372,34 @@ int grid_for(long long items, int n_cu) {
   return g < 1 ? 1 : (int)g;
 }
 
+// slabs of a product with ntile tiles: one round of workgroups at two per CU, a multiple of 8
+int slabs_for(int ntile, int n_cu, int cap) {
+  int S = ((2 * n_cu) / ntile) & ~7;
+  if (S > cap) S = cap;
+  return S < 8 ? 8 : S;
+}
+
 // C = sum over rows of [A0|A1|A2]^T B into gW (and column sums of B into gb)
 void weight_gradient(const TrainPass& t, const float* A0, const float* A1, const float* A2, int d, int nseg,
                      const float* Bm, int ldb, int N, const int* nrows, float* gW, float* gb, hipStream_t s) {
   const int M = nseg * d;
-  const int ntile = ((M + kWT - 1) / kWT) * ((N + kWT - 1) / kWT);
+  const int ntile = ((M + kTM - 1) / kTM) * ((N + kTN - 1) / kTN);
+  const int S = slabs_for(ntile, t.n_cu, t.slabs);
   const long long stride = (long long)M * N + N;
-  hipLaunchKernelGGL(wgrad_kernel, dim3(ntile * t.slabs), dim3(256), 0, s, A0, A1, A2, d, nseg, Bm, ldb, N, nrows,
-                     t.part, stride, t.slabs, t.status);
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(stride, t.n_cu)), dim3(256), 0, s, t.part, stride, t.slabs,
+  hipLaunchKernelGGL(wgrad_kernel, dim3(ntile * S), dim3(512), 0, s, A0, A1, A2, d, nseg, Bm, ldb, N, nrows,
+                     t.part, stride, S, t.status);
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(stride, t.n_cu)), dim3(256), 0, s, t.part, stride, S,
                      (long long)M * N, N, gW, gb, t.status);
 }
 
 }  // namespace
 
 int train_slabs(int n_cu, int F, int H) {
-  // enough slabs that the smallest product of a pass still covers the chip twice
+  // the largest slab count weight_gradient() uses (the partial-result buffer is sized for it)
+  (void)n_cu;
   (void)F;
-  const int ntile = ((H + kWT - 1) / kWT) * ((H + kWT - 1) / kWT);
-  int S = (2 * n_cu + ntile - 1) / ntile;
-  S = (S + 7) & ~7;                       // the tile-to-XCD mapping of wgrad_kernel needs a multiple of 8
-  if (S > 128) S = 128;
-  return S;
+  (void)H;
+  return 128;
 }
 
 hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s) {
