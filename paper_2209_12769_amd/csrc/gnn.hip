@@ -318,7 +318,7 @@ template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
 void launch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
                    const float* bias, void* out, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  hipLaunchKernelGGL((update_kernel<kBf16, BM, BN, BK, WM, WN>), dim3(a.n_cu * 2), dim3(NT), 0, s, A0, A1, A2, d, nseg,
+  hipLaunchKernelGGL((update_kernel<kBf16, BM, BN, BK, WM, WN>), dim3(a.n_cu * (kBf16 ? 2 : 4)), dim3(NT), 0, s, A0, A1, A2, d, nseg,
                      Wl, bias, out, a.H, a.node_off, a.n_cand, a.status);
 }
 
@@ -339,8 +339,7 @@ void run_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2
     if (d % 64 == 0) dispatch_update<true, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
     else dispatch_update<true, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
   } else {
-    if (d % 32 == 0) dispatch_update<false, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
-    else dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+    dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
   }
 }
 
