@@ -298,7 +298,7 @@ def train_bench(args, w, B, torch):
     work = {"train_update": {"flops": gemm, "bytes": sum(M * (3 * d + H) * 4 for d in dims)},
             "train_wgrad": {"flops": gemm, "bytes": sum(M * (3 * d + H) * 4 for d in dims)},
             "train_dgrad": {"flops": 2 * M * 3 * H * H * (L - 1), "bytes": (L - 1) * M * 4 * H * 4},
-            "train_aggregate": {"bytes": sum(2 * (M + 2 * E) * d * 4 for d in dims) + sum(2 * M * d * 4 for d in dims)},
+            "train_aggregate": {"bytes": sum((2 * E + 2 * M) * d * 4 for d in dims)},      # gathered rows + both means
             "train_gather_back": {"bytes": (L - 1) * ((M + 2 * E) * H * 4 + 2 * M * H * 4)}}
     kernels = {}
     for name, (ms_total, launches) in fam.items():

@@ -309,7 +309,7 @@ typedef struct {
 /* Number of fp32 parameters, in the order W_layers | b_layers | head of dc_set_weights. */
 int64_t dc_num_params(const dc_ctx* ctx);
 
-/* Allocates the training buffers (device; about (L + 6) * max_rows * H * 4 bytes), clears both
+/* Allocates the training buffers (device; about (3 L + 6) * max_rows * max(F, H) * 4 bytes), clears both
  * moment vectors and the step count.  May be called again to restart or to change the sizes. */
 dc_status dc_train_begin(dc_ctx* ctx, const dc_train_params* params, void* stream);
 

@@ -1037,6 +1037,7 @@ dc_status dc_train_begin(dc_ctx* ctx, const dc_train_params* params, void* strea
     Arena a;
     a.base = pass ? ctx->train_mem : nullptr;
     t.hs = a.take<float>((size_t)c.L * R * H);
+    t.means = a.take<float>((size_t)c.L * 2 * R * dmax);
     t.dA = a.take<float>(R * 3 * H);
     t.R = a.take<float>(B * H);
     t.Z1 = a.take<float>(B * H);
@@ -1066,8 +1067,6 @@ dc_status dc_train_begin(dc_ctx* ctx, const dc_train_params* params, void* strea
   t.H = c.H;
   t.L = c.L;
   t.floor = p.floor;
-  t.mp = static_cast<float*>(ctx->agg[0]);
-  t.ms = static_cast<float*>(ctx->agg[1]);
   t.dZ[0] = static_cast<float*>(ctx->act[0]);
   t.dZ[1] = static_cast<float*>(ctx->act[1]);
   t.slabs = S;

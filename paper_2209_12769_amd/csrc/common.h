@@ -236,8 +236,7 @@ struct TrainPass {
   float floor;
   // buffers
   float* hs;                   // [L][max_rows, H] activations after each layer
-  float* mp;                   // [max_rows, max(F,H)] predecessor mean of the layer at hand
-  float* ms;                   // successor mean
+  float* means;                // [L][2][max_rows, max(F,H)] predecessor mean, successor mean of every layer's input
   float* dZ[2];                // [max_rows, H] gradient at the pre-activations, ping-pong
   float* dA;                   // [max_rows, 3H]
   float* R;                    // [max_samples, H] each: R, Z1, Z2, dZ2, dZ1, dR

@@ -238,6 +238,120 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// update, fp32, H a multiple of 128: the same product with the K loop software-pipelined
+// ---------------------------------------------------------------------------
+// Chunks of 16 along K, double-buffered in LDS: while a chunk multiplies, the next one's global loads
+// are in flight and are stored to the other buffer afterwards (one barrier per chunk).  A in LDS
+// row-major with a row stride of 17 floats (conflict-free 4-byte fragment reads), W rows as they lie
+// in memory; MFMA block j of a wave takes columns 2l + j of its 64 (l = lane mod 32), so one 8-byte
+// LDS read feeds both of a lane's B operands and results leave as 8-byte stores.
+template <int BN, int WM>
+__global__ __launch_bounds__(512) void update32_kernel(const float* __restrict__ A0, const float* __restrict__ A1,
+                                                       const float* __restrict__ A2, int d, int nseg,
+                                                       const float* __restrict__ Wf, const float* __restrict__ bias,
+                                                       float* __restrict__ out, int H,
+                                                       const int* __restrict__ node_off, int C,
+                                                       const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  constexpr int BM = 128, BK = 16, WN = 64, NT = 512;
+  constexpr int TM = WM / 32;                         // 2 (BN = 256) or 1 (BN = 128)
+  constexpr int ASTR = BK + 1, BSTR = BN + 32;
+  constexpr int B_PER = (BK * BN / 4) / NT;           // 16-byte loads of W per thread and chunk
+  static_assert((BM / WM) * (BN / WN) == 8 && (B_PER == 1 || B_PER == 2), "eight waves, one or two pieces of W each");
+  __shared__ float As[2][BM * ASTR];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK * BSTR];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / (BN / WN), wn = wave % (BN / WN);
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int ntot = node_off[C];
+  const int nct = H / BN;
+  const int ntiles = ((ntot + BM - 1) / BM) * nct;
+  const int K = nseg * d, nk = K / BK;
+  const int ar = t >> 2, ach = t & 3;                 // loader: one 16-byte piece of A per thread and chunk
+
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int m0 = (tile / nct) * BM;
+    const int n0 = (tile % nct) * BN;
+    const bool arow_ok = m0 + ar < ntot;
+    // per-thread pieces of a chunk: one 16-byte piece of A, B_PER of W (kk = row of the chunk, c4 = piece of the row)
+    const size_t arow_off = (size_t)(m0 + ar) * d + ach * 4;
+    int bkk[B_PER], bc4[B_PER];
+#pragma unroll
+    for (int u = 0; u < B_PER; ++u) {
+      bkk[u] = (t + u * NT) / (BN / 4);
+      bc4[u] = (t + u * NT) % (BN / 4);
+    }
+    float4 ra = make_float4(0.f, 0.f, 0.f, 0.f), rb0, rb1 = make_float4(0.f, 0.f, 0.f, 0.f);
+#define DC_UPDATE32_FETCH(c_)                                                                              \
+    {                                                                                                      \
+      const int k0_ = (c_) * BK;                                                                           \
+      const int seg_ = k0_ / d;                                                                            \
+      const float* Aseg_ = seg_ == 0 ? A0 : (seg_ == 1 ? A1 : A2);                                         \
+      if (arow_ok) ra = *reinterpret_cast<const float4*>(Aseg_ + arow_off + (k0_ - seg_ * d));             \
+      rb0 = *reinterpret_cast<const float4*>(Wf + (size_t)(k0_ + bkk[0]) * H + n0 + bc4[0] * 4);           \
+      if constexpr (B_PER > 1)                                                                             \
+        rb1 = *reinterpret_cast<const float4*>(Wf + (size_t)(k0_ + bkk[B_PER - 1]) * H + n0 + bc4[B_PER - 1] * 4); \
+    }
+#define DC_UPDATE32_STASH(buf_)                                                                            \
+    {                                                                                                      \
+      float* p_ = &As[buf_][ar * ASTR + ach * 4];                                                          \
+      p_[0] = ra.x; p_[1] = ra.y; p_[2] = ra.z; p_[3] = ra.w;                                              \
+      *reinterpret_cast<float4*>(&Bs[buf_][bkk[0] * BSTR + bc4[0] * 4]) = rb0;                             \
+      if constexpr (B_PER > 1)                                                                             \
+        *reinterpret_cast<float4*>(&Bs[buf_][bkk[B_PER - 1] * BSTR + bc4[B_PER - 1] * 4]) = rb1;           \
+    }
+    f32x16 acc[TM][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    DC_UPDATE32_FETCH(0)
+    DC_UPDATE32_STASH(0)
+    __syncthreads();
+    for (int c = 0; c < nk; ++c) {
+      const int buf = c & 1;
+      if (c + 1 < nk) DC_UPDATE32_FETCH(c + 1)
+      __builtin_amdgcn_sched_barrier(0);     // keep the global loads ahead of this chunk's products
+#pragma unroll
+      for (int ks = 0; ks < BK / 2; ++ks) {
+        float a[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = As[buf][(wm * WM + i * 32 + l32) * ASTR + ks * 2 + lh];
+        const float2 b2 = *reinterpret_cast<const float2*>(&Bs[buf][(ks * 2 + lh) * BSTR + wn * WN + l32 * 2]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b2.x, acc[i][0], 0, 0, 0);
+          acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b2.y, acc[i][1], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (c + 1 < nk) DC_UPDATE32_STASH(buf ^ 1)   // last read one chunk ago, before that chunk's barrier
+      __syncthreads();
+    }
+#undef DC_UPDATE32_FETCH
+#undef DC_UPDATE32_STASH
+    // accumulator register v of lane (l32, lh) holds row 8*(v/4)+4*lh+(v%4) of its block; block j's
+    // column l32 is column 2*l32 + j of the wave's 64
+    const int col = n0 + wn * WN + l32 * 2;
+    const float bj0 = bias ? bias[col] : 0.f, bj1 = bias ? bias[col + 1] : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        if (row < ntot) {
+          float2 y = make_float2(acc[i][0][v], acc[i][1][v]);
+          if (bias) y = make_float2(fmaxf(y.x + bj0, 0.f), fmaxf(y.y + bj1, 0.f));
+          *reinterpret_cast<float2*>(out + (size_t)row * H + col) = y;
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // readout + head: one workgroup per candidate; sums in fp64, fixed order
 // ---------------------------------------------------------------------------
 template <bool kBf16>
@@ -339,7 +453,19 @@ void run_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2
     if (d % 64 == 0) dispatch_update<true, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
     else dispatch_update<true, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
   } else {
-    dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+    const float* f0 = static_cast<const float*>(A0);
+    const float* f1 = static_cast<const float*>(A1);
+    const float* f2 = static_cast<const float*>(A2);
+    if (a.H % 256 == 0)
+      hipLaunchKernelGGL((update32_kernel<256, 64>), dim3(a.n_cu * 2), dim3(512), 0, s, f0, f1, f2, d, nseg,
+                         static_cast<const float*>(Wl), bias, static_cast<float*>(out), a.H, a.node_off, a.n_cand,
+                         a.status);
+    else if (a.H % 128 == 0)
+      hipLaunchKernelGGL((update32_kernel<128, 32>), dim3(a.n_cu * 2), dim3(512), 0, s, f0, f1, f2, d, nseg,
+                         static_cast<const float*>(Wl), bias, static_cast<float*>(out), a.H, a.node_off, a.n_cand,
+                         a.status);
+    else
+      dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
   }
 }
 

@@ -423,6 +423,7 @@ hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s) 
   gh.n_cand = 1;
   gh.node_off = t.cnt;
   const long long rows_cap = t.max_rows;
+  const size_t dmax = (size_t)(F > H ? F : H);
   const float* W1 = t.head;
   const float* b1 = W1 + HH;
   const float* W2 = b1 + H;
@@ -450,11 +451,13 @@ hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s) 
   const float* bl = t.b;
   for (int l = 0; l < L; ++l) {
     float* hn = t.hs + (size_t)l * rows_cap * H;
+    float* mp = t.means + (size_t)(2 * l) * rows_cap * dmax;      // both means are kept for the reverse pass
+    float* ms = mp + (size_t)rows_cap * dmax;
     begin(kFamTrainAggregate);
-    launch_mean_aggregate(g, hcur, d, t.mp, t.ms, s);
+    launch_mean_aggregate(g, hcur, d, mp, ms, s);
     end();
     begin(kFamTrainUpdate);
-    launch_dense_update(g, hcur, t.mp, t.ms, d, 3, Wl, bl, hn, s);
+    launch_dense_update(g, hcur, mp, ms, d, 3, Wl, bl, hn, s);
     end();
     Wl += (size_t)3 * d * H;
     bl += H;
@@ -501,11 +504,10 @@ hipError_t launch_train_pass(const TrainPass& t, Profiler* prof, hipStream_t s) 
     const float* hl = l == 0 ? t.X : t.hs + (size_t)(l - 1) * rows_cap * H;
     size_t woff = 0;
     for (int k = 0; k < l; ++k) woff += (size_t)3 * (k == 0 ? F : H) * H;
-    begin(kFamTrainAggregate);
-    launch_mean_aggregate(g, hl, dl, t.mp, t.ms, s);
-    end();
+    const float* mp = t.means + (size_t)(2 * l) * rows_cap * dmax;
+    const float* ms = mp + (size_t)rows_cap * dmax;
     begin(kFamTrainWgrad);
-    weight_gradient(t, hl, t.mp, t.ms, dl, 3, dZ, H, H, nrows, gWl + woff, gbl + (size_t)l * H, s);
+    weight_gradient(t, hl, mp, ms, dl, 3, dZ, H, H, nrows, gWl + woff, gbl + (size_t)l * H, s);
     end();
     if (l == 0) break;
     begin(kFamTrainDgrad);
