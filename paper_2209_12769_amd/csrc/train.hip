@@ -202,6 +202,9 @@ __global__ __launch_bounds__(256) void gather_back_kernel(const float* __restric
 // and another its two B operands.  The column sums of B (bias gradients) ride
 // along in the waves of the first row of tiles.
 constexpr int kTM = 256, kTN = 128, kRC = 16;
+__device__ __forceinline__ float4 keep4(bool c, float4 x) {
+  return make_float4(c ? x.x : 0.f, c ? x.y : 0.f, c ? x.z : 0.f, c ? x.w : 0.f);
+}
 __global__ __launch_bounds__(512) void wgrad_kernel(const float* __restrict__ A0, const float* __restrict__ A1,
                                                     const float* __restrict__ A2, int d, int nseg,
                                                     const float* __restrict__ Bm, int ldb, int N,
@@ -237,35 +240,32 @@ __global__ __launch_bounds__(512) void wgrad_kernel(const float* __restrict__ A0
   const int bc4 = t & 31, brow = t >> 5;                 // brow 0..15
   const int bn = n0 + bc4 * 4;
   const bool bvec = (N & 3) == 0 && (ldb & 3) == 0;      // 16-byte loads of B are possible
-  float4 ra[2], rb[1];
-  auto fetch = [&](long long rbase) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const long long r = rbase + arow + 8 * u;
-      ra[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (aok && r < r1) ra[u] = *reinterpret_cast<const float4*>(pa + (size_t)r * d);
-    }
-#pragma unroll
-    for (int u = 0; u < 1; ++u) {
-      const long long r = rbase + brow;
-      rb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < r1) {
-        const float* q = Bm + (size_t)r * ldb;
-        if (bvec) {
-          if (bn < N) rb[u] = *reinterpret_cast<const float4*>(q + bn);
-        } else {
-          if (bn < N) rb[u].x = q[bn];
-          if (bn + 1 < N) rb[u].y = q[bn + 1];
-          if (bn + 2 < N) rb[u].z = q[bn + 2];
-          if (bn + 3 < N) rb[u].w = q[bn + 3];
-        }
-      }
+  // Straight-line loads: a row past the slab's end re-reads the slab's last row (in bounds) and a column
+  // past the matrix re-reads column 0; both are stored to LDS as zeros.
+  const int bnc = bn < N ? bn : 0;
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 ra0 = zero4, ra1 = zero4, rb0 = zero4;
+  const int ir1 = (int)r1, last = ir1 - 1;               // row counts fit an int
+  auto fetch = [&](int rbase) {
+    const int a0r = rbase + arow, a1r = a0r + 8, br = rbase + brow;
+    ra0 = *reinterpret_cast<const float4*>(pa + (size_t)(a0r < ir1 ? a0r : last) * d);
+    ra1 = *reinterpret_cast<const float4*>(pa + (size_t)(a1r < ir1 ? a1r : last) * d);
+    const float* q = Bm + (size_t)(br < ir1 ? br : last) * ldb;
+    if (bvec) {
+      rb0 = *reinterpret_cast<const float4*>(q + bnc);
+    } else {
+      rb0 = zero4;
+      if (bn < N) rb0.x = q[bn];
+      if (bn + 1 < N) rb0.y = q[bn + 1];
+      if (bn + 2 < N) rb0.z = q[bn + 2];
+      if (bn + 3 < N) rb0.w = q[bn + 3];
     }
   };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) *reinterpret_cast<float4*>(&As[buf][arow + 8 * u][ac4 * 4]) = ra[u];
-    *reinterpret_cast<float4*>(&Bs[buf][brow][bc4 * 4]) = rb[0];
+  auto stash = [&](int buf, int rbase) {
+    const int a0r = rbase + arow, a1r = a0r + 8, br = rbase + brow;
+    *reinterpret_cast<float4*>(&As[buf][arow][ac4 * 4]) = keep4(aok && a0r < ir1, ra0);
+    *reinterpret_cast<float4*>(&As[buf][arow + 8][ac4 * 4]) = keep4(aok && a1r < ir1, ra1);
+    *reinterpret_cast<float4*>(&Bs[buf][brow][bc4 * 4]) = keep4(bn < N && br < ir1, rb0);
   };
 
   f32x16 acc[2][2];
@@ -279,13 +279,13 @@ __global__ __launch_bounds__(512) void wgrad_kernel(const float* __restrict__ A0
 
   const int nchunk = r1 > r0 ? (int)((r1 - r0 + kRC - 1) / kRC) : 0;       // the same for the whole workgroup
   if (nchunk > 0) {
-    fetch(r0);
-    stash(0);
+    fetch((int)r0);
+    stash(0, (int)r0);
   }
   __syncthreads();
   for (int c = 0; c < nchunk; ++c) {
     const int buf = c & 1;
-    if (c + 1 < nchunk) fetch(r0 + (long long)(c + 1) * kRC);
+    if (c + 1 < nchunk) fetch((int)r0 + (c + 1) * kRC);
     __builtin_amdgcn_sched_barrier(0);       // keep the global loads ahead of this chunk's products
 #pragma unroll
     for (int ks = 0; ks < kRC / 2; ++ks) {
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(512) void wgrad_kernel(const float* __restrict__ A0
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (c + 1 < nchunk) stash(buf ^ 1);      // last read one iteration ago, before that iteration's barrier
+    if (c + 1 < nchunk) stash(buf ^ 1, (int)r0 + (c + 1) * kRC);   // buffer last read one iteration ago, before that barrier
     __syncthreads();
   }
 
