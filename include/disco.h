@@ -335,7 +335,9 @@ dc_status dc_loss_gradients(dc_ctx* ctx, const dc_batch* in, const float* target
 
 /* One training step: dc_loss_gradients followed by one Adam update of all parameters in place.
  * An empty batch (n_cand = 0) leaves everything as it is and reports a loss of 0.
- * No host synchronisation: steps may be queued back to back on one stream.                     */
+ * No host synchronisation: steps may be queued back to back on one stream.  The step count t
+ * of Adam's bias correction is host state of the context and enters the update kernel as an
+ * argument, so a step must not be replayed from a captured graph.                              */
 dc_status dc_train_step(dc_ctx* ctx, const dc_batch* in, const float* target, float* loss, void* stream);
 
 /* Copies the current weights to host arrays laid out as for dc_set_weights (DC_F32 contexts).

@@ -383,3 +383,53 @@ def test_bench_size_batch(B):
     for sl in tensor_slices(model):
         assert np.abs(acc[sl] - g_full[sl]).max() <= 1e-5 * np.abs(g_full[sl]).max()
     ev.close()
+
+
+def test_train_then_search_with_the_trained_estimator(B):
+    """The pieces in the order the paper uses them: the estimator is trained on fused-op samples of a
+    module (Sec. 3.3.3), then the search (Alg. 1) runs on that module with Cost() built on the trained
+    estimator.  Training follows the oracle's; the search result is checked on its own: the reported
+    costs of H_in and H_opt agree with the oracle's Cost() of the same labelings under the same weights
+    (the oracle's trained weights, handed to both sides)."""
+    import torch
+    base = wl.make("cfg2", 1)
+    g = base.graphs[0]
+    model = wl.ModelSpec(base.model.F, 64, 2, "f32")
+    w = wl.custom("pipe", model, [g], [wl.training_labels(g, 3, 4, kmax=16)], seed=2)
+    w.weights.head[-1] += 1.0
+    t, x = wl.profile_of(w)
+    ev, batch = gpu_fused_batch(B, w)
+    ob, member, _ = oracle_fused_batch(w)
+    target = wl.synthetic_fused_times(ob.node_off, member, t, 3)
+    steps, lr = 12, 3e-3
+    p0 = ot.Params.from_weights(w.weights, model.F, model.H, model.L)
+    p_o, losses_o = ot.train([ob] * steps, [target] * steps, p0, model.F, model.H, model.L, lr=lr)
+    ev.train_begin(lr, batch.c.n_cand, ob.ntot)
+    tg = torch.from_numpy(target).to(ev.device)
+    losses = [float(ev.train_step(batch, tg).cpu()[0]) for _ in range(steps)]
+    assert ev.check() == 0
+    np.testing.assert_allclose(losses, losses_o, rtol=2e-3)
+    assert losses[-1] < 0.6 * losses[0]
+    ev.close()
+    # the search on the same module with the trained estimator
+    L = model.L
+    trained = wl.Weights(np.concatenate([a.ravel() for a in p_o.W]).astype(np.float32),
+                         np.concatenate(p_o.b).astype(np.float32),
+                         np.concatenate([p_o.W1.ravel(), p_o.b1, p_o.W2.ravel(), p_o.b2, p_o.w3,
+                                         p_o.b3]).astype(np.float32))
+    P = 8
+    ident = np.tile(np.arange(g.n, dtype=np.int32), (2 * P, 1))
+    ws = wl.custom("pipe-search", model, [g], [ident], weights=trained)
+    es = B.evaluator_for(ws)
+    es.set_profile(t, x)
+    labels, r = es.search(0, g.n, alpha=1.05, beta=8, seed=4, ar_c=0.02, ar_d=0.01, max_unchanged=200, parents=P,
+                          max_steps=25)
+    es.close()
+    assert r.cost_opt <= r.cost_in and r.evaluated > 100
+    both = wl.custom("pipe-check", model, [g], [np.stack([np.arange(g.n, dtype=np.int32), labels])], weights=trained)
+    ref = orc.cost(both, t, x, 0.02, 0.01)
+    assert np.isfinite(ref).all()
+    assert r.cost_in == pytest.approx(ref[0], rel=1e-5)
+    assert r.cost_opt == pytest.approx(ref[1], rel=1e-5)
+    print(f"[train+search] loss {losses[0]:.4f} -> {losses[-1]:.4f} in {steps} steps; search cost {r.cost_in:.4f} -> "
+          f"{r.cost_opt:.4f} ({r.evaluated} evaluated, {len(np.unique(labels))} groups of {g.n})", flush=True)
