@@ -310,12 +310,33 @@ def test_edge_cases_and_errors(B):
     W3, _, _ = ev.get_weights()
     assert np.array_equal(W3, w.weights.layers)
     ev.close()
+    # the caller's batch too small for the training set: found on the device, reported by the call
+    w2 = sample_workload("cfg2", 1, 1, (32, 2))
+    ev2 = trainer_for(B, w2)
+    t2, x2 = wl.profile_of(w2)
+    ev2.set_profile(t2, x2)
+    nb2, eb2 = sizes(w2)
+    small = ev2.alloc_batch(nb2 // 2 + 1, nb2, ob.ntot - 1, eb2)          # one row short
+    cg2, co2, gid2 = ev2.to_device(w2.cand_graph), ev2.to_device(w2.cand_off), ev2.to_device(w2.group_id)
+    assert B.dc_fused_op_batch(ev2.ctx, 1, cg2.data_ptr(), co2.data_ptr(), gid2.data_ptr(), small.c, 0) == 4
+    assert small.c.n_cand == 0
+    # ... and the same call with enough room still works afterwards
+    ok = ev2.fused_op_batch(cg2, co2, gid2, ev2.alloc_batch(nb2 // 2 + 1, nb2, nb2, eb2))
+    assert ok.c.n_cand == K
+    # without the profile the ops cannot be told from the all-reduce nodes
+    ev3 = trainer_for(B, w2)
+    assert B.dc_fused_op_batch(ev3.ctx, 1, cg2.data_ptr(), co2.data_ptr(), gid2.data_ptr(), ok.c, 0) == 1
+    ev3.close()
+    ev2.close()
     # training is fp32 with the mean aggregator only
     wb = wl.make("cfg1", 2)
     m = wl.ModelSpec(wb.model.F, wb.model.H, wb.model.L, "bf16")
     evb = B.evaluator_for(wl.Workload(wb.name, m, wb.graphs, wb.cand_graph, wb.cand_off, wb.group_id, wb.weights))
     p = B.DcTrainParams(1e-3, 0.9, 0.999, 1e-8, 1e-6, 4, 64)
     assert B.dc_train_begin(evb.ctx, p, 0) == 7
+    Wn, bn, hn = (np.empty(1, np.float32) for _ in range(3))
+    assert B.dc_get_weights(evb.ctx, Wn, bn, hn, 0) == 7
+    assert B.dc_num_params(evb.ctx) > 0
     evb.close()
 
 
