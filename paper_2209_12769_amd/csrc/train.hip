@@ -330,6 +330,164 @@ __global__ __launch_bounds__(512) void wgrad_kernel(const float* __restrict__ A0
   }
 }
 
+// ---- the same product with the operands moved into LDS by DMA (global_load_lds_dwordx4) ----
+// For d a multiple of 256, N a multiple of 128 and 16-byte aligned rows of B: a tile's 256 columns
+// of A lie in one operand, so one wave instruction moves one row of the A chunk (64 lanes x 16
+// bytes = its 256 floats) or two rows of the B chunk straight into the layout the products read,
+// with no registers, LDS stores or selects in between.  Three chunk buffers: the DMA of chunk c+2
+// is issued when chunk c starts, so a load has two chunks' products to land.  The compiler does
+// not see these loads; the waits for them are placed by hand (loads return in issue order, so
+// "at most three newer outstanding" means the chunk before the newest has landed).  Rows that do
+// not fill a chunk at the end of a slab go through registers with zero fill.
+typedef __attribute__((address_space(3))) char lds_char;
+constexpr int kWgradRing = 3;
+constexpr int kWgradLds = kWgradRing * kRC * (kTM + kTN) * 4;       // 73728
+extern __shared__ __attribute__((aligned(1024))) char dc_wgrad_smem[];
+__device__ __forceinline__ void dma16_to_lds(const void* gaddr, unsigned lds_base) {
+  // lane l writes lds_base + 16 * l
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  asm volatile("s_waitcnt %0" : : "n"((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14)) : "memory");
+}
+
+__global__ __launch_bounds__(512) void wgrad_dma_kernel(const float* __restrict__ A0, const float* __restrict__ A1,
+                                                        const float* __restrict__ A2, int d, int nseg,
+                                                        const float* __restrict__ Bm, int ldb, int N,
+                                                        const int* __restrict__ nrows, float* __restrict__ part,
+                                                        long long part_stride, int S,
+                                                        const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  // dynamic LDS (72 KB, above the static limit): the A ring, then the B ring
+  typedef float AChunk[kRC][kTM];
+  typedef float BChunk[kRC][kTN];
+  AChunk* As = reinterpret_cast<AChunk*>(dc_wgrad_smem);
+  BChunk* Bs = reinterpret_cast<BChunk*>(dc_wgrad_smem + kWgradRing * sizeof(AChunk));
+  constexpr int kRing = kWgradRing;
+  const int M = nseg * d;                                // a multiple of kTM, N a multiple of kTN (host)
+  const int tiles_n = N / kTN, tiles_m = M / kTM;
+  const int ntile = tiles_m * tiles_n;
+  const int per_xcd = gridDim.x >> 3;                    // see wgrad_kernel
+  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int tile = item % ntile, slab = item / ntile;
+  if (slab >= S) return;
+  const int m0 = (tile / tiles_n) * kTM, n0 = (tile % tiles_n) * kTN;
+  const int rows = nrows[0];
+  const int per = (rows + S - 1) / S;
+  const long long r0l = (long long)slab * per;
+  const int r0 = (int)(r0l < rows ? r0l : rows);
+  const int r1 = r0 + per < rows ? r0 + per : rows;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lh = lane >> 5;
+  const int aseg = m0 / d;                               // the tile's columns lie in one operand
+  const float* Aseg = (aseg == 0 ? A0 : (aseg == 1 ? A1 : A2)) + (m0 - aseg * d);
+  const unsigned ldsA = (unsigned)(size_t)((lds_char*)dc_wgrad_smem);
+  const unsigned ldsB = ldsA + (unsigned)(kWgradRing * sizeof(AChunk));
+  constexpr unsigned kABuf = kRC * kTM * 4, kBBuf = kRC * kTN * 4;   // bytes per ring slot
+  const int nfull = (r1 - r0) / kRC;                     // chunks moved by DMA; the same for the whole workgroup
+
+  // wave w moves rows 2w and 2w+1 of the A chunk (one instruction each) and rows 2w, 2w+1 of the B
+  // chunk (one instruction: lanes 0-31 the first, lanes 32-63 the second): three per wave and chunk
+  auto dma_chunk = [&](int c) {
+    const int slot = c % kRing;
+    const size_t row = (size_t)(r0 + c * kRC + 2 * wave);           // < r1 - 1: the chunk is full
+    dma16_to_lds(Aseg + row * d + lane * 4, ldsA + slot * kABuf + (2 * wave) * (kTM * 4));
+    dma16_to_lds(Aseg + (row + 1) * d + lane * 4, ldsA + slot * kABuf + (2 * wave + 1) * (kTM * 4));
+    dma16_to_lds(Bm + (row + lh) * ldb + n0 + l32 * 4, ldsB + slot * kBBuf + (2 * wave) * (kTN * 4));
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  float bsum[2] = {0.f, 0.f};
+  auto multiply = [&](int slot) {
+    // the operands of the next row pair are requested before the products of the current one
+    float2 a2 = *reinterpret_cast<const float2*>(&As[slot][lh][wm * 64 + l32 * 2]);
+    float2 b2 = *reinterpret_cast<const float2*>(&Bs[slot][lh][wn * 64 + l32 * 2]);
+#pragma unroll
+    for (int ks = 0; ks < kRC / 2; ++ks) {
+      float2 an = a2, bn = b2;
+      if (ks + 1 < kRC / 2) {
+        an = *reinterpret_cast<const float2*>(&As[slot][2 * ks + 2 + lh][wm * 64 + l32 * 2]);
+        bn = *reinterpret_cast<const float2*>(&Bs[slot][2 * ks + 2 + lh][wn * 64 + l32 * 2]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      bsum[0] += b2.x;
+      bsum[1] += b2.y;
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.x, b2.x, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.x, b2.y, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.x, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.y, acc[1][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      a2 = an;
+      b2 = bn;
+    }
+  };
+
+  if (nfull > 0) dma_chunk(0);
+  if (nfull > 1) dma_chunk(1);
+  for (int c = 0; c < nfull; ++c) {
+    // this wave's part of chunk c has landed (newer: chunk c+1's three, if it exists) ...
+    if (c + 1 < nfull) wait_vmcnt<3>(); else wait_vmcnt<0>();
+    // ... and so has everybody's; all waves are also done with chunk c-1, whose slot chunk c+2 takes
+    __syncthreads();
+    if (c + 2 < nfull) dma_chunk(c + 2);
+    multiply(c % kRing);
+  }
+  if (r0 + nfull * kRC < r1) {
+    // the rows left over: through registers, zero-filled, into the slot after the last chunk's
+    // (last read two chunks ago; no DMA is outstanding)
+    const int slot = nfull % kRing;
+    const int rbase = r0 + nfull * kRC;
+    const int ac4 = t & 63, arow = t >> 6, bc4 = t & 31, brow = t >> 5;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int r = rbase + arow + 8 * u;
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < r1) x = *reinterpret_cast<const float4*>(Aseg + (size_t)r * d + ac4 * 4);
+      *reinterpret_cast<float4*>(&As[slot][arow + 8 * u][ac4 * 4]) = x;
+    }
+    {
+      const int r = rbase + brow;
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < r1) x = *reinterpret_cast<const float4*>(Bm + (size_t)r * ldb + n0 + bc4 * 4);
+      *reinterpret_cast<float4*>(&Bs[slot][brow][bc4 * 4]) = x;
+    }
+    __syncthreads();
+    multiply(slot);
+  }
+
+  float* P = part + (size_t)slab * (size_t)part_stride;
+  // same block-to-column assignment as wgrad_kernel
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = n0 + wn * 64 + l32 * 2 + j;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * 64 + (8 * (v >> 2) + 4 * lh + (v & 3)) * 2 + i;
+        P[(size_t)m * N + n] = acc[i][j][v];
+      }
+  }
+  if (m0 == 0 && wm == 0) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float tot = bsum[j] + __shfl_xor(bsum[j], 32, 64);
+      const int n = n0 + wn * 64 + l32 * 2 + j;
+      if (lh == 0) P[(size_t)M * N + n] = tot;
+    }
+  }
+}
+
 // gW [M*N] and gb [N] = sums of the slabs' partial results, fp64, ascending slab order
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part, long long part_stride,
                                                            int S, long long MN, int N, float* __restrict__ gW,
@@ -386,8 +544,18 @@ void weight_gradient(const TrainPass& t, const float* A0, const float* A1, const
   const int ntile = ((M + kTM - 1) / kTM) * ((N + kTN - 1) / kTN);
   const int S = slabs_for(ntile, t.n_cu, t.slabs);
   const long long stride = (long long)M * N + N;
-  hipLaunchKernelGGL(wgrad_kernel, dim3(ntile * S), dim3(512), 0, s, A0, A1, A2, d, nseg, Bm, ldb, N, nrows,
-                     t.part, stride, S, t.status);
+  static bool lds_ok = false, lds_tried = false;
+  if (!lds_tried) {
+    lds_tried = true;
+    lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kWgradLds) == hipSuccess;
+  }
+  if (lds_ok && d % kTM == 0 && N % kTN == 0 && ldb % 4 == 0)
+    hipLaunchKernelGGL(wgrad_dma_kernel, dim3(ntile * S), dim3(512), kWgradLds, s, A0, A1, A2, d, nseg, Bm, ldb, N, nrows,
+                       t.part, stride, S, t.status);
+  else
+    hipLaunchKernelGGL(wgrad_kernel, dim3(ntile * S), dim3(512), 0, s, A0, A1, A2, d, nseg, Bm, ldb, N, nrows,
+                       t.part, stride, S, t.status);
   hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(stride, t.n_cu)), dim3(256), 0, s, t.part, stride, S,
                      (long long)M * N, N, gW, gb, t.status);
 }
