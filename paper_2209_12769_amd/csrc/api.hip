@@ -44,6 +44,7 @@ struct dc_ctx {
   void* desc[2] = {nullptr, nullptr};
   int* status = nullptr;    // [2]
   int* totals = nullptr;    // [2]
+  char* zero_row = nullptr; // 1 KB of zeros
   int* h_pinned = nullptr;  // [4] pinned host mirror for status / totals
   // weights
   void* W = nullptr;
@@ -75,6 +76,7 @@ struct dc_ctx {
   bool have_profile = false;
   std::vector<int> h_gno, h_geo;   // host copies of the base graphs' offsets
   int allow_fused = 1;
+  int u1_dma = 1;
   // training (dc_train_begin)
   bool training = false;
   dc_train_params tp{};
@@ -133,6 +135,7 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   a.base = base;
   int* status = a.take<int>(64);
   int* totals = a.take<int>(64);
+  char* zero_row = a.take<char>(1024);
   ContractTmp t;
   t.tmp_eoff = a.take<int>(k.C + 1);
   t.members = a.take<int>(k.NB + 1);
@@ -167,6 +170,7 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
     ctx->score[0] = score0;
     ctx->score[1] = score1;
     ctx->status = status;
+    ctx->zero_row = zero_row;
     ctx->totals = totals;
     ctx->tmp = t;
     ctx->ib = b;
@@ -277,6 +281,7 @@ GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) 
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;
   g.allow_fused = ctx->allow_fused;
+  g.zero_row = ctx->u1_dma ? ctx->zero_row : nullptr;
   if (ctx->cfg.aggregator == DC_AGG_ATTENTION) {
     g.heads = ctx->cfg.heads;
     g.att = ctx->att;
@@ -430,6 +435,8 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
   {
     const char* env = getenv("DC_DISABLE_FUSED");   // debugging aid: run the unfused layer kernels
     ctx->allow_fused = !(env && env[0] == '1');
+    env = getenv("DC_U1_DMA");                           // 0: one-slot layers gather through registers, not by DMA
+    ctx->u1_dma = !(env && env[0] == '0');
   }
   hipError_t e = hipGetDevice(&ctx->device);
   if (e != hipSuccess) {
@@ -459,6 +466,7 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
   carve(*cfg, ctx->arena, ctx);
   e = hipMemset(ctx->status, 0, 64 * sizeof(int));
   if (e == hipSuccess) e = hipMemset(ctx->totals, 0, 64 * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(ctx->zero_row, 0, 1024);
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 64 * sizeof(int), hipHostMallocDefault);
   const size_t es = cfg->dtype == DC_BF16 ? 2 : 4;
   const size_t HH = (size_t)cfg->H * cfg->H;

@@ -351,7 +351,7 @@ struct MfmaConst {
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
 
-template <int DCH, bool DENSE>
+template <int DCH, bool DENSE, bool PF = false>
 __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
   constexpr int NK = Shape<DCH, DENSE>::NK;
   int n_req = 0;                            // requests of this step, in fours
@@ -394,6 +394,32 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   if (s >= 0) {
     const char* As = c.smem + (s % 3) * kABytes;
     const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (NK > 3 ? s % 3 : s % NK) * kBBytes);
+    if constexpr (PF) {
+      // The whole chunk is in LDS when the step starts: the fragments of the next 16 columns are
+      // requested before this 16's products are issued, so that the one MFMA wave of a SIMD does
+      // not wait out an LDS round trip per 16 columns.
+      bf16x8 a[2][2], b[2][4];
+#define DC_FRAGS(ks_, buf_)                                                                                  \
+      {                                                                                                      \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                        \
+          a[buf_][i] = *reinterpret_cast<const bf16x8*>(As + (c.wm * 64 + i * 32 + c.l32) * kARow +          \
+                                                        ((((ks_) * 2 + c.lh) ^ c.sw) << 4));                 \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                        \
+          b[buf_][j] = *reinterpret_cast<const bf16x8*>(Bs + (((ks_) * 2 + c.lh) * kBN + c.wn * 128 + j * 32 + c.l32) * 8); \
+      }
+      DC_FRAGS(0, 0)
+#pragma unroll
+      for (int ks = 0; ks < kBK / 16; ++ks) {
+        if (ks + 1 < kBK / 16) DC_FRAGS(ks + 1, (ks + 1) & 1)
+        __builtin_amdgcn_sched_barrier(0);     // keep these requests ahead of the products below
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
+      }
+#undef DC_FRAGS
+    } else {
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       bf16x8 a[2], b[4];
@@ -411,6 +437,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    }
     }
   }
   // All but this step's requests (eight W pieces and/or, for one of the node's own chunks, four
@@ -614,6 +641,132 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
   }
 }
 
+// The same layer for batches whose rows have at most one neighbour per direction in-kernel
+// (one gather slot; longer lists bring their finished mean from the pre-pass): the mean of such a row
+// is a row that already exists in memory -- the neighbour's, the pre-pass's, or a row of zeros for an
+// empty list -- so the data-moving waves copy it from global memory straight into the A ring by
+// DMA, exactly as the MFMA waves do with the node's own rows, and do no arithmetic at all.  Per
+// tile a lane turns the descriptors of its four rows into eight source addresses (requested one
+// tile ahead with ordinary loads); a gather step is then four DMA instructions.  The MFMA waves run
+// the very same steps as in layer256_kernel.
+template <int DCH>
+__global__ __launch_bounds__(kNT) void layer256_dma1_kernel(
+    const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
+    const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ zero_row,
+    const u16* __restrict__ Wp, const float* __restrict__ bias, u16* __restrict__ out,
+    const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  constexpr int NK = Shape<DCH, false>::NK;
+  if (status[0] != 0) return;
+  char* smem = dc_l256_smem;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int ntot = node_off[C];
+  const int ntiles = (ntot + kBM - 1) / kBM;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per = gridDim.x >> 3;   // as in layer256_kernel
+  const int tpx = (ntiles + 7) >> 3;
+  const int lim = min(tpx, ntiles - xcd * tpx);
+  const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
+  const int S = nt_wg * NK;
+  if (S == 0) return;
+  const int role_wave = wave & 3;
+  if (wave < 4) {
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    MfmaConst mc;
+    mc.Wp = Wp;
+    mc.bias = bias;
+    mc.out = out;
+    mc.smem = smem;
+    mc.h = reinterpret_cast<const char*>(h);
+    mc.stage = smem + kStageOff + role_wave * kStageBytes;
+    mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256_smem);
+    mc.ntot = ntot;
+    mc.tile0 = xcd * tpx + slot;
+    mc.per = per;
+    mc.wm = role_wave >> 1;
+    mc.wn = role_wave & 1;
+    mc.l32 = lane & 31;
+    mc.lh = lane >> 5;
+    mc.lane = lane;
+    mc.sw = ((lane & 31) >> 1) & 7;
+    mc.wave = __builtin_amdgcn_readfirstlane(role_wave);
+    __syncthreads();                          // step -3
+    for (int s = -2; s < S; ++s) {
+      mfma_step<DCH, false, true>(s, S, acc, mc);
+      __syncthreads();
+    }
+  } else {
+    constexpr unsigned kRowB = Shape<DCH>::ROWB;
+    const int mwave = __builtin_amdgcn_readfirstlane(role_wave);
+    const unsigned lds0 = (unsigned)(size_t)((lds_char*)dc_l256_smem);
+    const char* hb = reinterpret_cast<const char*>(h);
+    const char* pb_in = reinterpret_cast<const char*>(hin_heavy);
+    const char* pb_out = reinterpret_cast<const char*>(hout_heavy);
+    const char* zr = reinterpret_cast<const char*>(zero_row);
+    const int tile0 = xcd * tpx + slot;
+    // piece mwave*4 + i of a chunk is rows 8*piece .. 8*piece+7; lane l fills position l&7 of row l>>3
+    // of the piece, which under the swizzle holds column piece (l&7) ^ ((row>>1)&7)
+    const int r0l = mwave * 32 + (lane >> 3);                 // row of item 0 within the tile; item i: + 8 i
+    v4i nd0, nd1, nd2, nd3, ne0, ne1, ne2, ne3;               // next tile's descriptors: predecessors, successors
+    const char *si0, *si1, *si2, *si3, *so0, *so1, *so2, *so3;   // this tile's source addresses
+#define DC_REQUEST(ti_)                                                                      \
+    {                                                                                        \
+      const int mq_ = (tile0 + (ti_) * per) * kBM + r0l;                                     \
+      nd0 = desc_in[min(mq_, ntot - 1)];       ne0 = desc_out[min(mq_, ntot - 1)];           \
+      nd1 = desc_in[min(mq_ + 8, ntot - 1)];   ne1 = desc_out[min(mq_ + 8, ntot - 1)];       \
+      nd2 = desc_in[min(mq_ + 16, ntot - 1)];  ne2 = desc_out[min(mq_ + 16, ntot - 1)];      \
+      nd3 = desc_in[min(mq_ + 24, ntot - 1)];  ne3 = desc_out[min(mq_ + 24, ntot - 1)];      \
+    }
+    // code 0: empty list (zeros); 1: the neighbour's row of h; above 3: the row's own place in the pre-pass buffer
+#define DC_SOURCE(dd_, pb_, i_)                                                              \
+    (((dd_).w == 0 ? zr : (((dd_).w > 3 ? (pb_) : hb) + (size_t)(unsigned)(dd_).x * kRowB)) + \
+     ((((lane & 7) ^ (((r0l + 8 * (i_)) >> 1) & 7))) << 4))
+#define DC_ADOPT()                                                                           \
+    {                                                                                        \
+      si0 = DC_SOURCE(nd0, pb_in, 0);  so0 = DC_SOURCE(ne0, pb_out, 0);                      \
+      si1 = DC_SOURCE(nd1, pb_in, 1);  so1 = DC_SOURCE(ne1, pb_out, 1);                      \
+      si2 = DC_SOURCE(nd2, pb_in, 2);  so2 = DC_SOURCE(ne2, pb_out, 2);                      \
+      si3 = DC_SOURCE(nd3, pb_in, 3);  so3 = DC_SOURCE(ne3, pb_out, 3);                      \
+    }
+    DC_REQUEST(0)
+    DC_ADOPT()
+    DC_REQUEST(min(1, nt_wg - 1))
+    for (int s = -3; s < S; ++s) {
+      const int J = s + 2;
+      int n4 = 0;                              // vector-memory instructions of this step, in fours
+      if (J >= 0 && J < S) {
+        const int ti = J / NK, kc = J - ti * NK;
+        if (kc == 0 && ti > 0) {
+          DC_ADOPT()
+          DC_REQUEST(min(ti + 1, nt_wg - 1))
+          n4 += 2;
+        }
+        if (kc >= DCH) {
+          const bool succ = kc / DCH == 2;
+          const unsigned q = (unsigned)(kc % DCH) * (unsigned)kARow;      // 64 columns = 128 bytes
+          const unsigned ring = lds0 + (unsigned)(J % 3) * kABytes + (unsigned)mwave * 4096u;
+          load16_to_lds((succ ? so0 : si0) + q, ring);
+          load16_to_lds((succ ? so1 : si1) + q, ring + 1024u);
+          load16_to_lds((succ ? so2 : si2) + q, ring + 2048u);
+          load16_to_lds((succ ? so3 : si3) + q, ring + 3072u);
+          n4 += 1;
+        }
+      }
+      // everything but this step's requests has landed: the rows of job s+1, which the MFMA waves
+      // read after the barrier, were requested one step ago
+      wait_vm_times4(__builtin_amdgcn_readfirstlane(n4));
+      __syncthreads();
+    }
+#undef DC_REQUEST
+#undef DC_SOURCE
+#undef DC_ADOPT
+  }
+}
+
 // One gather descriptor per node and direction: the first `slots` neighbours (unused slots
 // and rows left to the pre-pass point at the node itself, always a valid row) and a code:
 // the number of slots that count, or 5 for a row left to the pre-pass.  Depends only on the
@@ -768,6 +921,25 @@ hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const f
   if (prof) prof->end(s);
   if (prof) prof->begin(DCH == 4 ? kFamLayer256 : kFamLayer64, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
+  if constexpr (U == 1) {
+    // one slot: the rows go to LDS by DMA (a context created under DC_U1_DMA=0 passes no zero row and
+    // keeps the register path)
+    static bool dma_attr = false, dma_ok = false;
+    auto kdma = layer256_dma1_kernel<DCH>;
+    if (!dma_attr) {
+      dma_attr = true;
+      dma_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kdma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kLdsTotal) == hipSuccess;
+    }
+    if (dma_ok && a.zero_row) {
+      hipLaunchKernelGGL(kdma, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
+                         static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
+                         static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(a.zero_row),
+                         static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand, a.status);
+      if (prof) prof->end(s);
+      return hipGetLastError();
+    }
+  }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
                      static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
                      static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(Wl), bias, static_cast<u16*>(out),

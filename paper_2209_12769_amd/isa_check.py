@@ -10,7 +10,7 @@ outside inline asm that reads or writes the destination registers of an asm load
 has covered that load.  It only sees hazards inside a block, which is where such copies land.
 
 Usage: python -m paper_2209_12769_amd.isa_check [listing.s [kernel-symbol-regex ...]]
-With no arguments it compiles csrc/gnn_layer256.hip to a listing and checks every layer256_kernel in it."""
+With no arguments it compiles csrc/gnn_layer256.hip to a listing and checks every layer256_*kernel in it."""
 import re, sys
 
 def regs(tok):
@@ -96,13 +96,13 @@ def kernels_in(path, name):
 
 
 def check_layer256(listing=None):
-    """{kernel symbol: hazards} for every instantiation of layer256_kernel."""
+    """{kernel symbol: hazards} for every instantiation of layer256_kernel and layer256_dma1_kernel."""
     import os, tempfile
     here = os.path.dirname(os.path.abspath(__file__))
     if listing is None:
         listing = listing_of(os.path.join(here, "csrc", "gnn_layer256.hip"),
                              os.path.join(tempfile.mkdtemp(), "gnn_layer256.s"))
-    return {k: check(listing, '^' + re.escape(k) + ':') for k in kernels_in(listing, "layer256_kernel")}
+    return {k: check(listing, '^' + re.escape(k) + ':') for k in kernels_in(listing, "layer256_")}
 
 
 if __name__ == '__main__':

@@ -294,3 +294,29 @@ def test_call_order_and_limits(B):
         ev.set_profile(t, x)
     assert e.value.status == B.DC_ERR_BAD_GRAPH
     ev.close()
+
+
+def test_one_slot_layers_by_dma_equal_the_register_path(B, monkeypatch):
+    """The fused-op batches run the layer kernel with one gather slot; by default its data-moving waves
+    copy the neighbour rows into LDS by DMA.  A context created under DC_U1_DMA=0 gathers through
+    registers instead: the same values reach the same LDS places, so the results agree bit for bit."""
+    w = positive(wl.make("cfg4", 24))
+    t, x = wl.profile_of(w)
+
+    def run():
+        ev = B.evaluator_for(w)
+        ev.set_profile(t, x)
+        cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+        cost = ev.cost_candidates(cg, co, gid, 0.02, 0.01).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        counts = ev.last_fused_ops()
+        ev.close()
+        return cost, counts
+
+    dma, counts = run()
+    monkeypatch.setenv("DC_U1_DMA", "0")
+    reg, counts2 = run()
+    monkeypatch.delenv("DC_U1_DMA")
+    assert counts == counts2 and counts[0] > 1000
+    assert np.isfinite(dma).all()
+    assert np.array_equal(dma, reg), np.abs(dma - reg).max()

@@ -51,6 +51,6 @@ def test_checker_flags_a_copy_of_a_register_whose_load_is_in_flight(tmp_path):
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
 def test_no_instruction_touches_a_load_in_flight_in_the_layer_kernels():
     res = isa_check.check_layer256()
-    assert len(res) >= 6                      # input widths 256 / 64, gather and plain product, 3 and 1 slots
+    assert len(res) >= 8                      # input widths 256 / 64: gather with 3 and 1 slots, plain product, one-slot DMA
     for kernel, hazards in res.items():
         assert hazards == [], (kernel, hazards[:3])
