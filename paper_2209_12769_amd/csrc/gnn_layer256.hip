@@ -120,10 +120,14 @@ __device__ __forceinline__ void wait_vm() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
-// s_waitcnt vmcnt(4 * n4), n4 in 0..3 (wave-uniform), as one statement: separate wait sites in
+// s_waitcnt vmcnt(4 * n4), n4 in 0..5 (wave-uniform), as one statement: separate wait sites in
 // an if/else around the tile epilogue made the register allocator spill.
 __device__ __forceinline__ void wait_vm_times4(int n4) {
   asm volatile(
+      "s_cmp_eq_u32 %0, 5\n\t"
+      "s_cbranch_scc1 .Ldc_w20_%=\n\t"
+      "s_cmp_eq_u32 %0, 4\n\t"
+      "s_cbranch_scc1 .Ldc_w16_%=\n\t"
       "s_cmp_eq_u32 %0, 3\n\t"
       "s_cbranch_scc1 .Ldc_w12_%=\n\t"
       "s_cmp_eq_u32 %0, 2\n\t"
@@ -139,7 +143,13 @@ __device__ __forceinline__ void wait_vm_times4(int n4) {
       "s_waitcnt vmcnt(8)\n\t"
       "s_branch .Ldc_wend_%=\n"
       ".Ldc_w12_%=:\n\t"
-      "s_waitcnt vmcnt(12)\n"
+      "s_waitcnt vmcnt(12)\n\t"
+      "s_branch .Ldc_wend_%=\n"
+      ".Ldc_w16_%=:\n\t"
+      "s_waitcnt vmcnt(16)\n\t"
+      "s_branch .Ldc_wend_%=\n"
+      ".Ldc_w20_%=:\n\t"
+      "s_waitcnt vmcnt(20)\n"
       ".Ldc_wend_%=:"
       :
       : "s"(n4)
@@ -351,11 +361,13 @@ struct MfmaConst {
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
 
-template <int DCH, bool DENSE, bool PF = false>
+// PF: the LDS fragments of the next 16 columns are requested ahead of the products.  NODMA: the
+// data-moving waves issue (and wait for) all DMA requests; this wave only multiplies and stores.
+template <int DCH, bool DENSE, bool PF = false, bool NODMA = false>
 __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], const MfmaConst c) {
   constexpr int NK = Shape<DCH, DENSE>::NK;
   int n_req = 0;                            // requests of this step, in fours
-  if (s + 2 >= 0) {
+  if (!NODMA && s + 2 >= 0) {
     const int J = s + 2;
     const int ti = J / NK, kc = J - ti * NK;
     if (J < S && kc < DCH) {
@@ -444,7 +456,7 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   // A pieces): everything requested one step ago, which job s+1 needs, is in LDS.  Loads
   // complete in issue order, so this holds whatever stores of an earlier tile are still
   // on their way; placed before the tile's stores so that it never waits for those.
-  wait_vm_times4(__builtin_amdgcn_readfirstlane(n_req));
+  if constexpr (!NODMA) wait_vm_times4(__builtin_amdgcn_readfirstlane(n_req));
   const bool tile_end = s >= 0 && (s % NK) == NK - 1;
   if (tile_end) {
     // ---- tile finished.  First bias and ReLU in place, one group of 32 columns at a time,
@@ -696,7 +708,7 @@ __global__ __launch_bounds__(kNT) void layer256_dma1_kernel(
     mc.wave = __builtin_amdgcn_readfirstlane(role_wave);
     __syncthreads();                          // step -3
     for (int s = -2; s < S; ++s) {
-      mfma_step<DCH, false, true>(s, S, acc, mc);
+      mfma_step<DCH, false, true, true>(s, S, acc, mc);
       __syncthreads();
     }
   } else {
@@ -744,6 +756,29 @@ __global__ __launch_bounds__(kNT) void layer256_dma1_kernel(
           DC_ADOPT()
           DC_REQUEST(min(ti + 1, nt_wg - 1))
           n4 += 2;
+        }
+        // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run, eight 1 KB pieces per
+        // wave.  With at most three chunks in all, chunk k always lands in ring slot k: the ring then
+        // holds the whole of W and only the first tile loads it.
+        if (NK > 3 || J < NK) {
+          const char* wsrc = reinterpret_cast<const char*>(Wp) + (size_t)kc * kBBytes + (size_t)mwave * 8192u + lane * 16;
+          const unsigned wring = lds0 + kBOff + (unsigned)(NK > 3 ? J % 3 : kc) * kBBytes + (unsigned)mwave * 8192u;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) load16_to_lds(wsrc + i * 1024, wring + i * 1024u);
+          n4 += 2;
+        }
+        if (kc < DCH) {
+          // the node's own rows: rows past the end are clamped to the last row (read, never stored)
+          const int m0 = (tile0 + ti * per) * kBM;
+          const unsigned ring = lds0 + (unsigned)(J % 3) * kABytes + (unsigned)mwave * 4096u;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int r = r0l + 8 * i;
+            const int col = (lane & 7) ^ ((r >> 1) & 7);
+            const int row = min(m0 + r, ntot - 1);
+            load16_to_lds(hb + (size_t)row * kRowB + kc * kARow + col * 16, ring + i * 1024u);
+          }
+          n4 += 1;
         }
         if (kc >= DCH) {
           const bool succ = kc / DCH == 2;
