@@ -189,11 +189,11 @@ def cost_bench(args, w, B, torch):
         peak = PEAK_MFMA_TFLOPS[m.dtype]
         ach = kernels[dom]["TFLOP/s"]
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": round(ach / peak, 4), "traffic": None}
+                "frac": round(ach / peak, 4), "traffic": read_traffic(w.name + "_cost", dom)}
     else:
         ach = kernels[dom].get("GB/s", 0.0)
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": read_traffic(w.name + "_cost", dom)}
     roof["avg_launch_ms"] = round(kernels[dom]["ms_per_step"] / max(kernels[dom]["launches_per_step"], 1), 4)
     out = {"metric": "fusion candidates costed/sec (contraction + estimator on every fused op + list scheduling) "
                      "on 1 MI355X",
