@@ -473,3 +473,34 @@ def test_eval_is_capturable_in_a_hip_graph_and_replays_identically(B):
         assert torch.equal(again, eager)
     assert ev.check() == B.DC_OK
     ev.close()
+
+
+def test_two_contexts_on_two_streams_equal_one_context(B):
+    """Contexts share no state: two halves of a batch, each in a context of its own and on a
+    stream of its own so that their kernels overlap on the device, give the numbers of the
+    whole batch in one context, bit for bit, step after step."""
+    import torch
+    w = wl.make("cfg3", 128)
+    whole = B.evaluator_for(w)
+    cg, co, gid = whole.to_device(w.cand_graph), whole.to_device(w.cand_off), whole.to_device(w.group_id)
+    want = whole.eval_candidates(cg, co, gid).clone()
+    torch.cuda.synchronize()
+    assert whole.check() == B.DC_OK
+    halves = [w.subset(range(0, 64)), w.subset(range(64, 128))]
+    evs = [B.evaluator_for(h) for h in halves]
+    args = [(e.to_device(h.cand_graph), e.to_device(h.cand_off), e.to_device(h.group_id),
+             torch.empty(h.n_cand, dtype=torch.float32, device=e.device)) for e, h in zip(evs, halves)]
+    streams = [torch.cuda.Stream(device=whole.device) for _ in halves]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for e, a, s in zip(evs, args, streams):
+            a[3].zero_()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                e.eval_candidates(*a)
+        torch.cuda.synchronize()
+        assert torch.equal(torch.cat([a[3] for a in args]), want), f"step {rep}"
+    for e in evs:
+        assert e.check() == B.DC_OK
+        e.close()
+    whole.close()
