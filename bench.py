@@ -82,20 +82,58 @@ def read_traffic(workload, kernel):
     return None
 
 
-def cpu_baseline(w, seconds_target=15.0):
+def host_cores():
+    """Threads the oracle may use: the host's CPU count, capped by the share the environment grants
+    (OMP_NUM_THREADS is set to the machine's CPU share on the GPU machines)."""
+    n = os.cpu_count() or 1
+    try:
+        n = min(n, len(os.sched_getaffinity(0)))
+    except (AttributeError, OSError):
+        pass
+    cap = os.environ.get("OMP_NUM_THREADS", "")
+    if cap.isdigit() and int(cap) > 0:
+        n = min(n, int(cap))
+    return max(1, n)
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, seconds_target=8.0):
+    """The oracle (contract + forward) timed on this host: one instance on one core, then one
+    independent single-threaded instance per core on disjoint candidate slices (measured aggregate).
+    Both on evenly spaced samples of the workload's candidates, sized for about `seconds_target`
+    seconds of wall time each."""
     from oracle import oracle as orc
     probe = w.subset([0])
     t0 = time.perf_counter()
     orc.evaluate(probe)
     per = max(time.perf_counter() - t0, 1e-4)
-    n = int(max(1, min(w.n_cand, seconds_target / per)))
-    idx = np.linspace(0, w.n_cand - 1, n).astype(np.int64)
-    sub = w.subset(idx)
+    n1 = int(max(1, min(w.n_cand, seconds_target / per)))
+    idx = np.linspace(0, w.n_cand - 1, n1).astype(np.int64)
     t0 = time.perf_counter()
-    orc.evaluate(sub)
-    dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n} of {w.n_cand} candidates of {w.name}, evenly spaced, contract+forward, {dt:.1f} s"}
+    orc.evaluate(w.subset(idx))
+    dt1 = time.perf_counter() - t0
+    cores = host_cores()
+    nc = int(max(cores, min(w.n_cand, cores * seconds_target / per)))
+    nc = min(nc, w.n_cand)
+    idx = np.unique(np.linspace(0, w.n_cand - 1, nc).astype(np.int64))
+    t0 = time.perf_counter()
+    orc.evaluate_parallel(w, False, cores, idx)
+    dtc = time.perf_counter() - t0
+    return {"value": len(idx) / dtc, "unit": "candidates/s", "cores": min(cores, len(idx)), "kind": "oracle",
+            "sample": f"{len(idx)} of {w.n_cand} candidates of {w.name}, evenly spaced, contract+forward, one "
+                      f"single-threaded oracle instance per core on disjoint slices, {dtc:.1f} s wall",
+            "single_core": {"value": n1 / dt1, "cores": 1,
+                            "sample": f"{n1} candidates, one instance, {dt1:.1f} s"},
+            "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
 
 
 def simulate_bench(args, w, B, torch):

@@ -325,7 +325,8 @@ dc_status dc_fused_op_batch(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gra
 
 /* Forward pass, loss and its gradient over one batch of sample graphs (any dc_batch: the
  * output of dc_fused_op_batch or of dc_contract_graphs).  All pointers device memory.
- *   target  [in->n_cand] profiled times, > 0
+ *   target  [in->n_cand] profiled times, positive and finite; any other value makes the call a
+ *           no-op (no loss, no gradient, no update) that dc_check reports as DC_ERR_INVALID_ARG
  *   loss    [1]
  *   pred    [in->n_cand] raw estimates y_g, or null
  *   grad    [dc_num_params] in the order of dc_num_params, or null
@@ -355,6 +356,18 @@ dc_status dc_check(dc_ctx* ctx, void* stream);
 /* After a synchronised dc_contract_graphs / dc_eval_candidates: totals of the last
  * contraction (contracted nodes, contracted edges).  Synchronises `stream`.        */
 dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* stream);
+
+/* Chooses between kernels that compute the same layer: a diagnostic switch for tests and
+ * measurements, never needed to obtain a result.  `which` is a sum of
+ *   DC_KERNELS_SEPARATE_LAYERS     neighbour means and node update as two kernels per layer with the
+ *                                  means written to memory, instead of the fused layer kernels
+ *   DC_KERNELS_ONE_SLOT_REGISTERS  the one-slot layer kernel (fused-op batches) gathers through
+ *                                  registers instead of by direct copies into LDS
+ *   DC_KERNELS_LAYER_8_WAVES       the bulk layer (H = 256, bf16) in its eight-wave form instead of
+ *                                  the sixteen-wave form
+ * 0 restores the defaults.  Takes effect from the next call on this context; host state only.  */
+enum { DC_KERNELS_SEPARATE_LAYERS = 1, DC_KERNELS_ONE_SLOT_REGISTERS = 2, DC_KERNELS_LAYER_8_WAVES = 4 };
+dc_status dc_select_kernels(dc_ctx* ctx, int32_t which);
 
 /* Human-readable detail of the last error on this context; owned by the context. */
 const char* dc_last_error(const dc_ctx* ctx);

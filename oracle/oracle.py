@@ -3,6 +3,11 @@
 Loads oracle/dc_oracle.cpp, compiled with g++ into oracle/_build/.  Nothing in
 the product package imports this module; it knows nothing of the HIP library.
 Only argument marshalling happens here: every number comes out of the C++.
+
+Every function computes the definition: fp32 storage, fp64 accumulation, one rounding.  The
+optional argument `bf16=True` additionally rounds features, activations, neighbour means and
+matrices to bf16 where a bf16 device path stores them; it is a diagnostic second mode that a test
+has to ask for, never the default.
 """
 from __future__ import annotations
 
@@ -16,7 +21,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dc_oracle.cpp")
-_SO = os.path.join(_HERE, "_build", "libdc_oracle.so")
+# DC_ORACLE_SANITIZE=1 in the environment selects a build with the address and undefined-behaviour
+# sanitizers (host code only); the process must then run with the sanitizer runtime preloaded.
+_SANITIZE = os.environ.get("DC_ORACLE_SANITIZE", "") == "1"
+_SO = os.path.join(_HERE, "_build", "libdc_oracle_san.so" if _SANITIZE else "libdc_oracle.so")
 _lib = None
 
 
@@ -24,7 +32,9 @@ def build(force: bool = True) -> str:
     if not force and os.path.exists(_SO) and os.path.getmtime(_SO) >= os.path.getmtime(_SRC):
         return _SO
     os.makedirs(os.path.dirname(_SO), exist_ok=True)
-    subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", _SO, _SRC])
+    flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+        if _SANITIZE else ["-O2"]
+    subprocess.check_call(["g++", *flags, "-std=c++17", "-shared", "-fPIC", "-o", _SO, _SRC])
     return _SO
 
 
@@ -76,11 +86,10 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
     return y
 
 
-def contract(w, bf16: Optional[bool] = None) -> Batch:
+def contract(w, bf16: bool = False) -> Batch:
     """Contracts all candidates of workload `w` (a workloads.Workload)."""
     lib = _load()
-    if bf16 is None:
-        bf16 = w.model.dtype == "bf16"
+    bf16 = bool(bf16)
     F = w.model.F
     gno, geo = w.g_node_off(), w.g_edge_off()
     rowptr, col, X = w.cat_rowptr(), w.cat_col(), w.cat_X()
@@ -111,11 +120,10 @@ def contract(w, bf16: Optional[bool] = None) -> Batch:
                  Xc[:nt], cnt[:nt])
 
 
-def gnn_forward(b: Batch, model, weights, bf16: Optional[bool] = None, want_hidden: bool = False):
+def gnn_forward(b: Batch, model, weights, bf16: bool = False, want_hidden: bool = False):
     """Predicted time per candidate; with want_hidden also (h_last, readout)."""
     lib = _load()
-    if bf16 is None:
-        bf16 = model.dtype == "bf16"
+    bf16 = bool(bf16)
     pred = np.zeros(b.n_cand, np.float32)
     h_last = np.zeros((max(b.ntot, 1), model.H), np.float32) if want_hidden else None
     ro = np.zeros((max(b.n_cand, 1), model.H), np.float32) if want_hidden else None
@@ -151,13 +159,12 @@ def simulate(b: Batch, op_time: np.ndarray, ar_size: np.ndarray, ar_c: float, ar
     return cost
 
 
-def fused_ops(w, b: Batch, ar_size_base: np.ndarray, bf16: Optional[bool] = None):
+def fused_ops(w, b: Batch, ar_size_base: np.ndarray, bf16: bool = False):
     """The fused ops (groups of two or more computation ops) of every candidate of `w`, each
     as the subgraph of its members: returns (batch with one graph per fused op, contracted
     node of each fused op, base node of each row).  `b` is contract(w)."""
     lib = _load()
-    if bf16 is None:
-        bf16 = w.model.dtype == "bf16"
+    bf16 = bool(bf16)
     F = w.model.F
     gno, geo = w.g_node_off(), w.g_edge_off()
     rowptr, col, X = w.cat_rowptr(), w.cat_col(), w.cat_X()
@@ -190,7 +197,7 @@ def fused_ops(w, b: Batch, ar_size_base: np.ndarray, bf16: Optional[bool] = None
     return fo, cnode[:K], member[:nt]
 
 
-def module_times(w, b: Batch, op_time_base: np.ndarray, ar_size_base: np.ndarray, bf16: Optional[bool] = None,
+def module_times(w, b: Batch, op_time_base: np.ndarray, ar_size_base: np.ndarray, bf16: bool = False,
                  want_fused: bool = False):
     """Per node of the contracted batch `b` = contract(w): execution time (profiled for single
     ops, estimated for fused ops, clamped at zero) and all-reduce tensor size (sum over the
@@ -216,13 +223,28 @@ def module_times(w, b: Batch, op_time_base: np.ndarray, ar_size_base: np.ndarray
 
 
 def cost(w, op_time_base: np.ndarray, ar_size_base: np.ndarray, ar_c: float, ar_d: float,
-         bf16: Optional[bool] = None) -> np.ndarray:
+         bf16: bool = False) -> np.ndarray:
     """Cost(H) per candidate: contraction, times of all nodes of the module, list scheduling."""
     b = contract(w, bf16)
     op_time, ar_size = module_times(w, b, op_time_base, ar_size_base, bf16)
     return simulate(b, op_time, ar_size, ar_c, ar_d)
 
 
-def evaluate(w, bf16: Optional[bool] = None) -> np.ndarray:
+def evaluate(w, bf16: bool = False) -> np.ndarray:
     """contract + forward: one predicted time per candidate of workload w."""
     return gnn_forward(contract(w, bf16), w.model, w.weights, bf16)
+
+
+def evaluate_parallel(w, bf16: bool = False, threads: Optional[int] = None, idx=None) -> np.ndarray:
+    """contract + forward with one independent, single-threaded oracle instance per thread, each on
+    its own disjoint slice of the candidates (`idx`: the candidates wanted, default all).  The
+    instances share nothing but the read-only inputs; the C++ runs outside the interpreter lock."""
+    from concurrent.futures import ThreadPoolExecutor
+    idx = np.arange(w.n_cand) if idx is None else np.asarray(idx, dtype=np.int64)
+    if idx.size == 0:
+        return np.zeros(0, np.float32)
+    threads = max(1, min(int(threads or os.cpu_count() or 1), idx.size))
+    parts = [p for p in np.array_split(idx, threads) if p.size]
+    with ThreadPoolExecutor(len(parts)) as ex:
+        outs = list(ex.map(lambda p: evaluate(w.subset(p), bf16), parts))
+    return np.concatenate(outs)

@@ -29,6 +29,7 @@ DC_F32 = 0
 DC_BF16 = 1
 DC_AGG_MEAN = 0
 DC_AGG_ATTENTION = 1
+DC_KERNELS_SEPARATE_LAYERS, DC_KERNELS_ONE_SLOT_REGISTERS, DC_KERNELS_LAYER_8_WAVES = 1, 2, 4
 STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "DC_ERR_BAD_PARTITION",
                 4: "DC_ERR_CAPACITY", 5: "DC_ERR_OOM", 6: "DC_ERR_HIP", 7: "DC_ERR_UNSUPPORTED"}
 
@@ -108,6 +109,7 @@ def lib():
         L.dc_train_step.argtypes = [vp, C.POINTER(DcBatch), vp, vp, vp]
         L.dc_get_weights.argtypes = [vp, vp, vp, vp, vp]
         L.dc_check.argtypes = [vp, vp]
+        L.dc_select_kernels.argtypes = [vp, i32]
         L.dc_last_totals.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
         L.dc_last_error.argtypes = [vp]
         L.dc_last_error.restype = C.c_char_p
@@ -116,7 +118,7 @@ def lib():
         for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
                   "dc_gnn_forward", "dc_eval_candidates", "dc_simulate", "dc_check", "dc_last_totals", "dc_profile_begin",
                   "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops", "dc_search",
-                  "dc_train_begin", "dc_fused_op_batch", "dc_loss_gradients", "dc_train_step", "dc_get_weights"):
+                  "dc_train_begin", "dc_select_kernels", "dc_fused_op_batch", "dc_loss_gradients", "dc_train_step", "dc_get_weights"):
             getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -223,6 +225,10 @@ def dc_get_weights(ctx, W_layers: np.ndarray, b_layers: np.ndarray, head: np.nda
 
 def dc_check(ctx, stream: int = 0) -> int:
     return lib().dc_check(ctx, stream)
+
+
+def dc_select_kernels(ctx, which: int) -> int:
+    return lib().dc_select_kernels(ctx, which)
 
 
 def dc_last_totals(ctx, stream: int = 0) -> Tuple[int, int, int]:
@@ -445,6 +451,11 @@ class Evaluator:
 
     def check(self) -> int:
         return dc_check(self.ctx, self._stream())
+
+    def select_kernels(self, which: int) -> None:
+        st = dc_select_kernels(self.ctx, which)
+        if st != DC_OK:
+            raise DiscoError(st, "dc_select_kernels")
 
     def last_totals(self) -> Tuple[int, int]:
         st, n, e = dc_last_totals(self.ctx, self._stream())

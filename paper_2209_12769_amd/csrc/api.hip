@@ -77,6 +77,7 @@ struct dc_ctx {
   std::vector<int> h_gno, h_geo;   // host copies of the base graphs' offsets
   int allow_fused = 1;
   int u1_dma = 1;
+  int layer_v1 = 0;
   // training (dc_train_begin)
   bool training = false;
   dc_train_params tp{};
@@ -281,6 +282,7 @@ GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) 
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;
   g.allow_fused = ctx->allow_fused;
+  g.layer_v1 = ctx->layer_v1;
   g.zero_row = ctx->u1_dma ? ctx->zero_row : nullptr;
   if (ctx->cfg.aggregator == DC_AGG_ATTENTION) {
     g.heads = ctx->cfg.heads;
@@ -432,12 +434,6 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
   dc_ctx* ctx = new (std::nothrow) dc_ctx();
   if (!ctx) return DC_ERR_OOM;
   ctx->cfg = *cfg;
-  {
-    const char* env = getenv("DC_DISABLE_FUSED");   // debugging aid: run the unfused layer kernels
-    ctx->allow_fused = !(env && env[0] == '1');
-    env = getenv("DC_U1_DMA");                           // 0: one-slot layers gather through registers, not by DMA
-    ctx->u1_dma = !(env && env[0] == '0');
-  }
   hipError_t e = hipGetDevice(&ctx->device);
   if (e != hipSuccess) {
     delete ctx;
@@ -1247,6 +1243,14 @@ dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* 
   if (e != hipSuccess) return hip_fail(ctx, e, "dc_last_totals");
   *n_nodes = ctx->h_pinned[8];
   *n_edges = ctx->h_pinned[9];
+  return DC_OK;
+}
+
+dc_status dc_select_kernels(dc_ctx* ctx, int32_t which) {
+  if (!ctx || which < 0 || which > 7) return DC_ERR_INVALID_ARG;
+  ctx->allow_fused = !(which & DC_KERNELS_SEPARATE_LAYERS);
+  ctx->u1_dma = !(which & DC_KERNELS_ONE_SLOT_REGISTERS);
+  ctx->layer_v1 = (which & DC_KERNELS_LAYER_8_WAVES) != 0;
   return DC_OK;
 }
 

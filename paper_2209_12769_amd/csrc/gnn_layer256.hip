@@ -957,7 +957,7 @@ hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const f
   if (prof) prof->begin(DCH == 4 ? kFamLayer256 : kFamLayer64, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
   if constexpr (U == 1) {
-    // one slot: the rows go to LDS by DMA (a context created under DC_U1_DMA=0 passes no zero row and
+    // one slot: the rows go to LDS by DMA (a context switched to the register path passes no zero row and
     // keeps the register path)
     static bool dma_attr = false, dma_ok = false;
     auto kdma = layer256_dma1_kernel<DCH>;

@@ -58,18 +58,25 @@ __global__ __launch_bounds__(256) void loss_kernel(const float* __restrict__ Z2,
                                                    const float* __restrict__ target, int B, float floor_,
                                                    float* __restrict__ y, float* __restrict__ dy,
                                                    double* __restrict__ lterm, float* __restrict__ pred,
-                                                   const int* __restrict__ status) {
+                                                   int* __restrict__ status) {
   if (status[0] != 0) return;
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
   for (int g = blockIdx.x * wpb + (threadIdx.x >> 6); g < B; g += gridDim.x * wpb) {
+    // a profiled time is positive and finite: anything else has no logarithm, and the call is refused
+    // (every later kernel of the call sees the status word and leaves its outputs alone)
+    const float tg = target[g];
+    if (!(tg > 0.f) || tg > 3.0e38f) {
+      if (lane == 0) set_error(status, DC_ERR_INVALID_ARG);
+      continue;
+    }
     double s = 0.0;
     for (int j = lane; j < H; j += 64) s += (double)Z2[(size_t)g * H + j] * (double)w3b3[j];
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
     if (lane == 0) {
       const float yf = (float)(s + (double)w3b3[H]);
       const double yc = yf > floor_ ? (double)yf : (double)floor_;
-      const double dl = log(yc) - log((double)target[g]);
+      const double dl = log(yc) - log((double)tg);
       y[g] = yf;
       if (pred) pred[g] = yf;
       lterm[g] = dl * dl;

@@ -8,7 +8,19 @@ from paper_2209_12769_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2}     # against the plain oracle (fp32 storage, fp64 accumulation)
+MIRROR_TOL = 6e-3                      # bf16 path against the oracle with the same bf16 storage points
+
+
+def check(got, w, tag):
+    want = orc.evaluate(w)
+    err = rel_err(got, want)
+    print(f"[attention] {tag} max rel err vs plain oracle {err.max():.3e}", flush=True)
+    assert err.max() <= TOL[w.model.dtype]
+    if w.model.dtype == "bf16":
+        err = rel_err(got, orc.evaluate(w, bf16=True))
+        print(f"[attention] {tag} max rel err vs oracle with bf16 storage points {err.max():.3e}", flush=True)
+        assert err.max() <= MIRROR_TOL
 
 
 @pytest.fixture(scope="module")
@@ -46,11 +58,7 @@ def test_small_batches_every_width(B, dtype, F, H, L, K):
     g = wl.random_dag(7, 300, 0.02, F)
     labs = wl.random_labels(8, g.n, 90, C=7)
     w = wl.custom(f"att-{dtype}-{F}-{H}-{L}-{K}", wl.ModelSpec(F, H, L, dtype, "attention", K), [g], [labs], seed=3)
-    got = run(B, w)
-    want = orc.evaluate(w)
-    err = rel_err(got, want)
-    print(f"[attention] {w.name} max rel err {err.max():.3e}", flush=True)
-    assert err.max() <= TOL[dtype]
+    check(run(B, w), w, w.name)
 
 
 def test_long_neighbour_lists_and_two_cycles(B):
@@ -77,11 +85,7 @@ def test_zero_attention_vectors_equal_uniform_coefficients(B):
 @pytest.mark.parametrize("name,n,heads", [("cfg1", 3, 4), ("cfg2", 64, 4), ("cfg3", 48, 8), ("cfg4", 12, 4)])
 def test_configurations_with_attention(B, name, n, heads):
     w = wl.with_attention(wl.make(name, n), heads)
-    got = run(B, w)
-    want = orc.evaluate(w)
-    err = rel_err(got, want)
-    print(f"[attention] {w.name} C={w.n_cand} max rel err {err.max():.3e}", flush=True)
-    assert err.max() <= TOL[w.model.dtype]
+    check(run(B, w), w, f"{w.name} C={w.n_cand}")
 
 
 def test_config_errors(B):

@@ -3,8 +3,9 @@ the C ABI: times and tensor sizes of every node of the candidate modules (dc_mod
 the end-to-end time (dc_cost_candidates).
 
 Tensor sizes, profiled times and the classification of every node are exact; the estimate of a
-fused op is floating point (rel 1e-5 fp32, 2e-2 bf16, measured against max(|estimate|, 1e-3 of
-the median estimate)).  The schedule's order does not depend on the durations, so the cost is a
+fused op is floating point (rel 1e-5 fp32, 2e-2 bf16 against the plain oracle -- fp32 storage,
+fp64 accumulation -- measured against max(|estimate|, 1e-3 of the median estimate); the bf16 path
+is held to a tighter bound against the oracle run with the device's bf16 storage points).  The schedule's order does not depend on the durations, so the cost is a
 fixed max-plus expression of them and inherits their relative tolerance."""
 import numpy as np
 import pytest
@@ -14,7 +15,9 @@ from paper_2209_12769_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2}     # against the plain oracle
+MIRROR_TOL = 1e-2                      # bf16 path against the oracle with bf16 storage points (the device also rounds
+                                       # the per-fused-op sums and the regression network's hidden layers to bf16)
 
 
 @pytest.fixture(scope="module")
@@ -82,6 +85,11 @@ def check_times(w, got_t, got_x, ref_b, t, x):
         scale = np.maximum(np.abs(fo_pred), floor)
         err = np.abs(got_t[cnode] - want_t[cnode]) / scale
         assert err.max() <= TOL[w.model.dtype], (w.name, err.max(), int(err.argmax()))
+        if w.model.dtype == "bf16":
+            mir_t = orc.module_times(w, ref_b, t, x, bf16=True)[0]
+            merr = np.abs(got_t[cnode] - mir_t[cnode]) / scale
+            print(f"[module_times] {w.name} max rel err vs oracle with bf16 storage points {merr.max():.2e}", flush=True)
+            assert merr.max() <= MIRROR_TOL, (w.name, merr.max())
         return float(err.max()), fo, fo_pred
     return 0.0, fo, fo_pred
 
@@ -112,6 +120,9 @@ def test_cost_of_the_configurations(B, name, n):
         assert np.all(np.isfinite(want)) and np.all(np.isfinite(got))
         err = np.abs(got - want) / np.abs(want)
         assert err.max() <= TOL[w.model.dtype], (name, c, d, err.max())
+        if w.model.dtype == "bf16":
+            mir = orc.cost(w, t, x, c, d, bf16=True)
+            assert np.max(np.abs(got - mir) / np.abs(mir)) <= MIRROR_TOL
     print(f"[cost] {name} C={n}: cost {want.min():.3f} .. {want.max():.3f}, max rel err {err.max():.2e}", flush=True)
 
 
@@ -296,15 +307,16 @@ def test_call_order_and_limits(B):
     ev.close()
 
 
-def test_one_slot_layers_by_dma_equal_the_register_path(B, monkeypatch):
+def test_one_slot_layers_by_dma_equal_the_register_path(B):
     """The fused-op batches run the layer kernel with one gather slot; by default its data-moving waves
-    copy the neighbour rows into LDS by DMA.  A context created under DC_U1_DMA=0 gathers through
+    copy the neighbour rows into LDS by DMA.  dc_select_kernels can make a context gather through
     registers instead: the same values reach the same LDS places, so the results agree bit for bit."""
     w = positive(wl.make("cfg4", 24))
     t, x = wl.profile_of(w)
 
-    def run():
+    def run(which=0):
         ev = B.evaluator_for(w)
+        ev.select_kernels(which)
         ev.set_profile(t, x)
         cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
         cost = ev.cost_candidates(cg, co, gid, 0.02, 0.01).cpu().numpy()
@@ -314,9 +326,7 @@ def test_one_slot_layers_by_dma_equal_the_register_path(B, monkeypatch):
         return cost, counts
 
     dma, counts = run()
-    monkeypatch.setenv("DC_U1_DMA", "0")
-    reg, counts2 = run()
-    monkeypatch.delenv("DC_U1_DMA")
+    reg, counts2 = run(B.DC_KERNELS_ONE_SLOT_REGISTERS)
     assert counts == counts2 and counts[0] > 1000
     assert np.isfinite(dma).all()
     assert np.array_equal(dma, reg), np.abs(dma - reg).max()

@@ -1,7 +1,10 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by
 element on the same seeded inputs.  Contraction (ids, offsets, neighbour lists)
 must match bit for bit; predicted times within rel 1e-5 (fp32 path) or 2e-2
-(bf16 path, against the oracle with the same bf16 storage points)."""
+(bf16 path) of the oracle as it is defined: fp32 storage, fp64 accumulation, no bf16
+anywhere.  The bf16 path is held, in addition, to a tighter bound against the oracle run with
+the device's bf16 storage points (features, activations, means, matrices rounded to bf16)."""
+import os
 import numpy as np
 import pytest
 
@@ -10,7 +13,9 @@ from paper_2209_12769_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2}     # against the plain oracle (bf16=False): the binding bound
+MIRROR_TOL = 6e-3                      # bf16 path against the oracle with the same bf16 storage points
+THREADS = min(16, os.cpu_count() or 1)
 
 
 @pytest.fixture(scope="module")
@@ -71,7 +76,7 @@ def check_contraction(B, w, ev=None):
     print(f"[contract] {w.name} C={w.n_cand}", flush=True)
     ev, batch = gpu_contract(B, w, ev)
     assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
-    ref = orc.contract(w)
+    ref = orc.contract(w, w.model.dtype == "bf16")      # bf16 models: features rounded once, as the device stores them
     nt, et = ev.last_totals()
     assert (nt, et) == (ref.ntot, ref.etot)
     assert np.array_equal(batch.node_off.cpu().numpy(), ref.node_off)
@@ -86,6 +91,9 @@ def check_contraction(B, w, ev=None):
         # fp32 sums in ascending member order, one rounding: at most one bf16 step from the oracle
         assert np.all(np.abs(Xc - ref.Xc) <= np.abs(ref.Xc) * 2.0 ** -7 + 1e-30)
         assert np.mean(Xc == ref.Xc) > 0.999
+        # and against the unrounded sums: half a bf16 step plus the fp32 summation error
+        plain = orc.contract(w, False).Xc
+        assert np.all(np.abs(Xc - plain) <= np.abs(plain) * (2.0 ** -8 + 2.0 ** -20) + 1e-30)
     else:
         np.testing.assert_allclose(Xc, ref.Xc, rtol=2e-6, atol=0)
     return ev, batch, ref
@@ -94,17 +102,35 @@ def check_contraction(B, w, ev=None):
 def check_forward(B, w, ev, batch, ref, sample=None, cancelling=False):
     pred = ev.gnn_forward(batch).cpu().numpy()
     assert ev.check() == B.DC_OK
-    if sample is None:
-        want, _, readout = orc.gnn_forward(ref, w.model, w.weights, want_hidden=True)
-        got = pred
-    else:
-        sub = orc.contract(w.subset(sample))
-        want, _, readout = orc.gnn_forward(sub, w.model, w.weights, want_hidden=True)
-        got = pred[sample]
-    err = rel_err(got, want, last_dot_scale(w, readout) if cancelling else None)
-    print(f"[forward] {w.name} dtype={w.model.dtype} max rel err {err.max():.3e} (n={len(want)})", flush=True)
-    assert err.max() <= TOL[w.model.dtype], (err.max(), int(err.argmax()))
+    idx = np.arange(w.n_cand) if sample is None else np.asarray(sample)
+    check_predictions(w, pred[idx], idx, cancelling)
     return pred
+
+
+def check_predictions(w, got, idx, cancelling=False, tag="forward"):
+    """`got` = device predictions of candidates `idx` of workload `w`."""
+    scale = None
+    if cancelling:
+        sub = orc.contract(w.subset(idx), False)
+        want, _, readout = orc.gnn_forward(sub, w.model, w.weights, False, want_hidden=True)
+        scale = last_dot_scale(w, readout)
+    else:
+        want = orc.evaluate_parallel(w, False, THREADS, idx)
+    err = rel_err(got, want, scale)
+    print(f"[{tag}] {w.name} dtype={w.model.dtype} max rel err vs plain oracle {err.max():.3e} (n={len(want)})",
+          flush=True)
+    assert err.max() <= TOL[w.model.dtype], (err.max(), int(err.argmax()))
+    if w.model.dtype == "bf16":
+        mirrored = orc.evaluate_parallel(w, True, THREADS, idx)
+        err = rel_err(got, mirrored)
+        print(f"[{tag}] {w.name} max rel err vs oracle with bf16 storage points {err.max():.3e}", flush=True)
+        assert err.max() <= MIRROR_TOL, (err.max(), int(err.argmax()))
+
+
+def stratified(w, n):
+    """n candidates spread evenly over the candidates ordered by the size of their base graph."""
+    order = np.argsort([w.graphs[b].n for b in w.cand_graph], kind="stable")
+    return sorted({int(order[i]) for i in np.linspace(0, w.n_cand - 1, n).astype(int)})
 
 
 # ---------------------------------------------------------------------------
@@ -129,8 +155,7 @@ def test_cfg5_heterogeneous_graphs_lds_and_global_paths(B):
     sizes = sorted(g.n for g in w.graphs)
     print("cfg5 graph sizes", sizes, flush=True)
     ev, batch, ref = check_contraction(B, w)
-    idx = [int(i) for i in np.argsort([w.graphs[b].n for b in w.cand_graph])[[0, 1, w.n_cand // 2, -1]]]
-    check_forward(B, w, ev, batch, ref, sample=idx)
+    check_forward(B, w, ev, batch, ref)
     ev.close()
 
 
@@ -174,17 +199,25 @@ def test_every_list_length_class_of_the_contraction(B):
     ev.close()
 
 
-@pytest.mark.timeout(300)
-@pytest.mark.parametrize("name,n_forward", [("cfg3", 8), ("cfg4", 0), ("cfg5", 3)])
-def test_full_size_contraction_of_every_candidate(B, name, n_forward):
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_full_size_contraction_of_every_candidate(B, name):
     # the configurations at their full candidate counts (1024, 4096, 8192 over 64 base graphs):
-    # every array of the contraction bit for bit, predictions on a few candidates
+    # every array of the contraction bit for bit; predictions on every candidate of cfg3, on 64
+    # candidates spread over the batch for cfg4 and on one candidate per base graph for cfg5
     w = wl.make(name, None)
     ev, batch, ref = check_contraction(B, w)
-    if n_forward:
-        order = np.argsort([w.graphs[b].n for b in w.cand_graph], kind="stable")
-        idx = sorted({int(order[i]) for i in np.linspace(0, w.n_cand - 1, n_forward).astype(int)})
-        check_forward(B, w, ev, batch, ref, sample=idx)
+    if name == "cfg3":
+        idx = None
+    elif name == "cfg4":
+        idx = stratified(w, 64)
+    else:
+        first = {}
+        for c, b in enumerate(w.cand_graph):
+            first.setdefault(int(b), c)
+        idx = sorted(first.values())
+        assert len(idx) == len(w.graphs)
+    check_forward(B, w, ev, batch, ref, sample=idx)
     ev.close()
 
 
@@ -201,13 +234,11 @@ def test_full_size_bulk_batch_sampled_and_deterministic(B):
     assert np.array_equal(pred, again)
     assert np.isfinite(pred).all()
     ntot, etot = ev.last_totals()
-    sample = [0, 1, 1777, 2048, 4094, 4095]
-    sub = orc.contract(w.subset(sample), True)
-    want = orc.gnn_forward(sub, w.model, w.weights)
-    err = rel_err(pred[sample], want)
-    print(f"[full size] nodes {ntot} edges {etot} sampled max rel err {err.max():.3e}", flush=True)
-    assert err.max() <= TOL["bf16"]
+    sample = sorted(set(stratified(w, 64)) | {0, 1, 4094, 4095})
+    print(f"[full size] nodes {ntot} edges {etot}", flush=True)
+    check_predictions(w, pred[sample], sample, tag="full size")
     # contracted sizes of the sampled candidates add up as the oracle says
+    sub = orc.contract(w.subset(sample), False)
     assert int(sub.ntot) == sum(int(sub.node_off[i + 1] - sub.node_off[i]) for i in range(len(sample)))
     ev.close()
 
@@ -421,7 +452,7 @@ def test_unsorted_duplicate_base_edges_are_accepted(B):
     ev.close()
 
 
-def test_fused_layer_matches_the_separate_kernels_bit_for_bit(B, monkeypatch):
+def test_fused_layer_matches_the_separate_kernels_bit_for_bit(B):
     # same arithmetic in the same order: the fused layer and aggregate + update agree exactly
     for name, n in (("cfg4", 12), ("cfg3", 40)):
         w = wl.make(name, n)
@@ -430,13 +461,12 @@ def test_fused_layer_matches_the_separate_kernels_bit_for_bit(B, monkeypatch):
         fused = ev.eval_candidates(cg, co, gid).cpu().numpy()
         assert ev.check() == B.DC_OK
         ev.close()
-        monkeypatch.setenv("DC_DISABLE_FUSED", "1")
         ev2 = B.evaluator_for(w)
+        ev2.select_kernels(B.DC_KERNELS_SEPARATE_LAYERS)
         plain = ev2.eval_candidates(ev2.to_device(w.cand_graph), ev2.to_device(w.cand_off),
                                     ev2.to_device(w.group_id)).cpu().numpy()
         assert ev2.check() == B.DC_OK
         ev2.close()
-        monkeypatch.delenv("DC_DISABLE_FUSED")
         assert np.array_equal(fused, plain), (name, np.abs(fused - plain).max())
 
 
