@@ -956,6 +956,13 @@ hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const f
   if (prof) prof->end(s);
   if (prof) prof->begin(DCH == 4 ? kFamLayer256 : kFamLayer64, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
+  if constexpr (U == kU) {
+    if (!a.layer_v1) {
+      hipError_t e = launch_layer256w(h, 64 * DCH, a, Wl, bias, out, s);
+      if (prof) prof->end(s);
+      return e;
+    }
+  }
   if constexpr (U == 1) {
     // one slot: the rows go to LDS by DMA (a context switched to the register path passes no zero row and
     // keeps the register path)

@@ -1,0 +1,466 @@
+// Sixteen-wave form of the fused layer for output width H = 256 and input width d = 256 or 64,
+// bf16 (gfx950):
+//     h'[v] = ReLU([h[v] | mean_pred(h)[v] | mean_succ(h)[v]] W + b)
+// (neighbourhood encoding of Sec. 3.3.1 with uniform coefficients), both means formed on the
+// fly, so that a layer reads h once and writes h' once.
+//
+// One workgroup of 16 waves per CU; every SIMD hosts two waves of each kind, so that one wave's
+// waits are covered by its twin's work.
+//   Waves 0-7 multiply: each owns a 64 x 64 block of the 128 x 256 output tile (64 accumulator
+//   registers), reads its fragments from LDS, and requests the copies that need no arithmetic
+//   (the chunks of W and the node's own K chunks) from global memory straight into the LDS rings,
+//   two steps ahead.  They have no other loads, so their hand-placed waits count exactly these.
+//   Waves 8-15 form the means: a lane owns two (row, 16-byte column) items per K chunk of 64
+//   columns; it loads up to three neighbour pieces per item two steps ahead, adds them in fp32 in
+//   ascending neighbour order, scales by 1/deg, rounds to bf16 and writes the piece into the A
+//   ring.  These are ordinary loads that the compiler tracks: no register is touched while a
+//   load into it is in flight, and the waits are the compiler's.  The steps of a tile are
+//   unrolled, so chunk offsets, ring slots and the direction are constants of each step.
+// Rows with more than three neighbours take their mean from a pre-pass (one slot: the finished
+// mean), so that no lane walks a long list here.  All waves meet at one barrier per step that
+// waits for LDS traffic only: global loads stay in flight across it.
+#include "common.h"
+
+namespace dc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short u16;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kBM = 128, kBN = 256, kBK = 64;
+constexpr int kNT = 1024;
+constexpr int kMfmaWaves = 8;
+// LDS: a ring of three A chunks (128 rows x 64 columns, the 16-byte pieces of a row XOR-swizzled so
+// that fragment reads are conflict free and a 1 KB copy is eight whole rows), a ring of three
+// B chunks (64 k x 256 columns of W), one 32 x 32 staging block per multiplying wave.
+constexpr int kARow = kBK * 2;                       // 128 bytes
+constexpr int kABytes = kBM * kARow;                 // 16384
+constexpr int kBBytes = (kBK / 8) * kBN * 8 * 2;     // 32768
+constexpr int kBOff = 3 * kABytes;
+constexpr int kStageOff = kBOff + 3 * kBBytes;
+constexpr int kStageBytes = 32 * 32 * 2;             // 2048
+constexpr int kLdsTotal = kStageOff + kMfmaWaves * kStageBytes;
+static_assert(kLdsTotal <= 160 * 1024, "one workgroup per CU owns the whole LDS");
+
+template <int DCH>
+struct Shape {
+  static_assert(DCH == 4 || DCH == 1, "input widths 256 and 64");
+  static constexpr int D = 64 * DCH;
+  static constexpr int NK = 3 * DCH;                 // K chunks per tile: own, predecessors' mean, successors' mean
+  static constexpr unsigned ROWB = D * 2;            // bytes per row of h
+};
+
+// byte offset of 16-byte piece c (0..7) of row r in a swizzled 128-byte-row area
+__device__ __forceinline__ int swz(int r, int c) { return r * kARow + ((c ^ ((r >> 1) & 7)) << 4); }
+typedef __attribute__((address_space(3))) char lds_char;
+
+extern __shared__ __attribute__((aligned(16))) char dc_l256w_smem[];
+
+// Workgroup barrier that orders LDS traffic only: this wave's LDS reads have returned and its LDS
+// writes have landed, global loads and copies stay in flight.  One statement with a memory
+// clobber, so that the compiler moves no memory access across it, between two scheduling fences, so
+// that it moves no arithmetic across it either (the arithmetic of the next step, pulled up in front
+// of the barrier, would wait there for loads that were meant to stay in flight for a step).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// 16 bytes per lane from global memory straight into LDS (no registers): lane l of the wave
+// writes lds_base + 16 l.  Not tracked by the compiler; waited for with wait_copies().
+__device__ __forceinline__ void copy16_to_lds(const void* gaddr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "memory");
+}
+// s_waitcnt vmcnt(n), n in {0, 2, 4, 6} (wave-uniform): at most n newer vector-memory operations may
+// still be outstanding.  Loads return in issue order.
+__device__ __forceinline__ void wait_copies(int n) {
+  asm volatile(
+      "s_cmp_eq_u32 %0, 6\n\t"
+      "s_cbranch_scc1 .Ldcw_w6_%=\n\t"
+      "s_cmp_eq_u32 %0, 4\n\t"
+      "s_cbranch_scc1 .Ldcw_w4_%=\n\t"
+      "s_cmp_eq_u32 %0, 2\n\t"
+      "s_cbranch_scc1 .Ldcw_w2_%=\n\t"
+      "s_waitcnt vmcnt(0)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_w2_%=:\n\t"
+      "s_waitcnt vmcnt(2)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_w4_%=:\n\t"
+      "s_waitcnt vmcnt(4)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_w6_%=:\n\t"
+      "s_waitcnt vmcnt(6)\n"
+      ".Ldcw_end_%=:"
+      :
+      : "s"(n)
+      : "scc", "memory");
+}
+
+// ------------------------------------------------------------------------------------------
+// multiplying waves
+// ------------------------------------------------------------------------------------------
+struct MulCtx {
+  const char* Wp;
+  const char* h;
+  const float* bias64;  // the 64 bias values of this wave's columns (uniform address)
+  u16* out;
+  char* smem;
+  char* stage;
+  unsigned lds0;        // LDS byte address of smem
+  int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
+};
+
+// Step g of a multiplying wave: request the copies for step g + 2 (four 1 KB pieces of the W chunk
+// and, if that step multiplies the node's own columns, two pieces of eight rows each), run the
+// products of step g, make sure what was requested one step ago has landed and, at the end of a tile,
+// write the tile out.
+template <int DCH>
+__device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], const MulCtx& c) {
+  constexpr int NK = Shape<DCH>::NK;
+  int n_req = 0;
+  {
+    const int J = g + 2;
+    if (J < S) {
+      const int ti = J / NK, kc = J - ti * NK;
+      if (kc < DCH) {
+        // piece p of an A chunk is rows 8p .. 8p+7; lane l fills position l&7 of row l>>3 of the piece,
+        // which under the swizzle holds column piece (l&7) ^ ((row>>1)&7).  Rows past the end are
+        // clamped to the last row (read, never stored).
+        n_req += 2;
+        const int m0 = (c.tile0 + ti * c.per) * kBM;
+        const unsigned aring = c.lds0 + (unsigned)(J % 3) * kABytes;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int piece = c.wave * 2 + i;
+          const int r = piece * 8 + (c.lane >> 3);
+          const int col = (c.lane & 7) ^ ((r >> 1) & 7);
+          const int row = min(m0 + r, c.ntot - 1);
+          copy16_to_lds(c.h + (size_t)row * Shape<DCH>::ROWB + kc * kARow + col * 16, aring + piece * 1024);
+        }
+      }
+      // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run.  With three chunks in
+      // all (d = 64) chunk k always lands in ring slot k: the ring holds the whole of W and only the
+      // first tile loads it.
+      if (NK > 3 || J < NK) {
+        n_req += 4;
+        const char* wsrc = c.Wp + (size_t)kc * kBBytes + c.lane * 16;
+        const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int piece = c.wave * 4 + i;
+          copy16_to_lds(wsrc + piece * 1024, ring + piece * 1024);
+        }
+      }
+    }
+  }
+  if (g >= 0) {
+    const char* As = c.smem + (g % 3) * kABytes;
+    const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (g % 3) * kBBytes);
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)          // rows wm*64 + i*32 + l32 all share the swizzle of row l32
+        a[i] = *reinterpret_cast<const bf16x8*>(As + (c.wm * 64 + i * 32 + c.l32) * kARow +
+                                                (((ks * 2 + c.lh) ^ c.sw) << 4));
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(Bs + ((ks * 2 + c.lh) * kBN + c.wn * 64 + j * 32 + c.l32) * 8);
+      // operands swapped: the accumulator block is (column, row); a lane owns one output row and four
+      // consecutive columns per register quad
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    }
+  }
+  // Everything requested one step ago (needed by step g + 1 after the barrier) is older than this
+  // step's n_req copies; placed before the tile's stores so that it never waits for those.
+  wait_copies(__builtin_amdgcn_readfirstlane(n_req));
+  if (g >= 0 && (g % NK) == NK - 1) {
+    // ---- tile finished: bias, ReLU, bf16; one 32 x 32 block at a time through the wave's staging
+    // block (16-byte pieces of a 64-byte row XOR-swizzled), then 16-byte stores of half cache lines
+    const int ti = g / NK;
+    const int m0 = (c.tile0 + ti * c.per) * kBM;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          // uniform addresses: scalar loads, which the vector-memory counter does not see
+          const float4 blo = *reinterpret_cast<const float4*>(c.bias64 + j * 32 + 8 * q);
+          const float4 bhi = *reinterpret_cast<const float4*>(c.bias64 + j * 32 + 8 * q + 4);
+          const float b0 = c.lh ? bhi.x : blo.x, b1 = c.lh ? bhi.y : blo.y;
+          const float b2 = c.lh ? bhi.z : blo.z, b3 = c.lh ? bhi.w : blo.w;
+          v2u p;
+          p.x = pack_bf16x2(fmaxf(acc[i][j][4 * q + 0] + b0, 0.f), fmaxf(acc[i][j][4 * q + 1] + b1, 0.f));
+          p.y = pack_bf16x2(fmaxf(acc[i][j][4 * q + 2] + b2, 0.f), fmaxf(acc[i][j][4 * q + 3] + b3, 0.f));
+          *reinterpret_cast<v2u*>(c.stage + c.l32 * 64 + ((q ^ ((c.l32 >> 2) & 3)) << 4) + 8 * c.lh) = p;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          const int idx = c.lane + 64 * k;
+          const int r = idx >> 2, cc = idx & 3;
+          const int gr = m0 + c.wm * 64 + i * 32 + r;
+          const v4u val = *reinterpret_cast<const v4u*>(c.stage + r * 64 + ((cc ^ ((r >> 2) & 3)) << 4));
+          if (gr < c.ntot)
+            *reinterpret_cast<v4u*>(c.out + (size_t)gr * kBN + c.wn * 64 + j * 32 + cc * 8) = val;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// mean-forming waves
+// ------------------------------------------------------------------------------------------
+struct Dsc {            // one (row, direction) of the tile at hand, decoded for this lane's column piece
+  const char* p0;       // first slot: the first neighbour's piece, or the row's finished mean from the pre-pass
+  unsigned o1, o2;      // second and third slot: byte offsets from the tile's base row of h
+  unsigned k1, k2;      // bf16 1.0 where the slot counts, 0 where it does not
+  float sc;             // 1 / (number of slots that count), 0 for an empty list
+};
+
+struct MeanCtx {
+  const char* h;
+  const char* hin;      // pre-pass means (rows with long lists): predecessors / successors
+  const char* hout;
+  const v4i* desc_in;
+  const v4i* desc_out;
+  char* smem;
+  int ntot, tile0, per, nt_wg;
+  int r0;               // rows r0 and r0 + 64 of the tile
+  unsigned cb;          // byte offset of this lane's 16-byte piece within a 64-column chunk
+  int aoff;             // swizzled LDS offset of (r0, piece); row r0 + 64 lies 8192 bytes further
+};
+
+template <int DCH>
+struct MeanState {
+  Dsc cur[2][2];        // [direction][item]
+  v4i raw[2][2];        // the next tile's descriptors as loaded
+  v4u ld[2][2][3];      // neighbour pieces in flight: [consuming step & 1][item][slot]
+  const char* hb;       // h at the base row of the tile `cur` belongs to (uniform)
+  int base_row;
+};
+
+template <int DCH>
+__device__ __forceinline__ void request_descriptors(MeanState<DCH>& st, const MeanCtx& c, int t) {
+  const int m = (c.tile0 + min(t, c.nt_wg - 1) * c.per) * kBM;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = min(m + c.r0 + 64 * i, c.ntot - 1);
+    st.raw[0][i] = c.desc_in[row];
+    st.raw[1][i] = c.desc_out[row];
+  }
+}
+
+// Turns the loaded descriptors of tile t into addresses, slot factors and the scale.  A graph has
+// fewer than 65536 nodes, so every neighbour lies within 65536 rows of the tile: offsets from the
+// tile's base row fit 32 bits whatever the size of the batch.
+template <int DCH>
+__device__ __forceinline__ void adopt_descriptors(MeanState<DCH>& st, const MeanCtx& c, int t) {
+  constexpr unsigned ROWB = Shape<DCH>::ROWB;
+  const int m = (c.tile0 + min(t, c.nt_wg - 1) * c.per) * kBM;
+  st.base_row = max(m - 65536, 0);
+  st.hb = c.h + (size_t)st.base_row * ROWB;
+#pragma unroll
+  for (int dir = 0; dir < 2; ++dir)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const v4i d = st.raw[dir][i];
+      // last word: the number of slots that count (0..3), or 5 for a row left to the pre-pass, which has
+      // one slot (its finished mean, at the row's own place in the pre-pass buffer)
+      const int ns = d.w > 3 ? 1 : d.w;
+      Dsc& o = st.cur[dir][i];
+      o.p0 = (d.w > 3 ? (dir ? c.hout : c.hin) : c.h) + (size_t)(unsigned)d.x * ROWB + c.cb;
+      o.o1 = (unsigned)(d.y - st.base_row) * ROWB + c.cb;
+      o.o2 = (unsigned)(d.z - st.base_row) * ROWB + c.cb;
+      o.k1 = ns > 1 ? 0x3F80u : 0u;
+      o.k2 = ns > 2 ? 0x3F80u : 0u;
+      unsigned scb = ns == 1 ? 0x3F800000u : 0u;
+      scb = ns == 2 ? 0x3F000000u : scb;
+      scb = ns == 3 ? 0x3EAAAAABu : scb;             // 1/3 rounded to nearest
+      o.sc = __uint_as_float(scb);
+    }
+}
+
+// Step s (0 .. NK-1) of tile t for a mean-forming wave: request the neighbour pieces of the chunk that
+// step s + 2 multiplies, then reduce the chunk of step s + 1 (requested one step ago) into its A ring
+// slot.  The last step of a tile first turns to the next tile's descriptors: nothing of this tile is
+// requested or reduced from there on.
+template <int DCH, int s>
+__device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanCtx& c) {
+  constexpr int NK = Shape<DCH>::NK;
+  if constexpr (s == NK - 1) adopt_descriptors<DCH>(st, c, t + 1);
+  if constexpr (s == 0) request_descriptors<DCH>(st, c, t + 1);
+  constexpr int lq = (s + 2) % NK;                   // the step whose chunk is requested now
+  if constexpr (lq >= DCH) {
+    constexpr int dir = lq / DCH - 1;
+    constexpr unsigned coff = (unsigned)(lq % DCH) * kARow;      // 64 columns = 128 bytes
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const Dsc& d = st.cur[dir][i];
+      st.ld[lq & 1][i][0] = *reinterpret_cast<const v4u*>(d.p0 + coff);
+      st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
+      st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
+    }
+  }
+  constexpr int rq = (s + 1) % NK;                   // the step whose chunk is reduced now
+  if constexpr (rq >= DCH) {
+    constexpr int dir = rq / DCH - 1;
+    char* dst = c.smem + (rq % 3) * kABytes + c.aoff;            // NK is a multiple of 3: ring slot = step % 3
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const Dsc& d = st.cur[dir][i];
+      const v4u x0 = st.ld[rq & 1][i][0], x1 = st.ld[rq & 1][i][1], x2 = st.ld[rq & 1][i][2];
+      v4u o;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        // ascending neighbour order: the first neighbour unpacked exactly, the others added where their
+        // slot counts
+        float lo = __uint_as_float(x0[w] << 16);
+        float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
+        bf16_pair_add(lo, hi, x1[w], d.k1);
+        bf16_pair_add(lo, hi, x2[w], d.k2);
+        o[w] = pack_bf16x2(lo * d.sc, hi * d.sc);   // one slot: x * 1.0 repacks to the same bf16 values
+      }
+      *reinterpret_cast<v4u*>(dst + i * 64 * kARow) = o;         // row r0 + 64 shares the swizzle of row r0
+    }
+  }
+}
+
+template <int DCH, int s>
+__device__ __forceinline__ void mean_tile(int t, MeanState<DCH>& st, const MeanCtx& c) {
+  mean_step<DCH, s>(t, st, c);
+  lds_barrier();
+  if constexpr (s + 1 < Shape<DCH>::NK) mean_tile<DCH, s + 1>(t, st, c);
+}
+
+template <int DCH>
+__global__ __launch_bounds__(kNT) void layer256w_kernel(
+    const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
+    const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
+    const float* __restrict__ bias, u16* __restrict__ out, const int* __restrict__ node_off, int C,
+    const int* __restrict__ status) {
+  constexpr int NK = Shape<DCH>::NK;
+  if (status[0] != 0) return;
+  char* smem = dc_l256w_smem;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int ntot = node_off[C];
+  const int ntiles = (ntot + kBM - 1) / kBM;
+  // XCD-contiguous tile ranges (workgroups are dealt round-robin over the 8 XCDs)
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per = gridDim.x >> 3;
+  const int tpx = (ntiles + 7) >> 3;
+  const int lim = min(tpx, ntiles - xcd * tpx);
+  const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
+  const int S = nt_wg * NK;                 // steps of this workgroup
+  if (S == 0) return;                       // no tile for this workgroup (uniform)
+  // Both kinds of wave pass S + 2 barriers (steps -2 .. S-1).  Waves are dealt to the four SIMDs
+  // round-robin, so every SIMD hosts two waves of each kind.
+  if (wave < kMfmaWaves) {
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    MulCtx mc;
+    mc.Wp = reinterpret_cast<const char*>(Wp);
+    mc.h = reinterpret_cast<const char*>(h);
+    mc.wm = wave >> 2;
+    mc.wn = wave & 3;
+    mc.bias64 = bias + mc.wn * 64;
+    mc.out = out;
+    mc.smem = smem;
+    mc.stage = smem + kStageOff + wave * kStageBytes;
+    mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256w_smem);
+    mc.ntot = ntot;
+    mc.tile0 = xcd * tpx + slot;
+    mc.per = per;
+    mc.l32 = lane & 31;
+    mc.lh = lane >> 5;
+    mc.lane = lane;
+    mc.sw = ((lane & 31) >> 1) & 7;
+    mc.wave = wave;
+    for (int g = -2; g < S; ++g) {
+      mul_step<DCH>(g, S, acc, mc);
+      lds_barrier();
+    }
+  } else {
+    const int ml = (wave - kMfmaWaves) * 64 + lane;
+    MeanCtx mc;
+    mc.h = reinterpret_cast<const char*>(h);
+    mc.hin = reinterpret_cast<const char*>(hin_heavy);
+    mc.hout = reinterpret_cast<const char*>(hout_heavy);
+    mc.desc_in = desc_in;
+    mc.desc_out = desc_out;
+    mc.smem = smem;
+    mc.ntot = ntot;
+    mc.tile0 = xcd * tpx + slot;
+    mc.per = per;
+    mc.nt_wg = nt_wg;
+    mc.r0 = ml >> 3;
+    mc.cb = (unsigned)(ml & 7) * 16u;
+    mc.aoff = swz(mc.r0, ml & 7);
+    MeanState<DCH> st;
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int u = 0; u < 3; ++u) st.ld[p][i][u] = v4u{0u, 0u, 0u, 0u};
+    // steps -2 and -1: the first tile's descriptors; with d = 64 its first chunk of means is
+    // requested here, as the last step of a tile does for the tile after it
+    request_descriptors<DCH>(st, mc, 0);
+    lds_barrier();
+    mean_step<DCH, NK - 1>(-1, st, mc);
+    lds_barrier();
+    for (int tt = 0; tt < nt_wg; ++tt) mean_tile<DCH, 0>(tt, st, mc);
+  }
+}
+
+template <int DCH>
+hipError_t launch_w(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out, hipStream_t s) {
+  static bool attr_done = false;
+  auto kern = layer256w_kernel<DCH>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int grid = ((a.n_cu + 7) / 8) * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, static_cast<const u16*>(h),
+                     static_cast<const u16*>(a.agg[0]), static_cast<const u16*>(a.agg[1]),
+                     static_cast<const v4i*>(a.desc[0]), static_cast<const v4i*>(a.desc[1]),
+                     static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand, a.status);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// The layer kernel alone (descriptors built, pre-pass means in a.agg[]): d = 256 or 64, three gather slots.
+hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                            hipStream_t s) {
+  if (d == 256) return launch_w<4>(h, a, Wl, bias, out, s);
+  if (d == 64) return launch_w<1>(h, a, Wl, bias, out, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace dc

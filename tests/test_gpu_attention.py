@@ -58,6 +58,11 @@ def test_small_batches_every_width(B, dtype, F, H, L, K):
     g = wl.random_dag(7, 300, 0.02, F)
     labs = wl.random_labels(8, g.n, 90, C=7)
     w = wl.custom(f"att-{dtype}-{F}-{H}-{L}-{K}", wl.ModelSpec(F, H, L, dtype, "attention", K), [g], [labs], seed=3)
+    if dtype == "bf16":
+        # random signed weights let the last dot product cancel to a hundredth of its terms, where bf16
+        # storage alone (the oracle with bf16 storage points against the plain one) is 3e-2 off; the
+        # 2e-2 bound is about predictions that are sums of like-signed terms, as times are
+        w = wl.with_time_like_head(w)
     check(run(B, w), w, w.name)
 
 
