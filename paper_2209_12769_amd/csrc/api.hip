@@ -162,8 +162,9 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   void* act1 = a.take<char>((size_t)(k.NN + 1) * cfg.H * es);
   void* agg0 = a.take<char>((size_t)(k.NN + 1) * D * es);
   void* agg1 = a.take<char>((size_t)(k.NN + 1) * D * es);
-  void* desc0 = a.take<char>((size_t)(k.NN + 1) * 16);
-  void* desc1 = a.take<char>((size_t)(k.NN + 1) * 16);
+  // one 16-byte descriptor per node and direction, room for whole tiles of 128
+  void* desc0 = a.take<char>((size_t)(k.NN + 128) * 16);
+  void* desc1 = a.take<char>((size_t)(k.NN + 128) * 16);
   const size_t nscore = cfg.aggregator == DC_AGG_ATTENTION ? (size_t)(k.NN + 1) * cfg.heads : 0;
   float* score0 = a.take<float>(nscore);
   float* score1 = a.take<float>(nscore);

@@ -152,6 +152,7 @@ hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* W
                            Profiler* prof, hipStream_t s);
 // gnn_layer256w.hip: the same layer (three gather slots) with sixteen waves per workgroup; descriptors and
 // pre-pass means as for launch_layer256
+hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                             hipStream_t s);
 hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,

@@ -929,6 +929,8 @@ static_assert(kU == 3, "a descriptor holds three neighbour ids and the degree");
 static int slots_of(const GnnArgs& a) { return a.gather_slots == 1 ? 1 : kU; }
 
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s) {
+  // the sixteen-wave layer kernel takes its descriptors sorted per tile
+  if (slots_of(a) == kU && !a.layer_v1) return launch_build_desc_sorted(a, s);
   hipLaunchKernelGGL(build_desc_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
                      a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.node_off, a.n_cand,
                      slots_of(a), a.status);

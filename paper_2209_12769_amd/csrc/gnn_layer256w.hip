@@ -17,7 +17,11 @@
 //   load into it is in flight, and the waits are the compiler's.  The steps of a tile are
 //   unrolled, so chunk offsets, ring slots and the direction are constants of each step.
 // Rows with more than three neighbours take their mean from a pre-pass (one slot: the finished
-// mean), so that no lane walks a long list here.  All waves meet at one barrier per step that
+// mean), so that no lane walks a long list here.  The descriptors of a tile come sorted by the
+// number of slots that count, separately per direction: a lane may form the mean of any row of the
+// tile (it writes the piece to that row's place in the A chunk), so the eight rows that share a load
+// instruction are chosen to need the same slots, and slots and arithmetic that none of them needs
+// are skipped (a single slot is a plain copy).  All waves meet at one barrier per step that
 // waits for LDS traffic only: global loads stay in flight across it.
 #include "common.h"
 
@@ -76,10 +80,30 @@ __device__ __forceinline__ void lds_barrier() {
 __device__ __forceinline__ void copy16_to_lds(const void* gaddr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "memory");
 }
-// s_waitcnt vmcnt(n), n in {0, 2, 4, 6} (wave-uniform): at most n newer vector-memory operations may
-// still be outstanding.  Loads return in issue order.
+// s_waitcnt vmcnt(n), n even in 0 .. 14 (wave-uniform): at most n newer vector-memory operations may
+// still be outstanding.  Loads and stores leave the counter in issue order.
 __device__ __forceinline__ void wait_copies(int n) {
   asm volatile(
+      "s_cmp_lt_u32 %0, 8\n\t"
+      "s_cbranch_scc1 .Ldcw_lo_%=\n\t"
+      "s_cmp_eq_u32 %0, 8\n\t"
+      "s_cbranch_scc1 .Ldcw_w8_%=\n\t"
+      "s_cmp_eq_u32 %0, 10\n\t"
+      "s_cbranch_scc1 .Ldcw_w10_%=\n\t"
+      "s_cmp_eq_u32 %0, 12\n\t"
+      "s_cbranch_scc1 .Ldcw_w12_%=\n\t"
+      "s_waitcnt vmcnt(14)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_w8_%=:\n\t"
+      "s_waitcnt vmcnt(8)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_w10_%=:\n\t"
+      "s_waitcnt vmcnt(10)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_w12_%=:\n\t"
+      "s_waitcnt vmcnt(12)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_lo_%=:\n\t"
       "s_cmp_eq_u32 %0, 6\n\t"
       "s_cbranch_scc1 .Ldcw_w6_%=\n\t"
       "s_cmp_eq_u32 %0, 4\n\t"
@@ -182,8 +206,11 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
     }
   }
   // Everything requested one step ago (needed by step g + 1 after the barrier) is older than this
-  // step's n_req copies; placed before the tile's stores so that it never waits for those.
-  wait_copies(__builtin_amdgcn_readfirstlane(n_req));
+  // step's n_req copies, and older than the eight stores of a tile that ended one step ago (those
+  // were issued after that step's copies: they are counted, not waited for); placed before this
+  // tile's stores so that it never waits for those.
+  const int stores_behind = (g >= 1 && ((g - 1) % NK) == NK - 1) ? 8 : 0;
+  wait_copies(__builtin_amdgcn_readfirstlane(n_req + stores_behind));
   if (g >= 0 && (g % NK) == NK - 1) {
     // ---- tile finished: bias, ReLU, bf16; one 32 x 32 block at a time through the wave's staging
     // block (16-byte pieces of a 64-byte row XOR-swizzled), then 16-byte stores of half cache lines
@@ -233,6 +260,7 @@ struct Dsc {            // one (row, direction) of the tile at hand, decoded for
   unsigned o1, o2;      // second and third slot: byte offsets from the tile's base row of h
   unsigned k1, k2;      // bf16 1.0 where the slot counts, 0 where it does not
   float sc;             // 1 / (number of slots that count), 0 for an empty list
+  int aoff;             // swizzled LDS offset of (row, piece) within an A chunk
 };
 
 struct MeanCtx {
@@ -243,9 +271,9 @@ struct MeanCtx {
   const v4i* desc_out;
   char* smem;
   int ntot, tile0, per, nt_wg;
-  int r0;               // rows r0 and r0 + 64 of the tile
-  unsigned cb;          // byte offset of this lane's 16-byte piece within a 64-column chunk
-  int aoff;             // swizzled LDS offset of (r0, piece); row r0 + 64 lies 8192 bytes further
+  int pos[2];           // the two sorted positions (0..127) of the tile this lane serves
+  int piece;            // its 16-byte piece (0..7) of a 64-column chunk
+  unsigned cb;          // = 16 * piece
 };
 
 template <int DCH>
@@ -255,16 +283,17 @@ struct MeanState {
   v4u ld[2][2][3];      // neighbour pieces in flight: [consuming step & 1][item][slot]
   const char* hb;       // h at the base row of the tile `cur` belongs to (uniform)
   int base_row;
+  bool two[2][2], three[2][2];   // wave-uniform: some row of the item has a second / a third slot that counts
 };
 
 template <int DCH>
 __device__ __forceinline__ void request_descriptors(MeanState<DCH>& st, const MeanCtx& c, int t) {
+  // descriptors are stored tile by tile in sorted order, 128 per tile also for the last one
   const int m = (c.tile0 + min(t, c.nt_wg - 1) * c.per) * kBM;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int row = min(m + c.r0 + 64 * i, c.ntot - 1);
-    st.raw[0][i] = c.desc_in[row];
-    st.raw[1][i] = c.desc_out[row];
+    st.raw[0][i] = c.desc_in[m + c.pos[i]];
+    st.raw[1][i] = c.desc_out[m + c.pos[i]];
   }
 }
 
@@ -282,11 +311,16 @@ __device__ __forceinline__ void adopt_descriptors(MeanState<DCH>& st, const Mean
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const v4i d = st.raw[dir][i];
-      // last word: the number of slots that count (0..3), or 5 for a row left to the pre-pass, which has
-      // one slot (its finished mean, at the row's own place in the pre-pass buffer)
-      const int ns = d.w > 3 ? 1 : d.w;
+      // last word: low byte = the number of slots that count (0..3), or 5 for a row left to the pre-pass,
+      // which has one slot (its finished mean, at the row's own place in the pre-pass buffer); above it
+      // the row's place in the tile
+      const int code = d.w & 255, row = (d.w >> 8) & (kBM - 1);
+      const int ns = code > 3 ? 1 : code;
       Dsc& o = st.cur[dir][i];
-      o.p0 = (d.w > 3 ? (dir ? c.hout : c.hin) : c.h) + (size_t)(unsigned)d.x * ROWB + c.cb;
+      o.aoff = swz(row, c.piece);
+      st.two[dir][i] = __ballot(ns > 1) != 0;
+      st.three[dir][i] = __ballot(ns > 2) != 0;
+      o.p0 = (code > 3 ? (dir ? c.hout : c.hin) : c.h) + (size_t)(unsigned)d.x * ROWB + c.cb;
       o.o1 = (unsigned)(d.y - st.base_row) * ROWB + c.cb;
       o.o2 = (unsigned)(d.z - st.base_row) * ROWB + c.cb;
       o.k1 = ns > 1 ? 0x3F80u : 0u;
@@ -315,30 +349,44 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
     for (int i = 0; i < 2; ++i) {
       const Dsc& d = st.cur[dir][i];
       st.ld[lq & 1][i][0] = *reinterpret_cast<const v4u*>(d.p0 + coff);
-      st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
-      st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
+      if (st.two[dir][i]) st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
+      if (st.three[dir][i]) st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
     }
   }
   constexpr int rq = (s + 1) % NK;                   // the step whose chunk is reduced now
   if constexpr (rq >= DCH) {
     constexpr int dir = rq / DCH - 1;
-    char* dst = c.smem + (rq % 3) * kABytes + c.aoff;            // NK is a multiple of 3: ring slot = step % 3
+    char* dst = c.smem + (rq % 3) * kABytes;                     // NK is a multiple of 3: ring slot = step % 3
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const Dsc& d = st.cur[dir][i];
-      const v4u x0 = st.ld[rq & 1][i][0], x1 = st.ld[rq & 1][i][1], x2 = st.ld[rq & 1][i][2];
+      const v4u x0 = st.ld[rq & 1][i][0];
       v4u o;
+      if (!st.two[dir][i]) {
+        // one slot at most in all eight rows: the mean is the neighbour's piece (or the finished mean)
+        // as it is, or zero for an empty list
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        // ascending neighbour order: the first neighbour unpacked exactly, the others added where their
-        // slot counts
-        float lo = __uint_as_float(x0[w] << 16);
-        float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
-        bf16_pair_add(lo, hi, x1[w], d.k1);
-        bf16_pair_add(lo, hi, x2[w], d.k2);
-        o[w] = pack_bf16x2(lo * d.sc, hi * d.sc);   // one slot: x * 1.0 repacks to the same bf16 values
+        for (int w = 0; w < 4; ++w) o[w] = d.sc != 0.f ? x0[w] : 0u;
+      } else {
+        const v4u x1 = st.ld[rq & 1][i][1];
+        float lo[4], hi[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          // ascending neighbour order: the first neighbour unpacked exactly, the others added where their
+          // slot counts
+          lo[w] = __uint_as_float(x0[w] << 16);
+          hi[w] = __uint_as_float(x0[w] & 0xFFFF0000u);
+          bf16_pair_add(lo[w], hi[w], x1[w], d.k1);
+        }
+        if (st.three[dir][i]) {
+          const v4u x2 = st.ld[rq & 1][i][2];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], x2[w], d.k2);
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) o[w] = pack_bf16x2(lo[w] * d.sc, hi[w] * d.sc);   // x * 1.0 repacks to the same bf16 value
       }
-      *reinterpret_cast<v4u*>(dst + i * 64 * kARow) = o;         // row r0 + 64 shares the swizzle of row r0
+      *reinterpret_cast<v4u*>(dst + d.aoff) = o;
     }
   }
 }
@@ -403,7 +451,6 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
       lds_barrier();
     }
   } else {
-    const int ml = (wave - kMfmaWaves) * 64 + lane;
     MeanCtx mc;
     mc.h = reinterpret_cast<const char*>(h);
     mc.hin = reinterpret_cast<const char*>(hin_heavy);
@@ -415,9 +462,11 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
     mc.tile0 = xcd * tpx + slot;
     mc.per = per;
     mc.nt_wg = nt_wg;
-    mc.r0 = ml >> 3;
-    mc.cb = (unsigned)(ml & 7) * 16u;
-    mc.aoff = swz(mc.r0, ml & 7);
+    // A wave serves two groups of eight sorted positions: group w (few slots) and group 15 - w (many)
+    mc.pos[0] = (wave - kMfmaWaves) * 8 + (lane >> 3);
+    mc.pos[1] = (15 - (wave - kMfmaWaves)) * 8 + (lane >> 3);
+    mc.piece = lane & 7;
+    mc.cb = (unsigned)(lane & 7) * 16u;
     MeanState<DCH> st;
 #pragma unroll
     for (int p = 0; p < 2; ++p)
@@ -432,6 +481,59 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
     mean_step<DCH, NK - 1>(-1, st, mc);
     lds_barrier();
     for (int tt = 0; tt < nt_wg; ++tt) mean_tile<DCH, 0>(tt, st, mc);
+  }
+}
+
+// One gather descriptor per node and direction, stored tile by tile (128 per tile, also for the last one)
+// and, within a tile, sorted by the number of slots that count: first the rows with at most one (a single
+// neighbour, a finished mean from the pre-pass, or none), then two, then three.  Words: the first three
+// neighbours (unused slots, empty lists and rows left to the pre-pass point at the node itself, always a
+// valid row); then the code (0..3 slots that count, 5 = left to the pre-pass) in the low byte and the
+// row's place in its tile above it.  Places of the last tile past the end of the batch are empty lists.
+// Depends only on the graphs: built once per forward pass.  One workgroup of 256 per tile: threads
+// 0..127 the predecessors' lists, 128..255 the successors'.
+__global__ __launch_bounds__(256) void build_desc_sorted_kernel(
+    const int* __restrict__ in_rp, const int* __restrict__ in_ci, const int* __restrict__ out_rp,
+    const int* __restrict__ out_ci, v4i* __restrict__ desc_in, v4i* __restrict__ desc_out,
+    const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  __shared__ int cnt[2][4][3];               // [parity][wave][class]
+  const int ntot = node_off[C];
+  const int ntiles = (ntot + kBM - 1) / kBM;
+  const int t = threadIdx.x, wave = t >> 6, lane = t & 63, dir = t >> 7, r = t & 127;
+  int par = 0;
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x, par ^= 1) {
+    const int v = tile * kBM + r;
+    const bool valid = v < ntot;
+    const int vv = valid ? v : ntot - 1;
+    const int* rp = dir ? out_rp : in_rp;
+    const int* ci = dir ? out_ci : in_ci;
+    const int s = rp[vv], dg = valid ? rp[vv + 1] - s : 0;
+    const int ns = dg > 3 ? 1 : dg;
+    const int cls = ns <= 1 ? 0 : ns - 1;
+    int rank = 0;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const unsigned long long m = __ballot(cls == k);
+      if (cls == k) rank = __popcll(m & ((1ull << lane) - 1ull));
+      if (lane == 0) cnt[par][wave][k] = __popcll(m);
+    }
+    __syncthreads();                           // the next tile writes the other parity: one barrier per tile
+    const int w0 = dir * 2;
+    int start = 0;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const int c0 = cnt[par][w0][k], c1 = cnt[par][w0 + 1][k];
+      if (k < cls) start += c0 + c1;
+      if (k == cls && (wave & 1)) start += c0;
+    }
+    v4i d = v4i{vv, vv, vv, (dg > 3 ? 5 : dg) | (r << 8)};
+    if (dg <= 3 && dg > 0) {
+      d.x = ci[s];                             // unused slots repeat the first neighbour: never loaded or never summed
+      d.y = dg > 1 ? ci[s + 1] : d.x;
+      d.z = dg > 2 ? ci[s + 2] : d.x;
+    }
+    (dir ? desc_out : desc_in)[(size_t)tile * kBM + start + rank] = d;
   }
 }
 
@@ -455,7 +557,14 @@ hipError_t launch_w(const void* h, const GnnArgs& a, const void* Wl, const float
 
 }  // namespace
 
-// The layer kernel alone (descriptors built, pre-pass means in a.agg[]): d = 256 or 64, three gather slots.
+hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(build_desc_sorted_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
+                     a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.node_off, a.n_cand,
+                     a.status);
+  return hipGetLastError();
+}
+
+// The layer kernel alone (sorted descriptors built, pre-pass means in a.agg[]): d = 256 or 64, three gather slots.
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                             hipStream_t s) {
   if (d == 256) return launch_w<4>(h, a, Wl, bias, out, s);
