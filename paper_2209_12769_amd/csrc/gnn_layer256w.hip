@@ -140,12 +140,10 @@ struct MulCtx {
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
 
-// Step g of a multiplying wave: request the copies for step g + 2 (four 1 KB pieces of the W chunk
-// and, if that step multiplies the node's own columns, two pieces of eight rows each), run the
-// products of step g, make sure what was requested one step ago has landed and, at the end of a tile,
-// write the tile out.
+// The copies for step J = g + 2 (four 1 KB pieces of the W chunk and, if that step multiplies the node's
+// own columns, two pieces of eight rows each); returns how many were requested.
 template <int DCH>
-__device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], const MulCtx& c) {
+__device__ __forceinline__ int request_copies(int g, int S, const MulCtx& c) {
   constexpr int NK = Shape<DCH>::NK;
   int n_req = 0;
   {
@@ -183,6 +181,12 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
       }
     }
   }
+  return n_req;
+}
+
+// The products of step g.
+template <int DCH>
+__device__ __forceinline__ void products(int g, f32x16 (&acc)[2][2], const MulCtx& c) {
   if (g >= 0) {
     const char* As = c.smem + (g % 3) * kABytes;
     const u16* Bs = reinterpret_cast<const u16*>(c.smem + kBOff + (g % 3) * kBBytes);
@@ -205,6 +209,19 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   }
+}
+
+// Step g of a multiplying wave: request the copies for step g + 2 and run the products of step g --
+// the two multiplying waves of a SIMD in opposite order, so that while one stands in the queue of
+// the vector-memory unit with its requests the other one multiplies -- then make sure what was
+// requested one step ago has landed and, at the end of a tile, write the tile out.
+template <int DCH>
+__device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], const MulCtx& c) {
+  constexpr int NK = Shape<DCH>::NK;
+  const bool products_first = c.wm == 0;
+  if (products_first) products<DCH>(g, acc, c);
+  const int n_req = request_copies<DCH>(g, S, c);
+  if (!products_first) products<DCH>(g, acc, c);
   // Everything requested one step ago (needed by step g + 1 after the barrier) is older than this
   // step's n_req copies, and older than the eight stores of a tile that ended one step ago (those
   // were issued after that step's copies: they are counted, not waited for); placed before this
@@ -332,27 +349,15 @@ __device__ __forceinline__ void adopt_descriptors(MeanState<DCH>& st, const Mean
     }
 }
 
-// Step s (0 .. NK-1) of tile t for a mean-forming wave: request the neighbour pieces of the chunk that
-// step s + 2 multiplies, then reduce the chunk of step s + 1 (requested one step ago) into its A ring
-// slot.  The last step of a tile first turns to the next tile's descriptors: nothing of this tile is
+// Step s (0 .. NK-1) of tile t for a mean-forming wave: reduce the chunk of step s + 1 (requested one step
+// ago) into its A ring slot, then request the neighbour pieces of the chunk that step s + 2 multiplies
+// (requests last: a wave stands in the vector-memory unit's queue with them, and has nothing left to do).  The last step of a tile first turns to the next tile's descriptors: nothing of this tile is
 // requested or reduced from there on.
 template <int DCH, int s>
 __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanCtx& c) {
   constexpr int NK = Shape<DCH>::NK;
   if constexpr (s == NK - 1) adopt_descriptors<DCH>(st, c, t + 1);
   if constexpr (s == 0) request_descriptors<DCH>(st, c, t + 1);
-  constexpr int lq = (s + 2) % NK;                   // the step whose chunk is requested now
-  if constexpr (lq >= DCH) {
-    constexpr int dir = lq / DCH - 1;
-    constexpr unsigned coff = (unsigned)(lq % DCH) * kARow;      // 64 columns = 128 bytes
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const Dsc& d = st.cur[dir][i];
-      st.ld[lq & 1][i][0] = *reinterpret_cast<const v4u*>(d.p0 + coff);
-      if (st.two[dir][i]) st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
-      if (st.three[dir][i]) st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
-    }
-  }
   constexpr int rq = (s + 1) % NK;                   // the step whose chunk is reduced now
   if constexpr (rq >= DCH) {
     constexpr int dir = rq / DCH - 1;
@@ -387,6 +392,19 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
         for (int w = 0; w < 4; ++w) o[w] = pack_bf16x2(lo[w] * d.sc, hi[w] * d.sc);   // x * 1.0 repacks to the same bf16 value
       }
       *reinterpret_cast<v4u*>(dst + d.aoff) = o;
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  constexpr int lq = (s + 2) % NK;                   // the step whose chunk is requested now
+  if constexpr (lq >= DCH) {
+    constexpr int dir = lq / DCH - 1;
+    constexpr unsigned coff = (unsigned)(lq % DCH) * kARow;      // 64 columns = 128 bytes
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const Dsc& d = st.cur[dir][i];
+      st.ld[lq & 1][i][0] = *reinterpret_cast<const v4u*>(d.p0 + coff);
+      if (st.two[dir][i]) st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
+      if (st.three[dir][i]) st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
     }
   }
 }
