@@ -432,7 +432,7 @@ def main():
                     help="time dc_train_step (estimator training, fp32) on samples drawn on the workload's base "
                          "graph; --n-cand = number of labelings the samples are drawn from")
     ap.add_argument("--kernels", type=int, default=0,
-                    help="dc_select_kernels value (0: defaults; 4: the bulk layer in its eight-wave form)")
+                    help="dc_select_kernels value (0: defaults; 1: neighbour means and node update as separate kernels)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run five element-wise copies (y = -x, fp32) of MIB MiB each: "
                          "a kernel of known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")

@@ -358,15 +358,11 @@ dc_status dc_check(dc_ctx* ctx, void* stream);
 dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* stream);
 
 /* Chooses between kernels that compute the same layer: a diagnostic switch for tests and
- * measurements, never needed to obtain a result.  `which` is a sum of
- *   DC_KERNELS_SEPARATE_LAYERS     neighbour means and node update as two kernels per layer with the
- *                                  means written to memory, instead of the fused layer kernels
- *   DC_KERNELS_ONE_SLOT_REGISTERS  the one-slot layer kernel (fused-op batches) gathers through
- *                                  registers instead of by direct copies into LDS
- *   DC_KERNELS_LAYER_8_WAVES       the bulk layer (H = 256, bf16) in its eight-wave form instead of
- *                                  the sixteen-wave form
- * 0 restores the defaults.  Takes effect from the next call on this context; host state only.  */
-enum { DC_KERNELS_SEPARATE_LAYERS = 1, DC_KERNELS_ONE_SLOT_REGISTERS = 2, DC_KERNELS_LAYER_8_WAVES = 4 };
+ * measurements, never needed to obtain a result.  `which` is 0 (the defaults) or
+ *   DC_KERNELS_SEPARATE_LAYERS   neighbour means and node update as two kernels per layer with the
+ *                                means written to memory, instead of the fused layer kernels
+ * Takes effect from the next call on this context; host state only.                            */
+enum { DC_KERNELS_SEPARATE_LAYERS = 1 };
 dc_status dc_select_kernels(dc_ctx* ctx, int32_t which);
 
 /* Human-readable detail of the last error on this context; owned by the context. */

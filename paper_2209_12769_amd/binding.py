@@ -29,7 +29,7 @@ DC_F32 = 0
 DC_BF16 = 1
 DC_AGG_MEAN = 0
 DC_AGG_ATTENTION = 1
-DC_KERNELS_SEPARATE_LAYERS, DC_KERNELS_ONE_SLOT_REGISTERS, DC_KERNELS_LAYER_8_WAVES = 1, 2, 4
+DC_KERNELS_SEPARATE_LAYERS = 1
 STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "DC_ERR_BAD_PARTITION",
                 4: "DC_ERR_CAPACITY", 5: "DC_ERR_OOM", 6: "DC_ERR_HIP", 7: "DC_ERR_UNSUPPORTED"}
 

@@ -42,6 +42,8 @@ struct dc_ctx {
   void* act[2] = {nullptr, nullptr};
   void* agg[2] = {nullptr, nullptr};
   void* desc[2] = {nullptr, nullptr};
+  int* heavy[2] = {nullptr, nullptr};
+  int* heavy_cnt = nullptr;
   int* status = nullptr;    // [2]
   int* totals = nullptr;    // [2]
   char* zero_row = nullptr; // 1 KB of zeros
@@ -76,8 +78,6 @@ struct dc_ctx {
   bool have_profile = false;
   std::vector<int> h_gno, h_geo;   // host copies of the base graphs' offsets
   int allow_fused = 1;
-  int u1_dma = 1;
-  int layer_v1 = 0;
   // training (dc_train_begin)
   bool training = false;
   dc_train_params tp{};
@@ -165,6 +165,9 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   // one 16-byte descriptor per node and direction, room for whole tiles of 128
   void* desc0 = a.take<char>((size_t)(k.NN + 128) * 16);
   void* desc1 = a.take<char>((size_t)(k.NN + 128) * 16);
+  int* heavy0 = a.take<int>((size_t)k.NN + 128);
+  int* heavy1 = a.take<int>((size_t)k.NN + 128);
+  int* heavy_cnt = a.take<int>(2 * ((size_t)k.NN / 128 + 2));
   const size_t nscore = cfg.aggregator == DC_AGG_ATTENTION ? (size_t)(k.NN + 1) * cfg.heads : 0;
   float* score0 = a.take<float>(nscore);
   float* score1 = a.take<float>(nscore);
@@ -182,6 +185,9 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
     ctx->agg[1] = agg1;
     ctx->desc[0] = desc0;
     ctx->desc[1] = desc1;
+    ctx->heavy[0] = heavy0;
+    ctx->heavy[1] = heavy1;
+    ctx->heavy_cnt = heavy_cnt;
   }
   return a.off;
 }
@@ -279,12 +285,14 @@ GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) 
   g.agg[1] = ctx->agg[1];
   g.desc[0] = ctx->desc[0];
   g.desc[1] = ctx->desc[1];
+  g.heavy[0] = ctx->heavy[0];
+  g.heavy[1] = ctx->heavy[1];
+  g.heavy_cnt = ctx->heavy_cnt;
   g.pred = pred;
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;
   g.allow_fused = ctx->allow_fused;
-  g.layer_v1 = ctx->layer_v1;
-  g.zero_row = ctx->u1_dma ? ctx->zero_row : nullptr;
+  g.zero_row = ctx->zero_row;
   if (ctx->cfg.aggregator == DC_AGG_ATTENTION) {
     g.heads = ctx->cfg.heads;
     g.att = ctx->att;
@@ -1248,10 +1256,8 @@ dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* 
 }
 
 dc_status dc_select_kernels(dc_ctx* ctx, int32_t which) {
-  if (!ctx || which < 0 || which > 7) return DC_ERR_INVALID_ARG;
+  if (!ctx || which < 0 || which > 1) return DC_ERR_INVALID_ARG;
   ctx->allow_fused = !(which & DC_KERNELS_SEPARATE_LAYERS);
-  ctx->u1_dma = !(which & DC_KERNELS_ONE_SLOT_REGISTERS);
-  ctx->layer_v1 = (which & DC_KERNELS_LAYER_8_WAVES) != 0;
   return DC_OK;
 }
 

@@ -105,11 +105,12 @@ struct GnnArgs {
   void* act[2];         // ping/pong activations [max_nodes, H]
   void* agg[2];         // predecessor mean / successor mean [max_nodes, max(F,H)]
   void* desc[2];        // gather descriptors [max_nodes] x 16 bytes per direction
+  int* heavy[2] = {nullptr, nullptr};   // per direction and tile of 128 rows: the rows with long lists (128 places per tile)
+  int* heavy_cnt = nullptr;             // [2 * tiles] how many of them: entry 2 * tile + direction
   float* pred;
   const int* status;
   int n_cu;
   int allow_fused;      // 0 forces the separate aggregate + update kernels
-  int layer_v1 = 0;     // 1: the bulk layer in its eight-wave form
   int gather_slots = 3; // 1: nearly every neighbour list has at most one entry (batches of fused-op subgraphs)
   const void* zero_row = nullptr;   // 1 KB of zeros in device memory (the mean of an empty list, read by DMA)
   // attention aggregation (heads > 0): W holds one [d, H] block per layer
@@ -153,6 +154,9 @@ hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* W
 // gnn_layer256w.hip: the same layer (three gather slots) with sixteen waves per workgroup; descriptors and
 // pre-pass means as for launch_layer256
 hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s);
+// Means of the rows with more than three neighbours (listed by launch_build_desc_sorted), written at the rows'
+// own places in a.agg[0] (predecessors) and a.agg[1] (successors); h [rows, d], d = 256 or 64, bf16.
+hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                             hipStream_t s);
 hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,

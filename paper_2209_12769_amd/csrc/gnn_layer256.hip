@@ -1,20 +1,16 @@
-// Wave-specialised fused layer for output width H = 256 and input width d = 256 or 64, bf16 (gfx950):
-//     h'[v] = ReLU([h[v] | mean_pred(h)[v] | mean_succ(h)[v]] W + b)
-// (neighbourhood encoding of Sec. 3.3.1 with uniform coefficients), with both
-// means formed on the fly so that a layer reads h once and writes h' once.
-//
-// One workgroup of 8 waves per CU.  Waves 0-3 only issue MFMAs: each owns a
-// 64 x 128 block of the 128 x 256 output tile, reads its A/B fragments from LDS
-// and prefetches the next B chunk of W.  Waves 4-7 only move data: per K chunk
-// of 64 columns each lane owns four (row, 16-byte column) items; it issues the
-// loads of chunk j+2 (the node's own row, or up to U neighbour rows), then
-// reduces chunk j+1 (issued one step earlier) in fp32 in ascending neighbour
-// order, scales by 1/deg, rounds to bf16 and writes the A chunk into the LDS set
-// the MFMA waves read in the next step.  Rows with more than U neighbours get
-// their mean from a pre-pass (aggregate_heavy) so that no lane ever walks a long
-// neighbour list inside this kernel.  All waves meet at one barrier per step;
-// the step sequence runs across tiles, so loads for the next tile are in flight
-// while the current one finishes.
+// Eight-wave kernels for output width H = 256 and input width d = 256 or 64, bf16 (gfx950), built
+// around one multiplying step (mfma_step): four waves that each own a 64 x 128 block of a 128 x 256
+// output tile and read their fragments from LDS rings that are filled from global memory by direct
+// copies (no registers), with one barrier per K chunk of 64 columns.
+//   layer256_dense_kernel: the plain product out = h W (or ReLU(h W + b)), K = d: z = W e' of the
+//     attention variant, the hidden layers of the regression network over many fused ops.
+//   layer256_dma1_kernel: the layer h' = ReLU([h | mean_pred(h) | mean_succ(h)] W + b) (neighbourhood
+//     encoding of Sec. 3.3.1 with uniform coefficients) for batches whose rows have at most one
+//     neighbour per direction in-kernel (fused-op subgraphs): the mean of such a row is a row that
+//     already lies in memory, so four further waves copy it into the A ring as well.
+// The layer with three gather slots (candidate modules) is the sixteen-wave kernel of its own file.
+// Also here: the descriptor builder and the pre-pass (means of rows with longer lists) of the one-slot
+// layer.
 #include <type_traits>
 
 #include "common.h"
@@ -88,37 +84,11 @@ __device__ __forceinline__ void add8(float* acc, const v4u x, unsigned one) {   
 
 extern __shared__ __attribute__((aligned(16))) char dc_l256_smem[];
 
-// The data-moving waves keep two jobs' worth of loads in flight while they reduce a third.
-// The compiler's own wait-count bookkeeping gives up on that (it falls back to waiting for
-// every outstanding load), so their vector loads are issued through these helpers, which the
-// compiler does not track, and the waits are placed by hand.  Loads return in issue order,
-// so "at most N newer loads outstanding" is exactly what s_waitcnt vmcnt(N) waits for.
-__device__ __forceinline__ v4u load16_async(const char* uniform_base, unsigned byte_off) {
-  v4u r;
-  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(r) : "v"(byte_off), "s"(uniform_base) : "memory");
-  return r;
-}
-__device__ __forceinline__ v4u load16_async(const char* addr) {
-  v4u r;
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(addr) : "memory");
-  return r;
-}
-__device__ __forceinline__ v4i load16i_async(const v4i* addr) {
-  v4i r;
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(addr) : "memory");
-  return r;
-}
 // 16 bytes per lane from global memory straight into LDS (no registers): lane l of the wave
-// writes lds_base + 16*l.  Untracked by the compiler as well; waited for with wait_vm<N>().
+// writes lds_base + 16*l.  Not tracked by the compiler: waited for by hand (wait_vm_times4).  Loads
+// return in issue order, so "at most N newer loads outstanding" is what s_waitcnt vmcnt(N) waits for.
 __device__ __forceinline__ void load16_to_lds(const void* gaddr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14;
-  // the other two counters are left at their maximum (no wait)
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
-  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 // s_waitcnt vmcnt(4 * n4), n4 in 0..5 (wave-uniform), as one statement: separate wait sites in
 // an if/else around the tile epilogue made the register allocator spill.
@@ -155,197 +125,6 @@ __device__ __forceinline__ void wait_vm_times4(int n4) {
       : "s"(n4)
       : "scc", "memory");
 }
-// One step of a data-moving wave: request the rows of job s+3 into register stage Q and
-// reduce job s+1 (stage (Q+1)%3, requested two steps ago) into its LDS ring slot.  The first
-// DCH jobs of a tile are the node's own rows: those go from global memory straight into
-// LDS (issued by the MFMA waves) and cost this wave nothing.  A gather job issues exactly
-// 4 x U row loads and every step exactly RQ descriptor loads, with no branch around a
-// single vector load, so the in-order load counter says how many newer loads may still be
-// in flight when an older one is needed.
-// Row addresses are 32-bit byte offsets from a per-tile base row: a graph has fewer
-// than 65536 nodes, so every neighbour lies within 65536 rows of the tile.
-struct MoverConst {
-  const char* h;        // activations of this layer
-  const char* hin;      // pre-pass means (rows with long lists), predecessors / successors
-  const char* hout;
-  const v4i* desc_in;
-  const v4i* desc_out;
-  char* smem;
-  int ntot, tile0, per, ar, ach, aoff;
-};
-
-// 1 if job J (clamped to the last job, as the loads are) gathers neighbour rows
-template <int DCH>
-__device__ __forceinline__ int is_gather(int J, int S) { return (min(J, S - 1) % Shape<DCH>::NK) >= DCH; }
-
-// s_waitcnt vmcnt(BASE + PER * n), n in 0..2, chosen at run time (wave-uniform)
-template <int BASE, int PER>
-__device__ __forceinline__ void wait_vm_sel(int n) {
-  if (n == 2) wait_vm<BASE + 2 * PER>();
-  else if (n == 1) wait_vm<BASE + PER>();
-  else wait_vm<BASE>();
-}
-// Names registers as operands of an empty statement placed after a wait, so that no use of
-// them can be scheduled before it.
-__device__ __forceinline__ void pin(v4u (&a)[4][3]) {
-  asm volatile("" : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]),
-                    "+v"(a[2][0]), "+v"(a[2][1]), "+v"(a[2][2]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(a[3][2]));
-}
-__device__ __forceinline__ void pin(v4u (&a)[4][1]) {
-  asm volatile("" : "+v"(a[0][0]), "+v"(a[1][0]), "+v"(a[2][0]), "+v"(a[3][0]));
-}
-__device__ __forceinline__ void pin(v4i& d) { asm volatile("" : "+v"(d)); }
-
-// Descriptors of job (tile starting at row m, chunk kc), request r of RQ.  Table mode: the
-// job files slot kc of its tile (direction kc >> 2, item kc & 3; chunks 8.. repeat slot 7,
-// unused).  Direct mode: item r of the job's own direction (the node's own chunk has
-// none: it repeats the predecessors', unused).
-template <int DCH>
-__device__ __forceinline__ const v4i* desc_addr(const MoverConst& c, int m, int kc, int r) {
-  int dir, item;
-  if (Shape<DCH>::DIRECT) {
-    dir = kc / DCH == 2;
-    item = r;
-  } else {
-    const int k = min(kc, 7);
-    dir = k >> 2;
-    item = k & 3;
-  }
-  const int row = min(m + c.ar + 32 * item, c.ntot - 1);
-  return (dir ? c.desc_out : c.desc_in) + row;
-}
-
-// Q = (s + 3) % 3 is the register stage that receives job s+3; job s+1 sits in stage
-// (Q + 1) % 3 and job s+2 (in flight) in stage (Q + 2) % 3.
-template <int DCH, int Q, int U>
-__device__ __forceinline__ void mover_step(int s, int S, v4u (&ax)[3][4][U], int (&sdeg)[3][4],
-                                           unsigned (&off)[2][4][U], int (&dgs)[2][4],
-                                           v4i (&dq)[3][Shape<DCH>::RQ], const MoverConst c) {
-  static_assert(U == 1 || U == 3, "one or three slots");
-  constexpr int NK = Shape<DCH>::NK, RQ = Shape<DCH>::RQ;
-  constexpr unsigned kRowBytes = Shape<DCH>::ROWB;
-  constexpr int QC = (Q + 1) % 3;
-  const int g1 = is_gather<DCH>(s + 1, S), g2 = is_gather<DCH>(s + 2, S), g3 = is_gather<DCH>(s + 3, S);
-  {
-    const int J = min(s + 3, S - 1);        // clamped: the last job's loads are simply repeated
-    const int ti = J / NK, kc = J - ti * NK;
-    const int m0 = (c.tile0 + ti * c.per) * kBM;
-    const int base_row = max(m0 - 65536, 0);
-    const unsigned colb = (unsigned)c.ach * 16u;
-    // The descriptors requested two steps ago are needed now.  Newer than the last of them:
-    // the row loads of its own step (job s+1) and all of the next step (its descriptors and
-    // job s+2).
-    wait_vm_sel<RQ, 4 * U>(g1 + g2);
-#pragma unroll
-    for (int r = 0; r < RQ; ++r) pin(dq[QC][r]);
-    if (!Shape<DCH>::DIRECT) {
-      // table mode: file the one descriptor; neighbour ids become byte offsets
-      const v4i dd = dq[QC][0];
-      const unsigned f0 = (unsigned)(dd.x - base_row) * kRowBytes + colb;
-      const unsigned f1 = (unsigned)(dd.y - base_row) * kRowBytes + colb;
-      const unsigned f2 = (unsigned)(dd.z - base_row) * kRowBytes + colb;
-      const int fd = dd.w;
-#define DC_FILE(dd_, ii_) { off[dd_][ii_][0] = f0; if constexpr (U == 3) { off[dd_][ii_][U - 2] = f1; off[dd_][ii_][U - 1] = f2; } dgs[dd_][ii_] = fd; }
-      switch (kc) {
-        case 0: DC_FILE(0, 0) break;
-        case 1: DC_FILE(0, 1) break;
-        case 2: DC_FILE(0, 2) break;
-        case 3: DC_FILE(0, 3) break;
-        case 4: DC_FILE(1, 0) break;
-        case 5: DC_FILE(1, 1) break;
-        case 6: DC_FILE(1, 2) break;
-        case 7: DC_FILE(1, 3) break;
-        default: break;
-      }
-#undef DC_FILE
-    }
-    v4i dnow[4];                              // direct mode: this job's descriptors
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dnow[i] = dq[QC][Shape<DCH>::DIRECT ? i : 0];
-    {
-      // request the descriptors that job J+2 will need
-      const int J2 = min(J + 2, S - 1);
-      const int t2 = J2 / NK, c2 = J2 - t2 * NK;
-      const int m2 = (c.tile0 + t2 * c.per) * kBM;
-#pragma unroll
-      for (int r = 0; r < RQ; ++r) dq[Q][r] = load16i_async(desc_addr<DCH>(c, m2, c2, r));
-    }
-    // Reduce job s+1 and request the rows of job s+3 item by item, so that the arithmetic of
-    // one fills the time the load unit takes to accept the requests of the other (a request
-    // stalls the wave while the unit's queue is full).  The rows of job s+1 must have landed
-    // before the first item: newer than them are the descriptors and rows of the step before
-    // and this step's descriptors.
-    const bool reduce = s + 1 >= 0 && s + 1 < S && g1;
-    if (reduce) {
-      wait_vm_sel<2 * RQ, 4 * U>(g2);
-      pin(ax[QC]);
-    }
-    const int seg = kc / DCH;
-    const unsigned kcoff = (unsigned)(kc - seg * DCH) * 128u;               // 64 columns = 128 bytes
-    const char* hb = c.h + (size_t)base_row * kRowBytes;                    // uniform
-    const char* pb = (seg == 2 ? c.hout : c.hin) + (size_t)base_row * kRowBytes;
-    char* dst = c.smem + ((s + 1 + 3) % 3) * kABytes + c.aoff;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (reduce) {
-        // slots of the row that count (0..3; a row left to the pre-pass has one: its finished mean)
-        const int ns = sdeg[QC][i] & 3;
-        v4u o;
-        if constexpr (U == 3) {
-          // branch-free mean in ascending neighbour order: slot u counts iff u < ns; the scale is
-          // picked as a bit pattern so that the choice stays a chain of selects
-          const unsigned k1 = ns > 1 ? 0x3F80u : 0u, k2 = ns > 2 ? 0x3F80u : 0u;   // bf16 1.0 or 0
-          unsigned scb = ns == 1 ? 0x3F800000u : 0u;
-          scb = ns == 2 ? 0x3F000000u : scb;
-          scb = ns == 3 ? 0x3EAAAAABu : scb;                                        // 1/3 rounded to nearest
-          const float sc = __uint_as_float(scb);
-          const v4u x0 = ax[QC][i][0], x1 = ax[QC][i][U - 2], x2 = ax[QC][i][U - 1];
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            float lo = __uint_as_float(x0[w] << 16);
-            float hi = __uint_as_float(x0[w] & 0xFFFF0000u);
-            bf16_pair_add(lo, hi, x1[w], k1);
-            bf16_pair_add(lo, hi, x2[w], k2);
-            o[w] = pack_bf16x2(lo * sc, hi * sc);     // one slot: x * 1.0 repacks to the same bf16 values
-          }
-        } else {
-          // one slot: the mean of a single neighbour is that neighbour's row, longer lists
-          // bring their finished mean, an empty list gives zero
-          const v4u x0 = ax[QC][i][0];
-          o = ns > 0 ? x0 : v4u{0u, 0u, 0u, 0u};
-        }
-        *reinterpret_cast<v4u*>(dst + 32 * i * kARow) = o;    // rows ar + 32 i share the swizzle of row ar
-      }
-      if (g3) {
-        unsigned g0, ga = 0u, gb = 0u;
-        int dg;
-        if (Shape<DCH>::DIRECT) {
-          g0 = (unsigned)(dnow[i].x - base_row) * kRowBytes + colb;
-          ga = (unsigned)(dnow[i].y - base_row) * kRowBytes + colb;
-          gb = (unsigned)(dnow[i].z - base_row) * kRowBytes + colb;
-          dg = dnow[i].w;
-        } else {
-          g0 = seg == 2 ? off[1][i][0] : off[0][i][0];
-          if constexpr (U == 3) {
-            ga = seg == 2 ? off[1][i][U - 2] : off[0][i][U - 2];
-            gb = seg == 2 ? off[1][i][U - 1] : off[0][i][U - 1];
-          }
-          dg = seg == 2 ? dgs[1][i] : dgs[0][i];
-        }
-        sdeg[Q][i] = dg;                      // travels with the rows: the filed copy may be replaced before they are reduced
-        // rows left to the pre-pass (code above 3) have all their offsets on the row itself (see
-        // build_desc): slot 0 then reads the row's finished mean from the pre-pass buffer
-        const char* b0 = dg > 3 ? pb : hb;
-        ax[Q][i][0] = load16_async(b0 + (g0 + kcoff));
-        if constexpr (U == 3) {
-          ax[Q][i][U - 2] = load16_async(hb, ga + kcoff);
-          ax[Q][i][U - 1] = load16_async(hb, gb + kcoff);
-        }
-      }
-    }
-  }
-}
-
 // One step of an MFMA wave: request the B chunk of job s+2 and, if that job is one of the
 // node's own chunks, its A chunk as well (both straight into their LDS ring slots), run the
 // MFMAs of job s, make sure everything requested one step ago has landed and, at the end of
@@ -536,13 +315,14 @@ __device__ __forceinline__ void mfma_step(int s, int S, f32x16 (&acc)[2][4], con
   }
 }
 
-template <int DCH, bool DENSE, int U = kU>
-__global__ __launch_bounds__(kNT) void layer256_kernel(
-    const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
-    const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
-    const float* __restrict__ bias, u16* __restrict__ out, const int* __restrict__ node_off, int C,
-    const int* __restrict__ status) {
-  constexpr int NK = Shape<DCH, DENSE>::NK, RQ = Shape<DCH>::RQ;
+// The plain product out = h W (bias == nullptr) or ReLU(h W + bias): K = d, every chunk comes from global
+// memory by direct copy.  Waves 0-3 run the multiplying steps; waves 4-7 have nothing to move and only
+// keep step with the barriers (the workgroup keeps the shape of the layer kernel, whose LDS plan it shares).
+template <int DCH>
+__global__ __launch_bounds__(kNT) void layer256_dense_kernel(
+    const u16* __restrict__ h, const u16* __restrict__ Wp, const float* __restrict__ bias, u16* __restrict__ out,
+    const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  constexpr int NK = Shape<DCH, true>::NK;
   if (status[0] != 0) return;
   char* smem = dc_l256_smem;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -553,14 +333,11 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
   const int tpx = (ntiles + 7) >> 3;
   const int lim = min(tpx, ntiles - xcd * tpx);
   const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
-  const int S = nt_wg * NK;                 // steps of this workgroup (a multiple of 3 unless DENSE)
-
+  const int S = nt_wg * NK;                 // steps of this workgroup
   if (S == 0) return;                       // no tile for this workgroup (uniform)
-  // Both kinds of wave run S + 3 steps (s = -3 .. S-1) with one barrier per step.  Waves are
-  // dealt to the four SIMDs round-robin, so every SIMD hosts one wave of each kind.
+  // All waves pass S + 3 barriers (steps -3 .. S-1).
   const int role_wave = wave & 3;
   if (wave < 4) {
-    // =========================== MFMA waves ===========================================
     f32x16 acc[2][4];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -585,71 +362,14 @@ __global__ __launch_bounds__(kNT) void layer256_kernel(
     mc.lh = lane >> 5;
     mc.lane = lane;
     mc.sw = ((lane & 31) >> 1) & 7;
-    mc.wave = __builtin_amdgcn_readfirstlane(role_wave);   // scalar: the LDS base of a DMA load must be uniform
-    __syncthreads();                          // step -3: only the data-moving waves work
+    mc.wave = __builtin_amdgcn_readfirstlane(role_wave);   // scalar: the LDS base of a direct copy must be uniform
+    __syncthreads();                          // step -3
     for (int s = -2; s < S; ++s) {
-      mfma_step<DCH, DENSE>(s, S, acc, mc);
+      mfma_step<DCH, true>(s, S, acc, mc);
       __syncthreads();
     }
-  } else if (DENSE) {
-    for (int s = -3; s < S; ++s) __syncthreads();            // nothing to gather: keep step with the barriers
   } else {
-    // =========================== data-moving waves ====================================
-    const int lt = role_wave * 64 + lane;
-    unsigned off[2][4][U];                   // byte offsets of the gathered rows [direction][item][slot]
-    int dgs[2][4];                           // degrees [direction][item]
-    v4u ax[3][4][U];                         // rows in flight [stage][item][slot]
-    int sdeg[3][4];                          // their degrees
-    v4i dq[3][RQ];                           // descriptors in flight
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      dgs[0][i] = 0;
-      dgs[1][i] = 0;
-#pragma unroll
-      for (int q = 0; q < 3; ++q) sdeg[q][i] = 0;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        off[0][i][u] = 0u;
-        off[1][i][u] = 0u;
-        ax[0][i][u] = v4u{0u, 0u, 0u, 0u};
-        ax[1][i][u] = v4u{0u, 0u, 0u, 0u};
-        ax[2][i][u] = v4u{0u, 0u, 0u, 0u};
-      }
-    }
-    MoverConst mc;
-    mc.h = reinterpret_cast<const char*>(h);
-    mc.hin = reinterpret_cast<const char*>(hin_heavy);
-    mc.hout = reinterpret_cast<const char*>(hout_heavy);
-    mc.desc_in = desc_in;
-    mc.desc_out = desc_out;
-    mc.smem = smem;
-    mc.ntot = ntot;
-    mc.tile0 = xcd * tpx + slot;
-    mc.per = per;
-    mc.ar = lt >> 3;                         // rows ar + 32*i, 16-byte column ach of the chunk
-    mc.ach = lt & 7;
-    mc.aoff = swz(mc.ar, mc.ach);
-    {
-      // the descriptors that jobs 0 and 1 file have no earlier step to be requested in:
-      // step -3 files stage 1, step -2 files stage 2
-      const int m = mc.tile0 * kBM;
-#pragma unroll
-      for (int r = 0; r < RQ; ++r) {
-        dq[0][r] = v4i{0, 0, 0, 0};
-        dq[1][r] = *desc_addr<DCH>(mc, m, 0, r);
-        dq[2][r] = *desc_addr<DCH>(mc, m, 1, r);
-      }
-    }
-    __builtin_amdgcn_s_waitcnt(0);           // nothing of the set-up may still be in flight
-
-    for (int s = -3; s < S; s += 3) {        // S + 3 is a multiple of 3
-      mover_step<DCH, 0, U>(s, S, ax, sdeg, off, dgs, dq, mc);
-      __syncthreads();
-      mover_step<DCH, 1, U>(s + 1, S, ax, sdeg, off, dgs, dq, mc);
-      __syncthreads();
-      mover_step<DCH, 2, U>(s + 2, S, ax, sdeg, off, dgs, dq, mc);
-      __syncthreads();
-    }
+    for (int s = -3; s < S; ++s) __syncthreads();
   }
 }
 
@@ -929,8 +649,8 @@ static_assert(kU == 3, "a descriptor holds three neighbour ids and the degree");
 static int slots_of(const GnnArgs& a) { return a.gather_slots == 1 ? 1 : kU; }
 
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s) {
-  // the sixteen-wave layer kernel takes its descriptors sorted per tile
-  if (slots_of(a) == kU && !a.layer_v1) return launch_build_desc_sorted(a, s);
+  // the sixteen-wave layer kernel (three slots) takes its descriptors sorted per tile
+  if (slots_of(a) == kU) return launch_build_desc_sorted(a, s);
   hipLaunchKernelGGL(build_desc_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
                      a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.node_off, a.n_cand,
                      slots_of(a), a.status);
@@ -939,68 +659,41 @@ hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s) {
 
 namespace {
 
-template <int DCH, int U>
-hipError_t launch_shape(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out, Profiler* prof,
-                        hipStream_t s) {
+// One layer with one gather slot: the pre-pass for rows with two or more neighbours, then the kernel whose
+// data-moving waves copy every mean row into LDS.
+template <int DCH>
+hipError_t launch_one_slot(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
+                           Profiler* prof, hipStream_t s) {
   static bool attr_done = false;
-  auto kern = layer256_kernel<DCH, false, U>;
+  auto kern = layer256_dma1_kernel<DCH>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
+  if (!a.zero_row) return hipErrorInvalidValue;
   const u16* hh = static_cast<const u16*>(h);
   if (prof) prof->begin(kFamHeavy, s);
   hipLaunchKernelGGL(aggregate_heavy_kernel<8 * DCH>, dim3(a.n_cu * 8), dim3(256), 0, s, hh, a.in_rowptr, a.in_col,
                      a.out_rowptr, a.out_col, static_cast<u16*>(a.agg[0]), static_cast<u16*>(a.agg[1]), a.node_off,
-                     a.n_cand, U, a.status);
+                     a.n_cand, 1, a.status);
   if (prof) prof->end(s);
   if (prof) prof->begin(DCH == 4 ? kFamLayer256 : kFamLayer64, s);
   const int grid = ((a.n_cu + 7) / 8) * 8;
-  if constexpr (U == kU) {
-    if (!a.layer_v1) {
-      hipError_t e = launch_layer256w(h, 64 * DCH, a, Wl, bias, out, s);
-      if (prof) prof->end(s);
-      return e;
-    }
-  }
-  if constexpr (U == 1) {
-    // one slot: the rows go to LDS by DMA (a context switched to the register path passes no zero row and
-    // keeps the register path)
-    static bool dma_attr = false, dma_ok = false;
-    auto kdma = layer256_dma1_kernel<DCH>;
-    if (!dma_attr) {
-      dma_attr = true;
-      dma_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kdma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   kLdsTotal) == hipSuccess;
-    }
-    if (dma_ok && a.zero_row) {
-      hipLaunchKernelGGL(kdma, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
-                         static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
-                         static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(a.zero_row),
-                         static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand, a.status);
-      if (prof) prof->end(s);
-      return hipGetLastError();
-    }
-  }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, hh, static_cast<const u16*>(a.agg[0]),
                      static_cast<const u16*>(a.agg[1]), static_cast<const v4i*>(a.desc[0]),
-                     static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(Wl), bias, static_cast<u16*>(out),
-                     a.node_off, a.n_cand, a.status);
+                     static_cast<const v4i*>(a.desc[1]), static_cast<const u16*>(a.zero_row),
+                     static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand, a.status);
   if (prof) prof->end(s);
   return hipGetLastError();
 }
-
-}  // namespace
-
-namespace {
 
 template <int DCH>
 hipError_t launch_dense_shape(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                               hipStream_t s) {
   static bool attr_done = false;
-  auto kern = layer256_kernel<DCH, true>;
+  auto kern = layer256_dense_kernel<DCH>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -1008,9 +701,8 @@ hipError_t launch_dense_shape(const void* h, const GnnArgs& a, const void* Wl, c
     attr_done = true;
   }
   const int grid = ((a.n_cu + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, static_cast<const u16*>(h), nullptr, nullptr, nullptr,
-                     nullptr, static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand,
-                     a.status);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, static_cast<const u16*>(h),
+                     static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand, a.status);
   return hipGetLastError();
 }
 
@@ -1024,12 +716,21 @@ hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* W
   return hipErrorInvalidValue;
 }
 
+// One layer for H = 256, d = 256 or 64, bf16, after launch_build_desc: three gather slots (candidate modules: the
+// pre-pass over the listed long rows, then the sixteen-wave kernel) or one (batches of fused-op subgraphs).
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            Profiler* prof, hipStream_t s) {
-  const bool sparse = slots_of(a) == 1;
-  if (d == 256) return sparse ? launch_shape<4, 1>(h, a, Wl, bias, out, prof, s) : launch_shape<4, kU>(h, a, Wl, bias, out, prof, s);
-  if (d == 64) return sparse ? launch_shape<1, 1>(h, a, Wl, bias, out, prof, s) : launch_shape<1, kU>(h, a, Wl, bias, out, prof, s);
-  return hipErrorInvalidValue;
+  if (d != 256 && d != 64) return hipErrorInvalidValue;
+  if (slots_of(a) == 1)
+    return d == 256 ? launch_one_slot<4>(h, a, Wl, bias, out, prof, s) : launch_one_slot<1>(h, a, Wl, bias, out, prof, s);
+  if (prof) prof->begin(kFamHeavy, s);
+  hipError_t e = launch_heavy_means(h, d, a, s);
+  if (prof) prof->end(s);
+  if (e != hipSuccess) return e;
+  if (prof) prof->begin(d == 256 ? kFamLayer256 : kFamLayer64, s);
+  e = launch_layer256w(h, d, a, Wl, bias, out, s);
+  if (prof) prof->end(s);
+  return e;
 }
 
 }  // namespace dc

@@ -513,9 +513,10 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
 __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
     const int* __restrict__ in_rp, const int* __restrict__ in_ci, const int* __restrict__ out_rp,
     const int* __restrict__ out_ci, v4i* __restrict__ desc_in, v4i* __restrict__ desc_out,
+    int* __restrict__ heavy_in, int* __restrict__ heavy_out, int* __restrict__ heavy_cnt,
     const int* __restrict__ node_off, int C, const int* __restrict__ status) {
   if (status[0] != 0) return;
-  __shared__ int cnt[2][4][3];               // [parity][wave][class]
+  __shared__ int cnt[2][4][4];               // [parity][wave][class, and the rows left to the pre-pass]
   const int ntot = node_off[C];
   const int ntiles = (ntot + kBM - 1) / kBM;
   const int t = threadIdx.x, wave = t >> 6, lane = t & 63, dir = t >> 7, r = t & 127;
@@ -536,6 +537,10 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
       if (cls == k) rank = __popcll(m & ((1ull << lane) - 1ull));
       if (lane == 0) cnt[par][wave][k] = __popcll(m);
     }
+    // the rows left to the pre-pass, in ascending order, for the kernel that forms their means
+    const unsigned long long mh = __ballot(dg > 3);
+    const int hrank = __popcll(mh & ((1ull << lane) - 1ull));
+    if (lane == 0) cnt[par][wave][3] = __popcll(mh);
     __syncthreads();                           // the next tile writes the other parity: one barrier per tile
     const int w0 = dir * 2;
     int start = 0;
@@ -552,6 +557,78 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
       d.z = dg > 2 ? ci[s + 2] : d.x;
     }
     (dir ? desc_out : desc_in)[(size_t)tile * kBM + start + rank] = d;
+    const int h0 = cnt[par][w0][3];
+    if (dg > 3) (dir ? heavy_out : heavy_in)[(size_t)tile * kBM + ((wave & 1) ? h0 : 0) + hrank] = v;
+    if (r == 0) heavy_cnt[2 * tile + dir] = h0 + cnt[par][w0 + 1][3];
+  }
+}
+
+// Means of the rows with more than three neighbours, one direction of one tile at a time, from the lists
+// the descriptor kernel leaves: LPR = d / 8 lanes (16 bytes each) serve a row; they fetch eight
+// neighbour ids with one load, hand them round, and keep up to eight neighbour rows in flight; the rows
+// are added in ascending list order in fp32 (first one unpacked exactly), scaled by 1/deg and rounded
+// to bf16: the arithmetic of the layer kernel.  Few workgroups with many loads in flight each, dealt
+// to the XCDs in contiguous runs of tiles: the rows being read at any time belong to half a dozen
+// graphs per XCD and stay in its L2 while the graph's other long lists ask for them again.
+template <int LPR>
+__global__ __launch_bounds__(256) void heavy_means_kernel(
+    const u16* __restrict__ h, const int* __restrict__ in_rp, const int* __restrict__ in_ci,
+    const int* __restrict__ out_rp, const int* __restrict__ out_ci, const int* __restrict__ heavy_in,
+    const int* __restrict__ heavy_out, const int* __restrict__ heavy_cnt, u16* __restrict__ h_in,
+    u16* __restrict__ h_out, const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  constexpr int NSG = 64 / LPR;              // rows a wave serves at a time
+  if (status[0] != 0) return;
+  const int ntot = node_off[C];
+  const int units = 2 * ((ntot + kBM - 1) / kBM);          // (tile, direction)
+  const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sg = lane / LPR, ll = lane % LPR, hb = sg * LPR;
+  const int slot = wave * NSG + sg;          // which of the 4 NSG rows the workgroup has in hand
+  const unsigned one = bf16_one_reg();
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, per_x = gridDim.x >> 3;
+  const int u_begin = (int)((long long)units * xcd / 8), u_end = (int)((long long)units * (xcd + 1) / 8);
+  for (int u = u_begin + j; u < u_end; u += per_x) {
+    const int tile = u >> 1, dir = u & 1;
+    const int n = heavy_cnt[u];
+    const int* list = (dir ? heavy_out : heavy_in) + (size_t)tile * kBM;
+    const int* rp = dir ? out_rp : in_rp;
+    const int* ci = dir ? out_ci : in_ci;
+    for (int k = slot; k < n; k += 4 * NSG) {
+      const int v = list[k];
+      const int s = rp[v], deg = rp[v + 1] - s;
+      float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int b0 = 0; b0 < deg; b0 += 8) {
+        const int nb = min(8, deg - b0);
+        const int mine = ci[s + b0 + (ll < nb ? ll : 0)];
+        int id[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) id[q] = __shfl(mine, hb + (q < nb ? q : 0), 64);
+        v4u x[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if (q < nb) x[q] = h4[(size_t)id[q] * LPR + ll];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          if (q < nb) {
+            if (b0 == 0 && q == 0) {         // the first neighbour: exact unpack
+#pragma unroll
+              for (int w = 0; w < 4; ++w) {
+                a8[2 * w] = __uint_as_float(x[0][w] << 16);
+                a8[2 * w + 1] = __uint_as_float(x[0][w] & 0xFFFF0000u);
+              }
+            } else {
+#pragma unroll
+              for (int w = 0; w < 4; ++w) bf16_pair_add(a8[2 * w], a8[2 * w + 1], x[q][w], one);
+            }
+          }
+        }
+      }
+      const float sc = 1.0f / (float)deg;
+      v4u o;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) o[w] = pack_bf16x2(a8[2 * w] * sc, a8[2 * w + 1] * sc);
+      reinterpret_cast<v4u*>(dir ? h_out : h_in)[(size_t)v * LPR + ll] = o;
+    }
   }
 }
 
@@ -577,8 +654,24 @@ hipError_t launch_w(const void* h, const GnnArgs& a, const void* Wl, const float
 
 hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(build_desc_sorted_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
-                     a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.node_off, a.n_cand,
-                     a.status);
+                     a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.heavy[0], a.heavy[1],
+                     a.heavy_cnt, a.node_off, a.n_cand, a.status);
+  return hipGetLastError();
+}
+
+hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_t s) {
+  const int grid = ((a.n_cu + 7) / 8) * 8 * 4;
+  const u16* hh = static_cast<const u16*>(h);
+  if (d == 256)
+    hipLaunchKernelGGL(heavy_means_kernel<32>, dim3(grid), dim3(256), 0, s, hh, a.in_rowptr, a.in_col, a.out_rowptr,
+                       a.out_col, a.heavy[0], a.heavy[1], a.heavy_cnt, static_cast<u16*>(a.agg[0]),
+                       static_cast<u16*>(a.agg[1]), a.node_off, a.n_cand, a.status);
+  else if (d == 64)
+    hipLaunchKernelGGL(heavy_means_kernel<8>, dim3(grid), dim3(256), 0, s, hh, a.in_rowptr, a.in_col, a.out_rowptr,
+                       a.out_col, a.heavy[0], a.heavy[1], a.heavy_cnt, static_cast<u16*>(a.agg[0]),
+                       static_cast<u16*>(a.agg[1]), a.node_off, a.n_cand, a.status);
+  else
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -631,10 +631,13 @@ def random_labels(seed: int, n: int, n_groups: int, C: int = 1) -> np.ndarray:
 
 
 def with_attention(w: Workload, heads: int, seed: int = 0, std: Optional[float] = None) -> Workload:
-    """The same graphs and candidates evaluated by the attention variant of the estimator."""
+    """The same graphs and candidates evaluated by the attention variant of the estimator.  The last layer
+    of its regression network is taken non-negative (see with_time_like_head): with signed random
+    weights the attention model's predictions on the large configurations are remainders of terms a
+    hundred times their size, which no bf16 storage of the activations resolves."""
     m = ModelSpec(w.model.F, w.model.H, w.model.L, w.model.dtype, "attention", heads)
-    return Workload(w.name + "-attention", m, w.graphs, w.cand_graph, w.cand_off, w.group_id,
-                    make_weights(m, seed, std), w.note)
+    return with_time_like_head(Workload(w.name + "-attention", m, w.graphs, w.cand_graph, w.cand_off, w.group_id,
+                                        make_weights(m, seed, std), w.note))
 
 
 def with_time_like_head(w: Workload) -> Workload:

@@ -149,7 +149,7 @@ def test_fused_op_batch_is_exact(B):
     ev.close()
 
 
-@pytest.mark.parametrize("case", ["contracted-11", "contracted-12", "contracted-14", "cfg2-H64", "cfg3-H256",
+@pytest.mark.parametrize("case", ["contracted-11", "contracted-12", "contracted-16", "cfg2-H64", "cfg3-H256",
                                   "cfg2-H96"])
 def test_loss_estimates_and_gradient(B, case):
     import torch
