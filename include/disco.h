@@ -210,6 +210,32 @@ dc_status dc_gnn_forward(dc_ctx* ctx, const dc_batch* in, float* pred, void* str
 dc_status dc_simulate(dc_ctx* ctx, const dc_batch* in, const float* op_time, const float* ar_size, float ar_c,
                       float ar_d, float* cost, void* stream);
 
+/* dc_simulate for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It takes no context and calls neither hipMalloc nor
+ * hipFree nor any allocating routine: the status words and the working sets of modules too large for
+ * LDS live in a device array that is part of the library itself (16 MiB + 256 bytes, held by every GPU
+ * the library runs on until the process ends).  Arguments as for dc_simulate, with
+ *   in                a caller's batch (node_off, out_rowptr, out_col, in_rowptr, in_col, n_cand,
+ *                     cap_nodes and cap_edges = the lengths of the node and edge arrays); validated
+ *                     on the device as dc_simulate does
+ *   max_module_nodes, max_module_edges   the caller's bound on the largest module of the batch.
+ *                     Limit: 24 bytes per node + 2 bytes per edge must not exceed 256 KiB (e.g.
+ *                     9000 nodes with 20000 edges); beyond it the call returns DC_ERR_CAPACITY with
+ *                     nothing enqueued (dc_simulate_static_error says why).  A module that exceeds
+ *                     what the caller stated, but not the limit, is still simulated; one that
+ *                     exceeds the limit gets cost +infinity and the status DC_ERR_CAPACITY
+ *   dev_status        dev [1] or null: receives the first device-detected error of this call
+ *                     (DC_OK, DC_ERR_BAD_GRAPH, DC_ERR_CAPACITY)
+ * Results are those of dc_simulate, bit for bit.  Asynchronous on `stream`; the current HIP device is
+ * used.  All calls on one GPU share the one array, which keeps the contents of the last call (what
+ * must start at zero is cleared by a kernel at the start of each call): calls that overlap on one GPU,
+ * on different streams or from different threads, race -- serialise them.                          */
+dc_status dc_simulate_static(const dc_batch* in, int32_t max_module_nodes, int32_t max_module_edges,
+                             const float* op_time, const float* ar_size, float ar_c, float ar_d, float* cost,
+                             int32_t* dev_status, void* stream);
+/* Detail of the last error dc_simulate_static returned on this thread; owned by the library. */
+const char* dc_simulate_static_error(void);
+
 /* Profiled data of the base graphs (Sec. 3.1, Profiler), host fp32 arrays over all base nodes in
  * the order of X in dc_set_base_graphs:
  *   op_time  execution time of each individual op (ignored for all-reduce nodes)

@@ -96,6 +96,10 @@ def lib():
         L.dc_gnn_forward.argtypes = [vp, C.POINTER(DcBatch), vp, vp]
         L.dc_eval_candidates.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.dc_simulate.argtypes = [vp, C.POINTER(DcBatch), vp, vp, C.c_float, C.c_float, vp, vp]
+        L.dc_simulate_static.argtypes = [C.POINTER(DcBatch), i32, i32, vp, vp, C.c_float, C.c_float, vp, vp, vp]
+        L.dc_simulate_static.restype = i32
+        L.dc_simulate_static_error.argtypes = []
+        L.dc_simulate_static_error.restype = C.c_char_p
         L.dc_set_profile.argtypes = [vp, vp, vp, vp]
         L.dc_module_times.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp, vp, vp]
         L.dc_cost_candidates.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp]
@@ -225,6 +229,16 @@ def dc_get_weights(ctx, W_layers: np.ndarray, b_layers: np.ndarray, head: np.nda
 
 def dc_check(ctx, stream: int = 0) -> int:
     return lib().dc_check(ctx, stream)
+
+
+def dc_simulate_static(batch: DcBatch, max_module_nodes: int, max_module_edges: int, op_time_ptr, ar_size_ptr,
+                       ar_c: float, ar_d: float, cost_ptr, dev_status_ptr, stream: int = 0) -> int:
+    return lib().dc_simulate_static(C.byref(batch), max_module_nodes, max_module_edges, op_time_ptr, ar_size_ptr,
+                                    ar_c, ar_d, cost_ptr, dev_status_ptr, stream)
+
+
+def dc_simulate_static_error() -> str:
+    return lib().dc_simulate_static_error().decode()
 
 
 def dc_select_kernels(ctx, which: int) -> int:

@@ -427,6 +427,14 @@ __global__ void empty_batch_kernel(int* node_off, int* edge_off, int* orp, int* 
 
 }  // namespace
 
+namespace dc {
+void launch_check_batch(const int* node_off, int n_cand, long long max_nodes, long long cap_edges, const int* out_rp,
+                        const int* out_ci, const int* in_rp, const int* in_ci, int* status, int n_cu, hipStream_t s) {
+  hipLaunchKernelGGL(check_batch_kernel, dim3(n_cu * 4), dim3(256), 0, s, node_off, n_cand, max_nodes, cap_edges, out_rp,
+                     out_ci, in_rp, in_ci, status);
+}
+}  // namespace dc
+
 extern "C" {
 
 size_t dc_workspace_bytes(const dc_config* cfg) {

@@ -277,6 +277,10 @@ hipError_t launch_adam(float* theta, const float* grad, float* m, float* v, long
                        float beta2, float eps, double c1, double c2, const int* status, hipStream_t s);
 
 __global__ void reset_status_kernel(int* status);
+// Device-side validation of a caller's batch (sizes within the capacities, graphs below 65536 nodes, row
+// pointers ascending, neighbours inside their own graph); sets the status word on a violation.
+void launch_check_batch(const int* node_off, int n_cand, long long max_nodes, long long cap_edges, const int* out_rp,
+                        const int* out_ci, const int* in_rp, const int* in_ci, int* status, int n_cu, hipStream_t s);
 
 // fp32 -> bf16, round to nearest even, in hardware (v_cvt_pk_bf16_f32): a in the low half
 __device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {

@@ -20,6 +20,8 @@
 // the rules fix, so the result does not depend on the implementation.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace dc {
@@ -179,4 +181,113 @@ hipError_t launch_simulate(const SimArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---- the simulator for callers that cannot allocate ------------------------------------------------
+namespace {
+
+constexpr int kStaticLdsBytes = 80 * 1024;              // modules up to this size are walked in LDS
+constexpr int kStaticSlices = 64;                       // workgroups of the global-memory walk
+constexpr size_t kStaticSliceBytes = 256 * 1024;        // working set of the largest module accepted
+constexpr size_t kStaticHeaderBytes = 256;              // status words
+// Device memory of the library itself: the status words and the slices of the global-memory walk.
+// In host code this name only stands for the symbol; the address on each device comes from
+// hipGetSymbolAddress (static_scratch below) and is what every kernel and launch receives.
+static __device__ __align__(256) char dc_sim_static_scratch[kStaticHeaderBytes + kStaticSlices * kStaticSliceBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+char* g_static_ptr[kMaxDevices] = {};
+int g_static_cus[kMaxDevices] = {};
+
+// The scratch array's address on the current device (every device holds its own copy), looked up once.
+hipError_t static_scratch(char** ptr, int* n_cu) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(dc_sim_static_scratch));
+    if (e != hipSuccess) return e;
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    g_static_cus[dev] = cus > 0 ? cus : 1;
+    g_static_ptr[dev] = static_cast<char*>(p);
+  }
+  *ptr = g_static_ptr[dev];
+  *n_cu = g_static_cus[dev];
+  return hipSuccess;
+}
+
+__global__ void export_status_kernel(const int* __restrict__ status, int* __restrict__ out) { out[0] = status[0]; }
+
+thread_local const char* t_static_error = "";
+
+}  // namespace
 }  // namespace dc
+
+extern "C" dc_status dc_simulate_static(const dc_batch* in, int32_t max_module_nodes, int32_t max_module_edges,
+                                        const float* op_time, const float* ar_size, float ar_c, float ar_d, float* cost,
+                                        int32_t* dev_status, void* stream) {
+  using namespace dc;
+  t_static_error = "";
+  if (!in || in->n_cand < 0 || max_module_nodes < 0 || max_module_edges < 0) {
+    t_static_error = "null batch or negative size";
+    return DC_ERR_INVALID_ARG;
+  }
+  if (in->n_cand == 0) return DC_OK;
+  if (!cost || !op_time || !ar_size || !in->node_off || !in->out_rowptr || !in->out_col || !in->in_rowptr || !in->in_col) {
+    t_static_error = "null array";
+    return DC_ERR_INVALID_ARG;
+  }
+  if (max_module_nodes >= 65536) {
+    t_static_error = "a module has fewer than 65536 nodes";
+    return DC_ERR_CAPACITY;
+  }
+  if (sim_bytes(max_module_nodes, max_module_edges) > kStaticSliceBytes) {
+    t_static_error = "the largest module needs more than the 256 KiB working set this entry point holds: "
+                     "24 bytes per node + 2 bytes per edge; use dc_simulate";
+    return DC_ERR_CAPACITY;
+  }
+  char* scratch = nullptr;
+  int n_cu = 0;
+  hipError_t e = static_scratch(&scratch, &n_cu);
+  if (e != hipSuccess) {
+    t_static_error = hipGetErrorString(e);
+    return DC_ERR_HIP;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int* status = reinterpret_cast<int*>(scratch);
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, status);          // a fill kernel, not a memset
+  launch_check_batch(in->node_off, in->n_cand, (long long)in->cap_nodes, (long long)in->cap_edges, in->out_rowptr,
+                     in->out_col, in->in_rowptr, in->in_col, status, n_cu, s);
+  SimArgs a;
+  a.n_cand = in->n_cand;
+  a.node_off = in->node_off;
+  a.out_rowptr = in->out_rowptr;
+  a.out_col = in->out_col;
+  a.in_rowptr = in->in_rowptr;
+  a.op_time = op_time;
+  a.ar_size = ar_size;
+  a.ar_c = ar_c;
+  a.ar_d = ar_d;
+  a.cost = cost;
+  a.lds_bytes = kStaticLdsBytes;
+  a.scratch = scratch + kStaticHeaderBytes;
+  a.scratch_stride = kStaticSliceBytes;
+  a.n_slices = kStaticSlices;
+  a.status = status;
+  e = launch_simulate(a, s);
+  if (e == hipSuccess && dev_status) {
+    hipLaunchKernelGGL(export_status_kernel, dim3(1), dim3(1), 0, s, status, dev_status);
+    e = hipGetLastError();
+  }
+  if (e != hipSuccess) {
+    t_static_error = hipGetErrorString(e);
+    return DC_ERR_HIP;
+  }
+  return DC_OK;
+}
+
+extern "C" const char* dc_simulate_static_error(void) { return dc::t_static_error; }
