@@ -493,6 +493,7 @@ def main():
 
     work = algorithmic_work(w, ntot, etot)
     fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
+    contract_parts = {k: round(fam[k][0] / args.steps, 4) for k in ("prep_scan", "contract", "finalize")}
     kernels = {}
     for name, key in (("contract", "contract_all"), ("aggregate", "aggregate"), ("update", "update"),
                       ("fused_layer", "fused_layer"), ("layer256", "layer256"), ("layer256_d64", "layer256_d64"),
@@ -509,6 +510,8 @@ def main():
             k["GB/s"] = round(work[name]["bytes"] / (per_step_ms * 1e-3) / 1e9, 1)
             if "flops" in work[name]:
                 k["TFLOP/s"] = round(work[name]["flops"] / (per_step_ms * 1e-3) / 1e12, 2)
+        if name == "contract":
+            k["parts_ms"] = contract_parts          # candidate check + scan, per-candidate contraction, placement + feature sums
         kernels[name] = k
     # the message-passing layers as a whole: the layer kernels charged with the pre-pass (means of rows with
     # long neighbour lists) and the descriptor build they cannot run without

@@ -12,10 +12,17 @@ Choices of this build where the paper is silent or where this build's scope cuts
   * H_opt starts as H_in; the counter counts evaluated valid candidates.
   * Methods: (i) op fusion and (iii) tensor fusion.  (ii) duplicates an op, which is not a
     partition of the node set, and is left out.
-  * (i) one application: draw a dependency u -> v between two computation ops of the base
-    module uniformly; if its ends are in different groups, the group of u joins the group of v.
-    (The paper draws an op and then one of its predecessors; drawing the dependency needs no
-    rebuilt module between applications.)
+  * (i) one application, as the paper words it (op_draw = "op"): draw a computation op of the
+    CURRENT module uniformly (a group of the labelling, groups taken in the order of their
+    smallest member), then one of its predecessor ops in the current module uniformly (the
+    groups of computation ops with a dependency into it, same order); the predecessor joins
+    the op.  An op without predecessors leaves the module as it is.  One 64-bit draw serves
+    both: the low 32 bits pick the op, the high 32 bits the predecessor.
+    The alternative (op_draw = "dependency", the device driver's default): draw a dependency
+    u -> v between two computation ops of the BASE module uniformly; if its ends are in
+    different groups, the group of u joins the group of v.  It needs no view of the current
+    module between applications, but it is a different distribution: ops with many
+    predecessors are chosen more often, and a dependency inside a group changes nothing.
   * (iii) one application: draw an all-reduce node a and a side uniformly; the nearest bucket on
     that side in production order, if any, joins the bucket of a.
   * Validity: the module must be acyclic (its cost is finite); op kinds that must not be fused
@@ -67,10 +74,40 @@ def op_edges(g) -> Tuple[np.ndarray, np.ndarray]:
     return src[keep], dst[keep]
 
 
-def random_apply(g, labels: np.ndarray, method: int, n: int, seed: int, step: int, child: int) -> np.ndarray:
+def current_op_groups(g, lab: np.ndarray) -> np.ndarray:
+    """Labels of the computation ops of the current module, in the order of their smallest member."""
+    ops = lab[:g.n_op]
+    _, first = np.unique(ops, return_index=True)
+    return ops[np.sort(first)]
+
+
+def current_predecessors(g, lab: np.ndarray, group: int, pred_lists=None) -> np.ndarray:
+    """Labels of the computation ops of the current module with a dependency into `group`, in the
+    order of their smallest member."""
+    src, dst = op_edges(g)
+    into = (lab[dst] == group) & (lab[src] != group)
+    cand = set(lab[src[into]].tolist())
+    order = current_op_groups(g, lab)
+    return np.array([l for l in order if l in cand], dtype=lab.dtype)
+
+
+def random_apply(g, labels: np.ndarray, method: int, n: int, seed: int, step: int, child: int,
+                 op_draw: str = "dependency") -> np.ndarray:
     """RandomApply(H, s, n): method 0 = op fusion, 1 = tensor fusion; draws 1..n of the child's stream."""
     lab = labels.copy()
-    if method == 0:
+    if method == 0 and op_draw == "op":
+        for i in range(n):
+            r = draw(seed, step, child, 1 + i)
+            groups = current_op_groups(g, lab)
+            if len(groups) == 0:
+                continue
+            op = groups[(r & 0xFFFFFFFF) % len(groups)]
+            preds = current_predecessors(g, lab, op)
+            if len(preds) == 0:
+                continue
+            p_ = preds[(r >> 32) % len(preds)]
+            lab[lab == p_] = op
+    elif method == 0:
         src, dst = op_edges(g)
         for i in range(n):
             r = draw(seed, step, child, 1 + i)
@@ -111,7 +148,7 @@ class SearchResult:
 
 def search(g, cost_fn: Callable[[np.ndarray], np.ndarray], alpha: float, beta: int, seed: int,
            max_unchanged: int = 1000, parents: int = 1, max_steps: int = 1 << 30, max_queue: int = 1 << 30,
-           keep_trace: bool = False) -> SearchResult:
+           keep_trace: bool = False, op_draw: str = "dependency") -> SearchResult:
     """cost_fn maps labels [C, n] (int32) to float32 costs [C] (+inf = invalid)."""
     h_in = np.arange(g.n, dtype=np.int32)
     cost_in = np.float32(cost_fn(h_in.reshape(1, -1))[0])
@@ -126,7 +163,7 @@ def search(g, cost_fn: Callable[[np.ndarray], np.ndarray], alpha: float, beta: i
             for s in range(2):
                 j = 2 * pi + s
                 n = draw(seed, step, j, 0) % (beta + 1)
-                kids.append(random_apply(g, lab, s, n, seed, step, j))
+                kids.append(random_apply(g, lab, s, n, seed, step, j, op_draw))
         costs = np.asarray(cost_fn(np.stack(kids).astype(np.int32)), dtype=np.float32)
         for j, c in enumerate(costs):
             res.evaluated += 1

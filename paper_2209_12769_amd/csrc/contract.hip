@@ -503,42 +503,65 @@ __global__ __launch_bounds__(256) void finalize_kernel(BaseGraphs bg, int C, con
     out.out_col[e0 + k] = n0 + tmp.oc[eslot + k];
     out.in_col[e0 + k] = n0 + tmp.ic[eslot + k];
   }
-  // feature sums: members in ascending base index, fp32 accumulation, one rounding
+  // feature sums: members in ascending base index, fp32 accumulation, one rounding.  A thread works on
+  // four (group, column quad) items at a time, so that the dependent loads of an item (list bounds,
+  // member numbers, member rows) overlap with those of three others: the loop is bound by memory latency.
   const int q = F >> 2;
   const float4* X4 = reinterpret_cast<const float4*>(bg.X) + (size_t)bg.gno[b] * q;
   const int* ms = tmp.mstart + nslot;
   const int* mem = tmp.members + coff;
-  for (int i = t; i < G * q; i += T) {
-    const int g = i / q, f = i - g * q;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    int m = ms[g];
-    const int me = ms[g + 1];
-#define DC_ADD(x_) { acc.x += x_.x; acc.y += x_.y; acc.z += x_.z; acc.w += x_.w; }
-    for (; m + 3 < me; m += 4) {               // four member rows in flight, added in member order
-      const int i0 = mem[m], i1 = mem[m + 1], i2 = mem[m + 2], i3 = mem[m + 3];
-      const float4 x0 = X4[(size_t)i0 * q + f], x1 = X4[(size_t)i1 * q + f];
-      const float4 x2 = X4[(size_t)i2 * q + f], x3 = X4[(size_t)i3 * q + f];
-      DC_ADD(x0) DC_ADD(x1) DC_ADD(x2) DC_ADD(x3)
+  const int items = G * q;
+  for (int i0 = t; i0 < items; i0 += 4 * T) {
+    int f[4], m[4], me[4], g[4];
+    float4 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = i0 + j * T;
+      const bool ok = i < items;
+      g[j] = ok ? i / q : 0;
+      f[j] = ok ? i - g[j] * q : 0;
+      m[j] = ok ? ms[g[j]] : 0;
+      me[j] = ok ? ms[g[j] + 1] : 0;
+      acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    if (m + 1 < me) {
-      const int i0 = mem[m], i1 = mem[m + 1];
-      const float4 x0 = X4[(size_t)i0 * q + f], x1 = X4[(size_t)i1 * q + f];
-      DC_ADD(x0) DC_ADD(x1)
-      m += 2;
+    // rounds of up to two members per item, the four items' loads in flight together
+    bool more = true;
+    while (more) {
+      int i0m[4], i1m[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        i0m[j] = m[j] < me[j] ? mem[m[j]] : -1;
+        i1m[j] = m[j] + 1 < me[j] ? mem[m[j] + 1] : -1;
+      }
+      float4 x0[4], x1[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        x0[j] = i0m[j] >= 0 ? X4[(size_t)i0m[j] * q + f[j]] : make_float4(0.f, 0.f, 0.f, 0.f);
+        x1[j] = i1m[j] >= 0 ? X4[(size_t)i1m[j] * q + f[j]] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      more = false;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        // added in member order; a member that does not exist adds nothing (not even +0 to a -0 sum)
+        if (i0m[j] >= 0) { acc[j].x += x0[j].x; acc[j].y += x0[j].y; acc[j].z += x0[j].z; acc[j].w += x0[j].w; }
+        if (i1m[j] >= 0) { acc[j].x += x1[j].x; acc[j].y += x1[j].y; acc[j].z += x1[j].z; acc[j].w += x1[j].w; }
+        m[j] += 2;
+        more |= m[j] < me[j];
+      }
     }
-    if (m < me) {
-      const float4 x0 = X4[(size_t)mem[m] * q + f];
-      DC_ADD(x0)
-    }
-#undef DC_ADD
-    const size_t row = (size_t)(n0 + g);
-    if (kBf16) {
-      uint2 p;
-      p.x = pack_bf16x2(acc.x, acc.y);
-      p.y = pack_bf16x2(acc.z, acc.w);
-      reinterpret_cast<uint2*>(out.Xc)[row * q + f] = p;
-    } else {
-      reinterpret_cast<float4*>(out.Xc)[row * q + f] = acc;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = i0 + j * T;
+      if (i >= items) continue;
+      const size_t row = (size_t)(n0 + g[j]);
+      if (kBf16) {
+        uint2 p;
+        p.x = pack_bf16x2(acc[j].x, acc[j].y);
+        p.y = pack_bf16x2(acc[j].z, acc[j].w);
+        reinterpret_cast<uint2*>(out.Xc)[row * q + f[j]] = p;
+      } else {
+        reinterpret_cast<float4*>(out.Xc)[row * q + f[j]] = acc[j];
+      }
     }
   }
 }

@@ -148,3 +148,69 @@ def test_hand_worked_queue_discipline():
     assert (r.evaluated, r.valid, r.enqueued, r.improved) == tuple(
         int(rec[k][0]) for k in ("evaluated", "valid", "enqueued", "improved"))
     assert r.trace[-1][4] == rec["final_unchanged"][0] and r.trace[-1][5] == rec["final_queue"][0]
+
+
+def star_with_tail(k):
+    """Ops 0..k-1 all feed op k (a centre with k predecessors), and k feeds k+1: k + 2 computation ops."""
+    n = k + 2
+    src = np.concatenate([np.arange(k), [k]])
+    dst = np.concatenate([np.full(k, k), [k + 1]])
+    rp, ci = wl._csr_from_edges(n, src, dst)
+    return wl.BaseGraph(n, n, rp, ci, np.zeros((n, 16), np.float32))
+
+
+def test_the_two_draws_of_op_fusion_have_the_distributions_their_definitions_give():
+    # One application on the unfused star: the paper's draw picks one of the k + 2 ops uniformly and then
+    # one of its predecessors, so the tail dependency (k -> k+1) is fused with probability 1 / (k + 2),
+    # a given leaf with probability 1 / (k + 2) * 1 / k, and nothing happens (a leaf was picked, it has no
+    # predecessor) with probability k / (k + 2).  Drawing a dependency of the base module uniformly fuses
+    # the tail with probability 1 / (k + 1) and always fuses something.
+    k = 4
+    g = star_with_tail(k)
+    h = np.arange(g.n, dtype=np.int32)
+    trials = 6000
+    tail = {"op": 0, "dependency": 0}
+    nothing = {"op": 0, "dependency": 0}
+    leaf0 = {"op": 0, "dependency": 0}
+    for mode in ("op", "dependency"):
+        for s in range(trials):
+            a = osr.random_apply(g, h, 0, 1, 17, s, 0, op_draw=mode)
+            tail[mode] += a[k] == a[k + 1]
+            leaf0[mode] += a[0] == a[k]
+            nothing[mode] += np.array_equal(a, h)
+    def close(count, p):
+        return abs(count / trials - p) < 4.0 * np.sqrt(p * (1 - p) / trials) + 1e-9
+    assert close(tail["op"], 1 / (k + 2)) and close(nothing["op"], k / (k + 2)) and close(leaf0["op"], 1 / (k + 2) / k)
+    assert close(tail["dependency"], 1 / (k + 1)) and nothing["dependency"] == 0 and close(leaf0["dependency"], 1 / (k + 1))
+
+
+def test_the_papers_draw_sees_the_current_module():
+    # after the centre has absorbed leaf 0, the centre's group has k - 1 predecessors left, the module has
+    # k + 1 ops, and the op that is drawn is a group, whichever of its members one looks at
+    k = 3
+    g = star_with_tail(k)
+    h = np.arange(g.n, dtype=np.int32)
+    h[0] = h[k]
+    assert osr.current_op_groups(g, h).tolist() == [k, 1, 2, k + 1]          # order of smallest member: {0, k}, 1, 2, k+1
+    assert osr.current_predecessors(g, h, k).tolist() == [1, 2]
+    assert osr.current_predecessors(g, h, k + 1).tolist() == [k]
+    assert osr.current_predecessors(g, h, 1).tolist() == []
+    # n applications never touch tensors and only ever merge along dependencies of the current module
+    w = wl.make("cfg1", 1)
+    gg = w.graphs[0]
+    hh = np.arange(gg.n, dtype=np.int32)
+    a = osr.random_apply(gg, hh, 0, 12, 3, 0, 0, op_draw="op")
+    assert np.array_equal(a[gg.n_op:], hh[gg.n_op:]) and len(np.unique(a)) < gg.n
+    src, dst = osr.op_edges(gg)
+    for l in np.unique(a[:gg.n_op]):
+        mem = np.nonzero(a == l)[0]
+        if len(mem) > 1:                                                     # connected through fused dependencies
+            inside = (a[src] == l) & (a[dst] == l)
+            assert inside.sum() >= len(mem) - 1
+    # a whole search runs with it and keeps the invariants of the result
+    g2, model, wt = chain_case(8, 0.25)
+    t = g2.X[:, 2].copy()
+    x = np.full(g2.n, -1.0, np.float32)
+    res = osr.search(g2, cost_fn_of(g2, model, wt, t, x, 0.0, 0.0), alpha=1.05, beta=3, seed=2, max_unchanged=60,
+                     op_draw="op")
+    assert res.cost_opt <= res.cost_in and res.evaluated > 0
