@@ -40,14 +40,13 @@ constexpr int kNT = 1024;
 constexpr int kMfmaWaves = 8;
 // LDS: a ring of three A chunks (128 rows x 64 columns, the 16-byte pieces of a row XOR-swizzled so
 // that fragment reads are conflict free and a 1 KB copy is eight whole rows), a ring of three
-// B chunks (64 k x 256 columns of W), one 32 x 32 staging block per multiplying wave.
+// B chunks (64 k x 256 columns of W), the bias vector.
 constexpr int kARow = kBK * 2;                       // 128 bytes
 constexpr int kABytes = kBM * kARow;                 // 16384
 constexpr int kBBytes = (kBK / 8) * kBN * 8 * 2;     // 32768
 constexpr int kBOff = 3 * kABytes;
-constexpr int kStageOff = kBOff + 3 * kBBytes;
-constexpr int kStageBytes = 32 * 32 * 2;             // 2048
-constexpr int kLdsTotal = kStageOff + kMfmaWaves * kStageBytes;
+constexpr int kBiasOff = kBOff + 3 * kBBytes;
+constexpr int kLdsTotal = kBiasOff + kBN * 4;
 static_assert(kLdsTotal <= 160 * 1024, "one workgroup per CU owns the whole LDS");
 
 template <int DCH>
@@ -132,10 +131,9 @@ __device__ __forceinline__ void wait_copies(int n) {
 struct MulCtx {
   const char* Wp;
   const char* h;
-  const float* bias64;  // the 64 bias values of this wave's columns (uniform address)
+  const float* bias64;  // the 64 bias values of this wave's columns, in LDS
   u16* out;
   char* smem;
-  char* stage;
   unsigned lds0;        // LDS byte address of smem
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
 };
@@ -211,10 +209,61 @@ __device__ __forceinline__ void products(int g, f32x16 (&acc)[2][2], const MulCt
   }
 }
 
+// Tile ti of a multiplying wave is complete: bias, ReLU, bf16, and out; the accumulators start the next
+// tile at zero.  A lane holds, of each 32 x 32 block, one row and
+// the columns 8q + 4 (lane / 32) .. + 3 for q = 0..3.  Swapping registers between the two halves
+// of the wave (v_permlane32_swap: lanes 32..63 of the first operand with lanes 0..31 of the second)
+// leaves lanes 0..31 with columns 0..15 of their row and lanes 32..63 with columns 16..31, each as
+// two 16-byte pieces.  A second swap between neighbouring groups of 16 lanes (v_permlane16_swap:
+// lanes 16..31 and 48..63 of the first operand with lanes 0..15 and 32..47 of the second) gives the
+// first piece of every lane to rows 0..15 of the block and the second to rows 16..31, so that one
+// store writes 16 rows of 64 contiguous bytes (a store whose lanes spread over 32 rows costs the
+// compute unit's memory path twice as long).  No staging through LDS, no waits between the stores.
+template <int DCH>
+__device__ __forceinline__ void write_tile(int ti, f32x16 (&acc)[2][2], const MulCtx& c) {
+  const int m0 = (c.tile0 + ti * c.per) * kBM;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int gr = m0 + c.wm * 64 + i * 32 + (c.l32 & 15);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      unsigned p[4][2];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 bq = *reinterpret_cast<const float4*>(c.bias64 + j * 32 + 8 * q + 4 * c.lh);
+        p[q][0] = pack_bf16x2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
+        p[q][1] = pack_bf16x2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const v2u sw = __builtin_amdgcn_permlane32_swap(p[q][e], p[q + 2][e], false, false);
+          p[q][e] = sw.x;
+          p[q + 2][e] = sw.y;
+        }
+#pragma unroll
+      for (int q = 0; q < 4; q += 2)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const v2u sw = __builtin_amdgcn_permlane16_swap(p[q][e], p[q + 1][e], false, false);
+          p[q][e] = sw.x;
+          p[q + 1][e] = sw.y;
+        }
+      u16* dst = c.out + (size_t)gr * kBN + c.wn * 64 + j * 32 + 16 * c.lh + 8 * (c.l32 >> 4);
+      if (gr < c.ntot) *reinterpret_cast<v4u*>(dst) = v4u{p[0][0], p[0][1], p[2][0], p[2][1]};
+      if (gr + 16 < c.ntot) *reinterpret_cast<v4u*>(dst + 16 * kBN) = v4u{p[1][0], p[1][1], p[3][0], p[3][1]};
+    }
+  }
+}
+
 // Step g of a multiplying wave: request the copies for step g + 2 and run the products of step g --
 // the two multiplying waves of a SIMD in opposite order, so that while one stands in the queue of
 // the vector-memory unit with its requests the other one multiplies -- then make sure what was
-// requested one step ago has landed and, at the end of a tile, write the tile out.
+// requested one step ago has landed and, at the end of a tile, write the tile out.  (Writing it out
+// behind the barrier, at the next tile's first step, was measured 2 % slower.)
 template <int DCH>
 __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], const MulCtx& c) {
   constexpr int NK = Shape<DCH>::NK;
@@ -225,48 +274,11 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
   // Everything requested one step ago (needed by step g + 1 after the barrier) is older than this
   // step's n_req copies, and older than the eight stores of a tile that ended one step ago (those
   // were issued after that step's copies: they are counted, not waited for); placed before this
-  // tile's stores so that it never waits for those.
+  // tile's stores so that it never waits for those.  The last tile of the batch may issue fewer
+  // stores; it is the last tile of its workgroup, and nothing is waited for after it.
   const int stores_behind = (g >= 1 && ((g - 1) % NK) == NK - 1) ? 8 : 0;
   wait_copies(__builtin_amdgcn_readfirstlane(n_req + stores_behind));
-  if (g >= 0 && (g % NK) == NK - 1) {
-    // ---- tile finished: bias, ReLU, bf16; one 32 x 32 block at a time through the wave's staging
-    // block (16-byte pieces of a 64-byte row XOR-swizzled), then 16-byte stores of half cache lines
-    const int ti = g / NK;
-    const int m0 = (c.tile0 + ti * c.per) * kBM;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          // uniform addresses: scalar loads, which the vector-memory counter does not see
-          const float4 blo = *reinterpret_cast<const float4*>(c.bias64 + j * 32 + 8 * q);
-          const float4 bhi = *reinterpret_cast<const float4*>(c.bias64 + j * 32 + 8 * q + 4);
-          const float b0 = c.lh ? bhi.x : blo.x, b1 = c.lh ? bhi.y : blo.y;
-          const float b2 = c.lh ? bhi.z : blo.z, b3 = c.lh ? bhi.w : blo.w;
-          v2u p;
-          p.x = pack_bf16x2(fmaxf(acc[i][j][4 * q + 0] + b0, 0.f), fmaxf(acc[i][j][4 * q + 1] + b1, 0.f));
-          p.y = pack_bf16x2(fmaxf(acc[i][j][4 * q + 2] + b2, 0.f), fmaxf(acc[i][j][4 * q + 3] + b3, 0.f));
-          *reinterpret_cast<v2u*>(c.stage + c.l32 * 64 + ((q ^ ((c.l32 >> 2) & 3)) << 4) + 8 * c.lh) = p;
-#pragma unroll
-          for (int v = 0; v < 4; ++v) acc[i][j][4 * q + v] = 0.f;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          const int idx = c.lane + 64 * k;
-          const int r = idx >> 2, cc = idx & 3;
-          const int gr = m0 + c.wm * 64 + i * 32 + r;
-          const v4u val = *reinterpret_cast<const v4u*>(c.stage + r * 64 + ((cc ^ ((r >> 2) & 3)) << 4));
-          if (gr < c.ntot)
-            *reinterpret_cast<v4u*>(c.out + (size_t)gr * kBN + c.wn * 64 + j * 32 + cc * 8) = val;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
-    }
-  }
+  if (g >= 0 && (g % NK) == NK - 1) write_tile<DCH>(g / NK, acc, c);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -436,6 +448,7 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
   const int nt_wg = lim > slot ? (lim - slot + per - 1) / per : 0;
   const int S = nt_wg * NK;                 // steps of this workgroup
   if (S == 0) return;                       // no tile for this workgroup (uniform)
+  if (t < kBN) reinterpret_cast<float*>(smem + kBiasOff)[t] = bias[t];   // read after many barriers, at the first tile's end
   // Both kinds of wave pass S + 2 barriers (steps -2 .. S-1).  Waves are dealt to the four SIMDs
   // round-robin, so every SIMD hosts two waves of each kind.
   if (wave < kMfmaWaves) {
@@ -451,10 +464,9 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
     mc.h = reinterpret_cast<const char*>(h);
     mc.wm = wave >> 2;
     mc.wn = wave & 3;
-    mc.bias64 = bias + mc.wn * 64;
+    mc.bias64 = reinterpret_cast<const float*>(smem + kBiasOff) + mc.wn * 64;
     mc.out = out;
     mc.smem = smem;
-    mc.stage = smem + kStageOff + wave * kStageBytes;
     mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256w_smem);
     mc.ntot = ntot;
     mc.tile0 = xcd * tpx + slot;
