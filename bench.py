@@ -70,6 +70,32 @@ def algorithmic_work(w, ntot, etot):
             "readout_head": {"bytes": ntot * m.H * s}}
 
 
+def long_list_stats(ev, w, cg, co, gid, ntot, etot, torch):
+    """(number of (row, direction) pairs with more than three neighbours, their neighbour count in all) of
+    the contracted batch: what the pre-pass of the bulk layer kernel serves.  Outside the timed region."""
+    batch = ev.alloc_batch(w.n_cand, int(w.cand_off[-1]), ntot, etot)
+    ev.contract_graphs(cg, co, gid, batch)
+    torch.cuda.synchronize()
+    pairs = entries = 0
+    for rp in (batch.in_rowptr, batch.out_rowptr):
+        deg = (rp[1:ntot + 1] - rp[:ntot]).to(torch.int64)
+        long = deg > 3
+        pairs += int(long.sum())
+        entries += int(deg[long].sum())
+    del batch
+    return pairs, entries
+
+
+def pre_pass_work(w, pairs, entries):
+    """Bytes the pre-pass must move per step: every neighbour row its lists name (2 bytes x d), the mean it
+    writes per list, the neighbour numbers (4 bytes each) and per list its row number and list bounds."""
+    m, by, d = w.model, 0, w.model.F
+    for _ in range(m.L):
+        by += entries * d * 2 + pairs * d * 2 + 4 * entries + 12 * pairs
+        d = m.H
+    return {"bytes": by}
+
+
 def read_traffic(workload, kernel):
     """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
     recorded in profiles/traffic_<workload>.txt as '<kernel>_traffic_bytes_per_launch: N'."""
@@ -492,6 +518,9 @@ def main():
     assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
 
     work = algorithmic_work(w, ntot, etot)
+    if fam.get("aggregate_heavy", (0, 0))[1] > 0 and args.kernels == 0:
+        pairs, entries = long_list_stats(ev, w, cg, co, gid, ntot, etot, torch)
+        work["aggregate_heavy"] = pre_pass_work(w, pairs, entries)
     fam["contract_all"] = (sum(fam[k][0] for k in ("prep_scan", "contract", "finalize")), fam["contract"][1])
     contract_parts = {k: round(fam[k][0] / args.steps, 4) for k in ("prep_scan", "contract", "finalize")}
     kernels = {}
