@@ -306,7 +306,8 @@ def search_bench(args, w, B, torch):
     t_base, x_base = wl.profile_of(ws)
     ev = B.evaluator_for(ws)
     ev.set_profile(t_base, x_base)
-    kw = dict(alpha=1.05, beta=16, seed=1, ar_c=0.02, ar_d=0.01, max_unchanged=1 << 30, parents=P, max_queue=4 * P)
+    kw = dict(alpha=1.05, beta=16, seed=1, ar_c=0.02, ar_d=0.01, max_unchanged=1 << 30, parents=P, max_queue=4 * P,
+              op_draw=B.DC_DRAW_OP if args.op_draw == "op" else B.DC_DRAW_DEPENDENCY)
     ev.search(0, g.n, max_steps=args.warmup, **kw)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -317,7 +318,7 @@ def search_bench(args, w, B, torch):
            "warmup": args.warmup, "ms_per_step": round(dt / max(r.steps, 1) * 1e3, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": w.model.dtype, "data": "synthetic",
            "config": {"workload": w.name, "base_nodes": g.n, "parents_per_step": P, "alpha": 1.05, "beta": 16,
-                      "evaluated": int(r.evaluated), "valid": int(r.valid), "enqueued": int(r.enqueued),
+                      "op_draw": args.op_draw, "evaluated": int(r.evaluated), "valid": int(r.valid), "enqueued": int(r.enqueued),
                       "improved": int(r.improved), "cost_in": r.cost_in, "cost_opt": r.cost_opt,
                       "groups_opt": int(len(np.unique(labels))),
                       "note": "includes the set-up of the call (first cost of H_in, buffers) and one stream "
@@ -454,6 +455,9 @@ def main():
     ap.add_argument("--search", action="store_true",
                     help="time the backtracking search (dc_search) on the workload's base graph; "
                          "--n-cand children per step, --steps search steps")
+    ap.add_argument("--op-draw", default="dependency", choices=["dependency", "op"],
+                    help="with --search: how op fusion draws (a dependency of the base module, or the paper's "
+                         "op of the current module and one of its predecessors)")
     ap.add_argument("--train", action="store_true",
                     help="time dc_train_step (estimator training, fp32) on samples drawn on the workload's base "
                          "graph; --n-cand = number of labelings the samples are drawn from")

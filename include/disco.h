@@ -276,9 +276,17 @@ dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, 
  * A strategy is a labelling of the nodes of base graph `graph`; the search starts from the
  * all-singleton labelling H_in with H_opt = H_in.  Per step up to `parents` entries leave the
  * priority queue (ascending cost, oldest first); each gets one child per optimisation method:
- *   op fusion      n = Random(0, beta) times: a dependency u -> v between two computation ops of
- *                  the base module is drawn uniformly; if its ends are in different groups, the
- *                  group of u joins the group of v                        (Sec. 4, method (i))
+ *   op fusion      n = Random(0, beta) times, in the form op_draw selects     (Sec. 4, method (i))
+ *                  DC_DRAW_DEPENDENCY: a dependency u -> v between two computation ops of the
+ *                  base module is drawn uniformly; if its ends are in different groups, the
+ *                  group of u joins the group of v.  Needs no view of the current module.
+ *                  DC_DRAW_OP (the paper's wording): a computation op of the current module is
+ *                  drawn uniformly (the groups of the labelling, in the order of their smallest
+ *                  member; low 32 bits of the draw), then one of its predecessor ops in the
+ *                  current module uniformly (the groups with a dependency into it, same order;
+ *                  high 32 bits), and the predecessor joins the op; an op without predecessors
+ *                  leaves the module as it is.  Needs 7 bytes of LDS per base node: graphs of
+ *                  more than about 23,000 nodes return DC_ERR_UNSUPPORTED.
  *   tensor fusion  n times: an all-reduce node a and a side are drawn uniformly; the nearest
  *                  bucket on that side in production order joins a's      (Sec. 4, method (iii))
  * (method (ii) duplicates an op; a labelling cannot express that).  The children of a step are
@@ -295,6 +303,7 @@ dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, 
  * labels_opt: host [N] out (may be NULL); res: host out.  Allocates its own device buffers
  * ((max_queue + 4 * parents) * N labels) for the duration of the call and synchronises `stream`
  * once per step.                                                                            */
+enum { DC_DRAW_DEPENDENCY = 0, DC_DRAW_OP = 1 };
 typedef struct {
   float alpha;           /* >= 1 */
   int32_t beta;          /* >= 0 */
@@ -304,6 +313,7 @@ typedef struct {
   int64_t max_steps;
   uint64_t seed;
   float ar_c, ar_d;      /* T = ar_c * size + ar_d */
+  int32_t op_draw;       /* DC_DRAW_DEPENDENCY or DC_DRAW_OP */
 } dc_search_params;
 typedef struct {
   float cost_in, cost_opt;

@@ -18,7 +18,7 @@ Choices of this build where the paper is silent or where this build's scope cuts
     groups of computation ops with a dependency into it, same order); the predecessor joins
     the op.  An op without predecessors leaves the module as it is.  One 64-bit draw serves
     both: the low 32 bits pick the op, the high 32 bits the predecessor.
-    The alternative (op_draw = "dependency", the device driver's default): draw a dependency
+    The alternative (op_draw = "dependency", the default of the device driver, which has both): draw a dependency
     u -> v between two computation ops of the BASE module uniformly; if its ends are in
     different groups, the group of u joins the group of v.  It needs no view of the current
     module between applications, but it is a different distribution: ops with many

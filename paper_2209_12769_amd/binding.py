@@ -30,6 +30,7 @@ DC_BF16 = 1
 DC_AGG_MEAN = 0
 DC_AGG_ATTENTION = 1
 DC_KERNELS_SEPARATE_LAYERS = 1
+DC_DRAW_DEPENDENCY, DC_DRAW_OP = 0, 1
 STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "DC_ERR_BAD_PARTITION",
                 4: "DC_ERR_CAPACITY", 5: "DC_ERR_OOM", 6: "DC_ERR_HIP", 7: "DC_ERR_UNSUPPORTED"}
 
@@ -51,7 +52,7 @@ class DcBatch(C.Structure):
 class DcSearchParams(C.Structure):
     _fields_ = [("alpha", C.c_float), ("beta", C.c_int32), ("max_unchanged", C.c_int32), ("parents", C.c_int32),
                 ("max_queue", C.c_int32), ("max_steps", C.c_int64), ("seed", C.c_uint64),
-                ("ar_c", C.c_float), ("ar_d", C.c_float)]
+                ("ar_c", C.c_float), ("ar_d", C.c_float), ("op_draw", C.c_int32)]
 
 
 class DcSearchResult(C.Structure):
@@ -409,9 +410,10 @@ class Evaluator:
         return cost[:n_cand]
 
     def search(self, graph: int, n_nodes: int, alpha: float, beta: int, seed: int, ar_c: float, ar_d: float,
-               max_unchanged: int = 1000, parents: int = 1, max_steps: int = 1 << 40, max_queue: int = 4096):
+               max_unchanged: int = 1000, parents: int = 1, max_steps: int = 1 << 40, max_queue: int = 4096,
+               op_draw: int = 0):
         """Alg. 1 on base graph `graph`; returns (labels_opt, DcSearchResult)."""
-        p = DcSearchParams(alpha, beta, max_unchanged, parents, max_queue, max_steps, seed, ar_c, ar_d)
+        p = DcSearchParams(alpha, beta, max_unchanged, parents, max_queue, max_steps, seed, ar_c, ar_d, op_draw)
         r = DcSearchResult()
         labels = np.zeros(n_nodes, np.int32)
         self._ok(dc_search(self.ctx, graph, p, labels, r, self._stream()), "dc_search")

@@ -945,6 +945,8 @@ dc_status dc_search(dc_ctx* ctx, int32_t graph, const dc_search_params* params, 
   if (graph < 0 || graph >= ctx->bg.n_graphs) return fail(ctx, DC_ERR_INVALID_ARG, "graph index out of range");
   if (!(p.alpha >= 1.0f) || p.beta < 0 || p.max_unchanged < 0 || p.parents < 1 || p.max_queue < 1 || p.max_steps < 0)
     return fail(ctx, DC_ERR_INVALID_ARG, "need alpha >= 1, beta >= 0, parents >= 1, max_queue >= 1");
+  if (p.op_draw != DC_DRAW_DEPENDENCY && p.op_draw != DC_DRAW_OP)
+    return fail(ctx, DC_ERR_INVALID_ARG, "op_draw must be DC_DRAW_DEPENDENCY or DC_DRAW_OP");
   SearchView g;
   g.n = ctx->h_gno[graph + 1] - ctx->h_gno[graph];
   g.e = ctx->h_geo[graph + 1] - ctx->h_geo[graph];
@@ -956,6 +958,7 @@ dc_status dc_search(dc_ctx* ctx, int32_t graph, const dc_search_params* params, 
     return fail(ctx, DC_ERR_CAPACITY, "the context must hold 2 * parents candidates of this graph per call");
   if (g.n == 0) return fail(ctx, DC_ERR_INVALID_ARG, "empty graph");
   st = run_search(ctx, g, graph, p, labels_opt, res, static_cast<hipStream_t>(stream));
+  if (st == DC_ERR_UNSUPPORTED && ctx->err.empty()) ctx->err = "the graph is too large for the mutation kernel's LDS with this op_draw";
   if (st != DC_OK && ctx->err.empty()) ctx->err = "search failed";
   return st;
 }

@@ -11,9 +11,14 @@
 // the loop as printed.
 //
 // Methods (Sec. 4, (i) and (iii); (ii) duplicates an op, which no labelling of the node set
-// expresses):  op fusion, one application: a dependency u -> v between two computation ops of
-// the base module is drawn uniformly; if its ends lie in different groups, the group of u
-// joins the group of v.  Tensor fusion, one application: an all-reduce node a and a side are
+// expresses):  op fusion, one application, in one of two forms.  DC_DRAW_DEPENDENCY: a dependency
+// u -> v between two computation ops of the base module is drawn uniformly; if its ends lie in
+// different groups, the group of u joins the group of v.  DC_DRAW_OP (the paper's wording): a
+// computation op of the current module is drawn uniformly (the groups of the labelling, in the
+// order of their smallest member), then one of its predecessor ops in the current module
+// uniformly (the groups with a dependency into it, same order), and the predecessor joins the
+// op; an op without predecessors leaves the module as it is; the low half of the 64-bit draw
+// picks the op, the high half the predecessor.  Tensor fusion, one application: an all-reduce node a and a side are
 // drawn uniformly; the nearest bucket on that side in production order, if there is one,
 // joins the bucket of a.  Validity is what the cost reports: a cyclic module costs +infinity.
 //
@@ -31,6 +36,8 @@
 namespace dc {
 namespace {
 
+constexpr int kMutateLdsLimit = 160 * 1024 - 2048;   // dynamic LDS of mutate_kernel next to its static arrays
+
 __host__ __device__ inline unsigned long long mix64(unsigned long long x) {
   unsigned long long z = x + 0x9E3779B97F4A7C15ull;
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -38,16 +45,60 @@ __host__ __device__ inline unsigned long long mix64(unsigned long long x) {
   return z ^ (z >> 31);
 }
 
-extern __shared__ unsigned short dc_search_lab[];
+extern __shared__ __attribute__((aligned(16))) unsigned short dc_search_lab[];
 
-// One workgroup per child: child j descends from parent j / 2 by method j % 2.
+// The k-th (from 0) position q of the op list, in ascending order, for which pred(q) holds, or -1 if
+// fewer than k + 1 do; `pick` is called with the count of such positions and returns k.  Every
+// thread of the workgroup takes a contiguous run of the list.  Three barriers; the result is
+// uniform.  cnt: 256 ints, sel: 4 ints of LDS.
+template <typename Pred, typename Pick>
+__device__ int select_kth(int n_op, int* cnt, int* sel, Pred pred, Pick pick) {
+  const int t = threadIdx.x, T = blockDim.x;
+  const int ch = (n_op + T - 1) / T, lo = min(n_op, t * ch), hi = min(n_op, lo + ch);
+  int c = 0;
+  for (int q = lo; q < hi; ++q) c += pred(q) ? 1 : 0;
+  cnt[t] = c;
+  __syncthreads();
+  if (t == 0) {
+    int total = 0;
+    for (int i = 0; i < T; ++i) total += cnt[i];
+    sel[0] = -1;
+    if (total > 0) {
+      int k = pick(total), w = 0;
+      while (k >= cnt[w]) k -= cnt[w++];
+      sel[0] = w;
+      sel[1] = k;
+    }
+  }
+  __syncthreads();
+  if (sel[0] == t) {
+    int k = sel[1], q = lo;
+    for (;; ++q)
+      if (pred(q) && k-- == 0) break;
+    sel[2] = q;
+  }
+  __syncthreads();
+  const int r = sel[0] < 0 ? -1 : sel[2];
+  __syncthreads();                           // sel and cnt may be written again
+  return r;
+}
+
+// One workgroup per child: child j descends from parent j / 2 by method j % 2.  op_draw != 0 takes
+// the paper's draw for op fusion and needs, behind the labels, 4 N bytes (smallest member per
+// label) and N bytes (marks) of LDS.
 __global__ __launch_bounds__(256) void mutate_kernel(const int* __restrict__ pool, const int* __restrict__ parent_slot,
                                                       int N, int n_edges, const int* __restrict__ esrc,
                                                       const int* __restrict__ edst, int n_ar,
-                                                      const int* __restrict__ ar_nodes, unsigned long long seed,
-                                                      unsigned long long step, int beta, int* __restrict__ children) {
+                                                      const int* __restrict__ ar_nodes, int n_op,
+                                                      const int* __restrict__ op_nodes, int op_draw,
+                                                      unsigned long long seed, unsigned long long step, int beta,
+                                                      int* __restrict__ children) {
   __shared__ int pair[2];
+  __shared__ int cnt[256];
+  __shared__ int sel[4];
   unsigned short* lab = dc_search_lab;
+  int* first = reinterpret_cast<int*>(lab + ((N + 1) & ~1));
+  unsigned char* mark = reinterpret_cast<unsigned char*>(first + N);
   const int j = blockIdx.x, t = threadIdx.x, T = blockDim.x;
   const int method = j & 1;
   const int* src = pool + (size_t)parent_slot[j >> 1] * N;
@@ -56,31 +107,61 @@ __global__ __launch_bounds__(256) void mutate_kernel(const int* __restrict__ poo
   const int n = (int)(mix64(key) % (unsigned long long)(beta + 1));
   __syncthreads();
   for (int i = 0; i < n; ++i) {
-    if (t == 0) {
-      const unsigned long long r = mix64(key + (unsigned long long)(1 + i) * 0xD1342543DE82EF95ull);
-      int from = -1, to = -1;
-      if (method == 0) {
-        if (n_edges > 0) {
-          const int k = (int)(r % (unsigned long long)n_edges);
-          from = lab[esrc[k]];
-          to = lab[edst[k]];
+    const unsigned long long r = mix64(key + (unsigned long long)(1 + i) * 0xD1342543DE82EF95ull);
+    int from = -1, to = -1;
+    if (method == 0 && op_draw != 0) {
+      // smallest member of every group of ops; a group's place in the order is that member's
+      for (int v = t; v < N; v += T) {
+        first[v] = 0x7FFFFFFF;
+        mark[v] = 0;
+      }
+      __syncthreads();
+      for (int q = t; q < n_op; q += T) atomicMin(&first[lab[op_nodes[q]]], op_nodes[q]);
+      __syncthreads();
+      const int qo = select_kth(
+          n_op, cnt, sel, [&](int q) { return first[lab[op_nodes[q]]] == op_nodes[q]; },
+          [&](int total) { return (int)((r & 0xFFFFFFFFull) % (unsigned long long)total); });
+      if (qo >= 0) {
+        const int op = lab[op_nodes[qo]];
+        for (int e = t; e < n_edges; e += T) {
+          const int lu = lab[esrc[e]];
+          if (lab[edst[e]] == op && lu != op) mark[first[lu]] = 1;
         }
-      } else if (n_ar > 0) {
-        const int pa = (int)(r % (unsigned long long)n_ar);
-        const int side = ((r >> 32) & 1ull) ? 1 : -1;
-        const int la = lab[ar_nodes[pa]];
-        int pb = pa + side;
-        while (pb >= 0 && pb < n_ar && lab[ar_nodes[pb]] == la) pb += side;
-        if (pb >= 0 && pb < n_ar) {
-          from = lab[ar_nodes[pb]];
-          to = la;
+        __syncthreads();
+        const int qp = select_kth(
+            n_op, cnt, sel, [&](int q) { return mark[op_nodes[q]] != 0; },
+            [&](int total) { return (int)((r >> 32) % (unsigned long long)total); });
+        if (qp >= 0) {
+          from = lab[op_nodes[qp]];
+          to = op;
         }
       }
-      pair[0] = from;
-      pair[1] = to;
+    } else {
+      if (t == 0) {
+        if (method == 0) {
+          if (n_edges > 0) {
+            const int k = (int)(r % (unsigned long long)n_edges);
+            from = lab[esrc[k]];
+            to = lab[edst[k]];
+          }
+        } else if (n_ar > 0) {
+          const int pa = (int)(r % (unsigned long long)n_ar);
+          const int side = ((r >> 32) & 1ull) ? 1 : -1;
+          const int la = lab[ar_nodes[pa]];
+          int pb = pa + side;
+          while (pb >= 0 && pb < n_ar && lab[ar_nodes[pb]] == la) pb += side;
+          if (pb >= 0 && pb < n_ar) {
+            from = lab[ar_nodes[pb]];
+            to = la;
+          }
+        }
+        pair[0] = from;
+        pair[1] = to;
+      }
+      __syncthreads();
+      from = pair[0];
+      to = pair[1];
     }
-    __syncthreads();
-    const int from = pair[0], to = pair[1];
     if (from >= 0 && from != to)
       for (int v = t; v < N; v += T)
         if (lab[v] == from) lab[v] = (unsigned short)to;
@@ -136,12 +217,13 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
   if (e == hipSuccess && N > 0) e = hipMemcpyAsync(ar.data(), g.ar_size, (size_t)N * sizeof(float), hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return DC_ERR_HIP;
-  std::vector<int> esrc, edst, arn;
+  std::vector<int> esrc, edst, arn, opn;
   for (int u = 0; u < N; ++u) {
     if (ar[u] >= 0.0f) {
       arn.push_back(u);
       continue;
     }
+    opn.push_back(u);
     for (int k = rp[u]; k < rp[u + 1]; ++k)
       if (ar[ci[k]] < 0.0f) {
         esrc.push_back(u);
@@ -153,6 +235,7 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
   int* d_esrc = mem.take<int>(esrc.size(), &e);
   int* d_edst = mem.take<int>(edst.size(), &e);
   int* d_arn = mem.take<int>(arn.size(), &e);
+  int* d_opn = mem.take<int>(opn.size(), &e);
   int* pool = mem.take<int>((size_t)slots * N, &e);
   int* children = mem.take<int>((size_t)C * N, &e);
   int* d_parent = mem.take<int>(P, &e);
@@ -175,8 +258,12 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
     if (e == hipSuccess) e = hipMemcpyAsync(d_edst, edst.data(), edst.size() * sizeof(int), hipMemcpyHostToDevice, s);
   }
   if (e == hipSuccess && !arn.empty()) e = hipMemcpyAsync(d_arn, arn.data(), arn.size() * sizeof(int), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && !opn.empty()) e = hipMemcpyAsync(d_opn, opn.data(), opn.size() * sizeof(int), hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return DC_ERR_HIP;
-  const size_t lds = (size_t)N * sizeof(unsigned short);
+  const int op_draw = p.op_draw == DC_DRAW_OP ? 1 : 0;
+  // labels as 16-bit values; the paper's op draw also keeps a 32-bit smallest member per label and a byte per node
+  const size_t lds = (size_t)((N + 1) & ~1) * sizeof(unsigned short) + (op_draw ? (size_t)N * 5 + 4 : 0);
+  if (lds > (size_t)kMutateLdsLimit) return DC_ERR_UNSUPPORTED;
   if (lds > 48 * 1024) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mutate_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds);
@@ -215,7 +302,8 @@ dc_status run_search(dc_ctx* ctx, const SearchView& g, int32_t graph, const dc_s
     for (int i = 0; i < np; ++i) h_parent[i] = used[i];
     if (hipMemcpyAsync(d_parent, h_parent, np * sizeof(int), hipMemcpyHostToDevice, s) != hipSuccess) return DC_ERR_HIP;
     hipLaunchKernelGGL(mutate_kernel, dim3(nc), dim3(256), lds, s, pool, d_parent, N, (int)esrc.size(), d_esrc, d_edst,
-                       (int)arn.size(), d_arn, (unsigned long long)p.seed, (unsigned long long)step, p.beta, children);
+                       (int)arn.size(), d_arn, (int)opn.size(), d_opn, op_draw, (unsigned long long)p.seed,
+                       (unsigned long long)step, p.beta, children);
     if (hipGetLastError() != hipSuccess) return DC_ERR_HIP;
     st = cost_of(children, nc);
     if (st != DC_OK) return st;

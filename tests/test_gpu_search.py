@@ -73,6 +73,25 @@ def test_same_path_as_the_oracle_with_an_exact_estimator(B, name, est, alpha, be
           f"{r.cost_opt:.4f}, {len(np.unique(labels))} groups of {g.n}", flush=True)
 
 
+@pytest.mark.parametrize("name,est,alpha,beta,parents,limit", [
+    ("cfg1", 0.04, 1.05, 4, 1, 60), ("cfg1", 0.04, 1.2, 6, 8, 150), ("cfg2", 0.03, 1.02, 8, 16, 200)])
+def test_same_path_as_the_oracle_with_the_papers_op_draw(B, name, est, alpha, beta, parents, limit):
+    """Method (i) as the paper words it: an op of the current module, then one of its current predecessors."""
+    base = wl.make(name, 1)
+    g, model = base.graphs[0], base.model
+    wt = constant_estimator(model, est)
+    t, x = wl.profile_of(base)
+    kw = dict(alpha=alpha, beta=beta, seed=7, max_unchanged=limit, max_steps=30)
+    ref = osr.search(g, oracle_cost_fn(g, model, wt, t, x, 0.02, 0.01), parents=parents, op_draw="op", **kw)
+    labels, r = gpu_search(B, g, model, wt, t, x, parents, ar_c=0.02, ar_d=0.01, op_draw=B.DC_DRAW_OP, **kw)
+    same_run(r, ref, labels, name)
+    other = osr.search(g, oracle_cost_fn(g, model, wt, t, x, 0.02, 0.01), parents=parents, **kw)
+    assert not np.array_equal(other.labels_opt, ref.labels_opt) or other.evaluated != ref.evaluated   # the draws differ
+    assert r.improved >= 1 and r.cost_opt < r.cost_in
+    print(f"[search, op draw] {name} P={parents}: {r.evaluated} evaluated, {r.valid} valid, cost {r.cost_in:.4f} -> "
+          f"{r.cost_opt:.4f}, {len(np.unique(labels))} groups of {g.n}", flush=True)
+
+
 def test_queue_limit_and_beta_zero(B):
     base = wl.make("cfg1", 1)
     g, model = base.graphs[0], base.model
@@ -134,6 +153,7 @@ def test_bad_arguments(B):
     assert e.value.status == B.DC_ERR_INVALID_ARG            # no profile
     ev.set_profile(t, x)
     for kw, want in ((dict(alpha=0.9), B.DC_ERR_INVALID_ARG), (dict(beta=-1), B.DC_ERR_INVALID_ARG),
+                     (dict(op_draw=2), B.DC_ERR_INVALID_ARG),
                      (dict(parents=0), B.DC_ERR_INVALID_ARG), (dict(parents=2), B.DC_ERR_CAPACITY)):
         args = dict(alpha=1.1, beta=2, seed=0, ar_c=0.1, ar_d=0.1, parents=1)
         args.update(kw)
