@@ -475,6 +475,28 @@ def test_fused_layer_matches_the_separate_kernels_bit_for_bit(B):
         assert np.array_equal(fused, plain), (name, np.abs(fused - plain).max())
 
 
+def test_bulk_layer_with_every_kind_of_ragged_last_tile(B):
+    """The bulk layer kernel writes a tile with stores of 16 rows each: batches whose row total leaves
+    1, 15, 16, 17, 31, 32, 33, 63, 65, 127 or 0 rows in the last 128-row tile must equal the separate
+    kernels bit for bit and the oracle within tolerance (identity labels: rows = nodes x candidates)."""
+    model = wl.ModelSpec(64, 256, 2, "bf16")
+    for n_nodes, C in ((1, 1), (15, 1), (16, 1), (17, 1), (31, 1), (32, 1), (33, 3), (63, 1), (65, 1), (127, 1),
+                       (128, 1), (129, 2), (143, 3), (161, 5)):
+        g = wl.random_dag(100 + n_nodes, n_nodes, min(1.0, 3.0 / max(n_nodes, 2)), 64)
+        labs = np.tile(np.arange(g.n, dtype=np.int32), (C, 1))
+        w = wl.with_time_like_head(wl.custom(f"ragged-{n_nodes}x{C}", model, [g], [labs], seed=4))
+        ev = B.evaluator_for(w)
+        cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+        fused = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.select_kernels(B.DC_KERNELS_SEPARATE_LAYERS)
+        plain = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.close()
+        assert np.array_equal(fused, plain), (n_nodes, C, np.abs(fused - plain).max())
+        check_predictions(w, fused, np.arange(C), tag=f"ragged {n_nodes}x{C}")
+
+
 def test_eval_is_capturable_in_a_hip_graph_and_replays_identically(B):
     """dc_eval_candidates enqueues kernels on the caller's stream only (no host round trip, no
     allocation, no memset), so a caller may capture it; every replay, with eager work and
