@@ -74,10 +74,17 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// 16 bytes per lane from global memory straight into LDS (no registers): lane l of the wave
+// 16 bytes per lane from global memory straight into LDS (no registers): lane l of the wave reads
+// base + off (a wave-uniform 64-bit address plus the lane's unsigned 32-bit byte offset) and
 // writes lds_base + 16 l.  Not tracked by the compiler; waited for with wait_copies().
-__device__ __forceinline__ void copy16_to_lds(const void* gaddr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "memory");
+__device__ __forceinline__ void copy16_to_lds(const char* base, unsigned off, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds_base) : "memory");
+}
+// A pointer the compiler may not know to be wave-uniform, as a scalar.
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const char*>(((unsigned long long)hi << 32) | lo);
 }
 // s_waitcnt vmcnt(n), n even in 0 .. 14 (wave-uniform): at most n newer vector-memory operations may
 // still be outstanding.  Loads and stores leave the counter in issue order.
@@ -155,13 +162,14 @@ __device__ __forceinline__ int request_copies(int g, int S, const MulCtx& c) {
         n_req += 2;
         const int m0 = (c.tile0 + ti * c.per) * kBM;
         const unsigned aring = c.lds0 + (unsigned)(J % 3) * kABytes;
+        const char* abase = uniform_ptr(c.h + (size_t)m0 * Shape<DCH>::ROWB + kc * kARow);
+        const int last = c.ntot - 1 - m0;                  // >= 0: the tile has at least one row
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           const int piece = c.wave * 2 + i;
           const int r = piece * 8 + (c.lane >> 3);
           const int col = (c.lane & 7) ^ ((r >> 1) & 7);
-          const int row = min(m0 + r, c.ntot - 1);
-          copy16_to_lds(c.h + (size_t)row * Shape<DCH>::ROWB + kc * kARow + col * 16, aring + piece * 1024);
+          copy16_to_lds(abase, (unsigned)min(r, last) * Shape<DCH>::ROWB + (unsigned)col * 16u, aring + piece * 1024);
         }
       }
       // W is [k/8][H][8]: the B tile of a chunk is one contiguous 32 KB run.  With three chunks in
@@ -169,12 +177,11 @@ __device__ __forceinline__ int request_copies(int g, int S, const MulCtx& c) {
       // first tile loads it.
       if (NK > 3 || J < NK) {
         n_req += 4;
-        const char* wsrc = c.Wp + (size_t)kc * kBBytes + c.lane * 16;
         const unsigned ring = c.lds0 + kBOff + (unsigned)(J % 3) * kBBytes;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int piece = c.wave * 4 + i;
-          copy16_to_lds(wsrc + piece * 1024, ring + piece * 1024);
+          copy16_to_lds(uniform_ptr(c.Wp + (size_t)kc * kBBytes + piece * 1024), (unsigned)c.lane * 16u, ring + piece * 1024);
         }
       }
     }
