@@ -46,7 +46,6 @@ struct dc_ctx {
   int* heavy_cnt = nullptr;
   int* status = nullptr;    // [2]
   int* totals = nullptr;    // [2]
-  char* zero_row = nullptr; // 1 KB of zeros
   int* h_pinned = nullptr;  // [4] pinned host mirror for status / totals
   // weights
   void* W = nullptr;
@@ -136,7 +135,6 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   a.base = base;
   int* status = a.take<int>(64);
   int* totals = a.take<int>(64);
-  char* zero_row = a.take<char>(1024);
   ContractTmp t;
   t.tmp_eoff = a.take<int>(k.C + 1);
   t.members = a.take<int>(k.NB + 1);
@@ -175,7 +173,6 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
     ctx->score[0] = score0;
     ctx->score[1] = score1;
     ctx->status = status;
-    ctx->zero_row = zero_row;
     ctx->totals = totals;
     ctx->tmp = t;
     ctx->ib = b;
@@ -292,7 +289,6 @@ GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) 
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;
   g.allow_fused = ctx->allow_fused;
-  g.zero_row = ctx->zero_row;
   if (ctx->cfg.aggregator == DC_AGG_ATTENTION) {
     g.heads = ctx->cfg.heads;
     g.att = ctx->att;
@@ -349,7 +345,6 @@ dc_status do_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph
   // the layer kernels only need the total row count: the batch is handed over as one graph
   GnnArgs g = gnn_args(ctx, 1, a.fb, nullptr);
   g.node_off = a.totals;
-  g.gather_slots = 1;                       // the members of a fused op have few dependencies among them
   const void* h_last = nullptr;
   e = launch_gnn_layers(g, prof, s, &h_last);
   if (e != hipSuccess) return hip_fail(ctx, e, "fused-op forward launch");
@@ -479,7 +474,6 @@ dc_status dc_create(dc_ctx** out, const dc_config* cfg) {
   carve(*cfg, ctx->arena, ctx);
   e = hipMemset(ctx->status, 0, 64 * sizeof(int));
   if (e == hipSuccess) e = hipMemset(ctx->totals, 0, 64 * sizeof(int));
-  if (e == hipSuccess) e = hipMemset(ctx->zero_row, 0, 1024);
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_pinned), 64 * sizeof(int), hipHostMallocDefault);
   const size_t es = cfg->dtype == DC_BF16 ? 2 : 4;
   const size_t HH = (size_t)cfg->H * cfg->H;

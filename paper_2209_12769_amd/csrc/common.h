@@ -111,8 +111,6 @@ struct GnnArgs {
   const int* status;
   int n_cu;
   int allow_fused;      // 0 forces the separate aggregate + update kernels
-  int gather_slots = 3; // 1: nearly every neighbour list has at most one entry (batches of fused-op subgraphs)
-  const void* zero_row = nullptr;   // 1 KB of zeros in device memory (the mean of an empty list, read by DMA)
   // attention aggregation (heads > 0): W holds one [d, H] block per layer
   int heads = 0;
   const float* att = nullptr;   // per layer a_src[H] | a_dst[H]

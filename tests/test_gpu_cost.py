@@ -309,9 +309,9 @@ def test_call_order_and_limits(B):
     ev.close()
 
 
-def test_one_slot_layers_equal_the_separate_kernels(B):
-    """The fused-op batches run the layer kernel with one gather slot, whose data-moving waves copy the
-    neighbour rows (or finished means) into LDS by direct copies.  dc_select_kernels can make a context
+def test_layers_on_a_fused_op_batch_equal_the_separate_kernels(B):
+    """The fused-op batches run the same fused layer kernel as the candidate modules (millions of rows in
+    tiny graphs: nearly every neighbour list has at most one entry).  dc_select_kernels can make a context
     run the neighbour means and the node update as separate kernels instead: the same arithmetic in the
     same order, so the costs agree bit for bit."""
     w = positive(wl.make("cfg4", 24))

@@ -68,6 +68,6 @@ def test_checker_carries_loads_in_flight_across_a_back_edge(tmp_path):
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
 def test_no_instruction_touches_a_load_in_flight_in_the_layer_kernels():
     res = isa_check.check_layer256()
-    assert len(res) >= 6                      # input widths 256 / 64: plain product, one-slot layer, three-slot layer
+    assert len(res) >= 4                      # input widths 256 / 64: the plain product and the message-passing layer
     for kernel, hazards in res.items():
         assert hazards == [], (kernel, hazards[:3])
