@@ -44,6 +44,8 @@ struct dc_ctx {
   void* desc[2] = {nullptr, nullptr};
   int* heavy[2] = {nullptr, nullptr};
   int* heavy_cnt = nullptr;
+  float* ro_part = nullptr; // chunk sums of the readout when the last layer forms them
+  int* ro_first = nullptr;
   int* status = nullptr;    // [2]
   int* totals = nullptr;    // [2]
   int* h_pinned = nullptr;  // [4] pinned host mirror for status / totals
@@ -166,6 +168,10 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   int* heavy0 = a.take<int>((size_t)k.NN + 128);
   int* heavy1 = a.take<int>((size_t)k.NN + 128);
   int* heavy_cnt = a.take<int>(2 * ((size_t)k.NN / 128 + 2));
+  // chunk sums of the readout formed by the last layer (bulk bf16 shapes with uniform coefficients only)
+  const bool ro = cfg.dtype == DC_BF16 && cfg.H == 256 && cfg.aggregator != DC_AGG_ATTENTION;
+  float* ro_part = a.take<float>(ro ? ((size_t)k.NN / 64 + (size_t)k.C + 2) * 256 : 0);
+  int* ro_first = a.take<int>(ro ? (size_t)k.NN / 64 + 2 : 0);
   const size_t nscore = cfg.aggregator == DC_AGG_ATTENTION ? (size_t)(k.NN + 1) * cfg.heads : 0;
   float* score0 = a.take<float>(nscore);
   float* score1 = a.take<float>(nscore);
@@ -185,6 +191,8 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
     ctx->heavy[0] = heavy0;
     ctx->heavy[1] = heavy1;
     ctx->heavy_cnt = heavy_cnt;
+    ctx->ro_part = ro ? ro_part : nullptr;
+    ctx->ro_first = ro ? ro_first : nullptr;
   }
   return a.off;
 }
@@ -254,7 +262,8 @@ dc_status do_contract(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, co
 GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred);
 
 dc_status do_forward(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred, hipStream_t s) {
-  const GnnArgs g = gnn_args(ctx, n_cand, in, pred);
+  GnnArgs g = gnn_args(ctx, n_cand, in, pred);
+  g.fuse_readout = 1;                        // nothing but the readout looks at the last layer's rows here
   hipError_t e = launch_gnn_forward(g, ctx->prof.on ? &ctx->prof : nullptr, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "forward launch");
   return DC_OK;
@@ -285,6 +294,8 @@ GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) 
   g.heavy[0] = ctx->heavy[0];
   g.heavy[1] = ctx->heavy[1];
   g.heavy_cnt = ctx->heavy_cnt;
+  g.ro_part = ctx->ro_part;
+  g.ro_first = ctx->ro_first;
   g.pred = pred;
   g.status = ctx->status;
   g.n_cu = ctx->n_cu;

@@ -107,6 +107,11 @@ struct GnnArgs {
   void* desc[2];        // gather descriptors [max_nodes] x 16 bytes per direction
   int* heavy[2] = {nullptr, nullptr};   // per direction and tile of 128 rows: the rows with long lists (128 places per tile)
   int* heavy_cnt = nullptr;             // [2 * tiles] how many of them: entry 2 * tile + direction
+  // the last layer forming the readout's sums itself (bulk bf16 shapes): per chunk of 64 rows and graph one row of
+  // H partial sums at row chunk + graph, and per chunk the graph its first row belongs to; 0 / nullptr: not used
+  int fuse_readout = 0;
+  float* ro_part = nullptr;             // [max_nodes / 64 + max_cand + 2][H]
+  int* ro_first = nullptr;              // [max_nodes / 64 + 2]
   float* pred;
   const int* status;
   int n_cu;
@@ -147,8 +152,11 @@ hipError_t launch_fused_layer(const void* h, int d, const GnnArgs& a, const void
 // gnn_layer256.hip: wave-specialised fused layer for H = 256, d = 256 or 64 (bf16); uses a.agg[] for rows with long lists.
 bool layer256_supported(int d, int H, int bf16);
 hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
+// readout: the layer leaves the readout's chunk sums in a.ro_part instead of its rows in out (needs
+// launch_chunk_first on the same batch before)
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
-                           Profiler* prof, hipStream_t s);
+                           bool readout, Profiler* prof, hipStream_t s);
+hipError_t launch_chunk_first(const GnnArgs& a, hipStream_t s);
 // gnn_layer256w.hip: the same layer (three gather slots) with sixteen waves per workgroup; descriptors and
 // pre-pass means as for launch_layer256
 hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s);
@@ -156,7 +164,7 @@ hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s);
 // own places in a.agg[0] (predecessors) and a.agg[1] (successors); h [rows, d], d = 256 or 64, bf16.
 hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
-                            hipStream_t s);
+                            bool readout, hipStream_t s);
 hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            hipStream_t s);
 

@@ -352,20 +352,73 @@ __global__ __launch_bounds__(512) void update32_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------
-// readout + head: one workgroup per candidate; sums in fp64, fixed order
+// readout + head: one workgroup per candidate; sums in fp64, fixed order.
+//
+// kOrder = 0: every column is summed over the graph's rows in fp64 (eight or four interleaved row
+// sequences, then those in order).
+// kOrder = 1, 2 (bf16, H = 256: the shapes of the bulk layer kernel, which can form the sums itself):
+// the rows are taken in chunks of 64 consecutive global row numbers (chunk k = rows 64k .. 64k+63).
+// Per chunk and column the 64 places -- a place holds the row's value if the row belongs to the
+// graph, else +0 -- are summed in fp32 in one fixed tree: u_l = place l + place l+32 (l = 0..31),
+// then pairs of neighbours ((u0+u1)+(u2+u3))+... up to the root; the chunk sums of a graph are added
+// in fp64 in ascending chunk order.  1 forms the chunk sums here from h; 2 reads them from `part`,
+// where the last layer's kernel left them (the sum of chunk k for graph c at row k + c: both grow
+// along the rows, so the place is unique).  The same tree on both routes: the same bits.
 // ---------------------------------------------------------------------------
-template <bool kBf16>
+template <bool kBf16, int kOrder>
 __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restrict__ h, int H,
                                                             const int* __restrict__ node_off, int C,
                                                             const float* __restrict__ head, float* __restrict__ pred,
+                                                            const float* __restrict__ part,
                                                             const int* __restrict__ status) {
   if (status[0] != 0) return;
   constexpr int kPer = kBf16 ? 8 : 4;
-  __shared__ double red[256 * kPer];   // [row group][H] partial sums
+  __shared__ double red[kOrder == 0 ? 256 * kPer : 1];   // [row group][H] partial sums
+  __shared__ float sub[kOrder == 1 ? 2 * 8 * 256 : 1];   // [buffer][row lane][column]: sums of four u's
   __shared__ float r[512], z[512];
   __shared__ double wred[4];
   const int c = blockIdx.x, t = threadIdx.x;
   const int n0 = node_off[c], n1 = node_off[c + 1];
+  if constexpr (kOrder == 2) {
+    // H = 256: thread t has column t
+    double acc = 0.0;
+    if (n1 > n0)
+      for (int k = n0 >> 6; k <= (n1 - 1) >> 6; ++k) acc += (double)part[(size_t)(k + c) * 256 + t];
+    r[t] = (float)acc;
+  } else if constexpr (kOrder == 1) {
+    // thread (row lane m = t / 32, 16-byte piece t % 32): places 4m .. 4m+3 and 32 more; column t in the second half
+    const int m = t >> 5, ch = t & 31;
+    const uint4* h4 = reinterpret_cast<const uint4*>(h);
+    double acc = 0.0;
+    int buf = 0;
+    if (n1 > n0)
+      for (int k = n0 >> 6; k <= (n1 - 1) >> 6; ++k, buf ^= 1) {
+        uint4 x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int row = 64 * k + 4 * m + (i & 3) + 32 * (i >> 2);
+          x[i] = (row >= n0 && row < n1) ? h4[(size_t)row * 32 + ch] : make_uint4(0u, 0u, 0u, 0u);
+        }
+        float* dst = sub + (buf * 8 + m) * 256 + ch * 8;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float lo[8], hi[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const unsigned v = w == 0 ? x[i].x : (w == 1 ? x[i].y : (w == 2 ? x[i].z : x[i].w));
+            lo[i] = __uint_as_float(v << 16);
+            hi[i] = __uint_as_float(v & 0xFFFF0000u);
+          }
+          dst[2 * w] = ((lo[0] + lo[4]) + (lo[1] + lo[5])) + ((lo[2] + lo[6]) + (lo[3] + lo[7]));
+          dst[2 * w + 1] = ((hi[0] + hi[4]) + (hi[1] + hi[5])) + ((hi[2] + hi[6]) + (hi[3] + hi[7]));
+        }
+        __syncthreads();                    // two buffers: the next chunk's sums go to the other one
+        const float* q = sub + buf * 8 * 256 + t;
+        acc += (double)(((q[0] + q[256]) + (q[512] + q[768])) + ((q[1024] + q[1280]) + (q[1536] + q[1792])));
+      }
+    r[t] = (float)acc;
+  }
+  if constexpr (kOrder == 0) {
   const int cpr = H / kPer;            // 16-byte chunks per row (<= 256 for H <= 1024)
   const int rg = 256 / cpr;            // rows handled in parallel
   const int myr = t / cpr, ch = t - myr * cpr;
@@ -400,6 +453,7 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
     double s = 0.0;
     for (int g = 0; g < rg; ++g) s += red[g * H + j];
     r[j] = (float)s;
+  }
   }
   __syncthreads();
   const float* W1 = head;
@@ -545,6 +599,15 @@ hipError_t attention_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, con
   return hipGetLastError();
 }
 
+// The sum readout follows chunks of 64 rows (see readout_head_kernel) where the last layer is one the bulk
+// kernel takes, whichever kernels run it; that kernel can then leave the chunk sums instead of its rows.
+bool chunked_readout(const GnnArgs& a) {
+  return a.heads == 0 && layer256_supported(a.L > 1 ? a.H : a.F, a.H, a.bf16);
+}
+bool readout_in_last_layer(const GnnArgs& a) {
+  return a.fuse_readout && a.allow_fused && chunked_readout(a) && a.ro_part && a.ro_first;
+}
+
 // Layers with uniform coefficients: mean over predecessors, mean over successors, dense update.
 hipError_t mean_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const void** h_last) {
   const void* hcur = a.Xc;
@@ -557,13 +620,15 @@ hipError_t mean_layers(const GnnArgs& a, Profiler* prof, hipStream_t s, const vo
     // neighbour descriptors depend on the graphs only: built once, used by every layer that gathers through them
     if (prof) prof->begin(kFamDesc, s);
     hipError_t e = launch_build_desc(a, s);
+    if (e == hipSuccess && readout_in_last_layer(a)) e = launch_chunk_first(a, s);
     if (prof) prof->end(s);
     if (e != hipSuccess) return e;
   }
   for (int l = 0; l < a.L; ++l) {
     void* hnext = a.act[l & 1];
     if (a.allow_fused && layer256_supported(d, a.H, a.bf16)) {
-      hipError_t e = launch_layer256(hcur, d, a, Wl, bl, hnext, prof, s);
+      const bool readout = l == a.L - 1 && readout_in_last_layer(a);   // then hnext is not written
+      hipError_t e = launch_layer256(hcur, d, a, Wl, bl, hnext, readout, prof, s);
       if (e != hipSuccess) return e;
     } else if (a.allow_fused && fused_layer_supported(d, a.H, a.bf16)) {
       if (prof) prof->begin(kFamFused, s);
@@ -625,12 +690,20 @@ hipError_t launch_gnn_forward(const GnnArgs& a, Profiler* prof, hipStream_t s) {
   hipError_t e = launch_gnn_layers(a, prof, s, &hcur);
   if (e != hipSuccess) return e;
   if (prof) prof->begin(kFamReadout, s);
-  if (a.bf16)
-    hipLaunchKernelGGL(readout_head_kernel<true>, dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
-                       a.head, a.pred, a.status);
-  else
-    hipLaunchKernelGGL(readout_head_kernel<false>, dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
-                       a.head, a.pred, a.status);
+  if (a.bf16 && chunked_readout(a)) {
+    if (readout_in_last_layer(a))
+      hipLaunchKernelGGL((readout_head_kernel<true, 2>), dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
+                         a.head, a.pred, a.ro_part, a.status);
+    else
+      hipLaunchKernelGGL((readout_head_kernel<true, 1>), dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
+                         a.head, a.pred, static_cast<const float*>(nullptr), a.status);
+  } else if (a.bf16) {
+    hipLaunchKernelGGL((readout_head_kernel<true, 0>), dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
+                       a.head, a.pred, static_cast<const float*>(nullptr), a.status);
+  } else {
+    hipLaunchKernelGGL((readout_head_kernel<false, 0>), dim3(a.n_cand), dim3(256), 0, s, hcur, a.H, a.node_off, a.n_cand,
+                       a.head, a.pred, static_cast<const float*>(nullptr), a.status);
+  }
   if (prof) prof->end(s);
   return hipGetLastError();
 }

@@ -348,14 +348,14 @@ hipError_t launch_dense256(const void* h, int d, const GnnArgs& a, const void* W
 // One layer for H = 256, d = 256 or 64, bf16, after launch_build_desc: the pre-pass over the listed long rows,
 // then the sixteen-wave kernel.
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
-                           Profiler* prof, hipStream_t s) {
+                           bool readout, Profiler* prof, hipStream_t s) {
   if (d != 256 && d != 64) return hipErrorInvalidValue;
   if (prof) prof->begin(kFamHeavy, s);
   hipError_t e = launch_heavy_means(h, d, a, s);
   if (prof) prof->end(s);
   if (e != hipSuccess) return e;
   if (prof) prof->begin(d == 256 ? kFamLayer256 : kFamLayer64, s);
-  e = launch_layer256w(h, d, a, Wl, bias, out, s);
+  e = launch_layer256w(h, d, a, Wl, bias, out, readout, s);
   if (prof) prof->end(s);
   return e;
 }

@@ -140,6 +140,10 @@ struct MulCtx {
   const char* h;
   const float* bias64;  // the 64 bias values of this wave's columns, in LDS
   u16* out;
+  float* part;          // readout variant: chunk sums [chunk + graph][256]
+  const int* chunk_first;   // readout variant: the graph that holds the first row of a chunk of 64 rows
+  const int* node_off;
+  int n_graphs;
   char* smem;
   unsigned lds0;        // LDS byte address of smem
   int ntot, tile0, per, wm, wn, l32, lh, lane, wave, sw;
@@ -266,13 +270,108 @@ __device__ __forceinline__ void write_tile(int ti, f32x16 (&acc)[2][2], const Mu
   }
 }
 
+// The last layer of a forward pass with a sum readout need not write its rows at all: what the readout
+// needs of tile ti is, per graph and column, the sum over the tile's rows of that graph.  A wave holds
+// 64 rows (one chunk of 64 consecutive global row numbers) x 64 columns.  Per graph with rows in the
+// chunk: the values (bias, ReLU, rounded to bf16 exactly as they would be stored) of rows outside the
+// graph are replaced by +0, then the 64 places are summed in fp32 in the fixed tree the readout kernel
+// documents -- place l + place l + 32 in registers, then neighbouring lanes, quads, eights, sixteens
+// (data-parallel primitives within a row of 16 lanes) and the two rows of 16 (v_permlane16_swap) --, and
+// lane l32 keeps the column it stores: 256 bytes per wave, graph and tile.  Returns the number of
+// stores issued (wave-uniform).
+template <int CTRL>
+__device__ __forceinline__ float lanes_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+template <int DCH>
+__device__ __forceinline__ int write_tile_readout(int ti, f32x16 (&acc)[2][2], const MulCtx& c) {
+  const int k = 2 * (c.tile0 + ti * c.per) + c.wm;          // chunk number
+  const int r0 = 64 * k;
+  int n_stores = 0;
+  if (r0 < c.ntot) {                                        // else: the second half of a ragged last tile (uniform)
+    // the values as they would be stored, kept in the accumulators' registers
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 bq = *reinterpret_cast<const float4*>(c.bias64 + j * 32 + 8 * q + 4 * c.lh);
+          const unsigned p0 = pack_bf16x2(fmaxf(acc[i][j][4 * q + 0] + bq.x, 0.f), fmaxf(acc[i][j][4 * q + 1] + bq.y, 0.f));
+          const unsigned p1 = pack_bf16x2(fmaxf(acc[i][j][4 * q + 2] + bq.z, 0.f), fmaxf(acc[i][j][4 * q + 3] + bq.w, 0.f));
+          acc[i][j][4 * q + 0] = __uint_as_float(p0 << 16);
+          acc[i][j][4 * q + 1] = __uint_as_float(p0 & 0xFFFF0000u);
+          acc[i][j][4 * q + 2] = __uint_as_float(p1 << 16);
+          acc[i][j][4 * q + 3] = __uint_as_float(p1 & 0xFFFF0000u);
+        }
+    const int r1 = min(r0 + 64, c.ntot);
+    const int row0 = r0 + c.l32, row1 = row0 + 32;
+    // lane l32 stores column (l32 / 16) * 32 + 8 * ((l32 / 4) % 4) + 4 * (lane / 32) + l32 % 4 of the wave's 64
+    const int col = c.wn * 64 + (c.l32 >> 4) * 32 + 8 * ((c.l32 >> 2) & 3) + 4 * c.lh + (c.l32 & 3);
+    int g = __builtin_amdgcn_readfirstlane(c.chunk_first[k]);
+    for (;;) {
+      const int lo = __builtin_amdgcn_readfirstlane(c.node_off[g]);
+      const int hi = __builtin_amdgcn_readfirstlane(c.node_off[g + 1]);
+      const bool whole = lo <= r0 && hi >= r0 + 64;         // every place of the chunk is a row of this graph
+      const bool in0 = row0 >= lo && row0 < hi, in1 = row1 >= lo && row1 < hi;
+      float mine = 0.f;
+      // eight columns at a time, level by level: the lane exchanges of one level do not depend on each other
+#pragma unroll
+      for (int b = 0; b < 32; b += 8) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int j = (b + e) >> 4, v = (b + e) & 15;
+          float a0 = acc[0][j][v], a1 = acc[1][j][v];
+          if (!whole) {
+            a0 = in0 ? a0 : 0.f;
+            a1 = in1 ? a1 : 0.f;
+          }
+          x[e] = a0 + a1;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0xB1>(x[e]);    // quad_perm [1,0,3,2]: lane ^ 1
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0x4E>(x[e]);    // quad_perm [2,3,0,1]: lane ^ 2
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0x141>(x[e]);   // row_half_mirror: the other quad of eight
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0x140>(x[e]);   // row_mirror: the other eight of sixteen
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const v2u sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(x[e]), __float_as_uint(x[e]), false, false);
+          x[e] = __uint_as_float(sw.x) + __uint_as_float(sw.y);      // this row of 16 lanes + the other one
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mine = c.l32 == b + e ? x[e] : mine;
+      }
+      c.part[(size_t)(k + g) * kBN + col] = mine;
+      ++n_stores;
+      if (hi >= r1 || g + 1 >= c.n_graphs) break;           // the next graph starts behind this chunk (uniform)
+      ++g;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  return n_stores;
+}
+
 // Step g of a multiplying wave: request the copies for step g + 2 and run the products of step g --
 // the two multiplying waves of a SIMD in opposite order, so that while one stands in the queue of
 // the vector-memory unit with its requests the other one multiplies -- then make sure what was
 // requested one step ago has landed and, at the end of a tile, write the tile out.  (Writing it out
 // behind the barrier, at the next tile's first step, was measured 2 % slower.)
-template <int DCH>
-__device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], const MulCtx& c) {
+template <int DCH, bool RO>
+__device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], const MulCtx& c, int& tile_stores) {
   constexpr int NK = Shape<DCH>::NK;
   const bool products_first = c.wm == 0;
   if (products_first) products<DCH>(g, acc, c);
@@ -282,10 +381,15 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
   // step's n_req copies, and older than the eight stores of a tile that ended one step ago (those
   // were issued after that step's copies: they are counted, not waited for); placed before this
   // tile's stores so that it never waits for those.  The last tile of the batch may issue fewer
-  // stores; it is the last tile of its workgroup, and nothing is waited for after it.
-  const int stores_behind = (g >= 1 && ((g - 1) % NK) == NK - 1) ? 8 : 0;
+  // stores; it is the last tile of its workgroup, and nothing is waited for after it.  The readout
+  // variant issues one store per graph in the wave's rows: counting fewer than were issued (an even
+  // number, eight at most) only waits for some of them.
+  const int stores_behind = (g >= 1 && ((g - 1) % NK) == NK - 1) ? (RO ? min(tile_stores & ~1, 8) : 8) : 0;
   wait_copies(__builtin_amdgcn_readfirstlane(n_req + stores_behind));
-  if (g >= 0 && (g % NK) == NK - 1) write_tile<DCH>(g / NK, acc, c);
+  if (g >= 0 && (g % NK) == NK - 1) {
+    if constexpr (RO) tile_stores = write_tile_readout<DCH>(g / NK, acc, c);
+    else write_tile<DCH>(g / NK, acc, c);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -435,11 +539,12 @@ __device__ __forceinline__ void mean_tile(int t, MeanState<DCH>& st, const MeanC
   if constexpr (s + 1 < Shape<DCH>::NK) mean_tile<DCH, s + 1>(t, st, c);
 }
 
-template <int DCH>
+template <int DCH, bool RO>
 __global__ __launch_bounds__(kNT) void layer256w_kernel(
     const u16* __restrict__ h, const u16* __restrict__ hin_heavy, const u16* __restrict__ hout_heavy,
     const v4i* __restrict__ desc_in, const v4i* __restrict__ desc_out, const u16* __restrict__ Wp,
-    const float* __restrict__ bias, u16* __restrict__ out, const int* __restrict__ node_off, int C,
+    const float* __restrict__ bias, u16* __restrict__ out, float* __restrict__ part,
+    const int* __restrict__ chunk_first, const int* __restrict__ node_off, int C,
     const int* __restrict__ status) {
   constexpr int NK = Shape<DCH>::NK;
   if (status[0] != 0) return;
@@ -473,6 +578,10 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
     mc.wn = wave & 3;
     mc.bias64 = reinterpret_cast<const float*>(smem + kBiasOff) + mc.wn * 64;
     mc.out = out;
+    mc.part = part;
+    mc.chunk_first = chunk_first;
+    mc.node_off = node_off;
+    mc.n_graphs = C;
     mc.smem = smem;
     mc.lds0 = (unsigned)(size_t)((lds_char*)dc_l256w_smem);
     mc.ntot = ntot;
@@ -483,8 +592,9 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
     mc.lane = lane;
     mc.sw = ((lane & 31) >> 1) & 7;
     mc.wave = wave;
+    int tile_stores = 0;
     for (int g = -2; g < S; ++g) {
-      mul_step<DCH>(g, S, acc, mc);
+      mul_step<DCH, RO>(g, S, acc, mc, tile_stores);
       lds_barrier();
     }
   } else {
@@ -669,10 +779,11 @@ __global__ __launch_bounds__(256) void heavy_means_kernel(
   }
 }
 
-template <int DCH>
+template <int DCH, bool RO>
 hipError_t launch_w(const void* h, const GnnArgs& a, const void* Wl, const float* bias, void* out, hipStream_t s) {
   static bool attr_done = false;
-  auto kern = layer256w_kernel<DCH>;
+  auto kern = layer256w_kernel<DCH, RO>;
+  if (RO && (!a.ro_part || !a.ro_first)) return hipErrorInvalidValue;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -683,11 +794,31 @@ hipError_t launch_w(const void* h, const GnnArgs& a, const void* Wl, const float
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), kLdsTotal, s, static_cast<const u16*>(h),
                      static_cast<const u16*>(a.agg[0]), static_cast<const u16*>(a.agg[1]),
                      static_cast<const v4i*>(a.desc[0]), static_cast<const v4i*>(a.desc[1]),
-                     static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.node_off, a.n_cand, a.status);
+                     static_cast<const u16*>(Wl), bias, static_cast<u16*>(out), a.ro_part, a.ro_first, a.node_off,
+                     a.n_cand, a.status);
   return hipGetLastError();
 }
 
+// The graph that holds the first row of every chunk of 64 rows: thread c marks the chunks that begin
+// inside graph c.
+__global__ __launch_bounds__(256) void chunk_first_kernel(const int* __restrict__ node_off, int C,
+                                                           int* __restrict__ chunk_first,
+                                                           const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  const int n0 = node_off[c], n1 = node_off[c + 1];
+  for (int k = (n0 + 63) >> 6; 64 * k < n1; ++k) chunk_first[k] = c;
+}
+
 }  // namespace
+
+hipError_t launch_chunk_first(const GnnArgs& a, hipStream_t s) {
+  if (!a.ro_first) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(chunk_first_kernel, dim3((a.n_cand + 255) / 256), dim3(256), 0, s, a.node_off, a.n_cand, a.ro_first,
+                     a.status);
+  return hipGetLastError();
+}
 
 hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(build_desc_sorted_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
@@ -714,9 +845,9 @@ hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_
 
 // The layer kernel alone (sorted descriptors built, pre-pass means in a.agg[]): d = 256 or 64, three gather slots.
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
-                            hipStream_t s) {
-  if (d == 256) return launch_w<4>(h, a, Wl, bias, out, s);
-  if (d == 64) return launch_w<1>(h, a, Wl, bias, out, s);
+                            bool readout, hipStream_t s) {
+  if (d == 256) return readout ? launch_w<4, true>(h, a, Wl, bias, out, s) : launch_w<4, false>(h, a, Wl, bias, out, s);
+  if (d == 64) return readout ? launch_w<1, true>(h, a, Wl, bias, out, s) : launch_w<1, false>(h, a, Wl, bias, out, s);
   return hipErrorInvalidValue;
 }
 
