@@ -23,7 +23,7 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def algorithmic_work(w, ntot, etot):
+def algorithmic_work(w, ntot, etot, fused_readout=False):
     """Bytes / flops each kernel family must move or compute per step (what the
     method needs, not what an implementation happens to touch)."""
     m = w.model
@@ -48,7 +48,8 @@ def algorithmic_work(w, ntot, etot):
     agg_b, upd_f, upd_b = 0, 0, 0
     fus = {"fused_layer": [0, 0], "layer256": [0, 0], "layer256_d64": [0, 0]}
     d = m.F
-    for _ in range(m.L):
+    readout_b = ntot * m.H * s
+    for l in range(m.L):
         bulk = m.dtype == "bf16" and m.H == 256 and d in (256, 64)
         fused = m.dtype == "bf16" and m.H in (128, 256) and d % 64 == 0
         idx = 2 * 4 * (ntot + etot)
@@ -56,7 +57,11 @@ def algorithmic_work(w, ntot, etot):
         if fused:       # means never leave the chip: read h, write h', read the neighbour lists and W
             k = fus[("layer256" if d == 256 else "layer256_d64") if bulk else "fused_layer"]
             k[0] += flops
-            k[1] += ntot * d * s + ntot * m.H * s + idx + 3 * d * m.H * s
+            out_b = ntot * m.H * s
+            if bulk and fused_readout and l == m.L - 1:
+                # the last layer leaves column sums per 64 rows and graph instead of its rows; the readout reads those
+                out_b = readout_b = (ntot // 64 + C) * m.H * 4
+            k[1] += ntot * d * s + out_b + idx + 3 * d * m.H * s
         else:           # read h, write both means; then read [h|h_in|h_out] and W, write h'
             agg_b += ntot * d * s + 2 * ntot * d * s + idx
             upd_f += flops
@@ -67,7 +72,7 @@ def algorithmic_work(w, ntot, etot):
             "fused_layer": {"flops": fus["fused_layer"][0], "bytes": fus["fused_layer"][1]},
             "layer256": {"flops": fus["layer256"][0], "bytes": fus["layer256"][1]},
             "layer256_d64": {"flops": fus["layer256_d64"][0], "bytes": fus["layer256_d64"][1]},
-            "readout_head": {"bytes": ntot * m.H * s}}
+            "readout_head": {"bytes": readout_b}}
 
 
 def long_list_stats(ev, w, cg, co, gid, ntot, etot, torch):
@@ -521,7 +526,7 @@ def main():
     fam = ev.profile_end()
     assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
 
-    work = algorithmic_work(w, ntot, etot)
+    work = algorithmic_work(w, ntot, etot, fused_readout=args.kernels == 0 and args.aggregator == "mean")
     if fam.get("aggregate_heavy", (0, 0))[1] > 0 and args.kernels == 0:
         pairs, entries = long_list_stats(ev, w, cg, co, gid, ntot, etot, torch)
         work["aggregate_heavy"] = pre_pass_work(w, pairs, entries)

@@ -359,9 +359,10 @@ __global__ __launch_bounds__(512) void update32_kernel(const float* __restrict__
 // kOrder = 1, 2 (bf16, H = 256: the shapes of the bulk layer kernel, which can form the sums itself):
 // the rows are taken in chunks of 64 consecutive global row numbers (chunk k = rows 64k .. 64k+63).
 // Per chunk and column the 64 places -- a place holds the row's value if the row belongs to the
-// graph, else +0 -- are summed in fp32 in one fixed tree: u_l = place l + place l+32 (l = 0..31),
-// then pairs of neighbours ((u0+u1)+(u2+u3))+... up to the root; the chunk sums of a graph are added
-// in fp64 in ascending chunk order.  1 forms the chunk sums here from h; 2 reads them from `part`,
+// graph, else +0 -- are summed in fp32 in one fixed tree (the one the bulk kernel's lane exchanges give):
+//   u_l = place l + place l+32 (l < 32), A_l = u_l + u_{l+16} (l < 16), B_l = A_l + A_{15-l} (l < 8),
+//   C_l = B_l + B_{7-l} (l < 4), sum = (C_0 + C_2) + (C_1 + C_3);
+// the chunk sums of a graph are added in fp64 in ascending chunk order.  1 forms the chunk sums here from h; 2 reads them from `part`,
 // where the last layer's kernel left them (the sum of chunk k for graph c at row k + c: both grow
 // along the rows, so the place is unique).  The same tree on both routes: the same bits.
 // ---------------------------------------------------------------------------
@@ -374,7 +375,7 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
   if (status[0] != 0) return;
   constexpr int kPer = kBf16 ? 8 : 4;
   __shared__ double red[kOrder == 0 ? 256 * kPer : 1];   // [row group][H] partial sums
-  __shared__ float sub[kOrder == 1 ? 2 * 8 * 256 : 1];   // [buffer][row lane][column]: sums of four u's
+  __shared__ float sub[kOrder == 1 ? 2 * 8 * 256 : 1];   // [buffer][row lane m][column]: B_m
   __shared__ float r[512], z[512];
   __shared__ double wred[4];
   const int c = blockIdx.x, t = threadIdx.x;
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
       for (int k = n0 >> 6; k <= (n1 - 1) >> 6; ++k) acc += (double)part[(size_t)(k + c) * 256 + t];
     r[t] = (float)acc;
   } else if constexpr (kOrder == 1) {
-    // thread (row lane m = t / 32, 16-byte piece t % 32): places 4m .. 4m+3 and 32 more; column t in the second half
+    // thread (row lane m = t / 32, 16-byte piece t % 32) forms B_m from its eight places; then thread t column t
     const int m = t >> 5, ch = t & 31;
     const uint4* h4 = reinterpret_cast<const uint4*>(h);
     double acc = 0.0;
@@ -396,7 +397,9 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
         uint4 x[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const int row = 64 * k + 4 * m + (i & 3) + 32 * (i >> 2);
+          // places m, m+32, m+16, m+48 (A_m), then 15-m, 47-m, 31-m, 63-m (A_{15-m})
+          const int place = (i < 4 ? m : 15 - m) + 32 * (i & 1) + 16 * ((i >> 1) & 1);
+          const int row = 64 * k + place;
           x[i] = (row >= n0 && row < n1) ? h4[(size_t)row * 32 + ch] : make_uint4(0u, 0u, 0u, 0u);
         }
         float* dst = sub + (buf * 8 + m) * 256 + ch * 8;
@@ -409,12 +412,13 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
             lo[i] = __uint_as_float(v << 16);
             hi[i] = __uint_as_float(v & 0xFFFF0000u);
           }
-          dst[2 * w] = ((lo[0] + lo[4]) + (lo[1] + lo[5])) + ((lo[2] + lo[6]) + (lo[3] + lo[7]));
-          dst[2 * w + 1] = ((hi[0] + hi[4]) + (hi[1] + hi[5])) + ((hi[2] + hi[6]) + (hi[3] + hi[7]));
+          dst[2 * w] = ((lo[0] + lo[1]) + (lo[2] + lo[3])) + ((lo[4] + lo[5]) + (lo[6] + lo[7]));
+          dst[2 * w + 1] = ((hi[0] + hi[1]) + (hi[2] + hi[3])) + ((hi[4] + hi[5]) + (hi[6] + hi[7]));
         }
         __syncthreads();                    // two buffers: the next chunk's sums go to the other one
         const float* q = sub + buf * 8 * 256 + t;
-        acc += (double)(((q[0] + q[256]) + (q[512] + q[768])) + ((q[1024] + q[1280]) + (q[1536] + q[1792])));
+        // B_0 .. B_7 at q[0], q[256], ...: ((B0 + B7) + (B2 + B5)) + ((B1 + B6) + (B3 + B4))
+        acc += (double)(((q[0] + q[1792]) + (q[512] + q[1280])) + ((q[256] + q[1536]) + (q[768] + q[1024])));
       }
     r[t] = (float)acc;
   }

@@ -275,13 +275,11 @@ __device__ __forceinline__ void write_tile(int ti, f32x16 (&acc)[2][2], const Mu
 // 64 rows (one chunk of 64 consecutive global row numbers) x 64 columns.  Per graph with rows in the
 // chunk: the values (bias, ReLU, rounded to bf16 exactly as they would be stored) of rows outside the
 // graph are replaced by +0, then the 64 places are summed in fp32 in the fixed tree the readout kernel
-// documents -- place l + place l + 32 in registers, then neighbouring lanes, quads, eights, sixteens
-// (data-parallel primitives within a row of 16 lanes) and the two rows of 16 (v_permlane16_swap) --, and
-// lane l32 keeps the column it stores: 256 bytes per wave, graph and tile.  Returns the number of
-// stores issued (wave-uniform).
+// documents, by exchanges between lanes, and lane l32 ends with the column it stores: 256 bytes per
+// wave, graph and tile.  Returns the number of stores issued (wave-uniform).
 template <int CTRL>
-__device__ __forceinline__ float lanes_add(float x) {
-  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+__device__ __forceinline__ float lanes_get(float x) {       // x of the lane the data-parallel pattern CTRL names
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
 }
 template <int DCH>
 __device__ __forceinline__ int write_tile_readout(int ti, f32x16 (&acc)[2][2], const MulCtx& c) {
@@ -314,42 +312,38 @@ __device__ __forceinline__ int write_tile_readout(int ti, f32x16 (&acc)[2][2], c
       const int hi = __builtin_amdgcn_readfirstlane(c.node_off[g + 1]);
       const bool whole = lo <= r0 && hi >= r0 + 64;         // every place of the chunk is a row of this graph
       const bool in0 = row0 >= lo && row0 < hi, in1 = row1 >= lo && row1 < hi;
-      float mine = 0.f;
-      // eight columns at a time, level by level: the lane exchanges of one level do not depend on each other
+      // u_n = place l32 + place l32 + 32 of column n (n = 16 j + v).  Then five exchanges, each of which
+      // halves what a lane holds: of the pair (n, n + half) a lane keeps the one its lane bit names, adds
+      // what its partner sends of it and gives the other away.  Partners: the lane 16 further (rows of 16
+      // swapped), then within a row of 16 lanes the mirrored lane, within eight the mirrored lane, lane ^ 2,
+      // lane ^ 1.  In the end lane l32 holds column n = l32, summed in the tree the readout kernel documents.
+      float y[16];
 #pragma unroll
-      for (int b = 0; b < 32; b += 8) {
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int j = (b + e) >> 4, v = (b + e) & 15;
-          float a0 = acc[0][j][v], a1 = acc[1][j][v];
-          if (!whole) {
-            a0 = in0 ? a0 : 0.f;
-            a1 = in1 ? a1 : 0.f;
-          }
-          x[e] = a0 + a1;
+      for (int n = 0; n < 16; ++n) {
+        float a0 = acc[0][0][n], a1 = acc[1][0][n], b0 = acc[0][1][n], b1 = acc[1][1][n];
+        if (!whole) {
+          a0 = in0 ? a0 : 0.f;
+          a1 = in1 ? a1 : 0.f;
+          b0 = in0 ? b0 : 0.f;
+          b1 = in1 ? b1 : 0.f;
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0xB1>(x[e]);    // quad_perm [1,0,3,2]: lane ^ 1
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0x4E>(x[e]);    // quad_perm [2,3,0,1]: lane ^ 2
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0x141>(x[e]);   // row_half_mirror: the other quad of eight
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = lanes_add<0x140>(x[e]);   // row_mirror: the other eight of sixteen
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const v2u sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(x[e]), __float_as_uint(x[e]), false, false);
-          x[e] = __uint_as_float(sw.x) + __uint_as_float(sw.y);      // this row of 16 lanes + the other one
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) mine = c.l32 == b + e ? x[e] : mine;
+        // lanes 0..15 of a half keep column n and get the partner's u_n, lanes 16..31 keep column n + 16
+        const v2u sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(a0 + a1), __float_as_uint(b0 + b1), false, false);
+        y[n] = __uint_as_float(sw.x) + __uint_as_float(sw.y);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      const bool b3 = (c.l32 & 8) != 0, b2 = (c.l32 & 4) != 0, b1 = (c.l32 & 2) != 0, b0 = (c.l32 & 1) != 0;
+      float z[8], w[4], t2[2];
+#pragma unroll
+      for (int n = 0; n < 8; ++n) z[n] = (b3 ? y[n + 8] : y[n]) + lanes_get<0x140>(b3 ? y[n] : y[n + 8]);   // row_mirror
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) w[n] = (b2 ? z[n + 4] : z[n]) + lanes_get<0x141>(b2 ? z[n] : z[n + 4]);   // row_half_mirror
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int n = 0; n < 2; ++n) t2[n] = (b1 ? w[n + 2] : w[n]) + lanes_get<0x4E>(b1 ? w[n] : w[n + 2]);   // lane ^ 2
+      __builtin_amdgcn_sched_barrier(0);
+      const float mine = (b0 ? t2[1] : t2[0]) + lanes_get<0xB1>(b0 ? t2[0] : t2[1]);                         // lane ^ 1
       c.part[(size_t)(k + g) * kBN + col] = mine;
       ++n_stores;
       if (hi >= r1 || g + 1 >= c.n_graphs) break;           // the next graph starts behind this chunk (uniform)

@@ -497,6 +497,32 @@ def test_bulk_layer_with_every_kind_of_ragged_last_tile(B):
         check_predictions(w, fused, np.arange(C), tag=f"ragged {n_nodes}x{C}")
 
 
+def test_readout_formed_by_the_last_layer_with_many_graphs_per_chunk(B):
+    """With the bulk shapes the last layer leaves, per chunk of 64 rows and graph, the column sums the readout
+    needs instead of its rows.  Batches of tiny graphs put many graphs into one chunk, graphs of 64 and 128
+    nodes end exactly on chunk borders, larger ones span several chunks: the predictions must equal those of
+    the separate kernels (which sum the stored rows in the same tree) bit for bit, and the oracle's within
+    tolerance; one layer only (d = 64 is then the last layer) as well."""
+    sizes = [1, 2, 3, 5, 7, 20, 31, 32, 33, 64, 64, 128, 100, 200, 1, 4, 60, 63, 65, 130]
+    graphs = [wl.random_dag(500 + i, n, min(1.0, 2.5 / max(n, 2)), 64) for i, n in enumerate(sizes)]
+    for L in (2, 1):
+        model = wl.ModelSpec(64, 256, L, "bf16")
+        labs = [np.tile(np.arange(g.n, dtype=np.int32), (3, 1)) for g in graphs]
+        w = wl.with_time_like_head(wl.custom(f"tiny-graphs-L{L}", model, graphs, labs, seed=6))
+        ev = B.evaluator_for(w)
+        cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+        fused = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        again = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.select_kernels(B.DC_KERNELS_SEPARATE_LAYERS)
+        plain = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.close()
+        assert np.array_equal(fused, again)
+        assert np.array_equal(fused, plain), (L, np.abs(fused - plain).max(), int(np.abs(fused - plain).argmax()))
+        check_predictions(w, fused, np.arange(w.n_cand), tag=f"tiny graphs L={L}")
+
+
 def test_eval_is_capturable_in_a_hip_graph_and_replays_identically(B):
     """dc_eval_candidates enqueues kernels on the caller's stream only (no host round trip, no
     allocation, no memset), so a caller may capture it; every replay, with eager work and
