@@ -2,7 +2,8 @@
 // bf16 (gfx950):
 //     h'[v] = ReLU([h[v] | mean_pred(h)[v] | mean_succ(h)[v]] W + b)
 // (neighbourhood encoding of Sec. 3.3.1 with uniform coefficients), both means formed on the
-// fly, so that a layer reads h once and writes h' once.
+// fly, so that a layer reads h once and writes h' once (the last layer of a forward pass with a sum
+// readout can leave the readout's sums instead of h': write_tile_readout).
 //
 // One workgroup of 16 waves per CU; every SIMD hosts two waves of each kind, so that one wave's
 // waits are covered by its twin's work.
@@ -11,12 +12,12 @@
 //   (the chunks of W and the node's own K chunks) from global memory straight into the LDS rings,
 //   two steps ahead.  They have no other loads, so their hand-placed waits count exactly these.
 //   Waves 8-15 form the means: a lane owns two (row, 16-byte column) items per K chunk of 64
-//   columns; it loads up to three neighbour pieces per item two steps ahead, adds them in fp32 in
+//   columns; it loads up to four neighbour pieces per item one step ahead, adds them in fp32 in
 //   ascending neighbour order, scales by 1/deg, rounds to bf16 and writes the piece into the A
 //   ring.  These are ordinary loads that the compiler tracks: no register is touched while a
 //   load into it is in flight, and the waits are the compiler's.  The steps of a tile are
 //   unrolled, so chunk offsets, ring slots and the direction are constants of each step.
-// Rows with more than three neighbours take their mean from a pre-pass (one slot: the finished
+// Rows with more than four neighbours take their mean from a pre-pass (one slot: the finished
 // mean), so that no lane walks a long list here.  The descriptors of a tile come sorted by the
 // number of slots that count, separately per direction: a lane may form the mean of any row of the
 // tile (it writes the piece to that row's place in the A chunk), so the eight rows that share a load
@@ -391,11 +392,12 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
 // ------------------------------------------------------------------------------------------
 struct Dsc {            // one (row, direction) of the tile at hand, decoded for this lane's column piece
   const char* p0;       // first slot: the first neighbour's piece, or the row's finished mean from the pre-pass
-  unsigned o1, o2;      // second and third slot: byte offsets from the tile's base row of h
-  unsigned k1, k2;      // bf16 1.0 where the slot counts, 0 where it does not
-  float sc;             // 1 / (number of slots that count), 0 for an empty list
+  unsigned o1, o2, o3;  // second to fourth slot: byte offsets from the tile's base row of h
+  int ns;               // slots that count (0..4): slot u counts where u < ns
+  float sc;             // 1 / ns, 0 for an empty list
   int aoff;             // swizzled LDS offset of (row, piece) within an A chunk
 };
+constexpr int kSlots = 4;   // neighbours gathered in the layer kernel per row and direction, at most
 
 struct MeanCtx {
   const char* h;
@@ -414,10 +416,10 @@ template <int DCH>
 struct MeanState {
   Dsc cur[2][2];        // [direction][item]
   v4i raw[2][2];        // the next tile's descriptors as loaded
-  v4u ld[2][2][3];      // neighbour pieces in flight: [consuming step & 1][item][slot]
+  v4u ld[2][2][kSlots]; // neighbour pieces in flight: [consuming step & 1][item][slot]
   const char* hb;       // h at the base row of the tile `cur` belongs to (uniform)
   int base_row;
-  bool two[2][2], three[2][2];   // wave-uniform: some row of the item has a second / a third slot that counts
+  bool two[2][2], three[2][2], four[2][2];   // wave-uniform: some row of the item has a second / third / fourth slot that counts
 };
 
 template <int DCH>
@@ -445,23 +447,25 @@ __device__ __forceinline__ void adopt_descriptors(MeanState<DCH>& st, const Mean
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const v4i d = st.raw[dir][i];
-      // last word: low byte = the number of slots that count (0..3), or 5 for a row left to the pre-pass,
-      // which has one slot (its finished mean, at the row's own place in the pre-pass buffer); above it
-      // the row's place in the tile
-      const int code = d.w & 255, row = (d.w >> 8) & (kBM - 1);
-      const int ns = code > 3 ? 1 : code;
+      // last word: bits 0-2 = the number of slots that count (0..4), or 5 for a row left to the pre-pass,
+      // which has one slot (its finished mean, at the row's own place in the pre-pass buffer); bits 3-9 the
+      // row's place in the tile; above them the fourth neighbour's distance from the third
+      const int code = d.w & 7, row = (d.w >> 3) & (kBM - 1);
+      const int ns = code > kSlots ? 1 : code;
       Dsc& o = st.cur[dir][i];
       o.aoff = swz(row, c.piece);
       st.two[dir][i] = __ballot(ns > 1) != 0;
       st.three[dir][i] = __ballot(ns > 2) != 0;
-      o.p0 = (code > 3 ? (dir ? c.hout : c.hin) : c.h) + (size_t)(unsigned)d.x * ROWB + c.cb;
+      st.four[dir][i] = __ballot(ns > 3) != 0;
+      o.p0 = (code > kSlots ? (dir ? c.hout : c.hin) : c.h) + (size_t)(unsigned)d.x * ROWB + c.cb;
       o.o1 = (unsigned)(d.y - st.base_row) * ROWB + c.cb;
       o.o2 = (unsigned)(d.z - st.base_row) * ROWB + c.cb;
-      o.k1 = ns > 1 ? 0x3F80u : 0u;
-      o.k2 = ns > 2 ? 0x3F80u : 0u;
+      o.o3 = (unsigned)(d.z + (int)((unsigned)d.w >> 10) - st.base_row) * ROWB + c.cb;
+      o.ns = ns;
       unsigned scb = ns == 1 ? 0x3F800000u : 0u;
       scb = ns == 2 ? 0x3F000000u : scb;
       scb = ns == 3 ? 0x3EAAAAABu : scb;             // 1/3 rounded to nearest
+      scb = ns == 4 ? 0x3E800000u : scb;
       o.sc = __uint_as_float(scb);
     }
 }
@@ -498,12 +502,19 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
           // slot counts
           lo[w] = __uint_as_float(x0[w] << 16);
           hi[w] = __uint_as_float(x0[w] & 0xFFFF0000u);
-          bf16_pair_add(lo[w], hi[w], x1[w], d.k1);
+          bf16_pair_add(lo[w], hi[w], x1[w], d.ns > 1 ? 0x3F80u : 0u);   // bf16 1.0 where the slot counts, else 0
         }
         if (st.three[dir][i]) {
           const v4u x2 = st.ld[rq & 1][i][2];
+          const unsigned k2 = d.ns > 2 ? 0x3F80u : 0u;
 #pragma unroll
-          for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], x2[w], d.k2);
+          for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], x2[w], k2);
+        }
+        if (st.four[dir][i]) {
+          const v4u x3 = st.ld[rq & 1][i][3];
+          const unsigned k3 = d.ns > 3 ? 0x3F80u : 0u;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], x3[w], k3);
         }
 #pragma unroll
         for (int w = 0; w < 4; ++w) o[w] = pack_bf16x2(lo[w] * d.sc, hi[w] * d.sc);   // x * 1.0 repacks to the same bf16 value
@@ -522,6 +533,7 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
       st.ld[lq & 1][i][0] = *reinterpret_cast<const v4u*>(d.p0 + coff);
       if (st.two[dir][i]) st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
       if (st.three[dir][i]) st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
+      if (st.four[dir][i]) st.ld[lq & 1][i][3] = *reinterpret_cast<const v4u*>(st.hb + d.o3 + coff);
     }
   }
 }
@@ -614,7 +626,7 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int u = 0; u < 3; ++u) st.ld[p][i][u] = v4u{0u, 0u, 0u, 0u};
+        for (int u = 0; u < kSlots; ++u) st.ld[p][i][u] = v4u{0u, 0u, 0u, 0u};
     // steps -2 and -1: the first tile's descriptors; with d = 64 its first chunk of means is
     // requested here, as the last step of a tile does for the tile after it
     request_descriptors<DCH>(st, mc, 0);
@@ -627,10 +639,12 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
 
 // One gather descriptor per node and direction, stored tile by tile (128 per tile, also for the last one)
 // and, within a tile, sorted by the number of slots that count: first the rows with at most one (a single
-// neighbour, a finished mean from the pre-pass, or none), then two, then three.  Words: the first three
+// neighbour, a finished mean from the pre-pass, or none), then two, three, four.  Words: the first three
 // neighbours (unused slots, empty lists and rows left to the pre-pass point at the node itself, always a
-// valid row); then the code (0..3 slots that count, 5 = left to the pre-pass) in the low byte and the
-// row's place in its tile above it.  Places of the last tile past the end of the batch are empty lists.
+// valid row); then, from the low end, the code (0..4 slots that count, 5 = left to the pre-pass) in three
+// bits, the row's place in its tile in seven, and the fourth neighbour's distance from the third (lists
+// ascend within one graph of fewer than 65536 nodes).  Places of the last tile past the end of the batch
+// are empty lists.
 // Depends only on the graphs: built once per forward pass.  One workgroup of 256 per tile: threads
 // 0..127 the predecessors' lists, 128..255 the successors'.
 __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
@@ -639,7 +653,7 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
     int* __restrict__ heavy_in, int* __restrict__ heavy_out, int* __restrict__ heavy_cnt,
     const int* __restrict__ node_off, int C, const int* __restrict__ status) {
   if (status[0] != 0) return;
-  __shared__ int cnt[2][4][4];               // [parity][wave][class, and the rows left to the pre-pass]
+  __shared__ int cnt[2][4][kSlots + 1];      // [parity][wave][class, and the rows left to the pre-pass]
   const int ntot = node_off[C];
   const int ntiles = (ntot + kBM - 1) / kBM;
   const int t = threadIdx.x, wave = t >> 6, lane = t & 63, dir = t >> 7, r = t & 127;
@@ -651,42 +665,43 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
     const int* rp = dir ? out_rp : in_rp;
     const int* ci = dir ? out_ci : in_ci;
     const int s = rp[vv], dg = valid ? rp[vv + 1] - s : 0;
-    const int ns = dg > 3 ? 1 : dg;
+    const int ns = dg > kSlots ? 1 : dg;
     const int cls = ns <= 1 ? 0 : ns - 1;
     int rank = 0;
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
+    for (int k = 0; k < kSlots; ++k) {
       const unsigned long long m = __ballot(cls == k);
       if (cls == k) rank = __popcll(m & ((1ull << lane) - 1ull));
       if (lane == 0) cnt[par][wave][k] = __popcll(m);
     }
     // the rows left to the pre-pass, in ascending order, for the kernel that forms their means
-    const unsigned long long mh = __ballot(dg > 3);
+    const unsigned long long mh = __ballot(dg > kSlots);
     const int hrank = __popcll(mh & ((1ull << lane) - 1ull));
-    if (lane == 0) cnt[par][wave][3] = __popcll(mh);
+    if (lane == 0) cnt[par][wave][kSlots] = __popcll(mh);
     __syncthreads();                           // the next tile writes the other parity: one barrier per tile
     const int w0 = dir * 2;
     int start = 0;
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
+    for (int k = 0; k < kSlots; ++k) {
       const int c0 = cnt[par][w0][k], c1 = cnt[par][w0 + 1][k];
       if (k < cls) start += c0 + c1;
       if (k == cls && (wave & 1)) start += c0;
     }
-    v4i d = v4i{vv, vv, vv, (dg > 3 ? 5 : dg) | (r << 8)};
-    if (dg <= 3 && dg > 0) {
+    v4i d = v4i{vv, vv, vv, (dg > kSlots ? 5 : dg) | (r << 3)};
+    if (dg <= kSlots && dg > 0) {
       d.x = ci[s];                             // unused slots repeat the first neighbour: never loaded or never summed
       d.y = dg > 1 ? ci[s + 1] : d.x;
       d.z = dg > 2 ? ci[s + 2] : d.x;
+      if (dg > 3) d.w |= (ci[s + 3] - d.z) << 10;   // lists ascend within one graph of fewer than 65536 nodes
     }
     (dir ? desc_out : desc_in)[(size_t)tile * kBM + start + rank] = d;
-    const int h0 = cnt[par][w0][3];
-    if (dg > 3) (dir ? heavy_out : heavy_in)[(size_t)tile * kBM + ((wave & 1) ? h0 : 0) + hrank] = v;
-    if (r == 0) heavy_cnt[2 * tile + dir] = h0 + cnt[par][w0 + 1][3];
+    const int h0 = cnt[par][w0][kSlots];
+    if (dg > kSlots) (dir ? heavy_out : heavy_in)[(size_t)tile * kBM + ((wave & 1) ? h0 : 0) + hrank] = v;
+    if (r == 0) heavy_cnt[2 * tile + dir] = h0 + cnt[par][w0 + 1][kSlots];
   }
 }
 
-// Means of the rows with more than three neighbours, one direction of one tile at a time, from the lists
+// Means of the rows with more than four neighbours, one direction of one tile at a time, from the lists
 // the descriptor kernel leaves: LPR = d / 8 lanes (16 bytes each) serve a row; they fetch eight
 // neighbour ids with one load, hand them round, and keep up to eight neighbour rows in flight; the rows
 // are added in ascending list order in fp32 (first one unpacked exactly), scaled by 1/deg and rounded
@@ -837,7 +852,7 @@ hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_
   return hipGetLastError();
 }
 
-// The layer kernel alone (sorted descriptors built, pre-pass means in a.agg[]): d = 256 or 64, three gather slots.
+// The layer kernel alone (sorted descriptors built, pre-pass means in a.agg[]): d = 256 or 64, four gather slots.
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                             bool readout, hipStream_t s) {
   if (d == 256) return readout ? launch_w<4, true>(h, a, Wl, bias, out, s) : launch_w<4, false>(h, a, Wl, bias, out, s);
