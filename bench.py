@@ -76,7 +76,7 @@ def algorithmic_work(w, ntot, etot, fused_readout=False):
 
 
 def long_list_stats(ev, w, cg, co, gid, ntot, etot, torch):
-    """(number of (row, direction) pairs with more than four neighbours -- the layer kernel gathers up to four
+    """(number of (row, direction) pairs with more than five neighbours -- the layer kernel gathers up to five
     itself --, their neighbour count in all) of the contracted batch: what the pre-pass of the bulk layer kernel
     serves.  Outside the timed region."""
     batch = ev.alloc_batch(w.n_cand, int(w.cand_off[-1]), ntot, etot)
@@ -85,7 +85,7 @@ def long_list_stats(ev, w, cg, co, gid, ntot, etot, torch):
     pairs = entries = 0
     for rp in (batch.in_rowptr, batch.out_rowptr):
         deg = (rp[1:ntot + 1] - rp[:ntot]).to(torch.int64)
-        long = deg > 4
+        long = deg > 5
         pairs += int(long.sum())
         entries += int(deg[long].sum())
     del batch

@@ -157,10 +157,10 @@ hipError_t launch_build_desc(const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                            bool readout, Profiler* prof, hipStream_t s);
 hipError_t launch_chunk_first(const GnnArgs& a, hipStream_t s);
-// gnn_layer256w.hip: the same layer (four gather slots) with sixteen waves per workgroup; descriptors and
+// gnn_layer256w.hip: the same layer (five gather slots) with sixteen waves per workgroup; descriptors and
 // pre-pass means as for launch_layer256
 hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s);
-// Means of the rows with more than four neighbours (listed by launch_build_desc_sorted), written at the rows'
+// Means of the rows with more than five neighbours (listed by launch_build_desc_sorted), written at the rows'
 // own places in a.agg[0] (predecessors) and a.agg[1] (successors); h [rows, d], d = 256 or 64, bf16.
 hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_t s);
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,

@@ -12,12 +12,12 @@
 //   (the chunks of W and the node's own K chunks) from global memory straight into the LDS rings,
 //   two steps ahead.  They have no other loads, so their hand-placed waits count exactly these.
 //   Waves 8-15 form the means: a lane owns two (row, 16-byte column) items per K chunk of 64
-//   columns; it loads up to four neighbour pieces per item one step ahead, adds them in fp32 in
+//   columns; it loads up to five neighbour pieces per item one step ahead, adds them in fp32 in
 //   ascending neighbour order, scales by 1/deg, rounds to bf16 and writes the piece into the A
 //   ring.  These are ordinary loads that the compiler tracks: no register is touched while a
 //   load into it is in flight, and the waits are the compiler's.  The steps of a tile are
 //   unrolled, so chunk offsets, ring slots and the direction are constants of each step.
-// Rows with more than four neighbours take their mean from a pre-pass (one slot: the finished
+// Rows with more than five neighbours take their mean from a pre-pass (one slot: the finished
 // mean), so that no lane walks a long list here.  The descriptors of a tile come sorted by the
 // number of slots that count, separately per direction: a lane may form the mean of any row of the
 // tile (it writes the piece to that row's place in the A chunk), so the eight rows that share a load
@@ -39,6 +39,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kBM = 128, kBN = 256, kBK = 64;
 constexpr int kNT = 1024;
 constexpr int kMfmaWaves = 8;
+constexpr int kSlots = 5;   // neighbours gathered in the layer kernel per row and direction, at most (up to 6 fit a descriptor)
 // LDS: a ring of three A chunks (128 rows x 64 columns, the 16-byte pieces of a row XOR-swizzled so
 // that fragment reads are conflict free and a 1 KB copy is eight whole rows), a ring of three
 // B chunks (64 k x 256 columns of W), the bias vector.
@@ -392,12 +393,26 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
 // ------------------------------------------------------------------------------------------
 struct Dsc {            // one (row, direction) of the tile at hand, decoded for this lane's column piece
   const char* p0;       // first slot: the first neighbour's piece, or the row's finished mean from the pre-pass
-  unsigned o1, o2, o3;  // second to fourth slot: byte offsets from the tile's base row of h
-  int ns;               // slots that count (0..4): slot u counts where u < ns
+  unsigned o[kSlots];   // slot u >= 1: byte offset from the tile's base row of h (o[0] unused)
+  int ns_row;           // bits 0-2: slots that count (slot u counts where u < ns); above: the row's place in its tile
   float sc;             // 1 / ns, 0 for an empty list
-  int aoff;             // swizzled LDS offset of (row, piece) within an A chunk
 };
-constexpr int kSlots = 4;   // neighbours gathered in the layer kernel per row and direction, at most
+// A descriptor (16 bytes) as a field of bits: the code (0 .. kSlots slots that count, 7 = left to the pre-pass)
+// in bits 0-2, the row's place in its tile in bits 3-9, then kSlots neighbours of 18 bits each, as distances
+// from the tile's base row (tile * 128 - 65536, at least 0): a graph has fewer than 65536 nodes, so every
+// neighbour of a row of the tile lies less than 2^18 rows above that base.
+constexpr int kDescHeavy = 7;
+__device__ __forceinline__ void desc_put(v4i& d, int f, unsigned v18) {
+  const int pos = 10 + 18 * f, w = pos >> 5, sh = pos & 31;
+  d[w] |= (int)(v18 << sh);
+  if (sh > 14) d[w + 1] |= (int)(v18 >> (32 - sh));
+}
+__device__ __forceinline__ unsigned desc_get(const v4i& d, int f) {
+  const int pos = 10 + 18 * f, w = pos >> 5, sh = pos & 31;
+  unsigned v = (unsigned)d[w] >> sh;
+  if (sh > 14) v |= (unsigned)d[w + 1] << (32 - sh);
+  return v & 0x3FFFFu;
+}
 
 struct MeanCtx {
   const char* h;
@@ -419,7 +434,7 @@ struct MeanState {
   v4u ld[2][2][kSlots]; // neighbour pieces in flight: [consuming step & 1][item][slot]
   const char* hb;       // h at the base row of the tile `cur` belongs to (uniform)
   int base_row;
-  bool two[2][2], three[2][2], four[2][2];   // wave-uniform: some row of the item has a second / third / fourth slot that counts
+  bool more[2][2][kSlots];   // wave-uniform: some row of the item has more than u slots that count
 };
 
 template <int DCH>
@@ -447,26 +462,16 @@ __device__ __forceinline__ void adopt_descriptors(MeanState<DCH>& st, const Mean
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const v4i d = st.raw[dir][i];
-      // last word: bits 0-2 = the number of slots that count (0..4), or 5 for a row left to the pre-pass,
-      // which has one slot (its finished mean, at the row's own place in the pre-pass buffer); bits 3-9 the
-      // row's place in the tile; above them the fourth neighbour's distance from the third
-      const int code = d.w & 7, row = (d.w >> 3) & (kBM - 1);
-      const int ns = code > kSlots ? 1 : code;
+      const int code = d.x & 7, row = (d.x >> 3) & (kBM - 1);
+      const int ns = code > kSlots ? 1 : code;   // a row left to the pre-pass has one slot: its finished mean
       Dsc& o = st.cur[dir][i];
-      o.aoff = swz(row, c.piece);
-      st.two[dir][i] = __ballot(ns > 1) != 0;
-      st.three[dir][i] = __ballot(ns > 2) != 0;
-      st.four[dir][i] = __ballot(ns > 3) != 0;
-      o.p0 = (code > kSlots ? (dir ? c.hout : c.hin) : c.h) + (size_t)(unsigned)d.x * ROWB + c.cb;
-      o.o1 = (unsigned)(d.y - st.base_row) * ROWB + c.cb;
-      o.o2 = (unsigned)(d.z - st.base_row) * ROWB + c.cb;
-      o.o3 = (unsigned)(d.z + (int)((unsigned)d.w >> 10) - st.base_row) * ROWB + c.cb;
-      o.ns = ns;
-      unsigned scb = ns == 1 ? 0x3F800000u : 0u;
-      scb = ns == 2 ? 0x3F000000u : scb;
-      scb = ns == 3 ? 0x3EAAAAABu : scb;             // 1/3 rounded to nearest
-      scb = ns == 4 ? 0x3E800000u : scb;
-      o.sc = __uint_as_float(scb);
+      o.ns_row = ns | (row << 3);
+#pragma unroll
+      for (int u = 1; u < kSlots; ++u) st.more[dir][i][u] = __ballot(ns > u) != 0;
+      o.p0 = (code > kSlots ? (dir ? c.hout : c.hin) : c.h) + (size_t)(st.base_row + (int)desc_get(d, 0)) * ROWB + c.cb;
+#pragma unroll
+      for (int u = 1; u < kSlots; ++u) o.o[u] = desc_get(d, u) * ROWB + c.cb;
+      o.sc = ns > 0 ? 1.0f / (float)ns : 0.f;    // the division the other kernels make
     }
 }
 
@@ -478,7 +483,7 @@ template <int DCH, int s>
 __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanCtx& c) {
   constexpr int NK = Shape<DCH>::NK;
   if constexpr (s == NK - 1) adopt_descriptors<DCH>(st, c, t + 1);
-  if constexpr (s == 0) request_descriptors<DCH>(st, c, t + 1);
+  if constexpr (s == (NK >= 3 ? NK - 2 : 0)) request_descriptors<DCH>(st, c, t + 1);   // one step before they are adopted: not held longer
   constexpr int rq = (s + 1) % NK;                   // the step whose chunk is reduced now
   if constexpr (rq >= DCH) {
     constexpr int dir = rq / DCH - 1;
@@ -486,40 +491,35 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const Dsc& d = st.cur[dir][i];
+      const int ns = d.ns_row & 7, row = d.ns_row >> 3;
       const v4u x0 = st.ld[rq & 1][i][0];
       v4u o;
-      if (!st.two[dir][i]) {
+      if (!st.more[dir][i][1]) {
         // one slot at most in all eight rows: the mean is the neighbour's piece (or the finished mean)
         // as it is, or zero for an empty list
 #pragma unroll
-        for (int w = 0; w < 4; ++w) o[w] = d.sc != 0.f ? x0[w] : 0u;
+        for (int w = 0; w < 4; ++w) o[w] = ns != 0 ? x0[w] : 0u;
       } else {
-        const v4u x1 = st.ld[rq & 1][i][1];
         float lo[4], hi[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           // ascending neighbour order: the first neighbour unpacked exactly, the others added where their
-          // slot counts
+          // slot counts (multiplied by bf16 1.0) and left out where it does not (by 0)
           lo[w] = __uint_as_float(x0[w] << 16);
           hi[w] = __uint_as_float(x0[w] & 0xFFFF0000u);
-          bf16_pair_add(lo[w], hi[w], x1[w], d.ns > 1 ? 0x3F80u : 0u);   // bf16 1.0 where the slot counts, else 0
         }
-        if (st.three[dir][i]) {
-          const v4u x2 = st.ld[rq & 1][i][2];
-          const unsigned k2 = d.ns > 2 ? 0x3F80u : 0u;
 #pragma unroll
-          for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], x2[w], k2);
-        }
-        if (st.four[dir][i]) {
-          const v4u x3 = st.ld[rq & 1][i][3];
-          const unsigned k3 = d.ns > 3 ? 0x3F80u : 0u;
+        for (int u = 1; u < kSlots; ++u)
+          if (st.more[dir][i][u]) {
+            const v4u xu = st.ld[rq & 1][i][u];
+            const unsigned ku = ns > u ? 0x3F80u : 0u;
 #pragma unroll
-          for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], x3[w], k3);
-        }
+            for (int w = 0; w < 4; ++w) bf16_pair_add(lo[w], hi[w], xu[w], ku);
+          }
 #pragma unroll
         for (int w = 0; w < 4; ++w) o[w] = pack_bf16x2(lo[w] * d.sc, hi[w] * d.sc);   // x * 1.0 repacks to the same bf16 value
       }
-      *reinterpret_cast<v4u*>(dst + d.aoff) = o;
+      *reinterpret_cast<v4u*>(dst + swz(row, c.piece)) = o;
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -531,9 +531,9 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
     for (int i = 0; i < 2; ++i) {
       const Dsc& d = st.cur[dir][i];
       st.ld[lq & 1][i][0] = *reinterpret_cast<const v4u*>(d.p0 + coff);
-      if (st.two[dir][i]) st.ld[lq & 1][i][1] = *reinterpret_cast<const v4u*>(st.hb + d.o1 + coff);
-      if (st.three[dir][i]) st.ld[lq & 1][i][2] = *reinterpret_cast<const v4u*>(st.hb + d.o2 + coff);
-      if (st.four[dir][i]) st.ld[lq & 1][i][3] = *reinterpret_cast<const v4u*>(st.hb + d.o3 + coff);
+#pragma unroll
+      for (int u = 1; u < kSlots; ++u)
+        if (st.more[dir][i][u]) st.ld[lq & 1][i][u] = *reinterpret_cast<const v4u*>(st.hb + d.o[u] + coff);
     }
   }
 }
@@ -639,12 +639,10 @@ __global__ __launch_bounds__(kNT) void layer256w_kernel(
 
 // One gather descriptor per node and direction, stored tile by tile (128 per tile, also for the last one)
 // and, within a tile, sorted by the number of slots that count: first the rows with at most one (a single
-// neighbour, a finished mean from the pre-pass, or none), then two, three, four.  Words: the first three
-// neighbours (unused slots, empty lists and rows left to the pre-pass point at the node itself, always a
-// valid row); then, from the low end, the code (0..4 slots that count, 5 = left to the pre-pass) in three
-// bits, the row's place in its tile in seven, and the fourth neighbour's distance from the third (lists
-// ascend within one graph of fewer than 65536 nodes).  Places of the last tile past the end of the batch
-// are empty lists.
+// neighbour, a finished mean from the pre-pass, or none), then two, three, ... kSlots.  The 16 bytes are
+// the field of bits desc_put / desc_get describe: code, the row's place in its tile, kSlots neighbours
+// (unused slots, empty lists and rows left to the pre-pass name the node itself, always a valid row).
+// Places of the last tile past the end of the batch are empty lists.
 // Depends only on the graphs: built once per forward pass.  One workgroup of 256 per tile: threads
 // 0..127 the predecessors' lists, 128..255 the successors'.
 __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
@@ -687,13 +685,13 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
       if (k < cls) start += c0 + c1;
       if (k == cls && (wave & 1)) start += c0;
     }
-    v4i d = v4i{vv, vv, vv, (dg > kSlots ? 5 : dg) | (r << 3)};
-    if (dg <= kSlots && dg > 0) {
-      d.x = ci[s];                             // unused slots repeat the first neighbour: never loaded or never summed
-      d.y = dg > 1 ? ci[s + 1] : d.x;
-      d.z = dg > 2 ? ci[s + 2] : d.x;
-      if (dg > 3) d.w |= (ci[s + 3] - d.z) << 10;   // lists ascend within one graph of fewer than 65536 nodes
-    }
+    const int base = max(tile * kBM - 65536, 0);
+    v4i d = v4i{(dg > kSlots ? kDescHeavy : dg) | (r << 3), 0, 0, 0};
+    // unused slots, empty lists and rows left to the pre-pass name the row itself (always a valid row)
+    const unsigned first = (unsigned)((dg <= kSlots && dg > 0 ? ci[s] : vv) - base);
+    desc_put(d, 0, first);
+#pragma unroll
+    for (int u = 1; u < kSlots; ++u) desc_put(d, u, dg <= kSlots && dg > u ? (unsigned)(ci[s + u] - base) : first);
     (dir ? desc_out : desc_in)[(size_t)tile * kBM + start + rank] = d;
     const int h0 = cnt[par][w0][kSlots];
     if (dg > kSlots) (dir ? heavy_out : heavy_in)[(size_t)tile * kBM + ((wave & 1) ? h0 : 0) + hrank] = v;
@@ -701,7 +699,7 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
   }
 }
 
-// Means of the rows with more than four neighbours, one direction of one tile at a time, from the lists
+// Means of the rows with more than kSlots neighbours, one direction of one tile at a time, from the lists
 // the descriptor kernel leaves: LPR = d / 8 lanes (16 bytes each) serve a row; they fetch eight
 // neighbour ids with one load, hand them round, and keep up to eight neighbour rows in flight; the rows
 // are added in ascending list order in fp32 (first one unpacked exactly), scaled by 1/deg and rounded
@@ -852,7 +850,7 @@ hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_
   return hipGetLastError();
 }
 
-// The layer kernel alone (sorted descriptors built, pre-pass means in a.agg[]): d = 256 or 64, four gather slots.
+// The layer kernel alone (sorted descriptors built, pre-pass means in a.agg[]): d = 256 or 64, kSlots gather slots.
 hipError_t launch_layer256w(const void* h, int d, const GnnArgs& a, const void* Wl, const float* bias, void* out,
                             bool readout, hipStream_t s) {
   if (d == 256) return readout ? launch_w<4, true>(h, a, Wl, bias, out, s) : launch_w<4, false>(h, a, Wl, bias, out, s);
