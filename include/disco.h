@@ -94,6 +94,11 @@ typedef enum { DC_AGG_MEAN = 0, DC_AGG_ATTENTION = 1 } dc_aggregator;
  *                    DC_BF16: contracted features, activations, both means and the
  *                    layer/head matrices are bfloat16 (round to nearest even);
  *                    sums, means, matrix accumulation, bias, ReLU and the head are fp32.
+ *                    The sum over a graph's nodes (Sec. 3.3.1, second equation) and the head's
+ *                    dot products are accumulated in fp64; with DC_BF16, H = 256 and
+ *                    DC_AGG_MEAN the node sum first adds each run of 64 consecutive rows in
+ *                    fp32 in one fixed order (the last layer's kernel forms these partial
+ *                    sums itself and writes no node embeddings), then the runs in fp64.
  *   max_cand         candidates per call
  *   max_base_nodes   bound on sum over candidates of base-graph node counts (= labels per call)
  *   max_base_edges   bound on sum over candidates of base-graph edge counts
