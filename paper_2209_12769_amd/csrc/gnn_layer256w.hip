@@ -88,46 +88,87 @@ __device__ __forceinline__ const char* uniform_ptr(const char* p) {
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
   return reinterpret_cast<const char*>(((unsigned long long)hi << 32) | lo);
 }
-// s_waitcnt vmcnt(n), n even in 0 .. 14 (wave-uniform): at most n newer vector-memory operations may
-// still be outstanding.  Loads and stores leave the counter in issue order.
+// s_waitcnt vmcnt(n), n in 0 .. 15 (wave-uniform; larger values wait as for 15): at most n newer
+// vector-memory operations may still be outstanding.  Loads and stores leave the counter in issue order.
 __device__ __forceinline__ void wait_copies(int n) {
   asm volatile(
       "s_cmp_lt_u32 %0, 8\n\t"
-      "s_cbranch_scc1 .Ldcw_lo_%=\n\t"
-      "s_cmp_eq_u32 %0, 8\n\t"
-      "s_cbranch_scc1 .Ldcw_w8_%=\n\t"
-      "s_cmp_eq_u32 %0, 10\n\t"
-      "s_cbranch_scc1 .Ldcw_w10_%=\n\t"
-      "s_cmp_eq_u32 %0, 12\n\t"
-      "s_cbranch_scc1 .Ldcw_w12_%=\n\t"
+      "s_cbranch_scc1 .Ldcw_r0_7_%=\n\t"
+      "s_cmp_lt_u32 %0, 12\n\t"
+      "s_cbranch_scc1 .Ldcw_r8_11_%=\n\t"
+      "s_cmp_lt_u32 %0, 14\n\t"
+      "s_cbranch_scc1 .Ldcw_r12_13_%=\n\t"
+      "s_cmp_lt_u32 %0, 15\n\t"
+      "s_cbranch_scc1 .Ldcw_r14_14_%=\n\t"
+      "s_waitcnt vmcnt(15)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r14_14_%=:\n\t"
       "s_waitcnt vmcnt(14)\n\t"
       "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_w8_%=:\n\t"
-      "s_waitcnt vmcnt(8)\n\t"
+      ".Ldcw_r12_13_%=:\n\t"
+      "s_cmp_lt_u32 %0, 13\n\t"
+      "s_cbranch_scc1 .Ldcw_r12_12_%=\n\t"
+      "s_waitcnt vmcnt(13)\n\t"
       "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_w10_%=:\n\t"
-      "s_waitcnt vmcnt(10)\n\t"
-      "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_w12_%=:\n\t"
+      ".Ldcw_r12_12_%=:\n\t"
       "s_waitcnt vmcnt(12)\n\t"
       "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_lo_%=:\n\t"
-      "s_cmp_eq_u32 %0, 6\n\t"
-      "s_cbranch_scc1 .Ldcw_w6_%=\n\t"
-      "s_cmp_eq_u32 %0, 4\n\t"
-      "s_cbranch_scc1 .Ldcw_w4_%=\n\t"
-      "s_cmp_eq_u32 %0, 2\n\t"
-      "s_cbranch_scc1 .Ldcw_w2_%=\n\t"
-      "s_waitcnt vmcnt(0)\n\t"
+      ".Ldcw_r8_11_%=:\n\t"
+      "s_cmp_lt_u32 %0, 10\n\t"
+      "s_cbranch_scc1 .Ldcw_r8_9_%=\n\t"
+      "s_cmp_lt_u32 %0, 11\n\t"
+      "s_cbranch_scc1 .Ldcw_r10_10_%=\n\t"
+      "s_waitcnt vmcnt(11)\n\t"
       "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_w2_%=:\n\t"
-      "s_waitcnt vmcnt(2)\n\t"
+      ".Ldcw_r10_10_%=:\n\t"
+      "s_waitcnt vmcnt(10)\n\t"
       "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_w4_%=:\n\t"
+      ".Ldcw_r8_9_%=:\n\t"
+      "s_cmp_lt_u32 %0, 9\n\t"
+      "s_cbranch_scc1 .Ldcw_r8_8_%=\n\t"
+      "s_waitcnt vmcnt(9)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r8_8_%=:\n\t"
+      "s_waitcnt vmcnt(8)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r0_7_%=:\n\t"
+      "s_cmp_lt_u32 %0, 4\n\t"
+      "s_cbranch_scc1 .Ldcw_r0_3_%=\n\t"
+      "s_cmp_lt_u32 %0, 6\n\t"
+      "s_cbranch_scc1 .Ldcw_r4_5_%=\n\t"
+      "s_cmp_lt_u32 %0, 7\n\t"
+      "s_cbranch_scc1 .Ldcw_r6_6_%=\n\t"
+      "s_waitcnt vmcnt(7)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r6_6_%=:\n\t"
+      "s_waitcnt vmcnt(6)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r4_5_%=:\n\t"
+      "s_cmp_lt_u32 %0, 5\n\t"
+      "s_cbranch_scc1 .Ldcw_r4_4_%=\n\t"
+      "s_waitcnt vmcnt(5)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r4_4_%=:\n\t"
       "s_waitcnt vmcnt(4)\n\t"
       "s_branch .Ldcw_end_%=\n"
-      ".Ldcw_w6_%=:\n\t"
-      "s_waitcnt vmcnt(6)\n"
+      ".Ldcw_r0_3_%=:\n\t"
+      "s_cmp_lt_u32 %0, 2\n\t"
+      "s_cbranch_scc1 .Ldcw_r0_1_%=\n\t"
+      "s_cmp_lt_u32 %0, 3\n\t"
+      "s_cbranch_scc1 .Ldcw_r2_2_%=\n\t"
+      "s_waitcnt vmcnt(3)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r2_2_%=:\n\t"
+      "s_waitcnt vmcnt(2)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r0_1_%=:\n\t"
+      "s_cmp_lt_u32 %0, 1\n\t"
+      "s_cbranch_scc1 .Ldcw_r0_0_%=\n\t"
+      "s_waitcnt vmcnt(1)\n\t"
+      "s_branch .Ldcw_end_%=\n"
+      ".Ldcw_r0_0_%=:\n\t"
+      "s_waitcnt vmcnt(0)\n\t"
+      "s_branch .Ldcw_end_%=\n"
       ".Ldcw_end_%=:"
       :
       : "s"(n)
@@ -378,9 +419,9 @@ __device__ __forceinline__ void mul_step(int g, int S, f32x16 (&acc)[2][2], cons
   // were issued after that step's copies: they are counted, not waited for); placed before this
   // tile's stores so that it never waits for those.  The last tile of the batch may issue fewer
   // stores; it is the last tile of its workgroup, and nothing is waited for after it.  The readout
-  // variant issues one store per graph in the wave's rows: counting fewer than were issued (an even
-  // number, eight at most) only waits for some of them.
-  const int stores_behind = (g >= 1 && ((g - 1) % NK) == NK - 1) ? (RO ? min(tile_stores & ~1, 8) : 8) : 0;
+  // variant issues one store per graph in the wave's rows: counting fewer than were issued (eight at
+  // most) only waits for some of them.
+  const int stores_behind = (g >= 1 && ((g - 1) % NK) == NK - 1) ? (RO ? min(tile_stores, 8) : 8) : 0;
   wait_copies(__builtin_amdgcn_readfirstlane(n_req + stores_behind));
   if (g >= 0 && (g % NK) == NK - 1) {
     if constexpr (RO) tile_stores = write_tile_readout<DCH>(g / NK, acc, c);
