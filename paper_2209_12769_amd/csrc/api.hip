@@ -44,6 +44,9 @@ struct dc_ctx {
   void* desc[2] = {nullptr, nullptr};
   int* heavy[2] = {nullptr, nullptr};
   int* heavy_cnt = nullptr;
+  int* heavy_ctr = nullptr;
+  int* heavy_off = nullptr;
+  unsigned* heavy_list = nullptr;
   float* ro_part = nullptr; // chunk sums of the readout when the last layer forms them
   int* ro_first = nullptr;
   int* status = nullptr;    // [2]
@@ -168,6 +171,9 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   int* heavy0 = a.take<int>((size_t)k.NN + 128);
   int* heavy1 = a.take<int>((size_t)k.NN + 128);
   int* heavy_cnt = a.take<int>(2 * ((size_t)k.NN / 128 + 2));
+  int* heavy_ctr = a.take<int>(kHeavyCtrInts);
+  int* heavy_off = a.take<int>(2 * ((size_t)k.NN / 128 + 2) + 1);
+  unsigned* heavy_list = a.take<unsigned>(2 * ((size_t)k.NN + 128));
   // chunk sums of the readout formed by the last layer (bulk bf16 shapes with uniform coefficients only)
   const bool ro = cfg.dtype == DC_BF16 && cfg.H == 256 && cfg.aggregator != DC_AGG_ATTENTION;
   float* ro_part = a.take<float>(ro ? ((size_t)k.NN / 64 + (size_t)k.C + 2) * 256 : 0);
@@ -191,6 +197,9 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
     ctx->heavy[0] = heavy0;
     ctx->heavy[1] = heavy1;
     ctx->heavy_cnt = heavy_cnt;
+    ctx->heavy_ctr = heavy_ctr;
+    ctx->heavy_off = heavy_off;
+    ctx->heavy_list = heavy_list;
     ctx->ro_part = ro ? ro_part : nullptr;
     ctx->ro_first = ro ? ro_first : nullptr;
   }
@@ -294,6 +303,9 @@ GnnArgs gnn_args(dc_ctx* ctx, int32_t n_cand, const BatchView& in, float* pred) 
   g.heavy[0] = ctx->heavy[0];
   g.heavy[1] = ctx->heavy[1];
   g.heavy_cnt = ctx->heavy_cnt;
+  g.heavy_ctr = ctx->heavy_ctr;
+  g.heavy_off = ctx->heavy_off;
+  g.heavy_list = ctx->heavy_list;
   g.ro_part = ctx->ro_part;
   g.ro_first = ctx->ro_first;
   g.pred = pred;

@@ -90,6 +90,9 @@ hipError_t launch_contract(const ContractLaunch& a, Profiler* prof, hipStream_t 
 int contract_working_set_bytes(int n_nodes, int n_edges);
 hipError_t contract_set_lds_limit(int bytes);
 
+// ints of the pre-pass's work counters: one counter per XCD, each on a cache line of its own
+constexpr int kHeavyCtrInts = 8 * 32;
+
 struct GnnArgs {
   int n_cand;
   const int* node_off;
@@ -107,6 +110,9 @@ struct GnnArgs {
   void* desc[2];        // gather descriptors [max_nodes] x 16 bytes per direction
   int* heavy[2] = {nullptr, nullptr};   // per direction and tile of 128 rows: the rows with long lists (128 places per tile)
   int* heavy_cnt = nullptr;             // [2 * tiles] how many of them: entry 2 * tile + direction
+  int* heavy_off = nullptr;             // [2 * tiles + 1] exclusive scan of heavy_cnt
+  unsigned* heavy_list = nullptr;       // the long rows of all tiles as one list: row number, bit 31 = successors' side
+  int* heavy_ctr = nullptr;             // [kHeavyCtrInts] the pre-pass's work counters, one per XCD (cleared by every launch)
   // the last layer forming the readout's sums itself (bulk bf16 shapes): per chunk of 64 rows and graph one row of
   // H partial sums at row chunk + graph, and per chunk the graph its first row belongs to; 0 / nullptr: not used
   int fuse_readout = 0;

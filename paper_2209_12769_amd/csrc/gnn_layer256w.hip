@@ -740,57 +740,188 @@ __global__ __launch_bounds__(256) void build_desc_sorted_kernel(
   }
 }
 
-// Means of the rows with more than kSlots neighbours, one direction of one tile at a time, from the lists
-// the descriptor kernel leaves: LPR = d / 8 lanes (16 bytes each) serve a row; they fetch eight
-// neighbour ids with one load, hand them round, and keep up to eight neighbour rows in flight; the rows
-// are added in ascending list order in fp32 (first one unpacked exactly), scaled by 1/deg and rounded
-// to bf16: the arithmetic of the layer kernel.  Few workgroups with many loads in flight each, dealt
-// to the XCDs in contiguous runs of tiles: the rows being read at any time belong to half a dozen
-// graphs per XCD and stay in its L2 while the graph's other long lists ask for them again.
-template <int LPR>
-__global__ __launch_bounds__(256) void heavy_means_kernel(
-    const u16* __restrict__ h, const int* __restrict__ in_rp, const int* __restrict__ in_ci,
-    const int* __restrict__ out_rp, const int* __restrict__ out_ci, const int* __restrict__ heavy_in,
-    const int* __restrict__ heavy_out, const int* __restrict__ heavy_cnt, u16* __restrict__ h_in,
-    u16* __restrict__ h_out, const int* __restrict__ node_off, int C, const int* __restrict__ status) {
-  constexpr int NSG = 64 / LPR;              // rows a wave serves at a time
+// The per-tile lists of the rows left to the pre-pass, made one list: an exclusive scan of the per-(tile,
+// direction) counts (one workgroup, eight entries per thread and round, the next round's entries loaded
+// before this round's barrier; a few hundred thousand entries at most), ...
+constexpr int kScanPer = 8;
+__global__ __launch_bounds__(1024) void heavy_scan_kernel(const int* __restrict__ heavy_cnt, int* __restrict__ heavy_off,
+                                                          const int* __restrict__ node_off, int C,
+                                                          const int* __restrict__ status) {
+  __shared__ int wsum[2][16];
   if (status[0] != 0) return;
   const int ntot = node_off[C];
-  const int units = 2 * ((ntot + kBM - 1) / kBM);          // (tile, direction)
+  const int n = 2 * ((ntot + kBM - 1) / kBM);
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  auto load = [&](int i, int (&x)[kScanPer]) {   // i is a multiple of 8: whole 16-byte pieces where they lie below n
+#pragma unroll
+    for (int q = 0; q < kScanPer; q += 4) {
+      if (i + q + 3 < n) {
+        const v4i p = *reinterpret_cast<const v4i*>(heavy_cnt + i + q);
+        x[q] = p.x; x[q + 1] = p.y; x[q + 2] = p.z; x[q + 3] = p.w;
+      } else {
+#pragma unroll
+        for (int k = q; k < q + 4; ++k) x[k] = i + k < n ? heavy_cnt[i + k] : 0;
+      }
+    }
+  };
+  int carry = 0, par = 0;                      // the same value in every thread
+  int x[kScanPer], xn[kScanPer];
+  load(kScanPer * t, x);
+  for (int i0 = 0; i0 < n; i0 += 1024 * kScanPer, par ^= 1) {
+    const int i = i0 + kScanPer * t;
+    load(i + 1024 * kScanPer, xn);
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) mine += x[k];
+    int incl = mine;                           // inclusive scan inside the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int y = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += y;
+    }
+    if (lane == 63) wsum[par][wave] = incl;
+    __syncthreads();                           // the next round writes the other half of wsum: one barrier per round
+    int before = carry, total = carry;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      const int ws = wsum[par][w];
+      if (w < wave) before += ws;
+      total += ws;
+    }
+    int run = before + incl - mine;
+#pragma unroll
+    for (int q = 0; q < kScanPer; q += 4) {
+      int o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        o[k] = run;
+        run += x[q + k];
+      }
+      if (i + q + 3 < n) {
+        *reinterpret_cast<v4i*>(heavy_off + i + q) = v4i{o[0], o[1], o[2], o[3]};
+      } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (i + q + k < n) heavy_off[i + q + k] = o[k];
+      }
+    }
+    carry = total;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) x[k] = xn[k];
+  }
+  if (t == 0) heavy_off[n] = carry;
+}
+
+// ... and the lists copied to their places in it: entry = row number, bit 31 set for the successors' direction;
+// a tile's predecessor-side rows first, each side in ascending row order.  A workgroup of 256 takes four
+// tiles at a time (thread = direction and place), so that their dependent loads overlap.
+__global__ __launch_bounds__(256) void heavy_compact_kernel(const int* __restrict__ heavy_in,
+                                                            const int* __restrict__ heavy_out,
+                                                            const int* __restrict__ heavy_cnt,
+                                                            const int* __restrict__ heavy_off,
+                                                            unsigned* __restrict__ heavy_list,
+                                                            const int* __restrict__ node_off, int C,
+                                                            const int* __restrict__ status) {
+  if (status[0] != 0) return;
+  const int ntot = node_off[C];
+  const int ntiles = (ntot + kBM - 1) / kBM;
+  const int dir = threadIdx.x >> 7, r = threadIdx.x & 127;
+  const int* list = dir ? heavy_out : heavy_in;
+  for (int tile0 = blockIdx.x * 4; tile0 < ntiles; tile0 += gridDim.x * 4) {
+    int cnt[4], off[4], v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) cnt[k] = tile0 + k < ntiles ? heavy_cnt[2 * (tile0 + k) + dir] : 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (r < cnt[k]) {
+        off[k] = heavy_off[2 * (tile0 + k) + dir];
+        v[k] = list[(size_t)(tile0 + k) * kBM + r];
+      }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (r < cnt[k]) heavy_list[off[k] + r] = (unsigned)v[k] | ((unsigned)dir << 31);
+  }
+}
+
+__global__ __launch_bounds__(256) void clear_heavy_ctr_kernel(int* __restrict__ ctr) {
+  if (threadIdx.x < kHeavyCtrInts) ctr[threadIdx.x] = 0;
+}
+
+// Means of the rows with more than kSlots neighbours (the pre-pass), from the list the two kernels above
+// leave.  LPR = d / 8 lanes (16 bytes each) serve a row: they fetch eight neighbour ids with one load, hand
+// them round, and keep up to eight neighbour rows in flight; the rows are added in ascending list order
+// in fp32 (first one unpacked exactly), scaled by 1/deg and rounded to bf16: the arithmetic of the layer
+// kernel.
+// The list is cut into eight contiguous runs of tiles, one per XCD, and a run is handed out in order, in
+// batches of kHeavyGroups rows per lane group, through a counter: whatever the rows cost, the rows being
+// worked on at any time are neighbours in the list, i.e. rows of one or two graphs per XCD, whose rows
+// stay in that XCD's L2 while the graph's other long lists ask for them again.  (Dealing the tiles out by
+// a fixed stride lets the workgroups drift apart, and every row then comes from HBM each time it is asked
+// for.)  The batch after the next one is claimed while the current one is summed, and what a row needs
+// before its neighbour rows can be asked for -- its number, its list's start and length, the first eight
+// neighbour ids -- is fetched while the row before it is summed, also across batches.
+constexpr int kHeavyGroups = 2;      // rows per lane group and batch
+constexpr int kHeavyThreads = 256;   // four waves share a batch
+constexpr int kHeavyWgs = 6;         // workgroups per CU: all that fit the kernel's registers
+static_assert(kHeavyThreads % 64 == 0 && kHeavyThreads >= 64 && kHeavyThreads <= 1024, "whole waves");
+template <int LPR>
+__global__ __launch_bounds__(kHeavyThreads) void heavy_means_kernel(
+    const u16* __restrict__ h, const int* __restrict__ in_rp, const int* __restrict__ in_ci,
+    const int* __restrict__ out_rp, const int* __restrict__ out_ci, const unsigned* __restrict__ heavy_list,
+    const int* __restrict__ heavy_off, u16* __restrict__ h_in, u16* __restrict__ h_out, int* __restrict__ ctr,
+    const int* __restrict__ node_off, int C, const int* __restrict__ status) {
+  constexpr int NSG = 64 / LPR;              // rows a wave serves at a time
+  __shared__ int claimed[2];
+  if (status[0] != 0) return;
+  const int ntot = node_off[C];
+  const int ntiles = (ntot + kBM - 1) / kBM;
   const v4u* __restrict__ h4 = reinterpret_cast<const v4u*>(h);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), n_waves = (int)(blockDim.x >> 6);
   const int sg = lane / LPR, ll = lane % LPR, hb = sg * LPR;
-  const int slot = wave * NSG + sg;          // which of the 4 NSG rows the workgroup has in hand
   const unsigned one = bf16_one_reg();
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, per_x = gridDim.x >> 3;
-  const int u_begin = (int)((long long)units * xcd / 8), u_end = (int)((long long)units * (xcd + 1) / 8);
-  // What a row needs before its neighbour rows can be asked for -- its number, its list's start and
-  // length, the first eight neighbour ids -- is fetched while the row before it is summed, so that a
-  // row costs one memory round trip instead of four.
-  int n_next = u_begin + j < u_end ? heavy_cnt[u_begin + j] : 0;
-  for (int u = u_begin + j; u < u_end; u += per_x) {
-    const int tile = u >> 1, dir = u & 1;
-    const int n = n_next;
-    if (u + per_x < u_end) n_next = heavy_cnt[u + per_x];
-    const int* list = (dir ? heavy_out : heavy_in) + (size_t)tile * kBM;
-    const int* rp = dir ? out_rp : in_rp;
-    const int* ci = dir ? out_ci : in_ci;
-    int v = 0, s = 0, deg = 0, mine = 0;
-    if (slot < n) {
-      v = list[slot];
+  const int xcd = blockIdx.x & 7;
+  const int t_begin = (int)((long long)ntiles * xcd / 8), t_end = (int)((long long)ntiles * (xcd + 1) / 8);
+  const int r0 = heavy_off[2 * t_begin], r1 = heavy_off[2 * t_end];
+  const int per_batch = n_waves * NSG * kHeavyGroups;
+  const int n_batches = (r1 - r0 + per_batch - 1) / per_batch;
+  int* my_ctr = ctr + xcd * 32;
+  if (threadIdx.x == 0) {
+    claimed[0] = atomicAdd(my_ctr, 1);
+    claimed[1] = atomicAdd(my_ctr, 1);
+  }
+  __syncthreads();
+  int cur = __builtin_amdgcn_readfirstlane(claimed[0]), nxt = __builtin_amdgcn_readfirstlane(claimed[1]);
+  __syncthreads();
+  int par = 0;
+  // list position of this lane group's row in group g of batch b
+  auto place = [&](int b, int g) { return r0 + b * per_batch + (g * n_waves + wave) * NSG + sg; };
+  int v = 0, s = 0, deg = 0, mine = 0, dir = 0;
+  bool have = false;
+  auto fetch = [&](int r) {
+    have = r < r1;
+    if (have) {
+      const unsigned e = heavy_list[r];
+      dir = (int)(e >> 31);
+      v = (int)(e & 0x7FFFFFFFu);
+      const int* rp = dir ? out_rp : in_rp;
       s = rp[v];
       deg = rp[v + 1] - s;
-      mine = ci[s + (ll < min(8, deg) ? ll : 0)];
+      mine = (dir ? out_ci : in_ci)[s + (ll < min(8, deg) ? ll : 0)];
     }
-    for (int k = slot; k < n; k += 4 * NSG) {
-      const int cv = v, cs = s, cdeg = deg;
+  };
+  if (cur < n_batches) fetch(place(cur, 0));
+  while (cur < n_batches) {
+    int after = 0;
+    if (threadIdx.x == 0) after = atomicAdd(my_ctr, 1);
+    for (int g = 0; g < kHeavyGroups; ++g) {
+      const bool chave = have;
+      const int cv = v, cs = s, cdeg = deg, cdir = dir;
       int cmine = mine;
-      if (k + 4 * NSG < n) {                  // the next row of this lane group
-        v = list[k + 4 * NSG];
-        s = rp[v];
-        deg = rp[v + 1] - s;
-        mine = ci[s + (ll < min(8, deg) ? ll : 0)];
-      }
+      // the next row of this lane group: in this batch, or the first one of the next batch
+      fetch(g + 1 < kHeavyGroups ? place(cur, g + 1) : (nxt < n_batches ? place(nxt, 0) : r1));
+      if (!chave) continue;
+      const int* ci = cdir ? out_ci : in_ci;
       float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int b0 = 0; b0 < cdeg; b0 += 8) {
         const int nb = min(8, cdeg - b0);
@@ -822,8 +953,14 @@ __global__ __launch_bounds__(256) void heavy_means_kernel(
       v4u o;
 #pragma unroll
       for (int w = 0; w < 4; ++w) o[w] = pack_bf16x2(a8[2 * w] * sc, a8[2 * w + 1] * sc);
-      reinterpret_cast<v4u*>(dir ? h_out : h_in)[(size_t)cv * LPR + ll] = o;
+      reinterpret_cast<v4u*>(cdir ? h_out : h_in)[(size_t)cv * LPR + ll] = o;
     }
+    if (threadIdx.x == 0) claimed[par] = after;
+    __syncthreads();
+    const int got = __builtin_amdgcn_readfirstlane(claimed[par]);
+    par ^= 1;
+    cur = nxt;
+    nxt = got;
   }
 }
 
@@ -869,25 +1006,30 @@ hipError_t launch_chunk_first(const GnnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_build_desc_sorted(const GnnArgs& a, hipStream_t s) {
+  if (!a.heavy_off || !a.heavy_list || !a.heavy_ctr) return hipErrorInvalidValue;
   hipLaunchKernelGGL(build_desc_sorted_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.in_rowptr, a.in_col, a.out_rowptr,
                      a.out_col, static_cast<v4i*>(a.desc[0]), static_cast<v4i*>(a.desc[1]), a.heavy[0], a.heavy[1],
                      a.heavy_cnt, a.node_off, a.n_cand, a.status);
+  hipLaunchKernelGGL(heavy_scan_kernel, dim3(1), dim3(1024), 0, s, a.heavy_cnt, a.heavy_off, a.node_off, a.n_cand,
+                     a.status);
+  hipLaunchKernelGGL(heavy_compact_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.heavy[0], a.heavy[1], a.heavy_cnt,
+                     a.heavy_off, a.heavy_list, a.node_off, a.n_cand, a.status);
   return hipGetLastError();
 }
 
 hipError_t launch_heavy_means(const void* h, int d, const GnnArgs& a, hipStream_t s) {
-  const int grid = ((a.n_cu + 7) / 8) * 8 * 12;   // measured: the time falls with the grid up to about here
+  if (d != 256 && d != 64) return hipErrorInvalidValue;
+  const int grid = ((a.n_cu + 7) / 8) * 8 * kHeavyWgs;
   const u16* hh = static_cast<const u16*>(h);
+  hipLaunchKernelGGL(clear_heavy_ctr_kernel, dim3(1), dim3(256), 0, s, a.heavy_ctr);
   if (d == 256)
-    hipLaunchKernelGGL(heavy_means_kernel<32>, dim3(grid), dim3(256), 0, s, hh, a.in_rowptr, a.in_col, a.out_rowptr,
-                       a.out_col, a.heavy[0], a.heavy[1], a.heavy_cnt, static_cast<u16*>(a.agg[0]),
-                       static_cast<u16*>(a.agg[1]), a.node_off, a.n_cand, a.status);
-  else if (d == 64)
-    hipLaunchKernelGGL(heavy_means_kernel<8>, dim3(grid), dim3(256), 0, s, hh, a.in_rowptr, a.in_col, a.out_rowptr,
-                       a.out_col, a.heavy[0], a.heavy[1], a.heavy_cnt, static_cast<u16*>(a.agg[0]),
-                       static_cast<u16*>(a.agg[1]), a.node_off, a.n_cand, a.status);
+    hipLaunchKernelGGL(heavy_means_kernel<32>, dim3(grid), dim3(kHeavyThreads), 0, s, hh, a.in_rowptr, a.in_col,
+                       a.out_rowptr, a.out_col, a.heavy_list, a.heavy_off, static_cast<u16*>(a.agg[0]),
+                       static_cast<u16*>(a.agg[1]), a.heavy_ctr, a.node_off, a.n_cand, a.status);
   else
-    return hipErrorInvalidValue;
+    hipLaunchKernelGGL(heavy_means_kernel<8>, dim3(grid), dim3(kHeavyThreads), 0, s, hh, a.in_rowptr, a.in_col,
+                       a.out_rowptr, a.out_col, a.heavy_list, a.heavy_off, static_cast<u16*>(a.agg[0]),
+                       static_cast<u16*>(a.agg[1]), a.heavy_ctr, a.node_off, a.n_cand, a.status);
   return hipGetLastError();
 }
 
