@@ -497,6 +497,48 @@ def test_bulk_layer_with_every_kind_of_ragged_last_tile(B):
         check_predictions(w, fused, np.arange(C), tag=f"ragged {n_nodes}x{C}")
 
 
+def test_bulk_layer_with_long_neighbour_lists_in_few_and_many_tiles(B):
+    """Rows with more than five neighbours take their means from the pre-pass, which works through one
+    list of such rows cut into eight runs of tiles: batches of 1, 3, 9 and 36 tiles in which a third to
+    all of the rows have long lists (so that runs are empty, hold one tile, or hold several batches of
+    rows), and one batch without any long list, must equal the separate kernels bit for bit and the
+    oracle within tolerance."""
+    model = wl.ModelSpec(64, 256, 3, "bf16")
+    for n_nodes, p, C in ((100, 0.2, 1), (300, 0.03, 1), (230, 0.06, 5), (900, 0.012, 5), (400, 0.001, 2), (500, -1.0, 3)):
+        if p >= 0:
+            g = wl.random_dag(200 + n_nodes, n_nodes, p, 64)
+        else:
+            # a chain with one source feeding every node and one sink fed by every node: lists of n - 1 entries
+            src = np.concatenate([np.arange(n_nodes - 1), np.zeros(n_nodes - 3, np.int64), np.arange(1, n_nodes - 2)])
+            dst = np.concatenate([np.arange(1, n_nodes), np.arange(2, n_nodes - 1), np.full(n_nodes - 3, n_nodes - 1)])
+            keep = np.unique(src * n_nodes + dst)
+            src, dst = keep // n_nodes, keep % n_nodes
+            rowptr = np.zeros(n_nodes + 1, np.int32)
+            np.add.at(rowptr, src + 1, 1)
+            g = wl.BaseGraph(n_nodes, n_nodes, np.cumsum(rowptr).astype(np.int32), dst.astype(np.int32),
+                             wl.random_dag(7, n_nodes, 0.0, 64).X)
+        labs = np.tile(np.arange(g.n, dtype=np.int32), (C, 1))
+        w = wl.with_time_like_head(wl.custom(f"long-{n_nodes}x{C}", model, [g], [labs], seed=6))
+        deg_out = np.diff(g.rowptr)
+        deg_in = np.bincount(g.col, minlength=g.n)
+        n_long = int((deg_out > 5).sum() + (deg_in > 5).sum())
+        print(f"{n_nodes} nodes x {C}: {n_long} long lists per candidate, longest {max(deg_out.max(), deg_in.max())}", flush=True)
+        assert (n_long == 0) == (p == 0.001)
+        ev = B.evaluator_for(w)
+        cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
+        fused = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        again = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.select_kernels(B.DC_KERNELS_SEPARATE_LAYERS)
+        plain = ev.eval_candidates(cg, co, gid).cpu().numpy()
+        assert ev.check() == B.DC_OK
+        ev.close()
+        assert np.array_equal(fused, again), (n_nodes, C)
+        assert np.array_equal(fused, plain), (n_nodes, C, np.abs(fused - plain).max())
+        check_predictions(w, fused, np.arange(C), tag=f"long lists {n_nodes}x{C}")
+
+
 def test_readout_formed_by_the_last_layer_with_many_graphs_per_chunk(B):
     """With the bulk shapes the last layer leaves, per chunk of 64 rows and graph, the column sums the readout
     needs instead of its rows.  Batches of tiny graphs put many graphs into one chunk, graphs of 64 and 128
