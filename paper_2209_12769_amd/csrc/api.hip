@@ -150,6 +150,8 @@ size_t carve(const dc_config& cfg, char* base, dc_ctx* ctx) {
   t.ic = a.take<int>(k.EB + 1);
   t.Gc = a.take<int>(k.C + 1);
   t.Ec = a.take<int>(k.C + 1);
+  t.big_order = a.take<int>(k.C + 1);
+  t.big_meta = a.take<int>(64);
   BatchView b;
   b.node_off = a.take<int>(k.C + 1);
   b.edge_off = a.take<int>(k.C + 1);

@@ -39,6 +39,8 @@ struct ContractTmp {
   int* ic;         // [sum E] local in columns
   int* Gc;         // [C] contracted node count
   int* Ec;         // [C] contracted edge count
+  int* big_order;  // [C] the candidates whose base graph does not fit LDS, largest working sets first
+  int* big_meta;   // [0] how many of them, [1] the counter that hands them out
 };
 
 struct BatchView {

@@ -405,27 +405,44 @@ __global__ __launch_bounds__(kCT) void contract_kernel(BaseGraphs bg, int C, con
                                                         size_t slab_stride, int lds_bytes) {
   __shared__ int wsum[kCW + 1];
   if (status[0] != 0) return;
-  for (int c = blockIdx.x; c < C; c += gridDim.x) {
-    const int b = cand_graph[c];
-    const int N = bg.gno[b + 1] - bg.gno[b];
-    const int E = bg.geo[b + 1] - bg.geo[b];
-    const Slab L = slab_layout(N, E);
-    const bool fits = L.total <= lds_bytes;
-    if (fits != kLds) continue;
-    if (kLds) {
+  if (kLds) {
+    for (int c = blockIdx.x; c < C; c += gridDim.x) {
+      const int b = cand_graph[c];
+      const int N = bg.gno[b + 1] - bg.gno[b];
+      const int E = bg.geo[b + 1] - bg.geo[b];
+      const Slab L = slab_layout(N, E);
+      if (L.total > lds_bytes) continue;
       contract_one<true>(bg, c, b, N, dc_smem, L, cand_off, label, tmp, new_id_out, status, wsum);
-    } else {
+      __syncthreads();
+    }
+  } else {
+    // The candidates that work in global memory are few and long and differ several times in size: they
+    // are handed out one at a time, largest first (the order prep_kernel leaves), through a counter.
+    __shared__ int next_item;
+    const int n_big = tmp.big_meta[0];
+    for (;;) {
+      if (threadIdx.x == 0) next_item = atomicAdd(&tmp.big_meta[1], 1);
+      __syncthreads();
+      const int i = next_item;
+      __syncthreads();                          // everyone has read it before thread 0 writes the next one
+      if (i >= n_big) break;
+      const int c = tmp.big_order[i];
+      const int b = cand_graph[c];
+      const int N = bg.gno[b + 1] - bg.gno[b];
+      const int E = bg.geo[b + 1] - bg.geo[b];
+      const Slab L = slab_layout(N, E);
       contract_one<false>(bg, c, b, N, gslab + (size_t)blockIdx.x * slab_stride, L, cand_off, label, tmp,
                           new_id_out, status, wsum);
+      __syncthreads();
     }
-    __syncthreads();
   }
 }
 
 // Validates the candidate list and scans the base edge counts (one workgroup).
 __global__ __launch_bounds__(1024) void prep_kernel(BaseGraphs bg, int C, const int* cand_graph, const int* cand_off,
                                                      int* tmp_eoff, long long max_base_nodes,
-                                                     long long max_base_edges, int* status) {
+                                                     long long max_base_edges, int* status, int* big_order,
+                                                     int* big_meta, int lds_bytes, int need_max) {
   __shared__ int wsum[16];
   const int t = threadIdx.x, T = blockDim.x;
   int bad = 0;
@@ -462,6 +479,39 @@ __global__ __launch_bounds__(1024) void prep_kernel(BaseGraphs bg, int C, const 
   }
   const int total = block_exscan(tmp_eoff, tmp_eoff, C, wsum);
   if (t == 0) tmp_eoff[C] = total;
+  // The candidates whose base graph does not fit LDS, in sixteen classes of working-set size, largest class
+  // first (the order inside a class is whatever the atomics give: it decides which workgroup contracts a
+  // candidate, not what is written).
+  __shared__ int hist[16], base[16];
+  if (t < 16) hist[t] = 0;
+  __syncthreads();
+  const int span = need_max > lds_bytes ? need_max - lds_bytes : 1;
+  auto size_class = [&](int c) {
+    const int b = cand_graph[c];
+    const int need = slab_layout(bg.gno[b + 1] - bg.gno[b], bg.geo[b + 1] - bg.geo[b]).total;
+    if (need <= lds_bytes) return -1;
+    const long long k = (long long)(need - lds_bytes) * 16 / span;
+    return (int)(k > 15 ? 15 : k);
+  };
+  for (int c = t; c < C; c += T) {
+    const int k = size_class(c);
+    if (k >= 0) atomicAdd(&hist[k], 1);
+  }
+  __syncthreads();
+  if (t == 0) {
+    int run = 0;
+    for (int k = 15; k >= 0; --k) {
+      base[k] = run;
+      run += hist[k];
+    }
+    big_meta[0] = run;
+    big_meta[1] = 0;
+  }
+  __syncthreads();
+  for (int c = t; c < C; c += T) {
+    const int k = size_class(c);
+    if (k >= 0) big_order[atomicAdd(&base[k], 1)] = c;
+  }
 }
 
 // Scans contracted sizes over the batch and checks the output capacities.
@@ -576,11 +626,11 @@ hipError_t launch_contract(const ContractLaunch& a, Profiler* prof, hipStream_t 
   if (a.n_cand <= 0) return hipSuccess;
   const int C = a.n_cand;
   if (prof) prof->begin(kFamPrep, s);
-  hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, s, a.bg, C, a.cand_graph, a.cand_off, a.tmp.tmp_eoff,
-                     a.max_base_nodes, a.max_base_edges, a.status);
-  if (prof) prof->end(s);
   const int need = slab_layout(a.max_graph_nodes, a.max_graph_edges).total;
   const int lds_bytes = need <= a.lds_limit ? need : a.lds_limit;
+  hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, s, a.bg, C, a.cand_graph, a.cand_off, a.tmp.tmp_eoff,
+                     a.max_base_nodes, a.max_base_edges, a.status, a.tmp.big_order, a.tmp.big_meta, lds_bytes, need);
+  if (prof) prof->end(s);
   if (prof) prof->begin(kFamContract, s);
   if (a.min_graph_need <= a.lds_limit) {   // at least one base graph fits in LDS
     hipLaunchKernelGGL(contract_kernel<true>, dim3(C), dim3(kCT), lds_bytes, s, a.bg, C, a.cand_graph, a.cand_off,
