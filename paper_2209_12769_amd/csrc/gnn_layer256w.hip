@@ -862,7 +862,7 @@ __global__ __launch_bounds__(256) void clear_heavy_ctr_kernel(int* __restrict__ 
 // neighbour ids -- is fetched while the row before it is summed, also across batches.
 constexpr int kHeavyGroups = 2;      // rows per lane group and batch
 constexpr int kHeavyThreads = 256;   // four waves share a batch
-constexpr int kHeavyWgs = 6;         // workgroups per CU: all that fit the kernel's registers
+constexpr int kHeavyWgs = 7;         // workgroups per CU: all that fit the kernel's registers
 static_assert(kHeavyThreads % 64 == 0 && kHeavyThreads >= 64 && kHeavyThreads <= 1024, "whole waves");
 template <int LPR>
 __global__ __launch_bounds__(kHeavyThreads) void heavy_means_kernel(
@@ -871,6 +871,7 @@ __global__ __launch_bounds__(kHeavyThreads) void heavy_means_kernel(
     const int* __restrict__ heavy_off, u16* __restrict__ h_in, u16* __restrict__ h_out, int* __restrict__ ctr,
     const int* __restrict__ node_off, int C, const int* __restrict__ status) {
   constexpr int NSG = 64 / LPR;              // rows a wave serves at a time
+  constexpr int kIds = LPR >= 16 ? 16 : 8;   // neighbour ids a lane group fetches with one load
   __shared__ int claimed[2];
   if (status[0] != 0) return;
   const int ntot = node_off[C];
@@ -907,7 +908,7 @@ __global__ __launch_bounds__(kHeavyThreads) void heavy_means_kernel(
       const int* rp = dir ? out_rp : in_rp;
       s = rp[v];
       deg = rp[v + 1] - s;
-      mine = (dir ? out_ci : in_ci)[s + (ll < min(8, deg) ? ll : 0)];
+      mine = (dir ? out_ci : in_ci)[s + (ll < min(kIds, deg) ? ll : 0)];
     }
   };
   if (cur < n_batches) fetch(place(cur, 0));
@@ -923,18 +924,21 @@ __global__ __launch_bounds__(kHeavyThreads) void heavy_means_kernel(
       if (!chave) continue;
       const int* ci = cdir ? out_ci : in_ci;
       float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int b0 = 0; b0 < cdeg; b0 += 8) {
-        const int nb = min(8, cdeg - b0);
+      // kIds neighbour ids per round, held by the first kIds lanes of the group; eight rows in flight: row
+      // q + 8 is asked for as soon as row q has been added (loads return in the order they were issued, so
+      // waiting for row q leaves the seven behind it in flight), and a list of up to kIds entries costs one
+      // memory round trip instead of one per eight
+      for (int b0 = 0; b0 < cdeg; b0 += kIds) {
+        const int nb = min(kIds, cdeg - b0);
         if (b0 > 0) cmine = ci[cs + b0 + (ll < nb ? ll : 0)];
-        int id[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) id[q] = __shfl(cmine, hb + (q < nb ? q : 0), 64);
         v4u x[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-          if (q < nb) x[q] = h4[(size_t)id[q] * LPR + ll];
-#pragma unroll
         for (int q = 0; q < 8; ++q) {
+          const int id = __shfl(cmine, hb + (q < nb ? q : 0), 64);
+          if (q < nb) x[q] = h4[(size_t)id * LPR + ll];
+        }
+#pragma unroll
+        for (int q = 0; q < kIds; ++q) {
           if (q < nb) {
             if (b0 == 0 && q == 0) {         // the first neighbour: exact unpack
 #pragma unroll
@@ -944,8 +948,12 @@ __global__ __launch_bounds__(kHeavyThreads) void heavy_means_kernel(
               }
             } else {
 #pragma unroll
-              for (int w = 0; w < 4; ++w) bf16_pair_add(a8[2 * w], a8[2 * w + 1], x[q][w], one);
+              for (int w = 0; w < 4; ++w) bf16_pair_add(a8[2 * w], a8[2 * w + 1], x[q & 7][w], one);
             }
+          }
+          if (q + 8 < kIds) {
+            const int id = __shfl(cmine, hb + (q + 8 < nb ? q + 8 : 0), 64);
+            if (q + 8 < nb) x[q & 7] = h4[(size_t)id * LPR + ll];
           }
         }
       }
