@@ -214,12 +214,15 @@ def simulate_bench(args, w, B, torch):
 
 
 def cost_bench(args, w, B, torch):
-    """Times dc_cost_candidates: contraction, the estimator on every fused op, per-node times,
-    list scheduling.  Profiled data are synthetic (workloads.profile_of)."""
+    """Times dc_cost_candidates: contraction, the estimator on the fused ops (once per distinct fused op of the
+    batch; --every-fused-op: on each of them), per-node times, list scheduling.  Profiled data are synthetic
+    (workloads.profile_of)."""
     from paper_2209_12769_amd import workloads as wl
     t_base, x_base = wl.profile_of(w)
     w.weights.head[-1] += 1.0                 # random weights: keeps most estimates above the clamp at zero
     ev = B.evaluator_for(w)
+    if args.every_fused_op:
+        ev.select_kernels(B.DC_KERNELS_EVERY_FUSED_OP)
     ev.set_profile(t_base, x_base)
     cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
     cost = torch.empty(w.n_cand, dtype=torch.float32, device=ev.device)
@@ -230,6 +233,7 @@ def cost_bench(args, w, B, torch):
     assert ev.check() == B.DC_OK, B.dc_last_error(ev.ctx)
     ntot, etot = ev.last_totals()
     K, M, E = ev.last_fused_ops()
+    repeats = ev.last_fused_op_repeats()
     ev.profile_begin()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -243,6 +247,8 @@ def cost_bench(args, w, B, torch):
     m = w.model
     s = 2 if m.dtype == "bf16" else 4
     work["fused_op_head"] = {"flops": 2 * 2 * K * m.H * m.H, "bytes": M * m.H * s + 5 * K * m.H * s}
+    # list scheduling: the module's lists in both directions, a time, a size and a completion time per node
+    work["simulate"] = {"bytes": 8 * (ntot + etot) + 12 * ntot}
     kernels = {}
     for name, (ms_total, launches) in fam.items():
         if launches == 0:
@@ -270,19 +276,20 @@ def cost_bench(args, w, B, torch):
         peak = PEAK_MFMA_TFLOPS[m.dtype]
         ach = kernels[dom]["TFLOP/s"]
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": round(ach / peak, 4), "traffic": read_traffic(w.name + "_cost", dom)}
+                "frac": round(ach / peak, 4), "traffic": read_traffic(w.name + ("_cost_every_fused_op" if args.every_fused_op else "_cost"), dom)}
     else:
         ach = kernels[dom].get("GB/s", 0.0)
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": read_traffic(w.name + "_cost", dom)}
+                "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": read_traffic(w.name + ("_cost_every_fused_op" if args.every_fused_op else "_cost"), dom)}
     roof["avg_launch_ms"] = round(kernels[dom]["ms_per_step"] / max(kernels[dom]["launches_per_step"], 1), 4)
-    out = {"metric": "fusion candidates costed/sec (contraction + estimator on every fused op + list scheduling) "
+    out = {"metric": "fusion candidates costed/sec (contraction + estimator on the fused ops + list scheduling) "
                      "on 1 MI355X",
            "value": round(w.n_cand * args.steps / dt, 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": m.dtype, "data": "synthetic",
            "config": {"workload": w.name, "candidates": w.n_cand, "contracted_nodes": ntot, "contracted_edges": etot,
-                      "fused_ops": K, "fused_op_rows": M, "fused_op_edges": E, "F": m.F, "H": m.H, "L": m.L,
+                      "fused_ops": K + repeats, "fused_ops_estimated": K, "fused_ops_repeating_an_estimated_one": repeats,
+                      "fused_op_rows": M, "fused_op_edges": E, "F": m.F, "H": m.H, "L": m.L,
                       "finite": int(torch.isfinite(cost).sum().item())},
            "roofline": roof, "kernels": kernels}
     if not args.no_cpu_baseline:
@@ -457,7 +464,10 @@ def main():
                          "contracted batch; per-node times and tensor sizes are synthetic (from the features)")
     ap.add_argument("--cost", action="store_true",
                     help="instead of one estimate per module, time Cost(H) as the paper composes it "
-                         "(dc_cost_candidates): estimator on every fused op, profiled single ops, simulator")
+                         "(dc_cost_candidates): estimator on the fused ops, profiled single ops, simulator")
+    ap.add_argument("--every-fused-op", action="store_true",
+                    help="with --cost: run the estimator on every fused op, also on those that repeat an earlier one "
+                         "of the batch (default: once per distinct fused op)")
     ap.add_argument("--search", action="store_true",
                     help="time the backtracking search (dc_search) on the workload's base graph; "
                          "--n-cand children per step, --steps search steps")

@@ -264,7 +264,12 @@ dc_status dc_set_profile(dc_ctx* ctx, const float* op_time, const float* ar_size
  *   ops and tensors mixed          op_time = +infinity (no strategy of Sec. 3.2 produces it)
  * op_time, ar_size: dev [out->cap_nodes] fp32; ar_size is negative for computation nodes.
  * On the bf16 path the sums over members and the two hidden layers of the regression network
- * are stored as bfloat16 (they are inputs of MFMA GEMMs).                                   */
+ * are stored as bfloat16 (they are inputs of MFMA GEMMs).
+ * The candidates of a batch mostly share their fused ops (Alg. 1 mutates a few groups of a
+ * parent per child): fused ops of one call with the same base graph and the same members are
+ * the same subgraph, so the estimator runs on the first of each kind and the others take its
+ * estimate (the same bits as if each had been estimated: a row's arithmetic does not depend on
+ * where it stands in the batch).  Nothing is kept from one call to the next.                */
 dc_status dc_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
                           const int32_t* group_id, dc_batch* out, float* op_time, float* ar_size, void* stream);
 
@@ -276,6 +281,11 @@ dc_status dc_cost_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
 /* After a synchronised dc_module_times / dc_cost_candidates: how many fused ops the estimator
  * ran on, their member rows and the edges inside them.  Synchronises `stream`.            */
 dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, int64_t* n_edges, void* stream);
+
+/* After the same calls: how many further fused ops of the batch repeated one of those and took
+ * its estimate (Sec. 3.3: the estimate depends on the fused op's subgraph only).  Synchronises
+ * `stream`.                                                                                 */
+dc_status dc_last_fused_op_repeats(dc_ctx* ctx, int64_t* n_repeats, void* stream);
 
 /* Backtracking search over fusion strategies (Alg. 1, Sec. 4) with dc_cost_candidates as Cost().
  * A strategy is a labelling of the nodes of base graph `graph`; the search starts from the
@@ -402,8 +412,10 @@ dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* 
  * measurements, never needed to obtain a result.  `which` is 0 (the defaults) or
  *   DC_KERNELS_SEPARATE_LAYERS   neighbour means and node update as two kernels per layer with the
  *                                means written to memory, instead of the fused layer kernels
- * Takes effect from the next call on this context; host state only.                            */
-enum { DC_KERNELS_SEPARATE_LAYERS = 1 };
+ *   DC_KERNELS_EVERY_FUSED_OP    dc_module_times / dc_cost_candidates run the estimator on every
+ *                                fused op, also on those that repeat an earlier one of the batch
+ * or both (bitwise or).  Takes effect from the next call on this context; host state only.     */
+enum { DC_KERNELS_SEPARATE_LAYERS = 1, DC_KERNELS_EVERY_FUSED_OP = 2 };
 dc_status dc_select_kernels(dc_ctx* ctx, int32_t which);
 
 /* Human-readable detail of the last error on this context; owned by the context. */

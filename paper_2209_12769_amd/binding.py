@@ -30,6 +30,7 @@ DC_BF16 = 1
 DC_AGG_MEAN = 0
 DC_AGG_ATTENTION = 1
 DC_KERNELS_SEPARATE_LAYERS = 1
+DC_KERNELS_EVERY_FUSED_OP = 2
 DC_DRAW_DEPENDENCY, DC_DRAW_OP = 0, 1
 STATUS_NAMES = {0: "DC_OK", 1: "DC_ERR_INVALID_ARG", 2: "DC_ERR_BAD_GRAPH", 3: "DC_ERR_BAD_PARTITION",
                 4: "DC_ERR_CAPACITY", 5: "DC_ERR_OOM", 6: "DC_ERR_HIP", 7: "DC_ERR_UNSUPPORTED"}
@@ -105,6 +106,7 @@ def lib():
         L.dc_module_times.argtypes = [vp, i32, vp, vp, vp, C.POINTER(DcBatch), vp, vp, vp]
         L.dc_cost_candidates.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp]
         L.dc_last_fused_ops.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp]
+        L.dc_last_fused_op_repeats.argtypes = [vp, C.POINTER(C.c_int64), vp]
         L.dc_search.argtypes = [vp, i32, C.POINTER(DcSearchParams), vp, C.POINTER(DcSearchResult), vp]
         L.dc_num_params.argtypes = [vp]
         L.dc_num_params.restype = C.c_int64
@@ -122,7 +124,8 @@ def lib():
         L.dc_profile_end.argtypes = [vp, C.POINTER(C.c_char_p), fp, C.POINTER(i32), i32]
         for n in ("dc_create", "dc_destroy", "dc_set_weights", "dc_set_attention_weights", "dc_set_base_graphs", "dc_contract_graphs",
                   "dc_gnn_forward", "dc_eval_candidates", "dc_simulate", "dc_check", "dc_last_totals", "dc_profile_begin",
-                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops", "dc_search",
+                  "dc_profile_end", "dc_set_profile", "dc_module_times", "dc_cost_candidates", "dc_last_fused_ops",
+                  "dc_last_fused_op_repeats", "dc_search",
                   "dc_train_begin", "dc_select_kernels", "dc_fused_op_batch", "dc_loss_gradients", "dc_train_step", "dc_get_weights"):
             getattr(L, n).restype = i32
         _lib = L
@@ -196,6 +199,12 @@ def dc_last_fused_ops(ctx, stream: int = 0) -> Tuple[int, int, int, int]:
     k, m, e = C.c_int64(), C.c_int64(), C.c_int64()
     st = lib().dc_last_fused_ops(ctx, C.byref(k), C.byref(m), C.byref(e), stream)
     return st, k.value, m.value, e.value
+
+
+def dc_last_fused_op_repeats(ctx, stream: int = 0) -> Tuple[int, int]:
+    n = C.c_int64()
+    st = lib().dc_last_fused_op_repeats(ctx, C.byref(n), stream)
+    return st, n.value
 
 
 def dc_search(ctx, graph: int, params: DcSearchParams, labels_opt: Optional[np.ndarray], res: DcSearchResult,
@@ -464,6 +473,11 @@ class Evaluator:
         st, k, m, e = dc_last_fused_ops(self.ctx, self._stream())
         self._ok(st, "dc_last_fused_ops")
         return k, m, e
+
+    def last_fused_op_repeats(self) -> int:
+        st, n = dc_last_fused_op_repeats(self.ctx, self._stream())
+        self._ok(st, "dc_last_fused_op_repeats")
+        return n
 
     def check(self) -> int:
         return dc_check(self.ctx, self._stream())

@@ -82,6 +82,7 @@ struct dc_ctx {
   bool have_profile = false;
   std::vector<int> h_gno, h_geo;   // host copies of the base graphs' offsets
   int allow_fused = 1;
+  int every_fused_op = 0;        // 1: the estimator also runs on fused ops that repeat an earlier one of the batch
   // training (dc_train_begin)
   bool training = false;
   dc_train_params tp{};
@@ -365,6 +366,7 @@ dc_status do_module_times(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph
   a.c_node_off = cb.node_off;
   a.op_time = op_time;
   a.ar_size = ar_size;
+  if (ctx->every_fused_op) a.table = nullptr;
   hipError_t e = launch_fused_op_extract(a, prof, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "fused-op extraction launch");
   // the layer kernels only need the total row count: the batch is handed over as one graph
@@ -868,6 +870,8 @@ dc_status dc_set_profile(dc_ctx* ctx, const float* op_time, const float* ar_size
     f.fb.node_off = a.take<int>(cap_ops + 1);
     f.fb.edge_off = a.take<int>(cap_ops + 1);
     f.fo_cnode = a.take<int>(cap_ops + 1);
+    f.table = a.take<int>(fused_op_table_entries(cap_ops));
+    f.dup_of = a.take<int>(k.NB + k.C + 1);
     f.fb.new_id = a.take<int>(k.NB + 1);
     f.fb.out_rowptr = a.take<int>(k.NB + 1);
     f.fb.in_rowptr = a.take<int>(k.NB + 1);
@@ -893,6 +897,7 @@ dc_status dc_set_profile(dc_ctx* ctx, const float* op_time, const float* ar_size
   f.fb.cap_nodes = k.NB;
   f.fb.cap_edges = k.EB;
   f.cap_ops = cap_ops;
+  f.table_mask = (unsigned)(fused_op_table_entries(cap_ops) - 1);
   f.cap_rows = k.NB;
   f.cap_edges = k.EB;
   f.op_time_base = tb;
@@ -992,6 +997,17 @@ dc_status dc_last_fused_ops(dc_ctx* ctx, int64_t* n_fused_ops, int64_t* n_rows, 
   if (n_rows) *n_rows = ctx->h_pinned[8 + 1];
   if (n_fused_ops) *n_fused_ops = ctx->h_pinned[8 + 3];
   if (n_edges) *n_edges = ctx->h_pinned[8 + 4];
+  return DC_OK;
+}
+
+dc_status dc_last_fused_op_repeats(dc_ctx* ctx, int64_t* n_repeats, void* stream) {
+  if (!ctx || !n_repeats) return DC_ERR_INVALID_ARG;
+  if (!ctx->have_profile) return fail(ctx, DC_ERR_INVALID_ARG, "dc_set_profile has not been called");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(ctx->h_pinned + 8, ctx->fo.totals, 8 * sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "dc_last_fused_op_repeats");
+  *n_repeats = ctx->every_fused_op ? 0 : ctx->h_pinned[8 + 5];
   return DC_OK;
 }
 
@@ -1158,6 +1174,7 @@ dc_status dc_fused_op_batch(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gra
   a.c_node_off = ctx->ib.node_off;
   a.op_time = ctx->m_op_time;
   a.ar_size = ctx->m_ar_size;
+  a.table = nullptr;                        // every fused op is a sample of its own
   // the batch goes to the caller's arrays, within the caller's capacities
   a.fb.node_off = out->node_off;
   a.fb.edge_off = out->edge_off;
@@ -1286,8 +1303,9 @@ dc_status dc_last_totals(dc_ctx* ctx, int64_t* n_nodes, int64_t* n_edges, void* 
 }
 
 dc_status dc_select_kernels(dc_ctx* ctx, int32_t which) {
-  if (!ctx || which < 0 || which > 1) return DC_ERR_INVALID_ARG;
+  if (!ctx || which < 0 || which > 3) return DC_ERR_INVALID_ARG;
   ctx->allow_fused = !(which & DC_KERNELS_SEPARATE_LAYERS);
+  ctx->every_fused_op = (which & DC_KERNELS_EVERY_FUSED_OP) != 0;
   return DC_OK;
 }
 

@@ -216,9 +216,14 @@ struct FusedOpsArgs {
   int* dgo;                    // per member position: edges inside groups before it, successors
   int* dgi;                    // the same, predecessors
   int* cnt;                    // [3][C+1] fused ops / rows / edges per candidate, scanned in place
-  int* totals;                 // {0, rows} {0, fused ops} edges
+  int* totals;                 // {0, rows} {0, fused ops} edges, [5] fused ops that repeat an earlier one
   BatchView fb;                // one graph per fused op; new_id holds the base node of each row
   int* fo_cnode;               // contracted node (global) of each fused op
+  // Fused ops with the same members in the same base graph have the same subgraph and hence the same
+  // estimate: with a table (not null) the estimator runs on the first of each kind only
+  int* table;                  // [table_mask + 1] open addressing, entry = contracted node (global) of that first one, -1 = free
+  unsigned table_mask;
+  int* dup_of;                 // slot cand_off[c] + c, per group: the contracted node (global) it repeats, or -1
   long long cap_ops, cap_rows, cap_edges;
   float* op_time;              // [contracted nodes] out
   float* ar_size;              // [contracted nodes] out
@@ -230,6 +235,7 @@ hipError_t launch_fused_op_extract(const FusedOpsArgs& a, Profiler* prof, hipStr
 hipError_t launch_fused_op_readout(const FusedOpsArgs& a, const void* h_last, void* R, hipStream_t s);
 hipError_t launch_fused_op_times(const FusedOpsArgs& a, const void* Z2, const float* w3b3, float* fo_pred,
                                  hipStream_t s);
+size_t fused_op_table_entries(long long max_fused_ops);
 
 // search.hip: the backtracking search driver; it sees one base graph and calls the public cost entry point
 struct SearchView {

@@ -10,7 +10,11 @@
 //
 //   fo_count_kernel   per candidate: classifies every contracted node (bucket of tensors /
 //                     single op / fused op / mixture), writes the times that need no
-//                     estimator, counts fused ops, their rows and their internal edges
+//                     estimator, counts fused ops, their rows and their internal edges.
+//                     Candidates of one batch mostly share their fused ops (a search step mutates
+//                     a few groups of a parent): a fused op whose base graph and member list equal
+//                     those of one met before (a hash table over the batch, members compared in
+//                     full) gets no rows of its own and takes that one's estimate afterwards
 //   fo_scan_kernel    offsets of every candidate's share of the fused-op batch
 //   fo_fill_kernel    writes the batch: one graph per fused op, rows = members in ascending
 //                     base index with their own features, edges = base edges inside the group
@@ -19,6 +23,7 @@
 //   (two dense layers with bias and ReLU on those sums run in the layer kernels' GEMM)
 //   fo_time_kernel    last layer of the regression network (Sec. 3.3.2), clamped at zero,
 //                     scattered to the fused op's node of the module
+//   fo_repeat_kernel  the time of every fused op that repeats an earlier one
 //
 // Per contracted node: all members tensors: size = sum of the members' sizes (Sec. 2.3), fp64
 // in ascending member order, rounded once; one op: its profiled time; two or more ops: the
@@ -34,6 +39,49 @@ namespace {
 
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
+constexpr int kMaxProbes = 4096;   // a fused op that finds no place within so many steps simply keeps its own rows
+
+__device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void fo_clear_table_kernel(int* __restrict__ table, unsigned mask, int* totals) {
+  const size_t n = (size_t)mask + 1;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) table[i] = -1;
+  if (blockIdx.x == 0 && threadIdx.x == 0) totals[5] = 0;
+}
+
+// The fused op (candidate c, group g: base graph b, members mem[s .. s + n)) against the table: returns the
+// contracted node (global) of an equal fused op entered before, or -1 after entering this one (`me`).
+__device__ __forceinline__ int find_or_enter(const FusedOpsArgs& a, int b, const int* mem, int s, int n, int me) {
+  unsigned long long h = mix64(0x9E3779B97F4A7C15ull + (unsigned)b);
+  for (int i = 0; i < n; ++i) h = mix64(h ^ (unsigned)mem[s + i]);
+  unsigned slot = (unsigned)h & a.table_mask;
+  for (int probe = 0; probe < kMaxProbes; ++probe) {
+    const int old = atomicCAS(&a.table[slot], -1, me);
+    if (old == -1) return -1;
+    int lo = 0, hi = a.n_cand;                 // the candidate of node `old`: the last one that starts at or before it
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.c_node_off[mid] <= old) lo = mid; else hi = mid;
+    }
+    if (a.cand_graph[lo] == b) {
+      const int coff2 = a.cand_off[lo];
+      const int* ms2 = a.mstart + coff2 + lo;
+      const int* mem2 = a.members + coff2;
+      const int g2 = old - a.c_node_off[lo];
+      const int s2 = ms2[g2];
+      bool same = ms2[g2 + 1] - s2 == n;
+      for (int i = 0; same && i < n; ++i) same = mem2[s2 + i] == mem[s + i];
+      if (same) return old;
+    }
+    slot = (slot + 1) & a.table_mask;
+  }
+  return -1;
+}
+
 __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
   __shared__ int wsum[8];
   if (a.status[0] != 0) return;
@@ -48,6 +96,7 @@ __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
   const float* xb = a.ar_size_base + gb;
   int* gfm = a.gfm + nslot;
   int* gfk = a.gfk + nslot;
+  int n_repeats = 0;
   for (int g = t; g < G; g += T) {
     const int s = ms[g], e = ms[g + 1], n = e - s;
     int n_ar = 0;
@@ -59,13 +108,21 @@ __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
         size += (double)x;
       }
     }
-    const bool fused = n_ar == 0 && n >= 2;
+    bool fused = n_ar == 0 && n >= 2;
+    if (a.table) {
+      const int first = fused ? find_or_enter(a, b, mem, s, n, n0 + g) : -1;
+      a.dup_of[nslot + g] = first;
+      if (first >= 0) {
+        fused = false;                         // no rows of its own
+        ++n_repeats;
+      }
+    }
     float ot, as;
     if (n_ar == n) {
       ot = 0.0f;
       as = (float)size;
     } else if (n_ar == 0) {
-      ot = n == 1 ? tb[mem[s]] : 0.0f;      // a fused op's time is written by fo_time_kernel
+      ot = n == 1 ? tb[mem[s]] : 0.0f;      // a fused op's time is written by fo_time_kernel / fo_repeat_kernel
       as = -1.0f;
     } else {
       ot = INFINITY;
@@ -75,6 +132,10 @@ __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
     a.ar_size[n0 + g] = as;
     gfm[g] = fused ? n : 0;
     gfk[g] = fused ? 1 : 0;
+  }
+  if (a.table) {
+    for (int o = 32; o > 0; o >>= 1) n_repeats += __shfl_down(n_repeats, o, 64);
+    if ((t & 63) == 0 && n_repeats > 0) atomicAdd(&a.totals[5], n_repeats);
   }
   __syncthreads();
   const int Mc = block_exscan(gfm, gfm, G, wsum);
@@ -329,11 +390,31 @@ __global__ __launch_bounds__(256) void fo_time_kernel(const void* __restrict__ Z
   }
 }
 
+// The time of a fused op that repeats an earlier one of the batch: that one's.
+__global__ __launch_bounds__(256) void fo_repeat_kernel(FusedOpsArgs a) {
+  if (a.status[0] != 0) return;
+  const int c = blockIdx.x;
+  const int nslot = a.cand_off[c] + c, G = a.Gc[c], n0 = a.c_node_off[c];
+  for (int g = threadIdx.x; g < G; g += blockDim.x) {
+    const int first = a.dup_of[nslot + g];
+    if (first >= 0) a.op_time[n0 + g] = a.op_time[first];
+  }
+}
+
 }  // namespace
+
+// Places of the table for up to `max_fused_ops` entries: a power of two, at most half full.
+size_t fused_op_table_entries(long long max_fused_ops) {
+  size_t n = 1024;
+  while (n < 2 * (size_t)(max_fused_ops > 0 ? max_fused_ops : 1)) n <<= 1;
+  return n;
+}
 
 hipError_t launch_fused_op_extract(const FusedOpsArgs& a, Profiler* prof, hipStream_t s) {
   if (a.n_cand <= 0) return hipSuccess;
   if (prof) prof->begin(kFamFusedOps, s);
+  if (a.table)
+    hipLaunchKernelGGL(fo_clear_table_kernel, dim3(a.n_cu * 8), dim3(256), 0, s, a.table, a.table_mask, a.totals);
   hipLaunchKernelGGL(fo_count_kernel, dim3(a.n_cand), dim3(256), 0, s, a);
   hipLaunchKernelGGL(fo_scan_kernel, dim3(1), dim3(1024), 0, s, a);
   if (a.bf16) hipLaunchKernelGGL(fo_fill_kernel<true>, dim3(a.n_cand), dim3(256), 0, s, a);
@@ -360,6 +441,7 @@ hipError_t launch_fused_op_times(const FusedOpsArgs& a, const void* Z2, const fl
   else
     hipLaunchKernelGGL(fo_time_kernel<false>, grid, block, 0, s, Z2, a.H, w3b3, a.fo_cnode, a.totals, a.op_time,
                        fo_pred, a.status);
+  if (a.table && a.n_cand > 0) hipLaunchKernelGGL(fo_repeat_kernel, dim3(a.n_cand), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

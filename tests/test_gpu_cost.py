@@ -48,8 +48,11 @@ def sizes(w):
     return nb, eb
 
 
-def gpu_module_times(B, w, t, x):
+def gpu_module_times(B, w, t, x, which=0):
+    """-> op_time, ar_size, node_off, (fused ops the estimator ran on, their rows, their edges), fused ops that
+    repeated one of those, status"""
     ev = B.evaluator_for(w)
+    ev.select_kernels(which)
     ev.set_profile(t, x)
     cg, co, gid = ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id)
     nb, eb = sizes(w)
@@ -58,9 +61,26 @@ def gpu_module_times(B, w, t, x):
     st = ev.check()
     ntot, _ = ev.last_totals()
     counts = ev.last_fused_ops()
-    out = (op_time[:ntot].cpu().numpy(), ar_size[:ntot].cpu().numpy(), batch.node_off.cpu().numpy(), counts, st)
+    repeats = ev.last_fused_op_repeats()
+    out = (op_time[:ntot].cpu().numpy(), ar_size[:ntot].cpu().numpy(), batch.node_off.cpu().numpy(), counts, repeats, st)
     ev.close()
     return out
+
+
+def distinct_fused_ops(w, ref_b, fo, cnode):
+    """Fused ops of the batch up to repetition (same base graph, same members): how many there are, their rows,
+    their edges, and how many fused ops repeat an earlier one."""
+    cand = np.searchsorted(ref_b.node_off, cnode, side="right") - 1
+    seen = set()
+    K = M = E = 0
+    for k in range(fo.n_cand):
+        key = (int(w.cand_graph[cand[k]]), fo.new_id[fo.node_off[k]:fo.node_off[k + 1]].tobytes())
+        if key not in seen:
+            seen.add(key)
+            K += 1
+            M += int(fo.node_off[k + 1] - fo.node_off[k])
+            E += int(fo.edge_off[k + 1] - fo.edge_off[k])
+    return (K, M, E), fo.n_cand - K
 
 
 def gpu_cost(B, w, t, x, c, d):
@@ -100,11 +120,12 @@ def test_module_times_of_the_configurations(B, name, n):
     w = positive(wl.make(name, n, n_graphs=12) if name == "cfg5" else wl.make(name, n))
     t, x = wl.profile_of(w)
     ref_b = orc.contract(w)
-    got_t, got_x, node_off, counts, st = gpu_module_times(B, w, t, x)
+    got_t, got_x, node_off, counts, repeats, st = gpu_module_times(B, w, t, x)
     assert st == B.DC_OK
     assert np.array_equal(node_off, ref_b.node_off)
     err, fo, fo_pred = check_times(w, got_t, got_x, ref_b, t, x)
-    assert counts == (fo.n_cand, fo.ntot, fo.etot)
+    cnode = orc.module_times(w, ref_b, t, x, want_fused=True)[3]
+    assert (counts, repeats) == distinct_fused_ops(w, ref_b, fo, cnode)
     assert np.mean(fo_pred > 0) > 0.5
     print(f"[module_times] {name} C={n}: {fo.n_cand} fused ops, {fo.ntot} rows, {fo.etot} edges, "
           f"max rel err {err:.2e}", flush=True)
@@ -125,6 +146,47 @@ def test_cost_of_the_configurations(B, name, n):
             mir = orc.cost(w, t, x, c, d, bf16=True)
             assert np.max(np.abs(got - mir) / np.abs(mir)) <= MIRROR_TOL
     print(f"[cost] {name} C={n}: cost {want.min():.3f} .. {want.max():.3f}, max rel err {err.max():.2e}", flush=True)
+
+
+def test_a_repeated_fused_op_takes_the_first_ones_estimate_bit_for_bit(B):
+    """Fused ops of one batch with the same base graph and the same members are estimated once: the times of
+    every node equal, bit for bit, those of a pass that runs the estimator on every fused op; the counts are
+    those of the oracle's batch up to repetition.  Cases: candidates that share most groups (cfg4, cfg3),
+    the same candidate three times over, and two base graphs with the same edges but other features under the
+    same labels (equal member lists that must not be taken for each other)."""
+    cases = [positive(wl.make("cfg4", 24)), positive(wl.make("cfg3", 40))]
+    w3 = wl.make("cfg3", 2)
+    n = w3.graphs[0].n
+    lab = w3.group_id.reshape(2, n)
+    cases.append(positive(wl.custom("thrice", w3.model, w3.graphs, [np.concatenate([lab[:1]] * 3 + [lab[1:]])])))
+    g0 = w3.graphs[0]
+    g1 = wl.BaseGraph(g0.n, g0.n_op, g0.rowptr, g0.col, (g0.X[::-1] * 0.5 + 0.25).astype(np.float32).copy())
+    cases.append(positive(wl.custom("twins", w3.model, [g0, g1], [lab, lab])))
+    for w in cases:
+        t, x = wl.profile_of(w)
+        ref_b = orc.contract(w)
+        once = gpu_module_times(B, w, t, x)
+        every = gpu_module_times(B, w, t, x, B.DC_KERNELS_EVERY_FUSED_OP)
+        assert once[5] == B.DC_OK and every[5] == B.DC_OK
+        assert np.array_equal(once[0], every[0]) and np.array_equal(once[1], every[1]), w.name
+        _, _, fo, cnode, _ = orc.module_times(w, ref_b, t, x, want_fused=True)
+        assert every[3] == (fo.n_cand, fo.ntot, fo.etot) and every[4] == 0
+        want = distinct_fused_ops(w, ref_b, fo, cnode)
+        assert (once[3], once[4]) == want, (w.name, once[3], once[4], want)
+        print(f"[repeats] {w.name}: {fo.n_cand} fused ops, {want[0][0]} up to repetition", flush=True)
+        if w.name == "thrice":
+            assert want[1] >= 2 * (fo.n_cand // 4)
+        if w.name == "twins":
+            assert want[0][0] >= 2 * len({fo.new_id[fo.node_off[k]:fo.node_off[k + 1]].tobytes() for k in range(fo.n_cand)}) - 0
+        c_once, st1 = gpu_cost(B, w, t, x, 0.02, 0.01)
+        ev = B.evaluator_for(w)
+        ev.select_kernels(B.DC_KERNELS_EVERY_FUSED_OP)
+        ev.set_profile(t, x)
+        c_every = ev.cost_candidates(ev.to_device(w.cand_graph), ev.to_device(w.cand_off), ev.to_device(w.group_id),
+                                     0.02, 0.01).cpu().numpy()
+        assert ev.check() == B.DC_OK and st1 == B.DC_OK
+        ev.close()
+        assert np.array_equal(c_once, c_every, equal_nan=True), w.name
 
 
 def test_cost_is_the_simulator_on_the_module_times(B):
@@ -203,7 +265,7 @@ def test_attention_estimator(B):
     w = positive(wl.with_attention(wl.make("cfg3", 16), 4))
     t, x = wl.profile_of(w)
     ref_b = orc.contract(w)
-    got_t, got_x, _, _, st = gpu_module_times(B, w, t, x)
+    got_t, got_x, _, _, _, st = gpu_module_times(B, w, t, x)
     assert st == B.DC_OK
     err, fo, _ = check_times(w, got_t, got_x, ref_b, t, x)
     want = orc.cost(w, t, x, 0.02, 0.01)
@@ -244,7 +306,7 @@ def test_edge_cases(B, dtype):
     w = edge_case_workload(dtype)
     t, x = wl.profile_of(w)
     ref_b = orc.contract(w)
-    got_t, got_x, _, counts, st = gpu_module_times(B, w, t, x)
+    got_t, got_x, _, counts, _, st = gpu_module_times(B, w, t, x)
     assert st == B.DC_OK
     # the sum over 300 member rows is rounded to bf16 before the regression network, a rounding point the
     # oracle's bf16 mode does not have: the bound against the plain oracle holds, the tighter one is not asked
@@ -265,8 +327,8 @@ def test_no_fused_op_at_all(B):
     n = w.graphs[0].n
     w = wl.custom("id", w.model, w.graphs, [np.tile(np.arange(n, dtype=np.int32), (3, 1))])
     t, x = wl.profile_of(w)
-    got_t, got_x, _, counts, st = gpu_module_times(B, w, t, x)
-    assert st == B.DC_OK and counts == (0, 0, 0)
+    got_t, got_x, _, counts, repeats, st = gpu_module_times(B, w, t, x)
+    assert st == B.DC_OK and counts == (0, 0, 0) and repeats == 0
     assert np.array_equal(got_t, np.tile(t, 3)) and np.array_equal(got_x, np.tile(x, 3))
     got, st = gpu_cost(B, w, t, x, 0.02, 0.01)
     assert st == B.DC_OK and np.array_equal(got, orc.cost(w, t, x, 0.02, 0.01))
