@@ -27,12 +27,31 @@
 namespace dc {
 namespace {
 
-constexpr int kAr = 1 << 30;    // flag in the dependency counter: the node is an all-reduce
-
+// The arrays of a module in global memory ...
 __host__ __device__ inline size_t sim_bytes(long long G, long long E) {
   // ready[G] f64 | val[G] f32 | dep[G] i32 | queue[G] i32 | rp[G+1] i32 | ci[E] u16 (padded to 8 bytes)
   return (size_t)G * (8 + 4 + 4 + 4) + (size_t)(G + 1) * 4 + (((size_t)E * 2 + 7) & ~(size_t)7) + 8;
 }
+// ... and in LDS, where a byte saved is a module more per CU: dependency counters and queue entries of 16 bits
+// (a module has fewer than 65536 nodes; the counter keeps bit 15 for the all-reduce flag, so it takes modules
+// of up to 32768 nodes, more than LDS holds anyway).
+__host__ __device__ inline size_t sim_lds_bytes(long long G, long long E) {
+  // ready[G] f64 | val[G] f32 | rp[G+1] i32 | dep[G] u16 | queue[G] u16 | ci[E] u16 (padded to 8 bytes)
+  if (G > 32768) return ~(size_t)0;
+  return (size_t)G * (8 + 4) + (size_t)(G + 1) * 4 + (((size_t)G * 4 + (size_t)E * 2 + 7) & ~(size_t)7) + 8;
+}
+template <bool kLds>
+struct SimTypes {                 // global memory
+  typedef int dep_t;
+  typedef int q_t;
+  static constexpr int kAr = 1 << 30;      // flag in the dependency counter: the node is an all-reduce
+};
+template <>
+struct SimTypes<true> {           // LDS
+  typedef unsigned short dep_t;
+  typedef unsigned short q_t;
+  static constexpr int kAr = 1 << 15;
+};
 
 extern __shared__ __attribute__((aligned(16))) char dc_sim_smem[];
 
@@ -55,12 +74,15 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
                                                        size_t gstride, int lds_lo, int lds_hi, int* status) {
   // kLds: this launch walks the modules whose arrays need more than lds_lo and at most lds_hi
   // bytes (its LDS allocation); !kLds: those that need more than lds_hi, in global memory
+  typedef typename SimTypes<kLds>::dep_t dep_t;
+  typedef typename SimTypes<kLds>::q_t q_t;
+  constexpr int kAr = SimTypes<kLds>::kAr;
   if (status[0] != 0) return;
   const int lane = threadIdx.x;
   for (int c = blockIdx.x; c < C; c += gridDim.x) {
     const int n0 = node_off[c], G = node_off[c + 1] - n0;
     const int e0 = out_rp[n0], E = out_rp[n0 + G] - e0;
-    const size_t need = sim_bytes(G, E);
+    const size_t need = sim_lds_bytes(G, E);
     if (kLds ? (need <= (size_t)lds_lo || need > (size_t)lds_hi) : need <= (size_t)lds_hi) continue;
     if (!kLds && sim_bytes(G, E) > gstride) {       // larger than any base graph of this context
       if (lane == 0) {
@@ -72,10 +94,21 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
     char* base = kLds ? dc_sim_smem : gscratch + (size_t)blockIdx.x * gstride;
     double* ready = reinterpret_cast<double*>(base);
     float* val = reinterpret_cast<float*>(ready + G);      // execution time, or tensor size of an all-reduce
-    int* dep = reinterpret_cast<int*>(val + G);
-    int* qu = dep + G;       // every node is queued once: ops fill it from the front, all-reduces from the back
-    int* rp = qu + G;
-    unsigned short* ci = reinterpret_cast<unsigned short*>(rp + G + 1);
+    dep_t* dep;
+    q_t* qu;                 // every node is queued once: ops fill it from the front, all-reduces from the back
+    int* rp;
+    unsigned short* ci;
+    if (kLds) {
+      rp = reinterpret_cast<int*>(val + G);
+      dep = reinterpret_cast<dep_t*>(rp + G + 1);
+      qu = reinterpret_cast<q_t*>(dep + G);
+      ci = reinterpret_cast<unsigned short*>(qu + G);
+    } else {
+      dep = reinterpret_cast<dep_t*>(val + G);
+      qu = reinterpret_cast<q_t*>(dep + G);
+      rp = reinterpret_cast<int*>(qu + G);
+      ci = reinterpret_cast<unsigned short*>(rp + G + 1);
+    }
     const double dc = (double)ar_c, dd = (double)ar_d;
 
     // ---- load the module
@@ -84,7 +117,7 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
       const bool ar = x >= 0.0f;
       ready[v] = 0.0;
       val[v] = ar ? x : op_time[n0 + v];
-      dep[v] = (in_rp[n0 + v + 1] - in_rp[n0 + v]) | (ar ? kAr : 0);
+      dep[v] = (dep_t)((in_rp[n0 + v + 1] - in_rp[n0 + v]) | (ar ? kAr : 0));
       rp[v] = out_rp[n0 + v] - e0;
     }
     if (lane == 0) rp[G] = E;
@@ -99,8 +132,8 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
       const bool src_op = d == 0, src_ar = d == kAr;
       const unsigned long long mo = __ballot(src_op), ma = __ballot(src_ar);
       const unsigned long long below = (1ull << lane) - 1ull;
-      if (src_op) qu[qt + __popcll(mo & below)] = v;
-      if (src_ar) qu[G - 1 - (at + __popcll(ma & below))] = v;
+      if (src_op) qu[qt + __popcll(mo & below)] = (q_t)v;
+      if (src_ar) qu[G - 1 - (at + __popcll(ma & below))] = (q_t)v;
       qt += __popcll(mo);
       at += __popcll(ma);
     }
@@ -132,15 +165,15 @@ __global__ __launch_bounds__(64) void simulate_kernel(const int* __restrict__ no
         if (k < e) {
           w = ci[k];
           if (done > ready[w]) ready[w] = done;
-          const int d = dep[w] - 1;
-          dep[w] = d;
+          const int d = (int)dep[w] - 1;
+          dep[w] = (dep_t)d;
           new_op = d == 0;
           new_ar = d == kAr;
         }
         const unsigned long long mo = __ballot(new_op), ma = __ballot(new_ar);
         const unsigned long long below = (1ull << lane) - 1ull;
-        if (new_op) qu[qt + __popcll(mo & below)] = w;
-        if (new_ar) qu[G - 1 - (at + __popcll(ma & below))] = w;
+        if (new_op) qu[qt + __popcll(mo & below)] = (q_t)w;
+        if (new_ar) qu[G - 1 - (at + __popcll(ma & below))] = (q_t)w;
         qt += __popcll(mo);
         at += __popcll(ma);
       }
@@ -159,10 +192,12 @@ size_t simulate_scratch_bytes(long long max_graph_nodes, long long max_graph_edg
 
 hipError_t launch_simulate(const SimArgs& a, hipStream_t s) {
   if (a.n_cand <= 0) return hipSuccess;
-  // Modules are walked on chip in four launches by size class, each with just the LDS its class
-  // needs (10, 5, 3 or 2 waves per CU); a workgroup whose candidate belongs to another class
-  // returns at once.  The rest walk in slices of global memory (a persistent grid).
-  const int classes[5] = {0, 16 * 1024, 32 * 1024, 53 * 1024, a.lds_bytes};
+  // Modules are walked on chip in five launches by size class, each with just the LDS its class
+  // needs (10, 6, 4, 3 or 2 waves per CU of 160 KB); a workgroup whose candidate belongs to another
+  // class returns at once.  The rest walk in slices of global memory (a persistent grid).
+  constexpr int kClasses = 5;
+  int classes[kClasses + 1] = {0, 16 * 1024, 26 * 1024 + 512, 40 * 1024, 53 * 1024, a.lds_bytes};
+  for (int k = 1; k < kClasses; ++k) classes[k] = classes[k] < a.lds_bytes ? classes[k] : a.lds_bytes;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&simulate_kernel<true>),
@@ -170,7 +205,8 @@ hipError_t launch_simulate(const SimArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  for (int k = 0; k < 4; ++k)
+  for (int k = 0; k < kClasses; ++k)
+    if (classes[k + 1] > classes[k])
     hipLaunchKernelGGL(simulate_kernel<true>, dim3(a.n_cand), dim3(64), classes[k + 1], s, a.node_off, a.out_rowptr,
                        a.out_col, a.in_rowptr, a.op_time, a.ar_size, a.n_cand, a.ar_c, a.ar_d, a.cost, nullptr,
                        (size_t)0, classes[k], classes[k + 1], a.status);
