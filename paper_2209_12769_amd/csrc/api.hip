@@ -243,8 +243,10 @@ dc_status hip_fail(dc_ctx* ctx, hipError_t e, const char* what) {
   return e == hipErrorOutOfMemory ? DC_ERR_OOM : DC_ERR_HIP;
 }
 
+// features = false: the contracted graphs without the feature sums (Cost(H) takes its per-node inputs from the
+// profile and the estimator's batch, not from the features of the module's nodes)
 dc_status do_contract(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, const int32_t* cand_off,
-                      const int32_t* group_id, const BatchView& out, hipStream_t s) {
+                      const int32_t* group_id, const BatchView& out, hipStream_t s, bool features = true) {
   ContractLaunch a;
   a.bg = ctx->bg;
   a.max_graph_nodes = ctx->max_gn;
@@ -256,7 +258,7 @@ dc_status do_contract(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_graph, co
   a.group_id = group_id;
   a.tmp = ctx->tmp;
   a.out = out;
-  a.F = ctx->cfg.F;
+  a.F = features ? ctx->cfg.F : 0;
   a.bf16 = ctx->cfg.dtype == DC_BF16;
   a.max_base_nodes = ctx->cfg.max_base_nodes;
   a.max_base_edges = ctx->cfg.max_base_edges;
@@ -952,7 +954,7 @@ dc_status dc_cost_candidates(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gr
   if (!cand_graph || !cand_off || !group_id || !cost) return fail(ctx, DC_ERR_INVALID_ARG, "null array");
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
-  st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s);
+  st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s, false);
   if (st != DC_OK) return st;
   st = do_module_times(ctx, n_cand, cand_graph, cand_off, ctx->ib, ctx->m_op_time, ctx->m_ar_size, s);
   if (st != DC_OK) return st;
@@ -1159,7 +1161,7 @@ dc_status dc_fused_op_batch(dc_ctx* ctx, int32_t n_cand, const int32_t* cand_gra
   if (!cand_graph || !cand_off || !group_id) return fail(ctx, DC_ERR_INVALID_ARG, "null candidate array");
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(1), 0, s, ctx->status);
-  st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s);
+  st = do_contract(ctx, n_cand, cand_graph, cand_off, group_id, ctx->ib, s, false);
   if (st != DC_OK) return st;
   Profiler* prof = ctx->prof.on ? &ctx->prof : nullptr;
   FusedOpsArgs a = ctx->fo;

@@ -47,6 +47,55 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
   return z ^ (z >> 31);
 }
 
+// Exclusive scans of a[0..n) and b[0..n) in place by a workgroup of 256 threads, in rounds of 1024 entries: a
+// thread takes four neighbouring entries of each array, so a wave reads and writes whole cache lines (the
+// arrays live in global memory; a contiguous run per thread would touch a line per entry).  One barrier per
+// round (the wave sums alternate between two halves of ws), one at the end.  Returns the totals.
+__device__ __forceinline__ void block_exscan_pair(int* a, int* b, int n, int (&ws)[2][2][4], int& total_a, int& total_b) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int carry_a = 0, carry_b = 0, par = 0;
+  for (int i0 = 0; i0 < n; i0 += 1024, par ^= 1) {
+    const int i = i0 + 4 * t;
+    int xa[4], xb[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      xa[k] = i + k < n ? a[i + k] : 0;
+      xb[k] = i + k < n ? b[i + k] : 0;
+    }
+    const int sa = xa[0] + xa[1] + xa[2] + xa[3], sb = xb[0] + xb[1] + xb[2] + xb[3];
+    const int ia = wave_incl_scan(sa), ib = wave_incl_scan(sb);
+    if (lane == 63) {
+      ws[par][0][wave] = ia;
+      ws[par][1][wave] = ib;
+    }
+    __syncthreads();
+    int before_a = carry_a, before_b = carry_b;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int wa = ws[par][0][w], wb = ws[par][1][w];
+      if (w < wave) {
+        before_a += wa;
+        before_b += wb;
+      }
+      carry_a += wa;
+      carry_b += wb;
+    }
+    int ra = before_a + ia - sa, rb = before_b + ib - sb;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (i + k < n) {
+        a[i + k] = ra;
+        b[i + k] = rb;
+      }
+      ra += xa[k];
+      rb += xb[k];
+    }
+  }
+  __syncthreads();
+  total_a = carry_a;
+  total_b = carry_b;
+}
+
 __global__ __launch_bounds__(256) void fo_clear_table_kernel(int* __restrict__ table, unsigned mask, int* totals) {
   const size_t n = (size_t)mask + 1;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) table[i] = -1;
@@ -83,7 +132,7 @@ __device__ __forceinline__ int find_or_enter(const FusedOpsArgs& a, int b, const
 }
 
 __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
-  __shared__ int wsum[8];
+  __shared__ int wsum[2][2][4];
   if (a.status[0] != 0) return;
   const int c = blockIdx.x, t = threadIdx.x, T = blockDim.x;
   const int b = a.cand_graph[c];
@@ -138,8 +187,8 @@ __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
     if ((t & 63) == 0 && n_repeats > 0) atomicAdd(&a.totals[5], n_repeats);
   }
   __syncthreads();
-  const int Mc = block_exscan(gfm, gfm, G, wsum);
-  const int Kc = block_exscan(gfk, gfk, G, wsum);
+  int Mc, Kc;
+  block_exscan_pair(gfm, gfk, G, wsum, Mc, Kc);
   if (t == 0) {
     gfm[G] = Mc;
     gfk[G] = Kc;
@@ -163,8 +212,8 @@ __global__ __launch_bounds__(256) void fo_count_kernel(FusedOpsArgs a) {
     dgi[i] = ni;
   }
   __syncthreads();
-  const int Eo = block_exscan(dgo, dgo, N, wsum);
-  const int Ei = block_exscan(dgi, dgi, N, wsum);
+  int Eo, Ei;
+  block_exscan_pair(dgo, dgi, N, wsum, Eo, Ei);
   if (t == 0) {
     dgo[N] = Eo;
     dgi[N] = Ei;
