@@ -368,6 +368,37 @@ __device__ __forceinline__ int block_exscan(const int* in, int* out, int n, int*
   return total;
 }
 
+// The same scan for arrays in global memory: rounds of four neighbouring entries per thread, so that a wave reads
+// and writes whole cache lines (a contiguous run per thread touches a line per entry).  blockDim.x <= 1024.
+__device__ __forceinline__ int block_exscan_lines(const int* in, int* out, int n, int* wsum) {
+  const int t = threadIdx.x, T = blockDim.x, lane = t & 63, wave = t >> 6, nw = T >> 6;
+  int carry = 0;
+  for (int i0 = 0; i0 < n; i0 += 4 * T) {
+    const int i = i0 + 4 * t;
+    int x[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) x[k] = i + k < n ? in[i + k] : 0;
+    const int s = x[0] + x[1] + x[2] + x[3];
+    const int inc = wave_incl_scan(s);
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    int before = carry;
+    for (int w = 0; w < nw; ++w) {
+      const int ws = wsum[w];
+      if (w < wave) before += ws;
+      carry += ws;
+    }
+    int run = before + inc - s;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (i + k < n) out[i + k] = run;
+      run += x[k];
+    }
+    __syncthreads();
+  }
+  return carry;
+}
+
 static inline __host__ __device__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 }  // namespace dc

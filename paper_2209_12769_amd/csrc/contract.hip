@@ -163,7 +163,7 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
   __syncthreads();
   for (int v = t; v < N; v += T) UL[v] = (A[LAB[v]] == v) ? 1 : 0;
   __syncthreads();
-  const int G = block_exscan(UL, UL, N, wsum);
+  const int G = kLds ? block_exscan(UL, UL, N, wsum) : block_exscan_lines(UL, UL, N, wsum);
   if (t == 0) UL[N] = G;
   __syncthreads();
   for (int v = t; v < N; v += T)
@@ -181,7 +181,7 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
   __syncthreads();
   for (int v = t; v < N; v += T) atomicAdd(&A[NID[v]], 1);
   __syncthreads();
-  block_exscan(A, MS, G, wsum);
+  if (kLds) block_exscan(A, MS, G, wsum); else block_exscan_lines(A, MS, G, wsum);
   if (t == 0) MS[G] = N;
   __syncthreads();
   for (int g = t; g < G; g += T) A[g] = MS[g];
@@ -269,7 +269,7 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
       A[i] = rp[u + 1] - rp[u];
     }
     __syncthreads();
-    const int Eraw = block_exscan(A, A, N, wsum);
+    const int Eraw = kLds ? block_exscan(A, A, N, wsum) : block_exscan_lines(A, A, N, wsum);
     if (t == 0) A[N] = Eraw;
     __syncthreads();
     // four member slots per thread and round: their row starts and first neighbours are
@@ -380,7 +380,7 @@ __device__ __forceinline__ void contract_one(const BaseGraphs& bg, int c, int b,
       }
     }
     __syncthreads();
-    Ec = block_exscan(UL, UL, G, wsum);
+    Ec = kLds ? block_exscan(UL, UL, G, wsum) : block_exscan_lines(UL, UL, G, wsum);
     if (t == 0) UL[G] = Ec;
     __syncthreads();
     for (int g = t; g <= G; g += T) t_rp[g] = UL[g];
