@@ -109,7 +109,10 @@ __device__ __forceinline__ int find_or_enter(const FusedOpsArgs& a, int b, const
   for (int i = 0; i < n; ++i) h = mix64(h ^ (unsigned)mem[s + i]);
   unsigned slot = (unsigned)h & a.table_mask;
   for (int probe = 0; probe < kMaxProbes; ++probe) {
-    const int old = atomicCAS(&a.table[slot], -1, me);
+    // a place only ever changes from free to taken, so whatever a plain read finds taken is final, and only a
+    // place that looks free needs the atomic (thousands of candidates may carry the same fused op)
+    int old = a.table[slot];
+    if (old == -1) old = atomicCAS(&a.table[slot], -1, me);
     if (old == -1) return -1;
     int lo = 0, hi = a.n_cand;                 // the candidate of node `old`: the last one that starts at or before it
     while (hi - lo > 1) {
