@@ -574,20 +574,27 @@ __global__ __launch_bounds__(256) void finalize_kernel(BaseGraphs bg, int C, con
       me[j] = ok ? ms[g[j] + 1] : 0;
       acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    // rounds of up to two members per item, the four items' loads in flight together
+    // rounds of up to two members per item, the four items' loads in flight together; the member numbers of the
+    // next round are asked for together with the rows of this one, so that a round costs one memory round trip
+    int i0m[4], i1m[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      i0m[j] = m[j] < me[j] ? mem[m[j]] : -1;
+      i1m[j] = m[j] + 1 < me[j] ? mem[m[j] + 1] : -1;
+    }
     bool more = true;
     while (more) {
-      int i0m[4], i1m[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        i0m[j] = m[j] < me[j] ? mem[m[j]] : -1;
-        i1m[j] = m[j] + 1 < me[j] ? mem[m[j] + 1] : -1;
-      }
       float4 x0[4], x1[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         x0[j] = i0m[j] >= 0 ? X4[(size_t)i0m[j] * q + f[j]] : make_float4(0.f, 0.f, 0.f, 0.f);
         x1[j] = i1m[j] >= 0 ? X4[(size_t)i1m[j] * q + f[j]] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      int n0m[4], n1m[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        n0m[j] = m[j] + 2 < me[j] ? mem[m[j] + 2] : -1;
+        n1m[j] = m[j] + 3 < me[j] ? mem[m[j] + 3] : -1;
       }
       more = false;
 #pragma unroll
@@ -597,6 +604,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(BaseGraphs bg, int C, con
         if (i1m[j] >= 0) { acc[j].x += x1[j].x; acc[j].y += x1[j].y; acc[j].z += x1[j].z; acc[j].w += x1[j].w; }
         m[j] += 2;
         more |= m[j] < me[j];
+        i0m[j] = n0m[j];
+        i1m[j] = n1m[j];
       }
     }
 #pragma unroll
