@@ -112,8 +112,10 @@ template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
     const void* __restrict__ A0, const void* __restrict__ A1, const void* __restrict__ A2, int d, int nseg,
     const void* __restrict__ Wl, const float* __restrict__ bias, void* __restrict__ out, int H,
-    const int* __restrict__ node_off, int C, const int* __restrict__ status) {
-  // nseg = 3: out = ReLU([A0 | A1 | A2] W + bias); nseg = 1 (bias == nullptr): out = A0 W
+    const int* __restrict__ node_off, int C, int interleave, const int* __restrict__ status) {
+  // nseg = 3: out = ReLU([A0 | A1 | A2] W + bias); nseg = 1 (bias == nullptr): out = A0 W.
+  // interleave: the K chunks in the order of the sixteen-wave layer kernel (chunk c of A0, of A1, of A2, then
+  // chunk c + 1 ...) instead of segment by segment, so that both add their products in the same order.
   if (status[0] != 0) return;
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -133,7 +135,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
   const int ntot = node_off[C];
   const int nct = H / BN;
   const int ntiles = ((ntot + BM - 1) / BM) * nct;
-  const int K = nseg * d;
 
   for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const int m0 = (tile / nct) * BM;
@@ -146,9 +147,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void update_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    for (int k0 = 0; k0 < K; k0 += BK) {
-      const int seg = k0 / d;
-      const int koff = k0 - seg * d;
+    const int nch = d / BK;                   // chunks per segment
+    for (int jc = 0; jc < nseg * nch; ++jc) {
+      const int seg = interleave ? jc % nseg : jc / nch;
+      const int koff = (interleave ? jc / nseg : jc - seg * nch) * BK;
+      const int k0 = seg * d + koff;          // row of W
       const void* Aseg = seg == 0 ? A0 : (seg == 1 ? A1 : A2);
       if (kBf16) {
         constexpr int CH = BK / 8;   // 16-byte chunks per A row
@@ -488,28 +491,30 @@ __global__ __launch_bounds__(256) void readout_head_kernel(const void* __restric
 
 template <bool kBf16, int BM, int BN, int BK, int WM, int WN>
 void launch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
-                   const float* bias, void* out, hipStream_t s) {
+                   const float* bias, void* out, int interleave, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   hipLaunchKernelGGL((update_kernel<kBf16, BM, BN, BK, WM, WN>), dim3(a.n_cu * (kBf16 ? 2 : 4)), dim3(NT), 0, s, A0, A1, A2, d, nseg,
-                     Wl, bias, out, a.H, a.node_off, a.n_cand, a.status);
+                     Wl, bias, out, a.H, a.node_off, a.n_cand, interleave, a.status);
 }
 
 template <bool kBf16, int BK>
 void dispatch_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
-                     const float* bias, void* out, hipStream_t s) {
+                     const float* bias, void* out, int interleave, hipStream_t s) {
   const int H = a.H;
-  if (H % 256 == 0) launch_update<kBf16, 128, 256, BK, 64, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
-  else if (H % 128 == 0) launch_update<kBf16, 128, 128, BK, 32, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
-  else if (H % 64 == 0) launch_update<kBf16, 128, 64, BK, 32, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
-  else launch_update<kBf16, 128, 32, BK, 32, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+  if (H % 256 == 0) launch_update<kBf16, 128, 256, BK, 64, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, interleave, s);
+  else if (H % 128 == 0) launch_update<kBf16, 128, 128, BK, 32, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, interleave, s);
+  else if (H % 64 == 0) launch_update<kBf16, 128, 64, BK, 32, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, interleave, s);
+  else launch_update<kBf16, 128, 32, BK, 32, 32>(a, A0, A1, A2, d, nseg, Wl, bias, out, interleave, s);
 }
 
 // [A0 | A1 | A2] W (nseg = 3) or A0 W (nseg = 1) with the chunk width the input width allows
 void run_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2, int d, int nseg, const void* Wl,
                 const float* bias, void* out, hipStream_t s) {
   if (a.bf16) {
-    if (d % 64 == 0) dispatch_update<true, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
-    else dispatch_update<true, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+    // the shapes the sixteen-wave layer kernel serves add their K chunks in its order
+    const int interleave = nseg == 3 && layer256_supported(d, a.H, a.bf16);
+    if (d % 64 == 0) dispatch_update<true, 64>(a, A0, A1, A2, d, nseg, Wl, bias, out, interleave, s);
+    else dispatch_update<true, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, 0, s);
   } else {
     const float* f0 = static_cast<const float*>(A0);
     const float* f1 = static_cast<const float*>(A1);
@@ -523,7 +528,7 @@ void run_update(const GnnArgs& a, const void* A0, const void* A1, const void* A2
                          static_cast<const float*>(Wl), bias, static_cast<float*>(out), a.H, a.node_off, a.n_cand,
                          a.status);
     else
-      dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, s);
+      dispatch_update<false, 16>(a, A0, A1, A2, d, nseg, Wl, bias, out, 0, s);
   }
 }
 

@@ -55,7 +55,7 @@ template <int DCH>
 struct Shape {
   static_assert(DCH == 4 || DCH == 1, "input widths 256 and 64");
   static constexpr int D = 64 * DCH;
-  static constexpr int NK = 3 * DCH;                 // K chunks per tile: own, predecessors' mean, successors' mean
+  static constexpr int NK = 3 * DCH;                 // K chunks per tile: own, predecessors' mean, successors' mean, taking turns
   static constexpr unsigned ROWB = D * 2;            // bytes per row of h
 };
 
@@ -201,15 +201,19 @@ __device__ __forceinline__ int request_copies(int g, int S, const MulCtx& c) {
   {
     const int J = g + 2;
     if (J < S) {
+      // step kc of a tile multiplies column chunk kc / 3 of the node's own row (kc % 3 = 0), of the predecessors'
+      // mean (1) or of the successors' mean (2): the three kinds take turns, so that a mean-forming wave has
+      // two chunks to deliver in every three steps
       const int ti = J / NK, kc = J - ti * NK;
-      if (kc < DCH) {
+      const int kind = kc % 3, colc = kc / 3;
+      if (kind == 0) {
         // piece p of an A chunk is rows 8p .. 8p+7; lane l fills position l&7 of row l>>3 of the piece,
         // which under the swizzle holds column piece (l&7) ^ ((row>>1)&7).  Rows past the end are
         // clamped to the last row (read, never stored).
         n_req += 2;
         const int m0 = (c.tile0 + ti * c.per) * kBM;
         const unsigned aring = c.lds0 + (unsigned)(J % 3) * kABytes;
-        const char* abase = uniform_ptr(c.h + (size_t)m0 * Shape<DCH>::ROWB + kc * kARow);
+        const char* abase = uniform_ptr(c.h + (size_t)m0 * Shape<DCH>::ROWB + colc * kARow);
         const int last = c.ntot - 1 - m0;                  // >= 0: the tile has at least one row
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -228,7 +232,7 @@ __device__ __forceinline__ int request_copies(int g, int S, const MulCtx& c) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int piece = c.wave * 4 + i;
-          copy16_to_lds(uniform_ptr(c.Wp + (size_t)kc * kBBytes + piece * 1024), (unsigned)c.lane * 16u, ring + piece * 1024);
+          copy16_to_lds(uniform_ptr(c.Wp + (size_t)(kind * DCH + colc) * kBBytes + piece * 1024), (unsigned)c.lane * 16u, ring + piece * 1024);
         }
       }
     }
@@ -526,8 +530,8 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
   if constexpr (s == NK - 1) adopt_descriptors<DCH>(st, c, t + 1);
   if constexpr (s == (NK >= 3 ? NK - 2 : 0)) request_descriptors<DCH>(st, c, t + 1);   // one step before they are adopted: not held longer
   constexpr int rq = (s + 1) % NK;                   // the step whose chunk is reduced now
-  if constexpr (rq >= DCH) {
-    constexpr int dir = rq / DCH - 1;
+  if constexpr (rq % 3 != 0) {
+    constexpr int dir = rq % 3 - 1;
     char* dst = c.smem + (rq % 3) * kABytes;                     // NK is a multiple of 3: ring slot = step % 3
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -565,9 +569,9 @@ __device__ __forceinline__ void mean_step(int t, MeanState<DCH>& st, const MeanC
   }
   __builtin_amdgcn_sched_barrier(0);
   constexpr int lq = (s + 2) % NK;                   // the step whose chunk is requested now
-  if constexpr (lq >= DCH) {
-    constexpr int dir = lq / DCH - 1;
-    constexpr unsigned coff = (unsigned)(lq % DCH) * kARow;      // 64 columns = 128 bytes
+  if constexpr (lq % 3 != 0) {
+    constexpr int dir = lq % 3 - 1;
+    constexpr unsigned coff = (unsigned)(lq / 3) * kARow;        // 64 columns = 128 bytes
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const Dsc& d = st.cur[dir][i];
