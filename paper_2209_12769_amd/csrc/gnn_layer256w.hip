@@ -17,6 +17,8 @@
 //   ring.  These are ordinary loads that the compiler tracks: no register is touched while a
 //   load into it is in flight, and the waits are the compiler's.  The steps of a tile are
 //   unrolled, so chunk offsets, ring slots and the direction are constants of each step.
+//   The K chunks take turns (64 columns of the own row, of the predecessors' mean, of the successors'
+//   mean, then the next 64): a mean-forming wave has two chunks to deliver in every three steps.
 // Rows with more than five neighbours take their mean from a pre-pass (one slot: the finished
 // mean), so that no lane walks a long list here.  The descriptors of a tile come sorted by the
 // number of slots that count, separately per direction: a lane may form the mean of any row of the
@@ -852,8 +854,8 @@ __global__ __launch_bounds__(256) void clear_heavy_ctr_kernel(int* __restrict__ 
 }
 
 // Means of the rows with more than kSlots neighbours (the pre-pass), from the list the two kernels above
-// leave.  LPR = d / 8 lanes (16 bytes each) serve a row: they fetch eight neighbour ids with one load, hand
-// them round, and keep up to eight neighbour rows in flight; the rows are added in ascending list order
+// leave.  LPR = d / 8 lanes (16 bytes each) serve a row: they fetch sixteen neighbour ids (eight at d = 64) with
+// one load, hand them round, and keep eight neighbour rows in flight; the rows are added in ascending list order
 // in fp32 (first one unpacked exactly), scaled by 1/deg and rounded to bf16: the arithmetic of the layer
 // kernel.
 // The list is cut into eight contiguous runs of tiles, one per XCD, and a run is handed out in order, in
@@ -862,8 +864,8 @@ __global__ __launch_bounds__(256) void clear_heavy_ctr_kernel(int* __restrict__ 
 // stay in that XCD's L2 while the graph's other long lists ask for them again.  (Dealing the tiles out by
 // a fixed stride lets the workgroups drift apart, and every row then comes from HBM each time it is asked
 // for.)  The batch after the next one is claimed while the current one is summed, and what a row needs
-// before its neighbour rows can be asked for -- its number, its list's start and length, the first eight
-// neighbour ids -- is fetched while the row before it is summed, also across batches.
+// before its neighbour rows can be asked for -- its number, its list's start and length, its first neighbour
+// ids -- is fetched while the row before it is summed, also across batches.
 constexpr int kHeavyGroups = 2;      // rows per lane group and batch
 constexpr int kHeavyThreads = 256;   // four waves share a batch
 constexpr int kHeavyWgs = 7;         // workgroups per CU: all that fit the kernel's registers
